@@ -1,0 +1,178 @@
+"""CPU oracle (test infrastructure): ctypes front end of gmp_oracle.c.
+
+Only tests, the smoke check and the CPU-baseline leg of the benchmark may import
+this package.  It shares nothing with the HIP library.  The wrapper marshals
+arguments (numpy arrays, bf16 passed as raw uint16 bits) and does no arithmetic
+of the method itself; weights in bf16 are widened to fp32, which is exact.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gmp_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+F32, BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile gmp_oracle.c with gcc -O2 -fopenmp into oracle/liboracle.so."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_num_threads.restype = ctypes.c_int
+        for name in ("oracle_score_pairs", "oracle_search", "oracle_brute_force"):
+            getattr(_lib, name).restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def widen_bf16(bits: np.ndarray) -> np.ndarray:
+    """uint16 bf16 bit patterns -> the same values as fp32 (exact)."""
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def _as_f32(a: np.ndarray) -> np.ndarray:
+    if a.dtype == np.uint16:
+        return widen_bf16(a)
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+class Mlp:
+    """Flat fp32 copy of the layers: W[l] is [dims[l+1], dims[l]] row-major."""
+
+    def __init__(self, W: Sequence[np.ndarray], b: Sequence[np.ndarray], head_w: np.ndarray):
+        self.n_layers = len(W)
+        dims = [int(W[0].shape[1])] + [int(w.shape[0]) for w in W]
+        for l, w in enumerate(W):
+            assert w.shape == (dims[l + 1], dims[l]), "layer shapes must chain"
+            assert b[l].shape == (dims[l + 1],)
+        assert len(head_w) == dims[-1]
+        self.dims = np.asarray(dims, dtype=np.int32)
+        self.W = np.concatenate([_as_f32(w).ravel() for w in W]).astype(np.float32)
+        self.b = np.concatenate([_as_f32(x).ravel() for x in b]).astype(np.float32)
+        self.head_w = np.ascontiguousarray(head_w, dtype=np.float32)
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _table(a: np.ndarray):
+    """(array, dtype code) for an embedding / user table given as fp32 or raw bf16 bits."""
+    if a.dtype == np.uint16:
+        return np.ascontiguousarray(a), BF16
+    return np.ascontiguousarray(a, dtype=np.float32), F32
+
+
+def score_pairs(emb: np.ndarray, users: np.ndarray, mlp: Mlp, q_idx: np.ndarray, item: np.ndarray,
+                act_round: int = 0, n_threads: int = 1) -> np.ndarray:
+    lib = _load()
+    emb, dt = _table(emb)
+    users, dtu = _table(users)
+    assert dt == dtu, "users and items must share a dtype"
+    q_idx = np.ascontiguousarray(q_idx, dtype=np.int32)
+    item = np.ascontiguousarray(item, dtype=np.int32)
+    M = q_idx.shape[0]
+    out = np.empty(M, dtype=np.float32)
+    rc = lib.oracle_score_pairs(
+        _ptr(emb), dt, ctypes.c_int64(emb.shape[0]), int(emb.shape[1]), _ptr(users),
+        int(users.shape[1]), ctypes.c_int64(users.shape[0]), mlp.n_layers, _ptr(mlp.dims),
+        _ptr(mlp.W), _ptr(mlp.b), _ptr(mlp.head_w), int(act_round), ctypes.c_int64(M),
+        _ptr(q_idx), _ptr(item), _ptr(out), int(n_threads))
+    if rc != 0:
+        raise ValueError(f"oracle_score_pairs failed rc={rc}")
+    return out
+
+
+def _per_query(v, Q: int) -> np.ndarray:
+    a = np.asarray(v, dtype=np.int32)
+    if a.ndim == 0:
+        a = np.full(Q, int(a), dtype=np.int32)
+    assert a.shape == (Q,)
+    return np.ascontiguousarray(a)
+
+
+def search(emb: np.ndarray, adj: np.ndarray, users: np.ndarray, mlp: Mlp, entries: np.ndarray,
+           W, L, k: int, max_iters=0, act_round: int = 0, n_threads: int = 1,
+           trace: bool = False, visited_cap: int = 0, trace_cap: int = 0) -> Dict:
+    """Runs the synchronous search for every query.  W, L, max_iters: scalars or [Q] arrays.
+    Returns ids [Q,k], scores [Q,k] and, with trace=True, n_scored / n_expanded / n_iters,
+    visited [Q,visited_cap] and worst [Q,trace_cap]."""
+    lib = _load()
+    emb, dt = _table(emb)
+    users, dtu = _table(users)
+    assert dt == dtu
+    adj = np.ascontiguousarray(adj, dtype=np.int32)
+    entries = np.ascontiguousarray(entries, dtype=np.int32)
+    Q, E = entries.shape
+    assert users.shape[0] == Q
+    Wq, Lq, cq = _per_query(W, Q), _per_query(L, Q), _per_query(max_iters, Q)
+    ids = np.empty((Q, k), dtype=np.int32)
+    scores = np.empty((Q, k), dtype=np.float32)
+    n_scored = np.zeros(Q, dtype=np.int64) if trace else None
+    n_expanded = np.zeros(Q, dtype=np.int64) if trace else None
+    n_iters = np.zeros(Q, dtype=np.int32) if trace else None
+    visited = np.empty((Q, visited_cap), dtype=np.int32) if trace and visited_cap > 0 else None
+    worst = np.empty((Q, trace_cap), dtype=np.float32) if trace and trace_cap > 0 else None
+    rc = lib.oracle_search(
+        _ptr(emb), dt, ctypes.c_int64(emb.shape[0]), int(emb.shape[1]), _ptr(adj),
+        int(adj.shape[1]), _ptr(users), int(users.shape[1]), ctypes.c_int64(Q), mlp.n_layers,
+        _ptr(mlp.dims), _ptr(mlp.W), _ptr(mlp.b), _ptr(mlp.head_w), int(act_round),
+        _ptr(entries), int(E), _ptr(Wq), _ptr(Lq), _ptr(cq), int(k), _ptr(ids), _ptr(scores),
+        _ptr(n_scored), _ptr(n_expanded), _ptr(n_iters), _ptr(visited),
+        ctypes.c_int64(visited_cap if visited is not None else 0), _ptr(worst),
+        int(trace_cap if worst is not None else 0), int(n_threads))
+    if rc != 0:
+        raise ValueError(f"oracle_search failed rc={rc}")
+    out = {"ids": ids, "scores": scores}
+    if trace:
+        out.update(n_scored=n_scored, n_expanded=n_expanded, n_iters=n_iters, visited=visited,
+                   worst=worst)
+    return out
+
+
+def brute_force(emb: np.ndarray, users: np.ndarray, mlp: Mlp, k: int, act_round: int = 0,
+                n_threads: int = 1) -> Dict:
+    lib = _load()
+    emb, dt = _table(emb)
+    users, dtu = _table(users)
+    assert dt == dtu
+    Q = users.shape[0]
+    ids = np.empty((Q, k), dtype=np.int32)
+    scores = np.empty((Q, k), dtype=np.float32)
+    rc = lib.oracle_brute_force(
+        _ptr(emb), dt, ctypes.c_int64(emb.shape[0]), int(emb.shape[1]), _ptr(users),
+        int(users.shape[1]), ctypes.c_int64(Q), mlp.n_layers, _ptr(mlp.dims), _ptr(mlp.W),
+        _ptr(mlp.b), _ptr(mlp.head_w), int(act_round), int(k), _ptr(ids), _ptr(scores),
+        int(n_threads))
+    if rc != 0:
+        raise ValueError(f"oracle_brute_force failed rc={rc}")
+    return {"ids": ids, "scores": scores}
+
+
+def recall_at(found_ids: np.ndarray, truth_ids: np.ndarray, k: int) -> float:
+    """Rec@k of Sec. 5.1.3: share of the true top-k found among the first k returned."""
+    hits = 0
+    for f, t in zip(found_ids[:, :k], truth_ids[:, :k]):
+        hits += len(set(int(v) for v in f if v >= 0) & set(int(v) for v in t))
+    return hits / float(truth_ids.shape[0] * k)

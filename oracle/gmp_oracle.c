@@ -1,0 +1,369 @@
+/*
+ * CPU oracle for the batched graph search with a learned MLP relevance score.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, obviously-correct
+ * statement of what the GPU library must compute.  It shares no code with the
+ * HIP path and must never be called from it; only the tests, the smoke check
+ * and the CPU-baseline leg of the benchmark may use it.
+ *
+ * What it follows (arXiv 2502.11490):
+ *   - relevance of one (user, item) pair: Sec. 3.1 (1), Eq. 5-8.  The MLP input
+ *     is the user vector followed by the item vector (Eq. 5); every layer is
+ *     W h + b with W stored [out][in] (Eq. 7); the J outputs of the last layer
+ *     are the per-behaviour predictions (Eq. 6) and the relevance is their fixed
+ *     weighted combination (Eq. 8).
+ *   - the search: Sec. 3.2 / Algorithm 1.  Several seeds per query are searched
+ *     jointly, every scored neighbour is pushed into ONE bounded best-first
+ *     container per query, larger relevance is better (Eq. 4).
+ *   - ground truth for recall: brute-force sorted items (Sec. 5.1.3).
+ *
+ * Readings adopted where the paper is silent (kept identical in the GPU path):
+ *   - ReLU after every hidden layer, none on the last layer; each head goes
+ *     through a logistic sigmoid before the weighted sum;
+ *   - the serendipity vector of Eq. 5 is not drawn here: a caller who wants it
+ *     adds it to the user vector beforehand;
+ *   - one sorted list per query of capacity C = max(L, k); per iteration the
+ *     first <= W not-yet-expanded entries among the first L ranks are expanded
+ *     together; order everywhere is (score descending, id ascending);
+ *   - an id is scored at most once per query (exact visited set, seeds included);
+ *     duplicates inside one iteration keep their first occurrence;
+ *   - a query stops when none of its first L ranks is unexpanded or when its
+ *     iteration cap (if > 0) is reached; seeding is not an iteration.
+ *
+ * Arithmetic: inputs are used exactly as stored (fp32, or bf16 widened exactly);
+ * all sums and the sigmoid are in double; the relevance is rounded once to fp32.
+ * With act_round = 1 each hidden activation is additionally rounded
+ * double -> fp32 -> bf16 (round to nearest even) after the ReLU: that is the
+ * precision the bf16 GPU kernels keep between layers, and is offered so that
+ * rank decisions can be compared at the kernel's precision.
+ *
+ * Parity pins (tests/test_oracle_*.py): closed forms and hand-worked values for
+ * the relevance, a library MLP forward pass, brute-force equality on complete
+ * graphs / L >= N, a hand-derived ring-graph trajectory, an independently
+ * written priority-queue best-first search for W = E = 1, monotonicity and
+ * uniqueness invariants, and entry/batch permutation symmetries.  The recall
+ * level reached on the synthetic graphs has no external pin: "parity unpinned"
+ * for that single quantity.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { MAX_W = 1024 }; /* largest per-iteration expansion width accepted */
+
+typedef struct {
+    int n_layers;
+    const int32_t *dims;   /* [n_layers + 1] */
+    const float *W;        /* layers back to back, each [out][in] row-major */
+    const float *b;        /* layers back to back, each [out] */
+    const float *head_w;   /* [dims[n_layers]] */
+    int act_round;
+    int max_width;
+} mlp_t;
+
+static float widen_bf16(uint16_t bits) {
+    uint32_t u = ((uint32_t)bits) << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+static double load_elem(const void *base, int dtype, int64_t idx) {
+    if (dtype == ORACLE_BF16) return (double)widen_bf16(((const uint16_t *)base)[idx]);
+    return (double)((const float *)base)[idx];
+}
+
+/* double -> fp32 -> bf16, both round-to-nearest-even, returned widened */
+static double round_to_bf16(double v) {
+    float f = (float)v;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (double)f; /* inf / nan unchanged */
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+static int mlp_max_width(const mlp_t *m) {
+    int w = 0;
+    for (int l = 0; l <= m->n_layers; ++l)
+        if (m->dims[l] > w) w = m->dims[l];
+    return w;
+}
+
+/* Eq. 5-8 for one pair.  x holds concat(user, item) in double; h0/h1 are scratch of max width. */
+static float relevance(const mlp_t *m, const double *x, double *h0, double *h1) {
+    const double *in = x;
+    double *out = h0;
+    const float *W = m->W;
+    const float *b = m->b;
+    for (int l = 0; l < m->n_layers; ++l) {
+        int n_in = m->dims[l], n_out = m->dims[l + 1];
+        int last = (l == m->n_layers - 1);
+        for (int o = 0; o < n_out; ++o) {
+            double acc = 0.0;
+            const float *row = W + (int64_t)o * n_in;
+            for (int i = 0; i < n_in; ++i) acc += (double)row[i] * in[i];
+            acc += (double)b[o];
+            if (!last) {
+                if (acc < 0.0) acc = 0.0;
+                if (m->act_round == 1) acc = round_to_bf16(acc);
+            }
+            out[o] = acc;
+        }
+        W += (int64_t)n_in * n_out;
+        b += n_out;
+        in = out;
+        out = (out == h0) ? h1 : h0;
+    }
+    int J = m->dims[m->n_layers];
+    double s = 0.0;
+    for (int j = 0; j < J; ++j) s += (double)m->head_w[j] * (1.0 / (1.0 + exp(-in[j])));
+    return (float)s;
+}
+
+static void build_input(double *x, const void *users, int dtype, int d_u, int64_t q,
+                        const void *emb, int d, int64_t v) {
+    for (int i = 0; i < d_u; ++i) x[i] = load_elem(users, dtype, q * d_u + i);
+    for (int i = 0; i < d; ++i) x[d_u + i] = load_elem(emb, dtype, v * d + i);
+}
+
+static mlp_t make_mlp(int n_layers, const int32_t *dims, const float *W, const float *b,
+                      const float *head_w, int act_round) {
+    mlp_t m;
+    m.n_layers = n_layers;
+    m.dims = dims;
+    m.W = W;
+    m.b = b;
+    m.head_w = head_w;
+    m.act_round = act_round;
+    m.max_width = 0;
+    m.max_width = mlp_max_width(&m);
+    return m;
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* relevance of an explicit list of pairs */
+int oracle_score_pairs(const void *emb, int dtype, int64_t N, int d, const void *users, int d_u,
+                       int64_t Q, int n_layers, const int32_t *dims, const float *W,
+                       const float *b, const float *head_w, int act_round, int64_t M,
+                       const int32_t *q_idx, const int32_t *item, float *out, int n_threads) {
+    if (n_layers < 1 || dims[0] != d_u + d) return -1;
+    mlp_t m = make_mlp(n_layers, dims, W, b, head_w, act_round);
+    for (int64_t r = 0; r < M; ++r)
+        if (q_idx[r] < 0 || q_idx[r] >= Q || item[r] < 0 || item[r] >= N) return -1;
+    if (n_threads < 1) n_threads = 1;
+#pragma omp parallel num_threads(n_threads)
+    {
+        double *x = (double *)malloc(sizeof(double) * (size_t)(dims[0] + 2 * m.max_width));
+        double *h0 = x + dims[0], *h1 = h0 + m.max_width;
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t r = 0; r < M; ++r) {
+            build_input(x, users, dtype, d_u, q_idx[r], emb, d, item[r]);
+            out[r] = relevance(&m, x, h0, h1);
+        }
+        free(x);
+    }
+    return 0;
+}
+
+typedef struct {
+    float score;
+    int32_t id;
+    int32_t expanded;
+} entry_t;
+
+/* (score descending, id ascending) */
+static int entry_cmp(const void *pa, const void *pb) {
+    const entry_t *a = (const entry_t *)pa, *b = (const entry_t *)pb;
+    if (a->score > b->score) return -1;
+    if (a->score < b->score) return 1;
+    if (a->id < b->id) return -1;
+    if (a->id > b->id) return 1;
+    return 0;
+}
+
+static int bit_get(const uint8_t *bm, int64_t i) { return (bm[i >> 3] >> (i & 7)) & 1; }
+static void bit_set(uint8_t *bm, int64_t i) { bm[i >> 3] |= (uint8_t)(1u << (i & 7)); }
+
+/*
+ * Synchronous search, one query after another (Algorithm 1, shared container).
+ * W_q, L_q, cap_q: per-query expansion width, eligible ranks, iteration cap (0 = none).
+ * Optional traces (NULL to skip):
+ *   n_scored[Q], n_expanded[Q], n_iters[Q];
+ *   visited_out[Q][visited_cap]: ids in the order they were scored (-1 padded);
+ *   worst_trace[Q][trace_cap]: entry t = score at rank L after iteration t (t = 0 is the
+ *   seeding), -inf while the list is shorter than L; unused slots = NaN.
+ */
+int oracle_search(const void *emb, int dtype, int64_t N, int d, const int32_t *adj, int R,
+                  const void *users, int d_u, int64_t Q, int n_layers, const int32_t *dims,
+                  const float *W, const float *b, const float *head_w, int act_round,
+                  const int32_t *entries, int E, const int32_t *W_q, const int32_t *L_q,
+                  const int32_t *cap_q, int k, int32_t *out_ids, float *out_scores,
+                  int64_t *n_scored, int64_t *n_expanded, int32_t *n_iters, int32_t *visited_out,
+                  int64_t visited_cap, float *worst_trace, int trace_cap, int n_threads) {
+    if (n_layers < 1 || dims[0] != d_u + d || k < 1 || E < 1 || R < 1) return -1;
+    for (int64_t q = 0; q < Q; ++q)
+        if (W_q[q] < 1 || W_q[q] > MAX_W || L_q[q] < 1 || cap_q[q] < 0) return -1;
+    mlp_t m = make_mlp(n_layers, dims, W, b, head_w, act_round);
+    if (n_threads < 1) n_threads = 1;
+    int fail = 0;
+#pragma omp parallel num_threads(n_threads)
+    {
+        double *x = (double *)malloc(sizeof(double) * (size_t)(dims[0] + 2 * m.max_width));
+        double *h0 = x + dims[0], *h1 = h0 + m.max_width;
+        uint8_t *visited = (uint8_t *)malloc((size_t)((N + 7) / 8));
+        entry_t *list = NULL;
+        int32_t *fresh = NULL;
+        size_t list_cap = 0, fresh_cap = 0;
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t q = 0; q < Q; ++q) {
+            const int Wq = W_q[q], Lq = L_q[q], cap = cap_q[q];
+            const int C = Lq > k ? Lq : k;
+            size_t need_list = (size_t)C + (size_t)Wq * R + (size_t)E;
+            size_t need_fresh = (size_t)Wq * R + (size_t)E;
+            if (need_list > list_cap) {
+                list = (entry_t *)realloc(list, need_list * sizeof(entry_t));
+                list_cap = need_list;
+            }
+            if (need_fresh > fresh_cap) {
+                fresh = (int32_t *)realloc(fresh, need_fresh * sizeof(int32_t));
+                fresh_cap = need_fresh;
+            }
+            if (!x || !visited || !list || !fresh) {
+                fail = 1;
+                continue;
+            }
+            memset(visited, 0, (size_t)((N + 7) / 8));
+            int64_t scored = 0, expanded = 0;
+            int len = 0;
+            if (worst_trace)
+                for (int t = 0; t < trace_cap; ++t) worst_trace[q * trace_cap + t] = NAN;
+            if (visited_out)
+                for (int64_t i = 0; i < visited_cap; ++i) visited_out[q * visited_cap + i] = -1;
+
+            /* seeds, in the order given */
+            for (int e = 0; e < E; ++e) {
+                int32_t v = entries[q * E + e];
+                if (v < 0 || v >= N || bit_get(visited, v)) continue;
+                bit_set(visited, v);
+                build_input(x, users, dtype, d_u, q, emb, d, v);
+                list[len].score = relevance(&m, x, h0, h1);
+                list[len].id = v;
+                list[len].expanded = 0;
+                ++len;
+                if (visited_out && scored < visited_cap) visited_out[q * visited_cap + scored] = v;
+                ++scored;
+            }
+            qsort(list, (size_t)len, sizeof(entry_t), entry_cmp);
+            if (len > C) len = C;
+            if (worst_trace && trace_cap > 0)
+                worst_trace[q * trace_cap] = (len >= Lq) ? list[Lq - 1].score : -INFINITY;
+
+            int t = 0;
+            for (;;) {
+                if (cap > 0 && t == cap) break;
+                /* the first <= W unexpanded entries among the first L ranks; all are chosen
+                   before any of their neighbours is merged */
+                int n_par = 0;
+                int32_t parents[MAX_W];
+                int lim = len < Lq ? len : Lq;
+                for (int r = 0; r < lim && n_par < Wq; ++r)
+                    if (!list[r].expanded) {
+                        list[r].expanded = 1;
+                        parents[n_par++] = list[r].id;
+                    }
+                if (n_par == 0) break;
+                expanded += n_par;
+                int n_new = 0;
+                for (int p = 0; p < n_par; ++p)
+                    for (int s = 0; s < R; ++s) {
+                        int32_t v = adj[(int64_t)parents[p] * R + s];
+                        if (v < 0 || v >= N || bit_get(visited, v)) continue;
+                        bit_set(visited, v);
+                        fresh[n_new++] = v;
+                    }
+                for (int i = 0; i < n_new; ++i) {
+                    int32_t v = fresh[i];
+                    build_input(x, users, dtype, d_u, q, emb, d, v);
+                    list[len].score = relevance(&m, x, h0, h1);
+                    list[len].id = v;
+                    list[len].expanded = 0;
+                    ++len;
+                    if (visited_out && scored < visited_cap)
+                        visited_out[q * visited_cap + scored] = v;
+                    ++scored;
+                }
+                qsort(list, (size_t)len, sizeof(entry_t), entry_cmp);
+                if (len > C) len = C;
+                ++t;
+                if (worst_trace && t < trace_cap)
+                    worst_trace[q * trace_cap + t] = (len >= Lq) ? list[Lq - 1].score : -INFINITY;
+            }
+            for (int i = 0; i < k; ++i) {
+                out_ids[q * k + i] = i < len ? list[i].id : -1;
+                out_scores[q * k + i] = i < len ? list[i].score : -INFINITY;
+            }
+            if (n_scored) n_scored[q] = scored;
+            if (n_expanded) n_expanded[q] = expanded;
+            if (n_iters) n_iters[q] = t;
+        }
+        free(x);
+        free(visited);
+        free(list);
+        free(fresh);
+    }
+    return fail ? -2 : 0;
+}
+
+/* exhaustive top-k of the same relevance (ground truth for recall) */
+int oracle_brute_force(const void *emb, int dtype, int64_t N, int d, const void *users, int d_u,
+                       int64_t Q, int n_layers, const int32_t *dims, const float *W,
+                       const float *b, const float *head_w, int act_round, int k,
+                       int32_t *out_ids, float *out_scores, int n_threads) {
+    if (n_layers < 1 || dims[0] != d_u + d || k < 1) return -1;
+    mlp_t m = make_mlp(n_layers, dims, W, b, head_w, act_round);
+    if (n_threads < 1) n_threads = 1;
+    int fail = 0;
+#pragma omp parallel num_threads(n_threads)
+    {
+        double *x = (double *)malloc(sizeof(double) * (size_t)(dims[0] + 2 * m.max_width));
+        double *h0 = x + dims[0], *h1 = h0 + m.max_width;
+        entry_t *all = (entry_t *)malloc(sizeof(entry_t) * (size_t)(N > 0 ? N : 1));
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t q = 0; q < Q; ++q) {
+            if (!x || !all) {
+                fail = 1;
+                continue;
+            }
+            for (int64_t v = 0; v < N; ++v) {
+                build_input(x, users, dtype, d_u, q, emb, d, v);
+                all[v].score = relevance(&m, x, h0, h1);
+                all[v].id = (int32_t)v;
+                all[v].expanded = 0;
+            }
+            qsort(all, (size_t)N, sizeof(entry_t), entry_cmp);
+            for (int i = 0; i < k; ++i) {
+                out_ids[q * k + i] = i < N ? all[i].id : -1;
+                out_scores[q * k + i] = i < N ? all[i].score : -INFINITY;
+            }
+        }
+        free(x);
+        free(all);
+    }
+    return fail ? -2 : 0;
+}
