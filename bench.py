@@ -1,0 +1,306 @@
+#!/usr/bin/env python3
+"""Throughput of the graph-retrieval hot path on one MI355X.
+
+A step = one ann_search call over the whole query batch of the workload (every stage of the hot
+path: seeding, rounds of parent choice / neighbour gather / visited filter, packing, MLP scoring,
+merge, top-k).  Inputs are generated once on the GPU and are resident in HBM when timing starts.
+
+Prints ONE JSON line (see the design doc for the fields).  Besides the headline queries/s it carries
+  roofline     : the MLP scoring kernel (the dominant kernel) against the dense bf16 MFMA peak,
+                 timed live with HIP events recorded on the search's stream by the library;
+  cpu_baseline : the CPU oracle, as it stands, on a bounded sample of the same queries.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0}
+HBM_PEAK_GBS = 8000.0
+
+
+def log(msg: str) -> None:
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def torch_ground_truth(wl, q_sel, k, chunk=1 << 20):
+    """Exhaustive top-k of the relevance (Sec. 3.1 Eq. 5-8; ground truth of Sec. 5.1.3) for the
+    queries q_sel, in plain fp32 torch ops on the GPU.  Independent of the HIP kernels."""
+    import torch
+
+    emb, users = wl["emb"], wl["users"]
+    Ws = [w.float() for w in wl["W"]]
+    bs = [b.float() for b in wl["b"]]
+    hw = wl["head_w"].float()
+    d_u = users.shape[1]
+    N = emb.shape[0]
+    out = torch.empty((len(q_sel), k), dtype=torch.int64, device=emb.device)
+    W1u, W1i = Ws[0][:, :d_u], Ws[0][:, d_u:]
+    for n, q in enumerate(q_sel):
+        pre = W1u @ users[q].float() + bs[0]
+        best_s = torch.full((0,), 0.0, device=emb.device)
+        best_i = torch.zeros((0,), dtype=torch.int64, device=emb.device)
+        for s in range(0, N, chunk):
+            h = emb[s:s + chunk].float() @ W1i.T + pre
+            for l in range(1, len(Ws)):
+                h = torch.relu(h) @ Ws[l].T + bs[l]
+            sc = torch.sigmoid(h) @ hw
+            kk = min(k, sc.numel())
+            v, i = torch.topk(sc, kk)
+            best_s = torch.cat([best_s, v])
+            best_i = torch.cat([best_i, i + s])
+            if best_s.numel() > k:
+                v, j = torch.topk(best_s, k)
+                best_s, best_i = v, best_i[j]
+        order = torch.argsort(best_s, descending=True)
+        out[n, : order.numel()] = best_i[order]
+    return out
+
+
+def recall_at(found, truth, k):
+    import torch
+
+    hits = 0
+    for f, t in zip(found[:, :k].tolist(), truth[:, :k].tolist()):
+        hits += len(set(v for v in f if v >= 0) & set(t))
+    return hits / float(truth.shape[0] * k)
+
+
+def flops_per_pair(dims, d_user, hoisted):
+    total = 0
+    for l in range(len(dims) - 1):
+        n_in = dims[l] - d_user if (l == 0 and hoisted) else dims[l]
+        total += 2 * n_in * dims[l + 1]
+    return total
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C3", help="preset name (C1..C5)")
+    ap.add_argument("--items", type=int, default=0, help="override the item count (smaller rehearsal)")
+    ap.add_argument("--L", type=int, default=0, help="fix L instead of sweeping for recall@100 >= 0.95")
+    ap.add_argument("--gt-queries", type=int, default=64, help="queries with exhaustive ground truth")
+    ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0 = pick for ~20 s)")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=3)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (queries would shard across GPUs "
+              "with the graph replicated; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2502_11490_amd as ann
+    from workloads import PRESETS, make_workload, scaled, to_host
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    cfg = PRESETS[args.workload]
+    if args.items:
+        cfg = scaled(cfg, args.items)
+    t0 = time.time()
+    log(f"generating {cfg.name}: N={cfg.N} d={cfg.d} {cfg.dtype} R={cfg.R} clusters={cfg.n_clusters} Q={cfg.Q}")
+    wl = make_workload(cfg, device="cuda:0")
+    torch.cuda.synchronize()
+    log(f"workload ready in {time.time() - t0:.1f} s")
+    dtype = ann.ANN_BF16 if cfg.dtype == "bf16" else ann.ANN_F32
+    g = ann.ann_graph_load(wl["adj"], wl["emb"], ann.ANN_VALIDATE)
+    m = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, dtype)
+    mfma = ann.ann_mlp_uses_mfma(m)
+    users, entries = wl["users"], wl["entries"]
+    Q, E, W, k = cfg.Q, cfg.E, cfg.W, cfg.k
+    ragged = cfg.ragged
+
+    # ---- ground truth on a subsample, then the smallest L that reaches recall@100 >= 0.95 ----
+    kr = min(100, k)
+    n_gt = min(args.gt_queries, Q)
+    gen = torch.Generator().manual_seed(250211490 + 20)
+    q_sel = torch.randperm(Q, generator=gen)[:n_gt].sort().values.tolist()
+    t1 = time.time()
+    truth = torch_ground_truth(wl, q_sel, kr)
+    torch.cuda.synchronize()
+    log(f"exhaustive ground truth for {n_gt} queries in {time.time() - t1:.1f} s")
+    sel = torch.tensor(q_sel, device="cuda:0")
+    users_s, entries_s = users[sel].contiguous(), entries[sel].contiguous()
+
+    def search_sample(L):
+        if ragged:
+            ids, _ = ann.ann_search_ragged(g, m, users_s, entries_s, wl["W_q"][sel].contiguous(),
+                                           wl["L_q"][sel].contiguous(), wl["cap_q"][sel].contiguous(),
+                                           cfg.W_range[1], cfg.L_range[1], k, cfg.cap_range[1])
+        else:
+            ids, _ = ann.ann_search(g, m, users_s, entries_s, W, L, k, 0)
+        torch.cuda.synchronize()
+        return recall_at(ids.cpu(), truth.cpu(), kr)
+
+    curve = {}
+    if ragged:
+        L_star = cfg.L_range[1]
+        curve[str(L_star)] = search_sample(L_star)
+    elif args.L:
+        L_star = args.L
+        curve[str(L_star)] = search_sample(L_star)
+    else:
+        L_star = None
+        for L in [cfg.L, cfg.L * 3 // 2, cfg.L * 2, cfg.L * 3, cfg.L * 4, cfg.L * 6, cfg.L * 8]:
+            if max(L, k) + W * cfg.R > 4096:
+                break
+            r = search_sample(L)
+            curve[str(L)] = round(r, 4)
+            log(f"L={L}: recall@{kr} = {r:.4f} on {n_gt} queries")
+            L_star = L
+            if r >= 0.95:
+                break
+    recall = curve[str(L_star)]
+    target_met = recall >= 0.95
+
+    # ---- timed region: K full-batch searches, inputs resident in HBM ----
+    if ragged:
+        Wm, Lm, capm = cfg.W_range[1], cfg.L_range[1], cfg.cap_range[1]
+        ws = torch.empty(ann.ann_search_workspace_bytes(g, m, Q, E, Wm, Lm, k, capm), dtype=torch.uint8, device="cuda:0")
+    else:
+        ws = torch.empty(ann.ann_search_workspace_bytes(g, m, Q, E, W, L_star, k, 0), dtype=torch.uint8, device="cuda:0")
+    out_ids = torch.empty((Q, k), dtype=torch.int32, device="cuda:0")
+    out_sc = torch.empty((Q, k), dtype=torch.float32, device="cuda:0")
+
+    def step():
+        if ragged:
+            ann.ann_search_ragged(g, m, users, entries, wl["W_q"], wl["L_q"], wl["cap_q"], Wm, Lm, k, capm,
+                                  workspace=ws, out_ids=out_ids, out_scores=out_sc)
+        else:
+            ann.ann_search(g, m, users, entries, W, L_star, k, 0, workspace=ws, out_ids=out_ids, out_scores=out_sc)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t2
+    ms_per_step = 1e3 * elapsed / args.steps
+    st = ann.ann_search_stats(ws)
+    qps = Q / (elapsed / args.steps)
+    scores_per_s = st.pairs_scored / (elapsed / args.steps)
+    log(f"{ms_per_step:.3f} ms/step, {qps:.0f} queries/s, {scores_per_s:.3e} MLP scores/s, "
+        f"{st.pairs_scored} pairs, {st.nodes_expanded} expansions, {st.max_query_iters} rounds")
+
+    # ---- per-stage time with HIP events on the search's stream ----
+    ann.ann_profile_enable(True)
+    for _ in range(args.profile_steps):
+        step()
+    prof = ann.ann_profile_read()
+    ann.ann_profile_enable(False)
+    torch.cuda.synchronize()
+    score_ms, score_launches = prof["score"]
+    round_ms, round_launches = prof["round"]
+    pack_ms, pack_launches = prof["pack"]
+    pairs_per_step = st.pairs_scored
+    fl_issued = flops_per_pair(cfg.dims, cfg.d, hoisted=mfma)
+    fl_full = flops_per_pair(cfg.dims, cfg.d, hoisted=False)
+    score_s_per_step = 1e-3 * score_ms / args.profile_steps
+    if mfma:
+        achieved = pairs_per_step * fl_issued / score_s_per_step / 1e12
+        peak = MFMA_PEAK_TFLOPS["bf16"]
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                    "frac": round(achieved / peak, 4), "traffic": None,
+                    "kernel": "mlp_mfma2_kernel", "avg_launch_us": round(1e3 * score_ms / max(score_launches, 1), 2),
+                    "launches_per_step": score_launches // args.profile_steps,
+                    "flop_per_pair_issued": fl_issued, "flop_per_pair_unhoisted": fl_full}
+    else:
+        achieved = pairs_per_step * fl_full / score_s_per_step / 1e12
+        peak = 78.6 if cfg.dtype == "f32" else 157.3
+        roofline = {"bound": "alu", "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
+                    "frac": round(achieved / peak, 5), "traffic": None, "kernel": "mlp_alu_kernel",
+                    "avg_launch_us": round(1e3 * score_ms / max(score_launches, 1), 2),
+                    "launches_per_step": score_launches // args.profile_steps}
+    # gather / filter stage against HBM: adjacency rows + (for the scoring kernel) embedding rows
+    es = 2 if cfg.dtype == "bf16" else 4
+    round_bytes = st.nodes_expanded * cfg.R * 4
+    gather_bytes = st.pairs_scored * (cfg.d * es + 8)
+    stages = {
+        "score_ms_per_step": round(score_ms / args.profile_steps, 4),
+        "round_ms_per_step": round(round_ms / args.profile_steps, 4),
+        "pack_ms_per_step": round(pack_ms / args.profile_steps, 4),
+        "round_adjacency_GBps": round(round_bytes / (1e-3 * round_ms / args.profile_steps) / 1e9, 2),
+        "score_embedding_GBps": round(gather_bytes / score_s_per_step / 1e9, 2),
+    }
+
+    # ---- the CPU oracle on a bounded sample of the same queries ----
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+
+        n_cpu = args.cpu_queries
+        threads = min(oracle.num_threads(), os.cpu_count() or 1)
+        if n_cpu <= 0:
+            # ~ pairs/query * flop/pair at about 1 GFLOP/s per core
+            per_query_s = (st.pairs_scored / Q) * fl_full / 1.0e9
+            n_cpu = int(max(threads, min(Q, 20.0 * threads / max(per_query_s, 1e-6))))
+            n_cpu = min(Q, max(threads, (n_cpu // threads) * threads))
+        t3 = time.time()
+        h = to_host({kk: wl[kk] for kk in ("emb", "adj", "W", "b", "head_w")})
+        hu = to_host({"users": users[:n_cpu], "entries": entries[:n_cpu]})
+        mlp = oracle.Mlp(h["W"], h["b"], h["head_w"])
+        log(f"host copies for the oracle in {time.time() - t3:.1f} s; timing {n_cpu} queries on {threads} threads")
+        if ragged:
+            Wq, Lq, cq = (wl[n][:n_cpu].cpu().numpy() for n in ("W_q", "L_q", "cap_q"))
+        else:
+            Wq, Lq, cq = W, L_star, 0
+        t4 = time.perf_counter()
+        ref = oracle.search(h["emb"], h["adj"], hu["users"], mlp, hu["entries"], Wq, Lq, k, cq, n_threads=threads,
+                            trace=True)
+        cpu_s = time.perf_counter() - t4
+        same = float(np.mean(np.all(ref["ids"] == out_ids[:n_cpu].cpu().numpy(), axis=1)))
+        cpu = {"value": round(n_cpu / cpu_s, 3), "unit": "queries/s", "cores": threads, "kind": "oracle",
+               "sample": f"first {n_cpu} of {Q} queries of the same batch, {cpu_s:.1f} s wall",
+               "scores_per_s": round(float(ref["n_scored"].sum()) / cpu_s, 1),
+               "identical_id_lists_vs_gpu": round(same, 4)}
+        log(f"oracle: {cpu['value']} queries/s on {threads} threads")
+
+    line = {
+        "metric": "queries/s at recall@100>=0.95 vs brute force (10M items, 1 GPU); MLP scores/s",
+        "value": round(qps, 1),
+        "unit": "queries/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: {cfg.N} items d={cfg.d} {cfg.dtype}, {cfg.n_clusters}-cluster mixture, R={cfg.R}, "
+                        f"MLP {'x'.join(str(v) for v in cfg.dims)}, Q={Q} E={E} W={W} L={L_star} k={k}",
+            "Q": Q, "E": E, "W": W, "L": L_star, "k": k,
+            "recall_at_100": round(recall, 4), "recall_target_met": bool(target_met),
+            "recall_curve_L": curve, "recall_queries": n_gt,
+            "mlp_scores_per_s": round(scores_per_s, 1),
+            "pairs_scored_per_step": int(st.pairs_scored), "nodes_expanded_per_step": int(st.nodes_expanded),
+            "rounds": int(st.max_query_iters), "mfma_kernel": bool(mfma), "stages": stages,
+        },
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,192 @@
+/*
+ * gmpgr_ann.h - C ABI of the MI355X graph-retrieval hot path.
+ *
+ * What the library computes (arXiv 2502.11490):
+ *   - the relevance of a (user, item) pair is a small multi-head MLP over
+ *     concat(user vector, item vector) (Sec. 3.1 (1), Eq. 5-7) whose J outputs are
+ *     combined with fixed weights (Eq. 8).  Readings fixed by this library: ReLU
+ *     after every hidden layer, a logistic sigmoid on every head, so
+ *         relevance = sum_j head_w[j] * sigmoid(z_j);
+ *   - retrieval is a joint best-first search on a fixed-degree item graph
+ *     (Sec. 3.2, Algorithm 1): all seeds of a query share ONE bounded candidate
+ *     container; larger relevance is better (Eq. 4);
+ *   - the ragged (user, item) groups produced by all queries in one round are
+ *     packed into dense fixed-size batches for the MLP (Sec. 3.2, Algorithm 2).
+ *
+ * Search rule (identical for every query, queries are independent):
+ *   list  = sorted by (relevance descending, id ascending), capacity C = max(L, k)
+ *   seed  : every distinct in-range entry id is scored once and inserted
+ *   round : the first <= W not-yet-expanded entries among the first L ranks are
+ *           marked expanded together; their adjacency rows are read; ids that are
+ *           out of range, already scored for this query, or repeated inside the
+ *           round are dropped (first occurrence kept); the rest are scored and
+ *           merged into the list
+ *   stop  : no unexpanded entry among the first L ranks, or max_iters rounds done
+ *   out   : first k list entries; unused slots are id -1, score -inf
+ *
+ * Conventions
+ *   - every pointer named *_dev is DEVICE memory, *_host is HOST memory;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); all
+ *     work is enqueued on it in order;
+ *   - every function returns ANN_OK (0) or a negative code and never throws,
+ *     aborts or prints; ann_last_error() gives the reason (thread local);
+ *   - arguments are checked before anything is launched; a failed call launches
+ *     nothing unless stated otherwise;
+ *   - the library performs every step on the GPU.  There is no CPU fallback.
+ */
+#ifndef GMPGR_ANN_H
+#define GMPGR_ANN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ANN_OK = 0,
+    ANN_EINVAL = -1,     /* bad argument or argument combination */
+    ANN_ENOMEM = -2,     /* host or device allocation failed */
+    ANN_EDEVICE = -3,    /* a HIP call failed */
+    ANN_ENOTIMPL = -4,   /* shape / dtype outside what the kernels support */
+    ANN_EWORKSPACE = -5  /* workspace too small, or a per-query visited table filled up */
+};
+
+enum { ANN_F32 = 0, ANN_BF16 = 1 };
+
+enum {
+    ANN_VALIDATE = 1u,   /* ann_graph_load: check on the device that every adjacency id is < N */
+    ANN_MLP_GENERIC = 2u /* ann_mlp_load: never pick the MFMA kernels (plain fp32-ALU path) */
+};
+
+typedef struct ann_graph ann_graph; /* opaque */
+typedef struct ann_mlp ann_mlp;     /* opaque */
+
+/* Counters of the last search that used a workspace (see ann_search_stats). */
+typedef struct ann_stats {
+    int64_t pairs_scored;    /* (user,item) pairs evaluated by the MLP, seeds included */
+    int64_t nodes_expanded;  /* adjacency rows read */
+    int64_t max_query_iters; /* largest number of rounds any query ran */
+    int64_t visited_overflow;/* queries stopped because their visited table filled up */
+    int64_t queries;         /* Q of that search */
+} ann_stats;
+
+/*
+ * The item graph of Sec. 3.2 (base layer, fixed out-degree).
+ *   adj_dev : [N][R] int32 row-major neighbour ids; ids outside [0, N) are ignored by the search
+ *   emb_dev : [N][d] row-major item vectors, fp32 (ANN_F32) or bf16 (ANN_BF16)
+ * Both arrays are BORROWED: they must stay valid and unchanged until ann_graph_free.
+ * Requirements: 1 <= N < 2^31, 1 <= R <= 64, 1 <= d <= 1024; rows must be 4-byte aligned,
+ * 16-byte alignment of emb_dev and d*sizeof(elem) % 16 == 0 are needed for the MFMA path.
+ * ANN_VALIDATE makes the call synchronise `stream` and return ANN_EINVAL if an id is >= N
+ * (negative ids are allowed and mean "no edge").
+ */
+int ann_graph_load(const int32_t *adj_dev, const void *emb_dev, int64_t N, int32_t R, int32_t d,
+                   int32_t dtype, uint32_t flags, void *stream, ann_graph **out);
+void ann_graph_free(ann_graph *g);
+
+/*
+ * The relevance metric of Sec. 3.1 (1): n_layers affine layers, Eq. 7 (W h + b).
+ *   dims_host   : [n_layers + 1]; dims[0] = d_user + d_item, dims[n_layers] = J (1 <= J <= 8)
+ *   W_host[l]   : [dims[l+1]][dims[l]] row-major, fp32 or bf16 as `dtype`; the first d_user
+ *                 columns of W_host[0] multiply the user vector (Eq. 5: user first)
+ *   b_host[l]   : [dims[l+1]] fp32
+ *   head_w_host : [J] fp32 combination weights (the vector A of Eq. 8)
+ * Everything is COPIED to the device (and re-laid-out for the kernels); the host arrays may
+ * be freed afterwards.  1 <= n_layers <= 8, every width <= 2048.
+ * dtype = ANN_BF16 means: items, users and weights are bf16, products are accumulated in
+ * fp32, every hidden activation is rounded to bf16 (nearest even) after its ReLU, head
+ * logits, sigmoid and the weighted sum stay in fp32 (the 16-bit deployment of Sec. 4.3).
+ */
+int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *W_host,
+                 const float *const *b_host, const float *head_w_host, int32_t d_user,
+                 int32_t dtype, uint32_t flags, void *stream, ann_mlp **out);
+void ann_mlp_free(ann_mlp *m);
+
+/* 1 if searches with this metric run the MFMA kernels, 0 if the plain ALU kernels. */
+int ann_mlp_uses_mfma(const ann_mlp *m);
+
+/*
+ * Bytes of device workspace ann_search / ann_search_ragged need for at most Q queries,
+ * E entry points, expansion width <= W_max, eligible ranks <= L_max, k results and
+ * <= max_iters_max rounds per query.  The per-query visited table is sized for
+ *     E + rounds * W_max * R ids,  rounds = max_iters_max > 0 ? max_iters_max
+ *                                                            : 4 * ceil(L_max / W_max) + 32
+ * (at most N).  A query that would outgrow its table stops early and is counted in
+ * ann_stats.visited_overflow.  Returns 0 on invalid arguments (see ann_last_error).
+ */
+size_t ann_search_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E,
+                                  int32_t W_max, int32_t L_max, int32_t k,
+                                  int32_t max_iters_max);
+
+/*
+ * Batched search (Sec. 3.2, Algorithms 1 and 2) for Q independent queries.
+ *   queries_dev   : [Q][d_user] user vectors, dtype of the metric
+ *   entry_dev     : [Q][E] int32 seed ids (out-of-range or repeated ids are ignored)
+ *   W, L, k       : expansion width, eligible ranks, results per query (all >= 1)
+ *   max_iters     : rounds per query, 0 = until converged
+ *   workspace_dev : >= ann_search_workspace_bytes(g, m, Q, E, W, L, k, max_iters) bytes,
+ *                   256-byte aligned; contents need not be preserved between calls
+ *   out_ids_dev   : [Q][k] int32, out_scores_dev : [Q][k] fp32 (padding: -1 / -inf)
+ * With max_iters > 0 the call only enqueues work.  With max_iters = 0 it also waits on
+ * `stream` every few rounds to learn whether every query has converged.
+ * Limits: W*R <= 1024, max(L,k) + W*R <= 4096, E <= 1024.
+ * Returns ANN_EWORKSPACE (results still written, for the truncated search) if the call
+ * waited on the stream and saw a query fill its visited table; with max_iters > 0 use
+ * ann_search_stats to learn about that.
+ * Calls that share a workspace must not overlap in time.
+ */
+int ann_search(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
+               const int32_t *entry_dev, int32_t E, int32_t W, int32_t L, int32_t k,
+               int32_t max_iters, void *workspace_dev, size_t workspace_bytes,
+               int32_t *out_ids_dev, float *out_scores_dev, void *stream);
+
+/*
+ * Same search with per-query parameters (device arrays of Q int32 each):
+ *   W_q_dev in [1, W_max], L_q_dev in [1, L_max], iters_q_dev in [0, max_iters_max]
+ *   (0 = until converged; allowed only when max_iters_max = 0).
+ * W_max, L_max, max_iters_max are the bounds the workspace was sized with; values outside
+ * them are clamped on the device.
+ */
+int ann_search_ragged(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
+                      const int32_t *entry_dev, int32_t E, const int32_t *W_q_dev,
+                      const int32_t *L_q_dev, const int32_t *iters_q_dev, int32_t W_max,
+                      int32_t L_max, int32_t k, int32_t max_iters_max, void *workspace_dev,
+                      size_t workspace_bytes, int32_t *out_ids_dev, float *out_scores_dev,
+                      void *stream);
+
+/*
+ * Relevance (Eq. 5-8) of an explicit list of M pairs: out_dev[r] = relevance(user q_idx[r],
+ * item item[r]).  q_idx_dev, item_dev: [M] int32; out_dev: [M] fp32.  Pairs whose indices
+ * are out of range get NaN.  Uses the same kernels as the search.  `tile_rows` (0 = default)
+ * sets how many pairs one batch of Algorithm 2 holds; results do not depend on it.
+ * The call allocates and frees a small temporary on `stream`'s device and synchronises.
+ */
+int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
+                    int64_t M, const int32_t *q_idx_dev, const int32_t *item_dev, float *out_dev,
+                    int32_t tile_rows, void *stream);
+
+/* Waits for `stream`, then copies the counters of the last search run on workspace_dev. */
+int ann_search_stats(const void *workspace_dev, ann_stats *out_host, void *stream);
+
+/*
+ * Stage timing for measurement runs.  While enabled on the calling host thread, ann_search and
+ * ann_search_ragged bracket every kernel launch with two HIP events recorded on the search's
+ * stream.  Stages: ANN_STAGE_SCORE = the MLP relevance kernel (Sec. 3.1), ANN_STAGE_ROUND =
+ * seeding and the per-query round kernel (merge, choice of parents, neighbour gather, visited
+ * filter; Algorithm 1), ANN_STAGE_PACK = prefix sum + packing of the ragged groups (Algorithm 2).
+ * ann_profile_read waits for the recorded events, writes per stage the summed elapsed
+ * milliseconds and the number of launches since the last read (arrays of ANN_STAGE_COUNT),
+ * and forgets them.  Event pairs are created on demand and kept until the process ends.
+ */
+enum { ANN_STAGE_SCORE = 0, ANN_STAGE_ROUND = 1, ANN_STAGE_PACK = 2, ANN_STAGE_COUNT = 3 };
+int ann_profile_enable(int on);
+int ann_profile_read(double *ms_out, int64_t *launches_out);
+
+const char *ann_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GMPGR_ANN_H */

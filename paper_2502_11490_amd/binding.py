@@ -1,0 +1,281 @@
+"""ctypes marshalling for include/gmpgr_ann.h.  PyTorch is used for device memory and the
+current HIP stream only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+ANN_OK, ANN_EINVAL, ANN_ENOMEM, ANN_EDEVICE, ANN_ENOTIMPL, ANN_EWORKSPACE = 0, -1, -2, -3, -4, -5
+ANN_F32, ANN_BF16 = 0, 1
+ANN_VALIDATE, ANN_MLP_GENERIC = 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgmpgr_ann.so")
+_lib = None
+
+EXPORTS = [
+    "ann_graph_load", "ann_graph_free", "ann_mlp_load", "ann_mlp_free", "ann_mlp_uses_mfma",
+    "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_score_pairs",
+    "ann_search_stats", "ann_profile_enable", "ann_profile_read", "ann_last_error",
+]
+
+
+class AnnError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"ann error {code}: {msg}")
+        self.code = code
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [("pairs_scored", ctypes.c_int64), ("nodes_expanded", ctypes.c_int64),
+                ("max_query_iters", ctypes.c_int64), ("visited_overflow", ctypes.c_int64),
+                ("queries", ctypes.c_int64)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libgmpgr_ann.so (built by paper_2502_11490_amd/build.py).  Raises if it is missing:
+    there is no other implementation to fall back to."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} not found: build it with `python -m paper_2502_11490_amd.build` "
+            "(or __graft_entry__.build()); the library has no CPU fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, u32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_size_t
+    lib.ann_graph_load.argtypes = [vp, vp, i64, i32, i32, i32, u32, vp, ctypes.POINTER(vp)]
+    lib.ann_graph_load.restype = ctypes.c_int
+    lib.ann_graph_free.argtypes = [vp]
+    lib.ann_graph_free.restype = None
+    lib.ann_mlp_load.argtypes = [i32, ctypes.POINTER(i32), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                 ctypes.POINTER(ctypes.c_float), i32, i32, u32, vp, ctypes.POINTER(vp)]
+    lib.ann_mlp_load.restype = ctypes.c_int
+    lib.ann_mlp_free.argtypes = [vp]
+    lib.ann_mlp_free.restype = None
+    lib.ann_mlp_uses_mfma.argtypes = [vp]
+    lib.ann_mlp_uses_mfma.restype = ctypes.c_int
+    lib.ann_search_workspace_bytes.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32]
+    lib.ann_search_workspace_bytes.restype = sz
+    lib.ann_search.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, vp, sz, vp, vp, vp]
+    lib.ann_search.restype = ctypes.c_int
+    lib.ann_search_ragged.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
+    lib.ann_search_ragged.restype = ctypes.c_int
+    lib.ann_score_pairs.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, i32, vp]
+    lib.ann_score_pairs.restype = ctypes.c_int
+    lib.ann_search_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
+    lib.ann_search_stats.restype = ctypes.c_int
+    lib.ann_profile_enable.argtypes = [ctypes.c_int]
+    lib.ann_profile_enable.restype = ctypes.c_int
+    lib.ann_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.ann_profile_read.restype = ctypes.c_int
+    lib.ann_last_error.argtypes = []
+    lib.ann_last_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def ann_last_error() -> str:
+    return load_library().ann_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != ANN_OK:
+        raise AnnError(rc, ann_last_error())
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return ANN_F32
+    if t.dtype == torch.bfloat16:
+        return ANN_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+class Graph:
+    """Owns the C handle and keeps the borrowed tensors alive."""
+
+    def __init__(self, handle, adj, emb):
+        self.handle, self.adj, self.emb = handle, adj, emb
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.ann_graph_free(self.handle)
+            self.handle = None
+
+
+class Mlp:
+    def __init__(self, handle, dims, d_user, dtype):
+        self.handle, self.dims, self.d_user, self.dtype = handle, list(dims), d_user, dtype
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.ann_mlp_free(self.handle)
+            self.handle = None
+
+
+def ann_graph_load(adj: torch.Tensor, emb: torch.Tensor, flags: int = 0, stream=None) -> Graph:
+    lib = load_library()
+    if adj.dim() != 2 or emb.dim() != 2 or adj.shape[0] != emb.shape[0]:
+        raise ValueError("adj must be [N,R] and emb [N,d]")
+    h = ctypes.c_void_p()
+    rc = lib.ann_graph_load(_dev_ptr(adj, "adj", torch.int32), _dev_ptr(emb, "emb"), adj.shape[0], adj.shape[1],
+                            emb.shape[1], _dtype_code(emb), flags, _stream_ptr(stream), ctypes.byref(h))
+    _check(rc)
+    return Graph(h, adj, emb)
+
+
+def _host_bytes(t) -> np.ndarray:
+    """Host copy of a weight tensor as a contiguous numpy array (bf16 as raw uint16)."""
+    if isinstance(t, torch.Tensor):
+        t = t.detach().to("cpu").contiguous()
+        if t.dtype == torch.bfloat16:
+            return t.view(torch.int16).numpy().view(np.uint16).copy()
+        return t.numpy().copy()
+    return np.ascontiguousarray(t)
+
+
+def ann_mlp_load(W: Sequence, b: Sequence, head_w, d_user: int, dtype: int, flags: int = 0, stream=None) -> Mlp:
+    """W[l]: [out,in] torch tensors (fp32 or bf16, matching dtype) or numpy arrays (bf16 as uint16 bits);
+    b[l]: [out] fp32; head_w: [J] fp32."""
+    lib = load_library()
+    n = len(W)
+    Wh = [_host_bytes(w) for w in W]
+    want = np.uint16 if dtype == ANN_BF16 else np.float32
+    for w in Wh:
+        if w.dtype != want:
+            raise TypeError(f"weights must be {'bf16' if dtype == ANN_BF16 else 'fp32'}")
+    bh = [np.ascontiguousarray(_host_bytes(x), dtype=np.float32) for x in b]
+    hw = np.ascontiguousarray(_host_bytes(head_w), dtype=np.float32)
+    dims = [Wh[0].shape[1]] + [w.shape[0] for w in Wh]
+    for l in range(n):
+        if Wh[l].shape != (dims[l + 1], dims[l]) or bh[l].shape != (dims[l + 1],):
+            raise ValueError("layer shapes do not chain")
+    if hw.shape != (dims[-1],):
+        raise ValueError("head_w must have one weight per head")
+    dims_c = (ctypes.c_int32 * (n + 1))(*dims)
+    W_c = (ctypes.c_void_p * n)(*[w.ctypes.data for w in Wh])
+    b_c = (ctypes.c_void_p * n)(*[x.ctypes.data for x in bh])
+    h = ctypes.c_void_p()
+    rc = lib.ann_mlp_load(n, dims_c, W_c, b_c, hw.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), d_user, dtype,
+                          flags, _stream_ptr(stream), ctypes.byref(h))
+    _check(rc)
+    return Mlp(h, dims, d_user, dtype)
+
+
+def ann_mlp_uses_mfma(m: Mlp) -> bool:
+    return bool(load_library().ann_mlp_uses_mfma(m.handle))
+
+
+def ann_search_workspace_bytes(g: Graph, m: Mlp, Q: int, E: int, W_max: int, L_max: int, k: int,
+                               max_iters_max: int) -> int:
+    n = load_library().ann_search_workspace_bytes(g.handle, m.handle, Q, E, W_max, L_max, k, max_iters_max)
+    if n == 0:
+        raise AnnError(ANN_EINVAL, ann_last_error())
+    return int(n)
+
+
+def _alloc_out(Q, k, device):
+    return (torch.empty((Q, k), dtype=torch.int32, device=device),
+            torch.empty((Q, k), dtype=torch.float32, device=device))
+
+
+def ann_search(g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.Tensor, W: int, L: int, k: int,
+               max_iters: int = 0, workspace: Optional[torch.Tensor] = None, out_ids=None, out_scores=None,
+               stream=None):
+    """Returns (ids [Q,k] int32, scores [Q,k] fp32) on the device.  `workspace` is a uint8 device tensor of at
+    least ann_search_workspace_bytes(...) bytes; one is allocated when omitted."""
+    lib = load_library()
+    Q, E = entries.shape
+    if workspace is None:
+        workspace = torch.empty(ann_search_workspace_bytes(g, m, Q, E, W, L, k, max_iters), dtype=torch.uint8,
+                                device=queries.device)
+    if out_ids is None:
+        out_ids, out_scores = _alloc_out(Q, k, queries.device)
+    rc = lib.ann_search(g.handle, m.handle, _dev_ptr(queries, "queries"), Q, _dev_ptr(entries, "entries", torch.int32),
+                        E, W, L, k, max_iters, _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+                        _dev_ptr(out_ids, "out_ids", torch.int32), _dev_ptr(out_scores, "out_scores", torch.float32),
+                        _stream_ptr(stream))
+    _check(rc)
+    return out_ids, out_scores
+
+
+def ann_search_ragged(g: Graph, m: Mlp, queries, entries, W_q, L_q, iters_q, W_max: int, L_max: int, k: int,
+                      max_iters_max: int, workspace: Optional[torch.Tensor] = None, out_ids=None, out_scores=None,
+                      stream=None):
+    lib = load_library()
+    Q, E = entries.shape
+    if workspace is None:
+        workspace = torch.empty(ann_search_workspace_bytes(g, m, Q, E, W_max, L_max, k, max_iters_max),
+                                dtype=torch.uint8, device=queries.device)
+    if out_ids is None:
+        out_ids, out_scores = _alloc_out(Q, k, queries.device)
+    rc = lib.ann_search_ragged(g.handle, m.handle, _dev_ptr(queries, "queries"), Q,
+                               _dev_ptr(entries, "entries", torch.int32), E, _dev_ptr(W_q, "W_q", torch.int32),
+                               _dev_ptr(L_q, "L_q", torch.int32), _dev_ptr(iters_q, "iters_q", torch.int32), W_max,
+                               L_max, k, max_iters_max, _dev_ptr(workspace, "workspace", torch.uint8),
+                               workspace.numel(), _dev_ptr(out_ids, "out_ids", torch.int32),
+                               _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
+    _check(rc)
+    return out_ids, out_scores
+
+
+def ann_score_pairs(g: Graph, m: Mlp, queries: torch.Tensor, q_idx: torch.Tensor, item: torch.Tensor,
+                    out: Optional[torch.Tensor] = None, tile_rows: int = 0, stream=None) -> torch.Tensor:
+    lib = load_library()
+    M = q_idx.numel()
+    if out is None:
+        out = torch.empty(M, dtype=torch.float32, device=queries.device)
+    rc = lib.ann_score_pairs(g.handle, m.handle, _dev_ptr(queries, "queries"), queries.shape[0], M,
+                             _dev_ptr(q_idx, "q_idx", torch.int32), _dev_ptr(item, "item", torch.int32),
+                             _dev_ptr(out, "out", torch.float32), tile_rows, _stream_ptr(stream))
+    _check(rc)
+    return out
+
+
+def ann_search_stats(workspace: torch.Tensor, stream=None) -> Stats:
+    st = Stats()
+    _check(load_library().ann_search_stats(_dev_ptr(workspace, "workspace", torch.uint8), ctypes.byref(st),
+                                           _stream_ptr(stream)))
+    return st
+
+
+STAGES = ("score", "round", "pack")
+
+
+def ann_profile_enable(on: bool) -> None:
+    _check(load_library().ann_profile_enable(1 if on else 0))
+
+
+def ann_profile_read() -> dict:
+    """{stage: (milliseconds, launches)} since the last read."""
+    ms = (ctypes.c_double * len(STAGES))()
+    n = (ctypes.c_int64 * len(STAGES))()
+    _check(load_library().ann_profile_read(ms, n))
+    return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(STAGES)}

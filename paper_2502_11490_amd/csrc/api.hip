@@ -1,0 +1,572 @@
+// C ABI of the library (include/gmpgr_ann.h): argument checks, handles, workspace plan and
+// the host side of the round loop.  Every step of the search runs in the kernels of
+// search_kernels.hip, mlp_alu.hip and mlp_mfma.hip; nothing here computes a score or a rank.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+namespace gmpgr {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+static inline int next_pow2(int64_t x) {
+    int64_t p = 1;
+    while (p < x) p <<= 1;
+    return (int)p;
+}
+
+constexpr size_t STATS_OFFSET = 256;  // bytes from the workspace base: int64[8] counters
+
+bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32_t W_max, int32_t L_max,
+               int32_t k, int32_t max_iters_max, Plan *p) {
+    if (!g || !m) {
+        set_error("null graph or metric handle");
+        return false;
+    }
+    if (Q < 0 || E < 1 || W_max < 1 || L_max < 1 || k < 1 || max_iters_max < 0) {
+        set_error("need Q >= 0, E >= 1, W >= 1, L >= 1, k >= 1, max_iters >= 0 (got Q=%d E=%d W=%d L=%d k=%d iters=%d)",
+                  Q, E, W_max, L_max, k, max_iters_max);
+        return false;
+    }
+    if (m->d_item != g->d) {
+        set_error("metric expects item width %d, graph has %d", m->d_item, g->d);
+        return false;
+    }
+    if (m->dtype != g->dtype) {
+        set_error("metric dtype %d differs from graph dtype %d", m->dtype, g->dtype);
+        return false;
+    }
+    if ((int64_t)W_max * g->R > MAX_WR || E > MAX_E) {
+        set_error("W*R = %lld exceeds %d or E = %d exceeds %d", (long long)W_max * g->R, MAX_WR, E, MAX_E);
+        return false;
+    }
+    p->Q = Q;
+    p->E = E;
+    p->W_max = W_max;
+    p->L_max = L_max;
+    p->k = k;
+    p->R = g->R;
+    p->max_iters_max = max_iters_max;
+    p->C = L_max > k ? L_max : k;
+    p->slots = W_max * g->R > E ? W_max * g->R : E;
+    if ((int64_t)p->C + p->slots > MAX_SORT) {
+        set_error("max(L,k) + max(W*R,E) = %lld exceeds %d", (long long)p->C + p->slots, MAX_SORT);
+        return false;
+    }
+    p->sort_n = next_pow2(p->C + p->slots);
+    if (p->sort_n < 2) p->sort_n = 2;
+    // ids one query can score: seeds + rounds * W * R; without a cap, 4*ceil(L/W)+32 rounds are assumed
+    int64_t rounds = max_iters_max > 0 ? max_iters_max : 4 * (int64_t)((L_max + W_max - 1) / W_max) + 32;
+    p->rounds_assumed = (int32_t)(rounds > 0x7fffffff ? 0x7fffffff : rounds);
+    int64_t visited = (int64_t)E + rounds * W_max * g->R;
+    if (visited > g->N) visited = g->N;
+    int64_t cap = 2 * (visited + (int64_t)W_max * g->R);
+    if (cap > (1ll << 30)) {
+        set_error("visited table of %lld entries per query is too large", (long long)cap);
+        return false;
+    }
+    p->hash_cap = next_pow2(cap < 64 ? 64 : cap);
+    p->M_max = (int64_t)Q * p->slots;
+    if (p->M_max > 0x7fffffffll) {
+        set_error("Q * max(W*R,E) = %lld pairs per round exceeds 2^31", (long long)p->M_max);
+        return false;
+    }
+    p->H1 = (m->kernel == MLP_MFMA2) ? m->dims[1] : 0;
+    size_t o = 0;
+    p->off_ctrl = o;
+    o += STATS_OFFSET;
+    p->off_stats = o;
+    o += 256;
+    p->off_state = o;
+    o = align256(o + (size_t)Q * sizeof(QState));
+    p->off_pool = o;
+    o = align256(o + (size_t)Q * p->C * 8);
+    p->off_hash = o;
+    o = align256(o + (size_t)Q * p->hash_cap * 4);
+    p->off_cand = o;
+    o = align256(o + (size_t)Q * p->slots * 4);
+    p->off_counts = o;
+    o = align256(o + (size_t)Q * 4);
+    p->off_offsets = o;
+    o = align256(o + (size_t)Q * 4);
+    p->off_pair_q = o;
+    o = align256(o + (size_t)p->M_max * 4);
+    p->off_pair_id = o;
+    o = align256(o + (size_t)p->M_max * 4);
+    p->off_scores = o;
+    o = align256(o + (size_t)p->M_max * 4);
+    p->off_upre = o;
+    o = align256(o + (size_t)Q * p->H1 * 4);
+    p->total = o;
+    return true;
+}
+
+// One pinned int32[16] per host thread for the "has every query converged" read-back.
+static int32_t *pinned_ctrl() {
+    static thread_local int32_t *buf = nullptr;
+    if (!buf) {
+        if (hipHostMalloc((void **)&buf, 64, hipHostMallocDefault) != hipSuccess) buf = nullptr;
+    }
+    return buf;
+}
+
+// Optional stage timing (ann_profile_enable): every kernel launch of a stage is bracketed by two
+// HIP events on the search's stream; ann_profile_read sums the elapsed times.
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> events;  // pairs: 2*i = start, 2*i+1 = stop
+    std::vector<int> stage;
+    size_t used = 0;
+    hipEvent_t *next(int st) {
+        if (used == stage.size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess) return nullptr;
+            if (hipEventCreate(&b) != hipSuccess) return nullptr;
+            events.push_back(a);
+            events.push_back(b);
+            stage.push_back(st);
+        }
+        stage[used] = st;
+        return &events[2 * used++];
+    }
+};
+static thread_local Profiler g_prof;
+
+struct StageTimer {
+    hipEvent_t *ev = nullptr;
+    hipStream_t s;
+    StageTimer(int stage, hipStream_t stream) : s(stream) {
+        if (g_prof.on) {
+            ev = g_prof.next(stage);
+            if (ev) (void)hipEventRecord(ev[0], s);
+        }
+    }
+    ~StageTimer() {
+        if (ev) (void)hipEventRecord(ev[1], s);
+    }
+};
+
+static int score_batch(const SearchArgs &a) {
+    StageTimer timer(ANN_STAGE_SCORE, a.stream);
+    const Plan &p = a.plan;
+    const int32_t *M_dev = &((const Ctrl *)(a.ws + p.off_ctrl))->M;
+    if (a.m->kernel == MLP_MFMA2)
+        return launch_mlp_mfma(a.g, a.m, (const float *)(a.ws + p.off_upre), (const int32_t *)(a.ws + p.off_pair_q),
+                               (const int32_t *)(a.ws + p.off_pair_id), M_dev, p.M_max, p.Q,
+                               (float *)(a.ws + p.off_scores), 0, a.stream);
+    return launch_mlp_alu(a.g, a.m, a.queries, (const int32_t *)(a.ws + p.off_pair_q),
+                          (const int32_t *)(a.ws + p.off_pair_id), M_dev, p.M_max, p.Q,
+                          (float *)(a.ws + p.off_scores), 0, a.stream);
+}
+
+static int run_search(SearchArgs &a) {
+    const Plan &p = a.plan;
+    int rc;
+    if (p.Q == 0) return ANN_OK;
+    if (a.m->kernel == MLP_MFMA2)
+        if ((rc = launch_user_pre(a.m, a.queries, p.Q, (float *)(a.ws + p.off_upre), a.stream)) != ANN_OK) return rc;
+    {
+        StageTimer timer(ANN_STAGE_ROUND, a.stream);
+        if ((rc = launch_init(a)) != ANN_OK) return rc;
+    }
+    const bool capped = p.max_iters_max > 0;
+    int32_t *host_ctrl = nullptr;
+    if (!capped) {
+        host_ctrl = pinned_ctrl();
+        if (!host_ctrl) {
+            set_error("pinned host allocation failed");
+            return ANN_ENOMEM;
+        }
+    }
+    const int check_every = 4;
+    bool overflow_seen = false;
+    // a query expands only ids it has scored, so it cannot run more rounds than its visited
+    // table holds ids: the loop is bounded even if no query ever reported convergence
+    const int64_t round_limit = capped ? (int64_t)p.max_iters_max : (int64_t)p.hash_cap / 2 + 1;
+    for (int64_t i = 0; i <= round_limit; ++i) {
+        {
+            StageTimer timer(ANN_STAGE_PACK, a.stream);
+            if ((rc = launch_scan_compact(a)) != ANN_OK) return rc;
+        }
+        if (!capped && i > 0 && (i % check_every) == 0) {
+            ANN_HIP_TRY(hipMemcpyAsync(host_ctrl, a.ws + p.off_ctrl, 16, hipMemcpyDeviceToHost, a.stream));
+            ANN_HIP_TRY(hipStreamSynchronize(a.stream));
+            if (host_ctrl[1] == 0) break;  // no query is running: nothing left to score or merge
+        }
+        if ((rc = score_batch(a)) != ANN_OK) return rc;
+        {
+            StageTimer timer(ANN_STAGE_ROUND, a.stream);
+            if ((rc = launch_round(a)) != ANN_OK) return rc;
+        }
+    }
+    if ((rc = launch_emit(a)) != ANN_OK) return rc;
+    if (!capped) {
+        int64_t stats[8];
+        ANN_HIP_TRY(hipMemcpyAsync(stats, a.ws + p.off_stats, sizeof(stats), hipMemcpyDeviceToHost, a.stream));
+        ANN_HIP_TRY(hipStreamSynchronize(a.stream));
+        overflow_seen = stats[3] > 0;
+        if (overflow_seen) {
+            set_error("%lld queries filled their visited table (sized for %d rounds) and stopped early",
+                      (long long)stats[3], p.rounds_assumed);
+            return ANN_EWORKSPACE;
+        }
+    }
+    return ANN_OK;
+}
+
+}  // namespace gmpgr
+
+using namespace gmpgr;
+
+extern "C" {
+
+const char *ann_last_error(void) { return g_err; }
+
+__global__ void validate_adj_kernel(const int32_t *adj, int64_t n, int64_t N, int *bad) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t step = (int64_t)gridDim.x * blockDim.x;
+    int found = 0;
+    for (; i < n; i += step)
+        if ((int64_t)adj[i] >= N) found = 1;
+    if (found) atomicOr(bad, 1);
+}
+
+int ann_graph_load(const int32_t *adj_dev, const void *emb_dev, int64_t N, int32_t R, int32_t d, int32_t dtype,
+                   uint32_t flags, void *stream, ann_graph **out) {
+    if (!out) {
+        set_error("out is null");
+        return ANN_EINVAL;
+    }
+    *out = nullptr;
+    if (!adj_dev || !emb_dev) {
+        set_error("adj_dev and emb_dev must not be null");
+        return ANN_EINVAL;
+    }
+    if (N < 1 || N >= (1ll << 31) || R < 1 || R > 64 || d < 1 || d > 1024) {
+        set_error("need 1 <= N < 2^31, 1 <= R <= 64, 1 <= d <= 1024 (got N=%lld R=%d d=%d)", (long long)N, R, d);
+        return ANN_EINVAL;
+    }
+    if (dtype != ANN_F32 && dtype != ANN_BF16) {
+        set_error("dtype must be ANN_F32 or ANN_BF16");
+        return ANN_EINVAL;
+    }
+    if (((uintptr_t)adj_dev & 3) || ((uintptr_t)emb_dev & 3)) {
+        set_error("adj_dev and emb_dev must be 4-byte aligned");
+        return ANN_EINVAL;
+    }
+    if (flags & ANN_VALIDATE) {
+        int *bad = nullptr;
+        hipStream_t s = (hipStream_t)stream;
+        ANN_HIP_TRY(hipMalloc((void **)&bad, sizeof(int)));
+        hipError_t e = hipMemsetAsync(bad, 0, sizeof(int), s);
+        int h = 0;
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(validate_adj_kernel, dim3(2048), dim3(256), 0, s, adj_dev, N * R, N, bad);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipMemcpyAsync(&h, bad, sizeof(int), hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        (void)hipFree(bad);
+        if (e != hipSuccess) {
+            set_error("adjacency validation failed: %s", hipGetErrorString(e));
+            return ANN_EDEVICE;
+        }
+        if (h) {
+            set_error("adjacency holds an id >= N");
+            return ANN_EINVAL;
+        }
+    }
+    ann_graph *g = new (std::nothrow) ann_graph;
+    if (!g) {
+        set_error("out of host memory");
+        return ANN_ENOMEM;
+    }
+    g->adj = adj_dev;
+    g->emb = emb_dev;
+    g->N = N;
+    g->R = R;
+    g->d = d;
+    g->dtype = dtype;
+    *out = g;
+    return ANN_OK;
+}
+
+void ann_graph_free(ann_graph *g) { delete g; }
+
+int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *W_host, const float *const *b_host,
+                 const float *head_w_host, int32_t d_user, int32_t dtype, uint32_t flags, void *stream,
+                 ann_mlp **out) {
+    if (!out) {
+        set_error("out is null");
+        return ANN_EINVAL;
+    }
+    *out = nullptr;
+    if (!dims_host || !W_host || !b_host || !head_w_host) {
+        set_error("dims_host, W_host, b_host and head_w_host must not be null");
+        return ANN_EINVAL;
+    }
+    if (n_layers < 1 || n_layers > MAX_LAYERS) {
+        set_error("need 1 <= n_layers <= %d", MAX_LAYERS);
+        return ANN_EINVAL;
+    }
+    if (dtype != ANN_F32 && dtype != ANN_BF16) {
+        set_error("dtype must be ANN_F32 or ANN_BF16");
+        return ANN_EINVAL;
+    }
+    for (int l = 0; l <= n_layers; ++l)
+        if (dims_host[l] < 1 || dims_host[l] > MAX_WIDTH) {
+            set_error("layer width %d out of [1, %d]", dims_host[l], MAX_WIDTH);
+            return ANN_EINVAL;
+        }
+    const int J = dims_host[n_layers];
+    if (J > MAX_HEADS) {
+        set_error("at most %d heads", MAX_HEADS);
+        return ANN_EINVAL;
+    }
+    if (d_user < 1 || d_user >= dims_host[0]) {
+        set_error("need 1 <= d_user < dims[0]");
+        return ANN_EINVAL;
+    }
+    for (int l = 0; l < n_layers; ++l)
+        if (!W_host[l] || !b_host[l]) {
+            set_error("layer %d has a null weight or bias array", l);
+            return ANN_EINVAL;
+        }
+    hipStream_t s = (hipStream_t)stream;
+    ann_mlp *m = new (std::nothrow) ann_mlp;
+    if (!m) {
+        set_error("out of host memory");
+        return ANN_ENOMEM;
+    }
+    memset(m, 0, sizeof(*m));
+    m->n_layers = n_layers;
+    for (int l = 0; l <= n_layers; ++l) m->dims[l] = dims_host[l];
+    m->d_user = d_user;
+    m->d_item = dims_host[0] - d_user;
+    m->dtype = dtype;
+    m->J = J;
+    for (int j = 0; j < J; ++j) m->head_w[j] = head_w_host[j];
+    if (hipGetDevice(&m->device) != hipSuccess) m->device = 0;
+    const size_t es = dtype == ANN_BF16 ? 2 : 4;
+    int64_t wtot = 0;
+    int32_t btot = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        m->w_off[l] = wtot;
+        m->b_off[l] = btot;
+        wtot += (int64_t)dims_host[l] * dims_host[l + 1];
+        wtot = (wtot + 63) & ~63ll;  // keep every layer 128-byte aligned
+        btot += (dims_host[l + 1] + 63) & ~63;
+    }
+    std::vector<unsigned char> wbuf((size_t)wtot * es, 0);
+    std::vector<float> bbuf((size_t)btot, 0.f);
+    for (int l = 0; l < n_layers; ++l) {
+        memcpy(wbuf.data() + (size_t)m->w_off[l] * es, W_host[l], (size_t)dims_host[l] * dims_host[l + 1] * es);
+        memcpy(bbuf.data() + m->b_off[l], b_host[l], (size_t)dims_host[l + 1] * sizeof(float));
+    }
+    int rc = ANN_OK;
+    auto fail = [&](int code) {
+        ann_mlp_free(m);
+        return code;
+    };
+    if (hipMalloc(&m->W_dev, wbuf.size()) != hipSuccess || hipMalloc((void **)&m->b_dev, bbuf.size() * 4) != hipSuccess ||
+        hipMalloc((void **)&m->head_w_dev, MAX_HEADS * 4) != hipSuccess) {
+        set_error("device allocation for the metric failed");
+        return fail(ANN_ENOMEM);
+    }
+    if (hipMemcpyAsync(m->W_dev, wbuf.data(), wbuf.size(), hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(m->b_dev, bbuf.data(), bbuf.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(m->head_w_dev, m->head_w, MAX_HEADS * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess) {
+        set_error("copy of the metric to the device failed");
+        return fail(ANN_EDEVICE);
+    }
+    m->kernel = MLP_ALU;
+    if (!(flags & ANN_MLP_GENERIC) && mfma_supported(m->dims, n_layers, d_user, dtype)) {
+        rc = build_mfma_fragments(m, W_host, s);
+        if (rc != ANN_OK) return fail(rc);
+        m->kernel = MLP_MFMA2;
+    }
+    *out = m;
+    return ANN_OK;
+}
+
+void ann_mlp_free(ann_mlp *m) {
+    if (!m) return;
+    if (m->W_dev) (void)hipFree(m->W_dev);
+    if (m->b_dev) (void)hipFree(m->b_dev);
+    if (m->head_w_dev) (void)hipFree(m->head_w_dev);
+    if (m->frag_dev) (void)hipFree(m->frag_dev);
+    delete m;
+}
+
+int ann_mlp_uses_mfma(const ann_mlp *m) { return m && m->kernel != MLP_ALU; }
+
+size_t ann_search_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32_t W_max,
+                                  int32_t L_max, int32_t k, int32_t max_iters_max) {
+    Plan p;
+    if (!make_plan(g, m, Q, E, W_max, L_max, k, max_iters_max, &p)) return 0;
+    return p.total;
+}
+
+static int search_common(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
+                         const int32_t *entry_dev, int32_t E, const int32_t *W_q, const int32_t *L_q,
+                         const int32_t *cap_q, int32_t W, int32_t L, int32_t k, int32_t max_iters, void *workspace_dev,
+                         size_t workspace_bytes, int32_t *out_ids_dev, float *out_scores_dev, void *stream) {
+    SearchArgs a;
+    if (!make_plan(g, m, Q, E, W, L, k, max_iters, &a.plan)) return ANN_EINVAL;
+    if (Q > 0 && (!queries_dev || !entry_dev || !out_ids_dev || !out_scores_dev)) {
+        set_error("queries_dev, entry_dev, out_ids_dev and out_scores_dev must not be null");
+        return ANN_EINVAL;
+    }
+    if (Q > 0 && (!workspace_dev || ((uintptr_t)workspace_dev & 255))) {
+        set_error("workspace_dev must be a 256-byte aligned device pointer");
+        return ANN_EINVAL;
+    }
+    if (workspace_bytes < a.plan.total) {
+        set_error("workspace holds %zu bytes, %zu needed", workspace_bytes, a.plan.total);
+        return ANN_EWORKSPACE;
+    }
+    a.g = g;
+    a.m = m;
+    a.queries = queries_dev;
+    a.entries = entry_dev;
+    a.W_q = W_q;
+    a.L_q = L_q;
+    a.cap_q = cap_q;
+    a.W = W;
+    a.L = L;
+    a.cap = max_iters;
+    a.ws = (char *)workspace_dev;
+    a.out_ids = out_ids_dev;
+    a.out_scores = out_scores_dev;
+    a.stream = (hipStream_t)stream;
+    return run_search(a);
+}
+
+int ann_search(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, const int32_t *entry_dev,
+               int32_t E, int32_t W, int32_t L, int32_t k, int32_t max_iters, void *workspace_dev,
+               size_t workspace_bytes, int32_t *out_ids_dev, float *out_scores_dev, void *stream) {
+    return search_common(g, m, queries_dev, Q, entry_dev, E, nullptr, nullptr, nullptr, W, L, k, max_iters,
+                         workspace_dev, workspace_bytes, out_ids_dev, out_scores_dev, stream);
+}
+
+int ann_search_ragged(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
+                      const int32_t *entry_dev, int32_t E, const int32_t *W_q_dev, const int32_t *L_q_dev,
+                      const int32_t *iters_q_dev, int32_t W_max, int32_t L_max, int32_t k, int32_t max_iters_max,
+                      void *workspace_dev, size_t workspace_bytes, int32_t *out_ids_dev, float *out_scores_dev,
+                      void *stream) {
+    if (Q > 0 && (!W_q_dev || !L_q_dev || !iters_q_dev)) {
+        set_error("W_q_dev, L_q_dev and iters_q_dev must not be null");
+        return ANN_EINVAL;
+    }
+    return search_common(g, m, queries_dev, Q, entry_dev, E, W_q_dev, L_q_dev, iters_q_dev, W_max, L_max, k,
+                         max_iters_max, workspace_dev, workspace_bytes, out_ids_dev, out_scores_dev, stream);
+}
+
+int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int64_t M,
+                    const int32_t *q_idx_dev, const int32_t *item_dev, float *out_dev, int32_t tile_rows,
+                    void *stream) {
+    if (!g || !m) {
+        set_error("null graph or metric handle");
+        return ANN_EINVAL;
+    }
+    if (m->d_item != g->d || m->dtype != g->dtype) {
+        set_error("metric (item width %d, dtype %d) does not match graph (%d, %d)", m->d_item, m->dtype, g->d,
+                  g->dtype);
+        return ANN_EINVAL;
+    }
+    if (M < 0 || M > 0x7fffffffll || Q < 1 || tile_rows < 0) {
+        set_error("need 0 <= M < 2^31, Q >= 1, tile_rows >= 0");
+        return ANN_EINVAL;
+    }
+    if (M == 0) return ANN_OK;
+    if (!queries_dev || !q_idx_dev || !item_dev || !out_dev) {
+        set_error("queries_dev, q_idx_dev, item_dev and out_dev must not be null");
+        return ANN_EINVAL;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (m->kernel != MLP_MFMA2)
+        return launch_mlp_alu(g, m, queries_dev, q_idx_dev, item_dev, nullptr, M, Q, out_dev, tile_rows, s);
+    char *tmp = nullptr;
+    size_t upre_bytes = (size_t)Q * m->dims[1] * sizeof(float);
+    if (hipMalloc((void **)&tmp, 256 + upre_bytes) != hipSuccess) {
+        set_error("device allocation of %zu bytes failed", 256 + upre_bytes);
+        return ANN_ENOMEM;
+    }
+    int32_t M32 = (int32_t)M;
+    int rc = ANN_OK;
+    hipError_t e = hipMemcpyAsync(tmp, &M32, 4, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) {
+        set_error("hipMemcpyAsync failed: %s", hipGetErrorString(e));
+        rc = ANN_EDEVICE;
+    }
+    if (rc == ANN_OK) rc = launch_user_pre(m, queries_dev, Q, (float *)(tmp + 256), s);
+    if (rc == ANN_OK)
+        rc = launch_mlp_mfma(g, m, (const float *)(tmp + 256), q_idx_dev, item_dev, (const int32_t *)tmp, M, Q,
+                             out_dev, tile_rows, s);
+    e = hipStreamSynchronize(s);
+    if (rc == ANN_OK && e != hipSuccess) {
+        set_error("hipStreamSynchronize failed: %s", hipGetErrorString(e));
+        rc = ANN_EDEVICE;
+    }
+    (void)hipFree(tmp);
+    return rc;
+}
+
+int ann_profile_enable(int on) {
+    g_prof.on = on != 0;
+    g_prof.used = 0;
+    return ANN_OK;
+}
+
+int ann_profile_read(double *ms_out, int64_t *launches_out) {
+    if (!ms_out || !launches_out) {
+        set_error("ms_out and launches_out must not be null");
+        return ANN_EINVAL;
+    }
+    for (int i = 0; i < ANN_STAGE_COUNT; ++i) {
+        ms_out[i] = 0.0;
+        launches_out[i] = 0;
+    }
+    for (size_t i = 0; i < g_prof.used; ++i) {
+        ANN_HIP_TRY(hipEventSynchronize(g_prof.events[2 * i + 1]));
+        float ms = 0.f;
+        ANN_HIP_TRY(hipEventElapsedTime(&ms, g_prof.events[2 * i], g_prof.events[2 * i + 1]));
+        ms_out[g_prof.stage[i]] += ms;
+        launches_out[g_prof.stage[i]] += 1;
+    }
+    g_prof.used = 0;
+    return ANN_OK;
+}
+
+int ann_search_stats(const void *workspace_dev, ann_stats *out_host, void *stream) {
+    if (!workspace_dev || !out_host) {
+        set_error("workspace_dev and out_host must not be null");
+        return ANN_EINVAL;
+    }
+    int64_t st[8];
+    hipStream_t s = (hipStream_t)stream;
+    ANN_HIP_TRY(hipMemcpyAsync(st, (const char *)workspace_dev + STATS_OFFSET, sizeof(st), hipMemcpyDeviceToHost, s));
+    ANN_HIP_TRY(hipStreamSynchronize(s));
+    out_host->pairs_scored = st[0];
+    out_host->nodes_expanded = st[1];
+    out_host->max_query_iters = st[2];
+    out_host->visited_overflow = st[3];
+    out_host->queries = st[4];
+    return ANN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,128 @@
+// Shared declarations of the HIP library: handles, workspace plan, kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/gmpgr_ann.h"
+
+namespace gmpgr {
+
+constexpr int MAX_LAYERS = 8;
+constexpr int MAX_WIDTH = 2048;
+constexpr int MAX_HEADS = 8;
+constexpr int MAX_WR = 1024;        // W*R survivors per query and round
+constexpr int MAX_SORT = 4096;      // max(L,k) + W*R entries sorted in LDS
+constexpr int MAX_E = 1024;
+constexpr uint32_t EMPTY_SLOT = 0xFFFFFFFFu;
+constexpr uint64_t KEY_SENTINEL = 0xFFFFFFFFFFFFFFFFull;
+
+void set_error(const char *fmt, ...);
+
+#define ANN_HIP_TRY(expr)                                                                \
+    do {                                                                                 \
+        hipError_t _e = (expr);                                                          \
+        if (_e != hipSuccess) {                                                          \
+            gmpgr::set_error("%s failed: %s", #expr, hipGetErrorString(_e));             \
+            return ANN_EDEVICE;                                                          \
+        }                                                                                \
+    } while (0)
+
+}  // namespace gmpgr
+
+struct ann_graph {
+    const int32_t *adj;
+    const void *emb;
+    int64_t N;
+    int32_t R, d, dtype;
+};
+
+// Which fused kernel serves the metric.
+enum MlpKernel { MLP_ALU = 0, MLP_MFMA2 = 1 /* two hidden layers, bf16 */ };
+
+struct ann_mlp {
+    int32_t n_layers;
+    int32_t dims[gmpgr::MAX_LAYERS + 1];
+    int32_t d_user, d_item, dtype, J;
+    int32_t kernel;        // MlpKernel
+    // plain copies, layer l at w_off[l] (elements) in W_dev, b_off[l] in b_dev
+    void *W_dev;           // fp32 or bf16, [out][in] row-major per layer
+    float *b_dev;
+    float *head_w_dev;
+    int64_t w_off[gmpgr::MAX_LAYERS];
+    int32_t b_off[gmpgr::MAX_LAYERS];
+    float head_w[gmpgr::MAX_HEADS];
+    // MFMA path: fragment-ordered bf16 copies (see mlp_mfma.hip)
+    void *frag_dev;        // W1 item half, W2, W_last (padded to 32 rows), in fragment order
+    int64_t frag_bytes;
+    int device;
+};
+
+namespace gmpgr {
+
+// Device workspace layout; every offset is in bytes from the workspace base, 256-aligned.
+struct Plan {
+    int32_t Q, E, W_max, L_max, k, C, R, max_iters_max, rounds_assumed;
+    int32_t slots;          // survivors kept per query and round: max(W_max*R, E)
+    int32_t hash_cap;       // per-query visited table entries (power of two)
+    int32_t sort_n;         // power of two >= C + slots
+    int64_t M_max;          // Q * slots
+    int32_t H1;             // first hidden width (user-half pre-activations), 0 if unused
+    size_t off_ctrl, off_state, off_pool, off_hash, off_cand, off_counts, off_offsets,
+        off_pair_q, off_pair_id, off_scores, off_upre, off_stats;
+    size_t total;
+};
+
+// Control block at off_ctrl (device), 64 int32.
+struct Ctrl {
+    int32_t M;            // pairs in the current round
+    int32_t n_active;     // queries not finished
+    int32_t pad[14];
+};
+
+// Per-query state at off_state.
+struct QState {
+    int32_t t;            // rounds done
+    int32_t done;         // 1 = finished
+    int32_t n_list;       // entries in the list
+    int32_t n_visited;    // ids in the visited table
+    int32_t W, L, cap;    // this query's parameters
+    int32_t overflow;
+};
+
+bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32_t W_max,
+               int32_t L_max, int32_t k, int32_t max_iters_max, Plan *p);
+
+struct SearchArgs {
+    const ann_graph *g;
+    const ann_mlp *m;
+    const void *queries;
+    const int32_t *entries;
+    const int32_t *W_q, *L_q, *cap_q;  // null = uniform
+    int32_t W, L, cap;
+    char *ws;
+    Plan plan;
+    int32_t *out_ids;
+    float *out_scores;
+    hipStream_t stream;
+};
+
+// search_kernels.hip
+int launch_init(const SearchArgs &a);
+int launch_scan_compact(const SearchArgs &a);
+int launch_round(const SearchArgs &a);
+int launch_emit(const SearchArgs &a);
+
+// mlp_alu.hip / mlp_mfma.hip: score `*M_dev` (<= M_max) pairs; M_dev is read on the device.
+int launch_mlp_alu(const ann_graph *g, const ann_mlp *m, const void *queries, const int32_t *pair_q,
+                   const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
+                   int32_t tile_rows, hipStream_t stream);
+int launch_user_pre(const ann_mlp *m, const void *queries, int32_t Q, float *upre, hipStream_t stream);
+int launch_mlp_mfma(const ann_graph *g, const ann_mlp *m, const float *upre, const int32_t *pair_q,
+                    const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
+                    int32_t tile_rows, hipStream_t stream);
+bool mfma_supported(const int32_t *dims, int32_t n_layers, int32_t d_user, int32_t dtype);
+int build_mfma_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream);
+
+}  // namespace gmpgr

@@ -1,0 +1,351 @@
+// Relevance metric of Sec. 3.1 (1), Eq. 5-8, as fused bf16 MFMA GEMM chains on gfx950.
+//
+// The dense pair list produced by the packing step (Algorithm 2) is cut into batches of
+// TILE pairs; a workgroup of four waves takes one batch, each wave owns RW = 32*CB pairs of
+// it and carries them through ALL layers without the activations ever leaving registers.
+//
+// Transposed formulation.  Every layer is computed as  H_out^T = W * H_in^T  with
+// v_mfma_f32_32x32x16_bf16: the weights are the A operand (32 output units x 16 inputs), the
+// activations of 32 pairs are the B operand (16 inputs x 32 pairs).  In the D layout a lane
+// holds, for ITS pair (lane % 32), output units  8*(i/4) + 4*(lane/32) + i%4  (i = 0..15).
+// Since the contraction index of the next layer may be visited in any order, those 16 values
+// (ReLU, rounded to bf16) ARE two B operands of the next layer, provided its weights are
+// stored in the matching input order.  ann_mlp_load writes the weights once in exactly the
+// order the lanes read them ("fragment order": 1 KB = 64 lanes x 8 bf16 per MFMA operand).
+//
+// Layer 1 is split as  W1 [u ; v] + b1 = (W1_user u + b1) + W1_item v  (Eq. 5, 7): the first
+// term depends on the query only and is computed once per search (user_pre_kernel, fp32);
+// it initialises the layer-1 accumulators, so only the item half is contracted per pair.
+//
+// Weights do not fit in registers and (for the largest metric) not in LDS either: they are
+// streamed through LDS in chunks, chunk nb = the 32 layer-1 units nb*32.. and the slab of
+// layer-2 weights that consumes exactly those units, double buffered; when all chunks fit
+// they are loaded once and stay resident.
+//
+// Numerics (bf16 mode of the library): bf16 inputs and weights, fp32 accumulation inside the
+// MFMA, hidden activations rounded to bf16 (nearest even) after ReLU, head logits, sigmoid
+// and the weighted sum (Eq. 8) in fp32.
+#include <vector>
+
+#include "common.h"
+
+namespace gmpgr {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int MF_BLOCK = 256;
+constexpr int MF_WAVES = 4;
+
+// Register plan.  The layer-2 accumulators of a wave fill all 256 accumulation registers
+// (AGPRs) for the whole batch; the compiler keeps the destination of every MFMA it selects
+// itself in AGPRs, which is right for layer 2 but leaves no room for the short-lived layer-1
+// and head accumulators.  Those two use mfma_vgpr(): the same instruction written as inline
+// assembly with the accumulator pinned to ordinary VGPRs.  The hazard rules the compiler
+// would otherwise enforce are kept by hand there:
+//   - a VGPR written by a vector-ALU instruction may not be read by an MFMA in the next two
+//     issue slots: every mfma_vgpr starts with s_nop 1;
+//   - an accumulator is never used by two consecutive MFMAs: callers alternate two of them;
+//   - the vector ALU may read an MFMA result only after the MFMA has drained: mfma_drain().
+__device__ __forceinline__ void mfma_vgpr(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_drain(f32x16 &x, f32x16 &y) {
+    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(x), "+v"(y));
+}
+
+__device__ __forceinline__ bf16x8 relu_pack(const f32x16 &acc, int half) {
+    f32x8 v;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = fmaxf(acc[half * 8 + j], 0.f);
+    return __builtin_convertvector(v, bf16x8);
+}
+
+// upre[q][n] = b1[n] + sum_{i < d_user} W1[n][i] * u_q[i]   (fp32 FMA chain in index order)
+__global__ void __launch_bounds__(256)
+user_pre_kernel(const uint16_t *__restrict__ W1, int n_in, int d_user, int H1, const float *__restrict__ b1,
+                const uint16_t *__restrict__ users, int Q, float *__restrict__ upre) {
+    extern __shared__ float u_s[];
+    const int q = blockIdx.x;
+    for (int i = threadIdx.x; i < d_user; i += blockDim.x)
+        u_s[i] = __uint_as_float(((uint32_t)users[(size_t)q * d_user + i]) << 16);
+    __syncthreads();
+    for (int n = threadIdx.x; n < H1; n += blockDim.x) {
+        float acc = b1[n];
+        const uint16_t *row = W1 + (size_t)n * n_in;
+        for (int i = 0; i < d_user; ++i) acc = fmaf(__uint_as_float(((uint32_t)row[i]) << 16), u_s[i], acc);
+        upre[(size_t)q * H1 + n] = acc;
+    }
+}
+
+// Fragment-ordered weights, all bf16, 1 KB per fragment (lane l at byte 16*l):
+//   chunk nb (nb < H1/32), CHUNK = (D/16 + 2*H2/32) fragments:
+//     [s < D/16]            lane (m,g): W1_item[nb*32+m][16s + 8g + j],                  j < 8
+//     [D/16 + 2*n2 + s2]    lane (m,g): W2[n2*32+m][nb*32 + 16*s2 + 8*(j/4) + 4g + j%4], j < 8
+//   then the head layer, H2/16 fragments, rows >= J are zero:
+//     [2*n2 + s2]           lane (m,g): W3[m][n2*32 + 16*s2 + 8*(j/4) + 4g + j%4]
+template <int D, int H1, int H2, int CB, bool RESIDENT>
+__global__ void __launch_bounds__(MF_BLOCK)
+mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__restrict__ upre,
+                 const uint4 *__restrict__ frag, const float *__restrict__ b2, const float *__restrict__ b3,
+                 const float *__restrict__ head_w, int J, const int32_t *__restrict__ pair_q,
+                 const int32_t *__restrict__ pair_id, const int32_t *__restrict__ M_dev, int64_t M_max, int32_t Q,
+                 float *__restrict__ scores) {
+    constexpr int KS1 = D / 16, NB1 = H1 / 32, NB2 = H2 / 32;
+    constexpr int CHUNK_FR = KS1 + 2 * NB2;          // fragments per chunk
+    constexpr int CHUNK_U4 = CHUNK_FR * 64;          // uint4 per chunk
+    constexpr int W3_FR = 2 * NB2;
+    constexpr int RW = 32 * CB, TILE = RW * MF_WAVES;
+    constexpr int NBUF = RESIDENT ? NB1 : 2;
+    constexpr int ST = (CHUNK_U4 + MF_BLOCK - 1) / MF_BLOCK;  // staged uint4 per thread and chunk
+    extern __shared__ __align__(16) uint4 lds[];
+    uint4 *wbuf = lds;                                // [NBUF][CHUNK_U4]
+    uint4 *w3buf = lds + (size_t)NBUF * CHUNK_U4;     // [W3_FR * 64]
+
+    int64_t M = (int64_t)*M_dev;
+    if (M > M_max) M = M_max;
+    const int64_t n_tiles = (M + TILE - 1) / TILE;
+    if ((int64_t)blockIdx.x >= n_tiles) return;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int g = lane >> 5, col = lane & 31;
+
+    // head-layer fragments, and either every chunk (resident) or chunk 0
+    for (int i = threadIdx.x; i < W3_FR * 64; i += MF_BLOCK) w3buf[i] = frag[(size_t)NB1 * CHUNK_U4 + i];
+    {
+        const int n_pre = RESIDENT ? NB1 * CHUNK_U4 : CHUNK_U4;
+        for (int i = threadIdx.x; i < n_pre; i += MF_BLOCK) wbuf[i] = frag[i];
+    }
+    __syncthreads();
+
+    float hw[4], bb3[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int j = 4 * g + i;
+        hw[i] = j < J ? head_w[j] : 0.f;
+        bb3[i] = j < J ? b3[j] : 0.f;
+    }
+
+    int cur = 0;
+#pragma unroll 1
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t row0 = tile * TILE + (int64_t)wave * RW;
+        bf16x8 xf[CB][KS1];
+        const float *up[CB];
+        bool bad[CB];
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            int64_t row = row0 + c * 32 + col;
+            int32_t v = 0, q = 0;
+            if (row < M) {
+                v = pair_id[row];
+                q = pair_q[row];
+            }
+            bad[c] = (v < 0 || (int64_t)v >= N || q < 0 || q >= Q);
+            if (bad[c]) v = 0, q = 0;
+            const bf16x8 *src = (const bf16x8 *)(emb + (size_t)v * D) + g;
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) xf[c][s] = src[2 * s];
+            up[c] = upre + (size_t)q * H1 + 4 * g;
+        }
+        f32x16 acc2[NB2][CB];
+#pragma unroll
+        for (int n2 = 0; n2 < NB2; ++n2) {
+            f32x16 init;
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) {
+                f32x4 bv = *(const f32x4 *)(b2 + n2 * 32 + 8 * t4 + 4 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) init[4 * t4 + e] = bv[e];
+            }
+#pragma unroll
+            for (int c = 0; c < CB; ++c) acc2[n2][c] = init;
+        }
+
+#pragma unroll 1
+        for (int nb = 0; nb < NB1; ++nb) {
+            const uint4 *wc = wbuf + (size_t)(RESIDENT ? nb : cur) * CHUNK_U4;
+            uint4 stage[ST];
+            if (!RESIDENT) {
+                const int nxt = (nb + 1 == NB1) ? 0 : nb + 1;
+                const uint4 *srcw = frag + (size_t)nxt * CHUNK_U4;
+#pragma unroll
+                for (int t = 0; t < ST; ++t) {
+                    int i = threadIdx.x + t * MF_BLOCK;
+                    if (i < CHUNK_U4) stage[t] = srcw[i];
+                }
+            }
+            // layer 1, units nb*32 .. nb*32+31: accumulators start from the per-query user term
+            f32x16 acc1[CB];
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+#pragma unroll
+                for (int t4 = 0; t4 < 4; ++t4) {
+                    f32x4 pv = *(const f32x4 *)(up[c] + nb * 32 + 8 * t4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc1[c][4 * t4 + e] = pv[e];
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) {
+                bf16x8 a = *(const bf16x8 *)(wc + s * 64 + lane);
+#pragma unroll
+                for (int c = 0; c < CB; ++c) mfma_vgpr(acc1[c], a, xf[c][s]);
+            }
+            mfma_drain(acc1[CB - 1], acc1[CB - 2]);
+            bf16x8 hf[CB][2];
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                hf[c][0] = relu_pack(acc1[c], 0);
+                hf[c][1] = relu_pack(acc1[c], 1);
+            }
+            // layer 2: every output unit consumes these 32 hidden units
+#pragma unroll
+            for (int n2 = 0; n2 < NB2; ++n2) {
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    bf16x8 a = *(const bf16x8 *)(wc + (KS1 + 2 * n2 + s2) * 64 + lane);
+#pragma unroll
+                    for (int c = 0; c < CB; ++c)
+                        acc2[n2][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, hf[c][s2], acc2[n2][c], 0, 0, 0);
+                }
+            }
+            if (!RESIDENT) {
+                uint4 *dst = wbuf + (size_t)(cur ^ 1) * CHUNK_U4;
+#pragma unroll
+                for (int t = 0; t < ST; ++t) {
+                    int i = threadIdx.x + t * MF_BLOCK;
+                    if (i < CHUNK_U4) dst[i] = stage[t];
+                }
+                __syncthreads();
+                cur ^= 1;
+            }
+        }
+
+        // head layer (rows >= J of the fragments are zero), then Eq. 8
+        static_assert(CB >= 2, "two accumulators must alternate");
+        f32x16 acc3[CB];
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc3[c][i] = 0.f;
+#pragma unroll
+        for (int n2 = 0; n2 < NB2; ++n2) {
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                bf16x8 a = *(const bf16x8 *)(w3buf + (2 * n2 + s2) * 64 + lane);
+#pragma unroll
+                for (int c = 0; c < CB; ++c) mfma_vgpr(acc3[c], a, relu_pack(acc2[n2][c], s2));
+            }
+        }
+        mfma_drain(acc3[CB - 1], acc3[CB - 2]);
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            float part = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) part = fmaf(hw[i], 1.0f / (1.0f + expf(-(acc3[c][i] + bb3[i]))), part);
+            float other = __shfl_xor(part, 32);
+            int64_t row = row0 + c * 32 + col;
+            if (g == 0 && row < M) scores[row] = bad[c] ? __uint_as_float(0x7fc00000u) : part + other;
+        }
+    }
+}
+
+struct MfmaShape {
+    int D, H1, H2;
+};
+
+bool mfma_supported(const int32_t *dims, int32_t n_layers, int32_t d_user, int32_t dtype) {
+    if (dtype != ANN_BF16 || n_layers != 3) return false;
+    int D = dims[0] - d_user, H1 = dims[1], H2 = dims[2], J = dims[3];
+    if (J < 1 || J > MAX_HEADS || d_user < 1) return false;
+    return (D == 128 && H1 == 512 && H2 == 256) || (D == 64 && H1 == 256 && H2 == 128);
+}
+
+static inline uint16_t w_at(const uint16_t *W, int n_in, int row, int colm) { return W[(size_t)row * n_in + colm]; }
+
+int build_mfma_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream) {
+    const int D = m->d_item, H1 = m->dims[1], H2 = m->dims[2], J = m->J, du = m->d_user;
+    const int KS1 = D / 16, NB1 = H1 / 32, NB2 = H2 / 32;
+    const int CHUNK_FR = KS1 + 2 * NB2;
+    const size_t n_frag = (size_t)NB1 * CHUNK_FR + 2 * NB2;
+    std::vector<uint16_t> buf(n_frag * 512, 0);
+    const uint16_t *W1 = (const uint16_t *)W_host[0], *W2 = (const uint16_t *)W_host[1],
+                   *W3 = (const uint16_t *)W_host[2];
+    for (int nb = 0; nb < NB1; ++nb) {
+        uint16_t *chunk = buf.data() + (size_t)nb * CHUNK_FR * 512;
+        for (int s = 0; s < KS1; ++s)
+            for (int l = 0; l < 64; ++l)
+                for (int j = 0; j < 8; ++j)
+                    chunk[(size_t)s * 512 + l * 8 + j] =
+                        w_at(W1, du + D, nb * 32 + (l & 31), du + 16 * s + 8 * (l >> 5) + j);
+        for (int n2 = 0; n2 < NB2; ++n2)
+            for (int s2 = 0; s2 < 2; ++s2)
+                for (int l = 0; l < 64; ++l)
+                    for (int j = 0; j < 8; ++j)
+                        chunk[(size_t)(KS1 + 2 * n2 + s2) * 512 + l * 8 + j] =
+                            w_at(W2, H1, n2 * 32 + (l & 31), nb * 32 + 16 * s2 + 8 * (j / 4) + 4 * (l >> 5) + j % 4);
+    }
+    uint16_t *head = buf.data() + (size_t)NB1 * CHUNK_FR * 512;
+    for (int n2 = 0; n2 < NB2; ++n2)
+        for (int s2 = 0; s2 < 2; ++s2)
+            for (int l = 0; l < 64; ++l)
+                for (int j = 0; j < 8; ++j)
+                    if ((l & 31) < J)
+                        head[(size_t)(2 * n2 + s2) * 512 + l * 8 + j] =
+                            w_at(W3, H2, l & 31, n2 * 32 + 16 * s2 + 8 * (j / 4) + 4 * (l >> 5) + j % 4);
+    m->frag_bytes = (int64_t)buf.size() * 2;
+    ANN_HIP_TRY(hipMalloc(&m->frag_dev, (size_t)m->frag_bytes));
+    ANN_HIP_TRY(hipMemcpyAsync(m->frag_dev, buf.data(), (size_t)m->frag_bytes, hipMemcpyHostToDevice, stream));
+    ANN_HIP_TRY(hipStreamSynchronize(stream));  // buf is freed on return
+    return ANN_OK;
+}
+
+int launch_user_pre(const ann_mlp *m, const void *queries, int32_t Q, float *upre, hipStream_t stream) {
+    if (Q <= 0) return ANN_OK;
+    hipLaunchKernelGGL(user_pre_kernel, dim3(Q), dim3(256), (size_t)m->d_user * sizeof(float), stream,
+                       (const uint16_t *)m->W_dev, m->dims[0], m->d_user, m->dims[1], m->b_dev,
+                       (const uint16_t *)queries, Q, upre);
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+template <int D, int H1, int H2, int CB, bool RESIDENT>
+static int launch_one(const ann_graph *g, const ann_mlp *m, const float *upre, const int32_t *pair_q,
+                      const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
+                      hipStream_t stream) {
+    constexpr int KS1 = D / 16, NB1 = H1 / 32, NB2 = H2 / 32;
+    constexpr int CHUNK_U4 = (KS1 + 2 * NB2) * 64;
+    constexpr int NBUF = RESIDENT ? NB1 : 2;
+    constexpr size_t smem = ((size_t)NBUF * CHUNK_U4 + 2 * NB2 * 64) * 16;
+    constexpr int TILE = 32 * CB * MF_WAVES;
+    static_assert(smem <= 160 * 1024, "LDS budget");
+    auto fn = mlp_mfma2_kernel<D, H1, H2, CB, RESIDENT>;
+    ANN_HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    int64_t tiles = (M_max + TILE - 1) / TILE;
+    int grid = (int)(tiles < 256 ? tiles : 256);
+    const float *b2 = m->b_dev + m->b_off[1], *b3 = m->b_dev + m->b_off[2];
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(MF_BLOCK), smem, stream, (const uint16_t *)g->emb, g->N, upre,
+                       (const uint4 *)m->frag_dev, b2, b3, m->head_w_dev, m->J, pair_q, pair_id, M_dev, M_max, Q,
+                       scores);
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+int launch_mlp_mfma(const ann_graph *g, const ann_mlp *m, const float *upre, const int32_t *pair_q,
+                    const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
+                    int32_t tile_rows, hipStream_t stream) {
+    (void)tile_rows;
+    if (M_max <= 0) return ANN_OK;
+    const int D = m->d_item, H1 = m->dims[1], H2 = m->dims[2];
+    if (D == 128 && H1 == 512 && H2 == 256)
+        return launch_one<128, 512, 256, 2, false>(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
+    if (D == 64 && H1 == 256 && H2 == 128)
+        return launch_one<64, 256, 128, 2, true>(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
+    set_error("no MFMA kernel for item width %d, hidden %d, %d", D, H1, H2);
+    return ANN_ENOTIMPL;
+}
+
+}  // namespace gmpgr

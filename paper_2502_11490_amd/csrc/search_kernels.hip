@@ -1,0 +1,450 @@
+// Per-query search state machine of the joint best-first search (Sec. 3.2, Algorithm 1)
+// and the packing of ragged survivor groups into one dense pair list (Algorithm 2).
+//
+// One workgroup owns one query in every kernel here: its sorted candidate list (the shared
+// container of Algorithm 1), its exact visited table and its survivors of the current round.
+// Per round:   scan_compact -> (MLP kernel) -> round
+//   round       : merge the scores of the previous round into the list, test termination,
+//                 pick <= W unexpanded entries among the first L ranks, read their adjacency
+//                 rows, drop out-of-range / repeated / already scored ids, keep the rest as
+//                 this query's survivors
+//   scan_compact: exclusive prefix sum of the survivor counts over all queries and a stable
+//                 copy of every group into the dense pair list (query-major, first-found
+//                 first), which the MLP kernel cuts into fixed-size batches
+#include "common.h"
+
+namespace gmpgr {
+
+constexpr int BLOCK = 256;
+constexpr int WAVES = BLOCK / 64;
+
+// ---- order-preserving key: ascending uint64 == (score descending, id ascending) ----------
+__device__ __forceinline__ uint64_t make_key(float score, int32_t id, uint32_t expanded) {
+    uint32_t f = __float_as_uint(score);
+    uint32_t asc = (f & 0x80000000u) ? ~f : (f | 0x80000000u);
+    return ((uint64_t)(~asc) << 32) | ((uint64_t)(uint32_t)id << 1) | expanded;
+}
+__device__ __forceinline__ float key_score(uint64_t key) {
+    uint32_t asc = ~(uint32_t)(key >> 32);
+    uint32_t f = (asc & 0x80000000u) ? (asc ^ 0x80000000u) : ~asc;
+    return __uint_as_float(f);
+}
+__device__ __forceinline__ int32_t key_id(uint64_t key) { return (int32_t)((uint32_t)key >> 1); }
+__device__ __forceinline__ uint32_t key_expanded(uint64_t key) { return (uint32_t)key & 1u; }
+
+__device__ __forceinline__ uint32_t hash_id(uint32_t id) { return id * 0x9E3779B1u; }
+
+// Exclusive prefix count of `flag` over the workgroup in thread order; *total = block sum.
+// wave_sums: LDS int[WAVES + 1].  Contains two barriers.
+__device__ __forceinline__ int block_excl_count(bool flag, int *wave_sums, int *total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long b = __ballot(flag);
+    int excl = __popcll(b & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_sums[wave] = __popcll(b);
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+        int c = wave_sums[w];
+        if (w < wave) base += c;
+        tot += c;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + excl;
+}
+
+// Ascending bitonic sort of keys[0..n) in LDS, n a power of two.
+__device__ void bitonic_sort(uint64_t *keys, int n) {
+    for (int k = 2; k <= n; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < (n >> 1); t += BLOCK) {
+                // t-th compare-exchange of this stage: indices i < ixj
+                int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                int ixj = i | j;
+                bool up = ((i & k) == 0);
+                uint64_t a = keys[i], b = keys[ixj];
+                if ((a > b) == up) {
+                    keys[i] = b;
+                    keys[ixj] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Drops ids that are out of range, repeated inside cand[0..n_cand) (first occurrence kept)
+// or already in this query's visited table; inserts the rest into the table and writes them,
+// in their order of occurrence, to out[0..n_new).  Returns n_new (same in every thread).
+//   cand      : LDS int32[n_cand]
+//   dd_key/dd_pos : LDS uint32[dd_n] each, dd_n a power of two >= 2 * n_cand
+//   table     : global uint32[hash_cap], EMPTY_SLOT = free; the caller guarantees that
+//               n_visited + n_cand <= hash_cap / 2, so probing always meets a free slot
+__device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_key, uint32_t *dd_pos,
+                                 int dd_n, uint32_t *table, int hash_cap, int64_t N, int32_t *out,
+                                 int *wave_sums) {
+    for (int i = threadIdx.x; i < dd_n; i += BLOCK) {
+        dd_key[i] = EMPTY_SLOT;
+        dd_pos[i] = 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    const uint32_t dd_mask = (uint32_t)dd_n - 1u;
+    // pass 1: smallest position of every distinct id
+    for (int p = threadIdx.x; p < n_cand; p += BLOCK) {
+        int32_t v = cand[p];
+        if (v < 0 || (int64_t)v >= N) continue;
+        uint32_t s = hash_id((uint32_t)v) & dd_mask;
+        for (;;) {
+            uint32_t old = atomicCAS(&dd_key[s], EMPTY_SLOT, (uint32_t)v);
+            if (old == EMPTY_SLOT || old == (uint32_t)v) {
+                atomicMin(&dd_pos[s], (uint32_t)p);
+                break;
+            }
+            s = (s + 1u) & dd_mask;
+        }
+    }
+    __syncthreads();
+    // pass 2: first occurrences probe / insert into the visited table; survivors compacted
+    const uint32_t hmask = (uint32_t)hash_cap - 1u;
+    const int shift = 32 - (31 - __clz(hash_cap));  // hash_cap = 2^b -> top b bits
+    int n_new = 0;
+    for (int p0 = 0; p0 < n_cand; p0 += BLOCK) {
+        int p = p0 + threadIdx.x;
+        bool fresh = false;
+        int32_t v = -1;
+        if (p < n_cand) {
+            v = cand[p];
+            if (v >= 0 && (int64_t)v < N) {
+                uint32_t s = hash_id((uint32_t)v) & dd_mask;
+                while (dd_key[s] != (uint32_t)v) s = (s + 1u) & dd_mask;
+                if (dd_pos[s] == (uint32_t)p) {
+                    uint32_t h = (hash_cap > 1) ? (hash_id((uint32_t)v) >> shift) : 0u;
+                    for (;;) {
+                        uint32_t cur = table[h];
+                        if (cur == (uint32_t)v) break;  // scored in an earlier round
+                        if (cur == EMPTY_SLOT) {
+                            uint32_t old = atomicCAS(&table[h], EMPTY_SLOT, (uint32_t)v);
+                            if (old == EMPTY_SLOT) {
+                                fresh = true;
+                                break;
+                            }
+                            if (old == (uint32_t)v) break;
+                        }
+                        h = (h + 1u) & hmask;
+                    }
+                }
+            }
+        }
+        int tot;
+        int pos = block_excl_count(fresh, wave_sums, &tot);
+        if (fresh) out[n_new + pos] = v;
+        n_new += tot;
+    }
+    return n_new;
+}
+
+// Counters and control block start at zero (a kernel, not a memset, so that a caller may
+// capture the launch sequence into a HIP graph).
+__global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q) {
+    if (threadIdx.x < 8) stats[threadIdx.x] = (threadIdx.x == 4) ? Q : 0;
+    if (threadIdx.x < 16) ((int32_t *)ctrl)[threadIdx.x] = 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// Seeding: clear the visited table, keep the distinct in-range entry ids as the survivors of
+// "round 0" (they are scored by the first MLP launch and merged by the first round kernel).
+__global__ void __launch_bounds__(BLOCK)
+init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state, uint32_t *hash,
+            int hash_cap, int32_t *cand_g, int slots, int32_t *counts, const int32_t *W_q,
+            const int32_t *L_q, const int32_t *cap_q, int W, int L, int cap, int W_max, int L_max,
+            int cap_max, int64_t *stats) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int q = blockIdx.x;
+    int dd_n = 2;
+    while (dd_n < 2 * E) dd_n <<= 1;
+    int32_t *cand = (int32_t *)smem;                 // [E]
+    uint32_t *dd_key = (uint32_t *)(cand + ((E + 3) & ~3));
+    uint32_t *dd_pos = dd_key + dd_n;
+    int *wave_sums = (int *)(dd_pos + dd_n);
+
+    uint32_t *table = hash + (size_t)q * hash_cap;
+    for (int i = threadIdx.x; i < hash_cap; i += BLOCK) table[i] = EMPTY_SLOT;
+    for (int i = threadIdx.x; i < E; i += BLOCK) cand[i] = entries[(size_t)q * E + i];
+    __threadfence_block();
+    __syncthreads();
+    int n = filter_and_insert(cand, E, dd_key, dd_pos, dd_n, table, hash_cap, N,
+                              cand_g + (size_t)q * slots, wave_sums);
+    if (threadIdx.x == 0) {
+        QState s;
+        s.t = 0;
+        s.done = 0;
+        s.n_list = 0;
+        s.n_visited = n;
+        int w = W_q ? W_q[q] : W, l = L_q ? L_q[q] : L, c = cap_q ? cap_q[q] : cap;
+        s.W = min(max(w, 1), W_max);
+        s.L = min(max(l, 1), L_max);
+        s.cap = cap_max > 0 ? min(max(c, 1), cap_max) : max(c, 0);
+        s.overflow = 0;
+        state[q] = s;
+        counts[q] = n;
+        if (n) atomicAdd((unsigned long long *)&stats[0], (unsigned long long)n);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Exclusive scan of survivor counts + stable packing into the dense pair list.
+constexpr int SCAN_QPB = 64;  // queries per workgroup
+__global__ void __launch_bounds__(BLOCK)
+scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__restrict__ cand_g, int slots,
+                    int32_t *offsets, int32_t *pair_q, int32_t *pair_id, Ctrl *ctrl) {
+    __shared__ int red[WAVES];
+    __shared__ int red_active[WAVES];
+    __shared__ int loc_off[SCAN_QPB + 1];
+    __shared__ int loc_cnt[SCAN_QPB];
+    const int q0 = blockIdx.x * SCAN_QPB;
+    const bool last = (blockIdx.x == gridDim.x - 1);
+    // pairs of all earlier queries (and, in the last workgroup, the number of running queries)
+    int sum = 0, act = 0;
+    const int lim = last ? Q : q0;
+    for (int i = threadIdx.x; i < lim; i += BLOCK) {
+        int c = counts[i];
+        if (i < q0) sum += max(c, 0);
+        act += (c >= 0);
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        sum += __shfl_down(sum, o);
+        act += __shfl_down(act, o);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        red[threadIdx.x >> 6] = sum;
+        red_active[threadIdx.x >> 6] = act;
+    }
+    __syncthreads();
+    int prefix = 0, n_active = 0;
+    for (int w = 0; w < WAVES; ++w) {
+        prefix += red[w];
+        n_active += red_active[w];
+    }
+    // scan of this workgroup's 64 counts by the first wave
+    if (threadIdx.x < 64) {
+        int q = q0 + threadIdx.x;
+        int c = (q < Q) ? max(counts[q], 0) : 0;
+        int inc = c;
+        for (int o = 1; o < 64; o <<= 1) {
+            int v = __shfl_up(inc, o);
+            if ((int)threadIdx.x >= o) inc += v;
+        }
+        loc_cnt[threadIdx.x] = c;
+        loc_off[threadIdx.x] = prefix + inc - c;
+        if (threadIdx.x == 63) loc_off[64] = prefix + inc;
+        if (q < Q) offsets[q] = prefix + inc - c;
+    }
+    __syncthreads();
+    if (last && threadIdx.x == 0) {
+        ctrl->M = loc_off[64];
+        ctrl->n_active = n_active;
+    }
+    for (int i = 0; i < SCAN_QPB; ++i) {
+        int q = q0 + i;
+        if (q >= Q) break;
+        int c = loc_cnt[i], off = loc_off[i];
+        const int32_t *src = cand_g + (size_t)q * slots;
+        for (int j = threadIdx.x; j < c; j += BLOCK) {
+            pair_id[off + j] = src[j];
+            pair_q[off + j] = q;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// One round of one query.
+__global__ void __launch_bounds__(BLOCK)
+round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, uint64_t *pool_g, int C,
+             uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
+             const int32_t *__restrict__ offsets, const float *__restrict__ scores, int sort_cap,
+             int W_max, int64_t *stats) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int q = blockIdx.x;
+    QState st = state[q];
+    if (st.done) {
+        if (threadIdx.x == 0) counts[q] = -1;
+        return;
+    }
+    int dd_n = 2;
+    while (dd_n < 2 * slots) dd_n <<= 1;
+    uint64_t *keys = (uint64_t *)smem;                       // [sort_cap]
+    int32_t *cand = (int32_t *)(keys + sort_cap);             // [slots]
+    uint32_t *dd_key = (uint32_t *)(cand + ((slots + 3) & ~3));
+    uint32_t *dd_pos = dd_key + dd_n;
+    int32_t *parents = (int32_t *)(dd_pos + dd_n);            // [W_max]
+    int *wave_sums = parents + ((W_max + 3) & ~3);            // [WAVES + 1]
+
+    uint64_t *pool = pool_g + (size_t)q * C;
+    int32_t *cand_q = cand_g + (size_t)q * slots;
+    const int n_prev = counts[q];
+    const int off = offsets[q];
+
+    // 1. merge the scores of the previous round (or of the seeds) into the sorted list
+    int n_all = st.n_list + n_prev;
+    if (n_prev > 0) {
+        int n2 = 2;
+        while (n2 < n_all) n2 <<= 1;
+        for (int i = threadIdx.x; i < n2; i += BLOCK) {
+            uint64_t key = KEY_SENTINEL;
+            if (i < st.n_list) key = pool[i];
+            else if (i < n_all) key = make_key(scores[off + i - st.n_list], cand_q[i - st.n_list], 0u);
+            keys[i] = key;
+        }
+        __syncthreads();
+        bitonic_sort(keys, n2);
+    } else {
+        for (int i = threadIdx.x; i < st.n_list; i += BLOCK) keys[i] = pool[i];
+        __syncthreads();
+    }
+    const int n_list = min(n_all, C);
+
+    // 2. termination test and choice of the parents
+    int n_par = 0;
+    const bool capped = (st.cap > 0 && st.t >= st.cap);
+    if (!capped) {
+        const int lim = min(st.L, n_list);
+        for (int i0 = 0; i0 < lim && n_par < st.W; i0 += BLOCK) {
+            int i = i0 + threadIdx.x;
+            bool open = (i < lim) && !key_expanded(keys[i]);
+            int tot;
+            int pos = block_excl_count(open, wave_sums, &tot);
+            if (open && n_par + pos < st.W) {
+                parents[n_par + pos] = key_id(keys[i]);
+                keys[i] |= 1ull;
+            }
+            n_par = min(st.W, n_par + tot);
+        }
+    }
+    __syncthreads();
+    // a visited table that could not take this round's ids ends the query
+    bool overflow = false;
+    if (n_par > 0 && (int64_t)st.n_visited + (int64_t)n_par * R > (int64_t)(hash_cap / 2)) {
+        overflow = true;
+        n_par = 0;
+    }
+    for (int i = threadIdx.x; i < n_list; i += BLOCK) pool[i] = keys[i];
+    if (n_par == 0) {
+        if (threadIdx.x == 0) {
+            st.n_list = n_list;
+            st.done = 1;
+            st.overflow = overflow ? 1 : 0;
+            state[q] = st;
+            counts[q] = -1;
+            if (overflow) atomicAdd((unsigned long long *)&stats[3], 1ull);
+            atomicMax((unsigned long long *)&stats[2], (unsigned long long)st.t);
+        }
+        return;
+    }
+
+    // 3. neighbour gather: one adjacency row per parent, consecutive lanes read consecutive ids
+    const int n_cand = n_par * R;
+    for (int j = threadIdx.x; j < n_cand; j += BLOCK) {
+        int p = j / R, s = j - p * R;
+        cand[j] = adj[(size_t)parents[p] * R + s];
+    }
+    __syncthreads();
+
+    // 4. visited filter, 5. survivors of this query for the next MLP launch
+    int n_new = filter_and_insert(cand, n_cand, dd_key, dd_pos, dd_n, hash + (size_t)q * hash_cap, hash_cap, N,
+                                  cand_q, wave_sums);
+    if (threadIdx.x == 0) {
+        st.n_list = n_list;
+        st.t += 1;
+        st.n_visited += n_new;
+        state[q] = st;
+        counts[q] = n_new;
+        atomicAdd((unsigned long long *)&stats[0], (unsigned long long)n_new);
+        atomicAdd((unsigned long long *)&stats[1], (unsigned long long)n_par);
+        atomicMax((unsigned long long *)&stats[2], (unsigned long long)st.t);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(BLOCK)
+emit_kernel(const QState *__restrict__ state, const uint64_t *__restrict__ pool_g, int C, int k,
+            int32_t *out_ids, float *out_scores) {
+    const int q = blockIdx.x;
+    const int n = state[q].n_list;
+    const uint64_t *pool = pool_g + (size_t)q * C;
+    for (int i = threadIdx.x; i < k; i += BLOCK) {
+        int32_t id = -1;
+        float sc = -INFINITY;
+        if (i < n) {
+            uint64_t key = pool[i];
+            id = key_id(key);
+            sc = key_score(key);
+        }
+        out_ids[(size_t)q * k + i] = id;
+        out_scores[(size_t)q * k + i] = sc;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+static size_t round_smem(const Plan &p) {
+    int dd_n = 2;
+    while (dd_n < 2 * p.slots) dd_n <<= 1;
+    return (size_t)p.sort_n * 8 + (size_t)((p.slots + 3) & ~3) * 4 + (size_t)dd_n * 8 +
+           (size_t)((p.W_max + 3) & ~3) * 4 + (WAVES + 1 + 4) * 4;
+}
+
+int launch_init(const SearchArgs &a) {
+    const Plan &p = a.plan;
+    int dd_n = 2;
+    while (dd_n < 2 * p.E) dd_n <<= 1;
+    size_t smem = (size_t)((p.E + 3) & ~3) * 4 + (size_t)dd_n * 8 + (WAVES + 1) * 4;
+    int64_t *stats = (int64_t *)(a.ws + p.off_stats);
+    hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, a.stream, stats, (Ctrl *)(a.ws + p.off_ctrl), p.Q);
+    hipLaunchKernelGGL(init_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.entries, p.E, a.g->N,
+                       (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), p.hash_cap,
+                       (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q,
+                       a.L_q, a.cap_q, a.W, a.L, a.cap, p.W_max, p.L_max, p.max_iters_max, stats);
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+int launch_scan_compact(const SearchArgs &a) {
+    const Plan &p = a.plan;
+    int blocks = (p.Q + SCAN_QPB - 1) / SCAN_QPB;
+    hipLaunchKernelGGL(scan_compact_kernel, dim3(blocks), dim3(BLOCK), 0, a.stream,
+                       (const int32_t *)(a.ws + p.off_counts), p.Q, (const int32_t *)(a.ws + p.off_cand),
+                       p.slots, (int32_t *)(a.ws + p.off_offsets), (int32_t *)(a.ws + p.off_pair_q),
+                       (int32_t *)(a.ws + p.off_pair_id), (Ctrl *)(a.ws + p.off_ctrl));
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+int launch_round(const SearchArgs &a) {
+    const Plan &p = a.plan;
+    static bool attr_set[16] = {false};
+    size_t smem = round_smem(p);
+    int dev = a.m->device;
+    if (smem > 48 * 1024 && dev >= 0 && dev < 16 && !attr_set[dev]) {
+        ANN_HIP_TRY(hipFuncSetAttribute((const void *)round_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        96 * 1024));
+        attr_set[dev] = true;
+    }
+    hipLaunchKernelGGL(round_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.g->adj, p.R, a.g->N,
+                       (QState *)(a.ws + p.off_state), (uint64_t *)(a.ws + p.off_pool), p.C,
+                       (uint32_t *)(a.ws + p.off_hash), p.hash_cap, (int32_t *)(a.ws + p.off_cand), p.slots,
+                       (int32_t *)(a.ws + p.off_counts), (const int32_t *)(a.ws + p.off_offsets),
+                       (const float *)(a.ws + p.off_scores), p.sort_n, p.W_max,
+                       (int64_t *)(a.ws + p.off_stats));
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+int launch_emit(const SearchArgs &a) {
+    const Plan &p = a.plan;
+    hipLaunchKernelGGL(emit_kernel, dim3(p.Q), dim3(BLOCK), 0, a.stream, (const QState *)(a.ws + p.off_state),
+                       (const uint64_t *)(a.ws + p.off_pool), p.C, p.k, a.out_ids, a.out_scores);
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+}  // namespace gmpgr

@@ -1,0 +1,70 @@
+"""The C-ABI library loads and exports every entry point that include/gmpgr_ann.h declares, and
+argument errors that are detected before any HIP call come back as error codes (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "gmpgr_ann.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ann_[a-z_0-9]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2502_11490_amd as ann
+
+    if not os.path.exists(ann.lib_path()):
+        from paper_2502_11490_amd.build import build
+
+        build()
+    return ann.load_library()
+
+
+def test_header_and_library_agree(lib):
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+    from paper_2502_11490_amd.binding import EXPORTS
+
+    assert sorted(EXPORTS) == names, "the Python binding must cover exactly the declared entry points"
+
+
+def test_errors_detected_before_any_device_work(lib):
+    out = ctypes.c_void_p()
+    assert lib.ann_graph_load(None, None, 10, 4, 8, 0, 0, None, ctypes.byref(out)) == -1
+    assert b"null" in lib.ann_last_error()
+    assert lib.ann_graph_load(ctypes.c_void_p(16), ctypes.c_void_p(16), 0, 4, 8, 0, 0, None, ctypes.byref(out)) == -1
+    assert lib.ann_graph_load(ctypes.c_void_p(16), ctypes.c_void_p(16), 10, 65, 8, 0, 0, None, ctypes.byref(out)) == -1
+    assert lib.ann_graph_load(ctypes.c_void_p(16), ctypes.c_void_p(16), 10, 4, 8, 7, 0, None, ctypes.byref(out)) == -1
+    assert lib.ann_graph_load(ctypes.c_void_p(18), ctypes.c_void_p(16), 10, 4, 8, 0, 0, None, ctypes.byref(out)) == -1
+    assert out.value is None
+    assert lib.ann_search_workspace_bytes(None, None, 4, 1, 1, 1, 1, 0) == 0
+    assert lib.ann_mlp_load(0, None, None, None, None, 4, 0, 0, None, ctypes.byref(out)) == -1
+    dims = (ctypes.c_int32 * 2)(8, 3)
+    Wp = (ctypes.c_void_p * 1)(None)
+    hw = (ctypes.c_float * 3)(0.5, 0.3, 0.2)
+    assert lib.ann_mlp_load(1, dims, Wp, Wp, hw, 4, 0, 0, None, ctypes.byref(out)) == -1   # null layer arrays
+    assert lib.ann_mlp_load(1, dims, Wp, Wp, hw, 8, 0, 0, None, ctypes.byref(out)) == -1   # d_user >= dims[0]
+    assert lib.ann_search_stats(None, None, None) == -1
+    assert lib.ann_profile_read(None, None) == -1
+    # a graph handle needs no device work: borrowed pointers, checked shapes
+    assert lib.ann_graph_load(ctypes.c_void_p(256), ctypes.c_void_p(512), 10, 4, 8, 0, 0, None, ctypes.byref(out)) == 0
+    g = ctypes.c_void_p(out.value)
+    assert lib.ann_search_workspace_bytes(g, None, 4, 1, 1, 1, 1, 0) == 0
+    lib.ann_graph_free(g)
+
+
+def test_missing_library_is_loud(monkeypatch):
+    import paper_2502_11490_amd.binding as b
+
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libgmpgr_ann.so")
+    with pytest.raises(FileNotFoundError):
+        b.load_library()
