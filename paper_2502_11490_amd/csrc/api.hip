@@ -109,7 +109,7 @@ bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32
     p->off_scores = o;
     o = align256(o + (size_t)p->M_max * 4);
     p->off_upre = o;
-    o = align256(o + (size_t)Q * p->H1 * 4);
+    o = align256(o + ((size_t)Q * p->H1 + 32) * 4);  // +32: the MFMA kernel pre-loads one block past a row
     p->total = o;
     return true;
 }
@@ -501,7 +501,7 @@ int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_de
     if (m->kernel != MLP_MFMA2)
         return launch_mlp_alu(g, m, queries_dev, q_idx_dev, item_dev, nullptr, M, Q, out_dev, tile_rows, s);
     char *tmp = nullptr;
-    size_t upre_bytes = (size_t)Q * m->dims[1] * sizeof(float);
+    size_t upre_bytes = ((size_t)Q * m->dims[1] + 32) * sizeof(float);
     if (hipMalloc((void **)&tmp, 256 + upre_bytes) != hipSuccess) {
         set_error("device allocation of %zu bytes failed", 256 + upre_bytes);
         return ANN_ENOMEM;

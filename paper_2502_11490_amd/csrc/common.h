@@ -123,6 +123,12 @@ int launch_mlp_mfma(const ann_graph *g, const ann_mlp *m, const float *upre, con
                     const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
                     int32_t tile_rows, hipStream_t stream);
 bool mfma_supported(const int32_t *dims, int32_t n_layers, int32_t d_user, int32_t dtype);
+// mlp_mfma_stream.hip: the hand-scheduled kernel for item width 128, hidden 512 x 256
+bool mfma_stream_supported(int D, int H1, int H2);
+int build_stream_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream);
+int launch_mlp_mfma_stream(const ann_graph *g, const ann_mlp *m, const float *upre, const int32_t *pair_q,
+                           const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
+                           hipStream_t stream);
 int build_mfma_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream);
 
 }  // namespace gmpgr

@@ -151,12 +151,17 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
             up[c] = upre + (size_t)q * H1 + 4 * g;
         }
         f32x16 acc2[NB2][CB];
+        // the bias pointer is laundered once per batch: otherwise the loads below are hoisted
+        // out of the batch loop and their 16*NB2 values are carried (spilled) across it
+        int opaque_zero = 0;
+        asm volatile("" : "+s"(opaque_zero));
+        const float *b2t = b2 + opaque_zero;
 #pragma unroll
         for (int n2 = 0; n2 < NB2; ++n2) {
             f32x16 init;
 #pragma unroll
             for (int t4 = 0; t4 < 4; ++t4) {
-                f32x4 bv = *(const f32x4 *)(b2 + n2 * 32 + 8 * t4 + 4 * g);
+                f32x4 bv = *(const f32x4 *)(b2t + n2 * 32 + 8 * t4 + 4 * g);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) init[4 * t4 + e] = bv[e];
             }
@@ -267,6 +272,7 @@ bool mfma_supported(const int32_t *dims, int32_t n_layers, int32_t d_user, int32
 static inline uint16_t w_at(const uint16_t *W, int n_in, int row, int colm) { return W[(size_t)row * n_in + colm]; }
 
 int build_mfma_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream) {
+    if (mfma_stream_supported(m->d_item, m->dims[1], m->dims[2])) return build_stream_fragments(m, W_host, stream);
     const int D = m->d_item, H1 = m->dims[1], H2 = m->dims[2], J = m->J, du = m->d_user;
     const int KS1 = D / 16, NB1 = H1 / 32, NB2 = H2 / 32;
     const int CHUNK_FR = KS1 + 2 * NB2;
@@ -340,8 +346,8 @@ int launch_mlp_mfma(const ann_graph *g, const ann_mlp *m, const float *upre, con
     (void)tile_rows;
     if (M_max <= 0) return ANN_OK;
     const int D = m->d_item, H1 = m->dims[1], H2 = m->dims[2];
-    if (D == 128 && H1 == 512 && H2 == 256)
-        return launch_one<128, 512, 256, 2, false>(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
+    if (mfma_stream_supported(D, H1, H2))
+        return launch_mlp_mfma_stream(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
     if (D == 64 && H1 == 256 && H2 == 128)
         return launch_one<64, 256, 128, 2, true>(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
     set_error("no MFMA kernel for item width %d, hidden %d, %d", D, H1, H2);

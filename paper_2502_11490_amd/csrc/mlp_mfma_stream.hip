@@ -1,0 +1,384 @@
+// Fused bf16 MFMA relevance kernel for the widest metric (item width 128, hidden 512 and 256):
+// Sec. 3.1 (1), Eq. 5-8, over the dense pair list of Algorithm 2.
+//
+// Same formulation as mlp_mfma.hip (activations transposed and register resident, weights as
+// the A operand in fragment order, user half of layer 1 pre-computed per query), but with the
+// per-wave register file planned by hand, because at this size it is full:
+//     256 AGPRs  layer-2 accumulators of 64 pairs x 256 units (16 MFMA tiles)
+//      64 VGPRs  the 64 item rows as layer-1 B operands
+//      64 VGPRs  layer-1 accumulators of this step and the pre-loaded user term of the next
+//      16 VGPRs  the 32 hidden units of the previous step as layer-2 B operands (bf16)
+//      16 VGPRs  four weight fragments in flight from LDS
+//      32 VGPRs  staging of the next weight chunk and of the next batch's item rows
+// The compiler's register allocator does not find this plan, so one step of the pipeline is a
+// single inline-assembly block with the register classes pinned by constraints.
+//
+// Pipeline.  Step i (0..NB1) contracts layer 1 for hidden units 32i..32i+31 and, skewed by one
+// step, layer 2 over the hidden units of step i-1; chunk i of the weights holds exactly those
+// fragments (8 of W1_item, then 16 of W2), streams L2 -> registers -> LDS while step i-1 runs
+// (double buffer, one barrier per step), and is read from LDS four fragments ahead of use.
+// ReLU + bf16 rounding of the fresh hidden units is the only vector-ALU work of a step; the
+// item rows of the workgroup's NEXT batch are fetched one 16-byte piece per lane and step into
+// a wave-private LDS area, so the HBM gather latency is hidden behind a whole batch of MFMAs.
+//
+// Hazards handled by hand inside the assembly (the compiler cannot see into it):
+//   - every block starts with s_waitcnt lgkmcnt(0): afterwards only its own LDS reads are in
+//     flight and the counted waits (lgkmcnt(3..0)) are exact;
+//   - an accumulator is never the target of two consecutive MFMAs (pairs 0 and 1 alternate);
+//   - results read by the vector ALU right after a block (layer-1 accumulators after the
+//     first step, layer-2 accumulators after the last) are waited for with s_nop;
+//   - a weight-fragment register is reloaded from LDS only after the MFMAs reading it have
+//     issued (MFMA operands are read at issue).
+#include <vector>
+
+#include "common.h"
+
+namespace gmpgr {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int ST_BLOCK = 256;
+
+// ReLU and round-to-nearest-even bf16 of half an accumulator tile, two instructions per packed
+// word: v_cvt_pk_bf16_f32 rounds two floats, and for bf16 bit patterns max(x, 0) is a signed
+// 16-bit integer max (negative values have the sign bit set).  Rounding before or after the
+// ReLU gives the same result.
+__device__ __forceinline__ bf16x8 relu_pack_i16(const f32x16 &acc, int half) {
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        asm("v_cvt_pk_bf16_f32 %0, %1, %2\n\tv_pk_max_i16 %0, %0, 0"
+            : "=&v"(w[j])
+            : "v"(acc[half * 8 + 2 * j]), "v"(acc[half * 8 + 2 * j + 1]));
+    uint4 u = make_uint4(w[0], w[1], w[2], w[3]);
+    return __builtin_bit_cast(bf16x8, u);
+}
+
+__device__ __forceinline__ void mfma_v(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void drain_v(f32x16 &x, f32x16 &y) {
+    asm volatile("s_nop 15" : "+v"(x), "+v"(y));
+}
+
+#define LD(buf, off) "ds_read_b128 %[" #buf "], %[wc] offset:" #off "\n\t"
+#define WT(n) "s_waitcnt lgkmcnt(" #n ")\n\t"
+#define M1(f, s)                                                                   \
+    "v_mfma_f32_32x32x16_bf16 %[p0], %[" #f "], %[x0" #s "], %[p0]\n\t"            \
+    "v_mfma_f32_32x32x16_bf16 %[p1], %[" #f "], %[x1" #s "], %[p1]\n\t"
+#define M2(f, n2, s2)                                                                      \
+    "v_mfma_f32_32x32x16_bf16 %[a" #n2 "0], %[" #f "], %[h0" #s2 "], %[a" #n2 "0]\n\t"     \
+    "v_mfma_f32_32x32x16_bf16 %[a" #n2 "1], %[" #f "], %[h1" #s2 "], %[a" #n2 "1]\n\t"
+
+// fragments 0..7 of the chunk: layer 1 (one per 16 item coordinates)
+#define L1_HEAD WT(0) LD(f0, 0) LD(f1, 1024) LD(f2, 2048) LD(f3, 3072)
+#define L1_BODY_STREAM                                                                     \
+    WT(3) M1(f0, 0) LD(f0, 4096) WT(3) M1(f1, 1) LD(f1, 5120) WT(3) M1(f2, 2) LD(f2, 6144)  \
+    WT(3) M1(f3, 3) LD(f3, 7168) WT(3) M1(f0, 4) LD(f0, 8192) WT(3) M1(f1, 5) LD(f1, 9216)  \
+    WT(3) M1(f2, 6) LD(f2, 10240) WT(3) M1(f3, 7) LD(f3, 11264)
+#define L1_BODY_ONLY                                                                       \
+    WT(3) M1(f0, 0) LD(f0, 4096) WT(3) M1(f1, 1) LD(f1, 5120) WT(3) M1(f2, 2) LD(f2, 6144)  \
+    WT(3) M1(f3, 3) LD(f3, 7168) WT(3) M1(f0, 4) WT(2) M1(f1, 5) WT(1) M1(f2, 6) WT(0) M1(f3, 7)
+// fragments 8..23 of the chunk: layer 2, fragment 8 + 2*n2 + s2
+#define L2_HEAD WT(0) LD(f0, 8192) LD(f1, 9216) LD(f2, 10240) LD(f3, 11264)
+#define L2_BODY                                                                               \
+    WT(3) M2(f0, 0, 0) LD(f0, 12288) WT(3) M2(f1, 0, 1) LD(f1, 13312) WT(3) M2(f2, 1, 0) LD(f2, 14336) \
+    WT(3) M2(f3, 1, 1) LD(f3, 15360) WT(3) M2(f0, 2, 0) LD(f0, 16384) WT(3) M2(f1, 2, 1) LD(f1, 17408) \
+    WT(3) M2(f2, 3, 0) LD(f2, 18432) WT(3) M2(f3, 3, 1) LD(f3, 19456) WT(3) M2(f0, 4, 0) LD(f0, 20480) \
+    WT(3) M2(f1, 4, 1) LD(f1, 21504) WT(3) M2(f2, 5, 0) LD(f2, 22528) WT(3) M2(f3, 5, 1) LD(f3, 23552) \
+    WT(3) M2(f0, 6, 0) WT(2) M2(f1, 6, 1) WT(1) M2(f2, 7, 0) WT(0) M2(f3, 7, 1)
+
+#define ACC2_OPERANDS                                                                              \
+    [a00] "+a"(acc2[0][0]), [a01] "+a"(acc2[0][1]), [a10] "+a"(acc2[1][0]), [a11] "+a"(acc2[1][1]), \
+    [a20] "+a"(acc2[2][0]), [a21] "+a"(acc2[2][1]), [a30] "+a"(acc2[3][0]), [a31] "+a"(acc2[3][1]), \
+    [a40] "+a"(acc2[4][0]), [a41] "+a"(acc2[4][1]), [a50] "+a"(acc2[5][0]), [a51] "+a"(acc2[5][1]), \
+    [a60] "+a"(acc2[6][0]), [a61] "+a"(acc2[6][1]), [a70] "+a"(acc2[7][0]), [a71] "+a"(acc2[7][1])
+#define FRAG_TEMPS [f0] "=&v"(f0), [f1] "=&v"(f1), [f2] "=&v"(f2), [f3] "=&v"(f3)
+#define X_OPERANDS                                                                                  \
+    [x00] "v"(xf[0][0]), [x01] "v"(xf[0][1]), [x02] "v"(xf[0][2]), [x03] "v"(xf[0][3]),             \
+    [x04] "v"(xf[0][4]), [x05] "v"(xf[0][5]), [x06] "v"(xf[0][6]), [x07] "v"(xf[0][7]),             \
+    [x10] "v"(xf[1][0]), [x11] "v"(xf[1][1]), [x12] "v"(xf[1][2]), [x13] "v"(xf[1][3]),             \
+    [x14] "v"(xf[1][4]), [x15] "v"(xf[1][5]), [x16] "v"(xf[1][6]), [x17] "v"(xf[1][7])
+#define H_OPERANDS [h00] "v"(hf[0][0]), [h01] "v"(hf[0][1]), [h10] "v"(hf[1][0]), [h11] "v"(hf[1][1])
+
+// Weight fragments, bf16, 1 KB each (lane l at byte 16*l), NB1 + 1 chunks of 24 fragments:
+//   chunk i, fragment s < 8       lane (m,g): W1_item[32i+m][16s + 8g + j]                      (zero for i = NB1)
+//   chunk i, fragment 8+2*n2+s2   lane (m,g): W2[32*n2+m][32(i-1) + 16*s2 + 8*(j/4) + 4g + j%4] (zero for i = 0)
+// then 16 head fragments [2*n2+s2], lane (m,g): W3[m][32*n2 + 16*s2 + 8*(j/4) + 4g + j%4], rows m >= J zero.
+template <int H1>
+__global__ void __launch_bounds__(ST_BLOCK)
+mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__restrict__ upre,
+                        const uint4 *__restrict__ frag, const float *__restrict__ b2, const float *__restrict__ b3,
+                        const float *__restrict__ head_w, int J, const int32_t *__restrict__ pair_q,
+                        const int32_t *__restrict__ pair_id, const int32_t *__restrict__ M_dev, int64_t M_max,
+                        int32_t Q, float *__restrict__ scores) {
+    constexpr int D = 128, KS1 = 8, NB1 = H1 / 32, NB2 = 8, CB = 2;
+    constexpr int NSTEP = NB1 + 1;
+    constexpr int CHUNK_U4 = 24 * 64;
+    constexpr int W3_U4 = 16 * 64;
+    constexpr int TILE = 64 * 4;
+    constexpr int ST = CHUNK_U4 / ST_BLOCK;  // 6 uint4 per thread and chunk
+    extern __shared__ __align__(16) uint4 lds[];
+    uint4 *wbuf = lds;                       // [2][CHUNK_U4]
+    uint4 *w3buf = lds + 2 * CHUNK_U4;       // [W3_U4]
+    uint4 *xbuf = w3buf + W3_U4;             // [4 waves][CB*KS1][64 lanes]
+
+    int64_t M = (int64_t)*M_dev;
+    if (M > M_max) M = M_max;
+    const int64_t n_tiles = (M + TILE - 1) / TILE;
+    if ((int64_t)blockIdx.x >= n_tiles) return;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int g = lane >> 5, col = lane & 31;
+    uint4 *xw = xbuf + (size_t)wave * (CB * KS1 * 64) + lane;
+
+    for (int i = threadIdx.x; i < W3_U4; i += ST_BLOCK) w3buf[i] = frag[(size_t)NSTEP * CHUNK_U4 + i];
+    for (int i = threadIdx.x; i < CHUNK_U4; i += ST_BLOCK) wbuf[i] = frag[i];
+
+    float hw[4], bb3[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int j = 4 * g + i;
+        hw[i] = j < J ? head_w[j] : 0.f;
+        bb3[i] = j < J ? b3[j] : 0.f;
+    }
+
+    // ids of the first batch and its item rows (the later batches are fetched during the one before)
+    int32_t idn[CB], qn[CB];
+    bool badn[CB];
+    auto load_ids = [&](int64_t tile) {
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            int64_t row = tile * TILE + (int64_t)wave * 64 + c * 32 + col;
+            int32_t v = 0, q = 0;
+            if (tile < n_tiles && row < M) {
+                v = pair_id[row];
+                q = pair_q[row];
+            }
+            badn[c] = (v < 0 || (int64_t)v >= N || q < 0 || q >= Q);
+            idn[c] = badn[c] ? 0 : v;
+            qn[c] = badn[c] ? 0 : q;
+        }
+    };
+    load_ids(blockIdx.x);
+#pragma unroll
+    for (int c = 0; c < CB; ++c) {
+        const uint4 *src = (const uint4 *)(emb + (size_t)idn[c] * D) + g;
+#pragma unroll
+        for (int s = 0; s < KS1; ++s) xw[(c * KS1 + s) * 64] = src[2 * s];
+    }
+    __syncthreads();
+
+    // `stage` always holds (in flight) the chunk of the next step
+    static_assert(ST == 6, "six staged uint4 per thread");
+    uint4 sg0, sg1, sg2, sg3, sg4, sg5;  // named scalars: an indexed array would live in scratch
+#define STAGE_LOAD(src)            \
+    sg0 = (src)[0 * ST_BLOCK];     \
+    sg1 = (src)[1 * ST_BLOCK];     \
+    sg2 = (src)[2 * ST_BLOCK];     \
+    sg3 = (src)[3 * ST_BLOCK];     \
+    sg4 = (src)[4 * ST_BLOCK];     \
+    sg5 = (src)[5 * ST_BLOCK];
+#define STAGE_STORE(dst)           \
+    (dst)[0 * ST_BLOCK] = sg0;     \
+    (dst)[1 * ST_BLOCK] = sg1;     \
+    (dst)[2 * ST_BLOCK] = sg2;     \
+    (dst)[3 * ST_BLOCK] = sg3;     \
+    (dst)[4 * ST_BLOCK] = sg4;     \
+    (dst)[5 * ST_BLOCK] = sg5;
+    {
+        const uint4 *src1 = frag + (size_t)1 * CHUNK_U4 + threadIdx.x;
+        STAGE_LOAD(src1)
+    }
+    int cur = 0;
+
+#pragma unroll 1
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t row0 = tile * TILE + (int64_t)wave * 64;
+        bf16x8 xf[CB][KS1];
+        const float *up[CB];
+        bool bad[CB];
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) xf[c][s] = __builtin_bit_cast(bf16x8, xw[(c * KS1 + s) * 64]);
+            up[c] = upre + (size_t)qn[c] * H1 + 4 * g;
+            bad[c] = badn[c];
+        }
+        load_ids(tile + gridDim.x);
+        size_t nxt_off[CB];  // element offsets of this lane's pieces of the next batch's rows
+#pragma unroll
+        for (int c = 0; c < CB; ++c) nxt_off[c] = (size_t)idn[c] * D + 8 * g;
+
+        f32x16 acc2[NB2][CB];
+        int opaque_zero = 0;
+        asm volatile("" : "+s"(opaque_zero));  // keeps the loads below inside the batch loop
+        const float *b2t = b2 + opaque_zero;
+#pragma unroll
+        for (int n2 = 0; n2 < NB2; ++n2) {
+            f32x16 init;
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) {
+                f32x4 bv = *(const f32x4 *)(b2t + n2 * 32 + 8 * t4 + 4 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) init[4 * t4 + e] = bv[e];
+            }
+#pragma unroll
+            for (int c = 0; c < CB; ++c) acc2[n2][c] = init;
+        }
+
+        // Two sets of layer-1 accumulators alternate: while one is used by a step, the other
+        // receives the per-query user term of the next step (no register copies).
+        f32x16 accA[CB], accB[CB];
+#define LOAD_USER_TERM(ACC, nb)                                                   \
+    _Pragma("unroll") for (int c = 0; c < CB; ++c)                                \
+        _Pragma("unroll") for (int t4 = 0; t4 < 4; ++t4) {                        \
+            f32x4 pv = *(const f32x4 *)(up[c] + (nb) * 32 + 8 * t4);              \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) ACC[c][4 * t4 + e] = pv[e]; \
+        }
+        LOAD_USER_TERM(accA, 0)
+        bf16x8 hf[CB][2];
+#pragma unroll
+        for (int c = 0; c < CB; ++c) hf[c][0] = hf[c][1] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+
+        // One pipeline step.  The 16-byte piece of the next batch's item rows fetched in step i is
+        // written to LDS at the end of step i+1, two steps after its load was issued.
+        // ACC holds this step's layer-1 start values, NEXT receives those of
+        // step i+1 (the row of user terms is padded by 32 floats, so i+1 = NB1 reads valid memory
+        // that is never used).  The same assembly block serves every step: in step 0 the layer-2
+        // half multiplies zero weights with zero activations, in step NB1 the layer-1 half
+        // multiplies zero weights and its result is dropped.
+#define STEP(i, ACC, NEXT, XP_NEW, XP_OLD, IS_FIRST, IS_LAST)                                       \
+    {                                                                                                \
+        if (!(IS_LAST)) {                                                                            \
+            LOAD_USER_TERM(NEXT, (i) + 1)                                                            \
+            XP_NEW = *(const uint4 *)(emb + ((((i) / KS1) & 1) ? nxt_off[1] : nxt_off[0]) + 16 * ((i) % KS1)); \
+        }                                                                                            \
+        const uint32_t wc = (uint32_t)(uintptr_t)(wbuf + (size_t)cur * CHUNK_U4 + lane);             \
+        bf16x8 f0, f1, f2, f3;                                                                       \
+        asm volatile(L1_HEAD L1_BODY_STREAM L2_BODY                                                  \
+                     : [p0] "+v"(ACC[0]), [p1] "+v"(ACC[1]), ACC2_OPERANDS, FRAG_TEMPS               \
+                     : [wc] "v"(wc), X_OPERANDS, H_OPERANDS);                                        \
+        if (!(IS_LAST)) {                                                                            \
+            _Pragma("unroll") for (int c = 0; c < CB; ++c) {                                         \
+                hf[c][0] = relu_pack_i16(ACC[c], 0);                                                 \
+                hf[c][1] = relu_pack_i16(ACC[c], 1);                                                 \
+            }                                                                                        \
+        }                                                                                            \
+        if (!(IS_FIRST)) xw[((i) - 1) * 64] = XP_OLD; /* piece fetched one step ago */               \
+        uint4 *dst = wbuf + (size_t)(cur ^ 1) * CHUNK_U4 + threadIdx.x;                              \
+        STAGE_STORE(dst)                                                                             \
+        __syncthreads();                                                                             \
+        cur ^= 1;                                                                                    \
+        int nx = (i) + 2;                                                                            \
+        if (nx >= NSTEP) nx -= NSTEP;                                                                \
+        const uint4 *srcw = frag + (size_t)nx * CHUNK_U4 + threadIdx.x;                              \
+        STAGE_LOAD(srcw)                                                                             \
+    }
+
+        static_assert(NB1 % 2 == 0 && NB1 == CB * KS1, "steps are unrolled in pairs; one item piece per step");
+        uint4 xpA, xpB;
+#pragma unroll 1
+        for (int i = 0; i < NB1; i += 2) {
+            STEP(i, accA, accB, xpA, xpB, i == 0, false)
+            STEP(i + 1, accB, accA, xpB, xpA, false, false)
+        }
+        STEP(NB1, accA, accB, xpA, xpB, false, true)
+        asm volatile("s_nop 15" : "+a"(acc2[NB2 - 1][0]), "+a"(acc2[NB2 - 1][1]));
+#undef STEP
+#undef LOAD_USER_TERM
+
+        // head layer (fragment rows >= J are zero), then Eq. 8
+        f32x16 acc3[CB];
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc3[c][e] = 0.f;
+#pragma unroll
+        for (int n2 = 0; n2 < NB2; ++n2) {
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                bf16x8 a = __builtin_bit_cast(bf16x8, w3buf[(2 * n2 + s2) * 64 + lane]);
+#pragma unroll
+                for (int c = 0; c < CB; ++c) mfma_v(acc3[c], a, relu_pack_i16(acc2[n2][c], s2));
+            }
+        }
+        drain_v(acc3[0], acc3[1]);
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) part = fmaf(hw[e], 1.0f / (1.0f + expf(-(acc3[c][e] + bb3[e]))), part);
+            float other = __shfl_xor(part, 32);
+            int64_t row = row0 + c * 32 + col;
+            if (g == 0 && row < M) scores[row] = bad[c] ? __uint_as_float(0x7fc00000u) : part + other;
+        }
+    }
+}
+
+bool mfma_stream_supported(int D, int H1, int H2) { return D == 128 && H2 == 256 && H1 == 512; }
+
+static inline uint16_t w_at(const uint16_t *W, int n_in, int row, int colm) { return W[(size_t)row * n_in + colm]; }
+
+int build_stream_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream) {
+    const int D = m->d_item, H1 = m->dims[1], H2 = m->dims[2], J = m->J, du = m->d_user;
+    const int KS1 = D / 16, NB1 = H1 / 32, NB2 = H2 / 32;
+    const int CHUNK_FR = KS1 + 2 * NB2;
+    const size_t n_frag = (size_t)(NB1 + 1) * CHUNK_FR + 2 * NB2;
+    std::vector<uint16_t> buf(n_frag * 512, 0);
+    const uint16_t *W1 = (const uint16_t *)W_host[0], *W2 = (const uint16_t *)W_host[1],
+                   *W3 = (const uint16_t *)W_host[2];
+    for (int i = 0; i <= NB1; ++i) {
+        uint16_t *chunk = buf.data() + (size_t)i * CHUNK_FR * 512;
+        if (i < NB1)
+            for (int s = 0; s < KS1; ++s)
+                for (int l = 0; l < 64; ++l)
+                    for (int j = 0; j < 8; ++j)
+                        chunk[(size_t)s * 512 + l * 8 + j] =
+                            w_at(W1, du + D, i * 32 + (l & 31), du + 16 * s + 8 * (l >> 5) + j);
+        if (i > 0)
+            for (int n2 = 0; n2 < NB2; ++n2)
+                for (int s2 = 0; s2 < 2; ++s2)
+                    for (int l = 0; l < 64; ++l)
+                        for (int j = 0; j < 8; ++j)
+                            chunk[(size_t)(KS1 + 2 * n2 + s2) * 512 + l * 8 + j] = w_at(
+                                W2, H1, n2 * 32 + (l & 31), (i - 1) * 32 + 16 * s2 + 8 * (j / 4) + 4 * (l >> 5) + j % 4);
+    }
+    uint16_t *head = buf.data() + (size_t)(NB1 + 1) * CHUNK_FR * 512;
+    for (int n2 = 0; n2 < NB2; ++n2)
+        for (int s2 = 0; s2 < 2; ++s2)
+            for (int l = 0; l < 64; ++l)
+                for (int j = 0; j < 8; ++j)
+                    if ((l & 31) < J)
+                        head[(size_t)(2 * n2 + s2) * 512 + l * 8 + j] =
+                            w_at(W3, H2, l & 31, n2 * 32 + 16 * s2 + 8 * (j / 4) + 4 * (l >> 5) + j % 4);
+    m->frag_bytes = (int64_t)buf.size() * 2;
+    ANN_HIP_TRY(hipMalloc(&m->frag_dev, (size_t)m->frag_bytes));
+    ANN_HIP_TRY(hipMemcpyAsync(m->frag_dev, buf.data(), (size_t)m->frag_bytes, hipMemcpyHostToDevice, stream));
+    ANN_HIP_TRY(hipStreamSynchronize(stream));
+    return ANN_OK;
+}
+
+int launch_mlp_mfma_stream(const ann_graph *g, const ann_mlp *m, const float *upre, const int32_t *pair_q,
+                           const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
+                           hipStream_t stream) {
+    constexpr int H1 = 512;
+    constexpr size_t smem = ((size_t)2 * 24 * 64 + 16 * 64 + 4 * 16 * 64) * 16;  // 48 + 16 + 64 KB
+    constexpr int TILE = 256;
+    auto fn = mlp_mfma2_stream_kernel<H1>;
+    ANN_HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    int64_t tiles = (M_max + TILE - 1) / TILE;
+    int grid = (int)(tiles < 256 ? tiles : 256);
+    const float *b2 = m->b_dev + m->b_off[1], *b3 = m->b_dev + m->b_off[2];
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(ST_BLOCK), smem, stream, (const uint16_t *)g->emb, g->N, upre,
+                       (const uint4 *)m->frag_dev, b2, b3, m->head_w_dev, m->J, pair_q, pair_id, M_dev, M_max, Q,
+                       scores);
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+}  // namespace gmpgr
