@@ -17,6 +17,9 @@
 // step, layer 2 over the hidden units of step i-1; chunk i of the weights holds exactly those
 // fragments (8 of W1_item, then 16 of W2), streams L2 -> registers -> LDS while step i-1 runs
 // (double buffer, one barrier per step), and is read from LDS four fragments ahead of use.
+// A step issues its global loads first and in the order their data is needed (next weight
+// chunk, next user term, one piece of the next batch's item rows), so that the in-order load
+// counter never makes a short-latency consumer wait for the long-latency gather.
 // ReLU + bf16 rounding of the fresh hidden units is the only vector-ALU work of a step; the
 // item rows of the workgroup's NEXT batch are fetched one 16-byte piece per lane and step into
 // a wave-private LDS area, so the HBM gather latency is hidden behind a whole batch of MFMAs.
@@ -43,18 +46,43 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int ST_BLOCK = 256;
 
+// Measurement switches (all off in the product build): each removes one source of stalls from
+// the step pipeline while keeping every access in bounds; results are then meaningless.
+#ifndef EXP_NO_STAGE
+#define EXP_NO_STAGE 0
+#endif
+#ifndef EXP_NO_USER
+#define EXP_NO_USER 0
+#endif
+#ifndef EXP_NO_XP
+#define EXP_NO_XP 0
+#endif
+#ifndef EXP_NO_BARRIER
+#define EXP_NO_BARRIER 0
+#endif
+#ifndef EXP_NO_RELU
+#define EXP_NO_RELU 0
+#endif
+
 // ReLU and round-to-nearest-even bf16 of half an accumulator tile, two instructions per packed
 // word: v_cvt_pk_bf16_f32 rounds two floats, and for bf16 bit patterns max(x, 0) is a signed
 // 16-bit integer max (negative values have the sign bit set).  Rounding before or after the
 // ReLU gives the same result.
 __device__ __forceinline__ bf16x8 relu_pack_i16(const f32x16 &acc, int half) {
-    uint32_t w[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        asm("v_cvt_pk_bf16_f32 %0, %1, %2\n\tv_pk_max_i16 %0, %0, 0"
-            : "=&v"(w[j])
-            : "v"(acc[half * 8 + 2 * j]), "v"(acc[half * 8 + 2 * j + 1]));
-    uint4 u = make_uint4(w[0], w[1], w[2], w[3]);
+    uint32_t w0, w1, w2, w3;
+    const int o = half * 8;
+    asm("v_cvt_pk_bf16_f32 %0, %4, %5\n\t"
+        "v_cvt_pk_bf16_f32 %1, %6, %7\n\t"
+        "v_cvt_pk_bf16_f32 %2, %8, %9\n\t"
+        "v_cvt_pk_bf16_f32 %3, %10, %11\n\t"
+        "v_pk_max_i16 %0, %0, 0\n\t"
+        "v_pk_max_i16 %1, %1, 0\n\t"
+        "v_pk_max_i16 %2, %2, 0\n\t"
+        "v_pk_max_i16 %3, %3, 0"
+        : "=&v"(w0), "=&v"(w1), "=&v"(w2), "=&v"(w3)
+        : "v"(acc[o + 0]), "v"(acc[o + 1]), "v"(acc[o + 2]), "v"(acc[o + 3]), "v"(acc[o + 4]), "v"(acc[o + 5]),
+          "v"(acc[o + 6]), "v"(acc[o + 7]));
+    uint4 u = make_uint4(w0, w1, w2, w3);
     return __builtin_bit_cast(bf16x8, u);
 }
 
@@ -190,10 +218,6 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
     (dst)[3 * ST_BLOCK] = sg3;     \
     (dst)[4 * ST_BLOCK] = sg4;     \
     (dst)[5 * ST_BLOCK] = sg5;
-    {
-        const uint4 *src1 = frag + (size_t)1 * CHUNK_U4 + threadIdx.x;
-        STAGE_LOAD(src1)
-    }
     int cur = 0;
 
 #pragma unroll 1
@@ -254,30 +278,33 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         // multiplies zero weights and its result is dropped.
 #define STEP(i, ACC, NEXT, XP_NEW, XP_OLD, IS_FIRST, IS_LAST)                                       \
     {                                                                                                \
+        /* loads in the order they are needed: next weight chunk, next user term, item piece */     \
+        {                                                                                            \
+            int nx = (i) + 1;                                                                        \
+            if (nx >= NSTEP) nx -= NSTEP;                                                            \
+            const uint4 *srcw = frag + (size_t)nx * CHUNK_U4 + threadIdx.x;                          \
+            if (!EXP_NO_STAGE) { STAGE_LOAD(srcw) }                                                  \
+        }                                                                                            \
         if (!(IS_LAST)) {                                                                            \
-            LOAD_USER_TERM(NEXT, (i) + 1)                                                            \
-            XP_NEW = *(const uint4 *)(emb + ((((i) / KS1) & 1) ? nxt_off[1] : nxt_off[0]) + 16 * ((i) % KS1)); \
+            if (!EXP_NO_USER) { LOAD_USER_TERM(NEXT, (i) + 1) }                                                            \
+            if (!EXP_NO_XP) XP_NEW = *(const uint4 *)(emb + ((((i) / KS1) & 1) ? nxt_off[1] : nxt_off[0]) + 16 * ((i) % KS1)); \
         }                                                                                            \
         const uint32_t wc = (uint32_t)(uintptr_t)(wbuf + (size_t)cur * CHUNK_U4 + lane);             \
         bf16x8 f0, f1, f2, f3;                                                                       \
         asm volatile(L1_HEAD L1_BODY_STREAM L2_BODY                                                  \
                      : [p0] "+v"(ACC[0]), [p1] "+v"(ACC[1]), ACC2_OPERANDS, FRAG_TEMPS               \
                      : [wc] "v"(wc), X_OPERANDS, H_OPERANDS);                                        \
-        if (!(IS_LAST)) {                                                                            \
+        if (!(IS_LAST) && !EXP_NO_RELU) {                                                            \
             _Pragma("unroll") for (int c = 0; c < CB; ++c) {                                         \
                 hf[c][0] = relu_pack_i16(ACC[c], 0);                                                 \
                 hf[c][1] = relu_pack_i16(ACC[c], 1);                                                 \
             }                                                                                        \
         }                                                                                            \
-        if (!(IS_FIRST)) xw[((i) - 1) * 64] = XP_OLD; /* piece fetched one step ago */               \
+        if (!(IS_FIRST) && !EXP_NO_XP) xw[((i) - 1) * 64] = XP_OLD; /* piece fetched one step ago */               \
         uint4 *dst = wbuf + (size_t)(cur ^ 1) * CHUNK_U4 + threadIdx.x;                              \
-        STAGE_STORE(dst)                                                                             \
-        __syncthreads();                                                                             \
+        if (!EXP_NO_STAGE) { STAGE_STORE(dst) }                                                      \
+        if (!EXP_NO_BARRIER) __syncthreads();                                                                             \
         cur ^= 1;                                                                                    \
-        int nx = (i) + 2;                                                                            \
-        if (nx >= NSTEP) nx -= NSTEP;                                                                \
-        const uint4 *srcw = frag + (size_t)nx * CHUNK_U4 + threadIdx.x;                              \
-        STAGE_LOAD(srcw)                                                                             \
     }
 
         static_assert(NB1 % 2 == 0 && NB1 == CB * KS1, "steps are unrolled in pairs; one item piece per step");
