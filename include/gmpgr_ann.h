@@ -112,7 +112,7 @@ int ann_mlp_uses_mfma(const ann_mlp *m);
  * E entry points, expansion width <= W_max, eligible ranks <= L_max, k results and
  * <= max_iters_max rounds per query.  The per-query visited table is sized for
  *     E + rounds * W_max * R ids,  rounds = max_iters_max > 0 ? max_iters_max
- *                                                            : 4 * ceil(L_max / W_max) + 32
+ *                                                            : 2 * ceil(L_max / W_max) + 32
  * (at most N).  A query that would outgrow its table stops early and is counted in
  * ann_stats.visited_overflow.  Returns 0 on invalid arguments (see ann_last_error).
  */
@@ -183,6 +183,14 @@ int ann_search_stats(const void *workspace_dev, ann_stats *out_host, void *strea
 enum { ANN_STAGE_SCORE = 0, ANN_STAGE_ROUND = 1, ANN_STAGE_PACK = 2, ANN_STAGE_COUNT = 3 };
 int ann_profile_enable(int on);
 int ann_profile_read(double *ms_out, int64_t *launches_out);
+
+/*
+ * Plain device-to-device copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned) by
+ * a grid-stride kernel, enqueued on `stream`.  It exists for measurement only: it reads and writes
+ * exactly `bytes` bytes of HBM, which gives hardware traffic counters (rocprofv3 FETCH_SIZE /
+ * WRITE_SIZE) a reference of known size in the same run as the search kernels.
+ */
+int ann_profile_copy(void *dst_dev, const void *src_dev, size_t bytes, void *stream);
 
 const char *ann_last_error(void);
 

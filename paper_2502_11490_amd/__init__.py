@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     ann_last_error,
     ann_mlp_load,
     ann_mlp_uses_mfma,
+    ann_profile_copy,
     ann_profile_enable,
     ann_profile_read,
     ann_score_pairs,

@@ -20,7 +20,7 @@ _lib = None
 EXPORTS = [
     "ann_graph_load", "ann_graph_free", "ann_mlp_load", "ann_mlp_free", "ann_mlp_uses_mfma",
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_score_pairs",
-    "ann_search_stats", "ann_profile_enable", "ann_profile_read", "ann_last_error",
+    "ann_search_stats", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
 
@@ -77,6 +77,8 @@ def load_library():
     lib.ann_profile_enable.restype = ctypes.c_int
     lib.ann_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.ann_profile_read.restype = ctypes.c_int
+    lib.ann_profile_copy.argtypes = [vp, vp, sz, vp]
+    lib.ann_profile_copy.restype = ctypes.c_int
     lib.ann_last_error.argtypes = []
     lib.ann_last_error.restype = ctypes.c_char_p
     _lib = lib
@@ -279,3 +281,11 @@ def ann_profile_read() -> dict:
     n = (ctypes.c_int64 * len(STAGES))()
     _check(load_library().ann_profile_read(ms, n))
     return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(STAGES)}
+
+
+def ann_profile_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """Reference copy of known size for hardware traffic counters (dst, src: same-size device tensors)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst and src must have the same size")
+    _check(load_library().ann_profile_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), nbytes, _stream_ptr(stream)))

@@ -68,8 +68,9 @@ bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32
     }
     p->sort_n = next_pow2(p->C + p->slots);
     if (p->sort_n < 2) p->sort_n = 2;
-    // ids one query can score: seeds + rounds * W * R; without a cap, 4*ceil(L/W)+32 rounds are assumed
-    int64_t rounds = max_iters_max > 0 ? max_iters_max : 4 * (int64_t)((L_max + W_max - 1) / W_max) + 32;
+    // ids one query can score: seeds + rounds * W * R with a cap; without one, (2*L + 32*W) * R ids are
+    // assumed (twice the expansions a list of L entries needs, plus slack for short lists)
+    int64_t rounds = max_iters_max > 0 ? max_iters_max : 2 * (int64_t)((L_max + W_max - 1) / W_max) + 32;
     p->rounds_assumed = (int32_t)(rounds > 0x7fffffff ? 0x7fffffff : rounds);
     int64_t visited = (int64_t)E + rounds * W_max * g->R;
     if (visited > g->N) visited = g->N;
@@ -549,6 +550,24 @@ int ann_profile_read(double *ms_out, int64_t *launches_out) {
         launches_out[g_prof.stage[i]] += 1;
     }
     g_prof.used = 0;
+    return ANN_OK;
+}
+
+__global__ void profile_copy_kernel(uint4 *dst, const uint4 *src, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) dst[i] = src[i];
+}
+
+int ann_profile_copy(void *dst_dev, const void *src_dev, size_t bytes, void *stream) {
+    if (!dst_dev || !src_dev || (bytes & 15) || ((uintptr_t)dst_dev & 15) || ((uintptr_t)src_dev & 15)) {
+        set_error("dst_dev, src_dev must be non-null and 16-byte aligned, bytes a multiple of 16");
+        return ANN_EINVAL;
+    }
+    if (bytes == 0) return ANN_OK;
+    hipLaunchKernelGGL(profile_copy_kernel, dim3(4096), dim3(256), 0, (hipStream_t)stream, (uint4 *)dst_dev,
+                       (const uint4 *)src_dev, bytes / 16);
+    ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
 

@@ -18,6 +18,23 @@ namespace gmpgr {
 constexpr int BLOCK = 256;
 constexpr int WAVES = BLOCK / 64;
 
+// Phase timing of the round kernel for measurement builds (-DROUND_TIMING): thread 0 of every
+// workgroup adds the shader-clock ticks of each phase to counters 8..15 of the stats block.
+#ifdef ROUND_TIMING
+#define PHASE_MARK(k)                                                                          \
+    do {                                                                                       \
+        if (threadIdx.x == 0) {                                                                \
+            long long now_ = clock64();                                                        \
+            atomicAdd((unsigned long long *)&stats[8 + (k)], (unsigned long long)(now_ - t_)); \
+            t_ = now_;                                                                         \
+        }                                                                                      \
+    } while (0)
+#define PHASE_START long long t_ = clock64();
+#else
+#define PHASE_MARK(k)
+#define PHASE_START
+#endif
+
 // ---- order-preserving key: ascending uint64 == (score descending, id ascending) ----------
 __device__ __forceinline__ uint64_t make_key(float score, int32_t id, uint32_t expanded) {
     uint32_t f = __float_as_uint(score);
@@ -120,17 +137,14 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
                 while (dd_key[s] != (uint32_t)v) s = (s + 1u) & dd_mask;
                 if (dd_pos[s] == (uint32_t)p) {
                     uint32_t h = (hash_cap > 1) ? (hash_id((uint32_t)v) >> shift) : 0u;
+                    // one atomic per probe: it returns the slot's content whether or not it swapped
                     for (;;) {
-                        uint32_t cur = table[h];
-                        if (cur == (uint32_t)v) break;  // scored in an earlier round
-                        if (cur == EMPTY_SLOT) {
-                            uint32_t old = atomicCAS(&table[h], EMPTY_SLOT, (uint32_t)v);
-                            if (old == EMPTY_SLOT) {
-                                fresh = true;
-                                break;
-                            }
-                            if (old == (uint32_t)v) break;
+                        uint32_t old = atomicCAS(&table[h], EMPTY_SLOT, (uint32_t)v);
+                        if (old == EMPTY_SLOT) {
+                            fresh = true;
+                            break;
                         }
+                        if (old == (uint32_t)v) break;  // scored in an earlier round
                         h = (h + 1u) & hmask;
                     }
                 }
@@ -147,7 +161,7 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
 // Counters and control block start at zero (a kernel, not a memset, so that a caller may
 // capture the launch sequence into a HIP graph).
 __global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q) {
-    if (threadIdx.x < 8) stats[threadIdx.x] = (threadIdx.x == 4) ? Q : 0;
+    if (threadIdx.x < 16) stats[threadIdx.x] = (threadIdx.x == 4) ? Q : 0;
     if (threadIdx.x < 16) ((int32_t *)ctrl)[threadIdx.x] = 0;
 }
 
@@ -193,8 +207,12 @@ init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state
 }
 
 // ------------------------------------------------------------------------------------------
-// Exclusive scan of survivor counts + stable packing into the dense pair list.
-constexpr int SCAN_QPB = 64;  // queries per workgroup
+// Exclusive scan of survivor counts + stable packing into the dense pair list (Algorithm 2).
+// A workgroup owns SCAN_QPB consecutive queries.  It first sums the counts of all earlier queries
+// (every workgroup re-reads them from L2: O(Q^2 / SCAN_QPB) four-byte reads in total, no waiting on
+// other workgroups, the same result every run), then scans its own counts and copies its groups,
+// one wave per query at a time.
+constexpr int SCAN_QPB = 16;  // queries per workgroup
 __global__ void __launch_bounds__(BLOCK)
 scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__restrict__ cand_g, int slots,
                     int32_t *offsets, int32_t *pair_q, int32_t *pair_id, Ctrl *ctrl) {
@@ -226,31 +244,33 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
         prefix += red[w];
         n_active += red_active[w];
     }
-    // scan of this workgroup's 64 counts by the first wave
     if (threadIdx.x < 64) {
         int q = q0 + threadIdx.x;
-        int c = (q < Q) ? max(counts[q], 0) : 0;
+        int c = (threadIdx.x < SCAN_QPB && q < Q) ? max(counts[q], 0) : 0;
         int inc = c;
-        for (int o = 1; o < 64; o <<= 1) {
+        for (int o = 1; o < SCAN_QPB; o <<= 1) {
             int v = __shfl_up(inc, o);
             if ((int)threadIdx.x >= o) inc += v;
         }
-        loc_cnt[threadIdx.x] = c;
-        loc_off[threadIdx.x] = prefix + inc - c;
-        if (threadIdx.x == 63) loc_off[64] = prefix + inc;
-        if (q < Q) offsets[q] = prefix + inc - c;
+        if (threadIdx.x < SCAN_QPB) {
+            loc_cnt[threadIdx.x] = c;
+            loc_off[threadIdx.x] = prefix + inc - c;
+            if (threadIdx.x == SCAN_QPB - 1) loc_off[SCAN_QPB] = prefix + inc;
+            if (q < Q) offsets[q] = prefix + inc - c;
+        }
     }
     __syncthreads();
     if (last && threadIdx.x == 0) {
-        ctrl->M = loc_off[64];
+        ctrl->M = loc_off[SCAN_QPB];
         ctrl->n_active = n_active;
     }
-    for (int i = 0; i < SCAN_QPB; ++i) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = wave; i < SCAN_QPB; i += WAVES) {
         int q = q0 + i;
         if (q >= Q) break;
         int c = loc_cnt[i], off = loc_off[i];
         const int32_t *src = cand_g + (size_t)q * slots;
-        for (int j = threadIdx.x; j < c; j += BLOCK) {
+        for (int j = lane; j < c; j += 64) {
             pair_id[off + j] = src[j];
             pair_q[off + j] = q;
         }
@@ -259,13 +279,30 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
 
 // ------------------------------------------------------------------------------------------
 // One round of one query.
+//
+// Merge (a6).  Only new entries that can enter the list are kept (better than the current worst
+// entry once the list is full), they are sorted on their own (bitonic, <= W*R keys) and merged
+// with the sorted list by rank: an entry's final position is its index in its own sequence plus
+// the number of entries of the other sequence that precede it (binary search).  Keys are unique
+// (an id is scored once per query), so the ranks are a permutation.
+__device__ __forceinline__ int lower_bound_keys(const uint64_t *a, int n, uint64_t key) {
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if (a[mid] < key) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo;
+}
+
 __global__ void __launch_bounds__(BLOCK)
 round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, uint64_t *pool_g, int C,
              uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
-             const int32_t *__restrict__ offsets, const float *__restrict__ scores, int sort_cap,
+             const int32_t *__restrict__ offsets, const float *__restrict__ scores, int new_cap,
              int W_max, int64_t *stats) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int q = blockIdx.x;
+    PHASE_START
     QState st = state[q];
     if (st.done) {
         if (threadIdx.x == 0) counts[q] = -1;
@@ -273,12 +310,16 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     }
     int dd_n = 2;
     while (dd_n < 2 * slots) dd_n <<= 1;
-    uint64_t *keys = (uint64_t *)smem;                       // [sort_cap]
-    int32_t *cand = (int32_t *)(keys + sort_cap);             // [slots]
+    // LDS: parents and scan scratch first; then one region used twice: by the list buffers until
+    // the list is written back, by the candidate ids and the dedupe table afterwards
+    int32_t *parents = (int32_t *)smem;                       // [W_max]
+    int *wave_sums = parents + ((W_max + 3) & ~3);            // [WAVES + 1], padded to 8
+    uint64_t *keys = (uint64_t *)(wave_sums + 8);             // [C]       merged list
+    uint64_t *oldk = keys + C;                                // [C]       list as stored
+    uint64_t *newk = oldk + C;                                // [new_cap] new entries, sorted
+    int32_t *cand = (int32_t *)keys;                          // [slots]
     uint32_t *dd_key = (uint32_t *)(cand + ((slots + 3) & ~3));
     uint32_t *dd_pos = dd_key + dd_n;
-    int32_t *parents = (int32_t *)(dd_pos + dd_n);            // [W_max]
-    int *wave_sums = parents + ((W_max + 3) & ~3);            // [WAVES + 1]
 
     uint64_t *pool = pool_g + (size_t)q * C;
     int32_t *cand_q = cand_g + (size_t)q * slots;
@@ -286,37 +327,66 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     const int off = offsets[q];
 
     // 1. merge the scores of the previous round (or of the seeds) into the sorted list
-    int n_all = st.n_list + n_prev;
-    if (n_prev > 0) {
-        int n2 = 2;
-        while (n2 < n_all) n2 <<= 1;
-        for (int i = threadIdx.x; i < n2; i += BLOCK) {
-            uint64_t key = KEY_SENTINEL;
-            if (i < st.n_list) key = pool[i];
-            else if (i < n_all) key = make_key(scores[off + i - st.n_list], cand_q[i - st.n_list], 0u);
-            keys[i] = key;
+    for (int i = threadIdx.x; i < st.n_list; i += BLOCK) oldk[i] = pool[i];
+    __syncthreads();
+    PHASE_MARK(0);  // state + list load
+    const bool full = (st.n_list == C);
+    const uint64_t worst = full ? oldk[C - 1] : KEY_SENTINEL;
+    int m = 0;
+    for (int j0 = 0; j0 < n_prev; j0 += BLOCK) {
+        int j = j0 + threadIdx.x;
+        uint64_t key = KEY_SENTINEL;
+        bool keep = false;
+        if (j < n_prev) {
+            key = make_key(scores[off + j], cand_q[j], 0u);
+            keep = key < worst;
         }
-        __syncthreads();
-        bitonic_sort(keys, n2);
-    } else {
-        for (int i = threadIdx.x; i < st.n_list; i += BLOCK) keys[i] = pool[i];
-        __syncthreads();
+        int tot;
+        int pos = block_excl_count(keep, wave_sums, &tot);
+        if (keep) newk[m + pos] = key;
+        m += tot;
     }
-    const int n_list = min(n_all, C);
+    PHASE_MARK(1);  // new keys: scores load + filter
+    const uint64_t *list = oldk;
+    int n_list = st.n_list;
+    if (m > 0) {
+        int m2 = 2;
+        while (m2 < m) m2 <<= 1;
+        for (int i = m + threadIdx.x; i < m2; i += BLOCK) newk[i] = KEY_SENTINEL;
+        __syncthreads();
+        bitonic_sort(newk, m2);
+        for (int i = threadIdx.x; i < st.n_list + m; i += BLOCK) {
+            uint64_t key;
+            int pos;
+            if (i < st.n_list) {
+                key = oldk[i];
+                pos = i + lower_bound_keys(newk, m, key);
+            } else {
+                key = newk[i - st.n_list];
+                pos = (i - st.n_list) + lower_bound_keys(oldk, st.n_list, key);
+            }
+            if (pos < C) keys[pos] = key;
+        }
+        n_list = min(C, st.n_list + m);
+        list = keys;
+    }
+    __syncthreads();
+    PHASE_MARK(2);  // sort + rank merge
+    uint64_t *lw = const_cast<uint64_t *>(list);
 
     // 2. termination test and choice of the parents
     int n_par = 0;
     const bool capped = (st.cap > 0 && st.t >= st.cap);
+    const int lim = min(st.L, n_list);
     if (!capped) {
-        const int lim = min(st.L, n_list);
         for (int i0 = 0; i0 < lim && n_par < st.W; i0 += BLOCK) {
             int i = i0 + threadIdx.x;
-            bool open = (i < lim) && !key_expanded(keys[i]);
+            bool open = (i < lim) && !key_expanded(lw[i]);
             int tot;
             int pos = block_excl_count(open, wave_sums, &tot);
             if (open && n_par + pos < st.W) {
-                parents[n_par + pos] = key_id(keys[i]);
-                keys[i] |= 1ull;
+                parents[n_par + pos] = key_id(lw[i]);
+                lw[i] |= 1ull;
             }
             n_par = min(st.W, n_par + tot);
         }
@@ -328,7 +398,10 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         overflow = true;
         n_par = 0;
     }
-    for (int i = threadIdx.x; i < n_list; i += BLOCK) pool[i] = keys[i];
+    // write back what changed: the whole list after a merge, else only the ranks whose
+    // expanded bit may have been set
+    const int n_store = (m > 0) ? n_list : lim;
+    for (int i = threadIdx.x; i < n_store; i += BLOCK) pool[i] = lw[i];
     if (n_par == 0) {
         if (threadIdx.x == 0) {
             st.n_list = n_list;
@@ -343,16 +416,20 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     }
 
     // 3. neighbour gather: one adjacency row per parent, consecutive lanes read consecutive ids
+    __syncthreads();  // the list buffers are dead from here on; their LDS is reused
+    PHASE_MARK(3);  // selection + write-back
     const int n_cand = n_par * R;
     for (int j = threadIdx.x; j < n_cand; j += BLOCK) {
         int p = j / R, s = j - p * R;
         cand[j] = adj[(size_t)parents[p] * R + s];
     }
     __syncthreads();
+    PHASE_MARK(4);  // adjacency gather
 
     // 4. visited filter, 5. survivors of this query for the next MLP launch
     int n_new = filter_and_insert(cand, n_cand, dd_key, dd_pos, dd_n, hash + (size_t)q * hash_cap, hash_cap, N,
                                   cand_q, wave_sums);
+    PHASE_MARK(5);  // dedupe + visited table
     if (threadIdx.x == 0) {
         st.n_list = n_list;
         st.t += 1;
@@ -386,11 +463,18 @@ emit_kernel(const QState *__restrict__ state, const uint64_t *__restrict__ pool_
 }
 
 // ------------------------------------------------------------------------------------------
+static int new_cap_of(const Plan &p) {
+    int n = 2;
+    while (n < p.slots) n <<= 1;
+    return n;
+}
+
 static size_t round_smem(const Plan &p) {
     int dd_n = 2;
     while (dd_n < 2 * p.slots) dd_n <<= 1;
-    return (size_t)p.sort_n * 8 + (size_t)((p.slots + 3) & ~3) * 4 + (size_t)dd_n * 8 +
-           (size_t)((p.W_max + 3) & ~3) * 4 + (WAVES + 1 + 4) * 4;
+    size_t lists = (size_t)(2 * p.C + new_cap_of(p)) * 8;
+    size_t filt = (size_t)((p.slots + 3) & ~3) * 4 + (size_t)dd_n * 8;
+    return (size_t)((p.W_max + 3) & ~3) * 4 + 8 * 4 + (lists > filt ? lists : filt);
 }
 
 int launch_init(const SearchArgs &a) {
@@ -426,14 +510,14 @@ int launch_round(const SearchArgs &a) {
     int dev = a.m->device;
     if (smem > 48 * 1024 && dev >= 0 && dev < 16 && !attr_set[dev]) {
         ANN_HIP_TRY(hipFuncSetAttribute((const void *)round_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        96 * 1024));
+                                        128 * 1024));
         attr_set[dev] = true;
     }
     hipLaunchKernelGGL(round_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.g->adj, p.R, a.g->N,
                        (QState *)(a.ws + p.off_state), (uint64_t *)(a.ws + p.off_pool), p.C,
                        (uint32_t *)(a.ws + p.off_hash), p.hash_cap, (int32_t *)(a.ws + p.off_cand), p.slots,
                        (int32_t *)(a.ws + p.off_counts), (const int32_t *)(a.ws + p.off_offsets),
-                       (const float *)(a.ws + p.off_scores), p.sort_n, p.W_max,
+                       (const float *)(a.ws + p.off_scores), new_cap_of(p), p.W_max,
                        (int64_t *)(a.ws + p.off_stats));
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;

@@ -1,0 +1,104 @@
+"""Parity at the full sizes of the named workloads, in the launch configuration bench.py times.
+
+The oracle cannot run whole batches at these sizes in seconds, so each test runs the GPU search
+on the full batch and checks (a) a seeded sample of queries against the oracle's search of those
+very queries, (b) every returned (id, score) of the sample against the oracle's relevance of
+that pair, (c) recall@k against an exhaustive ground truth for GPU and oracle, and (d) the
+structural properties that hold for every query of the batch at any size.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import PRESETS, make_workload, to_host
+
+pytestmark = pytest.mark.gpu
+
+ann = pytest.importorskip("paper_2502_11490_amd")
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+from bench import recall_at, torch_ground_truth  # noqa: E402  (plain torch reference, no HIP kernels)
+
+
+def _structure(ids, sc, N):
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    assert ids.min() >= -1 and ids.max() < N
+    assert np.array_equal(ids < 0, np.isneginf(sc))
+    s = np.where(ids >= 0, sc, -np.inf)
+    assert np.all(s[:, :-1] >= s[:, 1:]), "scores must be non-increasing"
+    srt = np.sort(ids, axis=1)
+    dup = (srt[:, 1:] == srt[:, :-1]) & (srt[:, 1:] >= 0)
+    assert not dup.any(), "an id was returned twice"
+    tie = (s[:, :-1] == s[:, 1:]) & (ids[:, 1:] >= 0)
+    assert np.all(ids[:, :-1][tie] < ids[:, 1:][tie]), "equal scores must be ordered by id"
+    return ids, sc
+
+
+def _sample_check(wl, cfg, ids, sc, q_sel, W, L, cap, k, recall_k):
+    h = to_host({n: wl[n] for n in ("emb", "adj", "W", "b", "head_w")})
+    hu = to_host({"users": wl["users"][q_sel], "entries": wl["entries"][q_sel]})
+    mlp = oracle.Mlp(h["W"], h["b"], h["head_w"])
+    ref = oracle.search(h["emb"], h["adj"], hu["users"], mlp, hu["entries"], W, L, k, cap, n_threads=16)
+    kern = oracle.search(h["emb"], h["adj"], hu["users"], mlp, hu["entries"], W, L, k, cap, act_round=1, n_threads=16)
+    got_ids, got_sc = ids[q_sel], sc[q_sel]
+    # (b) relevance of what was returned
+    qq = np.repeat(np.arange(len(q_sel)), k).astype(np.int32)
+    valid = got_ids.ravel() >= 0
+    exact = oracle.score_pairs(h["emb"], hu["users"], mlp, qq[valid], got_ids.ravel()[valid], n_threads=16)
+    assert np.max(np.abs(got_sc.ravel()[valid] - exact)) <= 1e-2
+    # (c) recall against exhaustive ground truth (plain torch fp32 on the GPU)
+    truth = torch_ground_truth(wl, list(q_sel), recall_k).cpu()
+    r_gpu = recall_at(torch.from_numpy(got_ids), truth, recall_k)
+    r_ref = recall_at(torch.from_numpy(ref["ids"]), truth, recall_k)
+    r_kern = recall_at(torch.from_numpy(kern["ids"]), truth, recall_k)
+    same_kern = float(np.mean(np.all(got_ids == kern["ids"], axis=1)))
+    print(f"{cfg.name}: recall@{recall_k} gpu {r_gpu:.4f} oracle {r_ref:.4f} oracle@kernel-precision {r_kern:.4f}; "
+          f"identical lists vs kernel-precision oracle {same_kern:.3f}")
+    assert abs(r_gpu - r_ref) <= 0.01 + 1e-9, (r_gpu, r_ref)
+    # valid padding: a query returns fewer than k ids only if the oracle does too
+    assert np.array_equal((got_ids >= 0).sum(1), (ref["ids"] >= 0).sum(1))
+
+
+# sample sizes: the recall difference of two searches has a standard error of about 0.02/sqrt(n)
+# at these recall levels, so 1 point is > 5 standard errors
+@pytest.mark.parametrize("preset,n_sample", [("C2", 128), ("C3", 192)])
+def test_full_size_uniform(preset, n_sample):
+    cfg = PRESETS[preset]
+    wl = make_workload(cfg, device="cuda:0")
+    dtype = ann.ANN_BF16
+    g = ann.ann_graph_load(wl["adj"], wl["emb"], ann.ANN_VALIDATE)
+    m = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, dtype)
+    assert ann.ann_mlp_uses_mfma(m)
+    ws = torch.empty(ann.ann_search_workspace_bytes(g, m, cfg.Q, cfg.E, cfg.W, cfg.L, cfg.k, 0), dtype=torch.uint8,
+                     device="cuda:0")
+    ids, sc = ann.ann_search(g, m, wl["users"], wl["entries"], cfg.W, cfg.L, cfg.k, 0, workspace=ws)
+    st = ann.ann_search_stats(ws)
+    assert st.visited_overflow == 0 and st.queries == cfg.Q
+    ids, sc = _structure(ids, sc, cfg.N)
+    q_sel = np.sort(np.random.default_rng(5).choice(cfg.Q, n_sample, replace=False))
+    _sample_check(wl, cfg, ids, sc, q_sel, cfg.W, cfg.L, 0, cfg.k, min(100, cfg.k))
+
+
+def test_full_size_ragged():
+    cfg = PRESETS["C5"]
+    wl = make_workload(cfg, device="cuda:0")
+    g = ann.ann_graph_load(wl["adj"], wl["emb"], ann.ANN_VALIDATE)
+    m = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, ann.ANN_BF16)
+    Wm, Lm, capm = cfg.W_range[1], cfg.L_range[1], cfg.cap_range[1]
+    ws = torch.empty(ann.ann_search_workspace_bytes(g, m, cfg.Q, cfg.E, Wm, Lm, cfg.k, capm), dtype=torch.uint8,
+                     device="cuda:0")
+    ids, sc = ann.ann_search_ragged(g, m, wl["users"], wl["entries"], wl["W_q"], wl["L_q"], wl["cap_q"], Wm, Lm,
+                                    cfg.k, capm, workspace=ws)
+    st = ann.ann_search_stats(ws)
+    assert st.visited_overflow == 0
+    assert st.max_query_iters <= capm
+    ids, sc = _structure(ids, sc, cfg.N)
+    # half of the users sit near hot clusters, half are N(0,1): sample both halves
+    rng = np.random.default_rng(6)
+    q_sel = np.sort(np.concatenate([rng.choice(cfg.Q // 2, 64, replace=False),
+                                    cfg.Q // 2 + rng.choice(cfg.Q // 2, 64, replace=False)]))
+    Wq, Lq, cq = (wl[n].cpu().numpy()[q_sel] for n in ("W_q", "L_q", "cap_q"))
+    _sample_check(wl, cfg, ids, sc, q_sel, Wq, Lq, cq, cfg.k, cfg.k)

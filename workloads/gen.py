@@ -151,7 +151,7 @@ def _knn_in_clusters(x: torch.Tensor, starts: torch.Tensor, counts: torch.Tensor
             s0, n = ss[i], cs[i]
             xb = x[s0:s0 + n]
             sqb = sq[s0:s0 + n]
-            rows = max(1, budget // n)
+            rows = max(1, (budget << 3) // n)  # a few GB of distances at a time on the big clusters
             for r0 in range(0, n, rows):
                 r1 = min(n, r0 + rows)
                 dist = sqb[r0:r1, None] + sqb[None, :] - 2.0 * (xb[r0:r1] @ xb.T)
