@@ -25,6 +25,8 @@
 // a wave-private LDS area, so the HBM gather latency is hidden behind a whole batch of MFMAs.
 //
 // Hazards handled by hand inside the assembly (the compiler cannot see into it):
+//   - the ReLU + bf16 conversion of a step's fresh layer-1 accumulators is interleaved with the
+//     layer-2 MFMAs of the same block and starts six MFMAs after the last layer-1 MFMA;
 //   - every block starts with s_waitcnt lgkmcnt(0): afterwards only its own LDS reads are in
 //     flight and the counted waits (lgkmcnt(3..0)) are exact;
 //   - an accumulator is never the target of two consecutive MFMAs (pairs 0 and 1 alternate);
@@ -43,6 +45,7 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int ST_BLOCK = 256;
 
@@ -59,6 +62,12 @@ constexpr int ST_BLOCK = 256;
 #endif
 #ifndef EXP_NO_BARRIER
 #define EXP_NO_BARRIER 0
+#endif
+#ifndef EXP_NO_STAGE_LOAD
+#define EXP_NO_STAGE_LOAD 0
+#endif
+#ifndef EXP_NO_STAGE_STORE
+#define EXP_NO_STAGE_STORE 0
 #endif
 #ifndef EXP_NO_RELU
 #define EXP_NO_RELU 0
@@ -93,45 +102,14 @@ __device__ __forceinline__ void drain_v(f32x16 &x, f32x16 &y) {
     asm volatile("s_nop 15" : "+v"(x), "+v"(y));
 }
 
-#define LD(buf, off) "ds_read_b128 %[" #buf "], %[wc] offset:" #off "\n\t"
-#define WT(n) "s_waitcnt lgkmcnt(" #n ")\n\t"
-#define M1(f, s)                                                                   \
-    "v_mfma_f32_32x32x16_bf16 %[p0], %[" #f "], %[x0" #s "], %[p0]\n\t"            \
-    "v_mfma_f32_32x32x16_bf16 %[p1], %[" #f "], %[x1" #s "], %[p1]\n\t"
-#define M2(f, n2, s2)                                                                      \
-    "v_mfma_f32_32x32x16_bf16 %[a" #n2 "0], %[" #f "], %[h0" #s2 "], %[a" #n2 "0]\n\t"     \
-    "v_mfma_f32_32x32x16_bf16 %[a" #n2 "1], %[" #f "], %[h1" #s2 "], %[a" #n2 "1]\n\t"
+#include "mlp_mfma_stream_asm.inc"  // STREAM_ASM_FIRST / MID_A / MID_B / LAST and their operand lists
 
-// fragments 0..7 of the chunk: layer 1 (one per 16 item coordinates)
-#define L1_HEAD WT(0) LD(f0, 0) LD(f1, 1024) LD(f2, 2048) LD(f3, 3072)
-#define L1_BODY_STREAM                                                                     \
-    WT(3) M1(f0, 0) LD(f0, 4096) WT(3) M1(f1, 1) LD(f1, 5120) WT(3) M1(f2, 2) LD(f2, 6144)  \
-    WT(3) M1(f3, 3) LD(f3, 7168) WT(3) M1(f0, 4) LD(f0, 8192) WT(3) M1(f1, 5) LD(f1, 9216)  \
-    WT(3) M1(f2, 6) LD(f2, 10240) WT(3) M1(f3, 7) LD(f3, 11264)
-#define L1_BODY_ONLY                                                                       \
-    WT(3) M1(f0, 0) LD(f0, 4096) WT(3) M1(f1, 1) LD(f1, 5120) WT(3) M1(f2, 2) LD(f2, 6144)  \
-    WT(3) M1(f3, 3) LD(f3, 7168) WT(3) M1(f0, 4) WT(2) M1(f1, 5) WT(1) M1(f2, 6) WT(0) M1(f3, 7)
-// fragments 8..23 of the chunk: layer 2, fragment 8 + 2*n2 + s2
-#define L2_HEAD WT(0) LD(f0, 8192) LD(f1, 9216) LD(f2, 10240) LD(f3, 11264)
-#define L2_BODY                                                                               \
-    WT(3) M2(f0, 0, 0) LD(f0, 12288) WT(3) M2(f1, 0, 1) LD(f1, 13312) WT(3) M2(f2, 1, 0) LD(f2, 14336) \
-    WT(3) M2(f3, 1, 1) LD(f3, 15360) WT(3) M2(f0, 2, 0) LD(f0, 16384) WT(3) M2(f1, 2, 1) LD(f1, 17408) \
-    WT(3) M2(f2, 3, 0) LD(f2, 18432) WT(3) M2(f3, 3, 1) LD(f3, 19456) WT(3) M2(f0, 4, 0) LD(f0, 20480) \
-    WT(3) M2(f1, 4, 1) LD(f1, 21504) WT(3) M2(f2, 5, 0) LD(f2, 22528) WT(3) M2(f3, 5, 1) LD(f3, 23552) \
-    WT(3) M2(f0, 6, 0) WT(2) M2(f1, 6, 1) WT(1) M2(f2, 7, 0) WT(0) M2(f3, 7, 1)
-
-#define ACC2_OPERANDS                                                                              \
-    [a00] "+a"(acc2[0][0]), [a01] "+a"(acc2[0][1]), [a10] "+a"(acc2[1][0]), [a11] "+a"(acc2[1][1]), \
-    [a20] "+a"(acc2[2][0]), [a21] "+a"(acc2[2][1]), [a30] "+a"(acc2[3][0]), [a31] "+a"(acc2[3][1]), \
-    [a40] "+a"(acc2[4][0]), [a41] "+a"(acc2[4][1]), [a50] "+a"(acc2[5][0]), [a51] "+a"(acc2[5][1]), \
-    [a60] "+a"(acc2[6][0]), [a61] "+a"(acc2[6][1]), [a70] "+a"(acc2[7][0]), [a71] "+a"(acc2[7][1])
 #define FRAG_TEMPS [f0] "=&v"(f0), [f1] "=&v"(f1), [f2] "=&v"(f2), [f3] "=&v"(f3)
 #define X_OPERANDS                                                                                  \
     [x00] "v"(xf[0][0]), [x01] "v"(xf[0][1]), [x02] "v"(xf[0][2]), [x03] "v"(xf[0][3]),             \
     [x04] "v"(xf[0][4]), [x05] "v"(xf[0][5]), [x06] "v"(xf[0][6]), [x07] "v"(xf[0][7]),             \
     [x10] "v"(xf[1][0]), [x11] "v"(xf[1][1]), [x12] "v"(xf[1][2]), [x13] "v"(xf[1][3]),             \
     [x14] "v"(xf[1][4]), [x15] "v"(xf[1][5]), [x16] "v"(xf[1][6]), [x17] "v"(xf[1][7])
-#define H_OPERANDS [h00] "v"(hf[0][0]), [h01] "v"(hf[0][1]), [h10] "v"(hf[1][0]), [h11] "v"(hf[1][1])
 
 // Weight fragments, bf16, 1 KB each (lane l at byte 16*l), NB1 + 1 chunks of 24 fragments:
 //   chunk i, fragment s < 8       lane (m,g): W1_item[32i+m][16s + 8g + j]                      (zero for i = NB1)
@@ -203,7 +181,7 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
 
     // `stage` always holds (in flight) the chunk of the next step
     static_assert(ST == 6, "six staged uint4 per thread");
-    uint4 sg0, sg1, sg2, sg3, sg4, sg5;  // named scalars: an indexed array would live in scratch
+    uint4 sg0 = {}, sg1 = {}, sg2 = {}, sg3 = {}, sg4 = {}, sg5 = {};  // named scalars: an indexed array would live in scratch
 #define STAGE_LOAD(src)            \
     sg0 = (src)[0 * ST_BLOCK];     \
     sg1 = (src)[1 * ST_BLOCK];     \
@@ -255,68 +233,87 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
             for (int c = 0; c < CB; ++c) acc2[n2][c] = init;
         }
 
-        // Two sets of layer-1 accumulators alternate: while one is used by a step, the other
-        // receives the per-query user term of the next step (no register copies).
-        f32x16 accA[CB], accB[CB];
-#define LOAD_USER_TERM(ACC, nb)                                                   \
-    _Pragma("unroll") for (int c = 0; c < CB; ++c)                                \
-        _Pragma("unroll") for (int t4 = 0; t4 < 4; ++t4) {                        \
-            f32x4 pv = *(const f32x4 *)(up[c] + (nb) * 32 + 8 * t4);              \
-            _Pragma("unroll") for (int e = 0; e < 4; ++e) ACC[c][4 * t4 + e] = pv[e]; \
-        }
-        LOAD_USER_TERM(accA, 0)
-        bf16x8 hf[CB][2];
-#pragma unroll
-        for (int c = 0; c < CB; ++c) hf[c][0] = hf[c][1] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-
-        // One pipeline step.  The 16-byte piece of the next batch's item rows fetched in step i is
-        // written to LDS at the end of step i+1, two steps after its load was issued.
-        // ACC holds this step's layer-1 start values, NEXT receives those of
-        // step i+1 (the row of user terms is padded by 32 floats, so i+1 = NB1 reads valid memory
-        // that is never used).  The same assembly block serves every step: in step 0 the layer-2
-        // half multiplies zero weights with zero activations, in step NB1 the layer-1 half
-        // multiplies zero weights and its result is dropped.
-#define STEP(i, ACC, NEXT, XP_NEW, XP_OLD, IS_FIRST, IS_LAST)                                       \
+        // Two sets of layer-1 accumulators (A, B) and of converted hidden units alternate by step;
+        // all of them, and the layer-2 accumulators, sit in fixed physical registers (see
+        // gen_stream_asm.py), so every variant of the step agrees on where they are.
+        f32x16 accA0, accA1, accB0, accB1;
+        u32x4 hA00, hA01, hA10, hA11, hB00, hB01, hB10, hB11;
+#define LOAD_USER_TERM(ACC0, ACC1, nb)                                            \
+    _Pragma("unroll") for (int t4 = 0; t4 < 4; ++t4) {                            \
+        f32x4 pv0 = *(const f32x4 *)(up[0] + (nb) * 32 + 8 * t4);                 \
+        f32x4 pv1 = *(const f32x4 *)(up[1] + (nb) * 32 + 8 * t4);                 \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                           \
+            ACC0[4 * t4 + e] = pv0[e];                                            \
+            ACC1[4 * t4 + e] = pv1[e];                                            \
+        }                                                                         \
+    }
+        // Before the assembly of step i: global loads in the order their data is needed (weight
+        // chunk i+1, user term of step i+1, one 16-byte piece of the next batch's item rows).
+#define STEP_PRE(i, NEXT0, NEXT1, XP_NEW, LOAD_NEXT, LOAD_XP)                                        \
     {                                                                                                \
-        /* loads in the order they are needed: next weight chunk, next user term, item piece */     \
-        {                                                                                            \
-            int nx = (i) + 1;                                                                        \
-            if (nx >= NSTEP) nx -= NSTEP;                                                            \
-            const uint4 *srcw = frag + (size_t)nx * CHUNK_U4 + threadIdx.x;                          \
-            if (!EXP_NO_STAGE) { STAGE_LOAD(srcw) }                                                  \
-        }                                                                                            \
-        if (!(IS_LAST)) {                                                                            \
-            if (!EXP_NO_USER) { LOAD_USER_TERM(NEXT, (i) + 1) }                                                            \
-            if (!EXP_NO_XP) XP_NEW = *(const uint4 *)(emb + ((((i) / KS1) & 1) ? nxt_off[1] : nxt_off[0]) + 16 * ((i) % KS1)); \
-        }                                                                                            \
-        const uint32_t wc = (uint32_t)(uintptr_t)(wbuf + (size_t)cur * CHUNK_U4 + lane);             \
-        bf16x8 f0, f1, f2, f3;                                                                       \
-        asm volatile(L1_HEAD L1_BODY_STREAM L2_BODY                                                  \
-                     : [p0] "+v"(ACC[0]), [p1] "+v"(ACC[1]), ACC2_OPERANDS, FRAG_TEMPS               \
-                     : [wc] "v"(wc), X_OPERANDS, H_OPERANDS);                                        \
-        if (!(IS_LAST) && !EXP_NO_RELU) {                                                            \
-            _Pragma("unroll") for (int c = 0; c < CB; ++c) {                                         \
-                hf[c][0] = relu_pack_i16(ACC[c], 0);                                                 \
-                hf[c][1] = relu_pack_i16(ACC[c], 1);                                                 \
-            }                                                                                        \
-        }                                                                                            \
-        if (!(IS_FIRST) && !EXP_NO_XP) xw[((i) - 1) * 64] = XP_OLD; /* piece fetched one step ago */               \
+        int nx = (i) + 1;                                                                            \
+        if (nx >= NSTEP) nx -= NSTEP;                                                                \
+        const uint4 *srcw = frag + (size_t)nx * CHUNK_U4 + threadIdx.x;                              \
+        if (!EXP_NO_STAGE && !EXP_NO_STAGE_LOAD) { STAGE_LOAD(srcw) }                                \
+        if ((LOAD_NEXT) && !EXP_NO_USER) { LOAD_USER_TERM(NEXT0, NEXT1, (i) + 1) }                    \
+        if ((LOAD_XP) && !EXP_NO_XP)                                                                 \
+            XP_NEW = *(const uint4 *)(emb + ((((i) / KS1) & 1) ? nxt_off[1] : nxt_off[0]) + 16 * ((i) % KS1)); \
+    }                                                                                                \
+    const uint32_t wc = (uint32_t)(uintptr_t)(wbuf + (size_t)cur * CHUNK_U4 + lane);                 \
+    bf16x8 f0, f1, f2, f3;
+        // After it: the piece fetched one step ago goes to LDS, the staged chunk to the other
+        // buffer, one barrier.
+#define STEP_POST(i, XP_OLD, STORE_XP)                                                               \
+    {                                                                                                \
+        if ((STORE_XP) && !EXP_NO_XP) xw[((i) - 1) * 64] = XP_OLD;                                   \
         uint4 *dst = wbuf + (size_t)(cur ^ 1) * CHUNK_U4 + threadIdx.x;                              \
-        if (!EXP_NO_STAGE) { STAGE_STORE(dst) }                                                      \
-        if (!EXP_NO_BARRIER) __syncthreads();                                                                             \
+        if (!EXP_NO_STAGE && !EXP_NO_STAGE_STORE) { STAGE_STORE(dst) }                               \
+        if (!EXP_NO_BARRIER) __syncthreads();                                                        \
         cur ^= 1;                                                                                    \
     }
-
-        static_assert(NB1 % 2 == 0 && NB1 == CB * KS1, "steps are unrolled in pairs; one item piece per step");
+        static_assert(NB1 % 2 == 0 && NB1 == CB * KS1, "steps come in A/B pairs; one item piece per step");
         uint4 xpA, xpB;
-#pragma unroll 1
-        for (int i = 0; i < NB1; i += 2) {
-            STEP(i, accA, accB, xpA, xpB, i == 0, false)
-            STEP(i + 1, accB, accA, xpB, xpA, false, false)
+        LOAD_USER_TERM(accA0, accA1, 0)
+        {   // step 0: layer 1 only
+            STEP_PRE(0, accB0, accB1, xpA, true, true)
+            asm volatile(STREAM_ASM_FIRST
+                         : STREAM_ACC_A(accA0, accA1), STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), FRAG_TEMPS
+                         : [wc] "v"(wc), X_OPERANDS);
+            STEP_POST(0, xpB, false)
         }
-        STEP(NB1, accA, accB, xpA, xpB, false, true)
-        asm volatile("s_nop 15" : "+a"(acc2[NB2 - 1][0]), "+a"(acc2[NB2 - 1][1]));
-#undef STEP
+#pragma unroll 1
+        for (int i = 1; i < NB1 - 1; i += 2) {
+            {
+                STEP_PRE(i, accA0, accA1, xpB, true, true)
+                asm volatile(STREAM_ASM_MID_B
+                             : STREAM_ACC_B(accB0, accB1), STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS
+                             : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11));
+                STEP_POST(i, xpA, true)
+            }
+            {
+                STEP_PRE(i + 1, accB0, accB1, xpA, true, true)
+                asm volatile(STREAM_ASM_MID_A
+                             : STREAM_ACC_A(accA0, accA1), STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), STREAM_ACC2, FRAG_TEMPS
+                             : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_B(hB00, hB01, hB10, hB11));
+                STEP_POST(i + 1, xpB, true)
+            }
+        }
+        {   // step NB1 - 1: the last layer-1 block
+            STEP_PRE(NB1 - 1, accA0, accA1, xpB, false, true)
+            asm volatile(STREAM_ASM_MID_B
+                         : STREAM_ACC_B(accB0, accB1), STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS
+                         : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11));
+            STEP_POST(NB1 - 1, xpA, true)
+        }
+        {   // step NB1: layer 2 only
+            STEP_PRE(NB1, accA0, accA1, xpA, false, false)
+            asm volatile(STREAM_ASM_LAST
+                         : STREAM_ACC2, FRAG_TEMPS
+                         : [wc] "v"(wc), STREAM_HF_IN_B(hB00, hB01, hB10, hB11));
+            STEP_POST(NB1, xpB, true)
+        }
+#undef STEP_PRE
+#undef STEP_POST
 #undef LOAD_USER_TERM
 
         // head layer (fragment rows >= J are zero), then Eq. 8

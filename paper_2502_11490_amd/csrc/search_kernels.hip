@@ -15,8 +15,14 @@
 
 namespace gmpgr {
 
-constexpr int BLOCK = 256;
+// Threads per query in the per-query kernels (seeding, round, output).
+#ifndef QUERY_BLOCK
+#define QUERY_BLOCK 256
+#endif
+constexpr int BLOCK = QUERY_BLOCK;
 constexpr int WAVES = BLOCK / 64;
+constexpr int SCAN_BLOCK = 256;
+constexpr int SCAN_WAVES = SCAN_BLOCK / 64;
 
 // Phase timing of the round kernel for measurement builds (-DROUND_TIMING): thread 0 of every
 // workgroup adds the shader-clock ticks of each phase to counters 8..15 of the stats block.
@@ -94,13 +100,22 @@ __device__ void bitonic_sort(uint64_t *keys, int n) {
 // Drops ids that are out of range, repeated inside cand[0..n_cand) (first occurrence kept)
 // or already in this query's visited table; inserts the rest into the table and writes them,
 // in their order of occurrence, to out[0..n_new).  Returns n_new (same in every thread).
-//   cand      : LDS int32[n_cand]
-//   dd_key/dd_pos : LDS uint32[dd_n] each, dd_n a power of two >= 2 * n_cand
-//   table     : global uint32[hash_cap], EMPTY_SLOT = free; the caller guarantees that
-//               n_visited + n_cand <= hash_cap / 2, so probing always meets a free slot
+//   cand          : LDS int32[n_cand]
+//   dd_key/dd_pos : LDS uint32[dd_n] each, dd_n a power of two >= 2 * n_cand (dedupe by id)
+//   bk_key/bk_cnt : LDS uint32[dd_n] each (arrivals per bucket in this pass)
+//   table         : global uint32[hash_cap]: hash_cap/16 buckets of 16 slots (one 64-byte line);
+//                   a bucket is filled from slot 0 up, EMPTY_SLOT = free.  An id lives in its home
+//                   bucket or, if that one is full, in the next ones up to the first bucket that
+//                   is not full.  The caller guarantees n_visited + n_cand <= hash_cap / 2.
+//
+// The table of a query is touched by one workgroup only, so it needs no global atomics (they
+// cost three times a plain access here): every candidate reads its whole bucket once (one line),
+// decides "seen / room / full" from that snapshot, and the candidates that arrive at the same
+// bucket in the same pass take consecutive free slots by a rank drawn from an LDS counter.
+// Stores of a pass become visible to the next pass through a device-scope fence + barrier.
 __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_key, uint32_t *dd_pos,
-                                 int dd_n, uint32_t *table, int hash_cap, int64_t N, int32_t *out,
-                                 int *wave_sums) {
+                                 uint32_t *bk_key, uint32_t *bk_cnt, int dd_n, uint32_t *table, int hash_cap,
+                                 int64_t N, int32_t *out, int *wave_sums) {
     for (int i = threadIdx.x; i < dd_n; i += BLOCK) {
         dd_key[i] = EMPTY_SLOT;
         dd_pos[i] = 0xFFFFFFFFu;
@@ -122,33 +137,77 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
         }
     }
     __syncthreads();
-    // pass 2: first occurrences probe / insert into the visited table; survivors compacted
-    const uint32_t hmask = (uint32_t)hash_cap - 1u;
-    const int shift = 32 - (31 - __clz(hash_cap));  // hash_cap = 2^b -> top b bits
+    // pass 2: first occurrences look themselves up in the visited table and enter it if absent
+    const int n_buckets = hash_cap >> 4;
+    const uint32_t bmask = (uint32_t)n_buckets - 1u;
+    const int bshift = 32 - (31 - __clz(n_buckets));  // n_buckets = 2^b (b >= 2) -> top b bits
     int n_new = 0;
     for (int p0 = 0; p0 < n_cand; p0 += BLOCK) {
-        int p = p0 + threadIdx.x;
-        bool fresh = false;
+        const int p = p0 + threadIdx.x;
+        bool fresh = false, active = false;
         int32_t v = -1;
+        uint32_t bkt = 0;
         if (p < n_cand) {
             v = cand[p];
             if (v >= 0 && (int64_t)v < N) {
                 uint32_t s = hash_id((uint32_t)v) & dd_mask;
                 while (dd_key[s] != (uint32_t)v) s = (s + 1u) & dd_mask;
-                if (dd_pos[s] == (uint32_t)p) {
-                    uint32_t h = (hash_cap > 1) ? (hash_id((uint32_t)v) >> shift) : 0u;
-                    // one atomic per probe: it returns the slot's content whether or not it swapped
+                active = (dd_pos[s] == (uint32_t)p);
+                bkt = hash_id((uint32_t)v) >> bshift;
+            }
+        }
+        for (;;) {
+            for (int i = threadIdx.x; i < dd_n; i += BLOCK) {
+                bk_key[i] = EMPTY_SLOT;
+                bk_cnt[i] = 0u;
+            }
+            // snapshot of the bucket: every read of this pass completes before any store of it
+            bool found = false;
+            int cnt = 0;
+            if (active) {
+                const uint4 *line = (const uint4 *)(table + (size_t)bkt * 16);
+                uint4 q0 = line[0], q1 = line[1], q2 = line[2], q3 = line[3];
+                const uint32_t w[16] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w,
+                                        q2.x, q2.y, q2.z, q2.w, q3.x, q3.y, q3.z, q3.w};
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    found |= (w[i] == (uint32_t)v);
+                    cnt += (w[i] != EMPTY_SLOT);
+                }
+            }
+            __syncthreads();
+            if (active) {
+                if (found) {
+                    active = false;  // scored in an earlier round
+                } else if (cnt == 16) {
+                    bkt = (bkt + 1u) & bmask;  // full: the id can only be further on
+                } else {
+                    uint32_t s = hash_id(bkt) & dd_mask;
                     for (;;) {
-                        uint32_t old = atomicCAS(&table[h], EMPTY_SLOT, (uint32_t)v);
-                        if (old == EMPTY_SLOT) {
-                            fresh = true;
-                            break;
-                        }
-                        if (old == (uint32_t)v) break;  // scored in an earlier round
-                        h = (h + 1u) & hmask;
+                        uint32_t old = atomicCAS(&bk_key[s], EMPTY_SLOT, bkt);
+                        if (old == EMPTY_SLOT || old == bkt) break;
+                        s = (s + 1u) & dd_mask;
+                    }
+                    const int slot = cnt + (int)atomicAdd(&bk_cnt[s], 1u);
+                    if (slot < 16) {
+                        table[(size_t)bkt * 16 + slot] = (uint32_t)v;
+                        fresh = true;
+                        active = false;
+                    } else {
+                        bkt = (bkt + 1u) & bmask;  // filled up by this pass: try the next bucket
                     }
                 }
             }
+            const bool more = (p0 + BLOCK < n_cand);
+            if (!__syncthreads_or(active ? 1 : 0)) {
+                if (more) {
+                    __threadfence();
+                    __syncthreads();
+                }
+                break;
+            }
+            __threadfence();  // this pass's stores must be seen by the next pass's bucket reads
+            __syncthreads();
         }
         int tot;
         int pos = block_excl_count(fresh, wave_sums, &tot);
@@ -180,14 +239,20 @@ init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state
     int32_t *cand = (int32_t *)smem;                 // [E]
     uint32_t *dd_key = (uint32_t *)(cand + ((E + 3) & ~3));
     uint32_t *dd_pos = dd_key + dd_n;
-    int *wave_sums = (int *)(dd_pos + dd_n);
+    uint32_t *bk_key = dd_pos + dd_n;
+    uint32_t *bk_cnt = bk_key + dd_n;
+    int *wave_sums = (int *)(bk_cnt + dd_n);
 
     uint32_t *table = hash + (size_t)q * hash_cap;
-    for (int i = threadIdx.x; i < hash_cap; i += BLOCK) table[i] = EMPTY_SLOT;
+    {
+        uint4 *t4 = (uint4 *)table;  // hash_cap is a power of two >= 64, the table 256-byte aligned
+        const uint4 e4 = make_uint4(EMPTY_SLOT, EMPTY_SLOT, EMPTY_SLOT, EMPTY_SLOT);
+        for (int i = threadIdx.x; i < hash_cap / 4; i += BLOCK) t4[i] = e4;
+    }
     for (int i = threadIdx.x; i < E; i += BLOCK) cand[i] = entries[(size_t)q * E + i];
     __threadfence_block();
     __syncthreads();
-    int n = filter_and_insert(cand, E, dd_key, dd_pos, dd_n, table, hash_cap, N,
+    int n = filter_and_insert(cand, E, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, hash_cap, N,
                               cand_g + (size_t)q * slots, wave_sums);
     if (threadIdx.x == 0) {
         QState s;
@@ -213,11 +278,11 @@ init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state
 // other workgroups, the same result every run), then scans its own counts and copies its groups,
 // one wave per query at a time.
 constexpr int SCAN_QPB = 16;  // queries per workgroup
-__global__ void __launch_bounds__(BLOCK)
+__global__ void __launch_bounds__(SCAN_BLOCK)
 scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__restrict__ cand_g, int slots,
                     int32_t *offsets, int32_t *pair_q, int32_t *pair_id, Ctrl *ctrl) {
-    __shared__ int red[WAVES];
-    __shared__ int red_active[WAVES];
+    __shared__ int red[SCAN_WAVES];
+    __shared__ int red_active[SCAN_WAVES];
     __shared__ int loc_off[SCAN_QPB + 1];
     __shared__ int loc_cnt[SCAN_QPB];
     const int q0 = blockIdx.x * SCAN_QPB;
@@ -225,7 +290,7 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
     // pairs of all earlier queries (and, in the last workgroup, the number of running queries)
     int sum = 0, act = 0;
     const int lim = last ? Q : q0;
-    for (int i = threadIdx.x; i < lim; i += BLOCK) {
+    for (int i = threadIdx.x; i < lim; i += SCAN_BLOCK) {
         int c = counts[i];
         if (i < q0) sum += max(c, 0);
         act += (c >= 0);
@@ -240,7 +305,7 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
     }
     __syncthreads();
     int prefix = 0, n_active = 0;
-    for (int w = 0; w < WAVES; ++w) {
+    for (int w = 0; w < SCAN_WAVES; ++w) {
         prefix += red[w];
         n_active += red_active[w];
     }
@@ -265,7 +330,7 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
         ctrl->n_active = n_active;
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int i = wave; i < SCAN_QPB; i += WAVES) {
+    for (int i = wave; i < SCAN_QPB; i += SCAN_WAVES) {
         int q = q0 + i;
         if (q >= Q) break;
         int c = loc_cnt[i], off = loc_off[i];
@@ -320,6 +385,8 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     int32_t *cand = (int32_t *)keys;                          // [slots]
     uint32_t *dd_key = (uint32_t *)(cand + ((slots + 3) & ~3));
     uint32_t *dd_pos = dd_key + dd_n;
+    uint32_t *bk_key = dd_pos + dd_n;
+    uint32_t *bk_cnt = bk_key + dd_n;
 
     uint64_t *pool = pool_g + (size_t)q * C;
     int32_t *cand_q = cand_g + (size_t)q * slots;
@@ -427,8 +494,8 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     PHASE_MARK(4);  // adjacency gather
 
     // 4. visited filter, 5. survivors of this query for the next MLP launch
-    int n_new = filter_and_insert(cand, n_cand, dd_key, dd_pos, dd_n, hash + (size_t)q * hash_cap, hash_cap, N,
-                                  cand_q, wave_sums);
+    int n_new = filter_and_insert(cand, n_cand, dd_key, dd_pos, bk_key, bk_cnt, dd_n, hash + (size_t)q * hash_cap,
+                                  hash_cap, N, cand_q, wave_sums);
     PHASE_MARK(5);  // dedupe + visited table
     if (threadIdx.x == 0) {
         st.n_list = n_list;
@@ -473,7 +540,7 @@ static size_t round_smem(const Plan &p) {
     int dd_n = 2;
     while (dd_n < 2 * p.slots) dd_n <<= 1;
     size_t lists = (size_t)(2 * p.C + new_cap_of(p)) * 8;
-    size_t filt = (size_t)((p.slots + 3) & ~3) * 4 + (size_t)dd_n * 8;
+    size_t filt = (size_t)((p.slots + 3) & ~3) * 4 + (size_t)dd_n * 16;
     return (size_t)((p.W_max + 3) & ~3) * 4 + 8 * 4 + (lists > filt ? lists : filt);
 }
 
@@ -481,7 +548,7 @@ int launch_init(const SearchArgs &a) {
     const Plan &p = a.plan;
     int dd_n = 2;
     while (dd_n < 2 * p.E) dd_n <<= 1;
-    size_t smem = (size_t)((p.E + 3) & ~3) * 4 + (size_t)dd_n * 8 + (WAVES + 1) * 4;
+    size_t smem = (size_t)((p.E + 3) & ~3) * 4 + (size_t)dd_n * 16 + (WAVES + 1) * 4;
     int64_t *stats = (int64_t *)(a.ws + p.off_stats);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, a.stream, stats, (Ctrl *)(a.ws + p.off_ctrl), p.Q);
     hipLaunchKernelGGL(init_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.entries, p.E, a.g->N,
@@ -495,7 +562,7 @@ int launch_init(const SearchArgs &a) {
 int launch_scan_compact(const SearchArgs &a) {
     const Plan &p = a.plan;
     int blocks = (p.Q + SCAN_QPB - 1) / SCAN_QPB;
-    hipLaunchKernelGGL(scan_compact_kernel, dim3(blocks), dim3(BLOCK), 0, a.stream,
+    hipLaunchKernelGGL(scan_compact_kernel, dim3(blocks), dim3(SCAN_BLOCK), 0, a.stream,
                        (const int32_t *)(a.ws + p.off_counts), p.Q, (const int32_t *)(a.ws + p.off_cand),
                        p.slots, (int32_t *)(a.ws + p.off_offsets), (int32_t *)(a.ws + p.off_pair_q),
                        (int32_t *)(a.ws + p.off_pair_id), (Ctrl *)(a.ws + p.off_ctrl));
