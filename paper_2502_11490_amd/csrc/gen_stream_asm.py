@@ -16,7 +16,21 @@ so that every variant of the step agrees on where the long-lived values are):
 Step variants:  FIRST  layer 1 only (set A), conversion exposed
                 MID_A  layer 1 into set A, layer 2 with the hidden units of set B, conversion of
                        set A interleaved with the layer-2 MFMAs;  MID_B the mirror image
+                END_B  MID_B of the last layer-1 block: no user term to fetch for a next block
                 LAST   layer 2 only, with the hidden units of set B
+
+Global loads of a step and their waits are part of the assembly too, because the compiler cannot
+count them: next to the global-to-LDS weight loads (which it issues itself, N_DMA per step, right
+before the block) any other vector-memory load makes it fall back to waiting for ALL outstanding
+loads, the weight chunks included.  A block therefore
+    - first loads the user term of the NEXT layer-1 block straight into the accumulator set that
+      is idle during this step (8 loads), then one 16-byte piece of the next batch's item rows;
+    - before its first layer-1 MFMA waits for its own user term, loaded one step earlier: the
+      counter is in order, and younger than that term are the piece fetched after it and this
+      step's own loads;
+    - at the end waits until only this step's own loads are outstanding (then the chunk the next
+      step reads has landed, and so has the piece fetched one step ago), stores that piece to the
+      wave's LDS area, waits for the store and joins the workgroup barrier.
 
 Run this script after changing it; the .inc file is committed next to it.
 """
@@ -24,6 +38,7 @@ import os
 
 ACC = {"A": (64, 80), "B": (96, 112)}       # first register of the c = 0 / c = 1 accumulator
 HF = {"A": 128, "B": 144}                   # first register of the four (c, half) tuples
+N_DMA = 6                                   # global-to-LDS loads the compiler issues before a block
 
 
 def vr(lo, n):
@@ -75,15 +90,18 @@ def convert_ops(s):
     return ops
 
 
-def schedule(frags, first_frag, compute, extra=None):
+def schedule(frags, first_frag, compute, extra=None, before_first=None):
     """Four fragments in flight: preload 4, then per fragment: wait until it has arrived (the LDS
     counter is in order), issue its MFMAs, reload its register with the fragment 4 ahead.
-    extra[t] = vector-ALU lines issued after the MFMAs of fragment t."""
+    extra[t] = vector-ALU lines issued after the MFMAs of fragment t; before_first = lines
+    placed right before the first MFMA."""
     n = len(frags)
     out = [wt(0)] + [ld(f"f{i}", first_frag + i) for i in range(min(4, n))]
     for t in range(n):
         issued = min(n, t + 4)
         out.append(wt(issued - t - 1))
+        if t == 0 and before_first:
+            out += before_first
         out += compute(t, f"f{t % 4}")
         if t + 4 < n:
             out.append(ld(f"f{t % 4}", first_frag + t + 4))
@@ -92,10 +110,25 @@ def schedule(frags, first_frag, compute, extra=None):
     return out
 
 
-def step(kind, s=None):
+def user_loads(into):
+    """User term of the next layer-1 block into accumulator set `into`: register 4*t4 + e of pair
+    c takes float 8*t4 + e of the 32 the lane's pointer %[upn<c>] addresses."""
+    return [f"global_load_dwordx4 {vr(ACC[into][c] + 4 * t4, 4)}, %[upn{c}], off offset:{32 * t4}"
+            for t4 in range(4) for c in (0, 1)]
+
+
+def step(kind, s=None, load_user=True, load_xp=True, store_xp=True, wait_user=True):
     other = "B" if s == "A" else "A"
+    own = N_DMA + (8 if load_user else 0) + (1 if load_xp else 0)
+    head = (user_loads(other) if load_user else []) + (["global_load_dwordx4 %[xpn], %[xpsrc], off"] if load_xp else [])
+    # own user term: younger are the piece fetched after it (one load) and this step's loads
+    before = [f"s_waitcnt vmcnt({own + 1})"] if wait_user else None
+    tail = [f"s_waitcnt vmcnt({own})"]
+    if store_xp:
+        tail += ["ds_write_b128 %[xwst], %[xpo]"]
+    tail += ["s_waitcnt lgkmcnt(0)", "s_barrier"]
     if kind == "FIRST":
-        lines = schedule(range(8), 0, lambda t, b: m1("A", b, t))
+        lines = schedule(range(8), 0, lambda t, b: m1("A", b, t), before_first=before)
         lines += ["s_nop 15"] + convert_ops("A")
     elif kind == "LAST":
         lines = schedule(range(16), 8, lambda t, b: m2("B", b, t // 2, t % 2))
@@ -116,8 +149,8 @@ def step(kind, s=None):
         def compute(t, b):
             return m1(s, b, t) if t < 8 else m2(other, b, (t - 8) // 2, (t - 8) % 2)
 
-        lines = schedule(range(24), 0, compute, extra)
-    return lines
+        lines = schedule(range(24), 0, compute, extra, before_first=before)
+    return head + lines + tail
 
 
 def c_string(lines):
@@ -127,15 +160,19 @@ def c_string(lines):
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
     out = ["// Generated by gen_stream_asm.py -- do not edit; see that script for the register plan.", ""]
-    for name, lines in (("FIRST", step("FIRST")), ("MID_A", step("MID", "A")), ("MID_B", step("MID", "B")),
-                        ("LAST", step("LAST"))):
+    variants = (("FIRST", step("FIRST", "A", store_xp=False, wait_user=False)),  # its user term: the compiler's load
+                ("MID_A", step("MID", "A")), ("MID_B", step("MID", "B")),
+                ("END_B", step("MID", "B", load_user=False)),
+                ("LAST", step("LAST", load_user=False, load_xp=False, wait_user=False)))
+    for name, lines in variants:
         out.append(f"#define STREAM_ASM_{name} \\\n    {c_string(lines)}")
         out.append("")
     # operand lists
     for s in "AB":
         out.append(f'#define STREAM_ACC_{s}(v0, v1) [p{s}0] "+{{{acc_reg(s, 0)}}}"(v0), [p{s}1] "+{{{acc_reg(s, 1)}}}"(v1)')
+        out.append(f'#define STREAM_ACC_OUT_{s}(v0, v1) [q{s}0] "=&{{{acc_reg(s, 0)}}}"(v0), [q{s}1] "=&{{{acc_reg(s, 1)}}}"(v1)')
         names = [(c, h) for c in (0, 1) for h in (0, 1)]
-        outs = ", ".join(f'[h{s}{c}{h}] "={{{hf_reg(s, c, h)}}}"(h{c}{h})' for c, h in names)
+        outs = ", ".join(f'[h{s}{c}{h}] "=&{{{hf_reg(s, c, h)}}}"(h{c}{h})' for c, h in names)
         ins = ", ".join(f'[h{s}{c}{h}] "{{{hf_reg(s, c, h)}}}"(h{c}{h})' for c, h in names)
         out.append(f"#define STREAM_HF_OUT_{s}(h00, h01, h10, h11) {outs}")
         out.append(f"#define STREAM_HF_IN_{s}(h00, h01, h10, h11) {ins}")

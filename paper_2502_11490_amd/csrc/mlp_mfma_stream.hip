@@ -9,17 +9,21 @@
 //      64 VGPRs  layer-1 accumulators of this step and the pre-loaded user term of the next
 //      16 VGPRs  the 32 hidden units of the previous step as layer-2 B operands (bf16)
 //      16 VGPRs  four weight fragments in flight from LDS
-//      32 VGPRs  staging of the next weight chunk and of the next batch's item rows
+//       8 VGPRs  staging of the next batch's item rows
 // The compiler's register allocator does not find this plan, so one step of the pipeline is a
 // single inline-assembly block with the register classes pinned by constraints.
 //
 // Pipeline.  Step i (0..NB1) contracts layer 1 for hidden units 32i..32i+31 and, skewed by one
 // step, layer 2 over the hidden units of step i-1; chunk i of the weights holds exactly those
-// fragments (8 of W1_item, then 16 of W2), streams L2 -> registers -> LDS while step i-1 runs
-// (double buffer, one barrier per step), and is read from LDS four fragments ahead of use.
-// A step issues its global loads first and in the order their data is needed (next weight
-// chunk, next user term, one piece of the next batch's item rows), so that the in-order load
-// counter never makes a short-latency consumer wait for the long-latency gather.
+// fragments (8 of W1_item, then 16 of W2) and streams L2 -> LDS directly (global_load_lds, no
+// registers in between) TWO steps ahead of its use into one of three 24 KB buffers: every CU of
+// the chip asks for the same 24 KB at about the same time, so the L2 delivers them slowly, and
+// a chunk gets two whole steps to arrive.  One barrier per step; before it each wave waits
+// (counted, the vector-memory counter is in order) for everything it issued before this step,
+// which includes its share of the chunk the next step reads.  Fragments are read from LDS four
+// ahead of use.  A step issues its global loads first, weights before the user term before one
+// piece of the next batch's item rows, so that the in-order counter never makes a
+// short-latency consumer wait for the long-latency gather.
 // ReLU + bf16 rounding of the fresh hidden units is the only vector-ALU work of a step; the
 // item rows of the workgroup's NEXT batch are fetched one 16-byte piece per lane and step into
 // a wave-private LDS area, so the HBM gather latency is hidden behind a whole batch of MFMAs.
@@ -46,32 +50,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void global_void;
 
 constexpr int ST_BLOCK = 256;
-
-// Measurement switches (all off in the product build): each removes one source of stalls from
-// the step pipeline while keeping every access in bounds; results are then meaningless.
-#ifndef EXP_NO_STAGE
-#define EXP_NO_STAGE 0
-#endif
-#ifndef EXP_NO_USER
-#define EXP_NO_USER 0
-#endif
-#ifndef EXP_NO_XP
-#define EXP_NO_XP 0
-#endif
-#ifndef EXP_NO_BARRIER
-#define EXP_NO_BARRIER 0
-#endif
-#ifndef EXP_NO_STAGE_LOAD
-#define EXP_NO_STAGE_LOAD 0
-#endif
-#ifndef EXP_NO_STAGE_STORE
-#define EXP_NO_STAGE_STORE 0
-#endif
-#ifndef EXP_NO_RELU
-#define EXP_NO_RELU 0
-#endif
 
 // ReLU and round-to-nearest-even bf16 of half an accumulator tile, two instructions per packed
 // word: v_cvt_pk_bf16_f32 rounds two floats, and for bf16 bit patterns max(x, 0) is a signed
@@ -102,6 +84,24 @@ __device__ __forceinline__ void drain_v(f32x16 &x, f32x16 &y) {
     asm volatile("s_nop 15" : "+v"(x), "+v"(y));
 }
 
+// LDS accesses made while weight chunks are in flight towards the LDS go through assembly: for an
+// LDS access it can see, the compiler first waits until every outstanding global-to-LDS load
+// has landed (it cannot tell that the addresses differ), which would undo the pipelining.
+__device__ __forceinline__ void lds_store_b128(uint32_t addr, const u32x4 &v) {
+    asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+// four 1 KB-strided 16-byte reads, complete on return
+__device__ __forceinline__ void lds_load4_b128(uint32_t addr, u32x4 &r0, u32x4 &r1, u32x4 &r2, u32x4 &r3) {
+    asm volatile("ds_read_b128 %0, %4\n\t"
+                 "ds_read_b128 %1, %4 offset:1024\n\t"
+                 "ds_read_b128 %2, %4 offset:2048\n\t"
+                 "ds_read_b128 %3, %4 offset:3072\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
+                 : "v"(addr)
+                 : "memory");
+}
+
 #include "mlp_mfma_stream_asm.inc"  // STREAM_ASM_FIRST / MID_A / MID_B / LAST and their operand lists
 
 #define FRAG_TEMPS [f0] "=&v"(f0), [f1] "=&v"(f1), [f2] "=&v"(f2), [f3] "=&v"(f3)
@@ -128,9 +128,10 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
     constexpr int W3_U4 = 16 * 64;
     constexpr int TILE = 64 * 4;
     constexpr int ST = CHUNK_U4 / ST_BLOCK;  // 6 uint4 per thread and chunk
+    constexpr int NBUF = 3;
     extern __shared__ __align__(16) uint4 lds[];
-    uint4 *wbuf = lds;                       // [2][CHUNK_U4]
-    uint4 *w3buf = lds + 2 * CHUNK_U4;       // [W3_U4]
+    uint4 *wbuf = lds;                       // [NBUF][CHUNK_U4]
+    uint4 *w3buf = lds + NBUF * CHUNK_U4;    // [W3_U4]
     uint4 *xbuf = w3buf + W3_U4;             // [4 waves][CB*KS1][64 lanes]
 
     int64_t M = (int64_t)*M_dev;
@@ -141,9 +142,10 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int g = lane >> 5, col = lane & 31;
     uint4 *xw = xbuf + (size_t)wave * (CB * KS1 * 64) + lane;
+    const uint32_t xw_addr = (uint32_t)(uintptr_t)xw, w3_addr = (uint32_t)(uintptr_t)(w3buf + lane);
 
     for (int i = threadIdx.x; i < W3_U4; i += ST_BLOCK) w3buf[i] = frag[(size_t)NSTEP * CHUNK_U4 + i];
-    for (int i = threadIdx.x; i < CHUNK_U4; i += ST_BLOCK) wbuf[i] = frag[i];
+    for (int i = threadIdx.x; i < 2 * CHUNK_U4; i += ST_BLOCK) wbuf[i] = frag[i];  // chunks 0 and 1
 
     float hw[4], bb3[4];
 #pragma unroll
@@ -179,24 +181,19 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
     }
     __syncthreads();
 
-    // `stage` always holds (in flight) the chunk of the next step
-    static_assert(ST == 6, "six staged uint4 per thread");
-    uint4 sg0 = {}, sg1 = {}, sg2 = {}, sg3 = {}, sg4 = {}, sg5 = {};  // named scalars: an indexed array would live in scratch
-#define STAGE_LOAD(src)            \
-    sg0 = (src)[0 * ST_BLOCK];     \
-    sg1 = (src)[1 * ST_BLOCK];     \
-    sg2 = (src)[2 * ST_BLOCK];     \
-    sg3 = (src)[3 * ST_BLOCK];     \
-    sg4 = (src)[4 * ST_BLOCK];     \
-    sg5 = (src)[5 * ST_BLOCK];
-#define STAGE_STORE(dst)           \
-    (dst)[0 * ST_BLOCK] = sg0;     \
-    (dst)[1 * ST_BLOCK] = sg1;     \
-    (dst)[2 * ST_BLOCK] = sg2;     \
-    (dst)[3 * ST_BLOCK] = sg3;     \
-    (dst)[4 * ST_BLOCK] = sg4;     \
-    (dst)[5 * ST_BLOCK] = sg5;
-    int cur = 0;
+    // Chunk `nx` of the weights straight into buffer `buf`: per instruction the workgroup moves
+    // 4 KB, wave w the 1 KB at +1024 w (the LDS base of such a load is wave-uniform, lane l lands
+    // at +16 l).
+    static_assert(ST == 6, "six 16-byte pieces per thread and chunk");
+    auto stream_chunk = [&](int nx, int buf) {
+        const uint4 *srcw = frag + (size_t)nx * CHUNK_U4 + threadIdx.x;
+        uint4 *dstw = wbuf + (size_t)buf * CHUNK_U4 + wave * 64;
+#pragma unroll
+        for (int t = 0; t < ST; ++t)
+            __builtin_amdgcn_global_load_lds((global_void *)(srcw + t * ST_BLOCK), (lds_void *)(dstw + t * ST_BLOCK),
+                                             16, 0, 0);
+    };
+    int cur = 0;  // buffer holding the chunk of the current step; (cur + 1) % 3 the next one's
 
 #pragma unroll 1
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -207,7 +204,14 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
 #pragma unroll
-            for (int s = 0; s < KS1; ++s) xf[c][s] = __builtin_bit_cast(bf16x8, xw[(c * KS1 + s) * 64]);
+            for (int s = 0; s < KS1; s += 4) {
+                u32x4 r0, r1, r2, r3;
+                lds_load4_b128(xw_addr + (c * KS1 + s) * 1024, r0, r1, r2, r3);
+                xf[c][s] = __builtin_bit_cast(bf16x8, r0);
+                xf[c][s + 1] = __builtin_bit_cast(bf16x8, r1);
+                xf[c][s + 2] = __builtin_bit_cast(bf16x8, r2);
+                xf[c][s + 3] = __builtin_bit_cast(bf16x8, r3);
+            }
             up[c] = upre + (size_t)qn[c] * H1 + 4 * g;
             bad[c] = badn[c];
         }
@@ -247,73 +251,79 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
             ACC1[4 * t4 + e] = pv1[e];                                            \
         }                                                                         \
     }
-        // Before the assembly of step i: global loads in the order their data is needed (weight
-        // chunk i+1, user term of step i+1, one 16-byte piece of the next batch's item rows).
-#define STEP_PRE(i, NEXT0, NEXT1, XP_NEW, LOAD_NEXT, LOAD_XP)                                        \
+        // Before the assembly of step i the compiler issues the global-to-LDS loads of weight
+        // chunk i+2 into the buffer that step i-1 read (fenced, so that they stay here); every
+        // other load of the step, its waits, the LDS store of the item-row piece fetched one
+        // step ago and the workgroup barrier are inside the assembly (see gen_stream_asm.py).
+#define STEP_PRE(i)                                                                                  \
+    asm volatile("" ::: "memory");                                                                   \
     {                                                                                                \
-        int nx = (i) + 1;                                                                            \
+        int nx = (i) + 2;                                                                            \
         if (nx >= NSTEP) nx -= NSTEP;                                                                \
-        const uint4 *srcw = frag + (size_t)nx * CHUNK_U4 + threadIdx.x;                              \
-        if (!EXP_NO_STAGE && !EXP_NO_STAGE_LOAD) { STAGE_LOAD(srcw) }                                \
-        if ((LOAD_NEXT) && !EXP_NO_USER) { LOAD_USER_TERM(NEXT0, NEXT1, (i) + 1) }                    \
-        if ((LOAD_XP) && !EXP_NO_XP)                                                                 \
-            XP_NEW = *(const uint4 *)(emb + ((((i) / KS1) & 1) ? nxt_off[1] : nxt_off[0]) + 16 * ((i) % KS1)); \
+        int into = cur + 2;                                                                          \
+        if (into >= NBUF) into -= NBUF;                                                              \
+        stream_chunk(nx, into);                                                                      \
     }                                                                                                \
+    asm volatile("" ::: "memory");                                                                   \
     const uint32_t wc = (uint32_t)(uintptr_t)(wbuf + (size_t)cur * CHUNK_U4 + lane);                 \
-    bf16x8 f0, f1, f2, f3;
-        // After it: the piece fetched one step ago goes to LDS, the staged chunk to the other
-        // buffer, one barrier.
-#define STEP_POST(i, XP_OLD, STORE_XP)                                                               \
-    {                                                                                                \
-        if ((STORE_XP) && !EXP_NO_XP) xw[((i) - 1) * 64] = XP_OLD;                                   \
-        uint4 *dst = wbuf + (size_t)(cur ^ 1) * CHUNK_U4 + threadIdx.x;                              \
-        if (!EXP_NO_STAGE && !EXP_NO_STAGE_STORE) { STAGE_STORE(dst) }                               \
-        if (!EXP_NO_BARRIER) __syncthreads();                                                        \
-        cur ^= 1;                                                                                    \
-    }
+    const float *upn0 = up[0] + ((i) + 1) * 32, *upn1 = up[1] + ((i) + 1) * 32; /* user term of step i+1 */ \
+    const uint16_t *xpsrc = emb + ((((i) / KS1) & 1) ? nxt_off[1] : nxt_off[0]) + 16 * ((i) % KS1);  \
+    const uint32_t xwst = xw_addr + ((i) - 1) * 1024; /* LDS slot of the piece fetched in step i-1 */ \
+    bf16x8 f0, f1, f2, f3;                                                                           \
+    cur = cur + 1 == NBUF ? 0 : cur + 1;
+#define LOADS_IN [upn0] "v"(upn0), [upn1] "v"(upn1), [xpsrc] "v"(xpsrc)
         static_assert(NB1 % 2 == 0 && NB1 == CB * KS1, "steps come in A/B pairs; one item piece per step");
-        uint4 xpA, xpB;
+        u32x4 xpA, xpB;
         LOAD_USER_TERM(accA0, accA1, 0)
         {   // step 0: layer 1 only
-            STEP_PRE(0, accB0, accB1, xpA, true, true)
+            STEP_PRE(0)
             asm volatile(STREAM_ASM_FIRST
-                         : STREAM_ACC_A(accA0, accA1), STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), FRAG_TEMPS
-                         : [wc] "v"(wc), X_OPERANDS);
-            STEP_POST(0, xpB, false)
+                         : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1),
+                           STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), FRAG_TEMPS, [xpn] "=&v"(xpA)
+                         : [wc] "v"(wc), X_OPERANDS, LOADS_IN
+                         : "memory");
         }
 #pragma unroll 1
         for (int i = 1; i < NB1 - 1; i += 2) {
             {
-                STEP_PRE(i, accA0, accA1, xpB, true, true)
+                STEP_PRE(i)
                 asm volatile(STREAM_ASM_MID_B
-                             : STREAM_ACC_B(accB0, accB1), STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS
-                             : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11));
-                STEP_POST(i, xpA, true)
+                             : STREAM_ACC_B(accB0, accB1), STREAM_ACC_OUT_A(accA0, accA1),
+                               STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpB)
+                             : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), LOADS_IN,
+                               [xpo] "v"(xpA), [xwst] "v"(xwst)
+                             : "memory");
             }
             {
-                STEP_PRE(i + 1, accB0, accB1, xpA, true, true)
+                STEP_PRE(i + 1)
                 asm volatile(STREAM_ASM_MID_A
-                             : STREAM_ACC_A(accA0, accA1), STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), STREAM_ACC2, FRAG_TEMPS
-                             : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_B(hB00, hB01, hB10, hB11));
-                STEP_POST(i + 1, xpB, true)
+                             : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1),
+                               STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpA)
+                             : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_B(hB00, hB01, hB10, hB11), LOADS_IN,
+                               [xpo] "v"(xpB), [xwst] "v"(xwst)
+                             : "memory");
             }
         }
         {   // step NB1 - 1: the last layer-1 block
-            STEP_PRE(NB1 - 1, accA0, accA1, xpB, false, true)
-            asm volatile(STREAM_ASM_MID_B
-                         : STREAM_ACC_B(accB0, accB1), STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS
-                         : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11));
-            STEP_POST(NB1 - 1, xpA, true)
+            STEP_PRE(NB1 - 1)
+            asm volatile(STREAM_ASM_END_B
+                         : STREAM_ACC_B(accB0, accB1), STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS,
+                           [xpn] "=&v"(xpB)
+                         : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), [xpsrc] "v"(xpsrc),
+                           [xpo] "v"(xpA), [xwst] "v"(xwst)
+                         : "memory");
+            (void)upn0, (void)upn1;
         }
         {   // step NB1: layer 2 only
-            STEP_PRE(NB1, accA0, accA1, xpA, false, false)
+            STEP_PRE(NB1)
             asm volatile(STREAM_ASM_LAST
                          : STREAM_ACC2, FRAG_TEMPS
-                         : [wc] "v"(wc), STREAM_HF_IN_B(hB00, hB01, hB10, hB11));
-            STEP_POST(NB1, xpB, true)
+                         : [wc] "v"(wc), STREAM_HF_IN_B(hB00, hB01, hB10, hB11), [xpo] "v"(xpB), [xwst] "v"(xwst)
+                         : "memory");
+            (void)upn0, (void)upn1, (void)xpsrc;
         }
+#undef LOADS_IN
 #undef STEP_PRE
-#undef STEP_POST
 #undef LOAD_USER_TERM
 
         // head layer (fragment rows >= J are zero), then Eq. 8
@@ -323,13 +333,14 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc3[c][e] = 0.f;
 #pragma unroll
-        for (int n2 = 0; n2 < NB2; ++n2) {
+        for (int n2 = 0; n2 < NB2; n2 += 2) {
+            u32x4 a[4];
+            lds_load4_b128(w3_addr + 2 * n2 * 1024, a[0], a[1], a[2], a[3]);
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                bf16x8 a = __builtin_bit_cast(bf16x8, w3buf[(2 * n2 + s2) * 64 + lane]);
+            for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int c = 0; c < CB; ++c) mfma_v(acc3[c], a, relu_pack_i16(acc2[n2][c], s2));
-            }
+                for (int c = 0; c < CB; ++c)
+                    mfma_v(acc3[c], __builtin_bit_cast(bf16x8, a[t]), relu_pack_i16(acc2[n2 + t / 2][c], t % 2));
         }
         drain_v(acc3[0], acc3[1]);
 #pragma unroll
@@ -342,6 +353,8 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
             if (g == 0 && row < M) scores[row] = bad[c] ? __uint_as_float(0x7fc00000u) : part + other;
         }
     }
+    // the last two steps streamed chunks nobody reads; they must have landed before the LDS is released
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 bool mfma_stream_supported(int D, int H1, int H2) { return D == 128 && H2 == 256 && H1 == 512; }
@@ -391,7 +404,7 @@ int launch_mlp_mfma_stream(const ann_graph *g, const ann_mlp *m, const float *up
                            const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
                            hipStream_t stream) {
     constexpr int H1 = 512;
-    constexpr size_t smem = ((size_t)2 * 24 * 64 + 16 * 64 + 4 * 16 * 64) * 16;  // 48 + 16 + 64 KB
+    constexpr size_t smem = ((size_t)3 * 24 * 64 + 16 * 64 + 4 * 16 * 64) * 16;  // 72 + 16 + 64 KB
     constexpr int TILE = 256;
     auto fn = mlp_mfma2_stream_kernel<H1>;
     ANN_HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
