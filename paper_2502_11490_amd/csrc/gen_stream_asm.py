@@ -16,14 +16,15 @@ so that every variant of the step agrees on where the long-lived values are):
 Step variants:  FIRST  layer 1 only (set A), conversion exposed
                 MID_A  layer 1 into set A, layer 2 with the hidden units of set B, conversion of
                        set A interleaved with the layer-2 MFMAs;  MID_B the mirror image
-                END_B  MID_B of the last layer-1 block: no user term to fetch for a next block
                 LAST   layer 2 only, with the hidden units of set B
 
 Global loads of a step and their waits are part of the assembly too, because the compiler cannot
-count them: next to the global-to-LDS weight loads (which it issues itself, N_DMA per step, right
-before the block) any other vector-memory load makes it fall back to waiting for ALL outstanding
-loads, the weight chunks included.  A block therefore
-    - first loads the user term of the NEXT layer-1 block straight into the accumulator set that
+count them: next to global-to-LDS loads any other vector-memory load makes it fall back to waiting
+for ALL outstanding loads, the weight chunks included (and it treats every LDS access it sees as
+depending on them).  A block therefore
+    - first issues the N_DMA global-to-LDS loads of the weight chunk two steps ahead (scalar base
+      %[sb<t>] + lane offset %[vo]; LDS base in M0, 4 KB further per load);
+    - then loads the user term of the NEXT layer-1 block straight into the accumulator set that
       is idle during this step (8 loads), then one 16-byte piece of the next batch's item rows;
     - before its first layer-1 MFMA waits for its own user term, loaded one step earlier: the
       counter is in order, and younger than that term are the piece fetched after it and this
@@ -38,7 +39,7 @@ import os
 
 ACC = {"A": (64, 80), "B": (96, 112)}       # first register of the c = 0 / c = 1 accumulator
 HF = {"A": 128, "B": 144}                   # first register of the four (c, half) tuples
-N_DMA = 6                                   # global-to-LDS loads the compiler issues before a block
+N_DMA = 6                                   # global-to-LDS loads per step: 6 x 256 lanes x 16 B = one chunk
 
 
 def vr(lo, n):
@@ -110,6 +111,15 @@ def schedule(frags, first_frag, compute, extra=None, before_first=None):
     return out
 
 
+def dma_loads():
+    out = ["s_mov_b32 m0, %[lb]"]
+    for t in range(N_DMA):
+        if t:
+            out.append("s_add_u32 m0, m0, 0x1000")
+        out += ["s_nop 0", f"global_load_lds_dwordx4 %[vo], %[sb{t}]"]  # one wait state between the M0 write and its use
+    return out
+
+
 def user_loads(into):
     """User term of the next layer-1 block into accumulator set `into`: register 4*t4 + e of pair
     c takes float 8*t4 + e of the 32 the lane's pointer %[upn<c>] addresses."""
@@ -120,7 +130,7 @@ def user_loads(into):
 def step(kind, s=None, load_user=True, load_xp=True, store_xp=True, wait_user=True):
     other = "B" if s == "A" else "A"
     own = N_DMA + (8 if load_user else 0) + (1 if load_xp else 0)
-    head = (user_loads(other) if load_user else []) + (["global_load_dwordx4 %[xpn], %[xpsrc], off"] if load_xp else [])
+    head = dma_loads() + (user_loads(other) if load_user else []) + (["global_load_dwordx4 %[xpn], %[xpsrc], off"] if load_xp else [])
     # own user term: younger are the piece fetched after it (one load) and this step's loads
     before = [f"s_waitcnt vmcnt({own + 1})"] if wait_user else None
     tail = [f"s_waitcnt vmcnt({own})"]
@@ -160,9 +170,9 @@ def c_string(lines):
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
     out = ["// Generated by gen_stream_asm.py -- do not edit; see that script for the register plan.", ""]
-    variants = (("FIRST", step("FIRST", "A", store_xp=False, wait_user=False)),  # its user term: the compiler's load
+    # FIRST: its user term was fetched by the last MID_B of the batch before and waited for by LAST
+    variants = (("FIRST", step("FIRST", "A", store_xp=False, wait_user=False)),
                 ("MID_A", step("MID", "A")), ("MID_B", step("MID", "B")),
-                ("END_B", step("MID", "B", load_user=False)),
                 ("LAST", step("LAST", load_user=False, load_xp=False, wait_user=False)))
     for name, lines in variants:
         out.append(f"#define STREAM_ASM_{name} \\\n    {c_string(lines)}")

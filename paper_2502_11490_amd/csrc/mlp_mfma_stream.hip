@@ -90,15 +90,16 @@ __device__ __forceinline__ void drain_v(f32x16 &x, f32x16 &y) {
 __device__ __forceinline__ void lds_store_b128(uint32_t addr, const u32x4 &v) {
     asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory");
 }
-// four 1 KB-strided 16-byte reads, complete on return
+// four 16-byte reads STRIDE bytes apart, complete on return
+template <int STRIDE>
 __device__ __forceinline__ void lds_load4_b128(uint32_t addr, u32x4 &r0, u32x4 &r1, u32x4 &r2, u32x4 &r3) {
     asm volatile("ds_read_b128 %0, %4\n\t"
-                 "ds_read_b128 %1, %4 offset:1024\n\t"
-                 "ds_read_b128 %2, %4 offset:2048\n\t"
-                 "ds_read_b128 %3, %4 offset:3072\n\t"
+                 "ds_read_b128 %1, %4 offset:%5\n\t"
+                 "ds_read_b128 %2, %4 offset:%6\n\t"
+                 "ds_read_b128 %3, %4 offset:%7\n\t"
                  "s_waitcnt lgkmcnt(0)"
                  : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
-                 : "v"(addr)
+                 : "v"(addr), "n"(STRIDE), "n"(2 * STRIDE), "n"(3 * STRIDE)
                  : "memory");
 }
 
@@ -133,6 +134,7 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
     uint4 *wbuf = lds;                       // [NBUF][CHUNK_U4]
     uint4 *w3buf = lds + NBUF * CHUNK_U4;    // [W3_U4]
     uint4 *xbuf = w3buf + W3_U4;             // [4 waves][CB*KS1][64 lanes]
+    float *b2buf = (float *)(xbuf + 4 * CB * KS1 * 64);  // [NB2 * 32] layer-2 bias, [8] head weights, [8] head bias
 
     int64_t M = (int64_t)*M_dev;
     if (M > M_max) M = M_max;
@@ -143,22 +145,26 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
     const int g = lane >> 5, col = lane & 31;
     uint4 *xw = xbuf + (size_t)wave * (CB * KS1 * 64) + lane;
     const uint32_t xw_addr = (uint32_t)(uintptr_t)xw, w3_addr = (uint32_t)(uintptr_t)(w3buf + lane);
+    const uint32_t b2_addr = (uint32_t)(uintptr_t)(b2buf + 4 * g);
 
     for (int i = threadIdx.x; i < W3_U4; i += ST_BLOCK) w3buf[i] = frag[(size_t)NSTEP * CHUNK_U4 + i];
     for (int i = threadIdx.x; i < 2 * CHUNK_U4; i += ST_BLOCK) wbuf[i] = frag[i];  // chunks 0 and 1
+    for (int i = threadIdx.x; i < NB2 * 32; i += ST_BLOCK) b2buf[i] = b2[i];
 
-    float hw[4], bb3[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int j = 4 * g + i;
-        hw[i] = j < J ? head_w[j] : 0.f;
-        bb3[i] = j < J ? b3[j] : 0.f;
+    if (threadIdx.x < 8) {  // head weights and head bias, zero beyond J
+        b2buf[NB2 * 32 + threadIdx.x] = (int)threadIdx.x < J ? head_w[threadIdx.x] : 0.f;
+        b2buf[NB2 * 32 + 8 + threadIdx.x] = (int)threadIdx.x < J ? b3[threadIdx.x] : 0.f;
     }
 
-    // ids of the first batch and its item rows (the later batches are fetched during the one before)
-    int32_t idn[CB], qn[CB];
-    bool badn[CB];
+    // Pair ids run two batches ahead of the arithmetic and item rows one batch ahead, so that no
+    // batch waits for a dependent chain of loads: (idc, qc) belong to the batch whose rows are in
+    // the wave's LDS area, (idn, qn) to the one after it.
+    struct Ids {
+        int32_t id[CB], q[CB];
+        bool bad[CB];
+    };
     auto load_ids = [&](int64_t tile) {
+        Ids r;
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
             int64_t row = tile * TILE + (int64_t)wave * 64 + c * 32 + col;
@@ -167,32 +173,35 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
                 v = pair_id[row];
                 q = pair_q[row];
             }
-            badn[c] = (v < 0 || (int64_t)v >= N || q < 0 || q >= Q);
-            idn[c] = badn[c] ? 0 : v;
-            qn[c] = badn[c] ? 0 : q;
+            r.bad[c] = (v < 0 || (int64_t)v >= N || q < 0 || q >= Q);
+            r.id[c] = r.bad[c] ? 0 : v;
+            r.q[c] = r.bad[c] ? 0 : q;
         }
+        return r;
     };
-    load_ids(blockIdx.x);
+    Ids idc = load_ids(blockIdx.x), idn = load_ids((int64_t)blockIdx.x + gridDim.x);
 #pragma unroll
     for (int c = 0; c < CB; ++c) {
-        const uint4 *src = (const uint4 *)(emb + (size_t)idn[c] * D) + g;
+        const uint4 *src = (const uint4 *)(emb + (size_t)idc.id[c] * D) + g;
 #pragma unroll
         for (int s = 0; s < KS1; ++s) xw[(c * KS1 + s) * 64] = src[2 * s];
     }
     __syncthreads();
 
-    // Chunk `nx` of the weights straight into buffer `buf`: per instruction the workgroup moves
-    // 4 KB, wave w the 1 KB at +1024 w (the LDS base of such a load is wave-uniform, lane l lands
-    // at +16 l).
-    static_assert(ST == 6, "six 16-byte pieces per thread and chunk");
-    auto stream_chunk = [&](int nx, int buf) {
-        const uint4 *srcw = frag + (size_t)nx * CHUNK_U4 + threadIdx.x;
-        uint4 *dstw = wbuf + (size_t)buf * CHUNK_U4 + wave * 64;
+    const uint32_t tid16 = threadIdx.x * 16;
+    // Set A of the layer-1 accumulators enters every batch holding the user term of hidden block
+    // 0: loaded here for the first batch, by the last layer-1 step of the batch before otherwise.
+    f32x16 accA0, accA1;
 #pragma unroll
-        for (int t = 0; t < ST; ++t)
-            __builtin_amdgcn_global_load_lds((global_void *)(srcw + t * ST_BLOCK), (lds_void *)(dstw + t * ST_BLOCK),
-                                             16, 0, 0);
-    };
+    for (int t4 = 0; t4 < 4; ++t4) {
+        f32x4 pv0 = *(const f32x4 *)(upre + (size_t)idc.q[0] * H1 + 4 * g + 8 * t4);
+        f32x4 pv1 = *(const f32x4 *)(upre + (size_t)idc.q[1] * H1 + 4 * g + 8 * t4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            accA0[4 * t4 + e] = pv0[e];
+            accA1[4 * t4 + e] = pv1[e];
+        }
+    }
     int cur = 0;  // buffer holding the chunk of the current step; (cur + 1) % 3 the next one's
 
 #pragma unroll 1
@@ -201,38 +210,36 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         bf16x8 xf[CB][KS1];
         const float *up[CB];
         bool bad[CB];
+        size_t nxt_off[CB];  // element offsets of this lane's pieces of the next batch's rows
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
 #pragma unroll
             for (int s = 0; s < KS1; s += 4) {
                 u32x4 r0, r1, r2, r3;
-                lds_load4_b128(xw_addr + (c * KS1 + s) * 1024, r0, r1, r2, r3);
+                lds_load4_b128<1024>(xw_addr + (c * KS1 + s) * 1024, r0, r1, r2, r3);
                 xf[c][s] = __builtin_bit_cast(bf16x8, r0);
                 xf[c][s + 1] = __builtin_bit_cast(bf16x8, r1);
                 xf[c][s + 2] = __builtin_bit_cast(bf16x8, r2);
                 xf[c][s + 3] = __builtin_bit_cast(bf16x8, r3);
             }
-            up[c] = upre + (size_t)qn[c] * H1 + 4 * g;
-            bad[c] = badn[c];
+            up[c] = upre + (size_t)idc.q[c] * H1 + 4 * g;
+            bad[c] = idc.bad[c];
+            nxt_off[c] = (size_t)idn.id[c] * D + 8 * g;
         }
-        load_ids(tile + gridDim.x);
-        size_t nxt_off[CB];  // element offsets of this lane's pieces of the next batch's rows
-#pragma unroll
-        for (int c = 0; c < CB; ++c) nxt_off[c] = (size_t)idn[c] * D + 8 * g;
+        idc = idn;
+        idn = load_ids(tile + 2 * (int64_t)gridDim.x);  // consumed one batch from now
 
+        // layer-2 accumulators start from the bias (kept in LDS: a global load here would be waited for)
         f32x16 acc2[NB2][CB];
-        int opaque_zero = 0;
-        asm volatile("" : "+s"(opaque_zero));  // keeps the loads below inside the batch loop
-        const float *b2t = b2 + opaque_zero;
 #pragma unroll
         for (int n2 = 0; n2 < NB2; ++n2) {
+            u32x4 bv[4];
+            lds_load4_b128<32>(b2_addr + n2 * 128, bv[0], bv[1], bv[2], bv[3]);
             f32x16 init;
 #pragma unroll
-            for (int t4 = 0; t4 < 4; ++t4) {
-                f32x4 bv = *(const f32x4 *)(b2t + n2 * 32 + 8 * t4 + 4 * g);
+            for (int t4 = 0; t4 < 4; ++t4)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) init[4 * t4 + e] = bv[e];
-            }
+                for (int e = 0; e < 4; ++e) init[4 * t4 + e] = __uint_as_float(bv[t4][e]);
 #pragma unroll
             for (int c = 0; c < CB; ++c) acc2[n2][c] = init;
         }
@@ -240,48 +247,41 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         // Two sets of layer-1 accumulators (A, B) and of converted hidden units alternate by step;
         // all of them, and the layer-2 accumulators, sit in fixed physical registers (see
         // gen_stream_asm.py), so every variant of the step agrees on where they are.
-        f32x16 accA0, accA1, accB0, accB1;
+        f32x16 accB0, accB1;
         u32x4 hA00, hA01, hA10, hA11, hB00, hB01, hB10, hB11;
-#define LOAD_USER_TERM(ACC0, ACC1, nb)                                            \
-    _Pragma("unroll") for (int t4 = 0; t4 < 4; ++t4) {                            \
-        f32x4 pv0 = *(const f32x4 *)(up[0] + (nb) * 32 + 8 * t4);                 \
-        f32x4 pv1 = *(const f32x4 *)(up[1] + (nb) * 32 + 8 * t4);                 \
-        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                           \
-            ACC0[4 * t4 + e] = pv0[e];                                            \
-            ACC1[4 * t4 + e] = pv1[e];                                            \
-        }                                                                         \
-    }
-        // Before the assembly of step i the compiler issues the global-to-LDS loads of weight
-        // chunk i+2 into the buffer that step i-1 read (fenced, so that they stay here); every
-        // other load of the step, its waits, the LDS store of the item-row piece fetched one
-        // step ago and the workgroup barrier are inside the assembly (see gen_stream_asm.py).
+        // Operands of step i.  Weight chunk i+2 goes straight to the buffer that step i-1 read: per
+        // load instruction the workgroup moves 4 KB, wave w the 1 KB at +1024 w (the LDS base of
+        // such a load is wave-uniform, lane l lands at +16 l); the global side is a scalar base
+        // per instruction plus one lane offset.
 #define STEP_PRE(i)                                                                                  \
-    asm volatile("" ::: "memory");                                                                   \
-    {                                                                                                \
-        int nx = (i) + 2;                                                                            \
-        if (nx >= NSTEP) nx -= NSTEP;                                                                \
-        int into = cur + 2;                                                                          \
-        if (into >= NBUF) into -= NBUF;                                                              \
-        stream_chunk(nx, into);                                                                      \
-    }                                                                                                \
-    asm volatile("" ::: "memory");                                                                   \
+    int nx = (i) + 2;                                                                                \
+    if (nx >= NSTEP) nx -= NSTEP;                                                                    \
+    int into = cur + 2;                                                                              \
+    if (into >= NBUF) into -= NBUF;                                                                  \
+    const char *sb0 = (const char *)frag + (size_t)nx * (CHUNK_U4 * 16);                             \
+    const uint32_t lb = __builtin_amdgcn_readfirstlane(                                              \
+        (uint32_t)(uintptr_t)(wbuf + (size_t)into * CHUNK_U4 + wave * 64));                          \
     const uint32_t wc = (uint32_t)(uintptr_t)(wbuf + (size_t)cur * CHUNK_U4 + lane);                 \
-    const float *upn0 = up[0] + ((i) + 1) * 32, *upn1 = up[1] + ((i) + 1) * 32; /* user term of step i+1 */ \
+    /* user term of step i+1, or of the next batch's step 0 (idc already names the next batch) */   \
+    const float *upn0 = (i) + 1 < NB1 ? up[0] + ((i) + 1) * 32 : upre + (size_t)idc.q[0] * H1 + 4 * g; \
+    const float *upn1 = (i) + 1 < NB1 ? up[1] + ((i) + 1) * 32 : upre + (size_t)idc.q[1] * H1 + 4 * g; \
     const uint16_t *xpsrc = emb + ((((i) / KS1) & 1) ? nxt_off[1] : nxt_off[0]) + 16 * ((i) % KS1);  \
     const uint32_t xwst = xw_addr + ((i) - 1) * 1024; /* LDS slot of the piece fetched in step i-1 */ \
     bf16x8 f0, f1, f2, f3;                                                                           \
     cur = cur + 1 == NBUF ? 0 : cur + 1;
-#define LOADS_IN [upn0] "v"(upn0), [upn1] "v"(upn1), [xpsrc] "v"(xpsrc)
+#define DMA_IN                                                                                       \
+    [vo] "v"(tid16), [lb] "s"(lb), [sb0] "s"(sb0), [sb1] "s"(sb0 + 4096), [sb2] "s"(sb0 + 2 * 4096), \
+        [sb3] "s"(sb0 + 3 * 4096), [sb4] "s"(sb0 + 4 * 4096), [sb5] "s"(sb0 + 5 * 4096)
+#define LOADS_IN DMA_IN, [upn0] "v"(upn0), [upn1] "v"(upn1), [xpsrc] "v"(xpsrc)
         static_assert(NB1 % 2 == 0 && NB1 == CB * KS1, "steps come in A/B pairs; one item piece per step");
         u32x4 xpA, xpB;
-        LOAD_USER_TERM(accA0, accA1, 0)
         {   // step 0: layer 1 only
             STEP_PRE(0)
             asm volatile(STREAM_ASM_FIRST
                          : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1),
                            STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), FRAG_TEMPS, [xpn] "=&v"(xpA)
                          : [wc] "v"(wc), X_OPERANDS, LOADS_IN
-                         : "memory");
+                         : "memory", "scc");
         }
 #pragma unroll 1
         for (int i = 1; i < NB1 - 1; i += 2) {
@@ -292,7 +292,7 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
                                STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpB)
                              : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), LOADS_IN,
                                [xpo] "v"(xpA), [xwst] "v"(xwst)
-                             : "memory");
+                             : "memory", "scc");
             }
             {
                 STEP_PRE(i + 1)
@@ -301,30 +301,29 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
                                STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpA)
                              : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_B(hB00, hB01, hB10, hB11), LOADS_IN,
                                [xpo] "v"(xpB), [xwst] "v"(xwst)
-                             : "memory");
+                             : "memory", "scc");
             }
         }
-        {   // step NB1 - 1: the last layer-1 block
+        {   // step NB1 - 1: the last layer-1 block; fetches the user term of the NEXT batch's block 0
             STEP_PRE(NB1 - 1)
-            asm volatile(STREAM_ASM_END_B
-                         : STREAM_ACC_B(accB0, accB1), STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS,
-                           [xpn] "=&v"(xpB)
-                         : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), [xpsrc] "v"(xpsrc),
+            asm volatile(STREAM_ASM_MID_B
+                         : STREAM_ACC_B(accB0, accB1), STREAM_ACC_OUT_A(accA0, accA1),
+                           STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpB)
+                         : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), LOADS_IN,
                            [xpo] "v"(xpA), [xwst] "v"(xwst)
-                         : "memory");
-            (void)upn0, (void)upn1;
+                         : "memory", "scc");
         }
         {   // step NB1: layer 2 only
             STEP_PRE(NB1)
             asm volatile(STREAM_ASM_LAST
                          : STREAM_ACC2, FRAG_TEMPS
-                         : [wc] "v"(wc), STREAM_HF_IN_B(hB00, hB01, hB10, hB11), [xpo] "v"(xpB), [xwst] "v"(xwst)
-                         : "memory");
+                         : [wc] "v"(wc), STREAM_HF_IN_B(hB00, hB01, hB10, hB11), DMA_IN, [xpo] "v"(xpB), [xwst] "v"(xwst)
+                         : "memory", "scc");
             (void)upn0, (void)upn1, (void)xpsrc;
         }
 #undef LOADS_IN
+#undef DMA_IN
 #undef STEP_PRE
-#undef LOAD_USER_TERM
 
         // head layer (fragment rows >= J are zero), then Eq. 8
         f32x16 acc3[CB];
@@ -335,7 +334,7 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
 #pragma unroll
         for (int n2 = 0; n2 < NB2; n2 += 2) {
             u32x4 a[4];
-            lds_load4_b128(w3_addr + 2 * n2 * 1024, a[0], a[1], a[2], a[3]);
+            lds_load4_b128<1024>(w3_addr + 2 * n2 * 1024, a[0], a[1], a[2], a[3]);
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -343,6 +342,16 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
                     mfma_v(acc3[c], __builtin_bit_cast(bf16x8, a[t]), relu_pack_i16(acc2[n2 + t / 2][c], t % 2));
         }
         drain_v(acc3[0], acc3[1]);
+        float hw[4], bb3[4];
+        {
+            u32x4 r0, r1, r2, r3;
+            lds_load4_b128<32>(b2_addr + NB2 * 128, r0, r1, r2, r3);  // [4g..] of the weights, +32 bytes: of the bias
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                hw[e] = __uint_as_float(r0[e]);
+                bb3[e] = __uint_as_float(r1[e]);
+            }
+        }
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
             float part = 0.f;
@@ -404,7 +413,7 @@ int launch_mlp_mfma_stream(const ann_graph *g, const ann_mlp *m, const float *up
                            const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
                            hipStream_t stream) {
     constexpr int H1 = 512;
-    constexpr size_t smem = ((size_t)3 * 24 * 64 + 16 * 64 + 4 * 16 * 64) * 16;  // 72 + 16 + 64 KB
+    constexpr size_t smem = ((size_t)3 * 24 * 64 + 16 * 64 + 4 * 16 * 64) * 16 + (256 + 32) * 4;  // 72 + 16 + 64 + 1 KB (+ head constants)
     constexpr int TILE = 256;
     auto fn = mlp_mfma2_stream_kernel<H1>;
     ANN_HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
