@@ -1,37 +1,44 @@
 #!/usr/bin/env python3
-"""Writes mlp_mfma_stream_asm.inc: the inline-assembly text of one pipeline step of the streaming
-MFMA relevance kernel (mlp_mfma_stream.hip), for item width 128 (8 layer-1 fragments per step) and
-second hidden width 256 (16 layer-2 fragments per step), 64 pairs per wave.
+"""Writes mlp_mfma_stream_asm.inc: the inline-assembly text of the NB1 + 1 = 17 pipeline steps of
+the streaming MFMA relevance kernel (mlp_mfma_stream.hip), for item width 128 (8 layer-1
+fragments per step), first hidden width 512 (16 blocks of 32 units) and second hidden width 256
+(16 layer-2 fragments per step), 64 pairs per wave.  Every step has its own text, so that all
+per-step addresses are immediates and nothing but one scalar add is left between two steps.
 
 Register plan of a wave (fixed physical registers, so that the vector-ALU instructions that turn
 fresh layer-1 accumulators into bf16 B operands can be interleaved with the MFMAs of layer 2 and
-so that every variant of the step agrees on where the long-lived values are):
+so that every step agrees on where the long-lived values are):
 
     256 AGPRs           layer-2 accumulators, 16 tiles (n2, c), constraint "a" (the allocator's choice)
     v[64:95], v[96:127] layer-1 accumulators, sets A and B (pairs c = 0, 1), alternating by step
     v[128:143]          hidden units produced from set A, tuple (c, half) at v[128 + 8c + 4half ...]
     v[144:159]          hidden units produced from set B
-    compiler's choice   the 16 item-row operands, four weight fragments, the LDS address
+    compiler's choice   the 16 item-row operands, four weight fragments, the LDS read address, pointers
 
-Step variants:  FIRST  layer 1 only (set A), conversion exposed
-                MID_A  layer 1 into set A, layer 2 with the hidden units of set B, conversion of
-                       set A interleaved with the layer-2 MFMAs;  MID_B the mirror image
-                LAST   layer 2 only, with the hidden units of set B
+Step i (0 .. 16):
+    layer 1   (i < 16)  hidden block i into set A (i even) or B (i odd); fragments 0..7 of chunk i
+    layer 2   (i > 0)   over the hidden units of block i-1 (the other set); fragments 8..23
+    convert   (i < 16)  ReLU + bf16 rounding of the fresh set, interleaved with the layer-2 MFMAs
+                        (exposed in step 0, which has none)
 
 Global loads of a step and their waits are part of the assembly too, because the compiler cannot
-count them: next to global-to-LDS loads any other vector-memory load makes it fall back to waiting
-for ALL outstanding loads, the weight chunks included (and it treats every LDS access it sees as
-depending on them).  A block therefore
-    - first issues the N_DMA global-to-LDS loads of the weight chunk two steps ahead (scalar base
-      %[sb<t>] + lane offset %[vo]; LDS base in M0, 4 KB further per load);
-    - then loads the user term of the NEXT layer-1 block straight into the accumulator set that
-      is idle during this step (8 loads), then one 16-byte piece of the next batch's item rows;
-    - before its first layer-1 MFMA waits for its own user term, loaded one step earlier: the
-      counter is in order, and younger than that term are the piece fetched after it and this
-      step's own loads;
-    - at the end waits until only this step's own loads are outstanding (then the chunk the next
-      step reads has landed, and so has the piece fetched one step ago), stores that piece to the
-      wave's LDS area, waits for the store and joins the workgroup barrier.
+count them: next to global-to-LDS loads any other vector-memory load makes it fall back to
+waiting for ALL outstanding loads, the weight chunks included (and it treats every LDS access it
+sees as depending on them).  Loads are spread over the step, one after the MFMAs of a fragment:
+issuing a vector-memory instruction holds the wave for some tens of cycles, which an MFMA in
+flight hides.  In issue order a step has
+    8   user term of hidden block i+1 (i < 15), straight into the accumulator set that is idle
+        during this step (block 0 is fetched by the kernel's own code before step 0)
+    1   one 16-byte piece of the next batch's item rows (i < 16)
+    6   weight chunk (i+2) mod 17 into the LDS buffer that step i-1 read: scalar base in
+        s[100:101] + lane offset %[vo]; LDS base in M0; both 4 KB further per load, so that the
+        scalar base ends a step at the next chunk (the kernel resets it where the chunks wrap)
+and waits (the counter is in order)
+    - before its first layer-1 MFMA for its own user term, issued first in step i-1: younger are
+      that step's item piece and chunk loads, 7 in all;
+    - at the end until only this step's own loads are outstanding: then the chunk the next step
+      reads has landed, and so has the piece fetched one step ago, which now goes to the wave's
+      LDS area; the store is waited for and the wave joins the workgroup barrier.
 
 Run this script after changing it; the .inc file is committed next to it.
 """
@@ -39,6 +46,8 @@ import os
 
 ACC = {"A": (64, 80), "B": (96, 112)}       # first register of the c = 0 / c = 1 accumulator
 HF = {"A": 128, "B": 144}                   # first register of the four (c, half) tuples
+NB1 = 16                                    # layer-1 blocks of 32 hidden units
+SB, SB_LO, SB_HI = "s[100:101]", "s100", "s101"   # scalar base of the weight chunk being fetched
 N_DMA = 6                                   # global-to-LDS loads per step: 6 x 256 lanes x 16 B = one chunk
 
 
@@ -91,76 +100,81 @@ def convert_ops(s):
     return ops
 
 
-def schedule(frags, first_frag, compute, extra=None, before_first=None):
+def schedule(n, first_frag, compute, extra, before_first):
     """Four fragments in flight: preload 4, then per fragment: wait until it has arrived (the LDS
     counter is in order), issue its MFMAs, reload its register with the fragment 4 ahead.
-    extra[t] = vector-ALU lines issued after the MFMAs of fragment t; before_first = lines
-    placed right before the first MFMA."""
-    n = len(frags)
+    extra[t] = lines issued after the MFMAs of fragment t; before_first = lines placed right
+    before the first MFMA."""
     out = [wt(0)] + [ld(f"f{i}", first_frag + i) for i in range(min(4, n))]
     for t in range(n):
         issued = min(n, t + 4)
         out.append(wt(issued - t - 1))
-        if t == 0 and before_first:
+        if t == 0:
             out += before_first
         out += compute(t, f"f{t % 4}")
         if t + 4 < n:
             out.append(ld(f"f{t % 4}", first_frag + t + 4))
-        if extra and t in extra:
-            out += extra[t]
+        out += extra.get(t, [])
     return out
 
 
-def dma_loads():
-    out = ["s_mov_b32 m0, %[lb]"]
+def vmem_ops(i, idle):
+    """The step's global loads in issue order, each a list of lines."""
+    ops = []
+    if i + 1 < NB1:
+        # register 4*t4 + e of pair c takes float 8*t4 + e of the 32 floats of block i+1
+        ops += [[f"global_load_dwordx4 {vr(ACC[idle][c] + 4 * t4, 4)}, %[up{c}], off offset:{(i + 1) * 128 + 32 * t4}"]
+                for t4 in range(4) for c in (0, 1)]
+    if i < NB1:
+        ops.append([f"global_load_dwordx4 %[xpn], %[xs], off offset:{32 * (i % 8)}"])  # %[xs]: row of pair c = i / 8
     for t in range(N_DMA):
-        if t:
-            out.append("s_add_u32 m0, m0, 0x1000")
-        out += ["s_nop 0", f"global_load_lds_dwordx4 %[vo], %[sb{t}]"]  # one wait state between the M0 write and its use
-    return out
+        # the M0 write sits right after the previous load: far more than the one wait state it needs
+        ops.append([f"global_load_lds_dwordx4 %[vo], {SB}", f"s_add_u32 {SB_LO}, {SB_LO}, 0x1000",
+                    f"s_addc_u32 {SB_HI}, {SB_HI}, 0"] + (["s_add_u32 m0, m0, 0x1000"] if t + 1 < N_DMA else []))
+    return ops
 
 
-def user_loads(into):
-    """User term of the next layer-1 block into accumulator set `into`: register 4*t4 + e of pair
-    c takes float 8*t4 + e of the 32 the lane's pointer %[upn<c>] addresses."""
-    return [f"global_load_dwordx4 {vr(ACC[into][c] + 4 * t4, 4)}, %[upn{c}], off offset:{32 * t4}"
-            for t4 in range(4) for c in (0, 1)]
+def step(i):
+    fresh = "A" if i % 2 == 0 else "B"      # set that layer 1 of this step fills
+    other = "B" if fresh == "A" else "A"    # its hidden units feed layer 2; its accumulators are idle
+    has_l1, has_l2 = i < NB1, i > 0
+    vm = vmem_ops(i, other)
+    own = len(vm)
+    before = [f"s_waitcnt vmcnt({1 + N_DMA})"] if 0 < i < NB1 else []   # step 0: the compiler's load and wait
+    n_frag = (8 if has_l1 else 0) + (16 if has_l2 else 0)
+    first_frag = 0 if has_l1 else 8
 
+    def compute(t, b):
+        f = first_frag + t
+        return m1(fresh, b, f) if f < 8 else m2(other, b, (f - 8) // 2, (f - 8) % 2)
 
-def step(kind, s=None, load_user=True, load_xp=True, store_xp=True, wait_user=True):
-    other = "B" if s == "A" else "A"
-    own = N_DMA + (8 if load_user else 0) + (1 if load_xp else 0)
-    head = dma_loads() + (user_loads(other) if load_user else []) + (["global_load_dwordx4 %[xpn], %[xpsrc], off"] if load_xp else [])
-    # own user term: younger are the piece fetched after it (one load) and this step's loads
-    before = [f"s_waitcnt vmcnt({own + 1})"] if wait_user else None
-    tail = [f"s_waitcnt vmcnt({own})"]
-    if store_xp:
-        tail += ["ds_write_b128 %[xwst], %[xpo]"]
-    tail += ["s_waitcnt lgkmcnt(0)", "s_barrier"]
-    if kind == "FIRST":
-        lines = schedule(range(8), 0, lambda t, b: m1("A", b, t), before_first=before)
-        lines += ["s_nop 15"] + convert_ops("A")
-    elif kind == "LAST":
-        lines = schedule(range(16), 8, lambda t, b: m2("B", b, t // 2, t % 2))
-        lines += ["s_nop 15"]
-    else:
-        ops = convert_ops(s)
+    extra = {t: [] for t in range(n_frag)}
+    # vector-memory loads: from the first fragment on, as evenly as they fit
+    per = -(-own // n_frag)
+    for k, op in enumerate(vm):
+        extra[k // per] += op
+    tail = []
+    if has_l1 and has_l2:
         # the last layer-1 MFMA is fragment 7; conversions start after fragment 9's layer-2 MFMAs
         # (four more MFMAs in between: far beyond the MFMA-to-VALU hazard window) and are spread
         # over the remaining fragments
+        ops = convert_ops(fresh)
         slots = list(range(10, 24))
-        per = -(-len(ops) // len(slots))
-        extra = {}
-        for i, t in enumerate(slots):
-            chunk = ops[i * per:(i + 1) * per]
-            if chunk:
-                extra[t] = chunk
-
-        def compute(t, b):
-            return m1(s, b, t) if t < 8 else m2(other, b, (t - 8) // 2, (t - 8) % 2)
-
-        lines = schedule(range(24), 0, compute, extra, before_first=before)
-    return head + lines + tail
+        cper = -(-len(ops) // len(slots))
+        for j, t in enumerate(slots):
+            extra[t] += ops[j * cper:(j + 1) * cper]
+    elif has_l1:
+        tail += ["s_nop 15"] + convert_ops(fresh)
+    else:
+        tail += ["s_nop 15"]    # the compiler's code reads the layer-2 accumulators next
+    tail += [f"s_waitcnt vmcnt({own})"]
+    if i > 0:
+        tail += [f"ds_write_b128 %[xw], %[xpo] offset:{(i - 1) * 1024}"]
+    tail += ["s_waitcnt lgkmcnt(0)", "s_barrier"]
+    # LDS read address of the lane: buffer base (scalar) + 16 * lane, the latter from the lane
+    # offset of the chunk loads (16 * thread index, 64 lanes per wave)
+    setup = ["s_mov_b32 m0, %[lb]", "v_and_b32 %[wc], 0x3ff, %[vo]", "v_add_u32 %[wc], %[wcs], %[wc]"]
+    return setup + schedule(n_frag, first_frag, compute, extra, before) + tail
 
 
 def c_string(lines):
@@ -170,12 +184,8 @@ def c_string(lines):
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
     out = ["// Generated by gen_stream_asm.py -- do not edit; see that script for the register plan.", ""]
-    # FIRST: its user term was fetched by the last MID_B of the batch before and waited for by LAST
-    variants = (("FIRST", step("FIRST", "A", store_xp=False, wait_user=False)),
-                ("MID_A", step("MID", "A")), ("MID_B", step("MID", "B")),
-                ("LAST", step("LAST", load_user=False, load_xp=False, wait_user=False)))
-    for name, lines in variants:
-        out.append(f"#define STREAM_ASM_{name} \\\n    {c_string(lines)}")
+    for i in range(NB1 + 1):
+        out.append(f"#define STREAM_ASM_STEP_{i} \\\n    {c_string(step(i))}")
         out.append("")
     # operand lists
     for s in "AB":
@@ -188,6 +198,7 @@ def main():
         out.append(f"#define STREAM_HF_IN_{s}(h00, h01, h10, h11) {ins}")
     acc2 = ", ".join(f'[a{n2}{c}] "+a"(acc2[{n2}][{c}])' for n2 in range(8) for c in (0, 1))
     out.append(f"#define STREAM_ACC2 {acc2}")
+    out.append(f'#define STREAM_SB(p) [sb] "+{{{SB}}}"(p)')
     out.append("")
     with open(os.path.join(here, "mlp_mfma_stream_asm.inc"), "w") as f:
         f.write("\n".join(out))

@@ -38,6 +38,7 @@
 //     first step, layer-2 accumulators after the last) are waited for with s_nop;
 //   - a weight-fragment register is reloaded from LDS only after the MFMAs reading it have
 //     issued (MFMA operands are read at issue).
+#include <type_traits>
 #include <vector>
 
 #include "common.h"
@@ -90,22 +91,32 @@ __device__ __forceinline__ void drain_v(f32x16 &x, f32x16 &y) {
 __device__ __forceinline__ void lds_store_b128(uint32_t addr, const u32x4 &v) {
     asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory");
 }
-// four 16-byte reads STRIDE bytes apart, complete on return
-template <int STRIDE>
+// f(integral_constant<int, I>) for I = 0 .. N-1: loop indices usable as template arguments
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// four 16-byte reads at addr + BASE + {0, 1, 2, 3} * STRIDE (immediates: no address registers), complete on return
+template <int BASE, int STRIDE>
 __device__ __forceinline__ void lds_load4_b128(uint32_t addr, u32x4 &r0, u32x4 &r1, u32x4 &r2, u32x4 &r3) {
-    asm volatile("ds_read_b128 %0, %4\n\t"
-                 "ds_read_b128 %1, %4 offset:%5\n\t"
-                 "ds_read_b128 %2, %4 offset:%6\n\t"
-                 "ds_read_b128 %3, %4 offset:%7\n\t"
+    static_assert(BASE >= 0 && BASE + 3 * STRIDE < 65536, "offsets are 16-bit immediates");
+    asm volatile("ds_read_b128 %0, %4 offset:%5\n\t"
+                 "ds_read_b128 %1, %4 offset:%6\n\t"
+                 "ds_read_b128 %2, %4 offset:%7\n\t"
+                 "ds_read_b128 %3, %4 offset:%8\n\t"
                  "s_waitcnt lgkmcnt(0)"
                  : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
-                 : "v"(addr), "n"(STRIDE), "n"(2 * STRIDE), "n"(3 * STRIDE)
+                 : "v"(addr), "n"(BASE), "n"(BASE + STRIDE), "n"(BASE + 2 * STRIDE), "n"(BASE + 3 * STRIDE)
                  : "memory");
 }
 
 #include "mlp_mfma_stream_asm.inc"  // STREAM_ASM_FIRST / MID_A / MID_B / LAST and their operand lists
 
-#define FRAG_TEMPS [f0] "=&v"(f0), [f1] "=&v"(f1), [f2] "=&v"(f2), [f3] "=&v"(f3)
+#define FRAG_TEMPS [f0] "=&v"(f0), [f1] "=&v"(f1), [f2] "=&v"(f2), [f3] "=&v"(f3), [wc] "=&v"(wct)
 #define X_OPERANDS                                                                                  \
     [x00] "v"(xf[0][0]), [x01] "v"(xf[0][1]), [x02] "v"(xf[0][2]), [x03] "v"(xf[0][3]),             \
     [x04] "v"(xf[0][4]), [x05] "v"(xf[0][5]), [x06] "v"(xf[0][6]), [x07] "v"(xf[0][7]),             \
@@ -144,8 +155,7 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int g = lane >> 5, col = lane & 31;
     uint4 *xw = xbuf + (size_t)wave * (CB * KS1 * 64) + lane;
-    const uint32_t xw_addr = (uint32_t)(uintptr_t)xw, w3_addr = (uint32_t)(uintptr_t)(w3buf + lane);
-    const uint32_t b2_addr = (uint32_t)(uintptr_t)(b2buf + 4 * g);
+    const uint32_t xw_addr = (uint32_t)(uintptr_t)xw;
 
     for (int i = threadIdx.x; i < W3_U4; i += ST_BLOCK) w3buf[i] = frag[(size_t)NSTEP * CHUNK_U4 + i];
     for (int i = threadIdx.x; i < 2 * CHUNK_U4; i += ST_BLOCK) wbuf[i] = frag[i];  // chunks 0 and 1
@@ -156,9 +166,9 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         b2buf[NB2 * 32 + 8 + threadIdx.x] = (int)threadIdx.x < J ? b3[threadIdx.x] : 0.f;
     }
 
-    // Pair ids run two batches ahead of the arithmetic and item rows one batch ahead, so that no
-    // batch waits for a dependent chain of loads: (idc, qc) belong to the batch whose rows are in
-    // the wave's LDS area, (idn, qn) to the one after it.
+    // Item rows are gathered one batch ahead of the arithmetic (into the wave's LDS area), so the
+    // item ids run two batches ahead; query ids and validity are read again one batch ahead rather
+    // than kept in registers through a batch.  Rows past the end read the last pair (never stored).
     struct Ids {
         int32_t id[CB], q[CB];
         bool bad[CB];
@@ -168,12 +178,10 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
             int64_t row = tile * TILE + (int64_t)wave * 64 + c * 32 + col;
-            int32_t v = 0, q = 0;
-            if (tile < n_tiles && row < M) {
-                v = pair_id[row];
-                q = pair_q[row];
-            }
-            r.bad[c] = (v < 0 || (int64_t)v >= N || q < 0 || q >= Q);
+            row = row < M ? row : M - 1;
+            const int32_t v = pair_id[row], q = pair_q[row];
+            // no short-circuit: both loads are issued before either value is looked at
+            r.bad[c] = ((uint64_t)(int64_t)v >= (uint64_t)N) | ((uint32_t)q >= (uint32_t)Q);
             r.id[c] = r.bad[c] ? 0 : v;
             r.q[c] = r.bad[c] ? 0 : q;
         }
@@ -190,51 +198,64 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
 
     const uint32_t tid16 = threadIdx.x * 16;
     // Set A of the layer-1 accumulators enters every batch holding the user term of hidden block
-    // 0: loaded here for the first batch, by the last layer-1 step of the batch before otherwise.
+    // 0: loaded here for the first batch, at the end of the batch before otherwise.
     f32x16 accA0, accA1;
+    const float *up[CB];
+    bool bad[CB];
+    auto load_user_term0 = [&]() {
 #pragma unroll
-    for (int t4 = 0; t4 < 4; ++t4) {
-        f32x4 pv0 = *(const f32x4 *)(upre + (size_t)idc.q[0] * H1 + 4 * g + 8 * t4);
-        f32x4 pv1 = *(const f32x4 *)(upre + (size_t)idc.q[1] * H1 + 4 * g + 8 * t4);
+        for (int t4 = 0; t4 < 4; ++t4) {
+            f32x4 pv0 = *(const f32x4 *)(up[0] + 8 * t4);
+            f32x4 pv1 = *(const f32x4 *)(up[1] + 8 * t4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            accA0[4 * t4 + e] = pv0[e];
-            accA1[4 * t4 + e] = pv1[e];
+            for (int e = 0; e < 4; ++e) {
+                accA0[4 * t4 + e] = pv0[e];
+                accA1[4 * t4 + e] = pv1[e];
+            }
         }
+    };
+#pragma unroll
+    for (int c = 0; c < CB; ++c) {
+        up[c] = upre + (size_t)idc.q[c] * H1 + 4 * g;
+        bad[c] = idc.bad[c];
     }
-    int cur = 0;  // buffer holding the chunk of the current step; (cur + 1) % 3 the next one's
+    load_user_term0();
+    // LDS address and global-to-LDS base (the wave's quarter) of the buffers that steps
+    // 0, 1, 2 (mod 3) of the current batch read
+    uint32_t wsv[NBUF], lbv[NBUF];
+#pragma unroll
+    for (int b = 0; b < NBUF; ++b) {
+        wsv[b] = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(wbuf + (size_t)b * CHUNK_U4));
+        lbv[b] = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(wbuf + (size_t)b * CHUNK_U4 + wave * 64));
+    }
 
 #pragma unroll 1
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t row0 = tile * TILE + (int64_t)wave * 64;
         bf16x8 xf[CB][KS1];
-        const float *up[CB];
-        bool bad[CB];
         size_t nxt_off[CB];  // element offsets of this lane's pieces of the next batch's rows
+        static_for<0, CB * KS1 / 4>([&](auto quad) {
+            constexpr int c = decltype(quad)::value / (KS1 / 4), s = 4 * (decltype(quad)::value % (KS1 / 4));
+            u32x4 r0, r1, r2, r3;
+            lds_load4_b128<(c * KS1 + s) * 1024, 1024>(xw_addr, r0, r1, r2, r3);
+            xf[c][s] = __builtin_bit_cast(bf16x8, r0);
+            xf[c][s + 1] = __builtin_bit_cast(bf16x8, r1);
+            xf[c][s + 2] = __builtin_bit_cast(bf16x8, r2);
+            xf[c][s + 3] = __builtin_bit_cast(bf16x8, r3);
+        });
 #pragma unroll
-        for (int c = 0; c < CB; ++c) {
-#pragma unroll
-            for (int s = 0; s < KS1; s += 4) {
-                u32x4 r0, r1, r2, r3;
-                lds_load4_b128<1024>(xw_addr + (c * KS1 + s) * 1024, r0, r1, r2, r3);
-                xf[c][s] = __builtin_bit_cast(bf16x8, r0);
-                xf[c][s + 1] = __builtin_bit_cast(bf16x8, r1);
-                xf[c][s + 2] = __builtin_bit_cast(bf16x8, r2);
-                xf[c][s + 3] = __builtin_bit_cast(bf16x8, r3);
-            }
-            up[c] = upre + (size_t)idc.q[c] * H1 + 4 * g;
-            bad[c] = idc.bad[c];
-            nxt_off[c] = (size_t)idn.id[c] * D + 8 * g;
-        }
-        idc = idn;
-        idn = load_ids(tile + 2 * (int64_t)gridDim.x);  // consumed one batch from now
+        for (int c = 0; c < CB; ++c) nxt_off[c] = (size_t)idn.id[c] * D + 8 * g;
 
         // layer-2 accumulators start from the bias (kept in LDS: a global load here would be waited for)
         f32x16 acc2[NB2][CB];
-#pragma unroll
-        for (int n2 = 0; n2 < NB2; ++n2) {
+        // small addresses are rebuilt where they are used rather than kept in registers across the steps
+        uint32_t t16 = tid16;
+        asm volatile("" : "+v"(t16));
+        const uint32_t b2_addr = (uint32_t)(uintptr_t)b2buf + ((t16 >> 5) & 16);  // 16 bytes * g
+        static_for<0, NB2>([&](auto n2c) {
+            constexpr int n2 = decltype(n2c)::value;
             u32x4 bv[4];
-            lds_load4_b128<32>(b2_addr + n2 * 128, bv[0], bv[1], bv[2], bv[3]);
+            lds_load4_b128<n2 * 128, 32>(b2_addr, bv[0], bv[1], bv[2], bv[3]);
             f32x16 init;
 #pragma unroll
             for (int t4 = 0; t4 < 4; ++t4)
@@ -242,88 +263,74 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
                 for (int e = 0; e < 4; ++e) init[4 * t4 + e] = __uint_as_float(bv[t4][e]);
 #pragma unroll
             for (int c = 0; c < CB; ++c) acc2[n2][c] = init;
-        }
+        });
 
         // Two sets of layer-1 accumulators (A, B) and of converted hidden units alternate by step;
         // all of them, and the layer-2 accumulators, sit in fixed physical registers (see
         // gen_stream_asm.py), so every variant of the step agrees on where they are.
         f32x16 accB0, accB1;
         u32x4 hA00, hA01, hA10, hA11, hB00, hB01, hB10, hB11;
-        // Operands of step i.  Weight chunk i+2 goes straight to the buffer that step i-1 read: per
-        // load instruction the workgroup moves 4 KB, wave w the 1 KB at +1024 w (the LDS base of
-        // such a load is wave-uniform, lane l lands at +16 l); the global side is a scalar base
-        // per instruction plus one lane offset.
-#define STEP_PRE(i)                                                                                  \
-    int nx = (i) + 2;                                                                                \
-    if (nx >= NSTEP) nx -= NSTEP;                                                                    \
-    int into = cur + 2;                                                                              \
-    if (into >= NBUF) into -= NBUF;                                                                  \
-    const char *sb0 = (const char *)frag + (size_t)nx * (CHUNK_U4 * 16);                             \
-    const uint32_t lb = __builtin_amdgcn_readfirstlane(                                              \
-        (uint32_t)(uintptr_t)(wbuf + (size_t)into * CHUNK_U4 + wave * 64));                          \
-    const uint32_t wc = (uint32_t)(uintptr_t)(wbuf + (size_t)cur * CHUNK_U4 + lane);                 \
-    /* user term of step i+1, or of the next batch's step 0 (idc already names the next batch) */   \
-    const float *upn0 = (i) + 1 < NB1 ? up[0] + ((i) + 1) * 32 : upre + (size_t)idc.q[0] * H1 + 4 * g; \
-    const float *upn1 = (i) + 1 < NB1 ? up[1] + ((i) + 1) * 32 : upre + (size_t)idc.q[1] * H1 + 4 * g; \
-    const uint16_t *xpsrc = emb + ((((i) / KS1) & 1) ? nxt_off[1] : nxt_off[0]) + 16 * ((i) % KS1);  \
-    const uint32_t xwst = xw_addr + ((i) - 1) * 1024; /* LDS slot of the piece fetched in step i-1 */ \
-    bf16x8 f0, f1, f2, f3;                                                                           \
-    cur = cur + 1 == NBUF ? 0 : cur + 1;
-#define DMA_IN                                                                                       \
-    [vo] "v"(tid16), [lb] "s"(lb), [sb0] "s"(sb0), [sb1] "s"(sb0 + 4096), [sb2] "s"(sb0 + 2 * 4096), \
-        [sb3] "s"(sb0 + 3 * 4096), [sb4] "s"(sb0 + 4 * 4096), [sb5] "s"(sb0 + 5 * 4096)
-#define LOADS_IN DMA_IN, [upn0] "v"(upn0), [upn1] "v"(upn1), [xpsrc] "v"(xpsrc)
-        static_assert(NB1 % 2 == 0 && NB1 == CB * KS1, "steps come in A/B pairs; one item piece per step");
+        // Operands of step i (see gen_stream_asm.py for the text).  Weight chunk i+2 goes straight
+        // to the buffer that step i-1 read: per load instruction the workgroup moves 4 KB, wave w
+        // the 1 KB at +1024 w (the LDS base of such a load is wave-uniform, lane l lands at +16 l);
+        // the global side is the chunk's scalar base plus one lane offset per instruction.
         u32x4 xpA, xpB;
-        {   // step 0: layer 1 only
-            STEP_PRE(0)
-            asm volatile(STREAM_ASM_FIRST
-                         : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1),
-                           STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), FRAG_TEMPS, [xpn] "=&v"(xpA)
-                         : [wc] "v"(wc), X_OPERANDS, LOADS_IN
-                         : "memory", "scc");
+        bf16x8 f0, f1, f2, f3;
+        uint32_t wct;
+        static_assert(NB1 == 16 && NB1 == CB * KS1 && NSTEP % NBUF == 2, "the generated steps assume these");
+        const char *sbv = (const char *)frag + 2 * (CHUNK_U4 * 16);   // chunk 2; every step leaves it at the next chunk
+        const uint16_t *xs = emb + nxt_off[0];                        // next batch's row of pair c = 0 (steps 0..7)
+#define STEP_COMMON(i) [wcs] "s"(wsv[(i) % NBUF]), [lb] "s"(lbv[((i) + 2) % NBUF]), [vo] "v"(tid16)
+#define STEP_LOADS [up0] "v"(up[0]), [up1] "v"(up[1]), [xs] "v"(xs)
+        // odd step: layer 1 into set B, layer 2 over the hidden units of set A; fetches into set A
+#define STEP_ODD(i)                                                                                   \
+    asm volatile(STREAM_ASM_STEP_##i                                                                  \
+                 : STREAM_ACC_B(accB0, accB1), STREAM_ACC_OUT_A(accA0, accA1), STREAM_SB(sbv),        \
+                   STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpB) \
+                 : STEP_COMMON(i), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), STEP_LOADS, \
+                   [xpo] "v"(xpA), [xw] "v"(xw_addr)                                                  \
+                 : "memory", "scc");
+#define STEP_EVEN(i)                                                                                  \
+    asm volatile(STREAM_ASM_STEP_##i                                                                  \
+                 : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1), STREAM_SB(sbv),        \
+                   STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpA) \
+                 : STEP_COMMON(i), X_OPERANDS, STREAM_HF_IN_B(hB00, hB01, hB10, hB11), STEP_LOADS, \
+                   [xpo] "v"(xpB), [xw] "v"(xw_addr)                                                  \
+                 : "memory", "scc");
+        // step 0: layer 1 only
+        asm volatile(STREAM_ASM_STEP_0
+                     : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1), STREAM_SB(sbv),
+                       STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), FRAG_TEMPS, [xpn] "=&v"(xpA)
+                     : STEP_COMMON(0), X_OPERANDS, STEP_LOADS
+                     : "memory", "scc");
+        STEP_ODD(1) STEP_EVEN(2) STEP_ODD(3) STEP_EVEN(4) STEP_ODD(5) STEP_EVEN(6) STEP_ODD(7)
+        xs = emb + nxt_off[1];  // steps 8..15 fetch the row of pair c = 1
+        STEP_EVEN(8) STEP_ODD(9) STEP_EVEN(10) STEP_ODD(11) STEP_EVEN(12) STEP_ODD(13) STEP_EVEN(14)
+        sbv = (const char *)frag;  // steps 15 and 16 fetch chunks 0 and 1 again
+        asm volatile(STREAM_ASM_STEP_15   // the last layer-1 block: no user term to fetch
+                     : STREAM_ACC_B(accB0, accB1), STREAM_SB(sbv), STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2,
+                       FRAG_TEMPS, [xpn] "=&v"(xpB)
+                     : STEP_COMMON(15), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), [xs] "v"(xs),
+                       [xpo] "v"(xpA), [xw] "v"(xw_addr)
+                     : "memory", "scc");
+        // step 16: layer 2 only
+        asm volatile(STREAM_ASM_STEP_16
+                     : STREAM_ACC2, FRAG_TEMPS, STREAM_SB(sbv)
+                     : STEP_COMMON(16), STREAM_HF_IN_B(hB00, hB01, hB10, hB11), [xpo] "v"(xpB), [xw] "v"(xw_addr)
+                     : "memory", "scc");
+#undef STEP_ODD
+#undef STEP_EVEN
+#undef STEP_LOADS
+#undef STEP_COMMON
+        {   // the buffers of steps 0, 1, 2 of the next batch: chunks 0 and 1 went where steps 15 and 16 sent them
+            uint32_t w = wsv[2], l = lbv[2];
+            wsv[2] = wsv[1], lbv[2] = lbv[1];
+            wsv[1] = wsv[0], lbv[1] = lbv[0];
+            wsv[0] = w, lbv[0] = l;
         }
-#pragma unroll 1
-        for (int i = 1; i < NB1 - 1; i += 2) {
-            {
-                STEP_PRE(i)
-                asm volatile(STREAM_ASM_MID_B
-                             : STREAM_ACC_B(accB0, accB1), STREAM_ACC_OUT_A(accA0, accA1),
-                               STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpB)
-                             : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), LOADS_IN,
-                               [xpo] "v"(xpA), [xwst] "v"(xwst)
-                             : "memory", "scc");
-            }
-            {
-                STEP_PRE(i + 1)
-                asm volatile(STREAM_ASM_MID_A
-                             : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1),
-                               STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpA)
-                             : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_B(hB00, hB01, hB10, hB11), LOADS_IN,
-                               [xpo] "v"(xpB), [xwst] "v"(xwst)
-                             : "memory", "scc");
-            }
-        }
-        {   // step NB1 - 1: the last layer-1 block; fetches the user term of the NEXT batch's block 0
-            STEP_PRE(NB1 - 1)
-            asm volatile(STREAM_ASM_MID_B
-                         : STREAM_ACC_B(accB0, accB1), STREAM_ACC_OUT_A(accA0, accA1),
-                           STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpB)
-                         : [wc] "v"(wc), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), LOADS_IN,
-                           [xpo] "v"(xpA), [xwst] "v"(xwst)
-                         : "memory", "scc");
-        }
-        {   // step NB1: layer 2 only
-            STEP_PRE(NB1)
-            asm volatile(STREAM_ASM_LAST
-                         : STREAM_ACC2, FRAG_TEMPS
-                         : [wc] "v"(wc), STREAM_HF_IN_B(hB00, hB01, hB10, hB11), DMA_IN, [xpo] "v"(xpB), [xwst] "v"(xwst)
-                         : "memory", "scc");
-            (void)upn0, (void)upn1, (void)xpsrc;
-        }
-#undef LOADS_IN
-#undef DMA_IN
-#undef STEP_PRE
+        // ids of the next batch (again) and of the one after it; the head layer hides their latency
+        idc = load_ids(tile + gridDim.x);
+        idn = load_ids(tile + 2 * (int64_t)gridDim.x);
 
         // head layer (fragment rows >= J are zero), then Eq. 8
         f32x16 acc3[CB];
@@ -331,21 +338,25 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         for (int c = 0; c < CB; ++c)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc3[c][e] = 0.f;
-#pragma unroll
-        for (int n2 = 0; n2 < NB2; n2 += 2) {
+        uint32_t h16 = tid16;
+        asm volatile("" : "+v"(h16));
+        const uint32_t w3_addr = (uint32_t)(uintptr_t)w3buf + (h16 & 1023);    // 16 bytes * lane
+        const uint32_t hb_addr = (uint32_t)(uintptr_t)b2buf + ((h16 >> 5) & 16);  // 16 bytes * g
+        static_for<0, NB2 / 2>([&](auto n2c) {
+            constexpr int n2 = 2 * decltype(n2c)::value;
             u32x4 a[4];
-            lds_load4_b128<1024>(w3_addr + 2 * n2 * 1024, a[0], a[1], a[2], a[3]);
+            lds_load4_b128<2 * n2 * 1024, 1024>(w3_addr, a[0], a[1], a[2], a[3]);
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int c = 0; c < CB; ++c)
                     mfma_v(acc3[c], __builtin_bit_cast(bf16x8, a[t]), relu_pack_i16(acc2[n2 + t / 2][c], t % 2));
-        }
+        });
         drain_v(acc3[0], acc3[1]);
         float hw[4], bb3[4];
         {
             u32x4 r0, r1, r2, r3;
-            lds_load4_b128<32>(b2_addr + NB2 * 128, r0, r1, r2, r3);  // [4g..] of the weights, +32 bytes: of the bias
+            lds_load4_b128<NB2 * 128, 32>(hb_addr, r0, r1, r2, r3);  // [4g..] of the weights, +32 bytes: of the bias
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 hw[e] = __uint_as_float(r0[e]);
@@ -361,6 +372,14 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
             int64_t row = row0 + c * 32 + col;
             if (g == 0 && row < M) scores[row] = bad[c] ? __uint_as_float(0x7fc00000u) : part + other;
         }
+        // the next batch's user pointers, validity, and its user term of hidden block 0 (the
+        // start of the next batch hides that latency)
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            up[c] = upre + (size_t)idc.q[c] * H1 + 4 * g;
+            bad[c] = idc.bad[c];
+        }
+        load_user_term0();
     }
     // the last two steps streamed chunks nobody reads; they must have landed before the LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
