@@ -13,7 +13,8 @@ so that every step agrees on where the long-lived values are):
     v[64:95], v[96:127] layer-1 accumulators, sets A and B (pairs c = 0, 1), alternating by step
     v[128:143]          hidden units produced from set A, tuple (c, half) at v[128 + 8c + 4half ...]
     v[144:159]          hidden units produced from set B
-    compiler's choice   the 16 item-row operands, four weight fragments, the LDS read address, pointers
+    v[160:175]          four weight fragments in flight from LDS (requested across step boundaries)
+    compiler's choice   the 16 item-row operands, LDS read addresses, pointers
 
 Step i (0 .. 16):
     layer 1   (i < 16)  hidden block i into set A (i even) or B (i odd); fragments 0..7 of chunk i
@@ -36,9 +37,13 @@ flight hides.  In issue order a step has
 and waits (the counter is in order)
     - before its first layer-1 MFMA for its own user term, issued first in step i-1: younger are
       that step's item piece and chunk loads, 7 in all;
-    - at the end until only this step's own loads are outstanding: then the chunk the next step
-      reads has landed, and so has the piece fetched one step ago, which now goes to the wave's
-      LDS area; the store is waited for and the wave joins the workgroup barrier.
+    - once its loads are issued, for the item piece fetched one step ago, which then goes to the
+      wave's LDS area;
+    - three fragments before its end until only this step's own loads are outstanding: then the
+      chunk the next step reads has landed; the LDS store is waited for and the wave joins the
+      workgroup barrier.  By then every read of this step's buffer has completed too: behind the barrier
+      the next step may refill it, and this step may already request the next step's first
+      fragments.
 
 Run this script after changing it; the .inc file is committed next to it.
 """
@@ -67,20 +72,16 @@ def acc2_reg(n2, c):
     return f"%[a{n2}{c}]"  # layer-2 accumulators: any AGPR tuple, the allocator keeps them in place
 
 
-def ld(buf, frag):
-    return f"ds_read_b128 %[{buf}], %[wc] offset:{frag * 1024}"
-
-
 def wt(n):
     return f"s_waitcnt lgkmcnt({n})"
 
 
 def m1(s, buf, k):
-    return [f"v_mfma_f32_32x32x16_bf16 {acc_reg(s, c)}, %[{buf}], %[x{c}{k}], {acc_reg(s, c)}" for c in (0, 1)]
+    return [f"v_mfma_f32_32x32x16_bf16 {acc_reg(s, c)}, {buf}, %[x{c}{k}], {acc_reg(s, c)}" for c in (0, 1)]
 
 
 def m2(hs, buf, n2, s2):
-    return [f"v_mfma_f32_32x32x16_bf16 {acc2_reg(n2, c)}, %[{buf}], {hf_reg(hs, c, s2)}, {acc2_reg(n2, c)}"
+    return [f"v_mfma_f32_32x32x16_bf16 {acc2_reg(n2, c)}, {buf}, {hf_reg(hs, c, s2)}, {acc2_reg(n2, c)}"
             for c in (0, 1)]
 
 
@@ -100,21 +101,79 @@ def convert_ops(s):
     return ops
 
 
-def schedule(n, first_frag, compute, extra, before_first):
-    """Four fragments in flight: preload 4, then per fragment: wait until it has arrived (the LDS
-    counter is in order), issue its MFMAs, reload its register with the fragment 4 ahead.
-    extra[t] = lines issued after the MFMAs of fragment t; before_first = lines placed right
-    before the first MFMA."""
-    out = [wt(0)] + [ld(f"f{i}", first_frag + i) for i in range(min(4, n))]
+FRAG = 160                                  # first register of the four weight fragments in flight
+
+
+def freg(k):
+    return vr(FRAG + 4 * (k % 4), 4)
+
+
+def ld(k, frag, addr="wc"):
+    return f"ds_read_b128 {freg(k)}, %[{addr}] offset:{frag * 1024}"
+
+
+def sync_slot(n):
+    """Slot after whose MFMAs the wave synchronises with the workgroup: all reads of this step's
+    buffer were issued two slots earlier, and three slots of MFMAs are left to cover the first
+    reads of the next step's buffer."""
+    return n - 3
+
+
+def schedule(n, first_frag, compute, extra, before_first, sync, preloaded, next_first, store):
+    """Fragment k of the step lives in register set k % 4; four are in flight.  Per slot t: wait
+    until fragment t has arrived (the LDS counter is in order: allow as many outstanding
+    operations as were issued after its read), issue its MFMAs, then re-use its registers for the
+    fragment four ahead.  The last four slots have nothing of this step left to read: after slot
+    n-3 comes `sync` (ending in the barrier), after which the next step's first fragments are
+    requested (from %[wcn], the buffer the next step reads; next_first = its first fragment, None =
+    no next step), so that the next block starts with its reads in flight (preloaded).
+    store = (slot, wait line, LDS store line) or None: an LDS store issued after that slot."""
+    out, queue = [], []          # queue: LDS operations issued and not known complete, in order
+
+    def issue(tag, line):
+        queue.append(tag)
+        out.append(line)
+
+    def wait_for(tag):
+        if tag not in queue:     # completed by an earlier full wait
+            return
+        younger = len(queue) - queue.index(tag) - 1
+        out.append(wt(younger))
+        del queue[:queue.index(tag) + 1]
+
+    if preloaded:
+        queue += [("f", k) for k in range(4)]
+    else:
+        out.append(wt(0))
+        for k in range(min(4, n)):
+            issue(("f", k), ld(k, first_frag + k))
     for t in range(n):
-        issued = min(n, t + 4)
-        out.append(wt(issued - t - 1))
+        wait_for(("f", t))
         if t == 0:
-            out += before_first
-        out += compute(t, f"f{t % 4}")
+            out.extend(before_first)
+        # an MFMA occupies the matrix pipe for 32 cycles during which the wave can issue other
+        # instructions: half of the slot's side work goes behind each of the two MFMAs (the
+        # fragment's registers can only be re-used after the second)
+        first, second = compute(t, freg(t))
+        units = extra.get(t, [])
+        half = (len(units) + 1) // 2
+        out.append(first)
+        for u in units[:half]:
+            out.extend(u)
+        out.append(second)
         if t + 4 < n:
-            out.append(ld(f"f{t % 4}", first_frag + t + 4))
-        out += extra.get(t, [])
+            issue(("f", t + 4), ld(t + 4, first_frag + t + 4))
+        for u in units[half:]:
+            out.extend(u)
+        if store and t == store[0]:
+            out.append(store[1])
+            issue(("w",), store[2])
+        if t == sync_slot(n):
+            out.extend(sync)     # ends with lgkmcnt(0): nothing outstanding
+            queue.clear()
+        if next_first is not None and t >= sync_slot(n):
+            for k in ([0, 1] if t == sync_slot(n) else [t - sync_slot(n) + 1]):
+                issue(("n", k), ld(k, next_first + k, "wcn"))
     return out
 
 
@@ -149,10 +208,10 @@ def step(i):
         return m1(fresh, b, f) if f < 8 else m2(other, b, (f - 8) // 2, (f - 8) % 2)
 
     extra = {t: [] for t in range(n_frag)}
-    # vector-memory loads: from the first fragment on, as evenly as they fit
-    per = -(-own // n_frag)
+    # vector-memory loads: from the first fragment on, as evenly as they fit before the synchronisation
+    per = -(-own // (sync_slot(n_frag) + 1))
     for k, op in enumerate(vm):
-        extra[k // per] += op
+        extra[k // per].append(op)
     tail = []
     if has_l1 and has_l2:
         # the last layer-1 MFMA is fragment 7; conversions start after fragment 9's layer-2 MFMAs
@@ -162,19 +221,27 @@ def step(i):
         slots = list(range(10, 24))
         cper = -(-len(ops) // len(slots))
         for j, t in enumerate(slots):
-            extra[t] += ops[j * cper:(j + 1) * cper]
+            extra[t] += [[op] for op in ops[j * cper:(j + 1) * cper]]
     elif has_l1:
         tail += ["s_nop 15"] + convert_ops(fresh)
     else:
         tail += ["s_nop 15"]    # the compiler's code reads the layer-2 accumulators next
-    tail += [f"s_waitcnt vmcnt({own})"]
+    sync = [f"s_waitcnt vmcnt({own})", "s_waitcnt lgkmcnt(0)", "s_barrier"]
+    store = None
     if i > 0:
-        tail += [f"ds_write_b128 %[xw], %[xpo] offset:{(i - 1) * 1024}"]
-    tail += ["s_waitcnt lgkmcnt(0)", "s_barrier"]
-    # LDS read address of the lane: buffer base (scalar) + 16 * lane, the latter from the lane
-    # offset of the chunk loads (16 * thread index, 64 lanes per wave)
-    setup = ["s_mov_b32 m0, %[lb]", "v_and_b32 %[wc], 0x3ff, %[vo]", "v_add_u32 %[wc], %[wcs], %[wc]"]
-    return setup + schedule(n_frag, first_frag, compute, extra, before) + tail
+        # the item piece fetched one step ago goes to the wave's LDS area once all of this step's
+        # loads are issued (younger than it: the 6 chunk loads behind it and this step's own),
+        # a few slots ahead of the synchronisation, which waits for the store
+        last_vm = (own - 1) // per
+        store = (max(last_vm + 1, sync_slot(n_frag) - 3), f"s_waitcnt vmcnt({N_DMA + own})",
+                 f"ds_write_b128 %[xw], %[xpo] offset:{(i - 1) * 1024}")
+        assert last_vm < store[0] < sync_slot(n_frag)
+    # LDS read addresses of the lane, this step's buffer and the next step's: buffer base (scalar)
+    # + 16 * lane, the latter from the lane offset of the chunk loads (16 * thread index, 64 lanes per wave)
+    setup = ["s_mov_b32 m0, %[lb]", "v_and_b32 %[wcn], 0x3ff, %[vo]", "v_add_u32 %[wc], %[wcs], %[wcn]",
+             "v_add_u32 %[wcn], %[wcsn], %[wcn]"]
+    next_first = None if i == NB1 else (0 if i + 1 < NB1 else 8)
+    return setup + schedule(n_frag, first_frag, compute, extra, before, sync, preloaded=i > 0, next_first=next_first, store=store) + tail
 
 
 def c_string(lines):
@@ -199,6 +266,8 @@ def main():
     acc2 = ", ".join(f'[a{n2}{c}] "+a"(acc2[{n2}][{c}])' for n2 in range(8) for c in (0, 1))
     out.append(f"#define STREAM_ACC2 {acc2}")
     out.append(f'#define STREAM_SB(p) [sb] "+{{{SB}}}"(p)')
+    frs = ", ".join(f'[f{k}] "+{{{freg(k)}}}"(f{k})' for k in range(4))
+    out.append(f"#define STREAM_FRAGS(f0, f1, f2, f3) {frs}")
     out.append("")
     with open(os.path.join(here, "mlp_mfma_stream_asm.inc"), "w") as f:
         f.write("\n".join(out))

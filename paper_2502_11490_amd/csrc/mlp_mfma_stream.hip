@@ -116,7 +116,7 @@ __device__ __forceinline__ void lds_load4_b128(uint32_t addr, u32x4 &r0, u32x4 &
 
 #include "mlp_mfma_stream_asm.inc"  // STREAM_ASM_FIRST / MID_A / MID_B / LAST and their operand lists
 
-#define FRAG_TEMPS [f0] "=&v"(f0), [f1] "=&v"(f1), [f2] "=&v"(f2), [f3] "=&v"(f3), [wc] "=&v"(wct)
+#define FRAG_TEMPS STREAM_FRAGS(f0, f1, f2, f3), [wc] "=&v"(wct), [wcn] "=&v"(wcnt)
 #define X_OPERANDS                                                                                  \
     [x00] "v"(xf[0][0]), [x01] "v"(xf[0][1]), [x02] "v"(xf[0][2]), [x03] "v"(xf[0][3]),             \
     [x04] "v"(xf[0][4]), [x05] "v"(xf[0][5]), [x06] "v"(xf[0][6]), [x07] "v"(xf[0][7]),             \
@@ -275,12 +275,13 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         // the 1 KB at +1024 w (the LDS base of such a load is wave-uniform, lane l lands at +16 l);
         // the global side is the chunk's scalar base plus one lane offset per instruction.
         u32x4 xpA, xpB;
-        bf16x8 f0, f1, f2, f3;
-        uint32_t wct;
+        bf16x8 f0 = {}, f1 = {}, f2 = {}, f3 = {};  // in flight from LDS across the step boundaries: never touched in between
+        uint32_t wct, wcnt;
         static_assert(NB1 == 16 && NB1 == CB * KS1 && NSTEP % NBUF == 2, "the generated steps assume these");
         const char *sbv = (const char *)frag + 2 * (CHUNK_U4 * 16);   // chunk 2; every step leaves it at the next chunk
         const uint16_t *xs = emb + nxt_off[0];                        // next batch's row of pair c = 0 (steps 0..7)
-#define STEP_COMMON(i) [wcs] "s"(wsv[(i) % NBUF]), [lb] "s"(lbv[((i) + 2) % NBUF]), [vo] "v"(tid16)
+#define STEP_COMMON(i) \
+    [wcs] "s"(wsv[(i) % NBUF]), [wcsn] "s"(wsv[((i) + 1) % NBUF]), [lb] "s"(lbv[((i) + 2) % NBUF]), [vo] "v"(tid16)
 #define STEP_LOADS [up0] "v"(up[0]), [up1] "v"(up[1]), [xs] "v"(xs)
         // odd step: layer 1 into set B, layer 2 over the hidden units of set A; fetches into set A
 #define STEP_ODD(i)                                                                                   \
