@@ -157,6 +157,35 @@ int ann_search_ragged(const ann_graph *g, const ann_mlp *m, const void *queries_
                       void *stream);
 
 /*
+ * Search down a hierarchy of nested graphs (Sec. 3.2: the search runs layer by layer through
+ * the HNSW structure, the items selected in one layer being the seeds of the next; the outer
+ * loop of Algorithm 1).
+ *   graphs    : host array of n_layers handles, coarsest first, finest (base) last.  Layer l
+ *               holds the items 0 .. N_l - 1 of ONE embedding table (the same emb_dev, d and
+ *               dtype in every handle, N_0 <= N_1 <= ...), so an id means the same item in
+ *               every layer that has it
+ *   entry_dev : [Q][E] seeds of the coarsest layer (ids >= N_0 are ignored there)
+ *   W_l, L_l  : host arrays [n_layers]: expansion width and eligible ranks per layer
+ *   K_l       : host array [n_layers]: results taken from layer l; K_l[l] of them seed layer
+ *               l + 1 (all of them, in rank order), K_l[n_layers - 1] = k are the output
+ *   max_iters : rounds per query and layer, 0 = until converged
+ * Each layer is one ann_search with the previous layer's result list as entry points; nothing
+ * else is carried over (a finer layer scores its seeds again: the visited set is per layer).
+ * out_ids_dev [Q][k], out_scores_dev [Q][k] as for ann_search.  Counters read by
+ * ann_search_stats are summed over the layers (max_query_iters: the maximum).
+ * Workspace: ann_search_layers_workspace_bytes with the same arguments; 0 on invalid ones.
+ */
+size_t ann_search_layers_workspace_bytes(const ann_graph *const *graphs, int32_t n_layers,
+                                         const ann_mlp *m, int32_t Q, int32_t E,
+                                         const int32_t *W_l, const int32_t *L_l,
+                                         const int32_t *K_l, int32_t max_iters);
+int ann_search_layers(const ann_graph *const *graphs, int32_t n_layers, const ann_mlp *m,
+                      const void *queries_dev, int32_t Q, const int32_t *entry_dev, int32_t E,
+                      const int32_t *W_l, const int32_t *L_l, const int32_t *K_l,
+                      int32_t max_iters, void *workspace_dev, size_t workspace_bytes,
+                      int32_t *out_ids_dev, float *out_scores_dev, void *stream);
+
+/*
  * Relevance (Eq. 5-8) of an explicit list of M pairs: out_dev[r] = relevance(user q_idx[r],
  * item item[r]).  q_idx_dev, item_dev: [M] int32; out_dev: [M] fp32.  Pairs whose indices
  * are out of range get NaN.  Uses the same kernels as the search.  `tile_rows` (0 = default)

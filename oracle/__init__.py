@@ -151,6 +151,31 @@ def search(emb: np.ndarray, adj: np.ndarray, users: np.ndarray, mlp: Mlp, entrie
     return out
 
 
+def search_layers(emb: np.ndarray, adjs, users: np.ndarray, mlp: Mlp, entries: np.ndarray,
+                  W_l, L_l, K_l, max_iters=0, act_round: int = 0, n_threads: int = 1,
+                  trace: bool = False) -> Dict:
+    """Layer-by-layer search (Sec. 3.2; the outer loop over HNSW layers of Algorithm 1): adjs[l]
+    is the graph of layer l over the items 0 .. len(adjs[l]) - 1, coarsest layer first; the
+    K_l[l] items a layer returns, in rank order, are the seeds of the next layer, which starts
+    from an empty candidate list and an empty visited set.  Returns the last layer's result
+    and, with trace=True, `layers`: the per-layer results (ids, scores, n_scored, ...)."""
+    assert len(adjs) == len(W_l) == len(L_l) == len(K_l) >= 1
+    seeds = np.ascontiguousarray(entries, dtype=np.int32)
+    layers = []
+    for adj, W, L, K in zip(adjs, W_l, L_l, K_l):
+        n = adj.shape[0]
+        res = search(emb[:n], adj, users, mlp, seeds, W, L, int(K), max_iters=max_iters,
+                     act_round=act_round, n_threads=n_threads, trace=trace)
+        layers.append(res)
+        seeds = res["ids"]      # padding (-1) is an absent seed for the next layer
+    out = dict(layers[-1])
+    if trace:
+        out["layers"] = layers
+        out["n_scored"] = sum(r["n_scored"] for r in layers)
+        out["n_expanded"] = sum(r["n_expanded"] for r in layers)
+    return out
+
+
 def brute_force(emb: np.ndarray, users: np.ndarray, mlp: Mlp, k: int, act_round: int = 0,
                 n_threads: int = 1) -> Dict:
     lib = _load()

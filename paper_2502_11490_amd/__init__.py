@@ -22,6 +22,8 @@ from .binding import (  # noqa: F401
     ann_profile_read,
     ann_score_pairs,
     ann_search,
+    ann_search_layers,
+    ann_search_layers_workspace_bytes,
     ann_search_ragged,
     ann_search_stats,
     ann_search_workspace_bytes,

@@ -19,7 +19,8 @@ _lib = None
 
 EXPORTS = [
     "ann_graph_load", "ann_graph_free", "ann_mlp_load", "ann_mlp_free", "ann_mlp_uses_mfma",
-    "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_score_pairs",
+    "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
+    "ann_search_layers", "ann_score_pairs",
     "ann_search_stats", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
@@ -69,6 +70,12 @@ def load_library():
     lib.ann_search.restype = ctypes.c_int
     lib.ann_search_ragged.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
     lib.ann_search_ragged.restype = ctypes.c_int
+    pi32 = ctypes.POINTER(i32)
+    lib.ann_search_layers_workspace_bytes.argtypes = [ctypes.POINTER(vp), i32, vp, i32, i32, pi32, pi32, pi32, i32]
+    lib.ann_search_layers_workspace_bytes.restype = sz
+    lib.ann_search_layers.argtypes = [ctypes.POINTER(vp), i32, vp, vp, i32, vp, i32, pi32, pi32, pi32, i32, vp, sz,
+                                      vp, vp, vp]
+    lib.ann_search_layers.restype = ctypes.c_int
     lib.ann_score_pairs.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, i32, vp]
     lib.ann_score_pairs.restype = ctypes.c_int
     lib.ann_search_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
@@ -243,6 +250,45 @@ def ann_search_ragged(g: Graph, m: Mlp, queries, entries, W_q, L_q, iters_q, W_m
                                _dev_ptr(L_q, "L_q", torch.int32), _dev_ptr(iters_q, "iters_q", torch.int32), W_max,
                                L_max, k, max_iters_max, _dev_ptr(workspace, "workspace", torch.uint8),
                                workspace.numel(), _dev_ptr(out_ids, "out_ids", torch.int32),
+                               _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
+    _check(rc)
+    return out_ids, out_scores
+
+
+def _layer_args(graphs: Sequence[Graph], W_l, L_l, K_l):
+    n = len(graphs)
+    if not (len(W_l) == len(L_l) == len(K_l) == n):
+        raise ValueError("W_l, L_l, K_l need one entry per layer")
+    handles = (ctypes.c_void_p * n)(*[g.handle for g in graphs])
+    arr = lambda v: (ctypes.c_int32 * n)(*[int(x) for x in v])
+    return n, handles, arr(W_l), arr(L_l), arr(K_l)
+
+
+def ann_search_layers_workspace_bytes(graphs: Sequence[Graph], m: Mlp, Q: int, E: int, W_l, L_l, K_l,
+                                      max_iters: int = 0) -> int:
+    n, handles, W, L, K = _layer_args(graphs, W_l, L_l, K_l)
+    nbytes = load_library().ann_search_layers_workspace_bytes(handles, n, m.handle, Q, E, W, L, K, max_iters)
+    if nbytes == 0:
+        raise AnnError(-1, ann_last_error())
+    return nbytes
+
+
+def ann_search_layers(graphs: Sequence[Graph], m: Mlp, queries: torch.Tensor, entries: torch.Tensor, W_l, L_l, K_l,
+                      max_iters: int = 0, workspace: Optional[torch.Tensor] = None, out_ids=None, out_scores=None,
+                      stream=None):
+    """Layer-by-layer search, coarsest graph first; K_l[-1] results per query.  Returns (ids, scores)."""
+    lib = load_library()
+    Q, E = entries.shape
+    n, handles, W, L, K = _layer_args(graphs, W_l, L_l, K_l)
+    if workspace is None:
+        workspace = torch.empty(ann_search_layers_workspace_bytes(graphs, m, Q, E, W_l, L_l, K_l, max_iters),
+                                dtype=torch.uint8, device=queries.device)
+    if out_ids is None:
+        out_ids, out_scores = _alloc_out(Q, int(K_l[-1]), queries.device)
+    rc = lib.ann_search_layers(handles, n, m.handle, _dev_ptr(queries, "queries"), Q,
+                               _dev_ptr(entries, "entries", torch.int32), E, W, L, K, max_iters,
+                               _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+                               _dev_ptr(out_ids, "out_ids", torch.int32),
                                _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
     _check(rc)
     return out_ids, out_scores

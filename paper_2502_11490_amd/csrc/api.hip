@@ -477,6 +477,107 @@ int ann_search_ragged(const ann_graph *g, const ann_mlp *m, const void *queries_
                          max_iters_max, workspace_dev, workspace_bytes, out_ids_dev, out_scores_dev, stream);
 }
 
+// Workspace of a layered search: the largest per-layer workspace first (so that the counters sit
+// where ann_search_stats looks for them), then two id buffers and one score buffer that carry
+// a layer's results to the next.
+struct LayerPlan {
+    size_t search_bytes, carry_off, carry_ids_bytes, total;
+    int32_t k_carry_max;
+};
+
+static bool make_layer_plan(const ann_graph *const *graphs, int32_t n_layers, const ann_mlp *m, int32_t Q, int32_t E,
+                            const int32_t *W_l, const int32_t *L_l, const int32_t *K_l, int32_t max_iters,
+                            LayerPlan *lp) {
+    if (!graphs || n_layers < 1 || n_layers > 16 || !W_l || !L_l || !K_l) {
+        set_error("graphs, W_l, L_l, K_l must not be null and 1 <= n_layers <= 16");
+        return false;
+    }
+    lp->search_bytes = 0;
+    lp->k_carry_max = 1;
+    for (int l = 0; l < n_layers; ++l) {
+        const ann_graph *g = graphs[l];
+        if (!g) {
+            set_error("graphs[%d] is null", l);
+            return false;
+        }
+        const ann_graph *base = graphs[n_layers - 1];
+        if (g->emb != base->emb || g->d != base->d || g->dtype != base->dtype) {
+            set_error("layer %d does not share the embedding table of the base layer", l);
+            return false;
+        }
+        if (l > 0 && g->N < graphs[l - 1]->N) {
+            set_error("layer %d holds fewer items than layer %d: layers must be nested, coarsest first", l, l - 1);
+            return false;
+        }
+        Plan p;
+        const int32_t seeds = l == 0 ? E : K_l[l - 1];
+        if (!make_plan(g, m, Q, seeds, W_l[l], L_l[l], K_l[l], max_iters, &p)) return false;
+        if (p.total > lp->search_bytes) lp->search_bytes = p.total;
+        if (l + 1 < n_layers && K_l[l] > lp->k_carry_max) lp->k_carry_max = K_l[l];
+    }
+    lp->carry_off = align256(lp->search_bytes);
+    lp->carry_ids_bytes = align256((size_t)(Q > 0 ? Q : 1) * lp->k_carry_max * 4);
+    lp->total = lp->carry_off + 3 * lp->carry_ids_bytes;
+    return true;
+}
+
+size_t ann_search_layers_workspace_bytes(const ann_graph *const *graphs, int32_t n_layers, const ann_mlp *m,
+                                         int32_t Q, int32_t E, const int32_t *W_l, const int32_t *L_l,
+                                         const int32_t *K_l, int32_t max_iters) {
+    LayerPlan lp;
+    if (!make_layer_plan(graphs, n_layers, m, Q, E, W_l, L_l, K_l, max_iters, &lp)) return 0;
+    return lp.total;
+}
+
+int ann_search_layers(const ann_graph *const *graphs, int32_t n_layers, const ann_mlp *m, const void *queries_dev,
+                      int32_t Q, const int32_t *entry_dev, int32_t E, const int32_t *W_l, const int32_t *L_l,
+                      const int32_t *K_l, int32_t max_iters, void *workspace_dev, size_t workspace_bytes,
+                      int32_t *out_ids_dev, float *out_scores_dev, void *stream) {
+    LayerPlan lp;
+    if (!make_layer_plan(graphs, n_layers, m, Q, E, W_l, L_l, K_l, max_iters, &lp)) return ANN_EINVAL;
+    if (Q > 0 && (!queries_dev || !entry_dev || !out_ids_dev || !out_scores_dev)) {
+        set_error("queries_dev, entry_dev, out_ids_dev and out_scores_dev must not be null");
+        return ANN_EINVAL;
+    }
+    if (Q > 0 && (!workspace_dev || ((uintptr_t)workspace_dev & 255))) {
+        set_error("workspace_dev must be a 256-byte aligned device pointer");
+        return ANN_EINVAL;
+    }
+    if (workspace_bytes < lp.total) {
+        set_error("workspace holds %zu bytes, %zu needed", workspace_bytes, lp.total);
+        return ANN_EWORKSPACE;
+    }
+    char *ws = (char *)workspace_dev;
+    int32_t *carry[2] = {(int32_t *)(ws + lp.carry_off), (int32_t *)(ws + lp.carry_off + lp.carry_ids_bytes)};
+    float *carry_scores = (float *)(ws + lp.carry_off + 2 * lp.carry_ids_bytes);
+    int worst = ANN_OK;
+    for (int l = 0; l < n_layers; ++l) {
+        const bool last = l + 1 == n_layers;
+        SearchArgs a;
+        const int32_t seeds = l == 0 ? E : K_l[l - 1];
+        if (!make_plan(graphs[l], m, Q, seeds, W_l[l], L_l[l], K_l[l], max_iters, &a.plan)) return ANN_EINVAL;
+        a.g = graphs[l];
+        a.m = m;
+        a.queries = queries_dev;
+        a.entries = l == 0 ? entry_dev : carry[(l - 1) & 1];
+        a.W_q = a.L_q = a.cap_q = nullptr;
+        a.W = W_l[l];
+        a.L = L_l[l];
+        a.cap = max_iters;
+        a.ws = ws;
+        a.out_ids = last ? out_ids_dev : carry[l & 1];
+        a.out_scores = last ? out_scores_dev : carry_scores;
+        a.stream = (hipStream_t)stream;
+        a.keep_stats = l > 0;
+        int rc = run_search(a);
+        if (rc == ANN_EWORKSPACE)
+            worst = rc;  // a visited table filled up in this layer: the search goes on with what it found
+        else if (rc != ANN_OK)
+            return rc;
+    }
+    return worst;
+}
+
 int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int64_t M,
                     const int32_t *q_idx_dev, const int32_t *item_dev, float *out_dev, int32_t tile_rows,
                     void *stream) {

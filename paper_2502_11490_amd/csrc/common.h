@@ -106,6 +106,7 @@ struct SearchArgs {
     int32_t *out_ids;
     float *out_scores;
     hipStream_t stream;
+    bool keep_stats = false;  // counters continue from an earlier search on this workspace
 };
 
 // search_kernels.hip

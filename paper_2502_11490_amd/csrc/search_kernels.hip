@@ -219,8 +219,8 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
 
 // Counters and control block start at zero (a kernel, not a memset, so that a caller may
 // capture the launch sequence into a HIP graph).
-__global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q) {
-    if (threadIdx.x < 16) stats[threadIdx.x] = (threadIdx.x == 4) ? Q : 0;
+__global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q, int keep_stats) {
+    if (threadIdx.x < 16 && !keep_stats) stats[threadIdx.x] = (threadIdx.x == 4) ? Q : 0;
     if (threadIdx.x < 16) ((int32_t *)ctrl)[threadIdx.x] = 0;
 }
 
@@ -550,7 +550,8 @@ int launch_init(const SearchArgs &a) {
     while (dd_n < 2 * p.E) dd_n <<= 1;
     size_t smem = (size_t)((p.E + 3) & ~3) * 4 + (size_t)dd_n * 16 + (WAVES + 1) * 4;
     int64_t *stats = (int64_t *)(a.ws + p.off_stats);
-    hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, a.stream, stats, (Ctrl *)(a.ws + p.off_ctrl), p.Q);
+    hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, a.stream, stats, (Ctrl *)(a.ws + p.off_ctrl), p.Q,
+                       a.keep_stats ? 1 : 0);
     hipLaunchKernelGGL(init_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.entries, p.E, a.g->N,
                        (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), p.hash_cap,
                        (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q,

@@ -275,3 +275,91 @@ def test_search_bf16_recall_matches_oracle(preset, flags):
                          n_threads=8)
     frac = same_list_fraction(ids, kern["ids"])
     print(f"{preset}: recall gpu {r_gpu:.4f} oracle {r_ref:.4f}; identical lists vs kernel-precision oracle {frac:.3f}")
+
+
+# ----------------------------------------------------------------------------- layer-by-layer search
+def _open_layers(wl, layers, flags_mlp=0):
+    """One graph handle per layer over the same embedding tensor; keeps the tensors alive."""
+    g_base, m, dev = open_handles(wl, flags_mlp=flags_mlp)
+    adjs = [a.to("cuda").contiguous() for a in layers["adjs"][:-1]]
+    graphs = [ann.ann_graph_load(a, dev["emb"][: a.shape[0]], ann.ANN_VALIDATE) for a in adjs] + [g_base]
+    return graphs, m, dev, layers["entries"].to("cuda").contiguous()
+
+
+@pytest.mark.parametrize("W_l,L_l,K_l,cap", [([2, 2, 2], [8, 16, 32], [4, 6, 10], 0), ([1, 4, 3], [4, 20, 12], [8, 3, 40], 0),
+                                             ([4, 4, 4], [16, 16, 16], [5, 5, 20], 3)])
+def test_layered_search_fp32_matches_oracle(W_l, L_l, K_l, cap):
+    from workloads import make_layers
+    cfg = replace(scaled(PRESETS["C1"], 6000, n_clusters=8, Q=33), E=3)
+    wl = _with_biases(make_workload(cfg, seed=5), cfg, 15)
+    layers = make_layers(wl, 3, growth=8)
+    assert len(layers["sizes"]) == 3
+    graphs, m, dev, entries = _open_layers(wl, layers)
+    nbytes = ann.ann_search_layers_workspace_bytes(graphs, m, cfg.Q, cfg.E, W_l, L_l, K_l, cap)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ids, sc = ann.ann_search_layers(graphs, m, dev["users"], entries, W_l, L_l, K_l, cap, workspace=ws)
+    h = to_host(wl)
+    ref = oracle.search_layers(h["emb"], [a.cpu().numpy() for a in layers["adjs"]], h["users"], oracle_mlp(h),
+                               layers["entries"].cpu().numpy(), W_l, L_l, K_l, cap, n_threads=8, trace=True)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    assert same_list_fraction(ids, ref["ids"]) >= 0.99
+    same = ids == ref["ids"]
+    np.testing.assert_allclose(sc[same], ref["scores"][same], rtol=1e-5)
+    st = ann.ann_search_stats(ws)
+    if same_list_fraction(ids, ref["ids"]) == 1.0:  # counters are summed over the layers
+        assert st.pairs_scored == int(ref["n_scored"].sum())
+        assert st.nodes_expanded == int(ref["n_expanded"].sum())
+    assert st.visited_overflow == 0 and st.queries == cfg.Q
+
+
+def test_layered_search_with_one_layer_is_the_flat_search():
+    cfg = replace(scaled(PRESETS["C1"], 3000, n_clusters=8, Q=20), E=2)
+    wl = make_workload(cfg, seed=6)
+    g, m, dev = open_handles(wl)
+    a = ann.ann_search(g, m, dev["users"], dev["entries"], 3, 20, 15, 0)
+    b = ann.ann_search_layers([g], m, dev["users"], dev["entries"], [3], [20], [15], 0)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_layered_search_bf16_recall_matches_oracle():
+    from workloads import make_layers
+    base = PRESETS["C3"]
+    cfg = replace(scaled(base, 60000, Q=64), E=base.E)
+    wl = make_workload(cfg)
+    layers = make_layers(wl, 3, growth=17)
+    graphs, m, dev, entries = _open_layers(wl, layers)
+    assert ann.ann_mlp_uses_mfma(m)
+    W_l, L_l, K_l, k = [8, 8, 8], [32, 32, 64], [16, 16, 50], 50
+    ids, sc = ann.ann_search_layers(graphs, m, dev["users"], entries, W_l, L_l, K_l, 0)
+    h = to_host(wl)
+    mlp = oracle_mlp(h)
+    adjs = [a.cpu().numpy() for a in layers["adjs"]]
+    ref = oracle.search_layers(h["emb"], adjs, h["users"], mlp, layers["entries"].cpu().numpy(), W_l, L_l, K_l, 0,
+                               n_threads=8)
+    bf = oracle.brute_force(h["emb"], h["users"][:24], mlp, k, n_threads=8)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    r_gpu = oracle.recall_at(ids[:24], bf["ids"], k)
+    r_ref = oracle.recall_at(ref["ids"][:24], bf["ids"], k)
+    assert abs(r_gpu - r_ref) <= 0.01 + 1e-9, (r_gpu, r_ref)
+    qq = np.repeat(np.arange(cfg.Q), k).astype(np.int32)
+    valid = ids.ravel() >= 0
+    exact = oracle.score_pairs(h["emb"], h["users"], mlp, qq[valid], ids.ravel()[valid], n_threads=8)
+    assert np.max(np.abs(sc.ravel()[valid] - exact)) <= 1e-2
+    kern = oracle.search_layers(h["emb"], adjs, h["users"], mlp, layers["entries"].cpu().numpy(), W_l, L_l, K_l, 0,
+                                act_round=1, n_threads=8)
+    print(f"layered C3-shaped: recall gpu {r_gpu:.4f} oracle {r_ref:.4f}; identical lists vs kernel-precision "
+          f"oracle {same_list_fraction(ids, kern['ids']):.3f}")
+
+
+def test_layered_search_argument_errors():
+    cfg = replace(scaled(PRESETS["C1"], 2000, n_clusters=4, Q=4), E=2)
+    wl = make_workload(cfg, seed=8)
+    g, m, dev = open_handles(wl)
+    other = ann.ann_graph_load(dev["adj"], dev["emb"].clone())  # same shape, another table
+    with pytest.raises(ann.AnnError):
+        ann.ann_search_layers([other, g], m, dev["users"], dev["entries"], [2, 2], [8, 8], [4, 4], 0)
+    small = ann.ann_graph_load(dev["adj"][:500] % 500, dev["emb"][:500])
+    with pytest.raises(ann.AnnError):   # finest layer must come last
+        ann.ann_search_layers([g, small], m, dev["users"], dev["entries"], [2, 2], [8, 8], [4, 4], 0)
+    with pytest.raises(ValueError):
+        ann.ann_search_layers([small, g], m, dev["users"], dev["entries"], [2], [8, 8], [4, 4], 0)

@@ -76,6 +76,89 @@ def test_ring_trajectory_by_hand(case):
     assert np.array_equal(s, r["scores"][0])
 
 
+# ----------------------------------------------------------------------------- layer-by-layer search
+def _ring(n, R):
+    return ((np.arange(n)[:, None] + np.arange(1, R + 1)[None, :]) % n).astype(np.int32)
+
+
+@pytest.mark.parametrize("case", json.load(open(os.path.join(GOLD, "layered_trajectories.json")))["cases"],
+                         ids=lambda c: c["name"])
+def test_layered_trajectory_by_hand(case):
+    N_l, R = case["N_l"], case["R"]
+    _, emb, mlp = _monotone_problem(N_l[-1], R, case["monotone"])
+    adjs = [_ring(n, R) for n in N_l]
+    users = np.zeros((1, 2), np.float32)
+    entries = np.asarray([case["seed"]], np.int32)
+    # the oracle's layer loop, with the per-layer traces taken from separate calls so that the
+    # visited order can be checked too
+    r = oracle.search_layers(emb, adjs, users, mlp, entries, case["W_l"], case["L_l"], case["K_l"],
+                             case["max_iters"], trace=True)
+    seeds = entries
+    for l, n in enumerate(N_l):
+        lay = r["layers"][l]
+        assert lay["ids"][0].tolist() == case["expected_ids_per_layer"][l]
+        assert int(lay["n_scored"][0]) == case["n_scored_per_layer"][l]
+        assert int(lay["n_expanded"][0]) == case["n_expanded_per_layer"][l]
+        assert int(lay["n_iters"][0]) == case["n_iters_per_layer"][l]
+        one = oracle.search(emb[:n], adjs[l], users, mlp, seeds, case["W_l"][l], case["L_l"][l], case["K_l"][l],
+                            case["max_iters"], trace=True, visited_cap=64)
+        vis = case["expected_visited_per_layer"][l]
+        want = list(range(*vis["range"])) if "range" in vis else vis["list"]
+        assert [v for v in one["visited"][0].tolist() if v >= 0] == want
+        seeds = np.asarray([case["expected_ids_per_layer"][l]], np.int32)
+    assert r["ids"][0].tolist() == case["expected_ids_per_layer"][-1]
+    assert int(r["n_scored"][0]) == sum(case["n_scored_per_layer"])
+
+
+def _nested_layers(wl, sizes, R, seed):
+    """Random nested graphs over the first sizes[l] items (valid ids only, no self loops)."""
+    rng = np.random.default_rng(seed)
+    adjs = []
+    for n in sizes:
+        a = rng.integers(0, n - 1, size=(n, R))
+        a = a + (a >= np.arange(n)[:, None])     # skip the node itself
+        adjs.append(a.astype(np.int32))
+    return adjs
+
+
+def test_one_layer_is_the_flat_search():
+    wl, mlp = _tiny(21)
+    a = oracle.search(wl["emb"], wl["adj"], wl["users"], mlp, wl["entries"], 2, 12, 9)
+    b = oracle.search_layers(wl["emb"], [wl["adj"]], wl["users"], mlp, wl["entries"], [2], [12], [9])
+    assert np.array_equal(a["ids"], b["ids"]) and np.array_equal(a["scores"], b["scores"])
+
+
+def test_layers_chain_through_their_result_lists():
+    # an independent statement of the outer loop: best-first search (written separately below)
+    # per layer with W = 1, the k best of a layer being the seeds of the next
+    wl, mlp = _tiny(22, N=400, Q=4, E=1)
+    sizes = [40, 150, 400]
+    adjs = _nested_layers(wl, sizes, 5, 7)
+    ef, K = [6, 8, 10], [3, 4, 7]
+    entries = (wl["entries"] % sizes[0]).astype(np.int32)
+    got = oracle.search_layers(wl["emb"], adjs, wl["users"], mlp, entries, [1, 1, 1], ef, K)
+    for q in range(4):
+        s = oracle.score_pairs(wl["emb"], wl["users"], mlp, np.full(400, q), np.arange(400)).astype(np.float64)
+        seeds = [int(entries[q, 0])]
+        for l, n in enumerate(sizes):
+            seeds = _best_first_multi(s[:n], adjs[l], seeds, ef[l], K[l])
+        assert got["ids"][q].tolist() == seeds + [-1] * (K[-1] - len(seeds))
+
+
+def test_complete_layers_equal_brute_force():
+    wl, mlp = _tiny(23, N=120, Q=5, E=2)
+    sizes = [15, 50, 120]
+    adjs = []
+    for n in sizes:
+        a = np.arange(n - 1)[None, :] + (np.arange(n - 1)[None, :] >= np.arange(n)[:, None])
+        adjs.append(a.astype(np.int32))
+    entries = (wl["entries"] % sizes[0]).astype(np.int32)
+    got = oracle.search_layers(wl["emb"], adjs, wl["users"], mlp, entries, [2, 3, 2], [4, 6, 5], [5, 8, 11])
+    ids, sc = _rank_all(wl["emb"], wl["users"], mlp, 11)
+    assert np.array_equal(got["ids"], ids)
+    assert np.array_equal(got["scores"], sc)
+
+
 # ----------------------------------------------------------------------------- brute force
 def test_brute_force_is_the_exhaustive_ranking():
     wl, mlp = _tiny(11)
@@ -211,6 +294,36 @@ def _best_first(scores, adj, seed, ef, k):
                     heapq.heappop(res)
     out = sorted(res, key=lambda t: (-t[0], -t[1]))[:k]
     return [-i for _, i in out], visited
+
+
+def _best_first_multi(scores, adj, seeds, ef, k):
+    """The same textbook search started from several entry points (all of them in the candidate
+    and result heaps from the start), as a hierarchical index runs it on every layer."""
+    visited, cand, res = set(), [], []
+    for s in seeds:
+        if s in visited:
+            continue
+        visited.add(s)
+        heapq.heappush(cand, (-scores[s], s))
+        heapq.heappush(res, (scores[s], -s))
+        if len(res) > ef:
+            heapq.heappop(res)
+    while cand:
+        neg, c = heapq.heappop(cand)
+        if len(res) >= ef and (-neg, -c) < res[0]:
+            break
+        for v in adj[c]:
+            v = int(v)
+            if v in visited:
+                continue
+            visited.add(v)
+            if len(res) < ef or (scores[v], -v) > res[0]:
+                heapq.heappush(cand, (-scores[v], v))
+                heapq.heappush(res, (scores[v], -v))
+                if len(res) > ef:
+                    heapq.heappop(res)
+    out = sorted(res, key=lambda t: (-t[0], -t[1]))[:k]
+    return [-i for _, i in out]
 
 
 def test_single_walker_is_classic_best_first_search():

@@ -9,6 +9,8 @@ from .gen import (  # noqa: F401
     SEED_BASE,
     Config,
     PRESETS,
+    layer_sizes,
+    make_layers,
     make_workload,
     random_mlp,
     to_host,

@@ -307,6 +307,70 @@ def make_workload(cfg: Config, device="cpu", seed: int = SEED_BASE, with_graph: 
     return out
 
 
+def _knn_global(x: torch.Tensor, K: int, budget: int = 1 << 27) -> torch.Tensor:
+    """x: [n,d] fp32.  [n,K] int64 indices of the K L2-nearest other rows, by exhaustive distances."""
+    n = x.shape[0]
+    dev = x.device
+    sq = (x * x).sum(1)
+    out = torch.empty((n, K), dtype=torch.int64, device=dev)
+    rows = max(1, budget // n)
+    for r0 in range(0, n, rows):
+        r1 = min(n, r0 + rows)
+        dist = sq[r0:r1, None] + sq[None, :] - 2.0 * (x[r0:r1] @ x.T)
+        ar = torch.arange(r0, r1, device=dev)
+        dist[ar - r0, ar] = float("inf")
+        out[r0:r1] = torch.topk(dist, K, dim=1, largest=False).indices
+    return out
+
+
+def layer_sizes(N: int, n_layers: int, growth: int, R: int) -> List[int]:
+    """Item counts of the nested layers, coarsest first: each layer `growth` times the one above
+    (Table 5 of the paper: four layers, about 17x per layer); layers too small to give every
+    node R distinct neighbours are left out."""
+    sizes = [-(-N // growth ** (n_layers - 1 - l)) for l in range(n_layers)]
+    return [n for n in sizes if n > R]
+
+
+def make_layers(wl: Dict, n_layers: int = 4, growth: int = 17) -> Dict:
+    """Nested graphs over the workload's items for the layer-by-layer search: layer l holds the
+    items with ids 0 .. sizes[l] - 1 (ids are a random permutation, so this is a uniform sample,
+    as the level draw of an HNSW index gives), the base layer is the workload's own graph.  An
+    upper layer has the same recipe as the base layer, R/2 L2-nearest neighbours + R/2 uniform
+    random ones without repeats or self loops; where a layer is too sparse for in-cluster
+    neighbours (fewer than R + 2 items per cluster on average) the nearest neighbours are taken
+    among all items of the layer.  Returns {"sizes", "adjs" (int32, coarsest first), "entries"
+    [Q,E] int32 distinct ids of the coarsest layer}."""
+    cfg = wl["cfg"]
+    seed = wl["seed"]
+    dev = wl["emb"].device
+    R, K = cfg.R, cfg.R // 2
+    sizes = layer_sizes(cfg.N, n_layers, growth, R)
+    adjs = []
+    for l, n in enumerate(sizes[:-1]):
+        x = wl["emb"][:n].to(torch.float32)
+        adj = torch.full((n, R), -1, dtype=torch.int64, device=dev)
+        if n >= cfg.n_clusters * (R + 2):
+            cl = wl["cluster"][:n].to(torch.int64)
+            order = torch.argsort(cl, stable=True)  # position -> id
+            counts = torch.bincount(cl, minlength=cfg.n_clusters)
+            starts = torch.cumsum(counts, 0) - counts
+            pos = _knn_in_clusters(x[order], starts, counts, K)
+            ids = torch.where(pos >= 0, order[pos.clamp(min=0)], pos)
+            adj[order, :K] = ids
+        else:
+            adj[:, :K] = _knn_global(x, K)
+        _fill_random_edges(adj, _gen(dev, seed + 20 + l))
+        adjs.append(adj.to(torch.int32).contiguous())
+    adjs.append(wl["adj"])
+    g_e = _gen(dev, seed + 19)
+    E = min(cfg.E, sizes[0])
+    if sizes[0] <= 8192:  # distinct ids per query: the E smallest of sizes[0] random keys
+        ent = torch.rand(cfg.Q, sizes[0], generator=g_e, device=dev).topk(E, dim=1, largest=False).indices
+    else:                 # repeats are possible and harmless (a repeated seed is ignored)
+        ent = torch.randint(0, sizes[0], (cfg.Q, E), generator=g_e, device=dev)
+    return {"sizes": sizes, "adjs": adjs, "entries": ent.to(torch.int32).contiguous()}
+
+
 def _np(t: torch.Tensor) -> np.ndarray:
     t = t.detach().to("cpu").contiguous()
     if t.dtype == torch.bfloat16:
