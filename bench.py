@@ -106,6 +106,7 @@ def main() -> int:
     ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0 = pick for ~20 s)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--no-layers", action="store_true", help="skip the layer-by-layer search beside the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain 256 MiB copy kernel (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -213,6 +214,37 @@ def main() -> int:
     log(f"{ms_per_step:.3f} ms/step, {qps:.0f} queries/s, {scores_per_s:.3e} MLP scores/s, "
         f"{st.pairs_scored} pairs, {st.nodes_expanded} expansions, {st.max_query_iters} rounds")
 
+    # ---- the layer-by-layer search (nested graphs, 17x per layer) at the same base-layer L:
+    #      reported beside the headline, not part of the timed step ----
+    layered = None
+    if not ragged and not args.no_layers:
+        from workloads import make_layers
+        t3 = time.time()
+        ly = make_layers(wl, 4, 17)
+        if len(ly["sizes"]) > 1:
+            graphs = [ann.ann_graph_load(a, wl["emb"][: a.shape[0]]) for a in ly["adjs"][:-1]] + [g]
+            nl = len(graphs)
+            W_l, L_l, K_l = [W] * nl, [128] * (nl - 1) + [L_star], [64] * (nl - 1) + [k]
+            wsl = torch.empty(ann.ann_search_layers_workspace_bytes(graphs, m, Q, E, W_l, L_l, K_l, 0),
+                              dtype=torch.uint8, device="cuda:0")
+            run = lambda: ann.ann_search_layers(graphs, m, users, ly["entries"], W_l, L_l, K_l, 0, workspace=wsl)
+            run()
+            torch.cuda.synchronize()
+            t4 = time.perf_counter()
+            for _ in range(3):
+                ids_l, _ = run()
+            torch.cuda.synchronize()
+            ms_l = 1e3 * (time.perf_counter() - t4) / 3
+            stl = ann.ann_search_stats(wsl)
+            layered = {"layer_sizes": ly["sizes"], "W_l": W_l, "L_l": L_l, "K_l": K_l,
+                       "recall_at_100": round(recall_at(ids_l[sel].cpu(), truth.cpu(), kr), 4),
+                       "ms_per_search": round(ms_l, 3), "queries_per_s": round(Q / ms_l * 1e3, 1),
+                       "pairs_scored": int(stl.pairs_scored)}
+            log(f"layered search {ly['sizes']}: recall@{kr} = {layered['recall_at_100']}, {ms_l:.1f} ms per search "
+                f"(layers built in {time.time() - t3:.1f} s)")
+            del graphs, wsl
+        del ly
+
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 255)
         dst = torch.empty_like(src)
@@ -319,6 +351,7 @@ def main() -> int:
             "mlp_scores_per_s": round(scores_per_s, 1),
             "pairs_scored_per_step": int(st.pairs_scored), "nodes_expanded_per_step": int(st.nodes_expanded),
             "rounds": int(st.max_query_iters), "mfma_kernel": bool(mfma), "stages": stages,
+            "layered_search": layered,
         },
         "roofline": roofline,
         "cpu_baseline": cpu,

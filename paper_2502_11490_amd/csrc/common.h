@@ -39,7 +39,7 @@ struct ann_graph {
 };
 
 // Which fused kernel serves the metric.
-enum MlpKernel { MLP_ALU = 0, MLP_MFMA2 = 1 /* two hidden layers, bf16 */ };
+enum MlpKernel { MLP_ALU = 0, MLP_MFMA2 = 1 /* the bf16 MFMA kernels: one or two hidden layers */ };
 
 struct ann_mlp {
     int32_t n_layers;

@@ -258,20 +258,151 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
     }
 }
 
-struct MfmaShape {
-    int D, H1, H2;
-};
+// One hidden layer (the metric of the 10^8-item configuration, 128 -> 256 -> J): the same scheme
+// without the middle layer.  Per block of 32 hidden units: layer 1 from the user term, ReLU,
+// bf16, and at once the two head MFMAs that consume those units; nothing but 2 x 16 head
+// accumulators lives across blocks.  All weights (D/16 + 2 fragments per block) stay in LDS.
+// The kernel is bound by the item-row gather, not by the MFMAs (about 250 flop per gathered
+// byte, below the ridge of the chip), so its few registers and 48 KB of LDS are what matter:
+// three workgroups share a CU and hide each other's gather latency.
+// Fragment order: block nb: [s < D/16] W1_item as above; [D/16 + s2] lane (m,g):
+// W_head[m][nb*32 + 16*s2 + 8*(j/4) + 4g + j%4], rows >= J zero.
+template <int D, int H1, int CB>
+__global__ void __launch_bounds__(MF_BLOCK)
+mlp_mfma1_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__restrict__ upre,
+                 const uint4 *__restrict__ frag, const float *__restrict__ b_head, const float *__restrict__ head_w,
+                 int J, const int32_t *__restrict__ pair_q, const int32_t *__restrict__ pair_id,
+                 const int32_t *__restrict__ M_dev, int64_t M_max, int32_t Q, float *__restrict__ scores) {
+    constexpr int KS1 = D / 16, NB1 = H1 / 32;
+    constexpr int BLK_FR = KS1 + 2;
+    constexpr int RW = 32 * CB, TILE = RW * MF_WAVES;
+    extern __shared__ __align__(16) uint4 lds[];  // [NB1][BLK_FR][64]
+
+    int64_t M = (int64_t)*M_dev;
+    if (M > M_max) M = M_max;
+    const int64_t n_tiles = (M + TILE - 1) / TILE;
+    if ((int64_t)blockIdx.x >= n_tiles) return;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int g = lane >> 5, col = lane & 31;
+    for (int i = threadIdx.x; i < NB1 * BLK_FR * 64; i += MF_BLOCK) lds[i] = frag[i];
+    __syncthreads();
+
+    float hw[4], bh[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int j = 4 * g + i;
+        hw[i] = j < J ? head_w[j] : 0.f;
+        bh[i] = j < J ? b_head[j] : 0.f;
+    }
+
+#pragma unroll 1
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t row0 = tile * TILE + (int64_t)wave * RW;
+        bf16x8 xf[CB][KS1];
+        const float *up[CB];
+        bool bad[CB];
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            int64_t row = row0 + c * 32 + col;
+            row = row < M ? row : M - 1;  // rows past the end read the last pair and are not stored
+            int32_t v = pair_id[row], q = pair_q[row];
+            bad[c] = ((uint64_t)(int64_t)v >= (uint64_t)N) | ((uint32_t)q >= (uint32_t)Q);
+            if (bad[c]) v = 0, q = 0;
+            const bf16x8 *src = (const bf16x8 *)(emb + (size_t)v * D) + g;
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) xf[c][s] = src[2 * s];
+            up[c] = upre + (size_t)q * H1 + 4 * g;
+        }
+        static_assert(CB >= 2, "two accumulators must alternate");
+        f32x16 acc3[CB];
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc3[c][i] = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < NB1; ++nb) {
+            const uint4 *wc = lds + (size_t)nb * BLK_FR * 64;
+            f32x16 acc1[CB];
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+#pragma unroll
+                for (int t4 = 0; t4 < 4; ++t4) {
+                    f32x4 pv = *(const f32x4 *)(up[c] + nb * 32 + 8 * t4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc1[c][4 * t4 + e] = pv[e];
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) {
+                bf16x8 a = *(const bf16x8 *)(wc + s * 64 + lane);
+#pragma unroll
+                for (int c = 0; c < CB; ++c) mfma_vgpr(acc1[c], a, xf[c][s]);
+            }
+            mfma_drain(acc1[CB - 1], acc1[CB - 2]);
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                bf16x8 a = *(const bf16x8 *)(wc + (KS1 + s2) * 64 + lane);
+#pragma unroll
+                for (int c = 0; c < CB; ++c) mfma_vgpr(acc3[c], a, relu_pack(acc1[c], s2));
+            }
+        }
+        mfma_drain(acc3[CB - 1], acc3[CB - 2]);
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            float part = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) part = fmaf(hw[i], 1.0f / (1.0f + expf(-(acc3[c][i] + bh[i]))), part);
+            float other = __shfl_xor(part, 32);
+            int64_t row = row0 + c * 32 + col;
+            if (g == 0 && row < M) scores[row] = bad[c] ? __uint_as_float(0x7fc00000u) : part + other;
+        }
+    }
+}
+
 
 bool mfma_supported(const int32_t *dims, int32_t n_layers, int32_t d_user, int32_t dtype) {
-    if (dtype != ANN_BF16 || n_layers != 3) return false;
-    int D = dims[0] - d_user, H1 = dims[1], H2 = dims[2], J = dims[3];
-    if (J < 1 || J > MAX_HEADS || d_user < 1) return false;
+    if (dtype != ANN_BF16 || d_user < 1 || (n_layers != 2 && n_layers != 3)) return false;
+    const int D = dims[0] - d_user, H1 = dims[1], J = dims[n_layers];
+    if (J < 1 || J > MAX_HEADS) return false;
+    if (n_layers == 2) return D == 64 && H1 == 256;
+    const int H2 = dims[2];
     return (D == 128 && H1 == 512 && H2 == 256) || (D == 64 && H1 == 256 && H2 == 128);
 }
 
 static inline uint16_t w_at(const uint16_t *W, int n_in, int row, int colm) { return W[(size_t)row * n_in + colm]; }
 
+static int upload_fragments(ann_mlp *m, const std::vector<uint16_t> &buf, hipStream_t stream) {
+    m->frag_bytes = (int64_t)buf.size() * 2;
+    ANN_HIP_TRY(hipMalloc(&m->frag_dev, (size_t)m->frag_bytes));
+    ANN_HIP_TRY(hipMemcpyAsync(m->frag_dev, buf.data(), (size_t)m->frag_bytes, hipMemcpyHostToDevice, stream));
+    ANN_HIP_TRY(hipStreamSynchronize(stream));  // buf is freed by the caller
+    return ANN_OK;
+}
+
+static int build_fragments_one_hidden(ann_mlp *m, const void *const *W_host, hipStream_t stream) {
+    const int D = m->d_item, H1 = m->dims[1], J = m->J, du = m->d_user;
+    const int KS1 = D / 16, NB1 = H1 / 32, BLK_FR = KS1 + 2;
+    std::vector<uint16_t> buf((size_t)NB1 * BLK_FR * 512, 0);
+    const uint16_t *W1 = (const uint16_t *)W_host[0], *Wh = (const uint16_t *)W_host[1];
+    for (int nb = 0; nb < NB1; ++nb) {
+        uint16_t *blk = buf.data() + (size_t)nb * BLK_FR * 512;
+        for (int s = 0; s < KS1; ++s)
+            for (int l = 0; l < 64; ++l)
+                for (int j = 0; j < 8; ++j)
+                    blk[(size_t)s * 512 + l * 8 + j] = W1[(size_t)(nb * 32 + (l & 31)) * (du + D) + du + 16 * s + 8 * (l >> 5) + j];
+        for (int s2 = 0; s2 < 2; ++s2)
+            for (int l = 0; l < 64; ++l)
+                for (int j = 0; j < 8; ++j)
+                    if ((l & 31) < J)
+                        blk[(size_t)(KS1 + s2) * 512 + l * 8 + j] =
+                            Wh[(size_t)(l & 31) * H1 + nb * 32 + 16 * s2 + 8 * (j / 4) + 4 * (l >> 5) + j % 4];
+    }
+    return upload_fragments(m, buf, stream);
+}
+
 int build_mfma_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream) {
+    if (m->n_layers == 2) return build_fragments_one_hidden(m, W_host, stream);
     if (mfma_stream_supported(m->d_item, m->dims[1], m->dims[2])) return build_stream_fragments(m, W_host, stream);
     const int D = m->d_item, H1 = m->dims[1], H2 = m->dims[2], J = m->J, du = m->d_user;
     const int KS1 = D / 16, NB1 = H1 / 32, NB2 = H2 / 32;
@@ -346,6 +477,19 @@ int launch_mlp_mfma(const ann_graph *g, const ann_mlp *m, const float *upre, con
     (void)tile_rows;
     if (M_max <= 0) return ANN_OK;
     const int D = m->d_item, H1 = m->dims[1], H2 = m->dims[2];
+    if (m->n_layers == 2 && D == 64 && H1 == 256) {
+        constexpr int CB = 2, TILE = 32 * CB * MF_WAVES;
+        constexpr size_t smem = (size_t)(256 / 32) * (64 / 16 + 2) * 64 * 16;  // 48 KB: three workgroups per CU
+        auto fn = mlp_mfma1_kernel<64, 256, CB>;
+        ANN_HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        int64_t tiles = (M_max + TILE - 1) / TILE;
+        int grid = (int)(tiles < 3 * 256 ? tiles : 3 * 256);
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(MF_BLOCK), smem, stream, (const uint16_t *)g->emb, g->N, upre,
+                           (const uint4 *)m->frag_dev, m->b_dev + m->b_off[1], m->head_w_dev, m->J, pair_q, pair_id,
+                           M_dev, M_max, Q, scores);
+        ANN_HIP_TRY(hipGetLastError());
+        return ANN_OK;
+    }
     if (mfma_stream_supported(D, H1, H2))
         return launch_mlp_mfma_stream(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
     if (D == 64 && H1 == 256 && H2 == 128)
