@@ -25,11 +25,12 @@ constexpr int SCAN_BLOCK = 256;
 constexpr int SCAN_WAVES = SCAN_BLOCK / 64;
 
 // Phase timing of the round kernel for measurement builds (-DROUND_TIMING): thread 0 of every
-// workgroup adds the shader-clock ticks of each phase to counters 8..15 of the stats block.
+// 64th workgroup adds the shader-clock ticks of each phase to counters 8..15 of the stats block
+// (every workgroup doing so would serialise on those few addresses and distort what is measured).
 #ifdef ROUND_TIMING
 #define PHASE_MARK(k)                                                                          \
     do {                                                                                       \
-        if (threadIdx.x == 0) {                                                                \
+        if (threadIdx.x == 0 && (blockIdx.x & 63) == 0) {                                      \
             long long now_ = clock64();                                                        \
             atomicAdd((unsigned long long *)&stats[8 + (k)], (unsigned long long)(now_ - t_)); \
             t_ = now_;                                                                         \
