@@ -186,6 +186,31 @@ int ann_search_layers(const ann_graph *const *graphs, int32_t n_layers, const an
                       int32_t *out_ids_dev, float *out_scores_dev, void *stream);
 
 /*
+ * Continuous batching (Sec. 3.2, Q-HiPANNS and Algorithm 2: requests of different users arrive
+ * and finish at different times and are aggregated into common batches).  Q_total queries are
+ * served by `slots` search states: a query enters the first state that becomes free, in index
+ * order, and leaves it when it has converged (or reached max_iters rounds), so every scoring
+ * batch is filled by the queries that are running at that moment instead of thinning out while
+ * the slowest query of a fixed batch finishes.  The result of every query is the one ann_search
+ * gives for it (queries do not influence each other; only the grouping of pairs into scoring
+ * batches differs, and a pair's relevance does not depend on that).
+ *   queries_dev [Q_total][d_user], entry_dev [Q_total][E], out_ids_dev / out_scores_dev [Q_total][k]
+ *   slots     : >= 1; more slots than queries leaves the surplus idle
+ *   max_iters : rounds per query, 0 = until converged
+ * The call waits on `stream` every few rounds (it has to learn when the last query is done).
+ * Workspace: ann_search_stream_workspace_bytes with the same arguments (0 on invalid ones); its
+ * size grows with `slots`, plus 4 * first-hidden-width bytes per query.  ann_search_stats reads
+ * the counters of all Q_total queries.
+ */
+size_t ann_search_stream_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q_total,
+                                         int32_t slots, int32_t E, int32_t W, int32_t L, int32_t k,
+                                         int32_t max_iters);
+int ann_search_stream(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q_total,
+                      const int32_t *entry_dev, int32_t E, int32_t slots, int32_t W, int32_t L,
+                      int32_t k, int32_t max_iters, void *workspace_dev, size_t workspace_bytes,
+                      int32_t *out_ids_dev, float *out_scores_dev, void *stream);
+
+/*
  * Relevance (Eq. 5-8) of an explicit list of M pairs: out_dev[r] = relevance(user q_idx[r],
  * item item[r]).  q_idx_dev, item_dev: [M] int32; out_dev: [M] fp32.  Pairs whose indices
  * are out of range get NaN.  Uses the same kernels as the search.  `tile_rows` (0 = default)

@@ -20,7 +20,7 @@ _lib = None
 EXPORTS = [
     "ann_graph_load", "ann_graph_free", "ann_mlp_load", "ann_mlp_free", "ann_mlp_uses_mfma",
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
-    "ann_search_layers", "ann_score_pairs",
+    "ann_search_layers", "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs",
     "ann_search_stats", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
@@ -76,6 +76,10 @@ def load_library():
     lib.ann_search_layers.argtypes = [ctypes.POINTER(vp), i32, vp, vp, i32, vp, i32, pi32, pi32, pi32, i32, vp, sz,
                                       vp, vp, vp]
     lib.ann_search_layers.restype = ctypes.c_int
+    lib.ann_search_stream_workspace_bytes.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32]
+    lib.ann_search_stream_workspace_bytes.restype = sz
+    lib.ann_search_stream.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp, vp]
+    lib.ann_search_stream.restype = ctypes.c_int
     lib.ann_score_pairs.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, i32, vp]
     lib.ann_score_pairs.restype = ctypes.c_int
     lib.ann_search_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
@@ -250,6 +254,35 @@ def ann_search_ragged(g: Graph, m: Mlp, queries, entries, W_q, L_q, iters_q, W_m
                                _dev_ptr(L_q, "L_q", torch.int32), _dev_ptr(iters_q, "iters_q", torch.int32), W_max,
                                L_max, k, max_iters_max, _dev_ptr(workspace, "workspace", torch.uint8),
                                workspace.numel(), _dev_ptr(out_ids, "out_ids", torch.int32),
+                               _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
+    _check(rc)
+    return out_ids, out_scores
+
+
+def ann_search_stream_workspace_bytes(g: Graph, m: Mlp, Q_total: int, slots: int, E: int, W: int, L: int, k: int,
+                                      max_iters: int = 0) -> int:
+    nbytes = load_library().ann_search_stream_workspace_bytes(g.handle, m.handle, Q_total, slots, E, W, L, k, max_iters)
+    if nbytes == 0:
+        raise AnnError(-1, ann_last_error())
+    return nbytes
+
+
+def ann_search_stream(g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.Tensor, slots: int, W: int, L: int,
+                      k: int, max_iters: int = 0, workspace: Optional[torch.Tensor] = None, out_ids=None,
+                      out_scores=None, stream=None):
+    """All queries, `slots` of them in flight at a time; a finished query's slot goes to the next one.
+    Returns (ids [Q_total,k], scores [Q_total,k])."""
+    lib = load_library()
+    Q, E = entries.shape
+    if workspace is None:
+        workspace = torch.empty(ann_search_stream_workspace_bytes(g, m, Q, slots, E, W, L, k, max_iters),
+                                dtype=torch.uint8, device=queries.device)
+    if out_ids is None:
+        out_ids, out_scores = _alloc_out(Q, k, queries.device)
+    rc = lib.ann_search_stream(g.handle, m.handle, _dev_ptr(queries, "queries"), Q,
+                               _dev_ptr(entries, "entries", torch.int32), E, slots, W, L, k, max_iters,
+                               _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+                               _dev_ptr(out_ids, "out_ids", torch.int32),
                                _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
     _check(rc)
     return out_ids, out_scores

@@ -164,12 +164,15 @@ static int score_batch(const SearchArgs &a) {
     StageTimer timer(ANN_STAGE_SCORE, a.stream);
     const Plan &p = a.plan;
     const int32_t *M_dev = &((const Ctrl *)(a.ws + p.off_ctrl))->M;
+    // pair_q names user vectors: slots and queries coincide unless queries stream through the slots
+    const int32_t n_users = a.Q_total > 0 ? a.Q_total : p.Q;
+    const float *upre = a.upre_all ? a.upre_all : (const float *)(a.ws + p.off_upre);
     if (a.m->kernel == MLP_MFMA2)
-        return launch_mlp_mfma(a.g, a.m, (const float *)(a.ws + p.off_upre), (const int32_t *)(a.ws + p.off_pair_q),
-                               (const int32_t *)(a.ws + p.off_pair_id), M_dev, p.M_max, p.Q,
+        return launch_mlp_mfma(a.g, a.m, upre, (const int32_t *)(a.ws + p.off_pair_q),
+                               (const int32_t *)(a.ws + p.off_pair_id), M_dev, p.M_max, n_users,
                                (float *)(a.ws + p.off_scores), 0, a.stream);
     return launch_mlp_alu(a.g, a.m, a.queries, (const int32_t *)(a.ws + p.off_pair_q),
-                          (const int32_t *)(a.ws + p.off_pair_id), M_dev, p.M_max, p.Q,
+                          (const int32_t *)(a.ws + p.off_pair_id), M_dev, p.M_max, n_users,
                           (float *)(a.ws + p.off_scores), 0, a.stream);
 }
 
@@ -224,6 +227,58 @@ static int run_search(SearchArgs &a) {
                       (long long)stats[3], p.rounds_assumed);
             return ANN_EWORKSPACE;
         }
+    }
+    return ANN_OK;
+}
+
+// Continuous batching: a.Q_total queries stream through a.plan.Q slots.  Every round starts with
+// the admission kernel (finished slots write their result and take the next waiting query); the
+// host learns every few rounds whether anything is still running or waiting.
+static int run_stream(SearchArgs &a) {
+    const Plan &p = a.plan;
+    int rc;
+    if (a.Q_total == 0 || p.Q == 0) return ANN_OK;
+    if (a.m->kernel == MLP_MFMA2)
+        if ((rc = launch_user_pre(a.m, a.queries, a.Q_total, a.upre_all, a.stream)) != ANN_OK) return rc;
+    if ((rc = launch_stream_reset(a)) != ANN_OK) return rc;
+    int32_t *host_ctrl = pinned_ctrl();
+    if (!host_ctrl) {
+        set_error("pinned host allocation failed");
+        return ANN_ENOMEM;
+    }
+    const int check_every = 4;
+    // every query ends within hash_cap / 2 + 1 rounds of its admission, and at least one slot is
+    // re-used per ceil(Q_total / Q) turn-overs: a generous bound that only guards against a bug
+    const int64_t per_query = p.max_iters_max > 0 ? (int64_t)p.max_iters_max + 2 : (int64_t)p.hash_cap / 2 + 3;
+    const int64_t round_limit = per_query * (((int64_t)a.Q_total + p.Q - 1) / p.Q + 1);
+    for (int64_t i = 0; i <= round_limit; ++i) {
+        {
+            StageTimer timer(ANN_STAGE_ROUND, a.stream);
+            if ((rc = launch_admit(a)) != ANN_OK) return rc;
+        }
+        {
+            StageTimer timer(ANN_STAGE_PACK, a.stream);
+            if ((rc = launch_scan_compact(a)) != ANN_OK) return rc;
+        }
+        if (i > 0 && (i % check_every) == 0) {
+            ANN_HIP_TRY(hipMemcpyAsync(host_ctrl, a.ws + p.off_ctrl, 16, hipMemcpyDeviceToHost, a.stream));
+            ANN_HIP_TRY(hipStreamSynchronize(a.stream));
+            // nothing running after an admission step, and nothing left to admit: every result is written
+            if (host_ctrl[1] == 0 && host_ctrl[2] >= a.Q_total) break;
+        }
+        if ((rc = score_batch(a)) != ANN_OK) return rc;
+        {
+            StageTimer timer(ANN_STAGE_ROUND, a.stream);
+            if ((rc = launch_round(a)) != ANN_OK) return rc;
+        }
+    }
+    int64_t stats[8];
+    ANN_HIP_TRY(hipMemcpyAsync(stats, a.ws + p.off_stats, sizeof(stats), hipMemcpyDeviceToHost, a.stream));
+    ANN_HIP_TRY(hipStreamSynchronize(a.stream));
+    if (stats[3] > 0) {
+        set_error("%lld queries filled their visited table (sized for %d rounds) and stopped early",
+                  (long long)stats[3], p.rounds_assumed);
+        return ANN_EWORKSPACE;
     }
     return ANN_OK;
 }
@@ -576,6 +631,74 @@ int ann_search_layers(const ann_graph *const *graphs, int32_t n_layers, const an
             return rc;
     }
     return worst;
+}
+
+// Workspace of a streamed search: the workspace of a search over `slots` queries, then the slot -> query
+// map and the user terms of all queries.
+struct StreamPlan {
+    Plan plan;
+    size_t off_slot_query, off_upre_all, total;
+};
+
+static bool make_stream_plan(const ann_graph *g, const ann_mlp *m, int32_t Q_total, int32_t slots, int32_t E, int32_t W,
+                             int32_t L, int32_t k, int32_t max_iters, StreamPlan *sp) {
+    if (Q_total < 0 || slots < 1) {
+        set_error("need Q_total >= 0 and slots >= 1 (got %d, %d)", Q_total, slots);
+        return false;
+    }
+    if (!make_plan(g, m, slots, E, W, L, k, max_iters, &sp->plan)) return false;
+    size_t o = align256(sp->plan.total);
+    sp->off_slot_query = o;
+    o = align256(o + (size_t)slots * 4);
+    sp->off_upre_all = o;
+    o = align256(o + ((size_t)Q_total * sp->plan.H1 + 32) * 4);
+    sp->total = o;
+    return true;
+}
+
+size_t ann_search_stream_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q_total, int32_t slots,
+                                         int32_t E, int32_t W, int32_t L, int32_t k, int32_t max_iters) {
+    StreamPlan sp;
+    if (!make_stream_plan(g, m, Q_total, slots, E, W, L, k, max_iters, &sp)) return 0;
+    return sp.total;
+}
+
+int ann_search_stream(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q_total,
+                      const int32_t *entry_dev, int32_t E, int32_t slots, int32_t W, int32_t L, int32_t k,
+                      int32_t max_iters, void *workspace_dev, size_t workspace_bytes, int32_t *out_ids_dev,
+                      float *out_scores_dev, void *stream) {
+    StreamPlan sp;
+    if (!make_stream_plan(g, m, Q_total, slots, E, W, L, k, max_iters, &sp)) return ANN_EINVAL;
+    if (Q_total > 0 && (!queries_dev || !entry_dev || !out_ids_dev || !out_scores_dev)) {
+        set_error("queries_dev, entry_dev, out_ids_dev and out_scores_dev must not be null");
+        return ANN_EINVAL;
+    }
+    if (Q_total > 0 && (!workspace_dev || ((uintptr_t)workspace_dev & 255))) {
+        set_error("workspace_dev must be a 256-byte aligned device pointer");
+        return ANN_EINVAL;
+    }
+    if (workspace_bytes < sp.total) {
+        set_error("workspace holds %zu bytes, %zu needed", workspace_bytes, sp.total);
+        return ANN_EWORKSPACE;
+    }
+    SearchArgs a;
+    a.plan = sp.plan;
+    a.g = g;
+    a.m = m;
+    a.queries = queries_dev;
+    a.entries = entry_dev;
+    a.W_q = a.L_q = a.cap_q = nullptr;
+    a.W = W;
+    a.L = L;
+    a.cap = max_iters;
+    a.ws = (char *)workspace_dev;
+    a.out_ids = out_ids_dev;
+    a.out_scores = out_scores_dev;
+    a.stream = (hipStream_t)stream;
+    a.Q_total = Q_total;
+    a.slot_query = (int32_t *)(a.ws + sp.off_slot_query);
+    a.upre_all = (float *)(a.ws + sp.off_upre_all);
+    return run_stream(a);
 }
 
 int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int64_t M,

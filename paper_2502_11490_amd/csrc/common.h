@@ -78,7 +78,8 @@ struct Plan {
 struct Ctrl {
     int32_t M;            // pairs in the current round
     int32_t n_active;     // queries not finished
-    int32_t pad[14];
+    int32_t next_query;   // continuous batching: queries admitted so far (may overshoot the total)
+    int32_t pad[13];
 };
 
 // Per-query state at off_state.
@@ -107,6 +108,10 @@ struct SearchArgs {
     float *out_scores;
     hipStream_t stream;
     bool keep_stats = false;  // counters continue from an earlier search on this workspace
+    // continuous batching: Q_total queries share plan.Q slots
+    int32_t Q_total = 0;          // 0 = every query owns a slot
+    int32_t *slot_query = nullptr;  // [plan.Q] query served by each slot, -1 = idle
+    float *upre_all = nullptr;    // [Q_total][H1] user terms of all queries (MFMA path)
 };
 
 // search_kernels.hip
@@ -114,6 +119,8 @@ int launch_init(const SearchArgs &a);
 int launch_scan_compact(const SearchArgs &a);
 int launch_round(const SearchArgs &a);
 int launch_emit(const SearchArgs &a);
+int launch_stream_reset(const SearchArgs &a);
+int launch_admit(const SearchArgs &a);
 
 // mlp_alu.hip / mlp_mfma.hip: score `*M_dev` (<= M_max) pairs; M_dev is read on the device.
 int launch_mlp_alu(const ann_graph *g, const ann_mlp *m, const void *queries, const int32_t *pair_q,

@@ -228,13 +228,11 @@ __global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q, int keep_st
 // ------------------------------------------------------------------------------------------
 // Seeding: clear the visited table, keep the distinct in-range entry ids as the survivors of
 // "round 0" (they are scored by the first MLP launch and merged by the first round kernel).
-__global__ void __launch_bounds__(BLOCK)
-init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state, uint32_t *hash,
-            int hash_cap, int32_t *cand_g, int slots, int32_t *counts, const int32_t *W_q,
-            const int32_t *L_q, const int32_t *cap_q, int W, int L, int cap, int W_max, int L_max,
-            int cap_max, int64_t *stats) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int q = blockIdx.x;
+// `slot` names the search state that is set up, `query` the row of entries / per-query parameters.
+__device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entries, int E, int64_t N, QState *state,
+                          uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
+                          const int32_t *W_q, const int32_t *L_q, const int32_t *cap_q, int W, int L, int cap,
+                          int W_max, int L_max, int cap_max, int64_t *stats, unsigned char *smem) {
     int dd_n = 2;
     while (dd_n < 2 * E) dd_n <<= 1;
     int32_t *cand = (int32_t *)smem;                 // [E]
@@ -244,32 +242,108 @@ init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state
     uint32_t *bk_cnt = bk_key + dd_n;
     int *wave_sums = (int *)(bk_cnt + dd_n);
 
-    uint32_t *table = hash + (size_t)q * hash_cap;
+    uint32_t *table = hash + (size_t)slot * hash_cap;
     {
         uint4 *t4 = (uint4 *)table;  // hash_cap is a power of two >= 64, the table 256-byte aligned
         const uint4 e4 = make_uint4(EMPTY_SLOT, EMPTY_SLOT, EMPTY_SLOT, EMPTY_SLOT);
         for (int i = threadIdx.x; i < hash_cap / 4; i += BLOCK) t4[i] = e4;
     }
-    for (int i = threadIdx.x; i < E; i += BLOCK) cand[i] = entries[(size_t)q * E + i];
+    for (int i = threadIdx.x; i < E; i += BLOCK) cand[i] = entries[(size_t)query * E + i];
     __threadfence_block();
     __syncthreads();
     int n = filter_and_insert(cand, E, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, hash_cap, N,
-                              cand_g + (size_t)q * slots, wave_sums);
+                              cand_g + (size_t)slot * slots, wave_sums);
     if (threadIdx.x == 0) {
         QState s;
         s.t = 0;
         s.done = 0;
         s.n_list = 0;
         s.n_visited = n;
-        int w = W_q ? W_q[q] : W, l = L_q ? L_q[q] : L, c = cap_q ? cap_q[q] : cap;
+        int w = W_q ? W_q[query] : W, l = L_q ? L_q[query] : L, c = cap_q ? cap_q[query] : cap;
         s.W = min(max(w, 1), W_max);
         s.L = min(max(l, 1), L_max);
         s.cap = cap_max > 0 ? min(max(c, 1), cap_max) : max(c, 0);
         s.overflow = 0;
-        state[q] = s;
-        counts[q] = n;
+        state[slot] = s;
+        counts[slot] = n;
         if (n) atomicAdd((unsigned long long *)&stats[0], (unsigned long long)n);
     }
+}
+
+__global__ void __launch_bounds__(BLOCK)
+init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state, uint32_t *hash,
+            int hash_cap, int32_t *cand_g, int slots, int32_t *counts, const int32_t *W_q,
+            const int32_t *L_q, const int32_t *cap_q, int W, int L, int cap, int W_max, int L_max,
+            int cap_max, int64_t *stats) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    seed_slot(blockIdx.x, blockIdx.x, entries, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W,
+              L, cap, W_max, L_max, cap_max, stats, smem);
+}
+
+// First k entries of a slot's list to row `row` of the outputs, padded with (-1, -inf).
+__device__ void emit_row(const QState *state, const uint64_t *pool_g, int C, int k, int slot, int64_t row,
+                         int32_t *out_ids, float *out_scores) {
+    const int n = state[slot].n_list;
+    const uint64_t *pool = pool_g + (size_t)slot * C;
+    for (int i = threadIdx.x; i < k; i += BLOCK) {
+        int32_t id = -1;
+        float sc = -INFINITY;
+        if (i < n) {
+            uint64_t key = pool[i];
+            id = key_id(key);
+            sc = key_score(key);
+        }
+        out_ids[(size_t)row * k + i] = id;
+        out_scores[(size_t)row * k + i] = sc;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Continuous batching (Sec. 3.2, Q-HiPANNS: requests arrive and finish at different times and are
+// aggregated into common batches).  The search state lives in slots; a slot whose query has
+// finished writes that query's result and takes the next waiting query, in index order (a
+// counter is the queue).  Runs before the packing step of every round.
+__global__ void stream_reset_kernel(int64_t *stats, Ctrl *ctrl, QState *state, int32_t *counts, int32_t *slot_query,
+                                    int S, int Q_total) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < 16) {
+        stats[i] = (i == 4) ? Q_total : 0;
+        ((int32_t *)ctrl)[i] = 0;
+    }
+    if (i < S) {
+        QState s = {};
+        s.done = 1;
+        state[i] = s;
+        counts[i] = -1;
+        slot_query[i] = -1;
+    }
+}
+
+__global__ void __launch_bounds__(BLOCK)
+admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state, uint32_t *hash, int hash_cap,
+             int32_t *cand_g, int slots, int32_t *counts, const int32_t *W_q, const int32_t *L_q,
+             const int32_t *cap_q, int W, int L, int cap, int W_max, int L_max, int cap_max, int64_t *stats,
+             Ctrl *ctrl, int32_t *slot_query, int Q_total, const uint64_t *pool_g, int C, int k, int32_t *out_ids,
+             float *out_scores) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int next_s;
+    const int slot = blockIdx.x;
+    if (!state[slot].done) return;  // still searching
+    const int served = slot_query[slot];
+    if (served >= 0) emit_row(state, pool_g, C, k, slot, served, out_ids, out_scores);
+    if (threadIdx.x == 0) {
+        int next = Q_total;
+        // the counter only grows; once it has passed the total nobody needs to touch it again
+        if (*(volatile int32_t *)&ctrl->next_query < Q_total) next = atomicAdd(&ctrl->next_query, 1);
+        next_s = next < Q_total ? next : -1;
+        slot_query[slot] = next_s;
+        if (next_s < 0) counts[slot] = -1;  // idle: contributes no pairs, is not counted as running
+    }
+    __syncthreads();  // also: the list of the served query has been read before the slot is re-seeded
+    const int next = next_s;
+    if (next < 0) return;
+    seed_slot(slot, next, entries, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W, L, cap,
+              W_max, L_max, cap_max, stats, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -281,7 +355,8 @@ init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state
 constexpr int SCAN_QPB = 16;  // queries per workgroup
 __global__ void __launch_bounds__(SCAN_BLOCK)
 scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__restrict__ cand_g, int slots,
-                    int32_t *offsets, int32_t *pair_q, int32_t *pair_id, Ctrl *ctrl) {
+                    int32_t *offsets, int32_t *pair_q, int32_t *pair_id, Ctrl *ctrl,
+                    const int32_t *__restrict__ slot_query) {
     __shared__ int red[SCAN_WAVES];
     __shared__ int red_active[SCAN_WAVES];
     __shared__ int loc_off[SCAN_QPB + 1];
@@ -336,9 +411,10 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
         if (q >= Q) break;
         int c = loc_cnt[i], off = loc_off[i];
         const int32_t *src = cand_g + (size_t)q * slots;
+        const int32_t user = slot_query ? slot_query[q] : q;  // whose user vector scores this group
         for (int j = lane; j < c; j += 64) {
             pair_id[off + j] = src[j];
-            pair_q[off + j] = q;
+            pair_q[off + j] = user;
         }
     }
 }
@@ -514,20 +590,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
 __global__ void __launch_bounds__(BLOCK)
 emit_kernel(const QState *__restrict__ state, const uint64_t *__restrict__ pool_g, int C, int k,
             int32_t *out_ids, float *out_scores) {
-    const int q = blockIdx.x;
-    const int n = state[q].n_list;
-    const uint64_t *pool = pool_g + (size_t)q * C;
-    for (int i = threadIdx.x; i < k; i += BLOCK) {
-        int32_t id = -1;
-        float sc = -INFINITY;
-        if (i < n) {
-            uint64_t key = pool[i];
-            id = key_id(key);
-            sc = key_score(key);
-        }
-        out_ids[(size_t)q * k + i] = id;
-        out_scores[(size_t)q * k + i] = sc;
-    }
+    emit_row(state, pool_g, C, k, blockIdx.x, blockIdx.x, out_ids, out_scores);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -545,11 +608,15 @@ static size_t round_smem(const Plan &p) {
     return (size_t)((p.W_max + 3) & ~3) * 4 + 8 * 4 + (lists > filt ? lists : filt);
 }
 
-int launch_init(const SearchArgs &a) {
-    const Plan &p = a.plan;
+static size_t seed_smem(const Plan &p) {
     int dd_n = 2;
     while (dd_n < 2 * p.E) dd_n <<= 1;
-    size_t smem = (size_t)((p.E + 3) & ~3) * 4 + (size_t)dd_n * 16 + (WAVES + 1) * 4;
+    return (size_t)((p.E + 3) & ~3) * 4 + (size_t)dd_n * 16 + (WAVES + 1) * 4;
+}
+
+int launch_init(const SearchArgs &a) {
+    const Plan &p = a.plan;
+    size_t smem = seed_smem(p);
     int64_t *stats = (int64_t *)(a.ws + p.off_stats);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, a.stream, stats, (Ctrl *)(a.ws + p.off_ctrl), p.Q,
                        a.keep_stats ? 1 : 0);
@@ -561,13 +628,35 @@ int launch_init(const SearchArgs &a) {
     return ANN_OK;
 }
 
+int launch_stream_reset(const SearchArgs &a) {
+    const Plan &p = a.plan;
+    const int n = p.Q > 16 ? p.Q : 16;
+    hipLaunchKernelGGL(stream_reset_kernel, dim3((n + 255) / 256), dim3(256), 0, a.stream,
+                       (int64_t *)(a.ws + p.off_stats), (Ctrl *)(a.ws + p.off_ctrl), (QState *)(a.ws + p.off_state),
+                       (int32_t *)(a.ws + p.off_counts), a.slot_query, p.Q, a.Q_total);
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+int launch_admit(const SearchArgs &a) {
+    const Plan &p = a.plan;
+    hipLaunchKernelGGL(admit_kernel, dim3(p.Q), dim3(BLOCK), seed_smem(p), a.stream, a.entries, p.E, a.g->N,
+                       (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), p.hash_cap,
+                       (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q, a.L_q,
+                       a.cap_q, a.W, a.L, a.cap, p.W_max, p.L_max, p.max_iters_max, (int64_t *)(a.ws + p.off_stats),
+                       (Ctrl *)(a.ws + p.off_ctrl), a.slot_query, a.Q_total, (const uint64_t *)(a.ws + p.off_pool), p.C,
+                       p.k, a.out_ids, a.out_scores);
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
 int launch_scan_compact(const SearchArgs &a) {
     const Plan &p = a.plan;
     int blocks = (p.Q + SCAN_QPB - 1) / SCAN_QPB;
     hipLaunchKernelGGL(scan_compact_kernel, dim3(blocks), dim3(SCAN_BLOCK), 0, a.stream,
                        (const int32_t *)(a.ws + p.off_counts), p.Q, (const int32_t *)(a.ws + p.off_cand),
                        p.slots, (int32_t *)(a.ws + p.off_offsets), (int32_t *)(a.ws + p.off_pair_q),
-                       (int32_t *)(a.ws + p.off_pair_id), (Ctrl *)(a.ws + p.off_ctrl));
+                       (int32_t *)(a.ws + p.off_pair_id), (Ctrl *)(a.ws + p.off_ctrl), a.slot_query);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }

@@ -363,3 +363,49 @@ def test_layered_search_argument_errors():
         ann.ann_search_layers([g, small], m, dev["users"], dev["entries"], [2, 2], [8, 8], [4, 4], 0)
     with pytest.raises(ValueError):
         ann.ann_search_layers([small, g], m, dev["users"], dev["entries"], [2], [8, 8], [4, 4], 0)
+
+
+# ----------------------------------------------------------------------------- continuous batching
+@pytest.mark.parametrize("slots", [1, 7, 40, 64])
+def test_streamed_search_equals_batched_search_fp32(slots):
+    # queries do not influence each other: any number of slots gives the results of ann_search
+    cfg = replace(scaled(PRESETS["C1"], 5000, n_clusters=8, Q=40), E=3)
+    wl = _with_biases(make_workload(cfg, seed=31), cfg, 16)
+    g, m, dev = open_handles(wl)
+    W, L, k = 3, 20, 12
+    ws = torch.empty(ann.ann_search_workspace_bytes(g, m, cfg.Q, cfg.E, W, L, k, 0), dtype=torch.uint8, device="cuda")
+    ids0, sc0 = ann.ann_search(g, m, dev["users"], dev["entries"], W, L, k, 0, workspace=ws)
+    st0 = ann.ann_search_stats(ws)
+    wss = torch.empty(ann.ann_search_stream_workspace_bytes(g, m, cfg.Q, slots, cfg.E, W, L, k, 0), dtype=torch.uint8,
+                      device="cuda")
+    ids1, sc1 = ann.ann_search_stream(g, m, dev["users"], dev["entries"], slots, W, L, k, 0, workspace=wss)
+    assert torch.equal(ids0, ids1) and torch.equal(sc0, sc1)
+    st1 = ann.ann_search_stats(wss)
+    assert (st1.pairs_scored, st1.nodes_expanded, st1.queries) == (st0.pairs_scored, st0.nodes_expanded, cfg.Q)
+    assert st1.visited_overflow == 0
+    # and the oracle agrees with both
+    ref = _oracle_search(to_host(wl), W, L, k, 0)
+    assert same_list_fraction(ids1.cpu().numpy(), ref["ids"]) >= 0.99
+
+
+def test_streamed_search_capped_and_bf16():
+    base = PRESETS["C3"]
+    cfg = replace(scaled(base, 30000, Q=150), E=base.E)
+    wl = make_workload(cfg)
+    g, m, dev = open_handles(wl)
+    assert ann.ann_mlp_uses_mfma(m)
+    for cap in (0, 5):
+        ids0, sc0 = ann.ann_search(g, m, dev["users"], dev["entries"], base.W, 48, 30, cap)
+        ids1, sc1 = ann.ann_search_stream(g, m, dev["users"], dev["entries"], 32, base.W, 48, 30, cap)
+        # the same pairs are scored, in other batches: a relevance does not depend on its batch
+        assert torch.equal(ids0, ids1) and torch.equal(sc0, sc1)
+
+
+def test_streamed_search_empty_and_errors():
+    cfg = replace(scaled(PRESETS["C1"], 2000, n_clusters=4, Q=4), E=2)
+    wl = make_workload(cfg, seed=9)
+    g, m, dev = open_handles(wl)
+    ids, sc = ann.ann_search_stream(g, m, dev["users"][:0], dev["entries"][:0], 8, 2, 8, 5, 0)
+    assert ids.shape == (0, 5)
+    with pytest.raises(ann.AnnError):
+        ann.ann_search_stream(g, m, dev["users"], dev["entries"], 0, 2, 8, 5, 0)
