@@ -107,6 +107,7 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=3)
     ap.add_argument("--no-layers", action="store_true", help="skip the layer-by-layer search beside the headline")
+    ap.add_argument("--no-stream", action="store_true", help="skip the continuous-batching run beside the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain 256 MiB copy kernel (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -245,6 +246,28 @@ def main() -> int:
             del graphs, wsl
         del ly
 
+    # ---- continuous batching: four copies of the batch stream through Q (and 2Q) search slots;
+    #      reported beside the headline, not part of the timed step ----
+    streamed = None
+    if not ragged and not args.no_stream:
+        users4, entries4 = users.repeat(4, 1).contiguous(), entries.repeat(4, 1).contiguous()
+        streamed = {"queries": 4 * Q, "same_results_as_batched": True}
+        for slots in (Q, 2 * Q):
+            wss = torch.empty(ann.ann_search_stream_workspace_bytes(g, m, 4 * Q, slots, E, W, L_star, k, 0),
+                              dtype=torch.uint8, device="cuda:0")
+            run = lambda: ann.ann_search_stream(g, m, users4, entries4, slots, W, L_star, k, 0, workspace=wss)
+            run()
+            torch.cuda.synchronize()
+            t5 = time.perf_counter()
+            ids_s, _ = run()
+            torch.cuda.synchronize()
+            ms_s = 1e3 * (time.perf_counter() - t5)
+            streamed[f"slots_{slots}"] = {"ms": round(ms_s, 2), "queries_per_s": round(4 * Q / ms_s * 1e3, 1)}
+            streamed["same_results_as_batched"] &= bool(torch.equal(ids_s[:Q], out_ids) and torch.equal(ids_s[3 * Q:], out_ids))
+            log(f"continuous batching, {4 * Q} queries through {slots} slots: {ms_s:.1f} ms, {4 * Q / ms_s * 1e3:.0f} queries/s")
+            del wss
+        del users4, entries4
+
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 255)
         dst = torch.empty_like(src)
@@ -351,7 +374,7 @@ def main() -> int:
             "mlp_scores_per_s": round(scores_per_s, 1),
             "pairs_scored_per_step": int(st.pairs_scored), "nodes_expanded_per_step": int(st.nodes_expanded),
             "rounds": int(st.max_query_iters), "mfma_kernel": bool(mfma), "stages": stages,
-            "layered_search": layered,
+            "layered_search": layered, "continuous_batching": streamed,
         },
         "roofline": roofline,
         "cpu_baseline": cpu,
