@@ -328,8 +328,8 @@ def main() -> int:
         n_cpu = args.cpu_queries
         threads = min(oracle.num_threads(), os.cpu_count() or 1)
         if n_cpu <= 0:
-            # ~ pairs/query * flop/pair at about 1 GFLOP/s per core
-            per_query_s = (st.pairs_scored / Q) * fl_full / 1.0e9
+            # ~ pairs/query * flop/pair at about 3 GFLOP/s per core (what the oracle's plain loops reach)
+            per_query_s = (st.pairs_scored / Q) * fl_full / 3.0e9
             n_cpu = int(max(threads, min(Q, 20.0 * threads / max(per_query_s, 1e-6))))
             n_cpu = min(Q, max(threads, (n_cpu // threads) * threads))
         t3 = time.time()
