@@ -17,6 +17,10 @@
 // term depends on the query only and is computed once per search (user_pre_kernel, fp32);
 // it initialises the layer-1 accumulators, so only the item half is contracted per pair.
 //
+// The weights of this kernel's shapes fill most of the LDS, so a CU runs one workgroup; it has
+// eight waves (two per SIMD, 256 registers each) so that one wave's item-row gather and
+// conversions overlap the other's MFMAs.
+//
 // Weights do not fit in registers and (for the largest metric) not in LDS either: they are
 // streamed through LDS in chunks, chunk nb = the 32 layer-1 units nb*32.. and the slab of
 // layer-2 weights that consumes exactly those units, double buffered; when all chunks fit
@@ -86,8 +90,8 @@ user_pre_kernel(const uint16_t *__restrict__ W1, int n_in, int d_user, int H1, c
 //     [D/16 + 2*n2 + s2]    lane (m,g): W2[n2*32+m][nb*32 + 16*s2 + 8*(j/4) + 4g + j%4], j < 8
 //   then the head layer, H2/16 fragments, rows >= J are zero:
 //     [2*n2 + s2]           lane (m,g): W3[m][n2*32 + 16*s2 + 8*(j/4) + 4g + j%4]
-template <int D, int H1, int H2, int CB, bool RESIDENT>
-__global__ void __launch_bounds__(MF_BLOCK)
+template <int D, int H1, int H2, int CB, bool RESIDENT, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES)
 mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__restrict__ upre,
                  const uint4 *__restrict__ frag, const float *__restrict__ b2, const float *__restrict__ b3,
                  const float *__restrict__ head_w, int J, const int32_t *__restrict__ pair_q,
@@ -97,9 +101,10 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
     constexpr int CHUNK_FR = KS1 + 2 * NB2;          // fragments per chunk
     constexpr int CHUNK_U4 = CHUNK_FR * 64;          // uint4 per chunk
     constexpr int W3_FR = 2 * NB2;
-    constexpr int RW = 32 * CB, TILE = RW * MF_WAVES;
+    constexpr int BLOCK_T = 64 * WAVES;
+    constexpr int RW = 32 * CB, TILE = RW * WAVES;
     constexpr int NBUF = RESIDENT ? NB1 : 2;
-    constexpr int ST = (CHUNK_U4 + MF_BLOCK - 1) / MF_BLOCK;  // staged uint4 per thread and chunk
+    constexpr int ST = (CHUNK_U4 + BLOCK_T - 1) / BLOCK_T;  // staged uint4 per thread and chunk
     extern __shared__ __align__(16) uint4 lds[];
     uint4 *wbuf = lds;                                // [NBUF][CHUNK_U4]
     uint4 *w3buf = lds + (size_t)NBUF * CHUNK_U4;     // [W3_FR * 64]
@@ -113,10 +118,10 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
     const int g = lane >> 5, col = lane & 31;
 
     // head-layer fragments, and either every chunk (resident) or chunk 0
-    for (int i = threadIdx.x; i < W3_FR * 64; i += MF_BLOCK) w3buf[i] = frag[(size_t)NB1 * CHUNK_U4 + i];
+    for (int i = threadIdx.x; i < W3_FR * 64; i += BLOCK_T) w3buf[i] = frag[(size_t)NB1 * CHUNK_U4 + i];
     {
         const int n_pre = RESIDENT ? NB1 * CHUNK_U4 : CHUNK_U4;
-        for (int i = threadIdx.x; i < n_pre; i += MF_BLOCK) wbuf[i] = frag[i];
+        for (int i = threadIdx.x; i < n_pre; i += BLOCK_T) wbuf[i] = frag[i];
     }
     __syncthreads();
 
@@ -128,28 +133,51 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
         bb3[i] = j < J ? b3[j] : 0.f;
     }
 
+    // Item rows are fetched one batch ahead, into the registers the layer-1 MFMAs of the current
+    // batch have finished with (its last layer-2 block and the head layer hide the latency); the
+    // pair ids run two batches ahead.  Rows past the end read the last pair and are not stored.
+    struct Ids {
+        int32_t id[CB], q[CB];
+        bool bad[CB];
+    };
+    auto load_ids = [&](int64_t tile) {
+        Ids r;
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            int64_t row = tile * TILE + (int64_t)wave * RW + c * 32 + col;
+            row = row < M ? row : M - 1;
+            const int32_t v = pair_id[row], q = pair_q[row];
+            r.bad[c] = ((uint64_t)(int64_t)v >= (uint64_t)N) | ((uint32_t)q >= (uint32_t)Q);
+            r.id[c] = r.bad[c] ? 0 : v;
+            r.q[c] = r.bad[c] ? 0 : q;
+        }
+        return r;
+    };
+    bf16x8 xf[CB][KS1];
+    auto gather = [&](const Ids &ids) {
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            const bf16x8 *src = (const bf16x8 *)(emb + (size_t)ids.id[c] * D) + g;
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) xf[c][s] = src[2 * s];
+        }
+    };
+    Ids idc = load_ids(blockIdx.x), idn = load_ids((int64_t)blockIdx.x + gridDim.x);
+    gather(idc);
+
     int cur = 0;
 #pragma unroll 1
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t row0 = tile * TILE + (int64_t)wave * RW;
-        bf16x8 xf[CB][KS1];
         const float *up[CB];
         bool bad[CB];
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
-            int64_t row = row0 + c * 32 + col;
-            int32_t v = 0, q = 0;
-            if (row < M) {
-                v = pair_id[row];
-                q = pair_q[row];
-            }
-            bad[c] = (v < 0 || (int64_t)v >= N || q < 0 || q >= Q);
-            if (bad[c]) v = 0, q = 0;
-            const bf16x8 *src = (const bf16x8 *)(emb + (size_t)v * D) + g;
-#pragma unroll
-            for (int s = 0; s < KS1; ++s) xf[c][s] = src[2 * s];
-            up[c] = upre + (size_t)q * H1 + 4 * g;
+            up[c] = upre + (size_t)idc.q[c] * H1 + 4 * g;
+            bad[c] = idc.bad[c];
         }
+        idc = idn;                                             // the next batch ...
+        idn = load_ids(tile + 2 * (int64_t)gridDim.x);         // ... and the one after it
         f32x16 acc2[NB2][CB];
         // the bias pointer is laundered once per batch: otherwise the loads below are hoisted
         // out of the batch loop and their 16*NB2 values are carried (spilled) across it
@@ -178,7 +206,7 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
                 const uint4 *srcw = frag + (size_t)nxt * CHUNK_U4;
 #pragma unroll
                 for (int t = 0; t < ST; ++t) {
-                    int i = threadIdx.x + t * MF_BLOCK;
+                    int i = threadIdx.x + t * BLOCK_T;
                     if (i < CHUNK_U4) stage[t] = srcw[i];
                 }
             }
@@ -221,13 +249,15 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
                 uint4 *dst = wbuf + (size_t)(cur ^ 1) * CHUNK_U4;
 #pragma unroll
                 for (int t = 0; t < ST; ++t) {
-                    int i = threadIdx.x + t * MF_BLOCK;
+                    int i = threadIdx.x + t * BLOCK_T;
                     if (i < CHUNK_U4) dst[i] = stage[t];
                 }
                 __syncthreads();
                 cur ^= 1;
             }
         }
+
+        gather(idc);  // the item rows of the next batch: layer 1 of this one is done with the registers
 
         // head layer (rows >= J of the fragments are zero), then Eq. 8
         static_assert(CB >= 2, "two accumulators must alternate");
@@ -449,7 +479,7 @@ int launch_user_pre(const ann_mlp *m, const void *queries, int32_t Q, float *upr
     return ANN_OK;
 }
 
-template <int D, int H1, int H2, int CB, bool RESIDENT>
+template <int D, int H1, int H2, int CB, bool RESIDENT, int WAVES>
 static int launch_one(const ann_graph *g, const ann_mlp *m, const float *upre, const int32_t *pair_q,
                       const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
                       hipStream_t stream) {
@@ -457,14 +487,14 @@ static int launch_one(const ann_graph *g, const ann_mlp *m, const float *upre, c
     constexpr int CHUNK_U4 = (KS1 + 2 * NB2) * 64;
     constexpr int NBUF = RESIDENT ? NB1 : 2;
     constexpr size_t smem = ((size_t)NBUF * CHUNK_U4 + 2 * NB2 * 64) * 16;
-    constexpr int TILE = 32 * CB * MF_WAVES;
+    constexpr int TILE = 32 * CB * WAVES;
     static_assert(smem <= 160 * 1024, "LDS budget");
-    auto fn = mlp_mfma2_kernel<D, H1, H2, CB, RESIDENT>;
+    auto fn = mlp_mfma2_kernel<D, H1, H2, CB, RESIDENT, WAVES>;
     ANN_HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     int64_t tiles = (M_max + TILE - 1) / TILE;
     int grid = (int)(tiles < 256 ? tiles : 256);
     const float *b2 = m->b_dev + m->b_off[1], *b3 = m->b_dev + m->b_off[2];
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(MF_BLOCK), smem, stream, (const uint16_t *)g->emb, g->N, upre,
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(64 * WAVES), smem, stream, (const uint16_t *)g->emb, g->N, upre,
                        (const uint4 *)m->frag_dev, b2, b3, m->head_w_dev, m->J, pair_q, pair_id, M_dev, M_max, Q,
                        scores);
     ANN_HIP_TRY(hipGetLastError());
@@ -493,7 +523,7 @@ int launch_mlp_mfma(const ann_graph *g, const ann_mlp *m, const float *upre, con
     if (mfma_stream_supported(D, H1, H2))
         return launch_mlp_mfma_stream(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
     if (D == 64 && H1 == 256 && H2 == 128)
-        return launch_one<64, 256, 128, 2, true>(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
+        return launch_one<64, 256, 128, 2, true, 8>(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
     set_error("no MFMA kernel for item width %d, hidden %d, %d", D, H1, H2);
     return ANN_ENOTIMPL;
 }
