@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -28,6 +29,21 @@ void set_error(const char *fmt, ...);
             return ANN_EDEVICE;                                                          \
         }                                                                                \
     } while (0)
+
+// Raises a kernel's dynamic-LDS limit once per device: the runtime call is a host-side lookup that
+// need not be repeated on every one of the hundreds of launches of a search.  `done` is the
+// launcher's own bit mask of devices already served.
+inline int raise_lds_limit(const void *fn, size_t bytes, int device, std::atomic<uint32_t> &done) {
+    const bool tracked = device >= 0 && device < 32;
+    if (tracked && ((done.load(std::memory_order_acquire) >> device) & 1u)) return ANN_OK;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) {
+        set_error("hipFuncSetAttribute(dynamic LDS %zu) failed: %s", bytes, hipGetErrorString(e));
+        return ANN_EDEVICE;
+    }
+    if (tracked) done.fetch_or(1u << device, std::memory_order_release);
+    return ANN_OK;
+}
 
 }  // namespace gmpgr
 

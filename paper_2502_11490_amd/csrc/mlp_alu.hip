@@ -155,8 +155,11 @@ int launch_mlp_alu(const ann_graph *g, const ann_mlp *m, const void *queries, co
         return ANN_ENOTIMPL;
     }
     const void *fn = bf16 ? (const void *)mlp_alu_kernel<true> : (const void *)mlp_alu_kernel<false>;
-    if (smem > 48 * 1024)
-        ANN_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
+    if (smem > 48 * 1024) {
+        static std::atomic<uint32_t> raised[2];
+        int rc = raise_lds_limit(fn, 144 * 1024, m->device, raised[bf16 ? 1 : 0]);
+        if (rc != ANN_OK) return rc;
+    }
     int64_t tiles = (M_max + T - 1) / T;
     int grid = (int)(tiles < 4096 ? tiles : 4096);
     if (bf16)

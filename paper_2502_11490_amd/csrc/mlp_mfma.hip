@@ -490,7 +490,8 @@ static int launch_one(const ann_graph *g, const ann_mlp *m, const float *upre, c
     constexpr int TILE = 32 * CB * WAVES;
     static_assert(smem <= 160 * 1024, "LDS budget");
     auto fn = mlp_mfma2_kernel<D, H1, H2, CB, RESIDENT, WAVES>;
-    ANN_HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    static std::atomic<uint32_t> raised;
+    if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised); rc != ANN_OK) return rc;
     int64_t tiles = (M_max + TILE - 1) / TILE;
     int grid = (int)(tiles < 256 ? tiles : 256);
     const float *b2 = m->b_dev + m->b_off[1], *b3 = m->b_dev + m->b_off[2];
@@ -511,7 +512,8 @@ int launch_mlp_mfma(const ann_graph *g, const ann_mlp *m, const float *upre, con
         constexpr int CB = 2, TILE = 32 * CB * MF_WAVES;
         constexpr size_t smem = (size_t)(256 / 32) * (64 / 16 + 2) * 64 * 16;  // 48 KB: three workgroups per CU
         auto fn = mlp_mfma1_kernel<64, 256, CB>;
-        ANN_HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        static std::atomic<uint32_t> raised;
+        if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised); rc != ANN_OK) return rc;
         int64_t tiles = (M_max + TILE - 1) / TILE;
         int grid = (int)(tiles < 3 * 256 ? tiles : 3 * 256);
         hipLaunchKernelGGL(fn, dim3(grid), dim3(MF_BLOCK), smem, stream, (const uint16_t *)g->emb, g->N, upre,

@@ -436,7 +436,8 @@ int launch_mlp_mfma_stream(const ann_graph *g, const ann_mlp *m, const float *up
     constexpr size_t smem = ((size_t)3 * 24 * 64 + 16 * 64 + 4 * 16 * 64) * 16 + (256 + 32) * 4;  // 72 + 16 + 64 + 1 KB (+ head constants)
     constexpr int TILE = 256;
     auto fn = mlp_mfma2_stream_kernel<H1>;
-    ANN_HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    static std::atomic<uint32_t> raised;
+    if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised); rc != ANN_OK) return rc;
     int64_t tiles = (M_max + TILE - 1) / TILE;
     int grid = (int)(tiles < 256 ? tiles : 256);
     const float *b2 = m->b_dev + m->b_off[1], *b3 = m->b_dev + m->b_off[2];

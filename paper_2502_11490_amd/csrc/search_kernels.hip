@@ -663,13 +663,10 @@ int launch_scan_compact(const SearchArgs &a) {
 
 int launch_round(const SearchArgs &a) {
     const Plan &p = a.plan;
-    static bool attr_set[16] = {false};
     size_t smem = round_smem(p);
-    int dev = a.m->device;
-    if (smem > 48 * 1024 && dev >= 0 && dev < 16 && !attr_set[dev]) {
-        ANN_HIP_TRY(hipFuncSetAttribute((const void *)round_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        128 * 1024));
-        attr_set[dev] = true;
+    if (smem > 48 * 1024) {
+        static std::atomic<uint32_t> raised;
+        if (int rc = raise_lds_limit((const void *)round_kernel, 128 * 1024, a.m->device, raised); rc != ANN_OK) return rc;
     }
     hipLaunchKernelGGL(round_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.g->adj, p.R, a.g->N,
                        (QState *)(a.ws + p.off_state), (uint64_t *)(a.ws + p.off_pool), p.C,
