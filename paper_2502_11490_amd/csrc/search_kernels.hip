@@ -78,12 +78,24 @@ __device__ __forceinline__ int block_excl_count(bool flag, int *wave_sums, int *
     return base + excl;
 }
 
-// Ascending bitonic sort of keys[0..n) in LDS, n a power of two.
+// Ascending bitonic sort of keys[0..n) in LDS, n a power of two.  Thread t owns the t-th
+// compare-exchange of every step (and t + BLOCK, ...): for strides up to 64 the 64 threads of a
+// wave then touch one and the same 128-key segment step after step, so those steps need no
+// workgroup barrier, only the wave's own program order (LDS executes a wave's operations in
+// order); a barrier is needed around the steps with larger strides and at the end.
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 __device__ void bitonic_sort(uint64_t *keys, int n) {
     for (int k = 2; k <= n; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
+            const bool across_waves = j > 64;
+            if (across_waves) __syncthreads();
             for (int t = threadIdx.x; t < (n >> 1); t += BLOCK) {
-                // t-th compare-exchange of this stage: indices i < ixj
+                // t-th compare-exchange of this step: indices i < ixj
                 int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
                 int ixj = i | j;
                 bool up = ((i & k) == 0);
@@ -93,9 +105,11 @@ __device__ void bitonic_sort(uint64_t *keys, int n) {
                     keys[ixj] = a;
                 }
             }
-            __syncthreads();
+            if (across_waves) __syncthreads();
+            else wave_lds_fence();
         }
     }
+    __syncthreads();
 }
 
 // Drops ids that are out of range, repeated inside cand[0..n_cand) (first occurrence kept)
