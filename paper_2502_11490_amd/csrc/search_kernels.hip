@@ -459,13 +459,6 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     extern __shared__ __align__(16) unsigned char smem[];
     const int q = blockIdx.x;
     PHASE_START
-    QState st = state[q];
-    if (st.done) {
-        if (threadIdx.x == 0) counts[q] = -1;
-        return;
-    }
-    int dd_n = 2;
-    while (dd_n < 2 * slots) dd_n <<= 1;
     // LDS: parents and scan scratch first; then one region used twice: by the list buffers until
     // the list is written back, by the candidate ids and the dedupe table afterwards
     int32_t *parents = (int32_t *)smem;                       // [W_max]
@@ -474,19 +467,30 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     uint64_t *oldk = keys + C;                                // [C]       list as stored
     uint64_t *newk = oldk + C;                                // [new_cap] new entries, sorted
     int32_t *cand = (int32_t *)keys;                          // [slots]
+    uint64_t *pool = pool_g + (size_t)q * C;
+    int32_t *cand_q = cand_g + (size_t)q * slots;
+
+    // Everything the round needs first is requested at once, before any of it is looked at (the
+    // whole list, not only its n_list valid entries): the workgroups of a launch start together,
+    // and every dependent trip to memory costs them all a few microseconds.
+    QState st = state[q];
+    const int n_prev = counts[q];
+    const int off = offsets[q];
+#pragma unroll 4
+    for (int i = threadIdx.x; i < C; i += BLOCK) oldk[i] = pool[i];
+    if (st.done) {
+        if (threadIdx.x == 0) counts[q] = -1;
+        return;
+    }
+    int dd_n = 2;
+    while (dd_n < 2 * slots) dd_n <<= 1;
     uint32_t *dd_key = (uint32_t *)(cand + ((slots + 3) & ~3));
     uint32_t *dd_pos = dd_key + dd_n;
     uint32_t *bk_key = dd_pos + dd_n;
     uint32_t *bk_cnt = bk_key + dd_n;
 
-    uint64_t *pool = pool_g + (size_t)q * C;
-    int32_t *cand_q = cand_g + (size_t)q * slots;
-    const int n_prev = counts[q];
-    const int off = offsets[q];
-
     // 1. merge the scores of the previous round (or of the seeds) into the sorted list
-    for (int i = threadIdx.x; i < st.n_list; i += BLOCK) oldk[i] = pool[i];
-    __syncthreads();
+    __syncthreads();  // oldk holds the stored list (entries beyond n_list are not used)
     PHASE_MARK(0);  // state + list load
     const bool full = (st.n_list == C);
     const uint64_t worst = full ? oldk[C - 1] : KEY_SENTINEL;
@@ -545,6 +549,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
             if (open && n_par + pos < st.W) {
                 parents[n_par + pos] = key_id(lw[i]);
                 lw[i] |= 1ull;
+                pool[i] = lw[i];  // ranks below the first inserted entry are not rewritten below
             }
             n_par = min(st.W, n_par + tot);
         }
@@ -556,10 +561,12 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         overflow = true;
         n_par = 0;
     }
-    // write back what changed: the whole list after a merge, else only the ranks whose
-    // expanded bit may have been set
-    const int n_store = (m > 0) ? n_list : lim;
-    for (int i = threadIdx.x; i < n_store; i += BLOCK) pool[i] = lw[i];
+    // write back what moved: the ranks from the first inserted entry on (the chosen parents
+    // have already stored their expanded bit)
+    if (m > 0) {
+        const int first_moved = lower_bound_keys(oldk, st.n_list, newk[0]);
+        for (int i = first_moved + threadIdx.x; i < n_list; i += BLOCK) pool[i] = lw[i];
+    }
     if (n_par == 0) {
         if (threadIdx.x == 0) {
             st.n_list = n_list;
