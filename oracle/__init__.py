@@ -37,7 +37,7 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         _lib.oracle_num_threads.restype = ctypes.c_int
-        for name in ("oracle_score_pairs", "oracle_search", "oracle_brute_force"):
+        for name in ("oracle_score_pairs", "oracle_search", "oracle_search_walkers", "oracle_brute_force"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -148,6 +148,43 @@ def search(emb: np.ndarray, adj: np.ndarray, users: np.ndarray, mlp: Mlp, entrie
     if trace:
         out.update(n_scored=n_scored, n_expanded=n_expanded, n_iters=n_iters, visited=visited,
                    worst=worst)
+    return out
+
+
+def search_walkers(emb: np.ndarray, adj: np.ndarray, users: np.ndarray, mlp: Mlp, entries: np.ndarray,
+                   T: int, k: int, act_round: int = 0, n_threads: int = 1, trace: bool = False,
+                   visited_cap: int = 0) -> Dict:
+    """Paper-literal inter-candidate search (Algorithm 1 read as independent walkers): one walker
+    per seed, T greedy hops each (a walker moves to the best of the neighbours it has newly scored
+    and dies when it has none), one shared visited set and one shared result list per query.
+    Returns ids [Q,k], scores [Q,k] and, with trace=True, n_scored / n_expanded / n_iters and
+    visited [Q,visited_cap]."""
+    lib = _load()
+    emb, dt = _table(emb)
+    users, dtu = _table(users)
+    assert dt == dtu
+    adj = np.ascontiguousarray(adj, dtype=np.int32)
+    entries = np.ascontiguousarray(entries, dtype=np.int32)
+    Q, E = entries.shape
+    assert users.shape[0] == Q
+    ids = np.empty((Q, k), dtype=np.int32)
+    scores = np.empty((Q, k), dtype=np.float32)
+    n_scored = np.zeros(Q, dtype=np.int64) if trace else None
+    n_expanded = np.zeros(Q, dtype=np.int64) if trace else None
+    n_iters = np.zeros(Q, dtype=np.int32) if trace else None
+    visited = np.empty((Q, visited_cap), dtype=np.int32) if trace and visited_cap > 0 else None
+    rc = lib.oracle_search_walkers(
+        _ptr(emb), dt, ctypes.c_int64(emb.shape[0]), int(emb.shape[1]), _ptr(adj),
+        int(adj.shape[1]), _ptr(users), int(users.shape[1]), ctypes.c_int64(Q), mlp.n_layers,
+        _ptr(mlp.dims), _ptr(mlp.W), _ptr(mlp.b), _ptr(mlp.head_w), int(act_round),
+        _ptr(entries), int(E), int(T), int(k), _ptr(ids), _ptr(scores), _ptr(n_scored),
+        _ptr(n_expanded), _ptr(n_iters), _ptr(visited),
+        ctypes.c_int64(visited_cap if visited is not None else 0), int(n_threads))
+    if rc != 0:
+        raise ValueError(f"oracle_search_walkers failed rc={rc}")
+    out = {"ids": ids, "scores": scores}
+    if trace:
+        out.update(n_scored=n_scored, n_expanded=n_expanded, n_iters=n_iters, visited=visited)
     return out
 
 

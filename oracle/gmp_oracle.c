@@ -330,6 +330,116 @@ int oracle_search(const void *emb, int dtype, int64_t N, int d, const int32_t *a
     return fail ? -2 : 0;
 }
 
+/* Paper-literal inter-candidate search (Algorithm 1 read as K independent walkers sharing one
+ * result container; Sec. 3.2: "execute k parallel search processes with different initial
+ * seeds; each search process traverses the graph by visiting the most relevant neighbours; a
+ * shared max heap ranks the current most relevant items among processes").
+ *
+ * Per query: every distinct in-range seed, in the order given, is scored, pushed into the
+ * shared list and becomes the position of one walker (walker index = position of the seed in
+ * the entries row).  Then T hops: in walker order, every live walker looks at the R neighbours
+ * of its position; the ones no walker of this query has scored before (shared visited set,
+ * first occurrence wins) are scored and pushed; the walker moves to the best of ITS newly
+ * scored neighbours (score desc, id asc) and dies if it has none.  All walkers of a hop read
+ * their neighbours before any of them moves.  Result: the k best of everything scored. */
+int oracle_search_walkers(const void *emb, int dtype, int64_t N, int d, const int32_t *adj, int R,
+                          const void *users, int d_u, int64_t Q, int n_layers, const int32_t *dims,
+                          const float *W, const float *b, const float *head_w, int act_round,
+                          const int32_t *entries, int E, int T, int k, int32_t *out_ids,
+                          float *out_scores, int64_t *n_scored, int64_t *n_expanded,
+                          int32_t *n_iters, int32_t *visited_out, int64_t visited_cap,
+                          int n_threads) {
+    if (n_layers < 1 || dims[0] != d_u + d || k < 1 || E < 1 || R < 1 || T < 0) return -1;
+    mlp_t m = make_mlp(n_layers, dims, W, b, head_w, act_round);
+    if (n_threads < 1) n_threads = 1;
+    int fail = 0;
+#pragma omp parallel num_threads(n_threads)
+    {
+        double *x = (double *)malloc(sizeof(double) * (size_t)(dims[0] + 2 * m.max_width));
+        double *h0 = x + dims[0], *h1 = h0 + m.max_width;
+        uint8_t *visited = (uint8_t *)malloc((size_t)((N + 7) / 8));
+        entry_t *list = (entry_t *)malloc(sizeof(entry_t) * ((size_t)k + (size_t)E * R + (size_t)E));
+        int32_t *pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)E);   /* walker -> item, -1 dead */
+        entry_t *best = (entry_t *)malloc(sizeof(entry_t) * (size_t)E);
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t q = 0; q < Q; ++q) {
+            if (!x || !visited || !list || !pos || !best) {
+                fail = 1;
+                continue;
+            }
+            memset(visited, 0, (size_t)((N + 7) / 8));
+            int64_t scored = 0, expanded = 0;
+            int len = 0;
+            if (visited_out)
+                for (int64_t i = 0; i < visited_cap; ++i) visited_out[q * visited_cap + i] = -1;
+            for (int e = 0; e < E; ++e) {
+                int32_t v = entries[q * E + e];
+                pos[e] = -1;
+                if (v < 0 || v >= N || bit_get(visited, v)) continue;
+                bit_set(visited, v);
+                pos[e] = v;
+                build_input(x, users, dtype, d_u, q, emb, d, v);
+                list[len].score = relevance(&m, x, h0, h1);
+                list[len].id = v;
+                list[len].expanded = 0;
+                ++len;
+                if (visited_out && scored < visited_cap) visited_out[q * visited_cap + scored] = v;
+                ++scored;
+            }
+            qsort(list, (size_t)len, sizeof(entry_t), entry_cmp);
+            if (len > k) len = k;
+            int t = 0;
+            for (; t < T; ++t) {
+                int live = 0;
+                for (int e = 0; e < E; ++e) live += (pos[e] >= 0);
+                if (!live) break;
+                expanded += live;
+                for (int e = 0; e < E; ++e) {
+                    int have = 0;
+                    if (pos[e] >= 0)
+                        for (int s = 0; s < R; ++s) {
+                            int32_t v = adj[(int64_t)pos[e] * R + s];
+                            if (v < 0 || v >= N || bit_get(visited, v)) continue;
+                            bit_set(visited, v);
+                            build_input(x, users, dtype, d_u, q, emb, d, v);
+                            entry_t c;
+                            c.score = relevance(&m, x, h0, h1);
+                            c.id = v;
+                            c.expanded = 0;
+                            list[len++] = c;
+                            if (!have || entry_cmp(&c, &best[e]) < 0) best[e] = c;
+                            have = 1;
+                            if (visited_out && scored < visited_cap)
+                                visited_out[q * visited_cap + scored] = v;
+                            ++scored;
+                        }
+                    /* positions change only after every walker has read its neighbours: they
+                       are taken from pos[], which is rewritten below */
+                    best[e].expanded = have;
+                }
+                for (int e = 0; e < E; ++e)
+                    if (pos[e] >= 0) pos[e] = best[e].expanded ? best[e].id : -1;
+                qsort(list, (size_t)len, sizeof(entry_t), entry_cmp);
+                if (len > k) len = k;
+            }
+            for (int i = 0; i < k; ++i) {
+                out_ids[q * k + i] = i < len ? list[i].id : -1;
+                out_scores[q * k + i] = i < len ? list[i].score : -INFINITY;
+            }
+            if (n_scored) n_scored[q] = scored;
+            if (n_expanded) n_expanded[q] = expanded;
+            if (n_iters) n_iters[q] = t;
+        }
+        free(x);
+        free(visited);
+        free(list);
+        free(pos);
+        free(best);
+    }
+    return fail ? -2 : 0;
+}
+
+
 /* exhaustive top-k of the same relevance (ground truth for recall) */
 int oracle_brute_force(const void *emb, int dtype, int64_t N, int d, const void *users, int d_u,
                        int64_t Q, int n_layers, const int32_t *dims, const float *W,

@@ -159,6 +159,81 @@ def test_complete_layers_equal_brute_force():
     assert np.array_equal(got["scores"], sc)
 
 
+# ----------------------------------------------------------------------------- walkers (paper-literal variant)
+@pytest.mark.parametrize("case", json.load(open(os.path.join(GOLD, "walker_trajectories.json")))["cases"],
+                         ids=lambda c: c["name"])
+def test_walker_trajectory_by_hand(case):
+    adj, emb, mlp = _monotone_problem(case["N"], case["R"], case["monotone"])
+    users = np.zeros((1, 2), np.float32)
+    entries = np.asarray([case["seed"]], np.int32)
+    r = oracle.search_walkers(emb, adj, users, mlp, entries, case["T"], case["k"], trace=True, visited_cap=64)
+    assert r["ids"][0].tolist() == case["expected_ids"]
+    vis = case["expected_visited_in_order"]
+    want = list(range(*vis["range"])) if "range" in vis else vis["list"]
+    assert [v for v in r["visited"][0].tolist() if v >= 0] == want
+    assert int(r["n_scored"][0]) == case["n_scored"]
+    assert int(r["n_expanded"][0]) == case["n_expanded"]
+    assert int(r["n_iters"][0]) == case["n_iters"]
+
+
+def _walkers_reference(scores, adj, seeds, T, k):
+    """The walker search written independently with dicts: returns the k best visited ids."""
+    seen, where = {}, []
+    for s in seeds:
+        if 0 <= s < len(scores) and s not in seen:
+            seen[s] = scores[s]
+            where.append(s)
+        else:
+            where.append(None)
+    for _ in range(T):
+        if all(w is None for w in where):
+            break
+        moves = []
+        for w in where:
+            mine = []
+            if w is not None:
+                for v in adj[w]:
+                    v = int(v)
+                    if v not in seen:
+                        seen[v] = scores[v]
+                        mine.append(v)
+            moves.append(min(mine, key=lambda v: (-scores[v], v)) if mine else None)
+        where = moves
+    return sorted(seen, key=lambda v: (-seen[v], v))[:k]
+
+
+def test_walkers_equal_an_independent_implementation():
+    wl, mlp = _tiny(31, N=500, Q=5, E=4, R=6)
+    entries = wl["entries"].copy()
+    entries[1, 2] = entries[1, 0]      # a repeated seed starts no second walker
+    entries[2, 1] = -5                 # nor does an invalid one
+    for T, k in ((1, 10), (4, 25), (12, 60)):
+        got = oracle.search_walkers(wl["emb"], wl["adj"], wl["users"], mlp, entries, T, k)
+        for q in range(5):
+            s = oracle.score_pairs(wl["emb"], wl["users"], mlp, np.full(500, q), np.arange(500)).astype(np.float64)
+            want = _walkers_reference(s, wl["adj"], [int(e) for e in entries[q]], T, k)
+            assert got["ids"][q].tolist() == want + [-1] * (k - len(want))
+
+
+def test_walkers_on_a_complete_graph_find_the_best_items_in_one_hop():
+    wl, mlp = _tiny(32, N=60, Q=4, E=3)
+    n = 60
+    adj = (np.arange(n - 1)[None, :] + (np.arange(n - 1)[None, :] >= np.arange(n)[:, None])).astype(np.int32)
+    got = oracle.search_walkers(wl["emb"], adj, wl["users"], mlp, wl["entries"] % n, 1, 12)
+    ids, sc = _rank_all(wl["emb"], wl["users"], mlp, 12)
+    assert np.array_equal(got["ids"], ids) and np.array_equal(got["scores"], sc)
+
+
+def test_single_walker_on_monotone_scores_is_the_flat_search_with_w1():
+    # with strictly increasing relevance along the ring, greedy hops and best-first expansion coincide
+    adj, emb, mlp = _monotone_problem(300, 8, "increasing")
+    users = np.zeros((1, 2), np.float32)
+    entries = np.asarray([[7]], np.int32)
+    a = oracle.search_walkers(emb, adj, users, mlp, entries, 9, 20)
+    b = oracle.search(emb, adj, users, mlp, entries, 1, 4, 20, 9)
+    assert np.array_equal(a["ids"], b["ids"])
+
+
 # ----------------------------------------------------------------------------- brute force
 def test_brute_force_is_the_exhaustive_ranking():
     wl, mlp = _tiny(11)
