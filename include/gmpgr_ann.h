@@ -186,6 +186,25 @@ int ann_search_layers(const ann_graph *const *graphs, int32_t n_layers, const an
                       int32_t *out_ids_dev, float *out_scores_dev, void *stream);
 
 /*
+ * Paper-literal inter-candidate search (Algorithm 1 read as independent search processes that
+ * share one result container; Sec. 3.2), for comparison with the joint best-first rule of
+ * ann_search.  One walker per distinct in-range seed (E <= 1024 / R of them).  Per hop every live
+ * walker scores the neighbours of its position that no walker of the query has scored before
+ * (walkers in seed order, first occurrence wins; all walkers read their neighbours before any
+ * moves) and moves to the best of its own newly scored neighbours (score descending, id
+ * ascending); a walker without one stops.  After T >= 1 hops, or when every walker has
+ * stopped, the k best of everything scored are returned, padded with (-1, -inf).
+ * The call only enqueues work.  Counters as for ann_search (nodes_expanded counts walker
+ * positions expanded).  Workspace: ann_search_walkers_workspace_bytes (0 on invalid arguments).
+ */
+size_t ann_search_walkers_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E,
+                                          int32_t T, int32_t k);
+int ann_search_walkers(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
+                       const int32_t *entry_dev, int32_t E, int32_t T, int32_t k,
+                       void *workspace_dev, size_t workspace_bytes, int32_t *out_ids_dev,
+                       float *out_scores_dev, void *stream);
+
+/*
  * Continuous batching (Sec. 3.2, Q-HiPANNS and Algorithm 2: requests of different users arrive
  * and finish at different times and are aggregated into common batches).  Q_total queries are
  * served by `slots` search states: a query enters the first state that becomes free, in index

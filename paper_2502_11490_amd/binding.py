@@ -20,7 +20,8 @@ _lib = None
 EXPORTS = [
     "ann_graph_load", "ann_graph_free", "ann_mlp_load", "ann_mlp_free", "ann_mlp_uses_mfma",
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
-    "ann_search_layers", "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs",
+    "ann_search_layers", "ann_search_walkers_workspace_bytes", "ann_search_walkers",
+    "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs",
     "ann_search_stats", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
@@ -76,6 +77,10 @@ def load_library():
     lib.ann_search_layers.argtypes = [ctypes.POINTER(vp), i32, vp, vp, i32, vp, i32, pi32, pi32, pi32, i32, vp, sz,
                                       vp, vp, vp]
     lib.ann_search_layers.restype = ctypes.c_int
+    lib.ann_search_walkers_workspace_bytes.argtypes = [vp, vp, i32, i32, i32, i32]
+    lib.ann_search_walkers_workspace_bytes.restype = sz
+    lib.ann_search_walkers.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, vp, sz, vp, vp, vp]
+    lib.ann_search_walkers.restype = ctypes.c_int
     lib.ann_search_stream_workspace_bytes.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32]
     lib.ann_search_stream_workspace_bytes.restype = sz
     lib.ann_search_stream.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp, vp]
@@ -255,6 +260,32 @@ def ann_search_ragged(g: Graph, m: Mlp, queries, entries, W_q, L_q, iters_q, W_m
                                L_max, k, max_iters_max, _dev_ptr(workspace, "workspace", torch.uint8),
                                workspace.numel(), _dev_ptr(out_ids, "out_ids", torch.int32),
                                _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
+    _check(rc)
+    return out_ids, out_scores
+
+
+def ann_search_walkers_workspace_bytes(g: Graph, m: Mlp, Q: int, E: int, T: int, k: int) -> int:
+    nbytes = load_library().ann_search_walkers_workspace_bytes(g.handle, m.handle, Q, E, T, k)
+    if nbytes == 0:
+        raise AnnError(-1, ann_last_error())
+    return nbytes
+
+
+def ann_search_walkers(g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.Tensor, T: int, k: int,
+                       workspace: Optional[torch.Tensor] = None, out_ids=None, out_scores=None, stream=None):
+    """One walker per seed, T greedy hops each, one shared result list.  Returns (ids [Q,k], scores [Q,k])."""
+    lib = load_library()
+    Q, E = entries.shape
+    if workspace is None:
+        workspace = torch.empty(ann_search_walkers_workspace_bytes(g, m, Q, E, T, k), dtype=torch.uint8,
+                                device=queries.device)
+    if out_ids is None:
+        out_ids, out_scores = _alloc_out(Q, k, queries.device)
+    rc = lib.ann_search_walkers(g.handle, m.handle, _dev_ptr(queries, "queries"), Q,
+                                _dev_ptr(entries, "entries", torch.int32), E, T, k,
+                                _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+                                _dev_ptr(out_ids, "out_ids", torch.int32),
+                                _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
     _check(rc)
     return out_ids, out_scores
 

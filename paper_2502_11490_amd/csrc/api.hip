@@ -99,6 +99,8 @@ bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32
     o = align256(o + (size_t)Q * p->hash_cap * 4);
     p->off_cand = o;
     o = align256(o + (size_t)Q * p->slots * 4);
+    p->off_tag = o;  // which parent (or seed) produced each survivor
+    o = align256(o + (size_t)Q * p->slots * 2);
     p->off_counts = o;
     o = align256(o + (size_t)Q * 4);
     p->off_offsets = o;
@@ -631,6 +633,55 @@ int ann_search_layers(const ann_graph *const *graphs, int32_t n_layers, const an
             return rc;
     }
     return worst;
+}
+
+size_t ann_search_walkers_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32_t T,
+                                          int32_t k) {
+    Plan p;
+    if (T < 1) {
+        set_error("need T >= 1 hops (got %d)", T);
+        return 0;
+    }
+    if (!make_plan(g, m, Q, E, E, 1, k, T, &p)) return 0;
+    return p.total;
+}
+
+int ann_search_walkers(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
+                       const int32_t *entry_dev, int32_t E, int32_t T, int32_t k, void *workspace_dev,
+                       size_t workspace_bytes, int32_t *out_ids_dev, float *out_scores_dev, void *stream) {
+    SearchArgs a;
+    if (T < 1) {
+        set_error("need T >= 1 hops (got %d)", T);
+        return ANN_EINVAL;
+    }
+    // one walker per seed: expansion width E, list capacity k, T rounds
+    if (!make_plan(g, m, Q, E, E, 1, k, T, &a.plan)) return ANN_EINVAL;
+    if (Q > 0 && (!queries_dev || !entry_dev || !out_ids_dev || !out_scores_dev)) {
+        set_error("queries_dev, entry_dev, out_ids_dev and out_scores_dev must not be null");
+        return ANN_EINVAL;
+    }
+    if (Q > 0 && (!workspace_dev || ((uintptr_t)workspace_dev & 255))) {
+        set_error("workspace_dev must be a 256-byte aligned device pointer");
+        return ANN_EINVAL;
+    }
+    if (workspace_bytes < a.plan.total) {
+        set_error("workspace holds %zu bytes, %zu needed", workspace_bytes, a.plan.total);
+        return ANN_EWORKSPACE;
+    }
+    a.g = g;
+    a.m = m;
+    a.queries = queries_dev;
+    a.entries = entry_dev;
+    a.W_q = a.L_q = a.cap_q = nullptr;
+    a.W = E;
+    a.L = 1;
+    a.cap = T;
+    a.ws = (char *)workspace_dev;
+    a.out_ids = out_ids_dev;
+    a.out_scores = out_scores_dev;
+    a.stream = (hipStream_t)stream;
+    a.walkers = true;
+    return run_search(a);
 }
 
 // Workspace of a streamed search: the workspace of a search over `slots` queries, then the slot -> query

@@ -85,7 +85,7 @@ struct Plan {
     int32_t sort_n;         // power of two >= C + slots
     int64_t M_max;          // Q * slots
     int32_t H1;             // first hidden width (user-half pre-activations), 0 if unused
-    size_t off_ctrl, off_state, off_pool, off_hash, off_cand, off_counts, off_offsets,
+    size_t off_ctrl, off_state, off_pool, off_hash, off_cand, off_tag, off_counts, off_offsets,
         off_pair_q, off_pair_id, off_scores, off_upre, off_stats;
     size_t total;
 };
@@ -128,6 +128,8 @@ struct SearchArgs {
     int32_t Q_total = 0;          // 0 = every query owns a slot
     int32_t *slot_query = nullptr;  // [plan.Q] query served by each slot, -1 = idle
     float *upre_all = nullptr;    // [Q_total][H1] user terms of all queries (MFMA path)
+    // paper-literal variant: one walker per seed, plan.max_iters_max hops (see round_kernel)
+    bool walkers = false;
 };
 
 // search_kernels.hip

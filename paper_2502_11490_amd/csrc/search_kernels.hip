@@ -118,6 +118,7 @@ __device__ void bitonic_sort(uint64_t *keys, int n) {
 //   cand          : LDS int32[n_cand]
 //   dd_key/dd_pos : LDS uint32[dd_n] each, dd_n a power of two >= 2 * n_cand (dedupe by id)
 //   bk_key/bk_cnt : LDS uint32[dd_n] each (arrivals per bucket in this pass)
+//   out_tag       : global uint16[n_new]: candidate position / tag_div of every survivor
 //   table         : global uint32[hash_cap]: hash_cap/16 buckets of 16 slots (one 64-byte line);
 //                   a bucket is filled from slot 0 up, EMPTY_SLOT = free.  An id lives in its home
 //                   bucket or, if that one is full, in the next ones up to the first bucket that
@@ -130,7 +131,7 @@ __device__ void bitonic_sort(uint64_t *keys, int n) {
 // Stores of a pass become visible to the next pass through a device-scope fence + barrier.
 __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_key, uint32_t *dd_pos,
                                  uint32_t *bk_key, uint32_t *bk_cnt, int dd_n, uint32_t *table, int hash_cap,
-                                 int64_t N, int32_t *out, int *wave_sums) {
+                                 int64_t N, int32_t *out, int *wave_sums, uint16_t *out_tag, int tag_div) {
     for (int i = threadIdx.x; i < dd_n; i += BLOCK) {
         dd_key[i] = EMPTY_SLOT;
         dd_pos[i] = 0xFFFFFFFFu;
@@ -226,7 +227,10 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
         }
         int tot;
         int pos = block_excl_count(fresh, wave_sums, &tot);
-        if (fresh) out[n_new + pos] = v;
+        if (fresh) {
+            out[n_new + pos] = v;
+            out_tag[n_new + pos] = (uint16_t)(p / tag_div);  // the parent (or seed) it came from
+        }
         n_new += tot;
     }
     return n_new;
@@ -246,7 +250,7 @@ __global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q, int keep_st
 __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entries, int E, int64_t N, QState *state,
                           uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
                           const int32_t *W_q, const int32_t *L_q, const int32_t *cap_q, int W, int L, int cap,
-                          int W_max, int L_max, int cap_max, int64_t *stats, unsigned char *smem) {
+                          int W_max, int L_max, int cap_max, int64_t *stats, unsigned char *smem, uint16_t *tag_g) {
     int dd_n = 2;
     while (dd_n < 2 * E) dd_n <<= 1;
     int32_t *cand = (int32_t *)smem;                 // [E]
@@ -266,7 +270,7 @@ __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entri
     __threadfence_block();
     __syncthreads();
     int n = filter_and_insert(cand, E, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, hash_cap, N,
-                              cand_g + (size_t)slot * slots, wave_sums);
+                              cand_g + (size_t)slot * slots, wave_sums, tag_g + (size_t)slot * slots, 1);
     if (threadIdx.x == 0) {
         QState s;
         s.t = 0;
@@ -288,10 +292,10 @@ __global__ void __launch_bounds__(BLOCK)
 init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state, uint32_t *hash,
             int hash_cap, int32_t *cand_g, int slots, int32_t *counts, const int32_t *W_q,
             const int32_t *L_q, const int32_t *cap_q, int W, int L, int cap, int W_max, int L_max,
-            int cap_max, int64_t *stats) {
+            int cap_max, int64_t *stats, uint16_t *tag_g) {
     extern __shared__ __align__(16) unsigned char smem[];
     seed_slot(blockIdx.x, blockIdx.x, entries, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W,
-              L, cap, W_max, L_max, cap_max, stats, smem);
+              L, cap, W_max, L_max, cap_max, stats, smem, tag_g);
 }
 
 // First k entries of a slot's list to row `row` of the outputs, padded with (-1, -inf).
@@ -338,7 +342,7 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
              int32_t *cand_g, int slots, int32_t *counts, const int32_t *W_q, const int32_t *L_q,
              const int32_t *cap_q, int W, int L, int cap, int W_max, int L_max, int cap_max, int64_t *stats,
              Ctrl *ctrl, int32_t *slot_query, int Q_total, const uint64_t *pool_g, int C, int k, int32_t *out_ids,
-             float *out_scores) {
+             float *out_scores, uint16_t *tag_g) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int next_s;
     const int slot = blockIdx.x;
@@ -357,7 +361,7 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
     const int next = next_s;
     if (next < 0) return;
     seed_slot(slot, next, entries, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W, L, cap,
-              W_max, L_max, cap_max, stats, smem);
+              W_max, L_max, cap_max, stats, smem, tag_g);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -455,7 +459,7 @@ __global__ void __launch_bounds__(BLOCK)
 round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, uint64_t *pool_g, int C,
              uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
              const int32_t *__restrict__ offsets, const float *__restrict__ scores, int new_cap,
-             int W_max, int64_t *stats) {
+             int W_max, int64_t *stats, uint16_t *tag_g, int walkers) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int q = blockIdx.x;
     PHASE_START
@@ -466,9 +470,11 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     uint64_t *keys = (uint64_t *)(wave_sums + 8);             // [C]       merged list
     uint64_t *oldk = keys + C;                                // [C]       list as stored
     uint64_t *newk = oldk + C;                                // [new_cap] new entries, sorted
+    uint64_t *best = newk + new_cap;                          // [W_max]   walkers: best new child of each
     int32_t *cand = (int32_t *)keys;                          // [slots]
     uint64_t *pool = pool_g + (size_t)q * C;
     int32_t *cand_q = cand_g + (size_t)q * slots;
+    uint16_t *tag_q = tag_g + (size_t)q * slots;
 
     // Everything the round needs first is requested at once, before any of it is looked at (the
     // whole list, not only its n_list valid entries): the workgroups of a launch start together,
@@ -489,6 +495,9 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     uint32_t *bk_key = dd_pos + dd_n;
     uint32_t *bk_cnt = bk_key + dd_n;
 
+    if (walkers)
+        for (int i = threadIdx.x; i < W_max; i += BLOCK) best[i] = KEY_SENTINEL;
+
     // 1. merge the scores of the previous round (or of the seeds) into the sorted list
     __syncthreads();  // oldk holds the stored list (entries beyond n_list are not used)
     PHASE_MARK(0);  // state + list load
@@ -502,6 +511,8 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         if (j < n_prev) {
             key = make_key(scores[off + j], cand_q[j], 0u);
             keep = key < worst;
+            // walkers: the best newly scored neighbour of each walker, whether it enters the list or not
+            if (walkers) atomicMin((unsigned long long *)&best[tag_q[j]], (unsigned long long)key);
         }
         int tot;
         int pos = block_excl_count(keep, wave_sums, &tot);
@@ -537,10 +548,24 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     uint64_t *lw = const_cast<uint64_t *>(list);
 
     // 2. termination test and choice of the parents
-    int n_par = 0;
+    int n_par = 0, n_live = 0;
     const bool capped = (st.cap > 0 && st.t >= st.cap);
-    const int lim = min(st.L, n_list);
-    if (!capped) {
+    const int lim = walkers ? 0 : min(st.L, n_list);
+    if (walkers && !capped) {
+        // Paper-literal variant (Alg. 1 read as independent walkers): walker s moves to the best of the
+        // neighbours it scored last round (round 0: to its seed); a walker without one is dead (-1) and
+        // contributes R invalid candidates, so that candidate position / R keeps naming the walker.
+        for (int s0 = 0; s0 < st.W; s0 += BLOCK) {
+            const int sl = s0 + threadIdx.x;
+            const bool live = sl < st.W && best[sl] != KEY_SENTINEL;
+            if (sl < st.W) parents[sl] = live ? key_id(best[sl]) : -1;
+            int tot;
+            (void)block_excl_count(live, wave_sums, &tot);
+            n_live += tot;
+        }
+        n_par = n_live > 0 ? st.W : 0;
+    }
+    if (!capped && !walkers) {
         for (int i0 = 0; i0 < lim && n_par < st.W; i0 += BLOCK) {
             int i = i0 + threadIdx.x;
             bool open = (i < lim) && !key_expanded(lw[i]);
@@ -586,14 +611,14 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     const int n_cand = n_par * R;
     for (int j = threadIdx.x; j < n_cand; j += BLOCK) {
         int p = j / R, s = j - p * R;
-        cand[j] = adj[(size_t)parents[p] * R + s];
+        cand[j] = parents[p] >= 0 ? adj[(size_t)parents[p] * R + s] : -1;
     }
     __syncthreads();
     PHASE_MARK(4);  // adjacency gather
 
     // 4. visited filter, 5. survivors of this query for the next MLP launch
     int n_new = filter_and_insert(cand, n_cand, dd_key, dd_pos, bk_key, bk_cnt, dd_n, hash + (size_t)q * hash_cap,
-                                  hash_cap, N, cand_q, wave_sums);
+                                  hash_cap, N, cand_q, wave_sums, tag_q, R);
     PHASE_MARK(5);  // dedupe + visited table
     if (threadIdx.x == 0) {
         st.n_list = n_list;
@@ -602,7 +627,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         state[q] = st;
         counts[q] = n_new;
         atomicAdd((unsigned long long *)&stats[0], (unsigned long long)n_new);
-        atomicAdd((unsigned long long *)&stats[1], (unsigned long long)n_par);
+        atomicAdd((unsigned long long *)&stats[1], (unsigned long long)(walkers ? n_live : n_par));
         atomicMax((unsigned long long *)&stats[2], (unsigned long long)st.t);
     }
 }
@@ -624,7 +649,7 @@ static int new_cap_of(const Plan &p) {
 static size_t round_smem(const Plan &p) {
     int dd_n = 2;
     while (dd_n < 2 * p.slots) dd_n <<= 1;
-    size_t lists = (size_t)(2 * p.C + new_cap_of(p)) * 8;
+    size_t lists = (size_t)(2 * p.C + new_cap_of(p) + p.W_max) * 8;
     size_t filt = (size_t)((p.slots + 3) & ~3) * 4 + (size_t)dd_n * 16;
     return (size_t)((p.W_max + 3) & ~3) * 4 + 8 * 4 + (lists > filt ? lists : filt);
 }
@@ -644,7 +669,8 @@ int launch_init(const SearchArgs &a) {
     hipLaunchKernelGGL(init_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.entries, p.E, a.g->N,
                        (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), p.hash_cap,
                        (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q,
-                       a.L_q, a.cap_q, a.W, a.L, a.cap, p.W_max, p.L_max, p.max_iters_max, stats);
+                       a.L_q, a.cap_q, a.W, a.L, a.cap, p.W_max, p.L_max, p.max_iters_max, stats,
+                       (uint16_t *)(a.ws + p.off_tag));
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
@@ -666,7 +692,7 @@ int launch_admit(const SearchArgs &a) {
                        (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q, a.L_q,
                        a.cap_q, a.W, a.L, a.cap, p.W_max, p.L_max, p.max_iters_max, (int64_t *)(a.ws + p.off_stats),
                        (Ctrl *)(a.ws + p.off_ctrl), a.slot_query, a.Q_total, (const uint64_t *)(a.ws + p.off_pool), p.C,
-                       p.k, a.out_ids, a.out_scores);
+                       p.k, a.out_ids, a.out_scores, (uint16_t *)(a.ws + p.off_tag));
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
@@ -694,7 +720,7 @@ int launch_round(const SearchArgs &a) {
                        (uint32_t *)(a.ws + p.off_hash), p.hash_cap, (int32_t *)(a.ws + p.off_cand), p.slots,
                        (int32_t *)(a.ws + p.off_counts), (const int32_t *)(a.ws + p.off_offsets),
                        (const float *)(a.ws + p.off_scores), new_cap_of(p), p.W_max,
-                       (int64_t *)(a.ws + p.off_stats));
+                       (int64_t *)(a.ws + p.off_stats), (uint16_t *)(a.ws + p.off_tag), a.walkers ? 1 : 0);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
