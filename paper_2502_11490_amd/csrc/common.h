@@ -101,11 +101,11 @@ struct Ctrl {
 // Per-query state at off_state.
 struct QState {
     int32_t t;            // rounds done
-    int32_t done;         // 1 = finished
+    int32_t done;         // bit 0 = finished, bit 1 = stopped because its visited table was full
     int32_t n_list;       // entries in the list
-    int32_t n_visited;    // ids in the visited table
+    int32_t n_visited;    // ids in the visited table = pairs scored for this query
     int32_t W, L, cap;    // this query's parameters
-    int32_t overflow;
+    int32_t n_expanded;   // nodes whose neighbours were fetched
 };
 
 bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32_t W_max,

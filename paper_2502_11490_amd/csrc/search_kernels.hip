@@ -128,7 +128,7 @@ __device__ void bitonic_sort(uint64_t *keys, int n) {
 // cost three times a plain access here): every candidate reads its whole bucket once (one line),
 // decides "seen / room / full" from that snapshot, and the candidates that arrive at the same
 // bucket in the same pass take consecutive free slots by a rank drawn from an LDS counter.
-// Stores of a pass become visible to the next pass through a device-scope fence + barrier.
+// Stores of a pass become visible to the next pass through a workgroup-scope fence + barrier.
 __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_key, uint32_t *dd_pos,
                                  uint32_t *bk_key, uint32_t *bk_cnt, int dd_n, uint32_t *table, int hash_cap,
                                  int64_t N, int32_t *out, int *wave_sums, uint16_t *out_tag, int tag_div) {
@@ -217,12 +217,15 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
             const bool more = (p0 + BLOCK < n_cand);
             if (!__syncthreads_or(active ? 1 : 0)) {
                 if (more) {
-                    __threadfence();
+                    __threadfence_block();
                     __syncthreads();
                 }
                 break;
             }
-            __threadfence();  // this pass's stores must be seen by the next pass's bucket reads
+            // This pass's stores must be seen by the next pass's bucket reads.  A table belongs to one workgroup,
+            // whose waves share a compute unit and its vector cache: workgroup scope is enough, and a device-scope
+            // fence would write the whole L2 slice back.
+            __threadfence_block();
             __syncthreads();
         }
         int tot;
@@ -281,10 +284,9 @@ __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entri
         s.W = min(max(w, 1), W_max);
         s.L = min(max(l, 1), L_max);
         s.cap = cap_max > 0 ? min(max(c, 1), cap_max) : max(c, 0);
-        s.overflow = 0;
+        s.n_expanded = 0;
         state[slot] = s;
         counts[slot] = n;
-        if (n) atomicAdd((unsigned long long *)&stats[0], (unsigned long long)n);
     }
 }
 
@@ -298,10 +300,20 @@ init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state
               L, cap, W_max, L_max, cap_max, stats, smem, tag_g);
 }
 
-// First k entries of a slot's list to row `row` of the outputs, padded with (-1, -inf).
+// First k entries of a slot's list to row `row` of the outputs, padded with (-1, -inf).  The query's
+// counters join the totals here, once per query: every workgroup adding to the same few words in
+// every round made those additions, which the memory side performs one after the other, the
+// longest part of a round.
 __device__ void emit_row(const QState *state, const uint64_t *pool_g, int C, int k, int slot, int64_t row,
-                         int32_t *out_ids, float *out_scores) {
-    const int n = state[slot].n_list;
+                         int32_t *out_ids, float *out_scores, int64_t *stats) {
+    const QState st = state[slot];
+    const int n = st.n_list;
+    if (threadIdx.x == 0) {
+        atomicAdd((unsigned long long *)&stats[0], (unsigned long long)st.n_visited);
+        atomicAdd((unsigned long long *)&stats[1], (unsigned long long)st.n_expanded);
+        atomicMax((unsigned long long *)&stats[2], (unsigned long long)st.t);
+        if (st.done & 2) atomicAdd((unsigned long long *)&stats[3], 1ull);
+    }
     const uint64_t *pool = pool_g + (size_t)slot * C;
     for (int i = threadIdx.x; i < k; i += BLOCK) {
         int32_t id = -1;
@@ -348,7 +360,7 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
     const int slot = blockIdx.x;
     if (!state[slot].done) return;  // still searching
     const int served = slot_query[slot];
-    if (served >= 0) emit_row(state, pool_g, C, k, slot, served, out_ids, out_scores);
+    if (served >= 0) emit_row(state, pool_g, C, k, slot, served, out_ids, out_scores, stats);
     if (threadIdx.x == 0) {
         int next = Q_total;
         // the counter only grows; once it has passed the total nobody needs to touch it again
@@ -595,12 +607,9 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     if (n_par == 0) {
         if (threadIdx.x == 0) {
             st.n_list = n_list;
-            st.done = 1;
-            st.overflow = overflow ? 1 : 0;
+            st.done = overflow ? 3 : 1;
             state[q] = st;
             counts[q] = -1;
-            if (overflow) atomicAdd((unsigned long long *)&stats[3], 1ull);
-            atomicMax((unsigned long long *)&stats[2], (unsigned long long)st.t);
         }
         return;
     }
@@ -624,19 +633,17 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         st.n_list = n_list;
         st.t += 1;
         st.n_visited += n_new;
+        st.n_expanded += walkers ? n_live : n_par;
         state[q] = st;
         counts[q] = n_new;
-        atomicAdd((unsigned long long *)&stats[0], (unsigned long long)n_new);
-        atomicAdd((unsigned long long *)&stats[1], (unsigned long long)(walkers ? n_live : n_par));
-        atomicMax((unsigned long long *)&stats[2], (unsigned long long)st.t);
     }
 }
 
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(BLOCK)
 emit_kernel(const QState *__restrict__ state, const uint64_t *__restrict__ pool_g, int C, int k,
-            int32_t *out_ids, float *out_scores) {
-    emit_row(state, pool_g, C, k, blockIdx.x, blockIdx.x, out_ids, out_scores);
+            int32_t *out_ids, float *out_scores, int64_t *stats) {
+    emit_row(state, pool_g, C, k, blockIdx.x, blockIdx.x, out_ids, out_scores, stats);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -728,7 +735,8 @@ int launch_round(const SearchArgs &a) {
 int launch_emit(const SearchArgs &a) {
     const Plan &p = a.plan;
     hipLaunchKernelGGL(emit_kernel, dim3(p.Q), dim3(BLOCK), 0, a.stream, (const QState *)(a.ws + p.off_state),
-                       (const uint64_t *)(a.ws + p.off_pool), p.C, p.k, a.out_ids, a.out_scores);
+                       (const uint64_t *)(a.ws + p.off_pool), p.C, p.k, a.out_ids, a.out_scores,
+                       (int64_t *)(a.ws + p.off_stats));
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
