@@ -108,6 +108,7 @@ def main() -> int:
     ap.add_argument("--profile-steps", type=int, default=3)
     ap.add_argument("--no-layers", action="store_true", help="skip the layer-by-layer search beside the headline")
     ap.add_argument("--no-stream", action="store_true", help="skip the continuous-batching run beside the headline")
+    ap.add_argument("--no-walkers", action="store_true", help="skip the walker-rule run beside the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain 256 MiB copy kernel (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -268,6 +269,28 @@ def main() -> int:
             del wss
         del users4, entries4
 
+    # ---- the walker rule (one greedy walker per seed, T hops, shared visited set and top-k list) at about
+    #      half the scored pairs of the headline; reported beside it, not part of the timed step ----
+    walkers = None
+    if not ragged and not args.no_walkers and E * cfg.R <= 1024:
+        T = 64
+        wsw = torch.empty(ann.ann_search_walkers_workspace_bytes(g, m, Q, E, T, k), dtype=torch.uint8, device="cuda:0")
+        run = lambda: ann.ann_search_walkers(g, m, users, entries, T, k, workspace=wsw)
+        run()
+        torch.cuda.synchronize()
+        t6 = time.perf_counter()
+        for _ in range(3):
+            ids_w, _ = run()
+        torch.cuda.synchronize()
+        ms_w = 1e3 * (time.perf_counter() - t6) / 3
+        stw = ann.ann_search_stats(wsw)
+        walkers = {"E": E, "T": T, "k": k, "recall_at_100": round(recall_at(ids_w[sel].cpu(), truth.cpu(), kr), 4),
+                   "ms_per_search": round(ms_w, 3), "queries_per_s": round(Q / ms_w * 1e3, 1),
+                   "pairs_scored": int(stw.pairs_scored), "rounds": int(stw.max_query_iters)}
+        log(f"walker search E={E} T={T}: recall@{kr} = {walkers['recall_at_100']}, {ms_w:.1f} ms per search, "
+            f"{stw.pairs_scored} pairs")
+        del wsw
+
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 255)
         dst = torch.empty_like(src)
@@ -374,7 +397,7 @@ def main() -> int:
             "mlp_scores_per_s": round(scores_per_s, 1),
             "pairs_scored_per_step": int(st.pairs_scored), "nodes_expanded_per_step": int(st.nodes_expanded),
             "rounds": int(st.max_query_iters), "mfma_kernel": bool(mfma), "stages": stages,
-            "layered_search": layered, "continuous_batching": streamed,
+            "layered_search": layered, "continuous_batching": streamed, "walker_search": walkers,
         },
         "roofline": roofline,
         "cpu_baseline": cpu,

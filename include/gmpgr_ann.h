@@ -129,8 +129,10 @@ size_t ann_search_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t 
  *   workspace_dev : >= ann_search_workspace_bytes(g, m, Q, E, W, L, k, max_iters) bytes,
  *                   256-byte aligned; contents need not be preserved between calls
  *   out_ids_dev   : [Q][k] int32, out_scores_dev : [Q][k] fp32 (padding: -1 / -inf)
- * With max_iters > 0 the call only enqueues work.  With max_iters = 0 it also waits on
- * `stream` every few rounds to learn whether every query has converged.
+ * With max_iters > 0 the call only enqueues work.  With max_iters = 0 it also follows the
+ * device's progress (a word in pinned host memory that the kernels update every round) to learn
+ * when every query has converged, stays a few rounds ahead of the device meanwhile, and waits
+ * on `stream` once, at the end.
  * Limits: W*R <= 1024, max(L,k) + W*R <= 4096, E <= 1024.
  * Returns ANN_EWORKSPACE (results still written, for the truncated search) if the call
  * waited on the stream and saw a query fill its visited table; with max_iters > 0 use

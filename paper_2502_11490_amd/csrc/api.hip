@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <chrono>
 #include <new>
 #include <vector>
 
@@ -117,13 +118,56 @@ bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32
     return true;
 }
 
-// One pinned int32[16] per host thread for the "has every query converged" read-back.
-static int32_t *pinned_ctrl() {
-    static thread_local int32_t *buf = nullptr;
-    if (!buf) {
-        if (hipHostMalloc((void **)&buf, 64, hipHostMallocDefault) != hipSuccess) buf = nullptr;
+// "Has every query converged": the packing step of every round stores one progress word to pinned
+// host memory (search tag, rounds packed so far, a finished bit).  The enqueuing thread reads it
+// between launches: it stops when the finished bit is up and otherwise only makes sure that it is not
+// more than AHEAD rounds in front of the device, so the stream never runs dry and no copy or
+// synchronisation is put between the kernels.  A round enqueued after the batch has finished is
+// three launches that find nothing to do.  "Finished" never reverts, so a late look is safe.
+// One word per host thread; the tag tells a search's word from an older search's.
+struct Mailbox {
+    static constexpr int AHEAD = 4;
+    volatile uint64_t *host = nullptr;
+    uint64_t *dev = nullptr;
+    uint64_t seq = 0;
+    bool ok = false;
+    bool init() {
+        if (ok) return true;
+        void *h = nullptr, *d = nullptr;
+        if (hipHostMalloc(&h, 64, hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) return false;
+        if (hipHostGetDevicePointer(&d, h, 0) != hipSuccess) return false;
+        host = (volatile uint64_t *)h;
+        dev = (uint64_t *)d;
+        *host = 0;
+        ok = true;
+        return true;
     }
-    return buf;
+    uint64_t new_tag() {
+        seq = (seq + 1) & 0xFFFFFFull;
+        if (seq == 0) seq = 1;
+        return seq << 40;
+    }
+    // Before enqueuing round `i` (0-based): 1 = the search has finished, 0 = go on, -1 = the device made no
+    // progress for a long time.
+    int gate(uint64_t tag, int64_t i) const {
+        const auto t0 = std::chrono::steady_clock::now();
+        for (int spin = 0;; ++spin) {
+            const uint64_t w = *host;
+            if ((w >> 40) == (tag >> 40)) {
+                if (w & 1ull) return 1;
+                if ((int64_t)((w & 0xFFFFFFFFFFull) >> 1) + AHEAD >= i) return 0;
+            } else if (i <= AHEAD) {
+                return 0;  // nothing reported yet
+            }
+            if ((spin & 1023) == 1023 &&
+                std::chrono::steady_clock::now() - t0 > std::chrono::seconds(30)) return -1;
+        }
+    }
+};
+
+static Mailbox *mailbox() {
+    static thread_local Mailbox box;
+    return box.init() ? &box : nullptr;
 }
 
 // Optional stage timing (ann_profile_enable): every kernel launch of a stage is bracketed by two
@@ -189,28 +233,33 @@ static int run_search(SearchArgs &a) {
         if ((rc = launch_init(a)) != ANN_OK) return rc;
     }
     const bool capped = p.max_iters_max > 0;
-    int32_t *host_ctrl = nullptr;
+    Mailbox *box = nullptr;
     if (!capped) {
-        host_ctrl = pinned_ctrl();
-        if (!host_ctrl) {
+        box = mailbox();
+        if (!box) {
             set_error("pinned host allocation failed");
             return ANN_ENOMEM;
         }
+        a.mailbox = box->dev;
+        a.mail_tag = box->new_tag();
     }
-    const int check_every = 4;
     bool overflow_seen = false;
     // a query expands only ids it has scored, so it cannot run more rounds than its visited
     // table holds ids: the loop is bounded even if no query ever reported convergence
     const int64_t round_limit = capped ? (int64_t)p.max_iters_max : (int64_t)p.hash_cap / 2 + 1;
     for (int64_t i = 0; i <= round_limit; ++i) {
+        if (box) {  // no query is running: nothing left to score or merge
+            const int g = box->gate(a.mail_tag, i);
+            if (g > 0) break;
+            if (g < 0) {
+                set_error("the device reported no progress for 30 s");
+                return ANN_EDEVICE;
+            }
+        }
+        a.round_index = (int32_t)i;
         {
             StageTimer timer(ANN_STAGE_PACK, a.stream);
             if ((rc = launch_scan_compact(a)) != ANN_OK) return rc;
-        }
-        if (!capped && i > 0 && (i % check_every) == 0) {
-            ANN_HIP_TRY(hipMemcpyAsync(host_ctrl, a.ws + p.off_ctrl, 16, hipMemcpyDeviceToHost, a.stream));
-            ANN_HIP_TRY(hipStreamSynchronize(a.stream));
-            if (host_ctrl[1] == 0) break;  // no query is running: nothing left to score or merge
         }
         if ((rc = score_batch(a)) != ANN_OK) return rc;
         {
@@ -243,17 +292,27 @@ static int run_stream(SearchArgs &a) {
     if (a.m->kernel == MLP_MFMA2)
         if ((rc = launch_user_pre(a.m, a.queries, a.Q_total, a.upre_all, a.stream)) != ANN_OK) return rc;
     if ((rc = launch_stream_reset(a)) != ANN_OK) return rc;
-    int32_t *host_ctrl = pinned_ctrl();
-    if (!host_ctrl) {
+    Mailbox *box = mailbox();
+    if (!box) {
         set_error("pinned host allocation failed");
         return ANN_ENOMEM;
     }
-    const int check_every = 4;
+    a.mailbox = box->dev;
+    a.mail_tag = box->new_tag();
     // every query ends within hash_cap / 2 + 1 rounds of its admission, and at least one slot is
     // re-used per ceil(Q_total / Q) turn-overs: a generous bound that only guards against a bug
     const int64_t per_query = p.max_iters_max > 0 ? (int64_t)p.max_iters_max + 2 : (int64_t)p.hash_cap / 2 + 3;
     const int64_t round_limit = per_query * (((int64_t)a.Q_total + p.Q - 1) / p.Q + 1);
     for (int64_t i = 0; i <= round_limit; ++i) {
+        {   // nothing running after an admission step, and nothing left to admit: every result is written
+            const int g = box->gate(a.mail_tag, i);
+            if (g > 0) break;
+            if (g < 0) {
+                set_error("the device reported no progress for 30 s");
+                return ANN_EDEVICE;
+            }
+        }
+        a.round_index = (int32_t)i;
         {
             StageTimer timer(ANN_STAGE_ROUND, a.stream);
             if ((rc = launch_admit(a)) != ANN_OK) return rc;
@@ -261,12 +320,6 @@ static int run_stream(SearchArgs &a) {
         {
             StageTimer timer(ANN_STAGE_PACK, a.stream);
             if ((rc = launch_scan_compact(a)) != ANN_OK) return rc;
-        }
-        if (i > 0 && (i % check_every) == 0) {
-            ANN_HIP_TRY(hipMemcpyAsync(host_ctrl, a.ws + p.off_ctrl, 16, hipMemcpyDeviceToHost, a.stream));
-            ANN_HIP_TRY(hipStreamSynchronize(a.stream));
-            // nothing running after an admission step, and nothing left to admit: every result is written
-            if (host_ctrl[1] == 0 && host_ctrl[2] >= a.Q_total) break;
         }
         if ((rc = score_batch(a)) != ANN_OK) return rc;
         {

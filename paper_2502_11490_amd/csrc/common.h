@@ -130,6 +130,11 @@ struct SearchArgs {
     float *upre_all = nullptr;    // [Q_total][H1] user terms of all queries (MFMA path)
     // paper-literal variant: one walker per seed, plan.max_iters_max hops (see round_kernel)
     bool walkers = false;
+    // progress word in pinned host memory, written by the packing step of every round (null = none):
+    // mail_tag | (rounds packed << 1) | finished
+    uint64_t *mailbox = nullptr;
+    uint64_t mail_tag = 0;
+    int32_t round_index = 0;
 };
 
 // search_kernels.hip

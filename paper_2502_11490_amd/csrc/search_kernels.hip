@@ -386,7 +386,7 @@ constexpr int SCAN_QPB = 16;  // queries per workgroup
 __global__ void __launch_bounds__(SCAN_BLOCK)
 scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__restrict__ cand_g, int slots,
                     int32_t *offsets, int32_t *pair_q, int32_t *pair_id, Ctrl *ctrl,
-                    const int32_t *__restrict__ slot_query) {
+                    const int32_t *__restrict__ slot_query, uint64_t *mailbox, uint64_t mail_word, int Q_total) {
     __shared__ int red[SCAN_WAVES];
     __shared__ int red_active[SCAN_WAVES];
     __shared__ int loc_off[SCAN_QPB + 1];
@@ -434,6 +434,12 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
     if (last && threadIdx.x == 0) {
         ctrl->M = loc_off[SCAN_QPB];
         ctrl->n_active = n_active;
+        if (mailbox) {
+            // progress for the enqueuing host thread: one store to pinned host memory, nobody waits for it
+            const bool finished = n_active == 0 && (Q_total <= 0 || ctrl->next_query >= Q_total);
+            __hip_atomic_store(mailbox, mail_word | (finished ? 1ull : 0ull), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
+        }
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int i = wave; i < SCAN_QPB; i += SCAN_WAVES) {
@@ -710,7 +716,8 @@ int launch_scan_compact(const SearchArgs &a) {
     hipLaunchKernelGGL(scan_compact_kernel, dim3(blocks), dim3(SCAN_BLOCK), 0, a.stream,
                        (const int32_t *)(a.ws + p.off_counts), p.Q, (const int32_t *)(a.ws + p.off_cand),
                        p.slots, (int32_t *)(a.ws + p.off_offsets), (int32_t *)(a.ws + p.off_pair_q),
-                       (int32_t *)(a.ws + p.off_pair_id), (Ctrl *)(a.ws + p.off_ctrl), a.slot_query);
+                       (int32_t *)(a.ws + p.off_pair_id), (Ctrl *)(a.ws + p.off_ctrl), a.slot_query, a.mailbox,
+                       a.mail_tag | ((uint64_t)(uint32_t)(a.round_index + 1) << 1), a.Q_total);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
