@@ -37,8 +37,11 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         _lib.oracle_num_threads.restype = ctypes.c_int
-        for name in ("oracle_score_pairs", "oracle_search", "oracle_search_walkers", "oracle_brute_force"):
+        for name in ("oracle_score_pairs", "oracle_search", "oracle_search_walkers", "oracle_brute_force",
+                     "oracle_users_add_noise"):
             getattr(_lib, name).restype = ctypes.c_int
+        _lib.oracle_noise_element.restype = ctypes.c_double
+        _lib.oracle_philox4x32_10.restype = None
     return _lib
 
 
@@ -238,3 +241,31 @@ def recall_at(found_ids: np.ndarray, truth_ids: np.ndarray, k: int) -> float:
     for f, t in zip(found_ids[:, :k], truth_ids[:, :k]):
         hits += len(set(int(v) for v in f if v >= 0) & set(int(v) for v in t))
     return hits / float(truth_ids.shape[0] * k)
+
+
+def philox4x32_10(ctr, key):
+    """One Philox4x32-10 block: ctr = 4 words, key = 2 words -> 4 output words."""
+    c = (ctypes.c_uint32 * 4)(*[int(x) & 0xFFFFFFFF for x in ctr])
+    k = (ctypes.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+    out = (ctypes.c_uint32 * 4)()
+    _load().oracle_philox4x32_10(c, k, out)
+    return [int(x) for x in out]
+
+
+def noise_element(seed: int, stream: int, e: int) -> float:
+    """The standard normal variate that element e of a [Q][d] user array receives (Eq. 5)."""
+    return float(_load().oracle_noise_element(ctypes.c_uint64(seed), ctypes.c_uint64(stream), ctypes.c_uint64(e)))
+
+
+def users_add_noise(users: np.ndarray, sigma: float, seed: int, stream: int = 0) -> np.ndarray:
+    """users + sigma * h~ with h~ ~ N(0, I) (Eq. 5: the serendipity vector added to the user half of the
+    metric input), drawn by the counter-based generator described in gmp_oracle.c; same dtype as `users`
+    (fp32, or bf16 bit patterns as uint16)."""
+    users, dt = _table(users)
+    out = np.empty_like(users)
+    rc = _load().oracle_users_add_noise(_ptr(users), dt, ctypes.c_int64(users.shape[0]), int(users.shape[1]),
+                                        ctypes.c_double(sigma), ctypes.c_uint64(seed), ctypes.c_uint64(stream),
+                                        _ptr(out))
+    if rc != 0:
+        raise ValueError(f"oracle_users_add_noise failed rc={rc}")
+    return out

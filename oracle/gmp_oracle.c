@@ -20,8 +20,9 @@
  * Readings adopted where the paper is silent (kept identical in the GPU path):
  *   - ReLU after every hidden layer, none on the last layer; each head goes
  *     through a logistic sigmoid before the weighted sum;
- *   - the serendipity vector of Eq. 5 is not drawn here: a caller who wants it
- *     adds it to the user vector beforehand;
+ *   - the serendipity vector of Eq. 5 is not drawn inside the search: a caller who
+ *     wants it adds it to the user vectors beforehand, with oracle_users_add_noise
+ *     (a counter-based generator, so that the same draw can be repeated anywhere);
  *   - one sorted list per query of capacity C = max(L, k); per iteration the
  *     first <= W not-yet-expanded entries among the first L ranks are expanded
  *     together; order everywhere is (score descending, id ascending);
@@ -41,7 +42,9 @@
  * the relevance, a library MLP forward pass, brute-force equality on complete
  * graphs / L >= N, a hand-derived ring-graph trajectory, an independently
  * written priority-queue best-first search for W = E = 1, monotonicity and
- * uniqueness invariants, and entry/batch permutation symmetries.  The recall
+ * uniqueness invariants, and entry/batch permutation symmetries; for the noise
+ * draw the generator's published known-answer vectors, goodness-of-fit of the
+ * variates and of the Box-Muller pairs, and an independent bf16 rounding.  The recall
  * level reached on the synthetic graphs has no external pin: "parity unpinned"
  * for that single quantity.
  */
@@ -476,4 +479,71 @@ int oracle_brute_force(const void *emb, int dtype, int64_t N, int d, const void 
         free(all);
     }
     return fail ? -2 : 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Serendipity vector (Eq. 5): the user half of the metric input is h_u + h~ with h~ drawn from a
+ * normal distribution, which the paper gives as N(0, 1); sigma scales it (sigma = 1 is the paper's).
+ *
+ * The draw is a pure function of (seed, stream, element index), so any implementation repeats it:
+ *   - Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3",
+ *     SC'11): counter = (block lo, block hi, stream lo, stream hi), key = (seed lo, seed hi), where
+ *     element e = q * d + c of the [Q][d] array lies in block e / 4 and takes output word e % 4;
+ *   - uniforms u_i = (x_i + 1/2) / 2^32, strictly inside (0, 1);
+ *   - Box-Muller on the pairs (u_0, u_1) and (u_2, u_3): r = sqrt(-2 ln u_a), t = 2 pi u_b,
+ *     the even word of a pair takes r cos t, the odd word r sin t;
+ *   - out = user + sigma * z in double, rounded double -> fp32 (-> bf16 for a bf16 array).
+ */
+static void mulhilo32(uint32_t a, uint32_t b, uint32_t *hi, uint32_t *lo) {
+    uint64_t p = (uint64_t)a * (uint64_t)b;
+    *hi = (uint32_t)(p >> 32);
+    *lo = (uint32_t)p;
+}
+
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint32_t hi0, lo0, hi1, lo1;
+        mulhilo32(0xD2511F53u, c0, &hi0, &lo0);
+        mulhilo32(0xCD9E8D57u, c2, &hi1, &lo1);
+        uint32_t n0 = hi1 ^ c1 ^ k0, n1 = lo1, n2 = hi0 ^ c3 ^ k1, n3 = lo0;
+        c0 = n0, c1 = n1, c2 = n2, c3 = n3;
+        k0 += 0x9E3779B9u; /* golden ratio */
+        k1 += 0xBB67AE85u; /* sqrt(3) - 1 */
+    }
+    out[0] = c0, out[1] = c1, out[2] = c2, out[3] = c3;
+}
+
+/* the standard normal variate of element e (see above) */
+double oracle_noise_element(uint64_t seed, uint64_t stream, uint64_t e) {
+    const uint64_t block = e >> 2;
+    const int word = (int)(e & 3);
+    const uint32_t ctr[4] = {(uint32_t)block, (uint32_t)(block >> 32), (uint32_t)stream, (uint32_t)(stream >> 32)};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t x[4];
+    oracle_philox4x32_10(ctr, key, x);
+    const int a = word & 2; /* first word of the pair */
+    const double ua = ((double)x[a] + 0.5) / 4294967296.0;
+    const double ub = ((double)x[a + 1] + 0.5) / 4294967296.0;
+    const double r = sqrt(-2.0 * log(ua));
+    const double t = 6.283185307179586476925286766559 * ub;
+    return (word & 1) ? r * sin(t) : r * cos(t);
+}
+
+int oracle_users_add_noise(const void *users, int dtype, int64_t Q, int d, double sigma, uint64_t seed,
+                           uint64_t stream, void *out) {
+    if (Q < 0 || d < 1 || (dtype != ORACLE_F32 && dtype != ORACLE_BF16)) return -1;
+    for (int64_t e = 0; e < Q * (int64_t)d; ++e) {
+        const double v = load_elem(users, dtype, e) + sigma * oracle_noise_element(seed, stream, (uint64_t)e);
+        if (dtype == ORACLE_BF16) {
+            float f = (float)round_to_bf16(v);
+            uint32_t u;
+            memcpy(&u, &f, 4);
+            ((uint16_t *)out)[e] = (uint16_t)(u >> 16);
+        } else {
+            ((float *)out)[e] = (float)v;
+        }
+    }
+    return 0;
 }
