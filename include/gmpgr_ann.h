@@ -218,7 +218,8 @@ int ann_search_walkers(const ann_graph *g, const ann_mlp *m, const void *queries
  *   queries_dev [Q_total][d_user], entry_dev [Q_total][E], out_ids_dev / out_scores_dev [Q_total][k]
  *   slots     : >= 1; more slots than queries leaves the surplus idle
  *   max_iters : rounds per query, 0 = until converged
- * The call waits on `stream` every few rounds (it has to learn when the last query is done).
+ * The call follows the device's progress as ann_search with max_iters = 0 does (it has to learn
+ * when the last query is done) and waits on `stream` at the end.
  * Workspace: ann_search_stream_workspace_bytes with the same arguments (0 on invalid ones); its
  * size grows with `slots`, plus 4 * first-hidden-width bytes per query.  ann_search_stats reads
  * the counters of all Q_total queries.
@@ -230,6 +231,22 @@ int ann_search_stream(const ann_graph *g, const ann_mlp *m, const void *queries_
                       const int32_t *entry_dev, int32_t E, int32_t slots, int32_t W, int32_t L,
                       int32_t k, int32_t max_iters, void *workspace_dev, size_t workspace_bytes,
                       int32_t *out_ids_dev, float *out_scores_dev, void *stream);
+
+/*
+ * Serendipity vector of the metric input (Eq. 5: the user half of the input is h_u + h~ with
+ * h~ ~ N(0, I)): out_dev[q][c] = users_dev[q][c] + sigma * z(seed, draw, q * d + c), for the
+ * caller to pass as `queries_dev` of a search.  sigma = 1 is the paper's distribution, 0 copies.
+ * z is a pure function of its arguments (so the same vectors can be drawn again, anywhere):
+ * Philox4x32-10 with counter (e / 4, draw) and key seed, uniforms (x + 1/2) / 2^32, Box-Muller on
+ * the word pairs (0,1) and (2,3) with the cosine on the even element; the sum is formed in fp64 and
+ * rounded to fp32 (then to bf16, nearest even, for ANN_BF16).  `draw` tells independent draws with
+ * one seed apart (one per batch of requests, say).
+ *   users_dev, out_dev : [Q][d] device arrays of `dtype` (ANN_F32 / ANN_BF16); may be the same array
+ * Only enqueues one kernel on `stream`; ANN_EINVAL on bad arguments (Q < 0, d < 1, negative or
+ * non-finite sigma, null arrays with Q > 0).
+ */
+int ann_users_add_noise(const void *users_dev, void *out_dev, int32_t Q, int32_t d, int32_t dtype,
+                        double sigma, uint64_t seed, uint64_t draw, void *stream);
 
 /*
  * Relevance (Eq. 5-8) of an explicit list of M pairs: out_dev[r] = relevance(user q_idx[r],

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     ann_profile_enable,
     ann_profile_read,
     ann_score_pairs,
+    ann_users_add_noise,
     ann_search,
     ann_search_layers,
     ann_search_layers_workspace_bytes,

@@ -21,7 +21,7 @@ EXPORTS = [
     "ann_graph_load", "ann_graph_free", "ann_mlp_load", "ann_mlp_free", "ann_mlp_uses_mfma",
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
     "ann_search_layers", "ann_search_walkers_workspace_bytes", "ann_search_walkers",
-    "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs",
+    "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs", "ann_users_add_noise",
     "ann_search_stats", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
@@ -87,6 +87,8 @@ def load_library():
     lib.ann_search_stream.restype = ctypes.c_int
     lib.ann_score_pairs.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, i32, vp]
     lib.ann_score_pairs.restype = ctypes.c_int
+    lib.ann_users_add_noise.argtypes = [vp, vp, i32, i32, i32, ctypes.c_double, ctypes.c_uint64, ctypes.c_uint64, vp]
+    lib.ann_users_add_noise.restype = ctypes.c_int
     lib.ann_search_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
     lib.ann_search_stats.restype = ctypes.c_int
     lib.ann_profile_enable.argtypes = [ctypes.c_int]
@@ -368,6 +370,22 @@ def ann_score_pairs(g: Graph, m: Mlp, queries: torch.Tensor, q_idx: torch.Tensor
                              _dev_ptr(q_idx, "q_idx", torch.int32), _dev_ptr(item, "item", torch.int32),
                              _dev_ptr(out, "out", torch.float32), tile_rows, _stream_ptr(stream))
     _check(rc)
+    return out
+
+
+def ann_users_add_noise(users: torch.Tensor, sigma: float, seed: int, draw: int = 0,
+                        out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """users + sigma * N(0, I) (Eq. 5), same dtype and shape; `out` may be `users`."""
+    if users.dim() != 2:
+        raise ValueError("users must be [Q][d]")
+    if out is None:
+        out = torch.empty_like(users)
+    if out.shape != users.shape or out.dtype != users.dtype:
+        raise ValueError("out must have the shape and dtype of users")
+    Q, d = users.shape
+    _check(load_library().ann_users_add_noise(_dev_ptr(users, "users") if Q else None, _dev_ptr(out, "out") if Q else None,
+                                              Q, d, _dtype_code(users), float(sigma), int(seed), int(draw),
+                                              _stream_ptr(stream)))
     return out
 
 

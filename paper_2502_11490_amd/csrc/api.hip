@@ -805,6 +805,20 @@ int ann_search_stream(const ann_graph *g, const ann_mlp *m, const void *queries_
     return run_stream(a);
 }
 
+int ann_users_add_noise(const void *users_dev, void *out_dev, int32_t Q, int32_t d, int32_t dtype, double sigma,
+                        uint64_t seed, uint64_t draw, void *stream) {
+    if (Q < 0 || d < 1 || (dtype != ANN_F32 && dtype != ANN_BF16) || !(sigma >= 0.0) || !(sigma < INFINITY)) {
+        set_error("need Q >= 0, d >= 1, dtype ANN_F32 or ANN_BF16, finite sigma >= 0");
+        return ANN_EINVAL;
+    }
+    if (Q == 0) return ANN_OK;
+    if (!users_dev || !out_dev) {
+        set_error("users_dev and out_dev must not be null");
+        return ANN_EINVAL;
+    }
+    return launch_users_add_noise(users_dev, out_dev, (int64_t)Q * d, dtype, sigma, seed, draw, (hipStream_t)stream);
+}
+
 int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int64_t M,
                     const int32_t *q_idx_dev, const int32_t *item_dev, float *out_dev, int32_t tile_rows,
                     void *stream) {

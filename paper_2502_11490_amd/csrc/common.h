@@ -145,6 +145,10 @@ int launch_emit(const SearchArgs &a);
 int launch_stream_reset(const SearchArgs &a);
 int launch_admit(const SearchArgs &a);
 
+// noise.hip: out = users + sigma * N(0, I), element-indexed counter-based draw (Eq. 5)
+int launch_users_add_noise(const void *users, void *out, int64_t n_elem, int dtype, double sigma, uint64_t seed,
+                           uint64_t stream_id, hipStream_t stream);
+
 // mlp_alu.hip / mlp_mfma.hip: score `*M_dev` (<= M_max) pairs; M_dev is read on the device.
 int launch_mlp_alu(const ann_graph *g, const ann_mlp *m, const void *queries, const int32_t *pair_q,
                    const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
