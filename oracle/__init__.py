@@ -40,6 +40,8 @@ def _load():
         for name in ("oracle_score_pairs", "oracle_search", "oracle_search_walkers", "oracle_brute_force",
                      "oracle_users_add_noise"):
             getattr(_lib, name).restype = ctypes.c_int
+        _lib.oracle_e4m3_encode.restype = ctypes.c_int64
+        _lib.oracle_e4m3_quantize.restype = ctypes.c_int64
         _lib.oracle_noise_element.restype = ctypes.c_double
         _lib.oracle_philox4x32_10.restype = None
     return _lib
@@ -268,4 +270,25 @@ def users_add_noise(users: np.ndarray, sigma: float, seed: int, stream: int = 0)
                                         _ptr(out))
     if rc != 0:
         raise ValueError(f"oracle_users_add_noise failed rc={rc}")
+    return out
+
+
+def e4m3_encode(a: np.ndarray, scale: float = 1.0) -> np.ndarray:
+    """The e4m3 codes (uint8) of scale * a, nearest even, magnitudes above 448 clamped (and counted:
+    raises if any was)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    out = np.empty(a.shape, dtype=np.uint8)
+    n = _load().oracle_e4m3_encode(_ptr(a), ctypes.c_int64(a.size), ctypes.c_double(scale), _ptr(out))
+    if n:
+        raise ValueError(f"{n} values exceed the e4m3 range at scale {scale}")
+    return out
+
+
+def e4m3_quantize(a: np.ndarray, scale: float = 1.0) -> np.ndarray:
+    """e4m3(scale * a) / scale as fp32: the values an 8-bit table or weight matrix really holds."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    out = np.empty(a.shape, dtype=np.float32)
+    n = _load().oracle_e4m3_quantize(_ptr(a), ctypes.c_int64(a.size), ctypes.c_double(scale), _ptr(out))
+    if n:
+        raise ValueError(f"{n} values exceed the e4m3 range at scale {scale}")
     return out

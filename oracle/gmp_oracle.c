@@ -37,6 +37,12 @@
  * double -> fp32 -> bf16 (round to nearest even) after the ReLU: that is the
  * precision the bf16 GPU kernels keep between layers, and is offered so that
  * rank decisions can be compared at the kernel's precision.
+ * With act_round = 2 (the 8-bit metric) the activation of hidden layer l (l = 1, 2, ..) is
+ * instead clamped to [0, 448 / s_l], s_l = 4^l, and rounded double -> fp32 -> e4m3 at that
+ * scale (OCP 8-bit float, 4 exponent and 3 mantissa bits, bias 7, largest value 448,
+ * nearest even), i.e. to e4m3(s_l * a) / s_l.  Weights and item vectors of that metric are
+ * quantised by the caller beforehand (oracle_e4m3_encode / _quantize) and arrive here as
+ * ordinary numbers.
  *
  * Parity pins (tests/test_oracle_*.py): closed forms and hand-worked values for
  * the relevance, a library MLP forward pass, brute-force equality on complete
@@ -94,6 +100,60 @@ static double round_to_bf16(double v) {
     return (double)f;
 }
 
+/* Nearest e4m3 value (ties to even) of v after rounding v to fp32; |v| above 448 gives +-448.
+ * e4m3: sign, 4 exponent bits (bias 7), 3 mantissa bits; normal values 2^(e-7) * (1 + m/8) for
+ * e = 1..15 (without e = 15, m = 7, which is NaN), subnormals m/8 * 2^-6. */
+static double round_to_e4m3(double v) {
+    double a = fabs((double)(float)v);
+    if (!(a == a)) return v;
+    if (a > 448.0) a = 448.0;
+    double quantum;
+    if (a < 0.015625) { /* below 2^-6: subnormal spacing */
+        quantum = 0.001953125; /* 2^-9 */
+    } else {
+        int e;
+        (void)frexp(a, &e);            /* a = f * 2^e, f in [0.5, 1) */
+        quantum = ldexp(1.0, e - 1 - 3); /* 2^(floor(log2 a) - 3) */
+    }
+    double q = nearbyint(a / quantum) * quantum; /* default rounding mode: nearest even */
+    if (q > 448.0) q = 448.0;
+    return signbit(v) ? -q : q;
+}
+
+/* the 8-bit code of an e4m3 value produced by round_to_e4m3 */
+static uint8_t e4m3_code(double q) {
+    uint8_t sign = (q < 0 || (q == 0 && signbit(q))) ? 0x80 : 0;
+    double a = fabs(q);
+    if (a == 0) return sign;
+    if (a < 0.015625) return (uint8_t)(sign | (uint8_t)(a / 0.001953125));
+    int e;
+    double f = frexp(a, &e); /* a = f * 2^e, f in [0.5, 1) -> 1.m = 2f, exponent e - 1 */
+    int m = (int)((2.0 * f - 1.0) * 8.0);
+    return (uint8_t)(sign | ((e - 1 + 7) << 3) | m);
+}
+
+/* codes[i] = e4m3(scale * in[i]); returns the number of elements whose magnitude had to be clamped */
+int64_t oracle_e4m3_encode(const float *in, int64_t n, double scale, uint8_t *codes) {
+    int64_t clamped = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        double v = (double)in[i] * scale;
+        if (fabs((double)(float)v) > 448.0) ++clamped;
+        codes[i] = e4m3_code(round_to_e4m3(v));
+    }
+    return clamped;
+}
+
+/* out[i] = e4m3(scale * in[i]) / scale */
+int64_t oracle_e4m3_quantize(const float *in, int64_t n, double scale, float *out) {
+    int64_t clamped = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        double v = (double)in[i] * scale;
+        if (fabs((double)(float)v) > 448.0) ++clamped;
+        out[i] = (float)(round_to_e4m3(v) / scale);
+    }
+    return clamped;
+}
+
 static int mlp_max_width(const mlp_t *m) {
     int w = 0;
     for (int l = 0; l <= m->n_layers; ++l)
@@ -118,6 +178,10 @@ static float relevance(const mlp_t *m, const double *x, double *h0, double *h1) 
             if (!last) {
                 if (acc < 0.0) acc = 0.0;
                 if (m->act_round == 1) acc = round_to_bf16(acc);
+                if (m->act_round == 2) {
+                    double scale = ldexp(1.0, 2 * (l + 1)); /* 4^(l+1) */
+                    acc = round_to_e4m3(acc * scale) / scale;
+                }
             }
             out[o] = acc;
         }

@@ -161,3 +161,60 @@ def test_rejects_out_of_range_pairs_and_bad_dims():
     bad = oracle.Mlp([np.zeros((1, 5), np.float32)], [np.zeros(1, np.float32)], np.ones(1, np.float32))
     with pytest.raises(ValueError):
         oracle.score_pairs(emb, users, bad, np.array([0]), np.array([0]))
+
+
+# ----------------------------------------------------------------------------- the 8-bit (e4m3) metric
+def _e4m3_value(code):
+    """An e4m3 code's value from the format's definition (sign, 4 exponent bits with bias 7, 3 mantissa
+    bits, no infinities, exponent 15 / mantissa 7 is NaN)."""
+    s = -1.0 if code & 0x80 else 1.0
+    e, m = (code >> 3) & 15, code & 7
+    if e == 15 and m == 7:
+        return float("nan")
+    return s * (m / 8 * 2.0 ** -6 if e == 0 else 2.0 ** (e - 7) * (1 + m / 8))
+
+
+def test_e4m3_codes_round_trip_and_known_values():
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], np.uint8)
+    values = np.array([_e4m3_value(int(c)) for c in codes], np.float32)
+    assert np.array_equal(oracle.e4m3_encode(values), codes)
+    assert np.array_equal(oracle.e4m3_quantize(values), values)
+    # 1 -> 0x38, -2 -> 0xC0, largest 448 -> 0x7E, smallest subnormal 2^-9 -> 0x01
+    assert oracle.e4m3_encode(np.array([1.0, -2.0, 448.0, 2.0 ** -9], np.float32)).tolist() == [0x38, 0xC0, 0x7E, 0x01]
+    # ties go to the even mantissa: between 1 (m=0) and 1.125 (m=1) -> 1; between 1.125 and 1.25 (m=2) -> 1.25;
+    # between the subnormals 1/512 and 2/512 -> 2/512; half of the smallest subnormal -> 0
+    assert oracle.e4m3_quantize(np.array([1.0625, 1.1875, 3 / 1024, 1 / 1024], np.float32)).tolist() == \
+        [1.0, 1.25, 2 / 512, 0.0]
+    # the scale is applied before and taken out after
+    assert oracle.e4m3_quantize(np.array([0.3], np.float32), 4.0).tolist() == [1.25 / 4]
+    with pytest.raises(ValueError):
+        oracle.e4m3_encode(np.array([500.0], np.float32))
+    with pytest.raises(ValueError):
+        oracle.e4m3_quantize(np.array([120.0], np.float32), 4.0)
+
+
+def test_e4m3_rounding_equals_a_library_conversion():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(100000) * s for s in (1e-3, 1e-2, 0.1, 1, 10, 100)]).astype(np.float32)
+    x = x[np.abs(x) <= 448]
+    t = torch.from_numpy(x).to(torch.float8_e4m3fn)
+    assert np.array_equal(oracle.e4m3_encode(x), t.view(torch.uint8).numpy())
+    assert np.array_equal(oracle.e4m3_quantize(x), t.to(torch.float32).numpy())
+
+
+def test_activation_rounding_option_rounds_to_e4m3_at_the_layers_scale():
+    # one hidden layer (scale 4): the unit passes x through; the logit is the quantised unit.
+    W = [np.array([[1.0, 0.0]], np.float32), np.array([[1.0]], np.float32)]
+    b = [np.zeros(1, np.float32), np.zeros(1, np.float32)]
+    # 4x = 1.0625 is a tie -> 1 -> 0.25;  4x = 1.2 -> 1.25 -> 0.3125;  relu first;  clamp at 448 / 4 = 112
+    for x, rounded in ((1.0625 / 4, 0.25), (0.3, 0.3125), (-3.0, 0.0), (200.0, 112.0), (1 / 4096, 0.0)):
+        assert _score_one([x], [0.0], W, b, [1.0], act_round=2) == pytest.approx(float(expit(rounded)), abs=6e-8)
+    # two hidden layers: the second one is quantised at scale 16 (0.3 * 16 = 4.8 -> 5 -> 0.3125; 20 -> 448 / 16)
+    W2 = [np.array([[1.0, 0.0]], np.float32), np.array([[1.0]], np.float32), np.array([[1.0]], np.float32)]
+    b2 = [np.zeros(1, np.float32)] * 3
+    assert _score_one([0.3125], [0.0], W2, b2, [1.0], act_round=2) == pytest.approx(float(expit(0.3125)), abs=6e-8)
+    b2s = [np.zeros(1, np.float32), np.array([0.0195], np.float32), np.zeros(1, np.float32)]
+    # 0.3125 + 0.0195 = 0.332 -> x16 = 5.312 -> 5.5 -> 0.34375
+    assert _score_one([0.3125], [0.0], W2, b2s, [1.0], act_round=2) == pytest.approx(float(expit(0.34375)), abs=6e-8)
+    assert _score_one([40.0], [0.0], W2, b2, [1.0], act_round=2) == pytest.approx(float(expit(28.0)), abs=6e-8)
