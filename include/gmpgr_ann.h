@@ -53,7 +53,7 @@ enum {
     ANN_EWORKSPACE = -5  /* workspace too small, or a per-query visited table filled up */
 };
 
-enum { ANN_F32 = 0, ANN_BF16 = 1 };
+enum { ANN_F32 = 0, ANN_BF16 = 1, ANN_F8 = 2 };
 
 enum {
     ANN_VALIDATE = 1u,   /* ann_graph_load: check on the device that every adjacency id is < N */
@@ -247,6 +247,24 @@ int ann_search_stream(const ann_graph *g, const ann_mlp *m, const void *queries_
  */
 int ann_users_add_noise(const void *users_dev, void *out_dev, int32_t Q, int32_t d, int32_t dtype,
                         double sigma, uint64_t seed, uint64_t draw, void *stream);
+
+/*
+ * The 8-bit metric (Sec. 4.3's quantised deployment taken below 16 bits; e4m3 = the OCP 8-bit float
+ * with 4 exponent and 3 mantissa bits, largest value 448, no infinities).
+ * dtype = ANN_F8 means: the item table holds e4m3 bytes, [N][d] (ann_graph_load); users stay bf16;
+ * ann_mlp_load takes bf16 weights as for ANN_BF16 and stores every matrix as e4m3(4 w) (the user
+ * half of the first layer stays bf16 and is applied in fp32, once per query); products are
+ * accumulated in fp32; the activations of hidden layer l are clamped to [0, 448 / 4^l] and rounded
+ * to e4m3 at scale 4^l (nearest even); logits, sigmoid and the weighted sum are fp32.
+ * Built for one shape: 64-wide items, hidden widths 256 and 128, up to 8 heads (else ANN_ENOTIMPL);
+ * ANN_EINVAL if a weight times 4 exceeds 448.
+ *
+ * ann_quantize_e4m3 makes such an item table: dst_dev[i] = e4m3(scale * src_dev[i]) (nearest even,
+ * magnitudes above 448 clamped), src_dev of src_dtype ANN_F32 / ANN_BF16, n elements; the metric
+ * above assumes scale = 1.  Only enqueues one kernel on `stream`.
+ */
+int ann_quantize_e4m3(const void *src_dev, int32_t src_dtype, int64_t n, float scale, uint8_t *dst_dev,
+                      void *stream);
 
 /*
  * Relevance (Eq. 5-8) of an explicit list of M pairs: out_dev[r] = relevance(user q_idx[r],

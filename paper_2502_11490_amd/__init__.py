@@ -6,6 +6,7 @@ of libgmpgr_ann.so.  There is no CPU fallback; importing works without a GPU, ca
 """
 from .binding import (  # noqa: F401
     ANN_BF16,
+    ANN_F8,
     ANN_F32,
     ANN_MLP_GENERIC,
     ANN_VALIDATE,
@@ -22,6 +23,7 @@ from .binding import (  # noqa: F401
     ann_profile_read,
     ann_score_pairs,
     ann_users_add_noise,
+    ann_quantize_e4m3,
     ann_search,
     ann_search_layers,
     ann_search_layers_workspace_bytes,

@@ -10,7 +10,7 @@ import numpy as np
 import torch
 
 ANN_OK, ANN_EINVAL, ANN_ENOMEM, ANN_EDEVICE, ANN_ENOTIMPL, ANN_EWORKSPACE = 0, -1, -2, -3, -4, -5
-ANN_F32, ANN_BF16 = 0, 1
+ANN_F32, ANN_BF16, ANN_F8 = 0, 1, 2
 ANN_VALIDATE, ANN_MLP_GENERIC = 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -21,7 +21,7 @@ EXPORTS = [
     "ann_graph_load", "ann_graph_free", "ann_mlp_load", "ann_mlp_free", "ann_mlp_uses_mfma",
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
     "ann_search_layers", "ann_search_walkers_workspace_bytes", "ann_search_walkers",
-    "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs", "ann_users_add_noise",
+    "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs", "ann_users_add_noise", "ann_quantize_e4m3",
     "ann_search_stats", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
@@ -89,6 +89,8 @@ def load_library():
     lib.ann_score_pairs.restype = ctypes.c_int
     lib.ann_users_add_noise.argtypes = [vp, vp, i32, i32, i32, ctypes.c_double, ctypes.c_uint64, ctypes.c_uint64, vp]
     lib.ann_users_add_noise.restype = ctypes.c_int
+    lib.ann_quantize_e4m3.argtypes = [vp, i32, i64, ctypes.c_float, vp, vp]
+    lib.ann_quantize_e4m3.restype = ctypes.c_int
     lib.ann_search_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
     lib.ann_search_stats.restype = ctypes.c_int
     lib.ann_profile_enable.argtypes = [ctypes.c_int]
@@ -123,6 +125,8 @@ def _dtype_code(t: torch.Tensor) -> int:
         return ANN_F32
     if t.dtype == torch.bfloat16:
         return ANN_BF16
+    if t.dtype == torch.float8_e4m3fn:
+        return ANN_F8
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
@@ -187,10 +191,10 @@ def ann_mlp_load(W: Sequence, b: Sequence, head_w, d_user: int, dtype: int, flag
     lib = load_library()
     n = len(W)
     Wh = [_host_bytes(w) for w in W]
-    want = np.uint16 if dtype == ANN_BF16 else np.float32
+    want = np.float32 if dtype == ANN_F32 else np.uint16  # the 8-bit metric takes bf16 weights and quantises them
     for w in Wh:
         if w.dtype != want:
-            raise TypeError(f"weights must be {'bf16' if dtype == ANN_BF16 else 'fp32'}")
+            raise TypeError(f"weights must be {'fp32' if dtype == ANN_F32 else 'bf16'}")
     bh = [np.ascontiguousarray(_host_bytes(x), dtype=np.float32) for x in b]
     hw = np.ascontiguousarray(_host_bytes(head_w), dtype=np.float32)
     dims = [Wh[0].shape[1]] + [w.shape[0] for w in Wh]
@@ -386,6 +390,22 @@ def ann_users_add_noise(users: torch.Tensor, sigma: float, seed: int, draw: int 
     _check(load_library().ann_users_add_noise(_dev_ptr(users, "users") if Q else None, _dev_ptr(out, "out") if Q else None,
                                               Q, d, _dtype_code(users), float(sigma), int(seed), int(draw),
                                               _stream_ptr(stream)))
+    return out
+
+
+def ann_quantize_e4m3(src: torch.Tensor, scale: float = 1.0, out: Optional[torch.Tensor] = None,
+                      stream=None) -> torch.Tensor:
+    """e4m3(scale * src) as a torch.float8_e4m3fn tensor of the same shape (src: fp32 or bf16, on the device)."""
+    if out is None:
+        out = torch.empty(src.shape, dtype=torch.float8_e4m3fn, device=src.device)
+    if out.shape != src.shape or out.dtype != torch.float8_e4m3fn:
+        raise ValueError("out must be float8_e4m3fn with the shape of src")
+    code = _dtype_code(src)
+    if code == ANN_F8:
+        raise TypeError("src must be fp32 or bf16")
+    n = src.numel()
+    _check(load_library().ann_quantize_e4m3(_dev_ptr(src, "src") if n else None, code, n, float(scale),
+                                            _dev_ptr(out, "out") if n else None, _stream_ptr(stream)))
     return out
 
 

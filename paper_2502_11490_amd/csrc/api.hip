@@ -370,8 +370,12 @@ int ann_graph_load(const int32_t *adj_dev, const void *emb_dev, int64_t N, int32
         set_error("need 1 <= N < 2^31, 1 <= R <= 64, 1 <= d <= 1024 (got N=%lld R=%d d=%d)", (long long)N, R, d);
         return ANN_EINVAL;
     }
-    if (dtype != ANN_F32 && dtype != ANN_BF16) {
-        set_error("dtype must be ANN_F32 or ANN_BF16");
+    if (dtype != ANN_F32 && dtype != ANN_BF16 && dtype != ANN_F8) {
+        set_error("dtype must be ANN_F32, ANN_BF16 or ANN_F8");
+        return ANN_EINVAL;
+    }
+    if (dtype == ANN_F8 && (((uintptr_t)emb_dev & 15) || (d & 15))) {
+        set_error("an 8-bit item table needs a 16-byte aligned base and a width that is a multiple of 16");
         return ANN_EINVAL;
     }
     if (((uintptr_t)adj_dev & 3) || ((uintptr_t)emb_dev & 3)) {
@@ -433,9 +437,13 @@ int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *
         set_error("need 1 <= n_layers <= %d", MAX_LAYERS);
         return ANN_EINVAL;
     }
-    if (dtype != ANN_F32 && dtype != ANN_BF16) {
-        set_error("dtype must be ANN_F32 or ANN_BF16");
+    if (dtype != ANN_F32 && dtype != ANN_BF16 && dtype != ANN_F8) {
+        set_error("dtype must be ANN_F32, ANN_BF16 or ANN_F8");
         return ANN_EINVAL;
+    }
+    if (dtype == ANN_F8 && !f8_supported(dims_host, n_layers, d_user)) {
+        set_error("the 8-bit metric is built for 64-wide items and hidden widths 256, 128 only");
+        return ANN_ENOTIMPL;
     }
     for (int l = 0; l <= n_layers; ++l)
         if (dims_host[l] < 1 || dims_host[l] > MAX_WIDTH) {
@@ -471,7 +479,7 @@ int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *
     m->J = J;
     for (int j = 0; j < J; ++j) m->head_w[j] = head_w_host[j];
     if (hipGetDevice(&m->device) != hipSuccess) m->device = 0;
-    const size_t es = dtype == ANN_BF16 ? 2 : 4;
+    const size_t es = dtype == ANN_F32 ? 4 : 2;  // the 8-bit metric takes bf16 weights and quantises them itself
     int64_t wtot = 0;
     int32_t btot = 0;
     for (int l = 0; l < n_layers; ++l) {
@@ -487,6 +495,8 @@ int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *
         memcpy(wbuf.data() + (size_t)m->w_off[l] * es, W_host[l], (size_t)dims_host[l] * dims_host[l + 1] * es);
         memcpy(bbuf.data() + m->b_off[l], b_host[l], (size_t)dims_host[l + 1] * sizeof(float));
     }
+    if (dtype == ANN_F8)  // the 8-bit kernel holds the second hidden layer at 16 x its value (see mlp_mfma_f8.hip)
+        for (int i = 0; i < dims_host[2]; ++i) bbuf[(size_t)m->b_off[1] + i] *= 16.f;
     int rc = ANN_OK;
     auto fail = [&](int code) {
         ann_mlp_free(m);
@@ -505,7 +515,11 @@ int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *
         return fail(ANN_EDEVICE);
     }
     m->kernel = MLP_ALU;
-    if (!(flags & ANN_MLP_GENERIC) && mfma_supported(m->dims, n_layers, d_user, dtype)) {
+    if (dtype == ANN_F8) {
+        rc = build_f8_fragments(m, W_host, s);
+        if (rc != ANN_OK) return fail(rc);
+        m->kernel = MLP_MFMA2;
+    } else if (!(flags & ANN_MLP_GENERIC) && mfma_supported(m->dims, n_layers, d_user, dtype)) {
         rc = build_mfma_fragments(m, W_host, s);
         if (rc != ANN_OK) return fail(rc);
         m->kernel = MLP_MFMA2;
@@ -817,6 +831,20 @@ int ann_users_add_noise(const void *users_dev, void *out_dev, int32_t Q, int32_t
         return ANN_EINVAL;
     }
     return launch_users_add_noise(users_dev, out_dev, (int64_t)Q * d, dtype, sigma, seed, draw, (hipStream_t)stream);
+}
+
+int ann_quantize_e4m3(const void *src_dev, int32_t src_dtype, int64_t n, float scale, uint8_t *dst_dev,
+                      void *stream) {
+    if (n < 0 || (src_dtype != ANN_F32 && src_dtype != ANN_BF16) || !(scale > 0.f) || !(scale < INFINITY)) {
+        set_error("need n >= 0, a source of ANN_F32 or ANN_BF16, a finite scale > 0");
+        return ANN_EINVAL;
+    }
+    if (n == 0) return ANN_OK;
+    if (!src_dev || !dst_dev) {
+        set_error("src_dev and dst_dev must not be null");
+        return ANN_EINVAL;
+    }
+    return launch_quantize_e4m3(src_dev, src_dtype, n, scale, dst_dev, (hipStream_t)stream);
 }
 
 int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int64_t M,

@@ -149,6 +149,14 @@ int launch_admit(const SearchArgs &a);
 int launch_users_add_noise(const void *users, void *out, int64_t n_elem, int dtype, double sigma, uint64_t seed,
                            uint64_t stream_id, hipStream_t stream);
 
+// mlp_mfma_f8.hip: the 8-bit (e4m3) metric
+bool f8_supported(const int32_t *dims, int32_t n_layers, int32_t d_user);
+int build_f8_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream);
+int launch_mlp_mfma_f8(const ann_graph *g, const ann_mlp *m, const float *upre, const int32_t *pair_q,
+                       const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
+                       hipStream_t stream);
+int launch_quantize_e4m3(const void *in, int dtype, int64_t n, float scale, uint8_t *out, hipStream_t stream);
+
 // mlp_alu.hip / mlp_mfma.hip: score `*M_dev` (<= M_max) pairs; M_dev is read on the device.
 int launch_mlp_alu(const ann_graph *g, const ann_mlp *m, const void *queries, const int32_t *pair_q,
                    const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,

@@ -70,7 +70,7 @@ __device__ __forceinline__ bf16x8 relu_pack(const f32x16 &acc, int half) {
 // upre[q][n] = b1[n] + sum_{i < d_user} W1[n][i] * u_q[i]   (fp32 FMA chain in index order)
 __global__ void __launch_bounds__(256)
 user_pre_kernel(const uint16_t *__restrict__ W1, int n_in, int d_user, int H1, const float *__restrict__ b1,
-                const uint16_t *__restrict__ users, int Q, float *__restrict__ upre) {
+                const uint16_t *__restrict__ users, int Q, float *__restrict__ upre, float out_scale) {
     extern __shared__ float u_s[];
     const int q = blockIdx.x;
     for (int i = threadIdx.x; i < d_user; i += blockDim.x)
@@ -80,7 +80,7 @@ user_pre_kernel(const uint16_t *__restrict__ W1, int n_in, int d_user, int H1, c
         float acc = b1[n];
         const uint16_t *row = W1 + (size_t)n * n_in;
         for (int i = 0; i < d_user; ++i) acc = fmaf(__uint_as_float(((uint32_t)row[i]) << 16), u_s[i], acc);
-        upre[(size_t)q * H1 + n] = acc;
+        upre[(size_t)q * H1 + n] = acc * out_scale;  // a power of two (1 for the bf16 kernels): exact
     }
 }
 
@@ -474,7 +474,7 @@ int launch_user_pre(const ann_mlp *m, const void *queries, int32_t Q, float *upr
     if (Q <= 0) return ANN_OK;
     hipLaunchKernelGGL(user_pre_kernel, dim3(Q), dim3(256), (size_t)m->d_user * sizeof(float), stream,
                        (const uint16_t *)m->W_dev, m->dims[0], m->d_user, m->dims[1], m->b_dev,
-                       (const uint16_t *)queries, Q, upre);
+                       (const uint16_t *)queries, Q, upre, m->dtype == ANN_F8 ? 4.f : 1.f);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
@@ -507,6 +507,7 @@ int launch_mlp_mfma(const ann_graph *g, const ann_mlp *m, const float *upre, con
                     int32_t tile_rows, hipStream_t stream) {
     (void)tile_rows;
     if (M_max <= 0) return ANN_OK;
+    if (m->dtype == ANN_F8) return launch_mlp_mfma_f8(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
     const int D = m->d_item, H1 = m->dims[1], H2 = m->dims[2];
     if (m->n_layers == 2 && D == 64 && H1 == 256) {
         constexpr int CB = 2, TILE = 32 * CB * MF_WAVES;

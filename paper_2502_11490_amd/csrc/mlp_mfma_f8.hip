@@ -1,0 +1,325 @@
+// The relevance metric of Sec. 3.1 (1), Eq. 5-8, with 8-bit operands (the quantised deployment of
+// Sec. 4.3 taken one step further than 16 bits): e4m3 item vectors, weights and hidden activations on
+// v_mfma_f32_32x32x64_f8f6f4, fp32 accumulation.  Shape served: 64-wide items, hidden 256 and 128.
+//
+// Same transposed formulation as the bf16 kernels (H_out^T = W * H_in^T, weights are the A operand,
+// the activations of 32 pairs the B operand), with a contraction of 64 per instruction: lane (m, g)
+// of an operand holds 32 bytes, the contraction indices 32g .. 32g+31, and A's byte b meets B's byte b.
+// The D layout is the one of every 32x32 MFMA: lane (pair, g) holds output units
+// 8*(i/4) + 4g + i%4, i = 0..15.  Two consecutive 32-unit blocks therefore give a lane the 32 values
+// that ARE its share of the next layer's B operand, once its weights are stored in the matching
+// order ("fragment order", written by build_f8_fragments).
+//
+// Scales (all powers of two, so they only move exponents): every weight matrix is stored as
+// e4m3(4 w); hidden layer 1 is held as e4m3(4 h), hidden layer 2 as e4m3(16 h).  With the user term
+// and the biases pre-multiplied (4 * (W1_user u + b1), 16 * b2) the accumulators of a layer are
+// already its activations at their scale: ReLU and the clamp to the largest e4m3 value are one
+// v_med3_f32, the rounding one v_cvt_pk_fp8_f32 per two values.  The head accumulators are 64 x the
+// logits.
+//
+// All weights (52 KB) stay in LDS; a workgroup of eight waves, 64 pairs per wave.
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+namespace gmpgr {
+
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float E4M3_MAX = 448.f;
+constexpr float F8_W_SCALE = 4.f;    // weights
+constexpr float F8_H1_SCALE = 4.f;   // = item scale (1) x weight scale
+constexpr float F8_H2_SCALE = 16.f;  // = H1 scale x weight scale
+constexpr float F8_LOGIT_SCALE = 64.f;
+
+__device__ __forceinline__ f32x16 mfma_f8(const i32x8 &a, const i32x8 &b, const f32x16 &c) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+}
+
+// relu, clamp, round: 16 accumulator values -> half (bytes 16 * half .. + 15) of the lane's next B operand
+__device__ __forceinline__ void quantize_half(const f32x16 &src, i32x8 &dst, int half) {
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const int i = 4 * w;
+        int v = 0;
+        v = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(src[i], 0.f, E4M3_MAX),
+                                            __builtin_amdgcn_fmed3f(src[i + 1], 0.f, E4M3_MAX), v, false);
+        v = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(src[i + 2], 0.f, E4M3_MAX),
+                                            __builtin_amdgcn_fmed3f(src[i + 3], 0.f, E4M3_MAX), v, true);
+        dst[4 * half + w] = v;
+    }
+}
+
+// Fragments, 2 KB each, stored as two 1 KB halves (lane l's bytes 0..15 at 16*l of the first half,
+// bytes 16..31 at 16*l of the second):
+//   [blk < H1/32]                       lane (m,g) byte b: e4m3(4 W1_item[32 blk + m][32g + b])
+//   [H1/32 + (H2/32) c + n2], c < H1/64 lane (m,g) byte b: e4m3(4 W2[32 n2 + m][unit(c, g, b)])
+//   [H1/32 + (H1/64)(H2/32) + p], p < H2/64              : e4m3(4 W3[m][unit(p, g, b)]), rows m >= J zero
+//   unit(c, g, b) = 64c + 32 (b / 16) + 8 ((b % 16) / 4) + 4g + b % 4
+template <int D, int H1, int H2, int CB, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES)
+mlp_mfma2_f8_kernel(const uint8_t *__restrict__ emb, int64_t N, const float *__restrict__ upre,
+                    const uint4 *__restrict__ frag, const float *__restrict__ b2s, const float *__restrict__ b3,
+                    const float *__restrict__ head_w, int J, const int32_t *__restrict__ pair_q,
+                    const int32_t *__restrict__ pair_id, const int32_t *__restrict__ M_dev, int64_t M_max, int32_t Q,
+                    float *__restrict__ scores) {
+    static_assert(D == 64, "one contraction step of 64 covers the item vector");
+    constexpr int NB1 = H1 / 32, NC = H1 / 64, NB2 = H2 / 32, NP = H2 / 64;
+    constexpr int N_FRAG = NB1 + NC * NB2 + NP;
+    constexpr int BLOCK_T = 64 * WAVES;
+    constexpr int RW = 32 * CB, TILE = RW * WAVES;
+    extern __shared__ __align__(16) uint4 lds[];  // [N_FRAG][2][64]
+
+    int64_t M = (int64_t)*M_dev;
+    if (M > M_max) M = M_max;
+    const int64_t n_tiles = (M + TILE - 1) / TILE;
+    if ((int64_t)blockIdx.x >= n_tiles) return;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int g = lane >> 5, col = lane & 31;
+    for (int i = threadIdx.x; i < N_FRAG * 128; i += BLOCK_T) lds[i] = frag[i];
+    __syncthreads();
+
+    auto fragment = [&](int f) {
+        const uint4 lo = lds[f * 128 + lane], hi = lds[f * 128 + 64 + lane];
+        i32x8 a;
+        a[0] = lo.x, a[1] = lo.y, a[2] = lo.z, a[3] = lo.w, a[4] = hi.x, a[5] = hi.y, a[6] = hi.z, a[7] = hi.w;
+        return a;
+    };
+
+    float hw[4], bb3[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int j = 4 * g + i;
+        hw[i] = j < J ? head_w[j] : 0.f;
+        bb3[i] = j < J ? b3[j] : 0.f;
+    }
+
+#pragma unroll 1
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t row0 = tile * TILE + (int64_t)wave * RW;
+        i32x8 x[CB];
+        const float *up[CB];
+        bool bad[CB];
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            int64_t row = row0 + c * 32 + col;
+            row = row < M ? row : M - 1;  // rows past the end read the last pair and are not stored
+            int32_t v = pair_id[row], q = pair_q[row];
+            bad[c] = ((uint64_t)(int64_t)v >= (uint64_t)N) | ((uint32_t)q >= (uint32_t)Q);
+            if (bad[c]) v = 0, q = 0;
+            const uint4 *src = (const uint4 *)(emb + (size_t)v * D + 32 * g);
+            const uint4 lo = src[0], hi = src[1];
+            x[c][0] = lo.x, x[c][1] = lo.y, x[c][2] = lo.z, x[c][3] = lo.w;
+            x[c][4] = hi.x, x[c][5] = hi.y, x[c][6] = hi.z, x[c][7] = hi.w;
+            up[c] = upre + (size_t)q * H1 + 4 * g;
+        }
+        f32x16 acc2[NB2][CB];
+        // the bias pointer is laundered once per batch: otherwise its loads are hoisted out of the batch
+        // loop and their values carried (spilled) across it
+        int opaque_zero = 0;
+        asm volatile("" : "+s"(opaque_zero));
+        const float *b2t = b2s + opaque_zero;
+#pragma unroll
+        for (int n2 = 0; n2 < NB2; ++n2) {
+            f32x16 init;
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) {
+                f32x4 bv = *(const f32x4 *)(b2t + n2 * 32 + 8 * t4 + 4 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) init[4 * t4 + e] = bv[e];
+            }
+#pragma unroll
+            for (int c = 0; c < CB; ++c) acc2[n2][c] = init;
+        }
+#pragma unroll 1
+        for (int ch = 0; ch < NC; ++ch) {
+            // layer 1, units 64 ch .. 64 ch + 63, one block of 32 at a time: accumulators start from the
+            // (scaled) user term, their rounded ReLU is one half of the layer-2 operand
+            i32x8 h1q[CB];
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb) {
+                f32x16 acc1[CB];
+#pragma unroll
+                for (int c = 0; c < CB; ++c)
+#pragma unroll
+                    for (int t4 = 0; t4 < 4; ++t4) {
+                        f32x4 pv = *(const f32x4 *)(up[c] + (2 * ch + hb) * 32 + 8 * t4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc1[c][4 * t4 + e] = pv[e];
+                    }
+                const i32x8 a = fragment(2 * ch + hb);
+#pragma unroll
+                for (int c = 0; c < CB; ++c) acc1[c] = mfma_f8(a, x[c], acc1[c]);
+#pragma unroll
+                for (int c = 0; c < CB; ++c) quantize_half(acc1[c], h1q[c], hb);
+            }
+            // layer 2: every output unit consumes these 64 hidden units
+#pragma unroll
+            for (int n2 = 0; n2 < NB2; ++n2) {
+                const i32x8 a = fragment(NB1 + NB2 * ch + n2);
+#pragma unroll
+                for (int c = 0; c < CB; ++c) acc2[n2][c] = mfma_f8(a, h1q[c], acc2[n2][c]);
+            }
+        }
+        // head layer (rows >= J of its fragments are zero), then Eq. 8
+        f32x16 acc3[CB];
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc3[c][i] = 0.f;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const i32x8 a = fragment(NB1 + NC * NB2 + p);
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                i32x8 h2q;
+                quantize_half(acc2[2 * p][c], h2q, 0);
+                quantize_half(acc2[2 * p + 1][c], h2q, 1);
+                acc3[c] = mfma_f8(a, h2q, acc3[c]);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            float part = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float logit = acc3[c][i] * (1.0f / F8_LOGIT_SCALE) + bb3[i];
+                part = fmaf(hw[i], 1.0f / (1.0f + expf(-logit)), part);
+            }
+            float other = __shfl_xor(part, 32);
+            int64_t row = row0 + c * 32 + col;
+            if (g == 0 && row < M) scores[row] = bad[c] ? __uint_as_float(0x7fc00000u) : part + other;
+        }
+    }
+}
+
+// ---- host side: e4m3 encoding of the weights (nearest even; the format: sign, 4 exponent bits with
+// bias 7, 3 mantissa bits, subnormals below 2^-6, largest value 448) ----
+static bool encode_e4m3(float v, uint8_t *code) {
+    const uint8_t sign = signbit(v) ? 0x80 : 0;
+    const float a = fabsf(v);
+    if (!(a <= E4M3_MAX)) return false;
+    if (a < 0.015625f) {  // subnormal spacing 2^-9; 8 steps carry into the first normal code by themselves
+        *code = (uint8_t)(sign | (uint8_t)nearbyintf(a * 512.f));
+        return true;
+    }
+    int e;
+    const float f = frexpf(a, &e);                       // a = f 2^e, f in [0.5, 1)
+    int mant = (int)nearbyintf((2.f * f - 1.f) * 8.f);   // 0..8
+    int ex = e - 1 + 7;
+    if (mant == 8) mant = 0, ++ex;
+    *code = (uint8_t)(sign | (ex << 3) | mant);
+    return true;
+}
+
+static inline float bf16_value(uint16_t bits) {
+    uint32_t u = (uint32_t)bits << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+bool f8_supported(const int32_t *dims, int32_t n_layers, int32_t d_user) {
+    if (n_layers != 3 || d_user < 1) return false;
+    const int J = dims[3];
+    return dims[0] - d_user == 64 && dims[1] == 256 && dims[2] == 128 && J >= 1 && J <= MAX_HEADS;
+}
+
+static inline int f8_unit(int c, int g, int b) { return 64 * c + 32 * (b / 16) + 8 * ((b % 16) / 4) + 4 * g + b % 4; }
+
+// W_host: bf16 matrices as for the bf16 metric.  Fails (ANN_EINVAL) if a weight times 4 exceeds 448.
+int build_f8_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream) {
+    const int D = m->d_item, H1 = m->dims[1], H2 = m->dims[2], J = m->J, du = m->d_user;
+    const int NB1 = H1 / 32, NC = H1 / 64, NB2 = H2 / 32, NP = H2 / 64;
+    const int n_frag = NB1 + NC * NB2 + NP;
+    std::vector<uint8_t> buf((size_t)n_frag * 2048, 0);
+    const uint16_t *W1 = (const uint16_t *)W_host[0], *W2 = (const uint16_t *)W_host[1],
+                   *W3 = (const uint16_t *)W_host[2];
+    bool ok = true;
+    auto put = [&](int f, int l, int b, uint16_t w) {
+        uint8_t code = 0;
+        ok &= encode_e4m3(F8_W_SCALE * bf16_value(w), &code);
+        buf[(size_t)f * 2048 + (size_t)(b / 16) * 1024 + (size_t)l * 16 + b % 16] = code;
+    };
+    for (int l = 0; l < 64; ++l) {
+        const int mrow = l & 31, g = l >> 5;
+        for (int b = 0; b < 32; ++b) {
+            for (int blk = 0; blk < NB1; ++blk) put(blk, l, b, W1[(size_t)(32 * blk + mrow) * (du + D) + du + 32 * g + b]);
+            for (int c = 0; c < NC; ++c)
+                for (int n2 = 0; n2 < NB2; ++n2)
+                    put(NB1 + NB2 * c + n2, l, b, W2[(size_t)(32 * n2 + mrow) * H1 + f8_unit(c, g, b)]);
+            if (mrow < J)
+                for (int p = 0; p < NP; ++p) put(NB1 + NC * NB2 + p, l, b, W3[(size_t)mrow * H2 + f8_unit(p, g, b)]);
+        }
+    }
+    if (!ok) {
+        set_error("a weight is too large for the 8-bit metric (|4 w| must not exceed 448)");
+        return ANN_EINVAL;
+    }
+    m->frag_bytes = (int64_t)buf.size();
+    ANN_HIP_TRY(hipMalloc(&m->frag_dev, (size_t)m->frag_bytes));
+    ANN_HIP_TRY(hipMemcpyAsync(m->frag_dev, buf.data(), (size_t)m->frag_bytes, hipMemcpyHostToDevice, stream));
+    ANN_HIP_TRY(hipStreamSynchronize(stream));  // buf is freed on return
+    return ANN_OK;
+}
+
+int launch_mlp_mfma_f8(const ann_graph *g, const ann_mlp *m, const float *upre, const int32_t *pair_q,
+                       const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
+                       hipStream_t stream) {
+    if (M_max <= 0) return ANN_OK;
+    constexpr int D = 64, H1 = 256, H2 = 128, CB = 2, WAVES = 8;
+    constexpr int N_FRAG = H1 / 32 + (H1 / 64) * (H2 / 32) + H2 / 64;
+    constexpr size_t smem = (size_t)N_FRAG * 2048;  // 52 KB
+    constexpr int TILE = 32 * CB * WAVES;
+    auto fn = mlp_mfma2_f8_kernel<D, H1, H2, CB, WAVES>;
+    static std::atomic<uint32_t> raised;
+    if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised); rc != ANN_OK) return rc;
+    int64_t tiles = (M_max + TILE - 1) / TILE;
+    int grid = (int)(tiles < 256 ? tiles : 256);
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(64 * WAVES), smem, stream, (const uint8_t *)g->emb, g->N, upre,
+                       (const uint4 *)m->frag_dev, m->b_dev + m->b_off[1], m->b_dev + m->b_off[2], m->head_w_dev, m->J,
+                       pair_q, pair_id, M_dev, M_max, Q, scores);
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+// out[i] = e4m3(scale * in[i]), magnitudes above 448 clamped (the conversion instruction would give NaN)
+template <bool BF16>
+__global__ void __launch_bounds__(256)
+quantize_e4m3_kernel(const void *__restrict__ in, uint8_t *__restrict__ out, int64_t n, float scale) {
+    const int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i0 >= n) return;
+    float v[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int64_t i = i0 + t < n ? i0 + t : n - 1;
+        const float f = BF16 ? __uint_as_float((uint32_t)((const uint16_t *)in)[i] << 16) : ((const float *)in)[i];
+        v[t] = __builtin_amdgcn_fmed3f(f * scale, -E4M3_MAX, E4M3_MAX);
+    }
+    int r = 0;
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], r, false);
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], r, true);
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        if (i0 + t < n) out[i0 + t] = (uint8_t)((uint32_t)r >> (8 * t));
+}
+
+int launch_quantize_e4m3(const void *in, int dtype, int64_t n, float scale, uint8_t *out, hipStream_t stream) {
+    if (n == 0) return ANN_OK;
+    const int64_t groups = (n + 3) / 4;
+    const unsigned grid = (unsigned)((groups + 255) / 256);
+    if (dtype == ANN_BF16)
+        hipLaunchKernelGGL(quantize_e4m3_kernel<true>, dim3(grid), dim3(256), 0, stream, in, out, n, scale);
+    else
+        hipLaunchKernelGGL(quantize_e4m3_kernel<false>, dim3(grid), dim3(256), 0, stream, in, out, n, scale);
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+}  // namespace gmpgr
