@@ -109,6 +109,7 @@ def main() -> int:
     ap.add_argument("--no-layers", action="store_true", help="skip the layer-by-layer search beside the headline")
     ap.add_argument("--no-stream", action="store_true", help="skip the continuous-batching run beside the headline")
     ap.add_argument("--no-walkers", action="store_true", help="skip the walker-rule run beside the headline")
+    ap.add_argument("--no-f8", action="store_true", help="skip the 8-bit metric run (on C2) beside the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain 256 MiB copy kernel (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -291,6 +292,48 @@ def main() -> int:
             f"{stw.pairs_scored} pairs")
         del wsw
 
+    # ---- the 8-bit (e4m3) metric beside the 16-bit one, on the configuration whose shape it is built for
+    #      (C2: 64-wide items, 128 -> 256 -> 128 -> J); reported beside the headline, not part of the timed step ----
+    f8 = None
+    if not ragged and not args.no_f8:
+        cfg2 = PRESETS["C2"]
+        wl2 = make_workload(cfg2, device="cuda:0")
+        sel2 = list(range(64))
+        truth2 = torch_ground_truth(wl2, sel2, 100)
+        L2 = 4 * cfg2.L
+        f8 = {"workload": f"C2: {cfg2.N} items d={cfg2.d}, MLP {'x'.join(str(x) for x in cfg2.dims)}, Q={cfg2.Q} "
+                          f"E={cfg2.E} W={cfg2.W} L={L2} k={cfg2.k}"}
+        fl2 = flops_per_pair(cfg2.dims, cfg2.d, hoisted=True)
+        for name, code in (("bf16", ann.ANN_BF16), ("e4m3", ann.ANN_F8)):
+            emb2 = wl2["emb"] if code == ann.ANN_BF16 else ann.ann_quantize_e4m3(wl2["emb"])
+            g2 = ann.ann_graph_load(wl2["adj"], emb2)
+            m2 = ann.ann_mlp_load(wl2["W"], wl2["b"], wl2["head_w"], cfg2.d, code)
+            ws2 = torch.empty(ann.ann_search_workspace_bytes(g2, m2, cfg2.Q, cfg2.E, cfg2.W, L2, cfg2.k, 0),
+                              dtype=torch.uint8, device="cuda:0")
+            run = lambda: ann.ann_search(g2, m2, wl2["users"], wl2["entries"], cfg2.W, L2, cfg2.k, 0, workspace=ws2)
+            run()
+            torch.cuda.synchronize()
+            t7 = time.perf_counter()
+            for _ in range(5):
+                ids2, _ = run()
+            torch.cuda.synchronize()
+            ms2 = 1e3 * (time.perf_counter() - t7) / 5
+            ann.ann_profile_enable(True)
+            ann.ann_profile_read()
+            run()
+            torch.cuda.synchronize()
+            prof2 = ann.ann_profile_read()
+            ann.ann_profile_enable(False)
+            st2 = ann.ann_search_stats(ws2)
+            f8[name] = {"ms_per_search": round(ms2, 3), "queries_per_s": round(cfg2.Q / ms2 * 1e3, 1),
+                        "recall_at_100": round(recall_at(ids2[sel2].cpu(), truth2.cpu(), 100), 4),
+                        "pairs_scored": int(st2.pairs_scored), "score_ms": round(prof2["score"][0], 3),
+                        "score_TFLOPs": round(st2.pairs_scored * fl2 / (prof2["score"][0] * 1e-3) / 1e12, 1)}
+            log(f"C2 {name}: {ms2:.2f} ms per search, recall@100 = {f8[name]['recall_at_100']}, scoring "
+                f"{prof2['score'][0]:.2f} ms")
+            del ws2, g2, m2, emb2
+        del wl2
+
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 255)
         dst = torch.empty_like(src)
@@ -397,7 +440,7 @@ def main() -> int:
             "mlp_scores_per_s": round(scores_per_s, 1),
             "pairs_scored_per_step": int(st.pairs_scored), "nodes_expanded_per_step": int(st.nodes_expanded),
             "rounds": int(st.max_query_iters), "mfma_kernel": bool(mfma), "stages": stages,
-            "layered_search": layered, "continuous_batching": streamed, "walker_search": walkers,
+            "layered_search": layered, "continuous_batching": streamed, "walker_search": walkers, "f8_metric": f8,
         },
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -100,25 +100,50 @@ mlp_mfma2_f8_kernel(const uint8_t *__restrict__ emb, int64_t N, const float *__r
         bb3[i] = j < J ? b3[j] : 0.f;
     }
 
+    // Item rows are fetched one batch ahead (the head layer of the current batch hides the latency), the pair
+    // ids two batches ahead.  Rows past the end read the last pair and are not stored.
+    struct Ids {
+        int32_t id[CB], q[CB];
+        bool bad[CB];
+    };
+    auto load_ids = [&](int64_t tile) {
+        Ids r;
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            int64_t row = tile * TILE + (int64_t)wave * RW + c * 32 + col;
+            row = row < M ? row : M - 1;
+            const int32_t v = pair_id[row], q = pair_q[row];
+            r.bad[c] = ((uint64_t)(int64_t)v >= (uint64_t)N) | ((uint32_t)q >= (uint32_t)Q);
+            r.id[c] = r.bad[c] ? 0 : v;
+            r.q[c] = r.bad[c] ? 0 : q;
+        }
+        return r;
+    };
+    i32x8 x[CB];
+    auto gather = [&](const Ids &ids) {
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            const uint4 *src = (const uint4 *)(emb + (size_t)ids.id[c] * D + 32 * g);
+            const uint4 lo = src[0], hi = src[1];
+            x[c][0] = lo.x, x[c][1] = lo.y, x[c][2] = lo.z, x[c][3] = lo.w;
+            x[c][4] = hi.x, x[c][5] = hi.y, x[c][6] = hi.z, x[c][7] = hi.w;
+        }
+    };
+    Ids idc = load_ids(blockIdx.x), idn = load_ids((int64_t)blockIdx.x + gridDim.x);
+    gather(idc);
+
 #pragma unroll 1
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t row0 = tile * TILE + (int64_t)wave * RW;
-        i32x8 x[CB];
         const float *up[CB];
         bool bad[CB];
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
-            int64_t row = row0 + c * 32 + col;
-            row = row < M ? row : M - 1;  // rows past the end read the last pair and are not stored
-            int32_t v = pair_id[row], q = pair_q[row];
-            bad[c] = ((uint64_t)(int64_t)v >= (uint64_t)N) | ((uint32_t)q >= (uint32_t)Q);
-            if (bad[c]) v = 0, q = 0;
-            const uint4 *src = (const uint4 *)(emb + (size_t)v * D + 32 * g);
-            const uint4 lo = src[0], hi = src[1];
-            x[c][0] = lo.x, x[c][1] = lo.y, x[c][2] = lo.z, x[c][3] = lo.w;
-            x[c][4] = hi.x, x[c][5] = hi.y, x[c][6] = hi.z, x[c][7] = hi.w;
-            up[c] = upre + (size_t)q * H1 + 4 * g;
+            up[c] = upre + (size_t)idc.q[c] * H1 + 4 * g;
+            bad[c] = idc.bad[c];
         }
+        idc = idn;                                      // the next batch ...
+        idn = load_ids(tile + 2 * (int64_t)gridDim.x);  // ... and the one after it
         f32x16 acc2[NB2][CB];
         // the bias pointer is laundered once per batch: otherwise its loads are hoisted out of the batch
         // loop and their values carried (spilled) across it
@@ -144,20 +169,19 @@ mlp_mfma2_f8_kernel(const uint8_t *__restrict__ emb, int64_t N, const float *__r
             i32x8 h1q[CB];
 #pragma unroll
             for (int hb = 0; hb < 2; ++hb) {
-                f32x16 acc1[CB];
+                const i32x8 a = fragment(2 * ch + hb);
 #pragma unroll
-                for (int c = 0; c < CB; ++c)
+                for (int c = 0; c < CB; ++c) {
+                    f32x16 acc1;
 #pragma unroll
                     for (int t4 = 0; t4 < 4; ++t4) {
                         f32x4 pv = *(const f32x4 *)(up[c] + (2 * ch + hb) * 32 + 8 * t4);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc1[c][4 * t4 + e] = pv[e];
+                        for (int e = 0; e < 4; ++e) acc1[4 * t4 + e] = pv[e];
                     }
-                const i32x8 a = fragment(2 * ch + hb);
-#pragma unroll
-                for (int c = 0; c < CB; ++c) acc1[c] = mfma_f8(a, x[c], acc1[c]);
-#pragma unroll
-                for (int c = 0; c < CB; ++c) quantize_half(acc1[c], h1q[c], hb);
+                    acc1 = mfma_f8(a, x[c], acc1);
+                    quantize_half(acc1, h1q[c], hb);
+                }
             }
             // layer 2: every output unit consumes these 64 hidden units
 #pragma unroll
@@ -167,6 +191,8 @@ mlp_mfma2_f8_kernel(const uint8_t *__restrict__ emb, int64_t N, const float *__r
                 for (int c = 0; c < CB; ++c) acc2[n2][c] = mfma_f8(a, h1q[c], acc2[n2][c]);
             }
         }
+        gather(idc);  // the item rows of the next batch: layer 1 of this one is done with the registers
+
         // head layer (rows >= J of its fragments are zero), then Eq. 8
         f32x16 acc3[CB];
 #pragma unroll

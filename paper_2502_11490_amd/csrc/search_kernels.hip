@@ -300,20 +300,22 @@ init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state
               L, cap, W_max, L_max, cap_max, stats, smem, tag_g);
 }
 
-// First k entries of a slot's list to row `row` of the outputs, padded with (-1, -inf).  The query's
-// counters join the totals here, once per query: every workgroup adding to the same few words in
-// every round made those additions, which the memory side performs one after the other, the
-// longest part of a round.
+// A query's counters join the totals once, when its result is written: every workgroup adding to the
+// same few words in every round made those additions, which the memory side performs one after the
+// other (about 10 ns each), the longest part of a round.  One lane calls this with sums over a
+// group of queries.
+__device__ __forceinline__ void add_to_totals(int64_t *stats, long long scored, long long expanded, int rounds,
+                                              int overflowed) {
+    atomicAdd((unsigned long long *)&stats[0], (unsigned long long)scored);
+    atomicAdd((unsigned long long *)&stats[1], (unsigned long long)expanded);
+    atomicMax((unsigned long long *)&stats[2], (unsigned long long)rounds);
+    if (overflowed) atomicAdd((unsigned long long *)&stats[3], (unsigned long long)overflowed);
+}
+
+// First k entries of a slot's list to row `row` of the outputs, padded with (-1, -inf).
 __device__ void emit_row(const QState *state, const uint64_t *pool_g, int C, int k, int slot, int64_t row,
-                         int32_t *out_ids, float *out_scores, int64_t *stats) {
-    const QState st = state[slot];
-    const int n = st.n_list;
-    if (threadIdx.x == 0) {
-        atomicAdd((unsigned long long *)&stats[0], (unsigned long long)st.n_visited);
-        atomicAdd((unsigned long long *)&stats[1], (unsigned long long)st.n_expanded);
-        atomicMax((unsigned long long *)&stats[2], (unsigned long long)st.t);
-        if (st.done & 2) atomicAdd((unsigned long long *)&stats[3], 1ull);
-    }
+                         int32_t *out_ids, float *out_scores) {
+    const int n = state[slot].n_list;
     const uint64_t *pool = pool_g + (size_t)slot * C;
     for (int i = threadIdx.x; i < k; i += BLOCK) {
         int32_t id = -1;
@@ -360,7 +362,13 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
     const int slot = blockIdx.x;
     if (!state[slot].done) return;  // still searching
     const int served = slot_query[slot];
-    if (served >= 0) emit_row(state, pool_g, C, k, slot, served, out_ids, out_scores, stats);
+    if (served >= 0) {
+        emit_row(state, pool_g, C, k, slot, served, out_ids, out_scores);
+        if (threadIdx.x == 0) {
+            const QState st = state[slot];
+            add_to_totals(stats, st.n_visited, st.n_expanded, st.t, (st.done & 2) ? 1 : 0);
+        }
+    }
     if (threadIdx.x == 0) {
         int next = Q_total;
         // the counter only grows; once it has passed the total nobody needs to touch it again
@@ -648,8 +656,25 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(BLOCK)
 emit_kernel(const QState *__restrict__ state, const uint64_t *__restrict__ pool_g, int C, int k,
-            int32_t *out_ids, float *out_scores, int64_t *stats) {
-    emit_row(state, pool_g, C, k, blockIdx.x, blockIdx.x, out_ids, out_scores, stats);
+            int32_t *out_ids, float *out_scores, int64_t *stats, int Q) {
+    emit_row(state, pool_g, C, k, blockIdx.x, blockIdx.x, out_ids, out_scores);
+    // counters: every 64th workgroup sums those of 64 consecutive queries in its first wave
+    if ((blockIdx.x & 63) == 0 && threadIdx.x < 64) {
+        const int q = blockIdx.x + threadIdx.x;
+        long long scored = 0, expanded = 0;
+        int rounds = 0, overflowed = 0;
+        if (q < Q) {
+            const QState st = state[q];
+            scored = st.n_visited, expanded = st.n_expanded, rounds = st.t, overflowed = (st.done & 2) ? 1 : 0;
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+            scored += __shfl_down(scored, o);
+            expanded += __shfl_down(expanded, o);
+            rounds = max(rounds, __shfl_down(rounds, o));
+            overflowed += __shfl_down(overflowed, o);
+        }
+        if (threadIdx.x == 0) add_to_totals(stats, scored, expanded, rounds, overflowed);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -743,7 +768,7 @@ int launch_emit(const SearchArgs &a) {
     const Plan &p = a.plan;
     hipLaunchKernelGGL(emit_kernel, dim3(p.Q), dim3(BLOCK), 0, a.stream, (const QState *)(a.ws + p.off_state),
                        (const uint64_t *)(a.ws + p.off_pool), p.C, p.k, a.out_ids, a.out_scores,
-                       (int64_t *)(a.ws + p.off_stats));
+                       (int64_t *)(a.ws + p.off_stats), p.Q);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
