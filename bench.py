@@ -411,11 +411,16 @@ def main() -> int:
         ref = oracle.search(h["emb"], h["adj"], hu["users"], mlp, hu["entries"], Wq, Lq, k, cq, n_threads=threads,
                             trace=True)
         cpu_s = time.perf_counter() - t4
-        same = float(np.mean(np.all(ref["ids"] == out_ids[:n_cpu].cpu().numpy(), axis=1)))
+        gpu_ids = out_ids[:n_cpu].cpu().numpy()
+        same = float(np.mean(np.all(ref["ids"] == gpu_ids, axis=1)))
+        # the oracle here is exact arithmetic, the device rounds activations to bf16: the trajectories part at
+        # the first near-tie, so whole lists rarely coincide; how much of the result is shared says more
+        overlap = float(np.mean([len(set(a[:kr].tolist()) & set(b[:kr].tolist()) - {-1}) / kr
+                                 for a, b in zip(ref["ids"], gpu_ids)]))
         cpu = {"value": round(n_cpu / cpu_s, 3), "unit": "queries/s", "cores": threads, "kind": "oracle",
                "sample": f"first {n_cpu} of {Q} queries of the same batch, {cpu_s:.1f} s wall",
                "scores_per_s": round(float(ref["n_scored"].sum()) / cpu_s, 1),
-               "identical_id_lists_vs_gpu": round(same, 4)}
+               "identical_id_lists_vs_gpu": round(same, 4), f"top{kr}_overlap_vs_gpu": round(overlap, 4)}
         log(f"oracle: {cpu['value']} queries/s on {threads} threads")
 
     line = {
