@@ -183,6 +183,15 @@ def main() -> int:
             if r >= 0.95:
                 break
 
+    # how recall goes on beyond the L the step is timed at, up to the largest list the kernels take
+    # (max(L, k) + W*R <= 4096): on the recall sample only, outside the timed step
+    beyond = {}
+    if not ragged and not args.L and L_star is not None and curve.get(str(L_star), 1.0) < 0.95:
+        for L in (cfg.L * 16, cfg.L * 24, 4096 - W * cfg.R):
+            if L > L_star and max(L, k) + W * cfg.R <= 4096:
+                beyond[str(L)] = round(search_sample(L), 4)
+        log(f"recall@{kr} beyond L={L_star}: {beyond}")
+
     # ---- timed region: K full-batch searches, inputs resident in HBM ----
     if ragged:
         Wm, Lm, capm = cfg.W_range[1], cfg.L_range[1], cfg.cap_range[1]
@@ -441,7 +450,7 @@ def main() -> int:
                         f"MLP {'x'.join(str(v) for v in cfg.dims)}, Q={Q} E={E} W={W} L={L_star} k={k}",
             "Q": Q, "E": E, "W": W, "L": L_star, "k": k,
             "recall_at_100": round(recall, 4), "recall_target_met": bool(target_met),
-            "recall_curve_L": curve, "recall_queries": n_gt,
+            "recall_curve_L": curve, "recall_beyond_timed_L": beyond, "recall_queries": n_gt,
             "mlp_scores_per_s": round(scores_per_s, 1),
             "pairs_scored_per_step": int(st.pairs_scored), "nodes_expanded_per_step": int(st.nodes_expanded),
             "rounds": int(st.max_query_iters), "mfma_kernel": bool(mfma), "stages": stages,
