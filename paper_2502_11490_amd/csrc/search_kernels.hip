@@ -554,6 +554,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         for (int i = m + threadIdx.x; i < m2; i += BLOCK) newk[i] = KEY_SENTINEL;
         __syncthreads();
         bitonic_sort(newk, m2);
+        PHASE_MARK(6);  // sort of the new keys
         for (int i = threadIdx.x; i < st.n_list + m; i += BLOCK) {
             uint64_t key;
             int pos;
