@@ -148,6 +148,11 @@ int launch_mlp_alu(const ann_graph *g, const ann_mlp *m, const void *queries, co
         T = 1;
         while (T * 2 <= tile_rows) T *= 2;
     }
+    // A small list (at most M_max pairs) is spread over more workgroups: fewer pairs per workgroup means more
+    // threads per pair, i.e. fewer output units (sequential FMA chains) per thread.  A pair's arithmetic does
+    // not depend on the batch it is in.
+    if (tile_rows <= 0)
+        while (T > 4 && (M_max + T - 1) / T < 512) T >>= 1;
     while (T > 1 && (size_t)2 * T * stride * asz > 144 * 1024) T >>= 1;
     size_t smem = (size_t)2 * T * stride * asz;
     if (smem > 144 * 1024) {
