@@ -404,11 +404,14 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
     // pairs of all earlier queries (and, in the last workgroup, the number of running queries)
     int sum = 0, act = 0;
     const int lim = last ? Q : q0;
-    for (int i = threadIdx.x; i < lim; i += SCAN_BLOCK) {
-        int c = counts[i];
-        if (i < q0) sum += max(c, 0);
-        act += (c >= 0);
+    // q0 is a multiple of 16 and the array is 256-byte aligned: four counts per load up to q0
+    const int4 *counts4 = (const int4 *)counts;
+    for (int i4 = threadIdx.x; i4 < (q0 >> 2); i4 += SCAN_BLOCK) {
+        const int4 c = counts4[i4];
+        sum += max(c.x, 0) + max(c.y, 0) + max(c.z, 0) + max(c.w, 0);
+        act += (c.x >= 0) + (c.y >= 0) + (c.z >= 0) + (c.w >= 0);
     }
+    for (int i = q0 + threadIdx.x; i < lim; i += SCAN_BLOCK) act += (counts[i] >= 0);  // last workgroup only
     for (int o = 32; o > 0; o >>= 1) {
         sum += __shfl_down(sum, o);
         act += __shfl_down(act, o);
