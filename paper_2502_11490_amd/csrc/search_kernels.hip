@@ -386,11 +386,11 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
 
 // ------------------------------------------------------------------------------------------
 // Exclusive scan of survivor counts + stable packing into the dense pair list (Algorithm 2).
-// A workgroup owns SCAN_QPB consecutive queries.  It first sums the counts of all earlier queries
-// (every workgroup re-reads them from L2: O(Q^2 / SCAN_QPB) four-byte reads in total, no waiting on
-// other workgroups, the same result every run), then scans its own counts and copies its groups,
-// one wave per query at a time.
-constexpr int SCAN_QPB = 16;  // queries per workgroup
+// A workgroup owns SCAN_QPB consecutive queries (4 or 8: few, so that many workgroups share the
+// copying).  It first sums the counts of all earlier queries (every workgroup re-reads them from
+// L2: O(Q^2 / SCAN_QPB) four-byte reads in total, no waiting on other workgroups, the same result
+// every run), then scans its own counts and copies its groups, one wave per query at a time.
+template <int SCAN_QPB>  // queries per workgroup, a multiple of 4
 __global__ void __launch_bounds__(SCAN_BLOCK)
 scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__restrict__ cand_g, int slots,
                     int32_t *offsets, int32_t *pair_q, int32_t *pair_id, Ctrl *ctrl,
@@ -404,7 +404,7 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
     // pairs of all earlier queries (and, in the last workgroup, the number of running queries)
     int sum = 0, act = 0;
     const int lim = last ? Q : q0;
-    // q0 is a multiple of 16 and the array is 256-byte aligned: four counts per load up to q0
+    // q0 is a multiple of 4 and the array is 256-byte aligned: four counts per load up to q0
     const int4 *counts4 = (const int4 *)counts;
     for (int i4 = threadIdx.x; i4 < (q0 >> 2); i4 += SCAN_BLOCK) {
         const int4 c = counts4[i4];
@@ -741,8 +741,11 @@ int launch_admit(const SearchArgs &a) {
 
 int launch_scan_compact(const SearchArgs &a) {
     const Plan &p = a.plan;
-    int blocks = (p.Q + SCAN_QPB - 1) / SCAN_QPB;
-    hipLaunchKernelGGL(scan_compact_kernel, dim3(blocks), dim3(SCAN_BLOCK), 0, a.stream,
+    // every workgroup reads the counts of all earlier queries: with very many queries fewer, larger workgroups
+    const int qpb = p.Q <= 8192 ? 4 : 8;
+    const int blocks = (p.Q + qpb - 1) / qpb;
+    auto fn = qpb == 4 ? scan_compact_kernel<4> : scan_compact_kernel<8>;
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(SCAN_BLOCK), 0, a.stream,
                        (const int32_t *)(a.ws + p.off_counts), p.Q, (const int32_t *)(a.ws + p.off_cand),
                        p.slots, (int32_t *)(a.ws + p.off_offsets), (int32_t *)(a.ws + p.off_pair_q),
                        (int32_t *)(a.ws + p.off_pair_id), (Ctrl *)(a.ws + p.off_ctrl), a.slot_query, a.mailbox,
