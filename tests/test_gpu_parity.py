@@ -486,3 +486,36 @@ def test_walker_search_bf16_mfma():
     # the share of identical lists is reported, the bar for bf16 is the score error and the recall above.
     print(f"walkers C3-shaped: recall gpu {r_gpu:.4f} oracle {r_ref:.4f}; identical lists vs kernel-precision "
           f"oracle {same_list_fraction(ids, kern['ids']):.3f}")
+
+
+# ----------------------------------------------------------------------------- host side
+def test_concurrent_searches_from_two_host_threads():
+    """Each host thread follows its own searches' progress (the convergence word is per thread): two threads
+    searching at once, on their own streams and workspaces, get what a single thread gets."""
+    import threading
+    cfg = scaled(PRESETS["C2"], 20000, n_clusters=16, Q=96)
+    wl = make_workload(cfg)
+    g, m, dev = open_handles(wl)
+    k = 20
+    want = [ann.ann_search(g, m, dev["users"], dev["entries"], cfg.W, L, k, 0)[0].cpu() for L in (32, 64)]
+    got, errors = [None, None], []
+
+    def worker(i, L):
+        try:
+            s = torch.cuda.Stream()
+            with torch.cuda.stream(s):
+                for _ in range(5):
+                    ids, _ = ann.ann_search(g, m, dev["users"], dev["entries"], cfg.W, L, k, 0, stream=s)
+                s.synchronize()
+            got[i] = ids.cpu()
+        except Exception as e:  # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i, L)) for i, L in enumerate((32, 64))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(120)
+    assert not errors, errors
+    assert all(not t.is_alive() for t in threads)
+    assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
