@@ -132,6 +132,19 @@ __device__ void bitonic_sort(uint64_t *keys, int n) {
 __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_key, uint32_t *dd_pos,
                                  uint32_t *bk_key, uint32_t *bk_cnt, int dd_n, uint32_t *table, int hash_cap,
                                  int64_t N, int32_t *out, int *wave_sums, uint16_t *out_tag, int tag_div) {
+    const int n_buckets = hash_cap >> 4;
+    const uint32_t bmask = (uint32_t)n_buckets - 1u;
+    const int bshift = 32 - (31 - __clz(n_buckets));  // n_buckets = 2^b (b >= 2) -> top b bits
+    // The first BLOCK candidates request their home bucket right away, repeated ids included: the lines
+    // travel while the dedupe below runs in LDS.  Nothing is stored to the table before pass 2.
+    uint4 pre0 = {}, pre1 = {}, pre2 = {}, pre3 = {};
+    if ((int)threadIdx.x < n_cand) {
+        const int32_t v = cand[threadIdx.x];
+        if (v >= 0 && (int64_t)v < N) {
+            const uint4 *line = (const uint4 *)(table + (size_t)(hash_id((uint32_t)v) >> bshift) * 16);
+            pre0 = line[0], pre1 = line[1], pre2 = line[2], pre3 = line[3];
+        }
+    }
     for (int i = threadIdx.x; i < dd_n; i += BLOCK) {
         dd_key[i] = EMPTY_SLOT;
         dd_pos[i] = 0xFFFFFFFFu;
@@ -154,9 +167,6 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
     }
     __syncthreads();
     // pass 2: first occurrences look themselves up in the visited table and enter it if absent
-    const int n_buckets = hash_cap >> 4;
-    const uint32_t bmask = (uint32_t)n_buckets - 1u;
-    const int bshift = 32 - (31 - __clz(n_buckets));  // n_buckets = 2^b (b >= 2) -> top b bits
     int n_new = 0;
     for (int p0 = 0; p0 < n_cand; p0 += BLOCK) {
         const int p = p0 + threadIdx.x;
@@ -172,6 +182,7 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
                 bkt = hash_id((uint32_t)v) >> bshift;
             }
         }
+        bool home = (p0 == 0);  // the bucket requested at the top is this candidate's and still current
         for (;;) {
             for (int i = threadIdx.x; i < dd_n; i += BLOCK) {
                 bk_key[i] = EMPTY_SLOT;
@@ -181,8 +192,11 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
             bool found = false;
             int cnt = 0;
             if (active) {
-                const uint4 *line = (const uint4 *)(table + (size_t)bkt * 16);
-                uint4 q0 = line[0], q1 = line[1], q2 = line[2], q3 = line[3];
+                uint4 q0 = pre0, q1 = pre1, q2 = pre2, q3 = pre3;
+                if (!home) {
+                    const uint4 *line = (const uint4 *)(table + (size_t)bkt * 16);
+                    q0 = line[0], q1 = line[1], q2 = line[2], q3 = line[3];
+                }
                 const uint32_t w[16] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w,
                                         q2.x, q2.y, q2.z, q2.w, q3.x, q3.y, q3.z, q3.w};
 #pragma unroll
@@ -227,6 +241,7 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
             // fence would write the whole L2 slice back.
             __threadfence_block();
             __syncthreads();
+            home = false;
         }
         int tot;
         int pos = block_excl_count(fresh, wave_sums, &tot);
@@ -484,7 +499,8 @@ __device__ __forceinline__ int lower_bound_keys(const uint64_t *a, int n, uint64
     return lo;
 }
 
-__global__ void __launch_bounds__(BLOCK)
+// Eight workgroups of 256 threads fill a CU's wave slots; that needs no more than 64 registers per lane.
+__global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8)))
 round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, uint64_t *pool_g, int C,
              uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
              const int32_t *__restrict__ offsets, const float *__restrict__ scores, int new_cap,
