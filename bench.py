@@ -5,10 +5,12 @@ A step = one ann_search call over the whole query batch of the workload (every s
 path: seeding, rounds of parent choice / neighbour gather / visited filter, packing, MLP scoring,
 merge, top-k).  Inputs are generated once on the GPU and are resident in HBM when timing starts.
 
-Prints ONE JSON line (see the design doc for the fields).  Besides the headline queries/s it carries
+Prints ONE JSON line.  Besides the headline queries/s it carries
   roofline     : the MLP scoring kernel (the dominant kernel) against the dense bf16 MFMA peak,
                  timed live with HIP events recorded on the search's stream by the library;
-  cpu_baseline : the CPU oracle, as it stands, on a bounded sample of the same queries.
+  cpu_baseline : the CPU oracle, as it stands, on a bounded sample of the same queries;
+  config       : the workload, its recall curve, per-stage times, and beside the timed step the
+                 layer-by-layer search, continuous batching, the walker rule and the 8-bit metric.
 """
 from __future__ import annotations
 
@@ -115,7 +117,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (queries would shard across GPUs "
-              "with the graph replicated; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "with the graph replicated). Run with --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np
