@@ -138,7 +138,8 @@ struct Mailbox {
         if (hipHostGetDevicePointer(&d, h, 0) != hipSuccess) return false;
         host = (volatile uint64_t *)h;
         dev = (uint64_t *)d;
-        *host = 0;
+        host[0] = 0;
+        host[1] = 0;
         ok = true;
         return true;
     }
@@ -146,6 +147,11 @@ struct Mailbox {
         seq = (seq + 1) & 0xFFFFFFull;
         if (seq == 0) seq = 1;
         return seq << 40;
+    }
+    // Queries still running at the last round the device reported for this search, -1 = nothing reported yet.
+    int64_t running(uint64_t tag) const {
+        const uint64_t w = host[1];
+        return (w >> 40) == (tag >> 40) ? (int64_t)(w & 0xFFFFFFFFull) : -1;
     }
     // Before enqueuing round `i` (0-based): 1 = the search has finished, 0 = go on, -1 = the device made no
     // progress for a long time.
@@ -264,6 +270,10 @@ static int run_search(SearchArgs &a) {
         if ((rc = score_batch(a)) != ANN_OK) return rc;
         {
             StageTimer timer(ANN_STAGE_ROUND, a.stream);
+            if (box) {
+                const int64_t n = box->running(a.mail_tag);
+                a.speculate = n < 0 || 2 * n >= p.Q;
+            }
             if ((rc = launch_round(a)) != ANN_OK) return rc;
         }
     }
@@ -324,6 +334,10 @@ static int run_stream(SearchArgs &a) {
         if ((rc = score_batch(a)) != ANN_OK) return rc;
         {
             StageTimer timer(ANN_STAGE_ROUND, a.stream);
+            if (box) {
+                const int64_t n = box->running(a.mail_tag);
+                a.speculate = n < 0 || 2 * n >= p.Q;
+            }
             if ((rc = launch_round(a)) != ANN_OK) return rc;
         }
     }

@@ -135,6 +135,8 @@ struct SearchArgs {
     uint64_t *mailbox = nullptr;
     uint64_t mail_tag = 0;
     int32_t round_index = 0;
+    // round kernel: request a query's list before knowing whether the query still runs (right while most do)
+    bool speculate = true;
 };
 
 // search_kernels.hip

@@ -463,6 +463,8 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
         if (mailbox) {
             // progress for the enqueuing host thread: one store to pinned host memory, nobody waits for it
             const bool finished = n_active == 0 && (Q_total <= 0 || ctrl->next_query >= Q_total);
+            __hip_atomic_store(mailbox + 1, (mail_word & ~0xFFFFFFFFFFull) | (uint64_t)(uint32_t)n_active,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);  // a hint only: see round_kernel
             __hip_atomic_store(mailbox, mail_word | (finished ? 1ull : 0ull), __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_SYSTEM);
         }
@@ -504,7 +506,7 @@ __global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8
 round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, uint64_t *pool_g, int C,
              uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
              const int32_t *__restrict__ offsets, const float *__restrict__ scores, int new_cap,
-             int W_max, int64_t *stats, uint16_t *tag_g, int walkers) {
+             int W_max, int64_t *stats, uint16_t *tag_g, int walkers, int speculate) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int q = blockIdx.x;
     PHASE_START
@@ -523,7 +525,11 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
 
     // Everything the round needs first is requested at once, before any of it is looked at (the
     // whole list, not only its n_list valid entries): the workgroups of a launch start together,
-    // and every dependent trip to memory costs them all a few microseconds.
+    // and every dependent trip to memory costs them all a few microseconds.  Once most queries of the
+    // batch have finished (the host says so, from what the packing kernel last reported; either way
+    // is correct) a workgroup looks first whether its query is still running: a finished one then
+    // costs four bytes instead of its whole list.
+    if (!speculate && counts[q] < 0) return;  // finished or idle: counts[q] stays -1
     QState st = state[q];
     const int n_prev = counts[q];
     const int off = offsets[q];
@@ -782,7 +788,8 @@ int launch_round(const SearchArgs &a) {
                        (uint32_t *)(a.ws + p.off_hash), p.hash_cap, (int32_t *)(a.ws + p.off_cand), p.slots,
                        (int32_t *)(a.ws + p.off_counts), (const int32_t *)(a.ws + p.off_offsets),
                        (const float *)(a.ws + p.off_scores), new_cap_of(p), p.W_max,
-                       (int64_t *)(a.ws + p.off_stats), (uint16_t *)(a.ws + p.off_tag), a.walkers ? 1 : 0);
+                       (int64_t *)(a.ws + p.off_stats), (uint16_t *)(a.ws + p.off_tag), a.walkers ? 1 : 0,
+                       a.speculate ? 1 : 0);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
