@@ -257,7 +257,8 @@ int ann_users_add_noise(const void *users_dev, void *out_dev, int32_t Q, int32_t
  * half of the first layer stays bf16 and is applied in fp32, once per query); products are
  * accumulated in fp32; the activations of hidden layer l are clamped to [0, 448 / 4^l] and rounded
  * to e4m3 at scale 4^l (nearest even); logits, sigmoid and the weighted sum are fp32.
- * Built for one shape: 64-wide items, hidden widths 256 and 128, up to 8 heads (else ANN_ENOTIMPL);
+ * Built for two shapes: 64-wide items with hidden widths 256 and 128, 128-wide items with hidden
+ * widths 512 and 256, up to 8 heads (else ANN_ENOTIMPL);
  * ANN_EINVAL if a weight times 4 exceeds 448.
  *
  * ann_quantize_e4m3 makes such an item table: dst_dev[i] = e4m3(scale * src_dev[i]) (nearest even,

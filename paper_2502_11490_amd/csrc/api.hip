@@ -134,7 +134,7 @@ struct Mailbox {
     bool init() {
         if (ok) return true;
         void *h = nullptr, *d = nullptr;
-        if (hipHostMalloc(&h, 64, hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) return false;
+        if (hipHostMalloc(&h, 64, hipHostMallocPortable | hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) return false;
         if (hipHostGetDevicePointer(&d, h, 0) != hipSuccess) return false;
         host = (volatile uint64_t *)h;
         dev = (uint64_t *)d;
@@ -456,7 +456,7 @@ int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *
         return ANN_EINVAL;
     }
     if (dtype == ANN_F8 && !f8_supported(dims_host, n_layers, d_user)) {
-        set_error("the 8-bit metric is built for 64-wide items and hidden widths 256, 128 only");
+        set_error("the 8-bit metric is built for 64-wide items with hidden widths 256, 128 and 128-wide items with 512, 256");
         return ANN_ENOTIMPL;
     }
     for (int l = 0; l <= n_layers; ++l)

@@ -1,6 +1,7 @@
 // The relevance metric of Sec. 3.1 (1), Eq. 5-8, with 8-bit operands (the quantised deployment of
 // Sec. 4.3 taken one step further than 16 bits): e4m3 item vectors, weights and hidden activations on
-// v_mfma_f32_32x32x64_f8f6f4, fp32 accumulation.  Shape served: 64-wide items, hidden 256 and 128.
+// v_mfma_f32_32x32x64_f8f6f4, fp32 accumulation.  Shapes served: 64-wide items with hidden 256 and 128 (all
+// weights resident in LDS), 128-wide items with hidden 512 and 256 (see mlp_mfma2_f8_wide_kernel).
 //
 // Same transposed formulation as the bf16 kernels (H_out^T = W * H_in^T, weights are the A operand,
 // the activations of 32 pairs the B operand), with a contraction of 64 per instruction: lane (m, g)
@@ -17,7 +18,7 @@
 // v_med3_f32, the rounding one v_cvt_pk_fp8_f32 per two values.  The head accumulators are 64 x the
 // logits.
 //
-// All weights (52 KB) stay in LDS; a workgroup of eight waves, 64 pairs per wave.
+// Narrow shape: all weights (52 KB) stay in LDS; a workgroup of eight waves, 64 pairs per wave.
 #include <math.h>
 #include <string.h>
 
@@ -225,6 +226,276 @@ mlp_mfma2_f8_kernel(const uint8_t *__restrict__ emb, int64_t N, const float *__r
     }
 }
 
+// The wide shape (128-wide items, hidden 512 and 256): 200 KB of e4m3 weights do not fit the LDS.  The
+// second layer's (128 KB) and the head's fragments stay resident; the first layer's 64 KB are read by every
+// wave straight from global memory (they are hot in L2: every wave of the chip reads the same 64 KB per batch),
+// one block of 32 hidden units ahead of its use, so the main loop has no barrier and no staging.
+// The 256 layer-2 accumulators of a wave fill the accumulation registers; the short-lived layer-1 and head
+// accumulators are pinned to ordinary registers by writing their MFMAs as inline assembly, with the hazards the
+// compiler would otherwise handle kept by hand:
+//   - a register written by a vector-ALU instruction is not read by an MFMA in the next two issue slots
+//     (s_nop 1 in front of every such MFMA);
+//   - an accumulator is not the target of two consecutive MFMAs (pairs 0 and 1 alternate);
+//   - the vector ALU reads an MFMA result only after the MFMA has drained (F8_DRAIN).
+// The MFMAs on pinned accumulators and the idle cycles that let the last of them finish are ONE statement:
+// between two statements the compiler may copy an accumulator to other registers (it does, to free the
+// tuple for the next block's user term), and such a copy right behind an MFMA reads a result that is not there yet.
+// A 16-pass MFMA writes its result 64 cycles after issue: five times 16 idle cycles cover the last one.
+#define F8_DRAIN "s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15"
+// one block of 32 hidden units, two contraction steps, two column blocks of pairs
+__device__ __forceinline__ void layer1_block(f32x16 &acc0, f32x16 &acc1, const i32x8 &w0, const i32x8 &w1,
+                                             const i32x8 &x00, const i32x8 &x01, const i32x8 &x10,
+                                             const i32x8 &x11) {
+    asm volatile("s_nop 1\n\t"
+                 "v_mfma_f32_32x32x64_f8f6f4 %0, %2, %4, %0\n\t"
+                 "v_mfma_f32_32x32x64_f8f6f4 %1, %2, %6, %1\n\t"
+                 "v_mfma_f32_32x32x64_f8f6f4 %0, %3, %5, %0\n\t"
+                 "v_mfma_f32_32x32x64_f8f6f4 %1, %3, %7, %1\n\t" F8_DRAIN
+                 : "+v"(acc0), "+v"(acc1)
+                 : "v"(w0), "v"(w1), "v"(x00), "v"(x01), "v"(x10), "v"(x11));
+}
+// one contraction step of the head layer for both column blocks
+__device__ __forceinline__ void head_step(f32x16 &acc0, f32x16 &acc1, const i32x8 &a, const i32x8 &h0,
+                                          const i32x8 &h1) {
+    asm volatile("s_nop 1\n\t"
+                 "v_mfma_f32_32x32x64_f8f6f4 %0, %2, %3, %0\n\t"
+                 "v_mfma_f32_32x32x64_f8f6f4 %1, %2, %4, %1\n\t" F8_DRAIN
+                 : "+v"(acc0), "+v"(acc1)
+                 : "v"(a), "v"(h0), "v"(h1));
+}
+// layer 2: accumulate in place in the accumulation registers (the allocator, left to itself, moves a tile to
+// a fresh tuple now and then, and there is none to spare)
+__device__ __forceinline__ void mfma_f8_a(f32x16 &acc, const i32x8 &a, const i32x8 &b) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// Fragments as above with two contraction steps in layer 1: fragment KS*blk + ks holds W1_item[32 blk + m][64 ks + 32g + b].
+template <int D, int H1, int H2>
+__global__ void __launch_bounds__(256)
+mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float *__restrict__ upre,
+                         const uint4 *__restrict__ frag, const float *__restrict__ b2s, const float *__restrict__ b3,
+                         const float *__restrict__ head_w, int J, const int32_t *__restrict__ pair_q,
+                         const int32_t *__restrict__ pair_id, const int32_t *__restrict__ M_dev, int64_t M_max,
+                         int32_t Q, float *__restrict__ scores) {
+    constexpr int CB = 2, WAVES = 4;
+    constexpr int KS = D / 64, NB1 = H1 / 32, NC = H1 / 64, NB2 = H2 / 32, NP = H2 / 64;
+    static_assert(KS == 2, "layer1_block contracts two steps of 64");
+    constexpr int N_W1 = NB1 * KS;                 // fragments that stay in global memory
+    constexpr int N_LDS = NC * NB2 + NP;           // fragments resident in LDS
+    constexpr int BLOCK_T = 64 * WAVES;
+    constexpr int RW = 32 * CB, TILE = RW * WAVES;
+    extern __shared__ __align__(16) uint4 lds[];   // [N_LDS][2][64]
+
+    int64_t M = (int64_t)*M_dev;
+    if (M > M_max) M = M_max;
+    const int64_t n_tiles = (M + TILE - 1) / TILE;
+    if ((int64_t)blockIdx.x >= n_tiles) return;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int g = lane >> 5, col = lane & 31;
+    for (int i = threadIdx.x; i < N_LDS * 128; i += BLOCK_T) lds[i] = frag[(size_t)N_W1 * 128 + i];
+    __syncthreads();
+
+    auto fragment = [&](int f) {   // f counts from the first resident fragment
+        const uint4 lo = lds[f * 128 + lane], hi = lds[f * 128 + 64 + lane];
+        i32x8 a;
+        a[0] = lo.x, a[1] = lo.y, a[2] = lo.z, a[3] = lo.w, a[4] = hi.x, a[5] = hi.y, a[6] = hi.z, a[7] = hi.w;
+        return a;
+    };
+    auto w1_fragment = [&](int f) {  // straight from global memory
+        const uint4 lo = frag[(size_t)f * 128 + lane], hi = frag[(size_t)f * 128 + 64 + lane];
+        i32x8 a;
+        a[0] = lo.x, a[1] = lo.y, a[2] = lo.z, a[3] = lo.w, a[4] = hi.x, a[5] = hi.y, a[6] = hi.z, a[7] = hi.w;
+        return a;
+    };
+
+    float hw[4], bb3[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int j = 4 * g + i;
+        hw[i] = j < J ? head_w[j] : 0.f;
+        bb3[i] = j < J ? b3[j] : 0.f;
+    }
+
+    struct Ids {
+        int32_t id[CB], q[CB];
+        bool bad[CB];
+    };
+    auto load_ids = [&](int64_t tile) {
+        Ids r;
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            int64_t row = tile * TILE + (int64_t)wave * RW + c * 32 + col;
+            row = row < M ? row : M - 1;  // rows past the end read the last pair and are not stored
+            const int32_t v = pair_id[row], q = pair_q[row];
+            r.bad[c] = ((uint64_t)(int64_t)v >= (uint64_t)N) | ((uint32_t)q >= (uint32_t)Q);
+            r.id[c] = r.bad[c] ? 0 : v;
+            r.q[c] = r.bad[c] ? 0 : q;
+        }
+        return r;
+    };
+    i32x8 x[CB][KS];
+    auto gather = [&](const Ids &ids) {
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const uint4 *src = (const uint4 *)(emb + (size_t)ids.id[c] * D + 64 * ks + 32 * g);
+                const uint4 lo = src[0], hi = src[1];
+                x[c][ks][0] = lo.x, x[c][ks][1] = lo.y, x[c][ks][2] = lo.z, x[c][ks][3] = lo.w;
+                x[c][ks][4] = hi.x, x[c][ks][5] = hi.y, x[c][ks][6] = hi.z, x[c][ks][7] = hi.w;
+            }
+    };
+    Ids idc = load_ids(blockIdx.x), idn = load_ids((int64_t)blockIdx.x + gridDim.x);
+    gather(idc);
+    // Two sets (P: even blocks, Q: odd blocks) of first-layer fragments and of layer-1 accumulators: once both
+    // blocks of a chunk are contracted, the sets receive the next chunk's fragments and user term, which travel
+    // while layer 2 of this chunk runs.  An empty memory-clobbering statement keeps the compiler from moving
+    // loads across it: requests are issued where they are written.
+#define F8_FENCE asm volatile("" ::: "memory")
+    i32x8 w1P[KS], w1Q[KS];
+    f32x16 accP[CB], accQ[CB];
+    auto load_user_term = [&](f32x16 (&acc)[CB], const float *const (&upc)[CB], int blk) {
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) {
+                f32x4 pv = *(const f32x4 *)(upc[c] + blk * 32 + 8 * t4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[c][4 * t4 + e] = pv[e];
+            }
+    };
+    const float *up[CB];
+    bool bad[CB];
+#pragma unroll
+    for (int c = 0; c < CB; ++c) {
+        up[c] = upre + (size_t)idc.q[c] * H1 + 4 * g;
+        bad[c] = idc.bad[c];
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        w1P[ks] = w1_fragment(ks);
+        w1Q[ks] = w1_fragment(KS + ks);
+    }
+    load_user_term(accP, up, 0);
+    load_user_term(accQ, up, 1);
+
+#pragma unroll 1
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t row0 = tile * TILE + (int64_t)wave * RW;
+        bool bad_now[CB];
+        const float *upn[CB];   // the next batch's user rows: its block 0 is requested during this batch's last block
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            bad_now[c] = bad[c];
+            upn[c] = upre + (size_t)idn.q[c] * H1 + 4 * g;
+        }
+        f32x16 acc2[NB2][CB];
+        int opaque_zero = 0;  // keeps the bias loads inside the batch loop (see the narrow kernel)
+        asm volatile("" : "+s"(opaque_zero));
+        const float *b2t = b2s + opaque_zero;
+#pragma unroll
+        for (int n2 = 0; n2 < NB2; ++n2) {
+            f32x16 init;
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) {
+                f32x4 bv = *(const f32x4 *)(b2t + n2 * 32 + 8 * t4 + 4 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) init[4 * t4 + e] = bv[e];
+            }
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                acc2[n2][c] = init;
+                asm volatile("" : "+a"(acc2[n2][c]));  // into the accumulation registers now, not at first use
+            }
+            F8_FENCE;
+        }
+#pragma unroll 1
+        for (int ch = 0; ch < NC; ++ch) {
+            // layer 1 of hidden units 64 ch .. 64 ch + 63: even block from set P, odd block from set Q
+            i32x8 h1q[CB];
+            layer1_block(accP[0], accP[1], w1P[0], w1P[1], x[0][0], x[0][1], x[1][0], x[1][1]);
+#pragma unroll
+            for (int c = 0; c < CB; ++c) quantize_half(accP[c], h1q[c], 0);
+            layer1_block(accQ[0], accQ[1], w1Q[0], w1Q[1], x[0][0], x[0][1], x[1][0], x[1][1]);
+#pragma unroll
+            for (int c = 0; c < CB; ++c) quantize_half(accQ[c], h1q[c], 1);
+            F8_FENCE;
+            // both sets are free now: they receive the next chunk's fragments and user term (after the last
+            // chunk: those of the next batch's first chunk), which travel while layer 2 runs
+            const bool wrap = (ch + 1 == NC);
+            const int nb = wrap ? 0 : 2 * ch + 2;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                w1P[ks] = w1_fragment(nb * KS + ks);
+                w1Q[ks] = w1_fragment((nb + 1) * KS + ks);
+            }
+            if (wrap) {
+                load_user_term(accP, upn, 0);
+                load_user_term(accQ, upn, 1);
+            } else {
+                load_user_term(accP, up, nb);
+                load_user_term(accQ, up, nb + 1);
+            }
+            F8_FENCE;
+            // layer 2: every output unit consumes these 64 hidden units; fragments one ahead (the fragment read
+            // and its wait separate the conversions above from the first MFMA by far more than two issue slots)
+            i32x8 a = fragment(NB2 * ch);
+#pragma unroll
+            for (int n2 = 0; n2 < NB2; ++n2) {
+                i32x8 an = a;
+                if (n2 + 1 < NB2) an = fragment(NB2 * ch + n2 + 1);
+                F8_FENCE;
+#pragma unroll
+                for (int c = 0; c < CB; ++c) mfma_f8_a(acc2[n2][c], a, h1q[c]);
+                a = an;
+            }
+            F8_FENCE;
+        }
+        // the last layer-2 MFMAs drain before their tiles are read (the earlier ones finished long ago)
+        asm volatile(F8_DRAIN : "+a"(acc2[NB2 - 1][0]), "+a"(acc2[NB2 - 1][1]), "+a"(acc2[NB2 - 2][0]), "+a"(acc2[NB2 - 2][1]));
+        // ids: the next batch becomes the current one, the one after it is requested
+        idc = idn;
+        idn = load_ids(tile + 2 * (int64_t)gridDim.x);
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            up[c] = upn[c];
+            bad[c] = idc.bad[c];
+        }
+        gather(idc);  // the item rows of the next batch: layer 1 of this one is done with the registers
+        F8_FENCE;
+
+        f32x16 acc3[CB];
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc3[c][i] = 0.f;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const i32x8 a = fragment(NC * NB2 + p);
+            i32x8 h2q[CB];
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                quantize_half(acc2[2 * p][c], h2q[c], 0);
+                quantize_half(acc2[2 * p + 1][c], h2q[c], 1);
+            }
+            head_step(acc3[0], acc3[1], a, h2q[0], h2q[1]);
+        }
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            float part = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float logit = acc3[c][i] * (1.0f / F8_LOGIT_SCALE) + bb3[i];
+                part = fmaf(hw[i], 1.0f / (1.0f + expf(-logit)), part);
+            }
+            float other = __shfl_xor(part, 32);
+            int64_t row = row0 + c * 32 + col;
+            if (g == 0 && row < M) scores[row] = bad_now[c] ? __uint_as_float(0x7fc00000u) : part + other;
+        }
+    }
+}
+
 // ---- host side: e4m3 encoding of the weights (nearest even; the format: sign, 4 exponent bits with
 // bias 7, 3 mantissa bits, subnormals below 2^-6, largest value 448) ----
 static bool encode_e4m3(float v, uint8_t *code) {
@@ -254,7 +525,9 @@ static inline float bf16_value(uint16_t bits) {
 bool f8_supported(const int32_t *dims, int32_t n_layers, int32_t d_user) {
     if (n_layers != 3 || d_user < 1) return false;
     const int J = dims[3];
-    return dims[0] - d_user == 64 && dims[1] == 256 && dims[2] == 128 && J >= 1 && J <= MAX_HEADS;
+    if (J < 1 || J > MAX_HEADS) return false;
+    const int D = dims[0] - d_user;
+    return (D == 64 && dims[1] == 256 && dims[2] == 128) || (D == 128 && dims[1] == 512 && dims[2] == 256);
 }
 
 static inline int f8_unit(int c, int g, int b) { return 64 * c + 32 * (b / 16) + 8 * ((b % 16) / 4) + 4 * g + b % 4; }
@@ -262,8 +535,9 @@ static inline int f8_unit(int c, int g, int b) { return 64 * c + 32 * (b / 16) +
 // W_host: bf16 matrices as for the bf16 metric.  Fails (ANN_EINVAL) if a weight times 4 exceeds 448.
 int build_f8_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream) {
     const int D = m->d_item, H1 = m->dims[1], H2 = m->dims[2], J = m->J, du = m->d_user;
-    const int NB1 = H1 / 32, NC = H1 / 64, NB2 = H2 / 32, NP = H2 / 64;
-    const int n_frag = NB1 + NC * NB2 + NP;
+    const int KS = D / 64, NB1 = H1 / 32, NC = H1 / 64, NB2 = H2 / 32, NP = H2 / 64;
+    const int n_w1 = NB1 * KS;
+    const int n_frag = n_w1 + NC * NB2 + NP;
     std::vector<uint8_t> buf((size_t)n_frag * 2048, 0);
     const uint16_t *W1 = (const uint16_t *)W_host[0], *W2 = (const uint16_t *)W_host[1],
                    *W3 = (const uint16_t *)W_host[2];
@@ -276,12 +550,14 @@ int build_f8_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stream
     for (int l = 0; l < 64; ++l) {
         const int mrow = l & 31, g = l >> 5;
         for (int b = 0; b < 32; ++b) {
-            for (int blk = 0; blk < NB1; ++blk) put(blk, l, b, W1[(size_t)(32 * blk + mrow) * (du + D) + du + 32 * g + b]);
+            for (int blk = 0; blk < NB1; ++blk)
+                for (int ks = 0; ks < KS; ++ks)
+                    put(blk * KS + ks, l, b, W1[(size_t)(32 * blk + mrow) * (du + D) + du + 64 * ks + 32 * g + b]);
             for (int c = 0; c < NC; ++c)
                 for (int n2 = 0; n2 < NB2; ++n2)
-                    put(NB1 + NB2 * c + n2, l, b, W2[(size_t)(32 * n2 + mrow) * H1 + f8_unit(c, g, b)]);
+                    put(n_w1 + NB2 * c + n2, l, b, W2[(size_t)(32 * n2 + mrow) * H1 + f8_unit(c, g, b)]);
             if (mrow < J)
-                for (int p = 0; p < NP; ++p) put(NB1 + NC * NB2 + p, l, b, W3[(size_t)mrow * H2 + f8_unit(p, g, b)]);
+                for (int p = 0; p < NP; ++p) put(n_w1 + NC * NB2 + p, l, b, W3[(size_t)mrow * H2 + f8_unit(p, g, b)]);
         }
     }
     if (!ok) {
@@ -299,6 +575,20 @@ int launch_mlp_mfma_f8(const ann_graph *g, const ann_mlp *m, const float *upre, 
                        const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
                        hipStream_t stream) {
     if (M_max <= 0) return ANN_OK;
+    if (m->d_item == 128) {
+        constexpr int D = 128, H1 = 512, H2 = 256, TILE = 256;
+        constexpr size_t smem = (size_t)((H1 / 64) * (H2 / 32) + H2 / 64) * 2048;  // 136 KB
+        auto fn = mlp_mfma2_f8_wide_kernel<D, H1, H2>;
+        static std::atomic<uint32_t> raised;
+        if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised); rc != ANN_OK) return rc;
+        int64_t tiles = (M_max + TILE - 1) / TILE;
+        int grid = (int)(tiles < 256 ? tiles : 256);
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(256), smem, stream, (const uint8_t *)g->emb, g->N, upre,
+                           (const uint4 *)m->frag_dev, m->b_dev + m->b_off[1], m->b_dev + m->b_off[2], m->head_w_dev,
+                           m->J, pair_q, pair_id, M_dev, M_max, Q, scores);
+        ANN_HIP_TRY(hipGetLastError());
+        return ANN_OK;
+    }
     constexpr int D = 64, H1 = 256, H2 = 128, CB = 2, WAVES = 8;
     constexpr int N_FRAG = H1 / 32 + (H1 / 64) * (H2 / 32) + H2 / 64;
     constexpr size_t smem = (size_t)N_FRAG * 2048;  // 52 KB

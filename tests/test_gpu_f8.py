@@ -53,10 +53,11 @@ def test_quantiser_clamps_and_handles_empty_and_bad_arguments():
             ann.ann_quantize_e4m3(x, bad)
 
 
-def _f8_problem(N=6000, Q=45, seed=13, bias_scale=0.2):
-    """A C2-shaped workload (64-wide items, 128 -> 256 -> 128 -> J) in the 8-bit metric: the device handles and
-    the oracle's view of the same numbers (quantised tables and weights as ordinary fp32 values)."""
-    cfg = scaled(PRESETS["C2"], N, n_clusters=12, Q=Q)
+def _f8_problem(N=6000, Q=45, seed=13, bias_scale=0.2, preset="C2"):
+    """A C2-shaped (64-wide items, 128 -> 256 -> 128 -> J) or C3-shaped (128-wide, 256 -> 512 -> 256 -> J) workload
+    in the 8-bit metric: the device handles and the oracle's view of the same numbers (quantised tables and
+    weights as ordinary fp32 values)."""
+    cfg = scaled(PRESETS[preset], N, n_clusters=12, Q=Q)
     wl = make_workload(cfg)
     wl["W"], wl["b"] = random_mlp(cfg.dims, seed, cfg.dtype, bias_scale=bias_scale)
     emb8 = ann.ann_quantize_e4m3(wl["emb"].cuda())
@@ -75,8 +76,9 @@ def _f8_problem(N=6000, Q=45, seed=13, bias_scale=0.2):
     return cfg, g, m, users, wl["entries"].cuda().contiguous(), view
 
 
-def test_relevance_f8():
-    cfg, g, m, users, _, v = _f8_problem()
+@pytest.mark.parametrize("preset", ["C2", "C3"])
+def test_relevance_f8(preset):
+    cfg, g, m, users, _, v = _f8_problem(preset=preset)
     rng = np.random.default_rng(3)
     M = 2 * 1024 + 77   # several batches and a ragged tail
     q = np.sort(rng.integers(0, cfg.Q, M)).astype(np.int32)
@@ -92,7 +94,7 @@ def test_relevance_f8():
     assert np.median(err) <= 1e-4, f"median {np.median(err)}"
     exact = oracle.score_pairs(v["emb_exact"], v["users"], v["mlp_exact"], q, it, n_threads=8)
     cost = np.abs(got - exact)
-    print(f"8-bit metric against the unquantised one: mean |error| {cost.mean():.4f}, max {cost.max():.4f}; "
+    print(f"{preset} 8-bit metric against the unquantised one: mean |error| {cost.mean():.4f}, max {cost.max():.4f}; "
           f"against the oracle at the kernel's precision: median {np.median(err):.2e}, max {err.max():.2e}")
     # the price of 3 mantissa bits (relative rounding error up to 1/16 per operand), reported; a loose guard here
     assert cost.mean() <= 0.03 and cost.max() <= 0.15
@@ -107,8 +109,9 @@ def test_relevance_f8_out_of_range_pairs_are_nan():
     assert np.isfinite(got[0]) and np.isfinite(got[4])
 
 
-def test_search_f8_recall_matches_oracle():
-    cfg, g, m, users, entries, v = _f8_problem(N=20000, Q=48, bias_scale=0.0)
+@pytest.mark.parametrize("preset", ["C2", "C3"])
+def test_search_f8_recall_matches_oracle(preset):
+    cfg, g, m, users, entries, v = _f8_problem(N=20000, Q=48, bias_scale=0.0, preset=preset)
     k = 50
     ids, sc = ann.ann_search(g, m, users, entries, cfg.W, cfg.L, k, 0)
     ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
@@ -124,7 +127,7 @@ def test_search_f8_recall_matches_oracle():
     r_gpu = oracle.recall_at(ids[:16], bf["ids"], k)
     r_kern = oracle.recall_at(kern["ids"][:16], bf["ids"], k)
     r_exact = oracle.recall_at(exact["ids"][:16], bf["ids"], k)
-    print(f"8-bit search: recall@{k} against the exact metric's ranking: gpu {r_gpu:.4f}, oracle at the kernel's "
+    print(f"{preset} 8-bit search: recall@{k} against the exact metric's ranking: gpu {r_gpu:.4f}, oracle at the kernel's "
           f"precision {r_kern:.4f}, oracle with the unquantised metric {r_exact:.4f}; identical lists vs the "
           f"kernel-precision oracle {same_list_fraction(ids, kern['ids']):.3f}")
     assert abs(r_gpu - r_kern) <= 0.01 + 1e-9
@@ -135,7 +138,7 @@ def test_search_f8_recall_matches_oracle():
 
 
 def test_f8_metric_argument_errors():
-    cfg = scaled(PRESETS["C3"], 2000, n_clusters=4, Q=4)
+    cfg = scaled(PRESETS["C4"], 2000, n_clusters=4, Q=4)
     wl = make_workload(cfg)
     with pytest.raises(ann.AnnError) as e:     # another shape
         ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, ann.ANN_F8)
