@@ -242,18 +242,8 @@ mlp_mfma2_f8_kernel(const uint8_t *__restrict__ emb, int64_t N, const float *__r
 // tuple for the next block's user term), and such a copy right behind an MFMA reads a result that is not there yet.
 // A 16-pass MFMA writes its result 64 cycles after issue: five times 16 idle cycles cover the last one.
 #define F8_DRAIN "s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15"
-// one block of 32 hidden units, two contraction steps, two column blocks of pairs
-__device__ __forceinline__ void layer1_block(f32x16 &acc0, f32x16 &acc1, const i32x8 &w0, const i32x8 &w1,
-                                             const i32x8 &x00, const i32x8 &x01, const i32x8 &x10,
-                                             const i32x8 &x11) {
-    asm volatile("s_nop 1\n\t"
-                 "v_mfma_f32_32x32x64_f8f6f4 %0, %2, %4, %0\n\t"
-                 "v_mfma_f32_32x32x64_f8f6f4 %1, %2, %6, %1\n\t"
-                 "v_mfma_f32_32x32x64_f8f6f4 %0, %3, %5, %0\n\t"
-                 "v_mfma_f32_32x32x64_f8f6f4 %1, %3, %7, %1\n\t" F8_DRAIN
-                 : "+v"(acc0), "+v"(acc1)
-                 : "v"(w0), "v"(w1), "v"(x00), "v"(x01), "v"(x10), "v"(x11));
-}
+#include "mlp_mfma_f8_wide_asm.inc"  // F8W_ASM_A / F8W_ASM_B and their operand lists
+
 // one contraction step of the head layer for both column blocks
 __device__ __forceinline__ void head_step(f32x16 &acc0, f32x16 &acc1, const i32x8 &a, const i32x8 &h0,
                                           const i32x8 &h1) {
@@ -279,7 +269,7 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
                          int32_t Q, float *__restrict__ scores) {
     constexpr int CB = 2, WAVES = 4;
     constexpr int KS = D / 64, NB1 = H1 / 32, NC = H1 / 64, NB2 = H2 / 32, NP = H2 / 64;
-    static_assert(KS == 2, "layer1_block contracts two steps of 64");
+    static_assert(KS == 2 && NB2 == 8, "the generated chunk statements assume these");
     constexpr int N_W1 = NB1 * KS;                 // fragments that stay in global memory
     constexpr int N_LDS = NC * NB2 + NP;           // fragments resident in LDS
     constexpr int BLOCK_T = 64 * WAVES;
@@ -348,6 +338,7 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
     };
     Ids idc = load_ids(blockIdx.x), idn = load_ids((int64_t)blockIdx.x + gridDim.x);
     gather(idc);
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)lds + 16u * (uint32_t)lane;
     // Two sets (P: even blocks, Q: odd blocks) of first-layer fragments and of layer-1 accumulators: once both
     // blocks of a chunk are contracted, the sets receive the next chunk's fragments and user term, which travel
     // while layer 2 of this chunk runs.  An empty memory-clobbering statement keeps the compiler from moving
@@ -410,17 +401,19 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
             }
             F8_FENCE;
         }
+        uint32_t wc = lds_addr;  // this lane's 16 bytes of the chunk's first layer-2 fragment
 #pragma unroll 1
         for (int ch = 0; ch < NC; ++ch) {
-            // layer 1 of hidden units 64 ch .. 64 ch + 63: even block from set P, odd block from set Q
-            i32x8 h1q[CB];
-            layer1_block(accP[0], accP[1], w1P[0], w1P[1], x[0][0], x[0][1], x[1][0], x[1][1]);
-#pragma unroll
-            for (int c = 0; c < CB; ++c) quantize_half(accP[c], h1q[c], 0);
-            layer1_block(accQ[0], accQ[1], w1Q[0], w1Q[1], x[0][0], x[0][1], x[1][0], x[1][1]);
-#pragma unroll
-            for (int c = 0; c < CB; ++c) quantize_half(accQ[c], h1q[c], 1);
-            F8_FENCE;
+            // statement A: layer 1 of hidden units 64 ch .. 64 ch + 63 (even block from set P, odd block from set Q)
+            // and their conversion; statement B: layer 2 over them.  See gen_f8_wide_asm.py.
+            i32x8 h0, h1, f0, f1, f2, f3;
+            asm volatile(F8W_ASM_A
+                         : F8W_ACC_P(accP[0], accP[1]), F8W_ACC_Q(accQ[0], accQ[1]), F8W_H_OUT(h0, h1),
+                           F8W_FRAGS_OUT(f0, f1, f2, f3)
+                         : [wP0] "v"(w1P[0]), [wP1] "v"(w1P[1]), [wQ0] "v"(w1Q[0]), [wQ1] "v"(w1Q[1]),
+                           [x00] "v"(x[0][0]), [x01] "v"(x[0][1]), [x10] "v"(x[1][0]), [x11] "v"(x[1][1]),
+                           [wc] "v"(wc), [fmax] "s"(E4M3_MAX)
+                         : "memory");
             // both sets are free now: they receive the next chunk's fragments and user term (after the last
             // chunk: those of the next batch's first chunk), which travel while layer 2 runs
             const bool wrap = (ch + 1 == NC);
@@ -437,20 +430,11 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
                 load_user_term(accP, up, nb);
                 load_user_term(accQ, up, nb + 1);
             }
-            F8_FENCE;
-            // layer 2: every output unit consumes these 64 hidden units; fragments one ahead (the fragment read
-            // and its wait separate the conversions above from the first MFMA by far more than two issue slots)
-            i32x8 a = fragment(NB2 * ch);
-#pragma unroll
-            for (int n2 = 0; n2 < NB2; ++n2) {
-                i32x8 an = a;
-                if (n2 + 1 < NB2) an = fragment(NB2 * ch + n2 + 1);
-                F8_FENCE;
-#pragma unroll
-                for (int c = 0; c < CB; ++c) mfma_f8_a(acc2[n2][c], a, h1q[c]);
-                a = an;
-            }
-            F8_FENCE;
+            asm volatile(F8W_ASM_B
+                         : F8W_FRAGS_IO(f0, f1, f2, f3), F8W_ACC2
+                         : F8W_H_IN(h0, h1), [wc] "v"(wc)
+                         : "memory");
+            wc += NB2 * 2048;
         }
         // the last layer-2 MFMAs drain before their tiles are read (the earlier ones finished long ago)
         asm volatile(F8_DRAIN : "+a"(acc2[NB2 - 1][0]), "+a"(acc2[NB2 - 1][1]), "+a"(acc2[NB2 - 2][0]), "+a"(acc2[NB2 - 2][1]));
