@@ -53,6 +53,11 @@ constexpr int MF_WAVES = 4;
 //     issue slots: every mfma_vgpr starts with s_nop 1;
 //   - an accumulator is never used by two consecutive MFMAs: callers alternate two of them;
 //   - the vector ALU may read an MFMA result only after the MFMA has drained: mfma_drain().
+// The compiler does not know that the result of such a statement arrives later: were it to put a register
+// copy of an accumulator between an MFMA statement and the drain, the copy would read too early.  It has no
+// reason to here (the accumulators are short-lived and nothing else wants their registers), and the parity
+// tests of these shapes would show it at once; where it did happen (the 8-bit kernel for the wide metric) the
+// MFMAs and their drain are one statement.
 __device__ __forceinline__ void mfma_vgpr(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
     asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
