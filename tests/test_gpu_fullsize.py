@@ -103,3 +103,54 @@ def test_full_size_ragged():
                                     cfg.Q // 2 + rng.choice(cfg.Q // 2, 64, replace=False)]))
     Wq, Lq, cq = (wl[n].cpu().numpy()[q_sel] for n in ("W_q", "L_q", "cap_q"))
     _sample_check(wl, cfg, ids, sc, q_sel, Wq, Lq, cq, cfg.k, cfg.k)
+
+
+def test_full_size_f8():
+    """The 8-bit metric on the headline workload at full size: the device's quantiser and kernel against the
+    oracle run on the same quantised operands (sampled queries), recall against the unquantised ground truth."""
+    cfg = PRESETS["C3"]
+    torch.cuda.empty_cache()
+    wl = make_workload(cfg, device="cuda:0")
+    emb8 = ann.ann_quantize_e4m3(wl["emb"])
+    g = ann.ann_graph_load(wl["adj"], emb8, ann.ANN_VALIDATE)
+    m = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, ann.ANN_F8)
+    ws = torch.empty(ann.ann_search_workspace_bytes(g, m, cfg.Q, cfg.E, cfg.W, cfg.L, cfg.k, 0), dtype=torch.uint8,
+                     device="cuda:0")
+    ids, sc = ann.ann_search(g, m, wl["users"], wl["entries"], cfg.W, cfg.L, cfg.k, 0, workspace=ws)
+    st = ann.ann_search_stats(ws)
+    assert st.visited_overflow == 0 and st.queries == cfg.Q
+    ids, sc = _structure(ids, sc, cfg.N)
+    n_sample, k, recall_k = 128, cfg.k, min(100, cfg.k)
+    q_sel = np.sort(np.random.default_rng(7).choice(cfg.Q, n_sample, replace=False))
+    # the oracle's view: every e4m3 value is a bf16 value, so the item table goes over as bf16 bit patterns
+    tab16 = np.zeros(256, np.uint16)
+    for c in range(256):
+        s_, e_, m_ = (-1.0 if c & 0x80 else 1.0), (c >> 3) & 15, c & 7
+        v = 0.0 if (e_ == 15 and m_ == 7) else s_ * (m_ / 8 * 2.0 ** -6 if e_ == 0 else 2.0 ** (e_ - 7) * (1 + m_ / 8))
+        tab16[c] = np.array([v], np.float32).view(np.uint32)[0] >> 16
+    codes = emb8.view(torch.uint8).cpu().numpy()
+    bf16_bits = wl["emb"].view(torch.int16).cpu().numpy().view(np.uint16)
+    sample_rows = np.random.default_rng(8).choice(cfg.N, 20000, replace=False)
+    assert np.array_equal(codes[sample_rows], oracle.e4m3_encode(oracle.widen_bf16(bf16_bits[sample_rows])))
+    emb_q = tab16[codes]
+    del codes, bf16_bits
+    h = to_host({n: wl[n] for n in ("adj", "W", "b", "head_w")})
+    hu = to_host({"users": wl["users"][q_sel], "entries": wl["entries"][q_sel]})
+    W = [oracle.widen_bf16(w) for w in h["W"]]
+    Wq = [np.concatenate([W[0][:, :cfg.d], oracle.e4m3_quantize(W[0][:, cfg.d:], 4.0)], axis=1),
+          oracle.e4m3_quantize(W[1], 4.0), oracle.e4m3_quantize(W[2], 4.0)]
+    mlp_q = oracle.Mlp(Wq, h["b"], h["head_w"])
+    kern = oracle.search(emb_q, h["adj"], hu["users"], mlp_q, hu["entries"], cfg.W, cfg.L, k, 0, act_round=2,
+                         n_threads=16)
+    got_ids, got_sc = ids[q_sel], sc[q_sel]
+    qq = np.repeat(np.arange(n_sample), k).astype(np.int32)
+    valid = got_ids.ravel() >= 0
+    ref_sc = oracle.score_pairs(emb_q, hu["users"], mlp_q, qq[valid], got_ids.ravel()[valid], act_round=2, n_threads=16)
+    assert np.max(np.abs(got_sc.ravel()[valid] - ref_sc)) <= 1e-2
+    truth = torch_ground_truth(wl, list(q_sel), recall_k).cpu()
+    r_gpu = recall_at(torch.from_numpy(got_ids), truth, recall_k)
+    r_kern = recall_at(torch.from_numpy(kern["ids"]), truth, recall_k)
+    print(f"C3 e4m3: recall@{recall_k} gpu {r_gpu:.4f} oracle@kernel-precision {r_kern:.4f}; identical lists "
+          f"{float(np.mean(np.all(got_ids == kern['ids'], axis=1))):.3f}")
+    assert abs(r_gpu - r_kern) <= 0.01 + 1e-9, (r_gpu, r_kern)
+    assert np.array_equal((got_ids >= 0).sum(1), (kern["ids"] >= 0).sum(1))
