@@ -68,3 +68,20 @@ def test_missing_library_is_loud(monkeypatch):
     monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libgmpgr_ann.so")
     with pytest.raises(FileNotFoundError):
         b.load_library()
+
+
+def test_generated_assembly_is_up_to_date(tmp_path):
+    """The .inc files next to the kernels are written by the generator scripts beside them: what is committed
+    must be what the scripts write."""
+    import importlib.util
+    import shutil
+    csrc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2502_11490_amd", "csrc")
+    for script, inc in (("gen_stream_asm.py", "mlp_mfma_stream_asm.inc"), ("gen_f8_wide_asm.py", "mlp_mfma_f8_wide_asm.inc")):
+        work = tmp_path / script.replace(".py", "")
+        work.mkdir()
+        shutil.copy(os.path.join(csrc, script), work / script)
+        spec = importlib.util.spec_from_file_location(script[:-3], str(work / script))
+        mod = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(mod)
+        mod.main()   # writes the .inc next to the copied script
+        assert (work / inc).read_text() == open(os.path.join(csrc, inc)).read(), f"{inc} is stale: run {script}"
