@@ -46,23 +46,31 @@ constexpr int MF_WAVES = 4;
 // Register plan.  The layer-2 accumulators of a wave fill all 256 accumulation registers
 // (AGPRs) for the whole batch; the compiler keeps the destination of every MFMA it selects
 // itself in AGPRs, which is right for layer 2 but leaves no room for the short-lived layer-1
-// and head accumulators.  Those two use mfma_vgpr(): the same instruction written as inline
+// and head accumulators.  Those two use mfma_vgpr_pair(): the same instruction written as inline
 // assembly with the accumulator pinned to ordinary VGPRs.  The hazard rules the compiler
 // would otherwise enforce are kept by hand there:
 //   - a VGPR written by a vector-ALU instruction may not be read by an MFMA in the next two
-//     issue slots: every mfma_vgpr starts with s_nop 1;
+//     issue slots: every mfma_vgpr_pair starts with s_nop 1;
 //   - an accumulator is never used by two consecutive MFMAs: callers alternate two of them;
-//   - the vector ALU may read an MFMA result only after the MFMA has drained: mfma_drain().
-// The compiler does not know that the result of such a statement arrives later: were it to put a register
-// copy of an accumulator between an MFMA statement and the drain, the copy would read too early.  It has no
-// reason to here (the accumulators are short-lived and nothing else wants their registers), and the parity
-// tests of these shapes would show it at once; where it did happen (the 8-bit kernel for the wide metric) the
-// MFMAs and their drain are one statement.
-__device__ __forceinline__ void mfma_vgpr(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma_drain(f32x16 &x, f32x16 &y) {
-    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(x), "+v"(y));
+//   - the vector ALU may read an MFMA result only after the MFMA has drained: the last pair of a group
+//     carries the idle cycles in its own statement.  (The compiler does not know that the result of such a
+//     statement arrives later: a register copy of an accumulator placed between the last MFMA and a
+//     separate statement of idle cycles would read too early; it was seen to do that in the 8-bit kernel
+//     for the wide metric.)
+// One weight fragment against both column blocks of pairs.  LAST: the group ends here; the idle cycles that
+// let its MFMAs finish are part of the same statement, so that nothing can come between them.
+template <bool LAST>
+__device__ __forceinline__ void mfma_vgpr_pair(f32x16 &acc0, f32x16 &acc1, const bf16x8 &a, const bf16x8 &b0,
+                                               const bf16x8 &b1) {
+    if (LAST)
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %2, %4, %1\n\t"
+                     "s_nop 15\n\ts_nop 7"
+                     : "+v"(acc0), "+v"(acc1)
+                     : "v"(a), "v"(b0), "v"(b1));
+    else
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %2, %4, %1"
+                     : "+v"(acc0), "+v"(acc1)
+                     : "v"(a), "v"(b0), "v"(b1));
 }
 
 __device__ __forceinline__ bf16x8 relu_pack(const f32x16 &acc, int half) {
@@ -229,10 +237,10 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
 #pragma unroll
             for (int s = 0; s < KS1; ++s) {
                 bf16x8 a = *(const bf16x8 *)(wc + s * 64 + lane);
-#pragma unroll
-                for (int c = 0; c < CB; ++c) mfma_vgpr(acc1[c], a, xf[c][s]);
+                static_assert(CB == 2, "pairs 0 and 1 alternate");
+                if (s == KS1 - 1) mfma_vgpr_pair<true>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
+                else mfma_vgpr_pair<false>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
             }
-            mfma_drain(acc1[CB - 1], acc1[CB - 2]);
             bf16x8 hf[CB][2];
 #pragma unroll
             for (int c = 0; c < CB; ++c) {
@@ -276,11 +284,11 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
                 bf16x8 a = *(const bf16x8 *)(w3buf + (2 * n2 + s2) * 64 + lane);
-#pragma unroll
-                for (int c = 0; c < CB; ++c) mfma_vgpr(acc3[c], a, relu_pack(acc2[n2][c], s2));
+                const bf16x8 h0 = relu_pack(acc2[n2][0], s2), h1 = relu_pack(acc2[n2][1], s2);
+                if (n2 == NB2 - 1 && s2 == 1) mfma_vgpr_pair<true>(acc3[0], acc3[1], a, h0, h1);
+                else mfma_vgpr_pair<false>(acc3[0], acc3[1], a, h0, h1);
             }
         }
-        mfma_drain(acc3[CB - 1], acc3[CB - 2]);
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
             float part = 0.f;
@@ -371,18 +379,18 @@ mlp_mfma1_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
 #pragma unroll
             for (int s = 0; s < KS1; ++s) {
                 bf16x8 a = *(const bf16x8 *)(wc + s * 64 + lane);
-#pragma unroll
-                for (int c = 0; c < CB; ++c) mfma_vgpr(acc1[c], a, xf[c][s]);
+                static_assert(CB == 2, "pairs 0 and 1 alternate");
+                if (s == KS1 - 1) mfma_vgpr_pair<true>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
+                else mfma_vgpr_pair<false>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
             }
-            mfma_drain(acc1[CB - 1], acc1[CB - 2]);
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
                 bf16x8 a = *(const bf16x8 *)(wc + (KS1 + s2) * 64 + lane);
-#pragma unroll
-                for (int c = 0; c < CB; ++c) mfma_vgpr(acc3[c], a, relu_pack(acc1[c], s2));
+                const bf16x8 h0 = relu_pack(acc1[0], s2), h1 = relu_pack(acc1[1], s2);
+                if (nb == NB1 - 1 && s2 == 1) mfma_vgpr_pair<true>(acc3[0], acc3[1], a, h0, h1);
+                else mfma_vgpr_pair<false>(acc3[0], acc3[1], a, h0, h1);
             }
         }
-        mfma_drain(acc3[CB - 1], acc3[CB - 2]);
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
             float part = 0.f;

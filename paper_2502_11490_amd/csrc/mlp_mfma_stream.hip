@@ -78,11 +78,21 @@ __device__ __forceinline__ bf16x8 relu_pack_i16(const f32x16 &acc, int half) {
     return __builtin_bit_cast(bf16x8, u);
 }
 
-__device__ __forceinline__ void mfma_v(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void drain_v(f32x16 &x, f32x16 &y) {
-    asm volatile("s_nop 15" : "+v"(x), "+v"(y));
+// Head layer: one weight fragment against both column blocks of pairs, accumulators in ordinary registers.
+// LAST: the idle cycles that let the MFMAs finish belong to the same statement (between two statements the
+// compiler may place a copy of an accumulator, which would then read a result that is still on its way).
+template <bool LAST>
+__device__ __forceinline__ void mfma_v_pair(f32x16 &acc0, f32x16 &acc1, const bf16x8 &a, const bf16x8 &b0,
+                                            const bf16x8 &b1) {
+    if (LAST)
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %2, %4, %1\n\t"
+                     "s_nop 15\n\ts_nop 7"
+                     : "+v"(acc0), "+v"(acc1)
+                     : "v"(a), "v"(b0), "v"(b1));
+    else
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %2, %4, %1"
+                     : "+v"(acc0), "+v"(acc1)
+                     : "v"(a), "v"(b0), "v"(b1));
 }
 
 // LDS accesses made while weight chunks are in flight towards the LDS go through assembly: for an
@@ -348,12 +358,14 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
             u32x4 a[4];
             lds_load4_b128<2 * n2 * 1024, 1024>(w3_addr, a[0], a[1], a[2], a[3]);
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int c = 0; c < CB; ++c)
-                    mfma_v(acc3[c], __builtin_bit_cast(bf16x8, a[t]), relu_pack_i16(acc2[n2 + t / 2][c], t % 2));
+            for (int t = 0; t < 4; ++t) {
+                const bf16x8 h0 = relu_pack_i16(acc2[n2 + t / 2][0], t % 2), h1 = relu_pack_i16(acc2[n2 + t / 2][1], t % 2);
+                if (n2 + 2 == NB2 && t == 3)
+                    mfma_v_pair<true>(acc3[0], acc3[1], __builtin_bit_cast(bf16x8, a[t]), h0, h1);
+                else
+                    mfma_v_pair<false>(acc3[0], acc3[1], __builtin_bit_cast(bf16x8, a[t]), h0, h1);
+            }
         });
-        drain_v(acc3[0], acc3[1]);
         float hw[4], bb3[4];
         {
             u32x4 r0, r1, r2, r3;
