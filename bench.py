@@ -104,12 +104,14 @@ def main() -> int:
     ap.add_argument("--workload", default="C3", help="preset name (C1..C5)")
     ap.add_argument("--items", type=int, default=0, help="override the item count (smaller rehearsal)")
     ap.add_argument("--L", type=int, default=0, help="fix L instead of sweeping for recall@100 >= 0.95")
-    ap.add_argument("--gt-queries", type=int, default=64, help="queries with exhaustive ground truth")
+    ap.add_argument("--gt-queries", type=int, default=0,
+                    help="queries with exhaustive ground truth (0 = 256, or 64 beyond 50 M items)")
     ap.add_argument("--cpu-queries", type=int, default=0, help="oracle sample size (0 = pick for ~20 s)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=3)
     ap.add_argument("--no-layers", action="store_true", help="skip the layer-by-layer search beside the headline")
     ap.add_argument("--no-stream", action="store_true", help="skip the continuous-batching run beside the headline")
+    ap.add_argument("--no-halves", action="store_true", help="skip the two-half-batches-at-once run beside the headline")
     ap.add_argument("--no-walkers", action="store_true", help="skip the walker-rule run beside the headline")
     ap.add_argument("--no-f8", action="store_true", help="skip the 8-bit metric run (on C2) beside the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -148,7 +150,7 @@ def main() -> int:
 
     # ---- ground truth on a subsample, then the smallest L that reaches recall@100 >= 0.95 ----
     kr = min(100, k)
-    n_gt = min(args.gt_queries, Q)
+    n_gt = min(args.gt_queries if args.gt_queries > 0 else (256 if cfg.N <= 50_000_000 else 64), Q)
     gen = torch.Generator().manual_seed(250211490 + 20)
     q_sel = torch.randperm(Q, generator=gen)[:n_gt].sort().values.tolist()
     t1 = time.time()
@@ -281,6 +283,52 @@ def main() -> int:
             del wss
         del users4, entries4
 
+    # ---- the batch as two half-batches searched at once from two host threads on two streams (one half's
+    #      scoring overlaps the other half's list updates); reported beside the headline, not the timed step ----
+    halves = None
+    if not ragged and not args.no_halves and Q >= 2:
+        import threading
+        h = Q // 2
+        parts = [(users[:h].contiguous(), entries[:h].contiguous()), (users[h:].contiguous(), entries[h:].contiguous())]
+        wsh = [torch.empty(ann.ann_search_workspace_bytes(g, m, u.shape[0], E, W, L_star, k, 0), dtype=torch.uint8,
+                           device="cuda:0") for u, _ in parts]
+        outs = [(torch.empty((u.shape[0], k), dtype=torch.int32, device="cuda:0"),
+                 torch.empty((u.shape[0], k), dtype=torch.float32, device="cuda:0")) for u, _ in parts]
+        side = [torch.cuda.Stream() for _ in parts]
+        failed = []
+
+        def half_worker(i, reps):
+            try:
+                with torch.cuda.stream(side[i]):
+                    for _ in range(reps):
+                        ann.ann_search(g, m, parts[i][0], parts[i][1], W, L_star, k, 0, workspace=wsh[i],
+                                       out_ids=outs[i][0], out_scores=outs[i][1], stream=side[i])
+                    side[i].synchronize()
+            except Exception as e:  # noqa: BLE001
+                failed.append(repr(e))
+
+        def both(reps):
+            th = [threading.Thread(target=half_worker, args=(i, reps)) for i in range(2)]
+            for t in th:
+                t.start()
+            for t in th:
+                t.join()
+
+        torch.cuda.synchronize()
+        both(2)
+        torch.cuda.synchronize()
+        t9 = time.perf_counter()
+        both(5)
+        torch.cuda.synchronize()
+        ms_h = 1e3 * (time.perf_counter() - t9) / 5
+        if failed:
+            raise RuntimeError(f"concurrent half-batch searches failed: {failed}")
+        halves = {"ms_per_batch": round(ms_h, 3), "queries_per_s": round(Q / ms_h * 1e3, 1),
+                  "same_results_as_batched": bool(torch.equal(torch.cat([o[0] for o in outs]), out_ids))}
+        log(f"two half-batches at once: {ms_h:.2f} ms per {Q} queries, {Q / ms_h * 1e3:.0f} queries/s, "
+            f"same results: {halves['same_results_as_batched']}")
+        del wsh, outs, parts
+
     # ---- the walker rule (one greedy walker per seed, T hops, shared visited set and top-k list) at about
     #      half the scored pairs of the headline; reported beside it, not part of the timed step ----
     walkers = None
@@ -407,7 +455,8 @@ def main() -> int:
                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
                     "algorithmic_bytes_per_launch": round(pairs_per_step / max(score_launches // args.profile_steps, 1)
                                                           * (cfg.d * 2 + 12)),
-                    "kernel": "mlp_mfma2_stream_kernel" if cfg.dims[1] == 512 else "mlp_mfma2_kernel", "avg_launch_us": round(1e3 * score_ms / max(score_launches, 1), 2),
+                    "kernel": ("mlp_mfma1_kernel" if len(cfg.dims) == 3 else
+                               "mlp_mfma2_stream_kernel" if cfg.dims[1] == 512 else "mlp_mfma2_kernel"), "avg_launch_us": round(1e3 * score_ms / max(score_launches, 1), 2),
                     "launches_per_step": score_launches // args.profile_steps,
                     "flop_per_pair_issued": fl_issued, "flop_per_pair_unhoisted": fl_full}
     else:
@@ -488,7 +537,8 @@ def main() -> int:
             "mlp_scores_per_s": round(scores_per_s, 1),
             "pairs_scored_per_step": int(st.pairs_scored), "nodes_expanded_per_step": int(st.nodes_expanded),
             "rounds": int(st.max_query_iters), "mfma_kernel": bool(mfma), "stages": stages,
-            "layered_search": layered, "continuous_batching": streamed, "walker_search": walkers, "f8_metric": f8,
+            "layered_search": layered, "continuous_batching": streamed, "concurrent_halves": halves,
+            "walker_search": walkers, "f8_metric": f8,
         },
         "roofline": roofline,
         "cpu_baseline": cpu,
