@@ -293,7 +293,7 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
         for (int c = 0; c < CB; ++c) {
             float part = 0.f;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) part = fmaf(hw[i], 1.0f / (1.0f + expf(-(acc3[c][i] + bb3[i]))), part);
+            for (int i = 0; i < 4; ++i) part = fmaf(hw[i], sigmoid_hw(acc3[c][i] + bb3[i]), part);
             float other = __shfl_xor(part, 32);
             int64_t row = row0 + c * 32 + col;
             if (g == 0 && row < M) scores[row] = bad[c] ? __uint_as_float(0x7fc00000u) : part + other;
@@ -395,7 +395,7 @@ mlp_mfma1_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
         for (int c = 0; c < CB; ++c) {
             float part = 0.f;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) part = fmaf(hw[i], 1.0f / (1.0f + expf(-(acc3[c][i] + bh[i]))), part);
+            for (int i = 0; i < 4; ++i) part = fmaf(hw[i], sigmoid_hw(acc3[c][i] + bh[i]), part);
             float other = __shfl_xor(part, 32);
             int64_t row = row0 + c * 32 + col;
             if (g == 0 && row < M) scores[row] = bad[c] ? __uint_as_float(0x7fc00000u) : part + other;

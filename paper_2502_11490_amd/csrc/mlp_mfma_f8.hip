@@ -217,7 +217,7 @@ mlp_mfma2_f8_kernel(const uint8_t *__restrict__ emb, int64_t N, const float *__r
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float logit = acc3[c][i] * (1.0f / F8_LOGIT_SCALE) + bb3[i];
-                part = fmaf(hw[i], 1.0f / (1.0f + expf(-logit)), part);
+                part = fmaf(hw[i], sigmoid_hw(logit), part);
             }
             float other = __shfl_xor(part, 32);
             int64_t row = row0 + c * 32 + col;
@@ -471,7 +471,7 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float logit = acc3[c][i] * (1.0f / F8_LOGIT_SCALE) + bb3[i];
-                part = fmaf(hw[i], 1.0f / (1.0f + expf(-logit)), part);
+                part = fmaf(hw[i], sigmoid_hw(logit), part);
             }
             float other = __shfl_xor(part, 32);
             int64_t row = row0 + c * 32 + col;

@@ -380,7 +380,7 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         for (int c = 0; c < CB; ++c) {
             float part = 0.f;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) part = fmaf(hw[e], 1.0f / (1.0f + expf(-(acc3[c][e] + bb3[e]))), part);
+            for (int e = 0; e < 4; ++e) part = fmaf(hw[e], sigmoid_hw(acc3[c][e] + bb3[e]), part);
             float other = __shfl_xor(part, 32);
             int64_t row = row0 + c * 32 + col;
             if (g == 0 && row < M) scores[row] = bad[c] ? __uint_as_float(0x7fc00000u) : part + other;
