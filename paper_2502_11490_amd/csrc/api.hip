@@ -124,7 +124,8 @@ bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32
 // more than AHEAD rounds in front of the device, so the stream never runs dry and no copy or
 // synchronisation is put between the kernels.  A round enqueued after the batch has finished is
 // three launches that find nothing to do.  "Finished" never reverts, so a late look is safe.
-// One word per host thread; the tag tells a search's word from an older search's.
+// One word per host thread; the tag tells a search's word from an older search's.  A thread's 64 pinned
+// bytes are never freed: a destructor at thread exit could run after the runtime has shut down.
 struct Mailbox {
     static constexpr int AHEAD = 4;
     volatile uint64_t *host = nullptr;
@@ -135,7 +136,10 @@ struct Mailbox {
         if (ok) return true;
         void *h = nullptr, *d = nullptr;
         if (hipHostMalloc(&h, 64, hipHostMallocPortable | hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) return false;
-        if (hipHostGetDevicePointer(&d, h, 0) != hipSuccess) return false;
+        if (hipHostGetDevicePointer(&d, h, 0) != hipSuccess) {
+            (void)hipHostFree(h);
+            return false;
+        }
         host = (volatile uint64_t *)h;
         dev = (uint64_t *)d;
         host[0] = 0;
@@ -187,7 +191,10 @@ struct Profiler {
         if (used == stage.size()) {
             hipEvent_t a, b;
             if (hipEventCreate(&a) != hipSuccess) return nullptr;
-            if (hipEventCreate(&b) != hipSuccess) return nullptr;
+            if (hipEventCreate(&b) != hipSuccess) {
+                (void)hipEventDestroy(a);
+                return nullptr;
+            }
             events.push_back(a);
             events.push_back(b);
             stage.push_back(st);

@@ -9,7 +9,7 @@ Register plan of a wave (fixed physical registers, so that the vector-ALU instru
 fresh layer-1 accumulators into bf16 B operands can be interleaved with the MFMAs of layer 2 and
 so that every step agrees on where the long-lived values are):
 
-    256 AGPRs           layer-2 accumulators, 16 tiles (n2, c), constraint "a" (the allocator's choice)
+    a[0:255]            layer-2 accumulators, tile (n2, c) at a[16 (2 n2 + c) ...]
     v[64:95], v[96:127] layer-1 accumulators, sets A and B (pairs c = 0, 1), alternating by step
     v[128:143]          hidden units produced from set A, tuple (c, half) at v[128 + 8c + 4half ...]
     v[144:159]          hidden units produced from set B
@@ -21,6 +21,8 @@ Step i (0 .. 16):
     layer 2   (i > 0)   over the hidden units of block i-1 (the other set); fragments 8..23
     convert   (i < 16)  ReLU + bf16 rounding of the fresh set, interleaved with the layer-2 MFMAs
                         (exposed in step 0, which has none)
+    head      (i = 16)  the last step runs layer 2 tile by tile and, behind every finished tile, its
+                        conversion to bf16 head operands and the head layer's MFMAs (see step16_head)
 
 Global loads of a step and their waits are part of the assembly too, because the compiler cannot
 count them: next to global-to-LDS loads any other vector-memory load makes it fall back to
@@ -68,8 +70,25 @@ def hf_reg(s, c, half):
     return vr(HF[s] + 8 * c + 4 * half, 4)
 
 
+def acc2_lo(n2, c):
+    return 16 * (2 * n2 + c)
+
+
 def acc2_reg(n2, c):
-    return f"%[a{n2}{c}]"  # layer-2 accumulators: any AGPR tuple, the allocator keeps them in place
+    """Layer-2 accumulator tile (n2, c).  The 256 accumulation registers are named outright and are not
+    operands: the head conversion reads single registers of a tile, which an operand cannot express, and
+    tiles pinned as operands make the allocator shuffle them between the statements.  Every statement lists
+    them as clobbered; the kernel's own code between the statements has no use for accumulation registers
+    (a test compiles the kernel and checks that none appears outside the statements)."""
+    return f"a[{acc2_lo(n2, c)}:{acc2_lo(n2, c) + 15}]"
+
+
+def init_acc2():
+    """The accumulators start from the layer-2 bias, read from LDS straight into the accumulation registers:
+    register 4 t4 + e of a tile holds unit 32 n2 + 8 t4 + 4 g + e, so a lane reads 16 bytes at
+    %[b2] (= bias base + 16 g) + 128 n2 + 32 t4 for both column blocks.  Step 0 starts with a full wait."""
+    return [f"ds_read_b128 a[{acc2_lo(n2, c) + 4 * t4}:{acc2_lo(n2, c) + 4 * t4 + 3}], %[b2] offset:{n2 * 128 + t4 * 32}"
+            for n2 in range(8) for c in (0, 1) for t4 in range(4)]
 
 
 def wt(n):
@@ -244,6 +263,102 @@ def step(i):
     return setup + schedule(n_frag, first_frag, compute, extra, before, sync, preloaded=i > 0, next_first=next_first, store=store) + tail
 
 
+# ---- the last step: layer 2 of hidden block 15 with the head layer folded in ----
+ACC3 = (96, 112)        # head accumulators of pairs c = 0, 1: set B's registers, idle since step 15's conversion
+RT = 64                 # 16 registers that receive one tile from the accumulation registers (set A's, idle)
+TSET = (80, 128)        # a tile's four bf16 head operands (c, s2) at TSET[n2 % 2] + 8 c + 4 s2: tiles alternate
+                        # between the rest of set A's registers and set A's hidden units (consumed by step 15)
+N_HEAD = 16             # head fragments [2 n2 + s2]
+
+
+def head_convert(n2, c):
+    """Tile (n2, c) of the layer-2 accumulators -> ReLU + bf16, the B operands of head fragments 2 n2 and
+    2 n2 + 1 for pair c: 16 reads out of the accumulation registers, 8 conversions, 8 signed 16-bit max."""
+    lo, t = acc2_lo(n2, c), TSET[n2 % 2] + 8 * c
+    ops = [f"v_accvgpr_read_b32 v{RT + j}, a{lo + j}" for j in range(16)]
+    ops += [f"v_cvt_pk_bf16_f32 v{t + j}, v{RT + 2 * j}, v{RT + 2 * j + 1}" for j in range(8)]
+    ops += [f"v_pk_max_i16 v{t + j}, v{t + j}, 0" for j in range(8)]
+    return ops
+
+
+def head_pair(u):
+    """Head fragment u against both column blocks; the first pair starts from zero."""
+    n2, s2 = divmod(u, 2)
+    out = []
+    for c in (0, 1):
+        acc = vr(ACC3[c], 16)
+        out.append(f"v_mfma_f32_32x32x16_bf16 {acc}, %[w3{u % 4}], {vr(TSET[n2 % 2] + 8 * c + 4 * s2, 4)}, "
+                   + ("0" if u == 0 else acc))
+    return out
+
+
+def step16_head():
+    """Step 16 issues layer 2 tile by tile (fragment t = (n2, s2) = (t / 2, t % 2)), so tile n2 has its
+    final value once slot 2 n2 + 1 has issued and two more MFMAs behind it.  From slot 4 on every slot
+    also converts one (tile, c) for the head layer, and from slot 6 on it also issues one head fragment's
+    pair of MFMAs (fragment u = t - 6: its operands were converted in slots 2 n2 + 4 and 2 n2 + 5); five
+    more slots after layer 2 finish the last two tiles and the last six head fragments.  Per slot 32
+    vector-ALU instructions stand against four MFMAs, 128 cycles each.  Head fragments come from LDS
+    through four compiler-chosen tuples %[w30..w33], re-requested like the weight fragments."""
+    n = 16
+    vm = vmem_ops(NB1, "B")
+    own = len(vm)
+    assert own == N_DMA
+    out = ["s_mov_b32 m0, %[lb]", "v_and_b32 %[wcn], 0x3ff, %[vo]", "v_add_u32 %[wc], %[wcs], %[wcn]",
+           "v_add_u32 %[wcn], %[wcsn], %[wcn]"]
+    queue = [("f", k) for k in range(4)]       # requested by step 15 after its barrier
+
+    def issue(tag, line):
+        queue.append(tag)
+        out.append(line)
+
+    def wait_for(tag):
+        if tag not in queue:
+            return
+        younger = len(queue) - queue.index(tag) - 1
+        out.append(wt(younger))
+        del queue[:queue.index(tag) + 1]
+
+    def w3_read(u):
+        issue(("h", u), f"ds_read_b128 %[w3{u % 4}], %[w3] offset:{u * 1024}")
+
+    for u in range(4):
+        w3_read(u)
+    convs = [(n2, c) for n2 in range(8) for c in (0, 1)]     # conversion k runs in slot k + 4
+    store_slot, sync_at = 10, sync_slot(n)
+    for t in range(n + 5):
+        side = head_convert(*convs[t - 4]) if 0 <= t - 4 < len(convs) else []
+        if t < own:
+            side = vm[t] + side
+        mf = []                                              # the slot's MFMAs, each with what it waits for
+        if t < n:
+            mf += [(("f", t), m) for m in m2("B", freg(t), t // 2, t % 2)]
+        heads = [t - 6] if 6 <= t < n + 4 else ([N_HEAD - 2, N_HEAD - 1] if t == n + 4 else [])
+        for u in heads:
+            mf += [(("h", u), m) for m in head_pair(u)]
+        per = -(-len(side) // max(len(mf), 1))
+        if t == n + 4:
+            out.append("s_nop 1")                            # the operands of fragment 14 were just written
+        for j, (tag, m) in enumerate(mf):
+            wait_for(tag)
+            out.append(m)
+            if j % 2 == 1:                                   # a fragment's registers are free behind its second MFMA
+                if tag[0] == "f" and tag[1] + 4 < n:
+                    issue(("f", tag[1] + 4), ld(tag[1] + 4, 8 + tag[1] + 4))
+                if tag[0] == "h" and tag[1] + 4 < N_HEAD:
+                    w3_read(tag[1] + 4)
+            out.extend(side[j * per:(j + 1) * per])
+        out.extend(side[len(mf) * per:])
+        if t == store_slot:
+            out.append(f"s_waitcnt vmcnt({N_DMA + own})")
+            issue(("w",), f"ds_write_b128 %[xw], %[xpo] offset:{(NB1 - 1) * 1024}")
+        if t == sync_at:
+            out += [f"s_waitcnt vmcnt({own})", "s_waitcnt lgkmcnt(0)", "s_barrier"]
+            queue.clear()
+    out += ["s_nop 15", "s_nop 7"]                           # the head accumulators are read next
+    return out
+
+
 def c_string(lines):
     return " \\\n    ".join('"' + l + '\\n\\t"' for l in lines)
 
@@ -252,8 +367,14 @@ def main():
     here = os.path.dirname(os.path.abspath(__file__))
     out = ["// Generated by gen_stream_asm.py -- do not edit; see that script for the register plan.", ""]
     for i in range(NB1 + 1):
-        out.append(f"#define STREAM_ASM_STEP_{i} \\\n    {c_string(step(i))}")
+        out.append(f"#define STREAM_ASM_STEP_{i} \\\n    {c_string(step16_head() if i == NB1 else step(i))}")
         out.append("")
+    out.append(f"#define STREAM_ASM_INIT_ACC2 \\\n    {c_string(init_acc2())}")
+    out.append("")
+    out.append("#define STREAM_ACC2_CLOBBERS " + ", ".join(f'"a{r}"' for r in range(256)))
+    out.append(f'#define STREAM_ACC3(v0, v1) [q30] "=&{{{vr(ACC3[0], 16)}}}"(v0), [q31] "=&{{{vr(ACC3[1], 16)}}}"(v1)')
+    scratch = list(range(RT, RT + 16)) + [r for t in TSET for r in range(t, t + 16)]
+    out.append("#define STREAM_HEAD_CLOBBERS " + ", ".join(f'"v{r}"' for r in sorted(scratch)))
     # operand lists
     for s in "AB":
         out.append(f'#define STREAM_ACC_{s}(v0, v1) [p{s}0] "+{{{acc_reg(s, 0)}}}"(v0), [p{s}1] "+{{{acc_reg(s, 1)}}}"(v1)')
@@ -263,8 +384,6 @@ def main():
         ins = ", ".join(f'[h{s}{c}{h}] "{{{hf_reg(s, c, h)}}}"(h{c}{h})' for c, h in names)
         out.append(f"#define STREAM_HF_OUT_{s}(h00, h01, h10, h11) {outs}")
         out.append(f"#define STREAM_HF_IN_{s}(h00, h01, h10, h11) {ins}")
-    acc2 = ", ".join(f'[a{n2}{c}] "+a"(acc2[{n2}][{c}])' for n2 in range(8) for c in (0, 1))
-    out.append(f"#define STREAM_ACC2 {acc2}")
     out.append(f'#define STREAM_SB(p) [sb] "+{{{SB}}}"(p)')
     frs = ", ".join(f'[f{k}] "+{{{freg(k)}}}"(f{k})' for k in range(4))
     out.append(f"#define STREAM_FRAGS(f0, f1, f2, f3) {frs}")

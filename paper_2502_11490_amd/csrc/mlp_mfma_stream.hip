@@ -11,7 +11,11 @@
 //      16 VGPRs  four weight fragments in flight from LDS
 //       8 VGPRs  staging of the next batch's item rows
 // The compiler's register allocator does not find this plan, so one step of the pipeline is a
-// single inline-assembly block with the register classes pinned by constraints.
+// single inline-assembly block with the register classes pinned by constraints.  The 256
+// accumulation registers are not operands at all: the statements name them outright and list them
+// as clobbered (tiles pinned as operands make the allocator shuffle them between the statements, and
+// the head layer reads single registers of a tile, which an operand cannot express); the code between
+// the statements has no use for accumulation registers, which a test checks on the compiled kernel.
 //
 // Pipeline.  Step i (0..NB1) contracts layer 1 for hidden units 32i..32i+31 and, skewed by one
 // step, layer 2 over the hidden units of step i-1; chunk i of the weights holds exactly those
@@ -24,7 +28,10 @@
 // ahead of use.  A step issues its global loads first, weights before the user term before one
 // piece of the next batch's item rows, so that the in-order counter never makes a
 // short-latency consumer wait for the long-latency gather.
-// ReLU + bf16 rounding of the fresh hidden units is the only vector-ALU work of a step; the
+// ReLU + bf16 rounding of the fresh hidden units is the only vector-ALU work of a step.  The last
+// step runs layer 2 tile by tile and carries the head layer: behind every finished tile its ReLU +
+// bf16 conversion (out of the accumulation registers) and the head MFMAs over it, so that the 512
+// vector-ALU instructions of that conversion run under MFMAs instead of behind them.  The
 // item rows of the workgroup's NEXT batch are fetched one 16-byte piece per lane and step into
 // a wave-private LDS area, so the HBM gather latency is hidden behind a whole batch of MFMAs.
 //
@@ -35,7 +42,8 @@
 //     flight and the counted waits (lgkmcnt(3..0)) are exact;
 //   - an accumulator is never the target of two consecutive MFMAs (pairs 0 and 1 alternate);
 //   - results read by the vector ALU right after a block (layer-1 accumulators after the
-//     first step, layer-2 accumulators after the last) are waited for with s_nop;
+//     first step, head accumulators after the last) are waited for with s_nop; a layer-2 tile is
+//     read at least four MFMAs after the last one that wrote it;
 //   - a weight-fragment register is reloaded from LDS only after the MFMAs reading it have
 //     issued (MFMA operands are read at issue).
 #include <type_traits>
@@ -55,45 +63,6 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void global_void;
 
 constexpr int ST_BLOCK = 256;
-
-// ReLU and round-to-nearest-even bf16 of half an accumulator tile, two instructions per packed
-// word: v_cvt_pk_bf16_f32 rounds two floats, and for bf16 bit patterns max(x, 0) is a signed
-// 16-bit integer max (negative values have the sign bit set).  Rounding before or after the
-// ReLU gives the same result.
-__device__ __forceinline__ bf16x8 relu_pack_i16(const f32x16 &acc, int half) {
-    uint32_t w0, w1, w2, w3;
-    const int o = half * 8;
-    asm("v_cvt_pk_bf16_f32 %0, %4, %5\n\t"
-        "v_cvt_pk_bf16_f32 %1, %6, %7\n\t"
-        "v_cvt_pk_bf16_f32 %2, %8, %9\n\t"
-        "v_cvt_pk_bf16_f32 %3, %10, %11\n\t"
-        "v_pk_max_i16 %0, %0, 0\n\t"
-        "v_pk_max_i16 %1, %1, 0\n\t"
-        "v_pk_max_i16 %2, %2, 0\n\t"
-        "v_pk_max_i16 %3, %3, 0"
-        : "=&v"(w0), "=&v"(w1), "=&v"(w2), "=&v"(w3)
-        : "v"(acc[o + 0]), "v"(acc[o + 1]), "v"(acc[o + 2]), "v"(acc[o + 3]), "v"(acc[o + 4]), "v"(acc[o + 5]),
-          "v"(acc[o + 6]), "v"(acc[o + 7]));
-    uint4 u = make_uint4(w0, w1, w2, w3);
-    return __builtin_bit_cast(bf16x8, u);
-}
-
-// Head layer: one weight fragment against both column blocks of pairs, accumulators in ordinary registers.
-// LAST: the idle cycles that let the MFMAs finish belong to the same statement (between two statements the
-// compiler may place a copy of an accumulator, which would then read a result that is still on its way).
-template <bool LAST>
-__device__ __forceinline__ void mfma_v_pair(f32x16 &acc0, f32x16 &acc1, const bf16x8 &a, const bf16x8 &b0,
-                                            const bf16x8 &b1) {
-    if (LAST)
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %2, %4, %1\n\t"
-                     "s_nop 15\n\ts_nop 7"
-                     : "+v"(acc0), "+v"(acc1)
-                     : "v"(a), "v"(b0), "v"(b1));
-    else
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %2, %4, %1"
-                     : "+v"(acc0), "+v"(acc1)
-                     : "v"(a), "v"(b0), "v"(b1));
-}
 
 // LDS accesses made while weight chunks are in flight towards the LDS go through assembly: for an
 // LDS access it can see, the compiler first waits until every outstanding global-to-LDS load
@@ -183,20 +152,41 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         int32_t id[CB], q[CB];
         bool bad[CB];
     };
-    auto load_ids = [&](int64_t tile) {
-        Ids r;
+    // Requesting a batch's ids and looking at them are two calls, so that a whole step can lie between them.
+    // Both are tied to their place among the assembly statements (which keep their order): the row index of
+    // request_ids passes through an empty statement, or the compiler would hoist these loads from read-only
+    // arrays above earlier steps, whose counted waits then make them wait for younger loads; check_ids passes
+    // the raw values through one, which keeps every use of them behind the statement written before it.
+    struct RawIds {
+        int32_t id[CB], q[CB];
+    };
+    auto request_ids = [&](int64_t tile) {
+        RawIds r;
+        int32_t here = 0;
+        asm volatile("" : "+s"(here));
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
-            int64_t row = tile * TILE + (int64_t)wave * 64 + c * 32 + col;
+            int64_t row = tile * TILE + (int64_t)wave * 64 + c * 32 + col + here;
             row = row < M ? row : M - 1;
-            const int32_t v = pair_id[row], q = pair_q[row];
-            // no short-circuit: both loads are issued before either value is looked at
+            r.id[c] = pair_id[row];
+            r.q[c] = pair_q[row];
+        }
+        return r;
+    };
+    auto check_ids = [&](RawIds raw) {
+        Ids r;
+        static_assert(CB == 2, "the statement below names two pairs");
+        asm volatile("" : "+v"(raw.id[0]), "+v"(raw.id[1]), "+v"(raw.q[0]), "+v"(raw.q[1]));
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            const int32_t v = raw.id[c], q = raw.q[c];
             r.bad[c] = ((uint64_t)(int64_t)v >= (uint64_t)N) | ((uint32_t)q >= (uint32_t)Q);
             r.id[c] = r.bad[c] ? 0 : v;
             r.q[c] = r.bad[c] ? 0 : q;
         }
         return r;
     };
+    auto load_ids = [&](int64_t tile) { return check_ids(request_ids(tile)); };
     Ids idc = load_ids(blockIdx.x), idn = load_ids((int64_t)blockIdx.x + gridDim.x);
 #pragma unroll
     for (int c = 0; c < CB; ++c) {
@@ -256,24 +246,15 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
 #pragma unroll
         for (int c = 0; c < CB; ++c) nxt_off[c] = (size_t)idn.id[c] * D + 8 * g;
 
-        // layer-2 accumulators start from the bias (kept in LDS: a global load here would be waited for)
-        f32x16 acc2[NB2][CB];
-        // small addresses are rebuilt where they are used rather than kept in registers across the steps
-        uint32_t t16 = tid16;
-        asm volatile("" : "+v"(t16));
-        const uint32_t b2_addr = (uint32_t)(uintptr_t)b2buf + ((t16 >> 5) & 16);  // 16 bytes * g
-        static_for<0, NB2>([&](auto n2c) {
-            constexpr int n2 = decltype(n2c)::value;
-            u32x4 bv[4];
-            lds_load4_b128<n2 * 128, 32>(b2_addr, bv[0], bv[1], bv[2], bv[3]);
-            f32x16 init;
-#pragma unroll
-            for (int t4 = 0; t4 < 4; ++t4)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) init[4 * t4 + e] = __uint_as_float(bv[t4][e]);
-#pragma unroll
-            for (int c = 0; c < CB; ++c) acc2[n2][c] = init;
-        });
+        // The layer-2 accumulators (the 256 accumulation registers, which only the assembly statements of this
+        // loop touch: see gen_stream_asm.py) start from the bias, read from LDS straight into them; step 0 begins
+        // with a full wait for LDS reads.
+        {
+            uint32_t t16 = tid16;  // small addresses are rebuilt where they are used rather than kept across the steps
+            asm volatile("" : "+v"(t16));
+            const uint32_t b2_addr = (uint32_t)(uintptr_t)b2buf + ((t16 >> 5) & 16);  // 16 bytes * g
+            asm volatile(STREAM_ASM_INIT_ACC2 : : [b2] "v"(b2_addr) : "memory", STREAM_ACC2_CLOBBERS);
+        }
 
         // Two sets of layer-1 accumulators (A, B) and of converted hidden units alternate by step;
         // all of them, and the layer-2 accumulators, sit in fixed physical registers (see
@@ -297,38 +278,51 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
 #define STEP_ODD(i)                                                                                   \
     asm volatile(STREAM_ASM_STEP_##i                                                                  \
                  : STREAM_ACC_B(accB0, accB1), STREAM_ACC_OUT_A(accA0, accA1), STREAM_SB(sbv),        \
-                   STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpB) \
+                   STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), FRAG_TEMPS, [xpn] "=&v"(xpB)              \
                  : STEP_COMMON(i), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), STEP_LOADS, \
                    [xpo] "v"(xpA), [xw] "v"(xw_addr)                                                  \
-                 : "memory", "scc");
+                 : "memory", "scc", STREAM_ACC2_CLOBBERS);
 #define STEP_EVEN(i)                                                                                  \
     asm volatile(STREAM_ASM_STEP_##i                                                                  \
                  : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1), STREAM_SB(sbv),        \
-                   STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), STREAM_ACC2, FRAG_TEMPS, [xpn] "=&v"(xpA) \
+                   STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), FRAG_TEMPS, [xpn] "=&v"(xpA)              \
                  : STEP_COMMON(i), X_OPERANDS, STREAM_HF_IN_B(hB00, hB01, hB10, hB11), STEP_LOADS, \
                    [xpo] "v"(xpB), [xw] "v"(xw_addr)                                                  \
-                 : "memory", "scc");
+                 : "memory", "scc", STREAM_ACC2_CLOBBERS);
         // step 0: layer 1 only
         asm volatile(STREAM_ASM_STEP_0
                      : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1), STREAM_SB(sbv),
                        STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), FRAG_TEMPS, [xpn] "=&v"(xpA)
                      : STEP_COMMON(0), X_OPERANDS, STEP_LOADS
-                     : "memory", "scc");
+                     : "memory", "scc", STREAM_ACC2_CLOBBERS);
         STEP_ODD(1) STEP_EVEN(2) STEP_ODD(3) STEP_EVEN(4) STEP_ODD(5) STEP_EVEN(6) STEP_ODD(7)
         xs = emb + nxt_off[1];  // steps 8..15 fetch the row of pair c = 1
         STEP_EVEN(8) STEP_ODD(9) STEP_EVEN(10) STEP_ODD(11) STEP_EVEN(12) STEP_ODD(13) STEP_EVEN(14)
         sbv = (const char *)frag;  // steps 15 and 16 fetch chunks 0 and 1 again
         asm volatile(STREAM_ASM_STEP_15   // the last layer-1 block: no user term to fetch
-                     : STREAM_ACC_B(accB0, accB1), STREAM_SB(sbv), STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), STREAM_ACC2,
+                     : STREAM_ACC_B(accB0, accB1), STREAM_SB(sbv), STREAM_HF_OUT_B(hB00, hB01, hB10, hB11),
                        FRAG_TEMPS, [xpn] "=&v"(xpB)
                      : STEP_COMMON(15), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), [xs] "v"(xs),
                        [xpo] "v"(xpA), [xw] "v"(xw_addr)
-                     : "memory", "scc");
-        // step 16: layer 2 only
-        asm volatile(STREAM_ASM_STEP_16
-                     : STREAM_ACC2, FRAG_TEMPS, STREAM_SB(sbv)
-                     : STEP_COMMON(16), STREAM_HF_IN_B(hB00, hB01, hB10, hB11), [xpo] "v"(xpB), [xw] "v"(xw_addr)
-                     : "memory", "scc");
+                     : "memory", "scc", STREAM_ACC2_CLOBBERS);
+        // ids of the next batch (again) and of the one after it: requested ahead of the last step, which hides
+        // their latency
+        const RawIds raw_c = request_ids(tile + gridDim.x), raw_n = request_ids(tile + 2 * (int64_t)gridDim.x);
+        // step 16: layer 2 of the last hidden block tile by tile, and behind each finished tile its ReLU + bf16
+        // conversion and the head layer's MFMAs over it (fragment rows >= J are zero)
+        f32x16 acc3[CB];
+        {
+            uint32_t h16 = tid16;
+            asm volatile("" : "+v"(h16));
+            const uint32_t w3_addr = (uint32_t)(uintptr_t)w3buf + (h16 & 1023);  // 16 bytes * lane
+            u32x4 w30, w31, w32, w33;  // head fragments in flight from LDS
+            asm volatile(STREAM_ASM_STEP_16
+                         : FRAG_TEMPS, STREAM_SB(sbv), STREAM_ACC3(acc3[0], acc3[1]),
+                           [w30] "=&v"(w30), [w31] "=&v"(w31), [w32] "=&v"(w32), [w33] "=&v"(w33)
+                         : STEP_COMMON(16), STREAM_HF_IN_B(hB00, hB01, hB10, hB11), [xpo] "v"(xpB), [xw] "v"(xw_addr),
+                           [w3] "v"(w3_addr)
+                         : "memory", "scc", STREAM_HEAD_CLOBBERS, STREAM_ACC2_CLOBBERS);
+        }
 #undef STEP_ODD
 #undef STEP_EVEN
 #undef STEP_LOADS
@@ -339,33 +333,12 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
             wsv[1] = wsv[0], lbv[1] = lbv[0];
             wsv[0] = w, lbv[0] = l;
         }
-        // ids of the next batch (again) and of the one after it; the head layer hides their latency
-        idc = load_ids(tile + gridDim.x);
-        idn = load_ids(tile + 2 * (int64_t)gridDim.x);
-
-        // head layer (fragment rows >= J are zero), then Eq. 8
-        f32x16 acc3[CB];
-#pragma unroll
-        for (int c = 0; c < CB; ++c)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc3[c][e] = 0.f;
+        idc = check_ids(raw_c);
+        idn = check_ids(raw_n);
+        // Eq. 8 over the head accumulators
         uint32_t h16 = tid16;
         asm volatile("" : "+v"(h16));
-        const uint32_t w3_addr = (uint32_t)(uintptr_t)w3buf + (h16 & 1023);    // 16 bytes * lane
         const uint32_t hb_addr = (uint32_t)(uintptr_t)b2buf + ((h16 >> 5) & 16);  // 16 bytes * g
-        static_for<0, NB2 / 2>([&](auto n2c) {
-            constexpr int n2 = 2 * decltype(n2c)::value;
-            u32x4 a[4];
-            lds_load4_b128<2 * n2 * 1024, 1024>(w3_addr, a[0], a[1], a[2], a[3]);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const bf16x8 h0 = relu_pack_i16(acc2[n2 + t / 2][0], t % 2), h1 = relu_pack_i16(acc2[n2 + t / 2][1], t % 2);
-                if (n2 + 2 == NB2 && t == 3)
-                    mfma_v_pair<true>(acc3[0], acc3[1], __builtin_bit_cast(bf16x8, a[t]), h0, h1);
-                else
-                    mfma_v_pair<false>(acc3[0], acc3[1], __builtin_bit_cast(bf16x8, a[t]), h0, h1);
-            }
-        });
         float hw[4], bb3[4];
         {
             u32x4 r0, r1, r2, r3;

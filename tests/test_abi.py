@@ -85,3 +85,35 @@ def test_generated_assembly_is_up_to_date(tmp_path):
         spec.loader.exec_module(mod)
         mod.main()   # writes the .inc next to the copied script
         assert (work / inc).read_text() == open(os.path.join(csrc, inc)).read(), f"{inc} is stale: run {script}"
+
+
+def test_stream_kernel_keeps_accumulation_registers_to_its_assembly(tmp_path):
+    """The widest bf16 kernel names its 256 accumulation registers outright inside its assembly statements and
+    only lists them as clobbered, so nothing the compiler generates between two statements may touch one (a
+    spill into them, a copy through them): in the kernel's compiled code every accumulation register sits
+    between the markers of an assembly statement, and nothing is spilled."""
+    import shutil
+    import subprocess
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("no hipcc here")
+    csrc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2502_11490_amd", "csrc")
+    out = tmp_path / "stream.s"
+    from paper_2502_11490_amd import build
+    flags = [f for f in build.FLAGS if f not in ("-shared", "-fPIC")]
+    subprocess.run([hipcc] + flags + ["-S", "--cuda-device-only", os.path.join(csrc, "mlp_mfma_stream.hip"), "-o", str(out)],
+                   check=True, capture_output=True)
+    text = out.read_text()
+    start = text.index("mlp_mfma2_stream_kernel")
+    inside, statements, outside = False, 0, []
+    for line in text[start:].split("\n"):
+        if "#ASMSTART" in line:
+            inside, statements = True, statements + 1
+        elif "#ASMEND" in line:
+            inside = False
+        elif not inside:
+            code = line.split(";")[0]
+            if re.search(r"\ba\[?\d+", code) or "accvgpr" in code or "scratch_" in code:
+                outside.append(line.strip())
+    assert statements >= 18          # the 17 steps and the bias statement were found
+    assert not outside, outside[:5]
