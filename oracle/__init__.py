@@ -44,6 +44,7 @@ def _load():
         _lib.oracle_e4m3_quantize.restype = ctypes.c_int64
         _lib.oracle_noise_element.restype = ctypes.c_double
         _lib.oracle_philox4x32_10.restype = None
+        _lib.oracle_f16_round.restype = None
     return _lib
 
 
@@ -59,6 +60,7 @@ def widen_bf16(bits: np.ndarray) -> np.ndarray:
 def _as_f32(a: np.ndarray) -> np.ndarray:
     if a.dtype == np.uint16:
         return widen_bf16(a)
+    # fp16 arrays widen exactly too (the cast below); they are then ordinary fp32 inputs
     return np.ascontiguousarray(a, dtype=np.float32)
 
 
@@ -86,7 +88,7 @@ def _table(a: np.ndarray):
     """(array, dtype code) for an embedding / user table given as fp32 or raw bf16 bits."""
     if a.dtype == np.uint16:
         return np.ascontiguousarray(a), BF16
-    return np.ascontiguousarray(a, dtype=np.float32), F32
+    return np.ascontiguousarray(a, dtype=np.float32), F32   # fp16 tables widen exactly
 
 
 def score_pairs(emb: np.ndarray, users: np.ndarray, mlp: Mlp, q_idx: np.ndarray, item: np.ndarray,
@@ -270,6 +272,14 @@ def users_add_noise(users: np.ndarray, sigma: float, seed: int, stream: int = 0)
                                         _ptr(out))
     if rc != 0:
         raise ValueError(f"oracle_users_add_noise failed rc={rc}")
+    return out
+
+
+def f16_round(a: np.ndarray) -> np.ndarray:
+    """fp32 -> binary16 (nearest even) -> fp32: the rounding act_round = 3 applies to hidden activations."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    out = np.empty(a.shape, dtype=np.float32)
+    _load().oracle_f16_round(_ptr(a), ctypes.c_int64(a.size), _ptr(out))
     return out
 
 

@@ -43,12 +43,16 @@
  * nearest even), i.e. to e4m3(s_l * a) / s_l.  Weights and item vectors of that metric are
  * quantised by the caller beforehand (oracle_e4m3_encode / _quantize) and arrive here as
  * ordinary numbers.
+ * With act_round = 3 (the fp16 metric, the 16-bit format of Sec. 4.3) each hidden activation is
+ * rounded double -> fp32 -> binary16 (nearest even, overflow to infinity) after the ReLU; fp16
+ * inputs and weights arrive widened to fp32, which is exact.
  *
  * Parity pins (tests/test_oracle_*.py): closed forms and hand-worked values for
  * the relevance, a library MLP forward pass, brute-force equality on complete
  * graphs / L >= N, a hand-derived ring-graph trajectory, an independently
  * written priority-queue best-first search for W = E = 1, monotonicity and
- * uniqueness invariants, and entry/batch permutation symmetries; for the noise
+ * uniqueness invariants, and entry/batch permutation symmetries; for the binary16
+ * rounding an independent library's conversion; for the noise
  * draw the generator's published known-answer vectors, goodness-of-fit of the
  * variates and of the Box-Muller pairs, and an independent bf16 rounding.  The recall
  * level reached on the synthetic graphs has no external pin: "parity unpinned"
@@ -144,6 +148,25 @@ int64_t oracle_e4m3_encode(const float *in, int64_t n, double scale, uint8_t *co
 }
 
 /* out[i] = e4m3(scale * in[i]) / scale */
+/* double -> fp32 -> binary16 (5 exponent bits, 10 fraction bits, subnormals below 2^-14), both
+ * round-to-nearest-even; beyond the largest value 65504 the result is infinity; returned widened */
+static double round_to_f16(double v) {
+    float f = (float)v;
+    if (f != f || f == 0.0f || isinf(f)) return (double)f;
+    float a = fabsf(f);
+    if (a >= 65520.0f) return f < 0 ? -INFINITY : INFINITY; /* 65520: half-way to 2^16, ties go to even */
+    int e;
+    (void)frexpf(a, &e);            /* a = m 2^e with m in [0.5, 1): 11 significant bits -> spacing 2^(e-11) */
+    int q = e - 11;
+    if (q < -24) q = -24;           /* subnormal spacing */
+    float r = ldexpf(nearbyintf(ldexpf(a, -q)), q); /* scaling by powers of two is exact */
+    return (double)(f < 0 ? -r : r);
+}
+
+void oracle_f16_round(const float *in, int64_t n, float *out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = (float)round_to_f16((double)in[i]);
+}
+
 int64_t oracle_e4m3_quantize(const float *in, int64_t n, double scale, float *out) {
     int64_t clamped = 0;
     for (int64_t i = 0; i < n; ++i) {
@@ -178,6 +201,7 @@ static float relevance(const mlp_t *m, const double *x, double *h0, double *h1) 
             if (!last) {
                 if (acc < 0.0) acc = 0.0;
                 if (m->act_round == 1) acc = round_to_bf16(acc);
+                if (m->act_round == 3) acc = round_to_f16(acc);
                 if (m->act_round == 2) {
                     double scale = ldexp(1.0, 2 * (l + 1)); /* 4^(l+1) */
                     acc = round_to_e4m3(acc * scale) / scale;

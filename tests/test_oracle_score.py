@@ -218,3 +218,32 @@ def test_activation_rounding_option_rounds_to_e4m3_at_the_layers_scale():
     # 0.3125 + 0.0195 = 0.332 -> x16 = 5.312 -> 5.5 -> 0.34375
     assert _score_one([0.3125], [0.0], W2, b2s, [1.0], act_round=2) == pytest.approx(float(expit(0.34375)), abs=6e-8)
     assert _score_one([40.0], [0.0], W2, b2, [1.0], act_round=2) == pytest.approx(float(expit(28.0)), abs=6e-8)
+
+
+# ----------------------------------------------------------------------------- the fp16 metric
+def test_f16_rounding_equals_a_library_conversion_and_known_values():
+    rng = np.random.default_rng(1)
+    x = np.concatenate([rng.standard_normal(100000) * s for s in (1e-7, 1e-5, 1e-3, 0.1, 1, 10, 1000, 30000)])
+    x = x.astype(np.float32)
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).astype(np.float32)     # numpy's conversion: IEEE nearest even
+    got = oracle.f16_round(x)
+    assert np.array_equal(got, want)
+    assert np.isinf(got).any() and (got == 0).any()        # the sample reaches both ends of the range
+    # by hand: 11 significant bits -> spacing 2^-10 at 1: the tie 1 + 2^-11 goes to the even 1, 1 + 3 * 2^-11 to
+    # 1 + 2^-9 ... (even mantissa 2); largest value 65504, 65520 is the tie that goes to infinity;
+    # smallest subnormal 2^-24, half of it goes to zero
+    hand = np.array([1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 65504.0, 65519.0, 65520.0, -65520.0, 2.0 ** -24, 2.0 ** -25,
+                     3 * 2.0 ** -25, -0.0], np.float32)
+    out = oracle.f16_round(hand)
+    assert out.tolist() == [1.0, 1 + 2.0 ** -9, 65504.0, 65504.0, np.inf, -np.inf, 2.0 ** -24, 0.0, 2.0 ** -23, 0.0]
+    assert np.signbit(out[-1])
+
+
+def test_activation_rounding_option_rounds_to_f16():
+    W = [np.array([[1.0, 0.0]], np.float32), np.array([[1.0]], np.float32)]
+    b = [np.zeros(1, np.float32), np.zeros(1, np.float32)]
+    for x, rounded in ((1 + 2.0 ** -11, 1.0), (1 + 3 * 2.0 ** -11, 1 + 2.0 ** -9), (-3.0, 0.0), (0.1, 0.0999755859375)):
+        assert _score_one([x], [0.0], W, b, [1.0], act_round=3) == pytest.approx(float(expit(rounded)), abs=6e-8)
+    # without the option the activation is not rounded
+    assert _score_one([0.1], [0.0], W, b, [1.0]) == pytest.approx(float(expit(np.float32(0.1))), abs=6e-8)
