@@ -53,7 +53,7 @@ enum {
     ANN_EWORKSPACE = -5  /* workspace too small, or a per-query visited table filled up */
 };
 
-enum { ANN_F32 = 0, ANN_BF16 = 1, ANN_F8 = 2 };
+enum { ANN_F32 = 0, ANN_BF16 = 1, ANN_F8 = 2, ANN_F16 = 3 };
 
 enum {
     ANN_VALIDATE = 1u,   /* ann_graph_load: check on the device that every adjacency id is < N */
@@ -75,7 +75,7 @@ typedef struct ann_stats {
 /*
  * The item graph of Sec. 3.2 (base layer, fixed out-degree).
  *   adj_dev : [N][R] int32 row-major neighbour ids; ids outside [0, N) are ignored by the search
- *   emb_dev : [N][d] row-major item vectors, fp32 (ANN_F32) or bf16 (ANN_BF16)
+ *   emb_dev : [N][d] row-major item vectors, fp32 (ANN_F32), bf16 (ANN_BF16) or fp16 (ANN_F16)
  * Both arrays are BORROWED: they must stay valid and unchanged until ann_graph_free.
  * Requirements: 1 <= N < 2^31, 1 <= R <= 64, 1 <= d <= 1024; rows must be 4-byte aligned,
  * 16-byte alignment of emb_dev and d*sizeof(elem) % 16 == 0 are needed for the MFMA path.
@@ -89,7 +89,7 @@ void ann_graph_free(ann_graph *g);
 /*
  * The relevance metric of Sec. 3.1 (1): n_layers affine layers, Eq. 7 (W h + b).
  *   dims_host   : [n_layers + 1]; dims[0] = d_user + d_item, dims[n_layers] = J (1 <= J <= 8)
- *   W_host[l]   : [dims[l+1]][dims[l]] row-major, fp32 or bf16 as `dtype`; the first d_user
+ *   W_host[l]   : [dims[l+1]][dims[l]] row-major, fp32, bf16 or fp16 as `dtype`; the first d_user
  *                 columns of W_host[0] multiply the user vector (Eq. 5: user first)
  *   b_host[l]   : [dims[l+1]] fp32
  *   head_w_host : [J] fp32 combination weights (the vector A of Eq. 8)
@@ -98,6 +98,9 @@ void ann_graph_free(ann_graph *g);
  * dtype = ANN_BF16 means: items, users and weights are bf16, products are accumulated in
  * fp32, every hidden activation is rounded to bf16 (nearest even) after its ReLU, head
  * logits, sigmoid and the weighted sum stay in fp32 (the 16-bit deployment of Sec. 4.3).
+ * dtype = ANN_F16 is the same with IEEE binary16 in place of bf16 (the format Sec. 4.3 names): items,
+ * users and weights are fp16, hidden activations are rounded to fp16 (nearest even) after the ReLU.
+ * ann_users_add_noise and ann_quantize_e4m3 do not take fp16 arrays.
  */
 int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *W_host,
                  const float *const *b_host, const float *head_w_host, int32_t d_user,

@@ -7,6 +7,7 @@ of libgmpgr_ann.so.  There is no CPU fallback; importing works without a GPU, ca
 from .binding import (  # noqa: F401
     ANN_BF16,
     ANN_F8,
+    ANN_F16,
     ANN_F32,
     ANN_MLP_GENERIC,
     ANN_VALIDATE,

@@ -10,7 +10,7 @@ import numpy as np
 import torch
 
 ANN_OK, ANN_EINVAL, ANN_ENOMEM, ANN_EDEVICE, ANN_ENOTIMPL, ANN_EWORKSPACE = 0, -1, -2, -3, -4, -5
-ANN_F32, ANN_BF16, ANN_F8 = 0, 1, 2
+ANN_F32, ANN_BF16, ANN_F8, ANN_F16 = 0, 1, 2, 3
 ANN_VALIDATE, ANN_MLP_GENERIC = 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -127,6 +127,8 @@ def _dtype_code(t: torch.Tensor) -> int:
         return ANN_BF16
     if t.dtype == torch.float8_e4m3fn:
         return ANN_F8
+    if t.dtype == torch.float16:
+        return ANN_F16
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
@@ -186,15 +188,16 @@ def _host_bytes(t) -> np.ndarray:
 
 
 def ann_mlp_load(W: Sequence, b: Sequence, head_w, d_user: int, dtype: int, flags: int = 0, stream=None) -> Mlp:
-    """W[l]: [out,in] torch tensors (fp32 or bf16, matching dtype) or numpy arrays (bf16 as uint16 bits);
+    """W[l]: [out,in] torch tensors (fp32, bf16 or fp16, matching dtype) or numpy arrays (bf16 as uint16 bits);
     b[l]: [out] fp32; head_w: [J] fp32."""
     lib = load_library()
     n = len(W)
     Wh = [_host_bytes(w) for w in W]
-    want = np.float32 if dtype == ANN_F32 else np.uint16  # the 8-bit metric takes bf16 weights and quantises them
+    # the 8-bit metric takes bf16 weights and quantises them
+    want = {ANN_F32: np.float32, ANN_F16: np.float16}.get(dtype, np.uint16)
     for w in Wh:
         if w.dtype != want:
-            raise TypeError(f"weights must be {'fp32' if dtype == ANN_F32 else 'bf16'}")
+            raise TypeError(f"weights must be {np.dtype(want).name if want != np.uint16 else 'bf16'}")
     bh = [np.ascontiguousarray(_host_bytes(x), dtype=np.float32) for x in b]
     hw = np.ascontiguousarray(_host_bytes(head_w), dtype=np.float32)
     dims = [Wh[0].shape[1]] + [w.shape[0] for w in Wh]

@@ -391,8 +391,8 @@ int ann_graph_load(const int32_t *adj_dev, const void *emb_dev, int64_t N, int32
         set_error("need 1 <= N < 2^31, 1 <= R <= 64, 1 <= d <= 1024 (got N=%lld R=%d d=%d)", (long long)N, R, d);
         return ANN_EINVAL;
     }
-    if (dtype != ANN_F32 && dtype != ANN_BF16 && dtype != ANN_F8) {
-        set_error("dtype must be ANN_F32, ANN_BF16 or ANN_F8");
+    if (dtype != ANN_F32 && dtype != ANN_BF16 && dtype != ANN_F8 && dtype != ANN_F16) {
+        set_error("dtype must be ANN_F32, ANN_BF16, ANN_F16 or ANN_F8");
         return ANN_EINVAL;
     }
     if (dtype == ANN_F8 && (((uintptr_t)emb_dev & 15) || (d & 15))) {
@@ -458,8 +458,8 @@ int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *
         set_error("need 1 <= n_layers <= %d", MAX_LAYERS);
         return ANN_EINVAL;
     }
-    if (dtype != ANN_F32 && dtype != ANN_BF16 && dtype != ANN_F8) {
-        set_error("dtype must be ANN_F32, ANN_BF16 or ANN_F8");
+    if (dtype != ANN_F32 && dtype != ANN_BF16 && dtype != ANN_F8 && dtype != ANN_F16) {
+        set_error("dtype must be ANN_F32, ANN_BF16, ANN_F16 or ANN_F8");
         return ANN_EINVAL;
     }
     if (dtype == ANN_F8 && !f8_supported(dims_host, n_layers, d_user)) {

@@ -1,6 +1,6 @@
 // Relevance metric of Sec. 3.1 (1), Eq. 5-8, on the vector ALUs (fp32 FMA).
 //
-// This is the path for fp32 metrics and the fallback for bf16 metrics whose shape the MFMA
+// This is the path for fp32 metrics and the fallback for 16-bit metrics whose shape the MFMA
 // kernels do not cover.  A workgroup takes one batch of T pairs from the dense pair list
 // (the fixed-size batch of Algorithm 2), keeps the activations of the whole batch in LDS and
 // walks the layers; a thread owns one pair and a strided set of output units, so a weight is
@@ -12,9 +12,9 @@
 // fp32 rate, and this mode is the reference-precision one), ReLU on hidden layers,
 // relevance = sum_j w_j / (1 + exp(-z_j)) in fp64 (Eq. 8), rounded once to fp32.  Rank
 // decisions therefore see the correctly rounded relevance, not fp32 summation noise.
-// bf16 mode: inputs and weights are bf16 widened to fp32, fp32 FMA chains starting from the
-// bias, every hidden activation rounded to bf16 (nearest even) after the ReLU; logits, sigmoid
-// and the weighted sum in fp32 (the arithmetic of the MFMA kernels, on the plain ALUs).
+// bf16 and fp16 modes: inputs and weights are widened to fp32, fp32 FMA chains with the bias
+// added last, every hidden activation rounded to the 16-bit format (nearest even) after the ReLU;
+// logits, sigmoid and the weighted sum in fp32 (the arithmetic of the MFMA kernels, on the plain ALUs).
 #include "common.h"
 
 namespace gmpgr {
@@ -29,8 +29,13 @@ __device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
-template <bool BF16> struct Elem;
-template <> struct Elem<false> {
+// binary16 <-> fp32 through the hardware's conversions (nearest even, subnormals kept)
+__device__ __forceinline__ float f16_bits_to_float(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+__device__ __forceinline__ uint16_t float_to_f16_rne(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+
+// KIND: the library's dtype code (ANN_F32, ANN_BF16, ANN_F16)
+template <int KIND> struct Elem;
+template <> struct Elem<ANN_F32> {
     using type = float;   // storage of items, users, weights
     using act = double;   // activations in LDS and accumulators
     static __device__ __forceinline__ float load(const float *p, size_t i) { return p[i]; }
@@ -38,13 +43,24 @@ template <> struct Elem<false> {
     static __device__ __forceinline__ double hidden(double a) { return a > 0.0 ? a : 0.0; }
     static __device__ __forceinline__ double sigmoid(double z) { return 1.0 / (1.0 + exp(-z)); }
 };
-template <> struct Elem<true> {
+template <> struct Elem<ANN_BF16> {
     using type = uint16_t;
     using act = float;
     static __device__ __forceinline__ float load(const uint16_t *p, size_t i) { return bf16_bits_to_float(p[i]); }
     static __device__ __forceinline__ float fma(float w, float x, float acc) { return fmaf(w, x, acc); }
     static __device__ __forceinline__ float hidden(float a) {
         return bf16_bits_to_float(float_to_bf16_rne(fmaxf(a, 0.f)));
+    }
+    static __device__ __forceinline__ float sigmoid(float z) { return 1.0f / (1.0f + expf(-z)); }
+};
+
+template <> struct Elem<ANN_F16> {
+    using type = uint16_t;
+    using act = float;
+    static __device__ __forceinline__ float load(const uint16_t *p, size_t i) { return f16_bits_to_float(p[i]); }
+    static __device__ __forceinline__ float fma(float w, float x, float acc) { return fmaf(w, x, acc); }
+    static __device__ __forceinline__ float hidden(float a) {
+        return f16_bits_to_float(float_to_f16_rne(fmaxf(a, 0.f)));
     }
     static __device__ __forceinline__ float sigmoid(float z) { return 1.0f / (1.0f + expf(-z)); }
 };
@@ -59,15 +75,15 @@ struct AluMlpParams {
 };
 
 // act buffers: two ping-pong arrays of T rows with row stride `stride` floats (odd).
-template <bool BF16>
+template <int KIND>
 __global__ void __launch_bounds__(ALU_BLOCK)
-mlp_alu_kernel(AluMlpParams P, const typename Elem<BF16>::type *__restrict__ emb, int64_t N,
-               const typename Elem<BF16>::type *__restrict__ users, int32_t Q,
-               const typename Elem<BF16>::type *__restrict__ W, const float *__restrict__ b,
+mlp_alu_kernel(AluMlpParams P, const typename Elem<KIND>::type *__restrict__ emb, int64_t N,
+               const typename Elem<KIND>::type *__restrict__ users, int32_t Q,
+               const typename Elem<KIND>::type *__restrict__ W, const float *__restrict__ b,
                const int32_t *__restrict__ pair_q, const int32_t *__restrict__ pair_id,
                const int32_t *__restrict__ M_dev, int64_t M_max, float *__restrict__ scores, int T, int stride) {
     extern __shared__ __align__(16) unsigned char act_raw[];
-    using E = Elem<BF16>;
+    using E = Elem<KIND>;
     using A = typename E::act;
     A *act = (A *)act_raw;
     int64_t M = M_dev ? (int64_t)*M_dev : M_max;
@@ -140,8 +156,8 @@ int launch_mlp_alu(const ann_graph *g, const ann_mlp *m, const void *queries, co
     P.J = m->J;
     for (int j = 0; j < m->J; ++j) P.head_w[j] = m->head_w[j];
     const int stride = maxw | 1;
-    const bool bf16 = (m->dtype == ANN_BF16);
-    const size_t asz = bf16 ? sizeof(float) : sizeof(double);
+    const bool half = (m->dtype != ANN_F32);  // a 16-bit metric: fp32 activations
+    const size_t asz = half ? sizeof(float) : sizeof(double);
     // largest batch (pairs per workgroup) whose two activation buffers fit in 144 KB of LDS
     int T = 64;
     if (tile_rows > 0 && tile_rows < 64) {
@@ -159,20 +175,26 @@ int launch_mlp_alu(const ann_graph *g, const ann_mlp *m, const void *queries, co
         set_error("layer width %d does not fit the ALU kernel", maxw);
         return ANN_ENOTIMPL;
     }
-    const void *fn = bf16 ? (const void *)mlp_alu_kernel<true> : (const void *)mlp_alu_kernel<false>;
+    const void *fn = m->dtype == ANN_BF16  ? (const void *)mlp_alu_kernel<ANN_BF16>
+                     : m->dtype == ANN_F16 ? (const void *)mlp_alu_kernel<ANN_F16>
+                                           : (const void *)mlp_alu_kernel<ANN_F32>;
     if (smem > 48 * 1024) {
-        static std::atomic<uint32_t> raised[2];
-        int rc = raise_lds_limit(fn, 144 * 1024, m->device, raised[bf16 ? 1 : 0]);
+        static std::atomic<uint32_t> raised[3];
+        int rc = raise_lds_limit(fn, 144 * 1024, m->device, raised[m->dtype == ANN_BF16 ? 1 : m->dtype == ANN_F16 ? 2 : 0]);
         if (rc != ANN_OK) return rc;
     }
     int64_t tiles = (M_max + T - 1) / T;
     int grid = (int)(tiles < 4096 ? tiles : 4096);
-    if (bf16)
-        hipLaunchKernelGGL(mlp_alu_kernel<true>, dim3(grid), dim3(ALU_BLOCK), smem, stream, P,
+    if (m->dtype == ANN_BF16)
+        hipLaunchKernelGGL(mlp_alu_kernel<ANN_BF16>, dim3(grid), dim3(ALU_BLOCK), smem, stream, P,
+                           (const uint16_t *)g->emb, g->N, (const uint16_t *)queries, Q,
+                           (const uint16_t *)m->W_dev, m->b_dev, pair_q, pair_id, M_dev, M_max, scores, T, stride);
+    else if (m->dtype == ANN_F16)
+        hipLaunchKernelGGL(mlp_alu_kernel<ANN_F16>, dim3(grid), dim3(ALU_BLOCK), smem, stream, P,
                            (const uint16_t *)g->emb, g->N, (const uint16_t *)queries, Q,
                            (const uint16_t *)m->W_dev, m->b_dev, pair_q, pair_id, M_dev, M_max, scores, T, stride);
     else
-        hipLaunchKernelGGL(mlp_alu_kernel<false>, dim3(grid), dim3(ALU_BLOCK), smem, stream, P,
+        hipLaunchKernelGGL(mlp_alu_kernel<ANN_F32>, dim3(grid), dim3(ALU_BLOCK), smem, stream, P,
                            (const float *)g->emb, g->N, (const float *)queries, Q, (const float *)m->W_dev,
                            m->b_dev, pair_q, pair_id, M_dev, M_max, scores, T, stride);
     ANN_HIP_TRY(hipGetLastError());

@@ -16,7 +16,7 @@ def open_handles(wl, flags_mlp: int = 0, validate: bool = True):
     for key in ("emb", "adj", "users", "entries", "W_q", "L_q", "cap_q"):
         if key in wl:
             dev[key] = wl[key].to("cuda").contiguous()
-    dtype = ann.ANN_BF16 if wl["emb"].dtype == torch.bfloat16 else ann.ANN_F32
+    dtype = {torch.bfloat16: ann.ANN_BF16, torch.float16: ann.ANN_F16}.get(wl["emb"].dtype, ann.ANN_F32)
     g = ann.ann_graph_load(dev["adj"], dev["emb"], ann.ANN_VALIDATE if validate else 0)
     d_user = wl["users"].shape[1]
     m = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], d_user, dtype, flags_mlp)

@@ -1,0 +1,97 @@
+"""GPU parity of the fp16 metric (IEEE binary16 in place of bf16: the 16-bit format Sec. 4.3 names).
+
+Bar as for bf16: relevance within 1e-2 absolute of the oracle's exact-arithmetic value and recall@k within one
+point of the oracle's.  Against the oracle run at the kernel's precision (hidden activations rounded to
+binary16, act_round = 3) what is left is fp32 summation order and the rare one-ulp flip it causes, and a
+binary16 ulp is an eighth of a bf16 ulp: 5e-4 at most, median below 5e-6.
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import PRESETS, make_workload, random_mlp, scaled, to_host
+
+pytestmark = pytest.mark.gpu
+
+ann = pytest.importorskip("paper_2502_11490_amd")
+from gpu_util import open_handles, oracle_mlp, same_list_fraction  # noqa: E402
+
+
+def _as_f16(wl):
+    """The bf16 workload with items, users and weights converted to fp16 (values move by a rounding)."""
+    out = dict(wl)
+    for key in ("emb", "users"):
+        out[key] = wl[key].to(torch.float16)
+    out["W"] = [w.to(torch.float16) for w in wl["W"]]
+    return out
+
+
+@pytest.mark.parametrize("preset,flags", [("C2", 0), ("C3", 0), ("C4", 0), ("C2", "generic"), ("C3", "generic")])
+def test_relevance_f16(preset, flags):
+    cfg = scaled(PRESETS[preset], 6000, n_clusters=12, Q=45)
+    wl = make_workload(cfg)
+    wl["W"], wl["b"] = random_mlp(cfg.dims, 23, cfg.dtype, bias_scale=0.2)
+    wl = _as_f16(wl)
+    g, m, dev = open_handles(wl, flags_mlp=ann.ANN_MLP_GENERIC if flags == "generic" else 0)
+    if flags == "generic":
+        assert not ann.ann_mlp_uses_mfma(m)
+    rng = np.random.default_rng(4)
+    M = 2 * 1024 + 77
+    q = np.sort(rng.integers(0, cfg.Q, M)).astype(np.int32)
+    it = rng.integers(0, cfg.N, M).astype(np.int32)
+    got = ann.ann_score_pairs(g, m, dev["users"], torch.from_numpy(q).cuda(), torch.from_numpy(it).cuda()).cpu().numpy()
+    h = to_host(wl)
+    mlp = oracle_mlp(h)
+    exact = oracle.score_pairs(h["emb"], h["users"], mlp, q, it, n_threads=8)
+    kern = oracle.score_pairs(h["emb"], h["users"], mlp, q, it, act_round=3, n_threads=8)
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got - exact)) <= 1e-2
+    err = np.abs(got - kern)
+    print(f"{preset} {flags}: mfma {ann.ann_mlp_uses_mfma(m)}, vs exact max {np.max(np.abs(got - exact)):.2e}, "
+          f"vs kernel precision max {np.max(err):.2e} median {np.median(err):.2e}")
+    assert np.max(err) <= 5e-4 and np.median(err) <= 5e-6
+
+
+@pytest.mark.parametrize("preset", ["C2", "C3"])
+def test_search_f16_recall_matches_oracle(preset):
+    base = PRESETS[preset]
+    cfg = replace(scaled(base, 60000, Q=96), E=base.E)
+    wl = _as_f16(make_workload(cfg))
+    g, m, dev = open_handles(wl)
+    k = 50
+    ids, sc = ann.ann_search(g, m, dev["users"], dev["entries"], base.W, base.L, k, 0)
+    h = to_host(wl)
+    mlp = oracle_mlp(h)
+    ref = oracle.search(h["emb"], h["adj"], h["users"], mlp, h["entries"], base.W, base.L, k, 0, n_threads=8)
+    bf = oracle.brute_force(h["emb"], h["users"][:24], mlp, k, n_threads=8)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    r_gpu = oracle.recall_at(ids[:24], bf["ids"], k)
+    r_ref = oracle.recall_at(ref["ids"][:24], bf["ids"], k)
+    assert abs(r_gpu - r_ref) <= 0.01 + 1e-9, (r_gpu, r_ref)
+    qq = np.repeat(np.arange(cfg.Q), k).astype(np.int32)
+    valid = ids.ravel() >= 0
+    exact = oracle.score_pairs(h["emb"], h["users"], mlp, qq[valid], ids.ravel()[valid], n_threads=8)
+    assert np.max(np.abs(sc.ravel()[valid] - exact)) <= 1e-2
+    for q in range(cfg.Q):
+        v = ids[q][ids[q] >= 0]
+        assert len(set(v.tolist())) == len(v)
+        assert np.all(sc[q][: len(v)][:-1] >= sc[q][: len(v)][1:])
+    kern = oracle.search(h["emb"], h["adj"], h["users"], mlp, h["entries"], base.W, base.L, k, 0, act_round=3,
+                         n_threads=8)
+    print(f"{preset} fp16: recall gpu {r_gpu:.4f} oracle {r_ref:.4f}; identical lists vs kernel-precision oracle "
+          f"{same_list_fraction(ids, kern['ids']):.3f}")
+
+
+def test_f16_rejections():
+    cfg = scaled(PRESETS["C2"], 2000, n_clusters=4, Q=8)
+    wl = _as_f16(make_workload(cfg))
+    g, m, dev = open_handles(wl)
+    with pytest.raises(ann.AnnError):     # the noise draw and the 8-bit quantiser take fp32 and bf16 arrays only
+        ann.ann_users_add_noise(dev["users"], 0.5, 1)
+    wl16 = make_workload(cfg)
+    g16, m16, dev16 = open_handles(wl16)
+    with pytest.raises(ann.AnnError):     # a bf16 metric over an fp16 table
+        ann.ann_search(g, m16, dev16["users"], dev["entries"], 2, 8, 5, 0)
