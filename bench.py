@@ -113,6 +113,7 @@ def main() -> int:
     ap.add_argument("--no-stream", action="store_true", help="skip the continuous-batching run beside the headline")
     ap.add_argument("--no-halves", action="store_true", help="skip the two-half-batches-at-once run beside the headline")
     ap.add_argument("--no-walkers", action="store_true", help="skip the walker-rule run beside the headline")
+    ap.add_argument("--no-f16", action="store_true", help="skip the fp16 metric run beside the headline")
     ap.add_argument("--no-f8", action="store_true", help="skip the 8-bit metric run (on C2) beside the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain 256 MiB copy kernel (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -425,6 +426,43 @@ def main() -> int:
             del ws2, g2, m2, emb2
         del wl2
 
+    # ---- the fp16 metric (IEEE binary16, the format Sec. 4.3 names) on this workload: the same kernels with the
+    #      other 16-bit MFMA; reported beside the headline, not part of the timed step ----
+    f16 = None
+    if not ragged and not args.no_f16 and cfg.dtype == "bf16":
+        import torch as _t
+        emb16, users16 = wl["emb"].to(_t.float16), users.to(_t.float16)
+        g16 = ann.ann_graph_load(wl["adj"], emb16)
+        m16 = ann.ann_mlp_load([w.to(_t.float16) for w in wl["W"]], wl["b"], wl["head_w"], cfg.d, ann.ANN_F16)
+        ws16 = torch.empty(ann.ann_search_workspace_bytes(g16, m16, Q, E, W, L_star, k, 0), dtype=torch.uint8,
+                           device="cuda:0")
+        run = lambda: ann.ann_search(g16, m16, users16, entries, W, L_star, k, 0, workspace=ws16)
+        run()
+        torch.cuda.synchronize()
+        t10 = time.perf_counter()
+        for _ in range(3):
+            ids16, _ = run()
+        torch.cuda.synchronize()
+        ms16 = 1e3 * (time.perf_counter() - t10) / 3
+        ann.ann_profile_enable(True)
+        ann.ann_profile_read()
+        run()
+        torch.cuda.synchronize()
+        prof16 = ann.ann_profile_read()
+        ann.ann_profile_enable(False)
+        st16 = ann.ann_search_stats(ws16)
+        fl16 = flops_per_pair(cfg.dims, cfg.d, hoisted=bool(ann.ann_mlp_uses_mfma(m16)))
+        f16 = {"L": L_star, "ms_per_search": round(ms16, 3), "queries_per_s": round(Q / ms16 * 1e3, 1),
+               "recall_at_100": round(recall_at(ids16[sel].cpu(), truth.cpu(), kr), 4),
+               "pairs_scored": int(st16.pairs_scored), "score_ms": round(prof16["score"][0], 3),
+               "score_TFLOPs": round(st16.pairs_scored * fl16 / (prof16["score"][0] * 1e-3) / 1e12, 1),
+               "mfma_kernel": bool(ann.ann_mlp_uses_mfma(m16)),
+               "note": "items, users and weights are the bf16 workload's converted to fp16; recall against the "
+                       "exhaustive ranking of the bf16 workload"}
+        log(f"fp16 metric on this workload: {ms16:.2f} ms per search, recall@{kr} = {f16['recall_at_100']}, "
+            f"scoring {prof16['score'][0]:.2f} ms")
+        del ws16, g16, m16, emb16, users16
+
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 255)
         dst = torch.empty_like(src)
@@ -538,7 +576,7 @@ def main() -> int:
             "pairs_scored_per_step": int(st.pairs_scored), "nodes_expanded_per_step": int(st.nodes_expanded),
             "rounds": int(st.max_query_iters), "mfma_kernel": bool(mfma), "stages": stages,
             "layered_search": layered, "continuous_batching": streamed, "concurrent_halves": halves,
-            "walker_search": walkers, "f8_metric": f8,
+            "walker_search": walkers, "f8_metric": f8, "f16_metric": f16,
         },
         "roofline": roofline,
         "cpu_baseline": cpu,

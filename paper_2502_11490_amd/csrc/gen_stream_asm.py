@@ -360,14 +360,20 @@ def step16_head():
 
 
 def c_string(lines):
-    return " \\\n    ".join('"' + l + '\\n\\t"' for l in lines)
+    """The lines as adjacent C string literals; the 16-bit format's name in the two mnemonics that carry it
+    (the MFMA and the packed conversion) is the macro argument T, "bf16" or "f16"."""
+    def lit(l):
+        for name in ("v_mfma_f32_32x32x16_bf16", "v_cvt_pk_bf16_f32"):
+            l = l.replace(name, name.replace("bf16", '" T "'))
+        return '"' + l + '\\n\\t"'
+    return " \\\n    ".join(lit(l) for l in lines)
 
 
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
     out = ["// Generated by gen_stream_asm.py -- do not edit; see that script for the register plan.", ""]
     for i in range(NB1 + 1):
-        out.append(f"#define STREAM_ASM_STEP_{i} \\\n    {c_string(step16_head() if i == NB1 else step(i))}")
+        out.append(f"#define STREAM_ASM_STEP_{i}(T) \\\n    {c_string(step16_head() if i == NB1 else step(i))}")
         out.append("")
     out.append(f"#define STREAM_ASM_INIT_ACC2 \\\n    {c_string(init_acc2())}")
     out.append("")

@@ -35,7 +35,12 @@
 
 namespace gmpgr {
 
+// Eight 16-bit operands of an MFMA.  The two 16-bit formats (bf16, and IEEE binary16 when the template flag
+// F16 is set) share every kernel: an operand is carried as bf16x8 whatever it holds, and only the three places
+// that look inside differ -- the MFMA instruction, the rounding of fresh hidden units, the widening of the
+// user vector and its weights for the per-query term.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -59,40 +64,62 @@ constexpr int MF_WAVES = 4;
 //     for the wide metric.)
 // One weight fragment against both column blocks of pairs.  LAST: the group ends here; the idle cycles that
 // let its MFMAs finish are part of the same statement, so that nothing can come between them.
-template <bool LAST>
+#define MFMA_PAIR_TEXT(T) "s_nop 1\n\tv_mfma_f32_32x32x16_" T " %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_" T " %1, %2, %4, %1"
+template <bool LAST, bool F16>
 __device__ __forceinline__ void mfma_vgpr_pair(f32x16 &acc0, f32x16 &acc1, const bf16x8 &a, const bf16x8 &b0,
                                                const bf16x8 &b1) {
-    if (LAST)
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %2, %4, %1\n\t"
-                     "s_nop 15\n\ts_nop 7"
-                     : "+v"(acc0), "+v"(acc1)
-                     : "v"(a), "v"(b0), "v"(b1));
+    if (LAST && F16)
+        asm volatile(MFMA_PAIR_TEXT("f16") "\n\ts_nop 15\n\ts_nop 7" : "+v"(acc0), "+v"(acc1) : "v"(a), "v"(b0), "v"(b1));
+    else if (LAST)
+        asm volatile(MFMA_PAIR_TEXT("bf16") "\n\ts_nop 15\n\ts_nop 7" : "+v"(acc0), "+v"(acc1) : "v"(a), "v"(b0), "v"(b1));
+    else if (F16)
+        asm volatile(MFMA_PAIR_TEXT("f16") : "+v"(acc0), "+v"(acc1) : "v"(a), "v"(b0), "v"(b1));
     else
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %2, %4, %1"
-                     : "+v"(acc0), "+v"(acc1)
-                     : "v"(a), "v"(b0), "v"(b1));
+        asm volatile(MFMA_PAIR_TEXT("bf16") : "+v"(acc0), "+v"(acc1) : "v"(a), "v"(b0), "v"(b1));
+}
+#undef MFMA_PAIR_TEXT
+
+// acc += A * B with the accumulator where the compiler puts it (the accumulation registers)
+template <bool F16>
+__device__ __forceinline__ f32x16 mfma16(const bf16x8 &a, const bf16x8 &b, const f32x16 &acc) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
 }
 
+// ReLU and rounding (nearest even) of half a tile of fresh hidden units to the metric's 16-bit format
+template <bool F16>
 __device__ __forceinline__ bf16x8 relu_pack(const f32x16 &acc, int half) {
     f32x8 v;
 #pragma unroll
     for (int j = 0; j < 8; ++j) v[j] = fmaxf(acc[half * 8 + j], 0.f);
-    return __builtin_convertvector(v, bf16x8);
+    if constexpr (F16)
+        return __builtin_bit_cast(bf16x8, __builtin_convertvector(v, f16x8));
+    else
+        return __builtin_convertvector(v, bf16x8);
+}
+
+template <bool F16>
+__device__ __forceinline__ float widen16(uint16_t bits) {
+    if constexpr (F16) return (float)__builtin_bit_cast(_Float16, bits);
+    else return __uint_as_float(((uint32_t)bits) << 16);
 }
 
 // upre[q][n] = b1[n] + sum_{i < d_user} W1[n][i] * u_q[i]   (fp32 FMA chain in index order)
+template <bool F16>
 __global__ void __launch_bounds__(256)
 user_pre_kernel(const uint16_t *__restrict__ W1, int n_in, int d_user, int H1, const float *__restrict__ b1,
                 const uint16_t *__restrict__ users, int Q, float *__restrict__ upre, float out_scale) {
     extern __shared__ float u_s[];
     const int q = blockIdx.x;
     for (int i = threadIdx.x; i < d_user; i += blockDim.x)
-        u_s[i] = __uint_as_float(((uint32_t)users[(size_t)q * d_user + i]) << 16);
+        u_s[i] = widen16<F16>(users[(size_t)q * d_user + i]);
     __syncthreads();
     for (int n = threadIdx.x; n < H1; n += blockDim.x) {
         float acc = b1[n];
         const uint16_t *row = W1 + (size_t)n * n_in;
-        for (int i = 0; i < d_user; ++i) acc = fmaf(__uint_as_float(((uint32_t)row[i]) << 16), u_s[i], acc);
+        for (int i = 0; i < d_user; ++i) acc = fmaf(widen16<F16>(row[i]), u_s[i], acc);
         upre[(size_t)q * H1 + n] = acc * out_scale;  // a power of two (1 for the bf16 kernels): exact
     }
 }
@@ -103,7 +130,7 @@ user_pre_kernel(const uint16_t *__restrict__ W1, int n_in, int d_user, int H1, c
 //     [D/16 + 2*n2 + s2]    lane (m,g): W2[n2*32+m][nb*32 + 16*s2 + 8*(j/4) + 4g + j%4], j < 8
 //   then the head layer, H2/16 fragments, rows >= J are zero:
 //     [2*n2 + s2]           lane (m,g): W3[m][n2*32 + 16*s2 + 8*(j/4) + 4g + j%4]
-template <int D, int H1, int H2, int CB, bool RESIDENT, int WAVES>
+template <int D, int H1, int H2, int CB, bool RESIDENT, int WAVES, bool F16>
 __global__ void __launch_bounds__(64 * WAVES)
 mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__restrict__ upre,
                  const uint4 *__restrict__ frag, const float *__restrict__ b2, const float *__restrict__ b3,
@@ -238,14 +265,14 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
             for (int s = 0; s < KS1; ++s) {
                 bf16x8 a = *(const bf16x8 *)(wc + s * 64 + lane);
                 static_assert(CB == 2, "pairs 0 and 1 alternate");
-                if (s == KS1 - 1) mfma_vgpr_pair<true>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
-                else mfma_vgpr_pair<false>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
+                if (s == KS1 - 1) mfma_vgpr_pair<true, F16>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
+                else mfma_vgpr_pair<false, F16>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
             }
             bf16x8 hf[CB][2];
 #pragma unroll
             for (int c = 0; c < CB; ++c) {
-                hf[c][0] = relu_pack(acc1[c], 0);
-                hf[c][1] = relu_pack(acc1[c], 1);
+                hf[c][0] = relu_pack<F16>(acc1[c], 0);
+                hf[c][1] = relu_pack<F16>(acc1[c], 1);
             }
             // layer 2: every output unit consumes these 32 hidden units
 #pragma unroll
@@ -255,7 +282,7 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
                     bf16x8 a = *(const bf16x8 *)(wc + (KS1 + 2 * n2 + s2) * 64 + lane);
 #pragma unroll
                     for (int c = 0; c < CB; ++c)
-                        acc2[n2][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, hf[c][s2], acc2[n2][c], 0, 0, 0);
+                        acc2[n2][c] = mfma16<F16>(a, hf[c][s2], acc2[n2][c]);
                 }
             }
             if (!RESIDENT) {
@@ -284,9 +311,9 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
                 bf16x8 a = *(const bf16x8 *)(w3buf + (2 * n2 + s2) * 64 + lane);
-                const bf16x8 h0 = relu_pack(acc2[n2][0], s2), h1 = relu_pack(acc2[n2][1], s2);
-                if (n2 == NB2 - 1 && s2 == 1) mfma_vgpr_pair<true>(acc3[0], acc3[1], a, h0, h1);
-                else mfma_vgpr_pair<false>(acc3[0], acc3[1], a, h0, h1);
+                const bf16x8 h0 = relu_pack<F16>(acc2[n2][0], s2), h1 = relu_pack<F16>(acc2[n2][1], s2);
+                if (n2 == NB2 - 1 && s2 == 1) mfma_vgpr_pair<true, F16>(acc3[0], acc3[1], a, h0, h1);
+                else mfma_vgpr_pair<false, F16>(acc3[0], acc3[1], a, h0, h1);
             }
         }
 #pragma unroll
@@ -310,7 +337,7 @@ mlp_mfma2_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
 // three workgroups share a CU and hide each other's gather latency.
 // Fragment order: block nb: [s < D/16] W1_item as above; [D/16 + s2] lane (m,g):
 // W_head[m][nb*32 + 16*s2 + 8*(j/4) + 4g + j%4], rows >= J zero.
-template <int D, int H1, int CB>
+template <int D, int H1, int CB, bool F16>
 __global__ void __launch_bounds__(MF_BLOCK)
 mlp_mfma1_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__restrict__ upre,
                  const uint4 *__restrict__ frag, const float *__restrict__ b_head, const float *__restrict__ head_w,
@@ -380,15 +407,15 @@ mlp_mfma1_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
             for (int s = 0; s < KS1; ++s) {
                 bf16x8 a = *(const bf16x8 *)(wc + s * 64 + lane);
                 static_assert(CB == 2, "pairs 0 and 1 alternate");
-                if (s == KS1 - 1) mfma_vgpr_pair<true>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
-                else mfma_vgpr_pair<false>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
+                if (s == KS1 - 1) mfma_vgpr_pair<true, F16>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
+                else mfma_vgpr_pair<false, F16>(acc1[0], acc1[1], a, xf[0][s], xf[1][s]);
             }
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
                 bf16x8 a = *(const bf16x8 *)(wc + (KS1 + s2) * 64 + lane);
-                const bf16x8 h0 = relu_pack(acc1[0], s2), h1 = relu_pack(acc1[1], s2);
-                if (nb == NB1 - 1 && s2 == 1) mfma_vgpr_pair<true>(acc3[0], acc3[1], a, h0, h1);
-                else mfma_vgpr_pair<false>(acc3[0], acc3[1], a, h0, h1);
+                const bf16x8 h0 = relu_pack<F16>(acc1[0], s2), h1 = relu_pack<F16>(acc1[1], s2);
+                if (nb == NB1 - 1 && s2 == 1) mfma_vgpr_pair<true, F16>(acc3[0], acc3[1], a, h0, h1);
+                else mfma_vgpr_pair<false, F16>(acc3[0], acc3[1], a, h0, h1);
             }
         }
 #pragma unroll
@@ -405,7 +432,7 @@ mlp_mfma1_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__res
 
 
 bool mfma_supported(const int32_t *dims, int32_t n_layers, int32_t d_user, int32_t dtype) {
-    if (dtype != ANN_BF16 || d_user < 1 || (n_layers != 2 && n_layers != 3)) return false;
+    if ((dtype != ANN_BF16 && dtype != ANN_F16) || d_user < 1 || (n_layers != 2 && n_layers != 3)) return false;
     const int D = dims[0] - d_user, H1 = dims[1], J = dims[n_layers];
     if (J < 1 || J > MAX_HEADS) return false;
     if (n_layers == 2) return D == 64 && H1 == 256;
@@ -485,14 +512,15 @@ int build_mfma_fragments(ann_mlp *m, const void *const *W_host, hipStream_t stre
 
 int launch_user_pre(const ann_mlp *m, const void *queries, int32_t Q, float *upre, hipStream_t stream) {
     if (Q <= 0) return ANN_OK;
-    hipLaunchKernelGGL(user_pre_kernel, dim3(Q), dim3(256), (size_t)m->d_user * sizeof(float), stream,
+    auto fn = m->dtype == ANN_F16 ? user_pre_kernel<true> : user_pre_kernel<false>;
+    hipLaunchKernelGGL(fn, dim3(Q), dim3(256), (size_t)m->d_user * sizeof(float), stream,
                        (const uint16_t *)m->W_dev, m->dims[0], m->d_user, m->dims[1], m->b_dev,
                        (const uint16_t *)queries, Q, upre, m->dtype == ANN_F8 ? 4.f : 1.f);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
 
-template <int D, int H1, int H2, int CB, bool RESIDENT, int WAVES>
+template <int D, int H1, int H2, int CB, bool RESIDENT, int WAVES, bool F16>
 static int launch_one(const ann_graph *g, const ann_mlp *m, const float *upre, const int32_t *pair_q,
                       const int32_t *pair_id, const int32_t *M_dev, int64_t M_max, int32_t Q, float *scores,
                       hipStream_t stream) {
@@ -502,7 +530,7 @@ static int launch_one(const ann_graph *g, const ann_mlp *m, const float *upre, c
     constexpr size_t smem = ((size_t)NBUF * CHUNK_U4 + 2 * NB2 * 64) * 16;
     constexpr int TILE = 32 * CB * WAVES;
     static_assert(smem <= 160 * 1024, "LDS budget");
-    auto fn = mlp_mfma2_kernel<D, H1, H2, CB, RESIDENT, WAVES>;
+    auto fn = mlp_mfma2_kernel<D, H1, H2, CB, RESIDENT, WAVES, F16>;
     static std::atomic<uint32_t> raised;
     if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised); rc != ANN_OK) return rc;
     int64_t tiles = (M_max + TILE - 1) / TILE;
@@ -525,9 +553,10 @@ int launch_mlp_mfma(const ann_graph *g, const ann_mlp *m, const float *upre, con
     if (m->n_layers == 2 && D == 64 && H1 == 256) {
         constexpr int CB = 2, TILE = 32 * CB * MF_WAVES;
         constexpr size_t smem = (size_t)(256 / 32) * (64 / 16 + 2) * 64 * 16;  // 48 KB: three workgroups per CU
-        auto fn = mlp_mfma1_kernel<64, 256, CB>;
-        static std::atomic<uint32_t> raised;
-        if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised); rc != ANN_OK) return rc;
+        const bool f16 = m->dtype == ANN_F16;
+        auto fn = f16 ? mlp_mfma1_kernel<64, 256, CB, true> : mlp_mfma1_kernel<64, 256, CB, false>;
+        static std::atomic<uint32_t> raised[2];
+        if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised[f16 ? 1 : 0]); rc != ANN_OK) return rc;
         int64_t tiles = (M_max + TILE - 1) / TILE;
         int grid = (int)(tiles < 3 * 256 ? tiles : 3 * 256);
         hipLaunchKernelGGL(fn, dim3(grid), dim3(MF_BLOCK), smem, stream, (const uint16_t *)g->emb, g->N, upre,
@@ -539,7 +568,9 @@ int launch_mlp_mfma(const ann_graph *g, const ann_mlp *m, const float *upre, con
     if (mfma_stream_supported(D, H1, H2))
         return launch_mlp_mfma_stream(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
     if (D == 64 && H1 == 256 && H2 == 128)
-        return launch_one<64, 256, 128, 2, true, 8>(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
+        return m->dtype == ANN_F16
+                   ? launch_one<64, 256, 128, 2, true, 8, true>(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream)
+                   : launch_one<64, 256, 128, 2, true, 8, false>(g, m, upre, pair_q, pair_id, M_dev, M_max, Q, scores, stream);
     set_error("no MFMA kernel for item width %d, hidden %d, %d", D, H1, H2);
     return ANN_ENOTIMPL;
 }

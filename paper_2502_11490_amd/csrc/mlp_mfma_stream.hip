@@ -106,7 +106,9 @@ __device__ __forceinline__ void lds_load4_b128(uint32_t addr, u32x4 &r0, u32x4 &
 //   chunk i, fragment s < 8       lane (m,g): W1_item[32i+m][16s + 8g + j]                      (zero for i = NB1)
 //   chunk i, fragment 8+2*n2+s2   lane (m,g): W2[32*n2+m][32(i-1) + 16*s2 + 8*(j/4) + 4g + j%4] (zero for i = 0)
 // then 16 head fragments [2*n2+s2], lane (m,g): W3[m][32*n2 + 16*s2 + 8*(j/4) + 4g + j%4], rows m >= J zero.
-template <int H1>
+// F16: items, weights and hidden units are IEEE binary16 instead of bf16 (the operands travel as the same
+// 16-byte tuples; the two mnemonics that name the format are a parameter of the step texts).
+template <int H1, bool F16>
 __global__ void __launch_bounds__(ST_BLOCK)
 mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float *__restrict__ upre,
                         const uint4 *__restrict__ frag, const float *__restrict__ b2, const float *__restrict__ b3,
@@ -275,22 +277,27 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
     [wcs] "s"(wsv[(i) % NBUF]), [wcsn] "s"(wsv[((i) + 1) % NBUF]), [lb] "s"(lbv[((i) + 2) % NBUF]), [vo] "v"(tid16)
 #define STEP_LOADS [up0] "v"(up[0]), [up1] "v"(up[1]), [xs] "v"(xs)
         // odd step: layer 1 into set B, layer 2 over the hidden units of set A; fetches into set A
+#define STREAM_STMT(TEXT, ...)                                \
+    do {                                                      \
+        if constexpr (F16) asm volatile(TEXT("f16") __VA_ARGS__); \
+        else asm volatile(TEXT("bf16") __VA_ARGS__);          \
+    } while (0)
 #define STEP_ODD(i)                                                                                   \
-    asm volatile(STREAM_ASM_STEP_##i                                                                  \
+    STREAM_STMT(STREAM_ASM_STEP_##i,                                                                  \
                  : STREAM_ACC_B(accB0, accB1), STREAM_ACC_OUT_A(accA0, accA1), STREAM_SB(sbv),        \
                    STREAM_HF_OUT_B(hB00, hB01, hB10, hB11), FRAG_TEMPS, [xpn] "=&v"(xpB)              \
                  : STEP_COMMON(i), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), STEP_LOADS, \
                    [xpo] "v"(xpA), [xw] "v"(xw_addr)                                                  \
                  : "memory", "scc", STREAM_ACC2_CLOBBERS);
 #define STEP_EVEN(i)                                                                                  \
-    asm volatile(STREAM_ASM_STEP_##i                                                                  \
+    STREAM_STMT(STREAM_ASM_STEP_##i,                                                                  \
                  : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1), STREAM_SB(sbv),        \
                    STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), FRAG_TEMPS, [xpn] "=&v"(xpA)              \
                  : STEP_COMMON(i), X_OPERANDS, STREAM_HF_IN_B(hB00, hB01, hB10, hB11), STEP_LOADS, \
                    [xpo] "v"(xpB), [xw] "v"(xw_addr)                                                  \
                  : "memory", "scc", STREAM_ACC2_CLOBBERS);
         // step 0: layer 1 only
-        asm volatile(STREAM_ASM_STEP_0
+        STREAM_STMT(STREAM_ASM_STEP_0,
                      : STREAM_ACC_A(accA0, accA1), STREAM_ACC_OUT_B(accB0, accB1), STREAM_SB(sbv),
                        STREAM_HF_OUT_A(hA00, hA01, hA10, hA11), FRAG_TEMPS, [xpn] "=&v"(xpA)
                      : STEP_COMMON(0), X_OPERANDS, STEP_LOADS
@@ -299,7 +306,7 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         xs = emb + nxt_off[1];  // steps 8..15 fetch the row of pair c = 1
         STEP_EVEN(8) STEP_ODD(9) STEP_EVEN(10) STEP_ODD(11) STEP_EVEN(12) STEP_ODD(13) STEP_EVEN(14)
         sbv = (const char *)frag;  // steps 15 and 16 fetch chunks 0 and 1 again
-        asm volatile(STREAM_ASM_STEP_15   // the last layer-1 block: no user term to fetch
+        STREAM_STMT(STREAM_ASM_STEP_15,   // the last layer-1 block: no user term to fetch
                      : STREAM_ACC_B(accB0, accB1), STREAM_SB(sbv), STREAM_HF_OUT_B(hB00, hB01, hB10, hB11),
                        FRAG_TEMPS, [xpn] "=&v"(xpB)
                      : STEP_COMMON(15), X_OPERANDS, STREAM_HF_IN_A(hA00, hA01, hA10, hA11), [xs] "v"(xs),
@@ -316,7 +323,7 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
             asm volatile("" : "+v"(h16));
             const uint32_t w3_addr = (uint32_t)(uintptr_t)w3buf + (h16 & 1023);  // 16 bytes * lane
             u32x4 w30, w31, w32, w33;  // head fragments in flight from LDS
-            asm volatile(STREAM_ASM_STEP_16
+            STREAM_STMT(STREAM_ASM_STEP_16,
                          : FRAG_TEMPS, STREAM_SB(sbv), STREAM_ACC3(acc3[0], acc3[1]),
                            [w30] "=&v"(w30), [w31] "=&v"(w31), [w32] "=&v"(w32), [w33] "=&v"(w33)
                          : STEP_COMMON(16), STREAM_HF_IN_B(hB00, hB01, hB10, hB11), [xpo] "v"(xpB), [xw] "v"(xw_addr),
@@ -324,6 +331,7 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
                          : "memory", "scc", STREAM_HEAD_CLOBBERS, STREAM_ACC2_CLOBBERS);
         }
 #undef STEP_ODD
+#undef STREAM_STMT
 #undef STEP_EVEN
 #undef STEP_LOADS
 #undef STEP_COMMON
@@ -420,9 +428,10 @@ int launch_mlp_mfma_stream(const ann_graph *g, const ann_mlp *m, const float *up
     constexpr int H1 = 512;
     constexpr size_t smem = ((size_t)3 * 24 * 64 + 16 * 64 + 4 * 16 * 64) * 16 + (256 + 32) * 4;  // 72 + 16 + 64 + 1 KB (+ head constants)
     constexpr int TILE = 256;
-    auto fn = mlp_mfma2_stream_kernel<H1>;
-    static std::atomic<uint32_t> raised;
-    if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised); rc != ANN_OK) return rc;
+    const bool f16 = m->dtype == ANN_F16;
+    auto fn = f16 ? mlp_mfma2_stream_kernel<H1, true> : mlp_mfma2_stream_kernel<H1, false>;
+    static std::atomic<uint32_t> raised[2];
+    if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised[f16 ? 1 : 0]); rc != ANN_OK) return rc;
     int64_t tiles = (M_max + TILE - 1) / TILE;
     int grid = (int)(tiles < 256 ? tiles : 256);
     const float *b2 = m->b_dev + m->b_off[1], *b3 = m->b_dev + m->b_off[2];

@@ -37,12 +37,13 @@ def _structure(ids, sc, N):
     return ids, sc
 
 
-def _sample_check(wl, cfg, ids, sc, q_sel, W, L, cap, k, recall_k):
+def _sample_check(wl, cfg, ids, sc, q_sel, W, L, cap, k, recall_k, act_round=1):
     h = to_host({n: wl[n] for n in ("emb", "adj", "W", "b", "head_w")})
     hu = to_host({"users": wl["users"][q_sel], "entries": wl["entries"][q_sel]})
     mlp = oracle.Mlp(h["W"], h["b"], h["head_w"])
     ref = oracle.search(h["emb"], h["adj"], hu["users"], mlp, hu["entries"], W, L, k, cap, n_threads=16)
-    kern = oracle.search(h["emb"], h["adj"], hu["users"], mlp, hu["entries"], W, L, k, cap, act_round=1, n_threads=16)
+    kern = oracle.search(h["emb"], h["adj"], hu["users"], mlp, hu["entries"], W, L, k, cap, act_round=act_round,
+                         n_threads=16)
     got_ids, got_sc = ids[q_sel], sc[q_sel]
     # (b) relevance of what was returned
     qq = np.repeat(np.arange(len(q_sel)), k).astype(np.int32)
@@ -81,6 +82,26 @@ def test_full_size_uniform(preset, n_sample):
     ids, sc = _structure(ids, sc, cfg.N)
     q_sel = np.sort(np.random.default_rng(5).choice(cfg.Q, n_sample, replace=False))
     _sample_check(wl, cfg, ids, sc, q_sel, cfg.W, cfg.L, 0, cfg.k, min(100, cfg.k))
+
+
+def test_full_size_f16():
+    """The fp16 metric on the headline workload at full size (items, users and weights converted to binary16)."""
+    cfg = PRESETS["C3"]
+    torch.cuda.empty_cache()
+    wl = make_workload(cfg, device="cuda:0")
+    wl["emb"], wl["users"] = wl["emb"].to(torch.float16), wl["users"].to(torch.float16)
+    wl["W"] = [w.to(torch.float16) for w in wl["W"]]
+    g = ann.ann_graph_load(wl["adj"], wl["emb"], ann.ANN_VALIDATE)
+    m = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, ann.ANN_F16)
+    assert ann.ann_mlp_uses_mfma(m)
+    ws = torch.empty(ann.ann_search_workspace_bytes(g, m, cfg.Q, cfg.E, cfg.W, cfg.L, cfg.k, 0), dtype=torch.uint8,
+                     device="cuda:0")
+    ids, sc = ann.ann_search(g, m, wl["users"], wl["entries"], cfg.W, cfg.L, cfg.k, 0, workspace=ws)
+    st = ann.ann_search_stats(ws)
+    assert st.visited_overflow == 0 and st.queries == cfg.Q
+    ids, sc = _structure(ids, sc, cfg.N)
+    q_sel = np.sort(np.random.default_rng(9).choice(cfg.Q, 96, replace=False))
+    _sample_check(wl, cfg, ids, sc, q_sel, cfg.W, cfg.L, 0, cfg.k, min(100, cfg.k), act_round=3)
 
 
 def test_full_size_ragged():
