@@ -116,6 +116,31 @@ __device__ void bitonic_sort(uint64_t *keys, int n) {
     __syncthreads();
 }
 
+// Sorts keys[0..m), 1 <= m <= BLK, ascending, by counting: the keys are distinct, so the rank of a key is the
+// number of smaller ones.  The count for key j is shared by BLK / m_pad threads (m_pad: m rounded up to a power
+// of two), each over its share of the keys, which a wave reads as LDS broadcasts, one after the other without
+// waiting; the shares meet in an LDS counter.  Three barriers and m * m_pad / BLK independent reads per
+// thread, where the bitonic network makes log2(m)^2 / 2 dependent trips to the LDS with most threads idle.
+//   cnt : LDS uint32[m_pad], any contents.   All threads of the workgroup call; ends with a barrier.
+template <int BLK>
+__device__ void rank_sort(uint64_t *keys, int m, uint32_t *cnt) {
+    int shift = 0;
+    while ((1 << shift) < m) ++shift;
+    const int m_pad = 1 << shift, groups = BLK >> shift;
+    const int j = threadIdx.x & (m_pad - 1), part = threadIdx.x >> shift;
+    if ((int)threadIdx.x < m_pad) cnt[threadIdx.x] = 0;
+    __syncthreads();  // the keys are all written, the counters are zero
+    const uint64_t key = j < m ? keys[j] : 0;
+    const int per = (m + groups - 1) / groups;
+    const int i0 = part * per, i1 = min(m, i0 + per);
+    uint32_t smaller = 0;
+    for (int i = i0; i < i1; ++i) smaller += keys[i] < key ? 1u : 0u;
+    if (j < m && smaller) atomicAdd(&cnt[j], smaller);
+    __syncthreads();  // every count is complete and nobody reads the unsorted keys any more
+    if (part == 0 && j < m) keys[cnt[j]] = key;
+    __syncthreads();
+}
+
 // Drops ids that are out of range, repeated inside cand[0..n_cand) (first occurrence kept)
 // or already in this query's visited table; inserts the rest into the table and writes them,
 // in their order of occurrence, to out[0..n_new).  Returns n_new (same in every thread).
@@ -584,9 +609,13 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     if (m > 0) {
         int m2 = 2;
         while (m2 < m) m2 <<= 1;
-        for (int i = m + threadIdx.x; i < m2; i += BLK) newk[i] = KEY_SENTINEL;
-        __syncthreads();
-        bitonic_sort<BLK>(newk, m2);
+        if (m <= BLK && 2 * C >= m2) {
+            rank_sort<BLK>(newk, m, (uint32_t *)keys);  // the merged list's buffer is free until the merge below
+        } else {
+            for (int i = m + threadIdx.x; i < m2; i += BLK) newk[i] = KEY_SENTINEL;
+            __syncthreads();
+            bitonic_sort<BLK>(newk, m2);
+        }
         PHASE_MARK(6);  // sort of the new keys
         for (int i = threadIdx.x; i < st.n_list + m; i += BLK) {
             uint64_t key;
