@@ -100,7 +100,7 @@ void ann_graph_free(ann_graph *g);
  * logits, sigmoid and the weighted sum stay in fp32 (the 16-bit deployment of Sec. 4.3).
  * dtype = ANN_F16 is the same with IEEE binary16 in place of bf16 (the format Sec. 4.3 names): items,
  * users and weights are fp16, hidden activations are rounded to fp16 (nearest even) after the ReLU.
- * ann_users_add_noise and ann_quantize_e4m3 do not take fp16 arrays.
+ * ann_quantize_e4m3 does not take fp16 arrays.
  */
 int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *W_host,
                  const float *const *b_host, const float *head_w_host, int32_t d_user,
@@ -243,9 +243,9 @@ int ann_search_stream(const ann_graph *g, const ann_mlp *m, const void *queries_
  * z is a pure function of its arguments (so the same vectors can be drawn again, anywhere):
  * Philox4x32-10 with counter (e / 4, draw) and key seed, uniforms (x + 1/2) / 2^32, Box-Muller on
  * the word pairs (0,1) and (2,3) with the cosine on the even element; the sum is formed in fp64 and
- * rounded to fp32 (then to bf16, nearest even, for ANN_BF16).  `draw` tells independent draws with
+ * rounded to fp32 (then to bf16 or fp16, nearest even, for ANN_BF16 / ANN_F16).  `draw` tells independent draws with
  * one seed apart (one per batch of requests, say).
- *   users_dev, out_dev : [Q][d] device arrays of `dtype` (ANN_F32 / ANN_BF16); may be the same array
+ *   users_dev, out_dev : [Q][d] device arrays of `dtype` (ANN_F32 / ANN_BF16 / ANN_F16); may be the same array
  * Only enqueues one kernel on `stream`; ANN_EINVAL on bad arguments (Q < 0, d < 1, negative or
  * non-finite sigma, null arrays with Q > 0).
  */

@@ -264,7 +264,11 @@ def noise_element(seed: int, stream: int, e: int) -> float:
 def users_add_noise(users: np.ndarray, sigma: float, seed: int, stream: int = 0) -> np.ndarray:
     """users + sigma * h~ with h~ ~ N(0, I) (Eq. 5: the serendipity vector added to the user half of the
     metric input), drawn by the counter-based generator described in gmp_oracle.c; same dtype as `users`
-    (fp32, or bf16 bit patterns as uint16)."""
+    (fp32, bf16 bit patterns as uint16, or fp16: the fp64 sum rounded to fp32 and then to binary16)."""
+    if users.dtype == np.float16:
+        wide = users_add_noise(users.astype(np.float32), sigma, seed, stream)
+        with np.errstate(over="ignore"):
+            return f16_round(wide).astype(np.float16)
     users, dt = _table(users)
     out = np.empty_like(users)
     rc = _load().oracle_users_add_noise(_ptr(users), dt, ctypes.c_int64(users.shape[0]), int(users.shape[1]),

@@ -842,8 +842,9 @@ int ann_search_stream(const ann_graph *g, const ann_mlp *m, const void *queries_
 
 int ann_users_add_noise(const void *users_dev, void *out_dev, int32_t Q, int32_t d, int32_t dtype, double sigma,
                         uint64_t seed, uint64_t draw, void *stream) {
-    if (Q < 0 || d < 1 || (dtype != ANN_F32 && dtype != ANN_BF16) || !(sigma >= 0.0) || !(sigma < INFINITY)) {
-        set_error("need Q >= 0, d >= 1, dtype ANN_F32 or ANN_BF16, finite sigma >= 0");
+    if (Q < 0 || d < 1 || (dtype != ANN_F32 && dtype != ANN_BF16 && dtype != ANN_F16) || !(sigma >= 0.0) ||
+        !(sigma < INFINITY)) {
+        set_error("need Q >= 0, d >= 1, dtype ANN_F32, ANN_BF16 or ANN_F16, finite sigma >= 0");
         return ANN_EINVAL;
     }
     if (Q == 0) return ANN_OK;

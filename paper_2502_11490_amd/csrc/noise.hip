@@ -37,7 +37,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
-template <bool BF16>
+// KIND: the library's dtype code of the array (ANN_F32, ANN_BF16, ANN_F16)
+template <int KIND>
 __global__ void __launch_bounds__(256)
 users_add_noise_kernel(const void *__restrict__ users, void *__restrict__ out, int64_t n_elem, double sigma,
                        uint64_t seed, uint64_t stream_id) {
@@ -60,9 +61,16 @@ users_add_noise_kernel(const void *__restrict__ users, void *__restrict__ out, i
     for (int t = 0; t < 4; ++t) {
         const int64_t e = e0 + t;
         if (e >= n_elem) break;
-        if (BF16) {
+        if (KIND == ANN_BF16) {
             const float u = __uint_as_float((uint32_t)((const uint16_t *)users)[e] << 16);
             ((uint16_t *)out)[e] = f32_to_bf16_rne((float)((double)u + sigma * z[t]));
+        } else if (KIND == ANN_F16) {
+            const float u = (float)((const _Float16 *)users)[e];
+            // fp64 -> fp32 -> binary16 as two roundings, like the bf16 branch (the empty statement keeps the compiler
+            // from rounding the fp64 sum to binary16 in one step, which differs on the fp32 values that are ties)
+            float f = (float)((double)u + sigma * z[t]);
+            asm volatile("" : "+v"(f));
+            ((_Float16 *)out)[e] = (_Float16)f;
         } else {
             ((float *)out)[e] = (float)((double)((const float *)users)[e] + sigma * z[t]);
         }
@@ -74,12 +82,10 @@ int launch_users_add_noise(const void *users, void *out, int64_t n_elem, int dty
     if (n_elem == 0) return ANN_OK;
     const int64_t blocks4 = (n_elem + 3) / 4;
     const unsigned grid = (unsigned)((blocks4 + 255) / 256);
-    if (dtype == ANN_BF16)
-        hipLaunchKernelGGL(users_add_noise_kernel<true>, dim3(grid), dim3(256), 0, stream, users, out, n_elem, sigma,
-                           seed, stream_id);
-    else
-        hipLaunchKernelGGL(users_add_noise_kernel<false>, dim3(grid), dim3(256), 0, stream, users, out, n_elem, sigma,
-                           seed, stream_id);
+    auto fn = dtype == ANN_BF16  ? users_add_noise_kernel<ANN_BF16>
+              : dtype == ANN_F16 ? users_add_noise_kernel<ANN_F16>
+                                 : users_add_noise_kernel<ANN_F32>;
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(256), 0, stream, users, out, n_elem, sigma, seed, stream_id);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }

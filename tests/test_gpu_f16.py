@@ -89,8 +89,8 @@ def test_f16_rejections():
     cfg = scaled(PRESETS["C2"], 2000, n_clusters=4, Q=8)
     wl = _as_f16(make_workload(cfg))
     g, m, dev = open_handles(wl)
-    with pytest.raises(ann.AnnError):     # the noise draw and the 8-bit quantiser take fp32 and bf16 arrays only
-        ann.ann_users_add_noise(dev["users"], 0.5, 1)
+    with pytest.raises((ann.AnnError, TypeError, ValueError)):   # the 8-bit quantiser takes fp32 and bf16 arrays only
+        ann.ann_quantize_e4m3(dev["emb"])
     wl16 = make_workload(cfg)
     g16, m16, dev16 = open_handles(wl16)
     with pytest.raises(ann.AnnError):     # a bf16 metric over an fp16 table

@@ -40,6 +40,16 @@ def test_noise_bf16_matches_oracle():
     assert np.abs(got.astype(np.int32) - want.astype(np.int32)).max() <= 1
 
 
+def test_noise_f16_matches_oracle():
+    rng = np.random.default_rng(4)
+    u = torch.from_numpy(rng.standard_normal((4096, 128)).astype(np.float32)).to(torch.float16)
+    got = ann.ann_users_add_noise(u.cuda(), 1.0, 5, 9).cpu().numpy()
+    want = oracle.users_add_noise(u.numpy(), 1.0, 5, 9)
+    assert got.dtype == np.float16 and want.dtype == np.float16
+    gb, wb = got.view(np.uint16).astype(np.int32), want.view(np.uint16).astype(np.int32)
+    assert (gb != wb).sum() <= 2 and np.abs(gb - wb).max() <= 1
+
+
 def test_noise_in_place_zero_sigma_empty_and_errors():
     u = torch.randn(33, 7, device="cuda")
     keep = u.clone()

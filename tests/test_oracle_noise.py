@@ -85,3 +85,12 @@ def test_bf16_output_is_the_rounded_sum():
     want = torch.from_numpy(ub.to(torch.float64).numpy() + 0.5 * z).to(torch.float32).to(torch.bfloat16)
     got = oracle.users_add_noise(bits, 0.5, 21, 0)
     assert np.array_equal(got, want.view(torch.int16).numpy().view(np.uint16))
+
+
+def test_fp16_arrays_get_the_fp32_result_rounded_to_binary16():
+    rng = np.random.default_rng(11)
+    u = rng.standard_normal((50, 12)).astype(np.float16)
+    out = oracle.users_add_noise(u, 0.7, 3, 2)
+    wide = oracle.users_add_noise(u.astype(np.float32), 0.7, 3, 2)
+    assert out.dtype == np.float16 and np.array_equal(out, wide.astype(np.float16))   # numpy's conversion
+    assert np.array_equal(oracle.users_add_noise(u, 0.0, 3, 2), u)
