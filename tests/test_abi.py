@@ -117,3 +117,15 @@ def test_stream_kernel_keeps_accumulation_registers_to_its_assembly(tmp_path):
                 outside.append(line.strip())
     assert statements >= 18          # the 17 steps and the bias statement were found
     assert not outside, outside[:5]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The library runs on one GPU; the benchmark says so instead of launching anything."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr or "--gpus 1" in r.stderr
+    assert not r.stdout.strip()
