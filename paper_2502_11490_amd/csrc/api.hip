@@ -5,7 +5,6 @@
 #include <stdio.h>
 #include <string.h>
 
-#include <chrono>
 #include <new>
 #include <vector>
 
@@ -157,20 +156,26 @@ struct Mailbox {
         const uint64_t w = host[1];
         return (w >> 40) == (tag >> 40) ? (int64_t)(w & 0xFFFFFFFFull) : -1;
     }
-    // Before enqueuing round `i` (0-based): 1 = the search has finished, 0 = go on, -1 = the device made no
-    // progress for a long time.
-    int gate(uint64_t tag, int64_t i) const {
-        const auto t0 = std::chrono::steady_clock::now();
+    // Before enqueuing round `i` (0-based): 1 = the search has finished, 0 = go on, -1 = the stream reports an
+    // error, or has run everything enqueued so far without the progress the kernels would have reported.
+    // While waiting, the stream is asked now and then: a search enqueued behind long work of the caller's waits
+    // as long as that takes, and a failed device ends the wait.
+    int gate(uint64_t tag, int64_t i, hipStream_t stream) const {
+        auto enough = [&](uint64_t w) {
+            if ((w >> 40) != (tag >> 40)) return i <= AHEAD ? 0 : -2;  // nothing reported yet
+            if (w & 1ull) return 1;
+            return (int64_t)((w & 0xFFFFFFFFFFull) >> 1) + AHEAD >= i ? 0 : -2;
+        };
         for (int spin = 0;; ++spin) {
-            const uint64_t w = *host;
-            if ((w >> 40) == (tag >> 40)) {
-                if (w & 1ull) return 1;
-                if ((int64_t)((w & 0xFFFFFFFFFFull) >> 1) + AHEAD >= i) return 0;
-            } else if (i <= AHEAD) {
-                return 0;  // nothing reported yet
+            int r = enough(*host);
+            if (r != -2) return r;
+            if ((spin & 4095) == 4095) {
+                const hipError_t e = hipStreamQuery(stream);
+                if (e == hipErrorNotReady) continue;
+                if (e != hipSuccess) return -1;
+                r = enough(*host);  // the stream is idle: every packing kernel enqueued so far has reported
+                return r != -2 ? r : -1;
             }
-            if ((spin & 1023) == 1023 &&
-                std::chrono::steady_clock::now() - t0 > std::chrono::seconds(30)) return -1;
         }
     }
 };
@@ -262,10 +267,10 @@ static int run_search(SearchArgs &a) {
     const int64_t round_limit = capped ? (int64_t)p.max_iters_max : (int64_t)p.hash_cap / 2 + 1;
     for (int64_t i = 0; i <= round_limit; ++i) {
         if (box) {  // no query is running: nothing left to score or merge
-            const int g = box->gate(a.mail_tag, i);
+            const int g = box->gate(a.mail_tag, i, a.stream);
             if (g > 0) break;
             if (g < 0) {
-                set_error("the device reported no progress for 30 s");
+                set_error("the stream failed or ran dry without the search's progress report");
                 return ANN_EDEVICE;
             }
         }
@@ -322,10 +327,10 @@ static int run_stream(SearchArgs &a) {
     const int64_t round_limit = per_query * (((int64_t)a.Q_total + p.Q - 1) / p.Q + 1);
     for (int64_t i = 0; i <= round_limit; ++i) {
         {   // nothing running after an admission step, and nothing left to admit: every result is written
-            const int g = box->gate(a.mail_tag, i);
+            const int g = box->gate(a.mail_tag, i, a.stream);
             if (g > 0) break;
             if (g < 0) {
-                set_error("the device reported no progress for 30 s");
+                set_error("the stream failed or ran dry without the search's progress report");
                 return ANN_EDEVICE;
             }
         }
