@@ -3,6 +3,8 @@
 relevance kernel for 128-wide items, hidden 512 and 256 (mlp_mfma2_f8_wide_kernel in mlp_mfma_f8.hip).
 
 A chunk is two statements: A = layer 1 of its two blocks and their conversion to e4m3 operands, B = layer 2.
+Two more frame a batch: INIT loads the layer-2 bias into the accumulators, HEAD converts the finished layer-2
+tiles and runs the head layer.
 Inside a statement nothing of the compiler's can come between an MFMA and the instruction that reads its
 result (between two statements it may, say, copy an accumulator, and would read a result that is still on
 its way), and the vector-ALU work of the conversion sits between MFMAs, which hide it.  Between A and B the
@@ -15,8 +17,12 @@ Fixed registers of a wave (the vector-ALU instructions name single registers of 
     v[96:111], v[112:127]   the same for the odd block (set Q)
     v[128:135], v[136:143]  the chunk's 64 hidden units as e4m3 B operands, c = 0, 1 (bytes 0..15: even block)
     v[144:175]              four layer-2 weight fragments in flight from LDS
-    compiler's choice       item rows (4 operands), first-layer fragments (4), the 16 layer-2 accumulator
-                            tiles (accumulation registers), the LDS address, the clamp constant 448.0
+    a[0:255]                the 16 layer-2 accumulator tiles, tile (n2, c) at a[16 (2 n2 + c) ...]: named
+                            outright and listed as clobbered, not operands (HEAD reads single registers of a
+                            tile, which an operand cannot express; the kernel's own code between the statements
+                            has no use for accumulation registers, which a test checks on the compiled kernel)
+    compiler's choice       item rows (4 operands), first-layer fragments (4), the head accumulators (2),
+                            the LDS addresses, the clamp constant 448.0
 
 Order of a chunk (A up to "convert Q", then B):
     8 reads      the first four layer-2 fragments are requested at once (they depend on nothing); A ends
@@ -29,10 +35,23 @@ Order of a chunk (A up to "convert Q", then B):
     layer 2      8 fragments x 2 MFMAs; a fragment's registers are requested again (four fragments ahead)
                  one slot after its MFMAs have issued; counted waits on the in-order LDS counter
 The layer-2 accumulators are still being written when B ends: the next statement that touches them is the
-next chunk's B (MFMA after MFMA, in order) or, after the last chunk, a statement of idle cycles.
+next chunk's B (MFMA after MFMA, in order) or, after the last chunk, HEAD, which starts with idle cycles.
+
+INIT: 64 LDS reads straight into the accumulation registers (register 4 t4 + e of a tile is unit
+32 n2 + 8 t4 + 4 g + e, so a lane reads 16 bytes at %[b2] (= bias copy + 16 g) + 128 n2 + 32 t4, for both
+column blocks); the first A of the batch ends with a full wait on the in-order LDS counter, before any B.
+
+HEAD (after the last chunk; the registers of the hidden units and of the layer-2 fragments are free then):
+    v[128:143]              one tile out of the accumulation registers
+    v[144:151], v[152:159]  64 layer-2 units as e4m3 B operands, c = 0, 1 (bytes 0..15: the even tile)
+    v[160:167], v[168:175]  two head fragments in flight from LDS
+per pair p of tiles: four tiles (c, half) x (16 reads, 16 clamps, 8 conversions), then the fragment's two
+MFMAs.  The conversion of the next pair starts with 32 instructions that do not write the operands, so they
+are rewritten long after the MFMAs that read them have taken them.
 """
 import os
 
+NP = 4                  # head fragments: one per 64 layer-2 units
 ACC = {"P": (64, 80), "Q": (96, 112)}
 H = (128, 136)
 FR = 144
@@ -94,6 +113,48 @@ def part_a():
     return out
 
 
+def acc2_lo(n2, c):
+    return 16 * (2 * n2 + c)
+
+
+def acc2(n2, c):
+    return f"a[{acc2_lo(n2, c)}:{acc2_lo(n2, c) + 15}]"
+
+
+def init_acc2():
+    return [f"ds_read_b128 a[{acc2_lo(n2, c) + 4 * t4}:{acc2_lo(n2, c) + 4 * t4 + 3}], %[b2] offset:{n2 * 128 + t4 * 32}"
+            for n2 in range(NB2) for c in (0, 1) for t4 in range(4)]
+
+
+RT, T, HF = 128, (144, 152), (160, 168)
+
+
+def head():
+    out = list(DRAIN)                                    # the last layer-2 MFMAs finish
+    def frag(p):
+        return [f"ds_read_b128 {vr(HF[p % 2], 4)}, %[w3] offset:{p * 2048}",
+                f"ds_read_b128 {vr(HF[p % 2] + 4, 4)}, %[w3] offset:{p * 2048 + 1024}"]
+    out += frag(0) + frag(1)
+    for p in range(NP):
+        for c in (0, 1):
+            for half in (0, 1):
+                lo = acc2_lo(2 * p + half, c)
+                out += [f"v_accvgpr_read_b32 v{RT + i}, a{lo + i}" for i in range(16)]
+                out += [f"v_med3_f32 v{RT + i}, v{RT + i}, 0, %[fmax]" for i in range(16)]
+                for w in range(4):
+                    d = T[c] + 4 * half + w
+                    out.append(f"v_cvt_pk_fp8_f32 v{d}, v{RT + 4 * w}, v{RT + 4 * w + 1}")
+                    out.append(f"v_cvt_pk_fp8_f32 v{d}, v{RT + 4 * w + 2}, v{RT + 4 * w + 3} op_sel:[0,0,1]")
+        out.append(f"s_waitcnt lgkmcnt({2 if p + 1 < NP else 0})")   # fragment p is there (p + 1 may be on its way)
+        out.append("s_nop 1")
+        for c in (0, 1):
+            out.append(f"v_mfma_f32_32x32x64_f8f6f4 %[q3{c}], {vr(HF[p % 2], 8)}, {vr(T[c], 8)}, "
+                       + ("0" if p == 0 else f"%[q3{c}]"))
+        if p + 2 < NP:
+            out += frag(p + 2)
+    return out + DRAIN
+
+
 def part_b():
     """Layer 2 over the chunk's 64 hidden units.  LDS reads complete in order: fragment k's two reads are
     followed by those of at most two more fragments."""
@@ -105,8 +166,8 @@ def part_b():
             out.append(f"s_waitcnt lgkmcnt({len(outstanding) - 1 - idx})")
             del outstanding[:idx + 1]
         f = vr(FR + 8 * (n2 % 4), 8)
-        out.append(mfma(f"%[a{n2}0]", f, vr(H[0], 8)))
-        out.append(mfma(f"%[a{n2}1]", f, vr(H[1], 8)))
+        out.append(mfma(acc2(n2, 0), f, vr(H[0], 8)))
+        out.append(mfma(acc2(n2, 1), f, vr(H[1], 8)))
         # the registers of fragment n2-1 are free once this slot's MFMAs have issued behind its own
         k = n2 - 1 + 4
         if n2 >= 1 and k < NB2:
@@ -133,8 +194,12 @@ def main():
     for kind, con in (("OUT", "=&"), ("IO", "+")):
         frs = ", ".join(f'[f{k}] "{con}{{{vr(FR + 8 * k, 8)}}}"(f{k})' for k in range(4))
         out.append(f"#define F8W_FRAGS_{kind}(f0, f1, f2, f3) {frs}")
-    acc2 = ", ".join(f'[a{n2}{c}] "+a"(acc2[{n2}][{c}])' for n2 in range(NB2) for c in (0, 1))
-    out.append(f"#define F8W_ACC2 {acc2}")
+    out.append(f"#define F8W_ASM_INIT \\\n    {c_string(init_acc2())}")
+    out.append("")
+    out.append(f"#define F8W_ASM_HEAD \\\n    {c_string(head())}")
+    out.append("")
+    out.append("#define F8W_ACC2_CLOBBERS " + ", ".join(f'"a{r}"' for r in range(256)))
+    out.append("#define F8W_HEAD_CLOBBERS " + ", ".join(f'"v{r}"' for r in range(RT, HF[1] + 8)))
     out.append("")
     with open(os.path.join(here, "mlp_mfma_f8_wide_asm.inc"), "w") as f:
         f.write("\n".join(out))

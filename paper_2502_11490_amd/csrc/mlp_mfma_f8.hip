@@ -230,34 +230,22 @@ mlp_mfma2_f8_kernel(const uint8_t *__restrict__ emb, int64_t N, const float *__r
 // second layer's (128 KB) and the head's fragments stay resident; the first layer's 64 KB are read by every
 // wave straight from global memory (they are hot in L2: every wave of the chip reads the same 64 KB per batch),
 // one block of 32 hidden units ahead of its use, so the main loop has no barrier and no staging.
-// The 256 layer-2 accumulators of a wave fill the accumulation registers; the short-lived layer-1 and head
-// accumulators are pinned to ordinary registers by writing their MFMAs as inline assembly, with the hazards the
-// compiler would otherwise handle kept by hand:
+// A batch is a handful of inline-assembly statements (text from gen_f8_wide_asm.py): the bias into the layer-2
+// accumulators, per chunk of 64 hidden units layer 1 + conversion and layer 2, and the head layer.  The 256
+// layer-2 accumulators of a wave fill the accumulation registers, which the statements name outright and list as
+// clobbered (the head layer reads single registers of a tile, which an operand cannot express; the code between
+// the statements has no use for accumulation registers, which a test checks on the compiled kernel).  The
+// short-lived layer-1 accumulators and operands are pinned to fixed ordinary registers.  Hazards the compiler
+// would otherwise handle are kept by hand inside the statements:
 //   - a register written by a vector-ALU instruction is not read by an MFMA in the next two issue slots
 //     (s_nop 1 in front of every such MFMA);
 //   - an accumulator is not the target of two consecutive MFMAs (pairs 0 and 1 alternate);
-//   - the vector ALU reads an MFMA result only after the MFMA has drained (F8_DRAIN).
-// The MFMAs on pinned accumulators and the idle cycles that let the last of them finish are ONE statement:
-// between two statements the compiler may copy an accumulator to other registers (it does, to free the
-// tuple for the next block's user term), and such a copy right behind an MFMA reads a result that is not there yet.
-// A 16-pass MFMA writes its result 64 cycles after issue: five times 16 idle cycles cover the last one.
-#define F8_DRAIN "s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15"
-#include "mlp_mfma_f8_wide_asm.inc"  // F8W_ASM_A / F8W_ASM_B and their operand lists
-
-// one contraction step of the head layer for both column blocks
-__device__ __forceinline__ void head_step(f32x16 &acc0, f32x16 &acc1, const i32x8 &a, const i32x8 &h0,
-                                          const i32x8 &h1) {
-    asm volatile("s_nop 1\n\t"
-                 "v_mfma_f32_32x32x64_f8f6f4 %0, %2, %3, %0\n\t"
-                 "v_mfma_f32_32x32x64_f8f6f4 %1, %2, %4, %1\n\t" F8_DRAIN
-                 : "+v"(acc0), "+v"(acc1)
-                 : "v"(a), "v"(h0), "v"(h1));
-}
-// layer 2: accumulate in place in the accumulation registers (the allocator, left to itself, moves a tile to
-// a fresh tuple now and then, and there is none to spare)
-__device__ __forceinline__ void mfma_f8_a(f32x16 &acc, const i32x8 &a, const i32x8 &b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
+//   - the vector ALU reads an MFMA result only after the MFMA has drained: a 16-pass MFMA writes its result
+//     64 cycles after issue, five times 16 idle cycles cover the last one.
+// MFMAs and the idle cycles that let the last of them finish are ONE statement: between two statements the
+// compiler may copy a register tuple (it does, to free one for the next block's user term), and such a copy
+// right behind an MFMA reads a result that is not there yet.
+#include "mlp_mfma_f8_wide_asm.inc"  // F8W_ASM_INIT / _A / _B / _HEAD and their operand and clobber lists
 
 // Fragments as above with two contraction steps in layer 1: fragment KS*blk + ks holds W1_item[32 blk + m][64 ks + 32g + b].
 template <int D, int H1, int H2>
@@ -274,7 +262,7 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
     constexpr int N_LDS = NC * NB2 + NP;           // fragments resident in LDS
     constexpr int BLOCK_T = 64 * WAVES;
     constexpr int RW = 32 * CB, TILE = RW * WAVES;
-    extern __shared__ __align__(16) uint4 lds[];   // [N_LDS][2][64]
+    extern __shared__ __align__(16) uint4 lds[];   // [N_LDS][2][64] fragments, then the H2 layer-2 biases
 
     int64_t M = (int64_t)*M_dev;
     if (M > M_max) M = M_max;
@@ -284,6 +272,7 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int g = lane >> 5, col = lane & 31;
     for (int i = threadIdx.x; i < N_LDS * 128; i += BLOCK_T) lds[i] = frag[(size_t)N_W1 * 128 + i];
+    for (int i = threadIdx.x; i < H2 / 4; i += BLOCK_T) lds[N_LDS * 128 + i] = ((const uint4 *)b2s)[i];
     __syncthreads();
 
     auto fragment = [&](int f) {   // f counts from the first resident fragment
@@ -339,6 +328,8 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
     Ids idc = load_ids(blockIdx.x), idn = load_ids((int64_t)blockIdx.x + gridDim.x);
     gather(idc);
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds + 16u * (uint32_t)lane;
+    const uint32_t w3_addr = lds_addr + (uint32_t)(NC * NB2) * 2048u;                           // head fragments
+    const uint32_t b2_addr = (uint32_t)(uintptr_t)lds + (uint32_t)N_LDS * 2048u + 16u * (uint32_t)g;  // bias copy
     // Two sets (P: even blocks, Q: odd blocks) of first-layer fragments and of layer-1 accumulators: once both
     // blocks of a chunk are contracted, the sets receive the next chunk's fragments and user term, which travel
     // while layer 2 of this chunk runs.  An empty memory-clobbering statement keeps the compiler from moving
@@ -381,26 +372,10 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
             bad_now[c] = bad[c];
             upn[c] = upre + (size_t)idn.q[c] * H1 + 4 * g;
         }
-        f32x16 acc2[NB2][CB];
-        int opaque_zero = 0;  // keeps the bias loads inside the batch loop (see the narrow kernel)
-        asm volatile("" : "+s"(opaque_zero));
-        const float *b2t = b2s + opaque_zero;
-#pragma unroll
-        for (int n2 = 0; n2 < NB2; ++n2) {
-            f32x16 init;
-#pragma unroll
-            for (int t4 = 0; t4 < 4; ++t4) {
-                f32x4 bv = *(const f32x4 *)(b2t + n2 * 32 + 8 * t4 + 4 * g);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) init[4 * t4 + e] = bv[e];
-            }
-#pragma unroll
-            for (int c = 0; c < CB; ++c) {
-                acc2[n2][c] = init;
-                asm volatile("" : "+a"(acc2[n2][c]));  // into the accumulation registers now, not at first use
-            }
-            F8_FENCE;
-        }
+        // The 16 layer-2 accumulator tiles live in the accumulation registers, which only the assembly statements
+        // of this loop touch (see gen_f8_wide_asm.py).  They start from the bias, read from its LDS copy straight
+        // into them; the first chunk's statement A ends with a full wait for LDS reads.
+        asm volatile(F8W_ASM_INIT : : [b2] "v"(b2_addr) : "memory", F8W_ACC2_CLOBBERS);
         uint32_t wc = lds_addr;  // this lane's 16 bytes of the chunk's first layer-2 fragment
 #pragma unroll 1
         for (int ch = 0; ch < NC; ++ch) {
@@ -431,13 +406,11 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
                 load_user_term(accQ, up, nb + 1);
             }
             asm volatile(F8W_ASM_B
-                         : F8W_FRAGS_IO(f0, f1, f2, f3), F8W_ACC2
+                         : F8W_FRAGS_IO(f0, f1, f2, f3)
                          : F8W_H_IN(h0, h1), [wc] "v"(wc)
-                         : "memory");
+                         : "memory", F8W_ACC2_CLOBBERS);
             wc += NB2 * 2048;
         }
-        // the last layer-2 MFMAs drain before their tiles are read (the earlier ones finished long ago)
-        asm volatile(F8_DRAIN : "+a"(acc2[NB2 - 1][0]), "+a"(acc2[NB2 - 1][1]), "+a"(acc2[NB2 - 2][0]), "+a"(acc2[NB2 - 2][1]));
         // ids: the next batch becomes the current one, the one after it is requested
         idc = idn;
         idn = load_ids(tile + 2 * (int64_t)gridDim.x);
@@ -449,22 +422,13 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
         gather(idc);  // the item rows of the next batch: layer 1 of this one is done with the registers
         F8_FENCE;
 
+        // head layer: the finished layer-2 tiles leave the accumulation registers through ReLU, clamp and e4m3
+        // rounding, pair of tiles by pair of tiles, each followed by its head fragment's two MFMAs
         f32x16 acc3[CB];
-#pragma unroll
-        for (int c = 0; c < CB; ++c)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc3[c][i] = 0.f;
-#pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            const i32x8 a = fragment(NC * NB2 + p);
-            i32x8 h2q[CB];
-#pragma unroll
-            for (int c = 0; c < CB; ++c) {
-                quantize_half(acc2[2 * p][c], h2q[c], 0);
-                quantize_half(acc2[2 * p + 1][c], h2q[c], 1);
-            }
-            head_step(acc3[0], acc3[1], a, h2q[0], h2q[1]);
-        }
+        asm volatile(F8W_ASM_HEAD
+                     : [q30] "=&v"(acc3[0]), [q31] "=&v"(acc3[1])
+                     : [w3] "v"(w3_addr), [fmax] "s"(E4M3_MAX)
+                     : "memory", F8W_HEAD_CLOBBERS, F8W_ACC2_CLOBBERS);
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
             float part = 0.f;
@@ -561,7 +525,7 @@ int launch_mlp_mfma_f8(const ann_graph *g, const ann_mlp *m, const float *upre, 
     if (M_max <= 0) return ANN_OK;
     if (m->d_item == 128) {
         constexpr int D = 128, H1 = 512, H2 = 256, TILE = 256;
-        constexpr size_t smem = (size_t)((H1 / 64) * (H2 / 32) + H2 / 64) * 2048;  // 136 KB
+        constexpr size_t smem = (size_t)((H1 / 64) * (H2 / 32) + H2 / 64) * 2048 + (size_t)H2 * 4;  // 136 + 1 KB
         auto fn = mlp_mfma2_f8_wide_kernel<D, H1, H2>;
         static std::atomic<uint32_t> raised;
         if (int rc = raise_lds_limit((const void *)fn, smem, m->device, raised); rc != ANN_OK) return rc;

@@ -87,36 +87,41 @@ def test_generated_assembly_is_up_to_date(tmp_path):
         assert (work / inc).read_text() == open(os.path.join(csrc, inc)).read(), f"{inc} is stale: run {script}"
 
 
-def test_stream_kernel_keeps_accumulation_registers_to_its_assembly(tmp_path):
-    """The widest bf16 kernel names its 256 accumulation registers outright inside its assembly statements and
-    only lists them as clobbered, so nothing the compiler generates between two statements may touch one (a
-    spill into them, a copy through them): in the kernel's compiled code every accumulation register sits
-    between the markers of an assembly statement, and nothing is spilled."""
+@pytest.mark.parametrize("source,kernel,min_statements", [("mlp_mfma_stream.hip", "mlp_mfma2_stream_kernel", 18),
+                                                          ("mlp_mfma_f8.hip", "mlp_mfma2_f8_wide_kernel", 4)])
+def test_kernels_keep_accumulation_registers_to_their_assembly(tmp_path, source, kernel, min_statements):
+    """The widest bf16 / fp16 kernel and the wide 8-bit kernel name their 256 accumulation registers outright
+    inside their assembly statements and only list them as clobbered, so nothing the compiler generates between
+    two statements may touch one (a spill into them, a copy through them): in the kernel's compiled code every
+    accumulation register sits between the markers of an assembly statement, and nothing is spilled."""
     import shutil
     import subprocess
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     if not os.path.exists(hipcc):
         pytest.skip("no hipcc here")
     csrc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2502_11490_amd", "csrc")
-    out = tmp_path / "stream.s"
+    out = tmp_path / "kernel.s"
     from paper_2502_11490_amd import build
     flags = [f for f in build.FLAGS if f not in ("-shared", "-fPIC")]
-    subprocess.run([hipcc] + flags + ["-S", "--cuda-device-only", os.path.join(csrc, "mlp_mfma_stream.hip"), "-o", str(out)],
+    subprocess.run([hipcc] + flags + ["-S", "--cuda-device-only", os.path.join(csrc, source), "-o", str(out)],
                    check=True, capture_output=True)
     text = out.read_text()
-    start = text.index("mlp_mfma2_stream_kernel")
-    inside, statements, outside = False, 0, []
-    for line in text[start:].split("\n"):
-        if "#ASMSTART" in line:
-            inside, statements = True, statements + 1
-        elif "#ASMEND" in line:
-            inside = False
-        elif not inside:
-            code = line.split(";")[0]
-            if re.search(r"\ba\[?\d+", code) or "accvgpr" in code or "scratch_" in code:
-                outside.append(line.strip())
-    assert statements >= 18          # the 17 steps and the bias statement were found
-    assert not outside, outside[:5]
+    # the bodies of this kernel's instantiations: from each "<mangled name>:" label to the end-of-function label
+    bodies = re.findall(r"^(_Z\w*" + kernel + r"\w*):[^\n]*\n(.*?)^\.Lfunc_end\d+:", text, re.S | re.M)
+    assert bodies, "kernel not found in the compiled code"
+    for name, body in bodies:
+        inside, statements, outside = False, 0, []
+        for line in body.split("\n"):
+            if "#ASMSTART" in line:
+                inside, statements = True, statements + 1
+            elif "#ASMEND" in line:
+                inside = False
+            elif not inside:
+                code = line.split(";")[0]
+                if re.search(r"\ba\[?\d+", code) or "accvgpr" in code or "scratch_" in code:
+                    outside.append(line.strip())
+        assert statements >= min_statements, (name, statements)
+        assert not outside, (name, outside[:5])
 
 
 def test_bench_refuses_more_than_one_gpu():
