@@ -116,7 +116,8 @@ def main() -> int:
     ap.add_argument("--no-f16", action="store_true", help="skip the fp16 metric run beside the headline")
     ap.add_argument("--no-f8", action="store_true", help="skip the 8-bit metric run (on C2) beside the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run the library's plain 256 MiB copy kernel (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+                    help="kept for the profile commands: the library's plain 256 MiB copy kernel (reference for "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE) now always runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (queries would shard across GPUs "
@@ -463,13 +464,22 @@ def main() -> int:
             f"scoring {prof16['score'][0]:.2f} ms")
         del ws16, g16, m16, emb16, users16
 
-    if args.calibrate_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 255)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            ann.ann_profile_copy(dst, src)
-        torch.cuda.synchronize()
-        del src, dst
+    # ---- what a plain copy reaches on this machine (context for the bandwidth figures below; with
+    #      --calibrate-copy it is also the reference of known size for the profiler's traffic counters) ----
+    src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        ann.ann_profile_copy(dst, src)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(5):
+        ann.ann_profile_copy(dst, src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_GBps = 5 * 2 * src.numel() / (1e-3 * ev0.elapsed_time(ev1)) / 1e9   # bytes read + bytes written
+    log(f"plain copy of 256 MiB: {copy_GBps:.0f} GB/s (read + write)")
+    del src, dst
 
     # ---- per-stage time with HIP events on the search's stream ----
     ann.ann_profile_enable(True)
@@ -514,6 +524,7 @@ def main() -> int:
         "pack_ms_per_step": round(pack_ms / args.profile_steps, 4),
         "round_adjacency_GBps": round(round_bytes / (1e-3 * round_ms / args.profile_steps) / 1e9, 2),
         "score_embedding_GBps": round(gather_bytes / score_s_per_step / 1e9, 2),
+        "plain_copy_GBps": round(copy_GBps, 1),
     }
 
     # ---- the CPU oracle on a bounded sample of the same queries ----
