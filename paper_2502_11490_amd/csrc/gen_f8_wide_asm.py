@@ -30,8 +30,11 @@ Order of a chunk (A up to "convert Q", then B):
     P1..P4       layer 1 of the even block: (step 0, c 0), (step 0, c 1), (step 1, c 0), (step 1, c 1)
     Q1, Q2       layer 1 of the odd block begins; two MFMAs have now issued behind P4, so its result is there
     convert P    ReLU, clamp, e4m3 of set P, spread behind Q2, Q3, Q4
-    idle         until Q4's result is there (a 16-pass MFMA writes it 64 cycles after issue)
-    convert Q    exposed
+    convert Q    exposed.  No idle cycles are needed in front of it: an instruction slot of a wave is four
+                 clocks (s_nop n takes 4 (n + 1)), a 16-pass MFMA has written its result 19 slots after it
+                 issued, and 33 slots lie between Q3 and the first instruction that reads its result (a third
+                 of convert P, Q4, another third), 40 between Q4 and the first that reads its (the rest of
+                 convert P and the conversion of pair 0)
     layer 2      8 fragments x 2 MFMAs; a fragment's registers are requested again (four fragments ahead)
                  one slot after its MFMAs have issued; counted waits on the in-order LDS counter
 The layer-2 accumulators are still being written when B ends: the next statement that touches them is the
@@ -56,7 +59,7 @@ ACC = {"P": (64, 80), "Q": (96, 112)}
 H = (128, 136)
 FR = 144
 NB2 = 8
-DRAIN = ["s_nop 15"] * 5
+DRAIN = ["s_nop 15", "s_nop 7"]     # 24 instruction slots: a 16-pass MFMA has written its result after 19
 
 
 def vr(lo, n):
@@ -107,8 +110,10 @@ def part_a():
     out += cp[third:2 * third]
     out.append(l1("Q", 1, 1))
     out += cp[2 * third:]
-    out += DRAIN
-    out += convert("Q")
+    cq = convert("Q")
+    # slots between the last MFMA on an accumulator and the first instruction that reads it (see above)
+    assert len(cp[third:2 * third]) + 1 + len(cp[2 * third:]) >= 19 and len(cp[2 * third:]) + len(cq) // 2 >= 19
+    out += cq
     out.append("s_waitcnt lgkmcnt(0)")
     return out
 
@@ -130,7 +135,9 @@ RT, T, HF = 128, (144, 152), (160, 168)
 
 
 def head():
-    out = list(DRAIN)                                    # the last layer-2 MFMAs finish
+    # The last chunk's layer 2 is still running: its MFMAs went tile 0 .. 7, and tile n2 is read here
+    # 160 n2 / 2 instruction slots in, which is 19 slots behind its last MFMA for every tile.
+    out = []
     def frag(p):
         return [f"ds_read_b128 {vr(HF[p % 2], 4)}, %[w3] offset:{p * 2048}",
                 f"ds_read_b128 {vr(HF[p % 2] + 4, 4)}, %[w3] offset:{p * 2048 + 1024}"]

@@ -63,15 +63,16 @@ constexpr int MF_WAVES = 4;
 //     separate statement of idle cycles would read too early; it was seen to do that in the 8-bit kernel
 //     for the wide metric.)
 // One weight fragment against both column blocks of pairs.  LAST: the group ends here; the idle cycles that
-// let its MFMAs finish are part of the same statement, so that nothing can come between them.
+// let its MFMAs finish are part of the same statement, so that nothing can come between them (an 8-pass MFMA
+// has written its result 11 instruction slots after it issued; s_nop n takes n + 1 slots of four clocks).
 #define MFMA_PAIR_TEXT(T) "s_nop 1\n\tv_mfma_f32_32x32x16_" T " %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_" T " %1, %2, %4, %1"
 template <bool LAST, bool F16>
 __device__ __forceinline__ void mfma_vgpr_pair(f32x16 &acc0, f32x16 &acc1, const bf16x8 &a, const bf16x8 &b0,
                                                const bf16x8 &b1) {
     if (LAST && F16)
-        asm volatile(MFMA_PAIR_TEXT("f16") "\n\ts_nop 15\n\ts_nop 7" : "+v"(acc0), "+v"(acc1) : "v"(a), "v"(b0), "v"(b1));
+        asm volatile(MFMA_PAIR_TEXT("f16") "\n\ts_nop 13" : "+v"(acc0), "+v"(acc1) : "v"(a), "v"(b0), "v"(b1));
     else if (LAST)
-        asm volatile(MFMA_PAIR_TEXT("bf16") "\n\ts_nop 15\n\ts_nop 7" : "+v"(acc0), "+v"(acc1) : "v"(a), "v"(b0), "v"(b1));
+        asm volatile(MFMA_PAIR_TEXT("bf16") "\n\ts_nop 13" : "+v"(acc0), "+v"(acc1) : "v"(a), "v"(b0), "v"(b1));
     else if (F16)
         asm volatile(MFMA_PAIR_TEXT("f16") : "+v"(acc0), "+v"(acc1) : "v"(a), "v"(b0), "v"(b1));
     else

@@ -240,8 +240,9 @@ mlp_mfma2_f8_kernel(const uint8_t *__restrict__ emb, int64_t N, const float *__r
 //   - a register written by a vector-ALU instruction is not read by an MFMA in the next two issue slots
 //     (s_nop 1 in front of every such MFMA);
 //   - an accumulator is not the target of two consecutive MFMAs (pairs 0 and 1 alternate);
-//   - the vector ALU reads an MFMA result only after the MFMA has drained: a 16-pass MFMA writes its result
-//     64 cycles after issue, five times 16 idle cycles cover the last one.
+//   - the vector ALU reads an MFMA result only after the MFMA has written it: 19 instruction slots after a
+//     16-pass MFMA issued (a slot of a wave is four clocks, s_nop n takes n + 1 slots), which the statements
+//     fill with other work wherever they can.
 // MFMAs and the idle cycles that let the last of them finish are ONE statement: between two statements the
 // compiler may copy a register tuple (it does, to free one for the next block's user term), and such a copy
 // right behind an MFMA reads a result that is not there yet.
