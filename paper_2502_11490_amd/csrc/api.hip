@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <chrono>
 #include <new>
 #include <vector>
 
@@ -158,18 +159,22 @@ struct Mailbox {
     }
     // Before enqueuing round `i` (0-based): 1 = the search has finished, 0 = go on, -1 = the stream reports an
     // error, or has run everything enqueued so far without the progress the kernels would have reported.
-    // While waiting, the stream is asked now and then: a search enqueued behind long work of the caller's waits
-    // as long as that takes, and a failed device ends the wait.
+    // A wait that lasts (20 ms without the word it needs, again every 20 ms) asks the stream: a search enqueued
+    // behind long work of the caller's waits as long as that takes, and a failed device ends the wait.  Rounds
+    // take microseconds, so a running search never asks (a stream query is not free: asked every few thousand
+    // spins it cost the small configurations, whose host thread mostly waits here, 0.4 ms per search).
     int gate(uint64_t tag, int64_t i, hipStream_t stream) const {
         auto enough = [&](uint64_t w) {
             if ((w >> 40) != (tag >> 40)) return i <= AHEAD ? 0 : -2;  // nothing reported yet
             if (w & 1ull) return 1;
             return (int64_t)((w & 0xFFFFFFFFFFull) >> 1) + AHEAD >= i ? 0 : -2;
         };
+        auto last = std::chrono::steady_clock::now();
         for (int spin = 0;; ++spin) {
             int r = enough(*host);
             if (r != -2) return r;
-            if ((spin & 4095) == 4095) {
+            if ((spin & 1023) == 1023 && std::chrono::steady_clock::now() - last > std::chrono::milliseconds(20)) {
+                last = std::chrono::steady_clock::now();
                 const hipError_t e = hipStreamQuery(stream);
                 if (e == hipErrorNotReady) continue;
                 if (e != hipSuccess) return -1;
