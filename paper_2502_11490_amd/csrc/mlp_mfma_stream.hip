@@ -236,27 +236,35 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         const int64_t row0 = tile * TILE + (int64_t)wave * 64;
         bf16x8 xf[CB][KS1];
         size_t nxt_off[CB];  // element offsets of this lane's pieces of the next batch's rows
-        static_for<0, CB * KS1 / 4>([&](auto quad) {
-            constexpr int c = decltype(quad)::value / (KS1 / 4), s = 4 * (decltype(quad)::value % (KS1 / 4));
-            u32x4 r0, r1, r2, r3;
-            lds_load4_b128<(c * KS1 + s) * 1024, 1024>(xw_addr, r0, r1, r2, r3);
-            xf[c][s] = __builtin_bit_cast(bf16x8, r0);
-            xf[c][s + 1] = __builtin_bit_cast(bf16x8, r1);
-            xf[c][s + 2] = __builtin_bit_cast(bf16x8, r2);
-            xf[c][s + 3] = __builtin_bit_cast(bf16x8, r3);
-        });
-#pragma unroll
-        for (int c = 0; c < CB; ++c) nxt_off[c] = (size_t)idn.id[c] * D + 8 * g;
-
         // The layer-2 accumulators (the 256 accumulation registers, which only the assembly statements of this
-        // loop touch: see gen_stream_asm.py) start from the bias, read from LDS straight into them; step 0 begins
-        // with a full wait for LDS reads.
+        // loop touch: see gen_stream_asm.py) start from the bias, read from LDS straight into them: requested first, so that the
+        // item rows' reads queue up behind them and one wait covers both.
         {
             uint32_t t16 = tid16;  // small addresses are rebuilt where they are used rather than kept across the steps
             asm volatile("" : "+v"(t16));
             const uint32_t b2_addr = (uint32_t)(uintptr_t)b2buf + ((t16 >> 5) & 16);  // 16 bytes * g
             asm volatile(STREAM_ASM_INIT_ACC2 : : [b2] "v"(b2_addr) : "memory", STREAM_ACC2_CLOBBERS);
         }
+
+        {   // the batch's 64 item rows out of the wave's LDS area: sixteen reads, one wait
+            static_assert(CB * KS1 == 16, "sixteen 16-byte pieces per lane");
+            u32x4 r[16];
+#define RD(k) "ds_read_b128 %" #k ", %16 offset:" #k "*1024\n\t"
+            asm volatile(RD(0) RD(1) RD(2) RD(3) RD(4) RD(5) RD(6) RD(7) RD(8) RD(9) RD(10) RD(11) RD(12) RD(13) RD(14) RD(15)
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]),
+                           "=&v"(r[7]), "=&v"(r[8]), "=&v"(r[9]), "=&v"(r[10]), "=&v"(r[11]), "=&v"(r[12]), "=&v"(r[13]),
+                           "=&v"(r[14]), "=&v"(r[15])
+                         : "v"(xw_addr)
+                         : "memory");
+#undef RD
+#pragma unroll
+            for (int c = 0; c < CB; ++c)
+#pragma unroll
+                for (int k = 0; k < KS1; ++k) xf[c][k] = __builtin_bit_cast(bf16x8, r[c * KS1 + k]);
+        }
+#pragma unroll
+        for (int c = 0; c < CB; ++c) nxt_off[c] = (size_t)idn.id[c] * D + 8 * g;
 
         // Two sets of layer-1 accumulators (A, B) and of converted hidden units alternate by step;
         // all of them, and the layer-2 accumulators, sit in fixed physical registers (see
