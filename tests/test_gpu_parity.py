@@ -519,3 +519,24 @@ def test_concurrent_searches_from_two_host_threads():
     assert not errors, errors
     assert all(not t.is_alive() for t in threads)
     assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
+
+
+def test_search_enqueued_behind_long_work_on_its_stream():
+    """The host follows a search's progress word; while the stream is still busy with the caller's earlier work
+    the word does not move, and the wait asks the stream instead of giving up."""
+    import time
+    cfg = scaled(PRESETS["C2"], 20000, n_clusters=16, Q=64)
+    wl = make_workload(cfg)
+    g, m, dev = open_handles(wl)
+    want = ann.ann_search(g, m, dev["users"], dev["entries"], cfg.W, 48, 20, 0)[0].cpu()
+    s = torch.cuda.Stream()
+    a = torch.randn(8192, 8192, device="cuda")
+    with torch.cuda.stream(s):
+        t0 = time.perf_counter()
+        for _ in range(40):          # a few hundred milliseconds of work ahead of the search
+            a = (a @ a) * 1e-4
+        ids, _ = ann.ann_search(g, m, dev["users"], dev["entries"], cfg.W, 48, 20, 0, stream=s)
+        s.synchronize()
+        waited = time.perf_counter() - t0
+    assert torch.equal(ids.cpu(), want)
+    print(f"search returned after {1e3 * waited:.0f} ms behind the stream's earlier work")
