@@ -33,10 +33,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float E4M3_MAX = 448.f;
-constexpr float F8_W_SCALE = 4.f;    // weights
-constexpr float F8_H1_SCALE = 4.f;   // = item scale (1) x weight scale
-constexpr float F8_H2_SCALE = 16.f;  // = H1 scale x weight scale
-constexpr float F8_LOGIT_SCALE = 64.f;
+constexpr float F8_W_SCALE = 4.f;    // weights; hidden layer 1 is therefore held at 4 x its value, layer 2 at 16 x,
+constexpr float F8_LOGIT_SCALE = 64.f;  // and the head's sums at 64 x
 
 __device__ __forceinline__ f32x16 mfma_f8(const i32x8 &a, const i32x8 &b, const f32x16 &c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
@@ -276,12 +274,6 @@ mlp_mfma2_f8_wide_kernel(const uint8_t *__restrict__ emb, int64_t N, const float
     for (int i = threadIdx.x; i < H2 / 4; i += BLOCK_T) lds[N_LDS * 128 + i] = ((const uint4 *)b2s)[i];
     __syncthreads();
 
-    auto fragment = [&](int f) {   // f counts from the first resident fragment
-        const uint4 lo = lds[f * 128 + lane], hi = lds[f * 128 + 64 + lane];
-        i32x8 a;
-        a[0] = lo.x, a[1] = lo.y, a[2] = lo.z, a[3] = lo.w, a[4] = hi.x, a[5] = hi.y, a[6] = hi.z, a[7] = hi.w;
-        return a;
-    };
     auto w1_fragment = [&](int f) {  // straight from global memory
         const uint4 lo = frag[(size_t)f * 128 + lane], hi = frag[(size_t)f * 128 + 64 + lane];
         i32x8 a;

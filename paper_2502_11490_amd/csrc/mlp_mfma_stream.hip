@@ -120,7 +120,6 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
     constexpr int CHUNK_U4 = 24 * 64;
     constexpr int W3_U4 = 16 * 64;
     constexpr int TILE = 64 * 4;
-    constexpr int ST = CHUNK_U4 / ST_BLOCK;  // 6 uint4 per thread and chunk
     constexpr int NBUF = 3;
     extern __shared__ __align__(16) uint4 lds[];
     uint4 *wbuf = lds;                       // [NBUF][CHUNK_U4]
