@@ -136,7 +136,9 @@ size_t ann_search_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t 
  * device's progress (a word in pinned host memory that the kernels update every round) to learn
  * when every query has converged, stays a few rounds ahead of the device meanwhile, and waits
  * on `stream` once, at the end (so such a call cannot be recorded into a HIP graph; a capped
- * one can: it launches kernels only).
+ * one can: it launches kernels only).  Work enqueued on `stream` before the call is waited for as
+ * long as it takes; ANN_EDEVICE if the stream reports an error or runs dry without the progress
+ * the kernels report.
  * Limits: W*R <= 1024, max(L,k) + W*R <= 4096, E <= 1024.
  * Returns ANN_EWORKSPACE (results still written, for the truncated search) if the call
  * waited on the stream and saw a query fill its visited table; with max_iters > 0 use
