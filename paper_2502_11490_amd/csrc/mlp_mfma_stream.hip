@@ -137,15 +137,6 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
     uint4 *xw = xbuf + (size_t)wave * (CB * KS1 * 64) + lane;
     const uint32_t xw_addr = (uint32_t)(uintptr_t)xw;
 
-    for (int i = threadIdx.x; i < W3_U4; i += ST_BLOCK) w3buf[i] = frag[(size_t)NSTEP * CHUNK_U4 + i];
-    for (int i = threadIdx.x; i < 2 * CHUNK_U4; i += ST_BLOCK) wbuf[i] = frag[i];  // chunks 0 and 1
-    for (int i = threadIdx.x; i < NB2 * 32; i += ST_BLOCK) b2buf[i] = b2[i];
-
-    if (threadIdx.x < 8) {  // head weights and head bias, zero beyond J
-        b2buf[NB2 * 32 + threadIdx.x] = (int)threadIdx.x < J ? head_w[threadIdx.x] : 0.f;
-        b2buf[NB2 * 32 + 8 + threadIdx.x] = (int)threadIdx.x < J ? b3[threadIdx.x] : 0.f;
-    }
-
     // Item rows are gathered one batch ahead of the arithmetic (into the wave's LDS area), so the
     // item ids run two batches ahead; query ids and validity are read again one batch ahead rather
     // than kept in registers through a batch.  Rows past the end read the last pair (never stored).
@@ -187,13 +178,29 @@ mlp_mfma2_stream_kernel(const uint16_t *__restrict__ emb, int64_t N, const float
         }
         return r;
     };
-    auto load_ids = [&](int64_t tile) { return check_ids(request_ids(tile)); };
-    Ids idc = load_ids(blockIdx.x), idn = load_ids((int64_t)blockIdx.x + gridDim.x);
+    // The launch's fixed cost is a chain of trips to memory (pair count, ids, item rows, user term); the copies
+    // of the head fragments, of weight chunks 0 and 1 and of the constants into LDS go between its links.
+    const RawIds raw_c = request_ids(blockIdx.x), raw_n = request_ids((int64_t)blockIdx.x + gridDim.x);
+    for (int i = threadIdx.x; i < W3_U4; i += ST_BLOCK) w3buf[i] = frag[(size_t)NSTEP * CHUNK_U4 + i];
+    for (int i = threadIdx.x; i < 2 * CHUNK_U4; i += ST_BLOCK) wbuf[i] = frag[i];  // chunks 0 and 1
+    Ids idc = check_ids(raw_c), idn = check_ids(raw_n);
+    {
+        uint4 rows[CB][KS1];
 #pragma unroll
-    for (int c = 0; c < CB; ++c) {
-        const uint4 *src = (const uint4 *)(emb + (size_t)idc.id[c] * D) + g;
+        for (int c = 0; c < CB; ++c) {
+            const uint4 *src = (const uint4 *)(emb + (size_t)idc.id[c] * D) + g;
 #pragma unroll
-        for (int s = 0; s < KS1; ++s) xw[(c * KS1 + s) * 64] = src[2 * s];
+            for (int s = 0; s < KS1; ++s) rows[c][s] = src[2 * s];
+        }
+        for (int i = threadIdx.x; i < NB2 * 32; i += ST_BLOCK) b2buf[i] = b2[i];
+        if (threadIdx.x < 8) {  // head weights and head bias, zero beyond J
+            b2buf[NB2 * 32 + threadIdx.x] = (int)threadIdx.x < J ? head_w[threadIdx.x] : 0.f;
+            b2buf[NB2 * 32 + 8 + threadIdx.x] = (int)threadIdx.x < J ? b3[threadIdx.x] : 0.f;
+        }
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) xw[(c * KS1 + s) * 64] = rows[c][s];
     }
     __syncthreads();
 
