@@ -144,6 +144,15 @@ def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
     return t.data_ptr()
 
 
+def _queries_ptr(queries: torch.Tensor, m) -> Optional[int]:
+    """User vectors must be [Q][d_user] in the metric's element type (bf16 for the 8-bit metric, whose user half
+    stays 16-bit): the library takes a bare pointer and could not tell."""
+    want = {ANN_F32: torch.float32, ANN_BF16: torch.bfloat16, ANN_F16: torch.float16, ANN_F8: torch.bfloat16}[m.dtype]
+    if queries.dim() != 2 or queries.shape[1] != m.d_user:
+        raise ValueError(f"queries must be [Q][{m.d_user}], got {tuple(queries.shape)}")
+    return _dev_ptr(queries, "queries", want)
+
+
 class Graph:
     """Owns the C handle and keeps the borrowed tensors alive."""
 
@@ -245,7 +254,7 @@ def ann_search(g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.Tensor, W
                                 device=queries.device)
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, k, queries.device)
-    rc = lib.ann_search(g.handle, m.handle, _dev_ptr(queries, "queries"), Q, _dev_ptr(entries, "entries", torch.int32),
+    rc = lib.ann_search(g.handle, m.handle, _queries_ptr(queries, m), Q, _dev_ptr(entries, "entries", torch.int32),
                         E, W, L, k, max_iters, _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                         _dev_ptr(out_ids, "out_ids", torch.int32), _dev_ptr(out_scores, "out_scores", torch.float32),
                         _stream_ptr(stream))
@@ -263,7 +272,7 @@ def ann_search_ragged(g: Graph, m: Mlp, queries, entries, W_q, L_q, iters_q, W_m
                                 dtype=torch.uint8, device=queries.device)
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, k, queries.device)
-    rc = lib.ann_search_ragged(g.handle, m.handle, _dev_ptr(queries, "queries"), Q,
+    rc = lib.ann_search_ragged(g.handle, m.handle, _queries_ptr(queries, m), Q,
                                _dev_ptr(entries, "entries", torch.int32), E, _dev_ptr(W_q, "W_q", torch.int32),
                                _dev_ptr(L_q, "L_q", torch.int32), _dev_ptr(iters_q, "iters_q", torch.int32), W_max,
                                L_max, k, max_iters_max, _dev_ptr(workspace, "workspace", torch.uint8),
@@ -290,7 +299,7 @@ def ann_search_walkers(g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.T
                                 device=queries.device)
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, k, queries.device)
-    rc = lib.ann_search_walkers(g.handle, m.handle, _dev_ptr(queries, "queries"), Q,
+    rc = lib.ann_search_walkers(g.handle, m.handle, _queries_ptr(queries, m), Q,
                                 _dev_ptr(entries, "entries", torch.int32), E, T, k,
                                 _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                                 _dev_ptr(out_ids, "out_ids", torch.int32),
@@ -319,7 +328,7 @@ def ann_search_stream(g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.Te
                                 dtype=torch.uint8, device=queries.device)
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, k, queries.device)
-    rc = lib.ann_search_stream(g.handle, m.handle, _dev_ptr(queries, "queries"), Q,
+    rc = lib.ann_search_stream(g.handle, m.handle, _queries_ptr(queries, m), Q,
                                _dev_ptr(entries, "entries", torch.int32), E, slots, W, L, k, max_iters,
                                _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                                _dev_ptr(out_ids, "out_ids", torch.int32),
@@ -358,7 +367,7 @@ def ann_search_layers(graphs: Sequence[Graph], m: Mlp, queries: torch.Tensor, en
                                 dtype=torch.uint8, device=queries.device)
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, int(K_l[-1]), queries.device)
-    rc = lib.ann_search_layers(handles, n, m.handle, _dev_ptr(queries, "queries"), Q,
+    rc = lib.ann_search_layers(handles, n, m.handle, _queries_ptr(queries, m), Q,
                                _dev_ptr(entries, "entries", torch.int32), E, W, L, K, max_iters,
                                _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                                _dev_ptr(out_ids, "out_ids", torch.int32),
@@ -373,7 +382,7 @@ def ann_score_pairs(g: Graph, m: Mlp, queries: torch.Tensor, q_idx: torch.Tensor
     M = q_idx.numel()
     if out is None:
         out = torch.empty(M, dtype=torch.float32, device=queries.device)
-    rc = lib.ann_score_pairs(g.handle, m.handle, _dev_ptr(queries, "queries"), queries.shape[0], M,
+    rc = lib.ann_score_pairs(g.handle, m.handle, _queries_ptr(queries, m), queries.shape[0], M,
                              _dev_ptr(q_idx, "q_idx", torch.int32), _dev_ptr(item, "item", torch.int32),
                              _dev_ptr(out, "out", torch.float32), tile_rows, _stream_ptr(stream))
     _check(rc)

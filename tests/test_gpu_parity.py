@@ -540,3 +540,16 @@ def test_search_enqueued_behind_long_work_on_its_stream():
         waited = time.perf_counter() - t0
     assert torch.equal(ids.cpu(), want)
     print(f"search returned after {1e3 * waited:.0f} ms behind the stream's earlier work")
+
+
+def test_binding_rejects_queries_of_the_wrong_type_or_width():
+    cfg = scaled(PRESETS["C2"], 2000, n_clusters=4, Q=8)
+    wl = make_workload(cfg)
+    g, m, dev = open_handles(wl)
+    with pytest.raises(TypeError):
+        ann.ann_search(g, m, dev["users"].float(), dev["entries"], 2, 8, 5, 0)
+    with pytest.raises(ValueError):
+        ann.ann_search(g, m, dev["users"][:, :-1].contiguous(), dev["entries"], 2, 8, 5, 0)
+    with pytest.raises(TypeError):
+        ann.ann_score_pairs(g, m, dev["users"].to(torch.float16), torch.zeros(4, dtype=torch.int32, device="cuda"),
+                            torch.zeros(4, dtype=torch.int32, device="cuda"))
