@@ -421,10 +421,11 @@ int oracle_search(const void *emb, int dtype, int64_t N, int d, const int32_t *a
     return fail ? -2 : 0;
 }
 
-/* Paper-literal inter-candidate search (Algorithm 1 read as K independent walkers sharing one
- * result container; Sec. 3.2: "execute k parallel search processes with different initial
- * seeds; each search process traverses the graph by visiting the most relevant neighbours; a
- * shared max heap ranks the current most relevant items among processes").
+/* Paper-literal inter-candidate search (Sec. 3.2, Algorithm 1 read as K independent walkers
+ * sharing one result container: one search process per seed runs at the same time as the
+ * others, each moving through the graph towards its most relevant neighbours, and the only
+ * thing the processes have in common is the bounded container that keeps the best items any
+ * of them has found).
  *
  * Per query: every distinct in-range seed, in the order given, is scored, pushed into the
  * shared list and becomes the position of one walker (walker index = position of the seed in

@@ -144,13 +144,35 @@ def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
     return t.data_ptr()
 
 
-def _queries_ptr(queries: torch.Tensor, m) -> Optional[int]:
+def _queries_ptr(queries: torch.Tensor, m, Q: Optional[int] = None) -> Optional[int]:
     """User vectors must be [Q][d_user] in the metric's element type (bf16 for the 8-bit metric, whose user half
-    stays 16-bit): the library takes a bare pointer and could not tell."""
+    stays 16-bit): the library takes a bare pointer and could not tell.  With Q given, the row count is checked
+    too (the kernels read Q rows)."""
     want = {ANN_F32: torch.float32, ANN_BF16: torch.bfloat16, ANN_F16: torch.float16, ANN_F8: torch.bfloat16}[m.dtype]
     if queries.dim() != 2 or queries.shape[1] != m.d_user:
         raise ValueError(f"queries must be [Q][{m.d_user}], got {tuple(queries.shape)}")
+    if Q is not None and queries.shape[0] != Q:
+        raise ValueError(f"queries has {queries.shape[0]} rows, entries has {Q}")
     return _dev_ptr(queries, "queries", want)
+
+
+def _entries_shape(entries: torch.Tensor):
+    if entries.dim() != 2:
+        raise ValueError(f"entries must be [Q][E], got {tuple(entries.shape)}")
+    return int(entries.shape[0]), int(entries.shape[1])
+
+
+def _check_out(out_ids, out_scores, Q: int, k: int) -> None:
+    """Caller-supplied result arrays must be exactly [Q][k]: the library writes Q * k elements into each."""
+    for name, t in (("out_ids", out_ids), ("out_scores", out_scores)):
+        if t is None or tuple(t.shape) != (Q, k):
+            raise ValueError(f"{name} must be [{Q}][{k}], got {None if t is None else tuple(t.shape)}")
+
+
+def _per_query_ptr(t: torch.Tensor, name: str, Q: int) -> Optional[int]:
+    if t is None or t.numel() != Q:
+        raise ValueError(f"{name} must hold one int32 per query ({Q}), got {None if t is None else t.numel()}")
+    return _dev_ptr(t, name, torch.int32)
 
 
 class Graph:
@@ -248,13 +270,14 @@ def ann_search(g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.Tensor, W
     """Returns (ids [Q,k] int32, scores [Q,k] fp32) on the device.  `workspace` is a uint8 device tensor of at
     least ann_search_workspace_bytes(...) bytes; one is allocated when omitted."""
     lib = load_library()
-    Q, E = entries.shape
+    Q, E = _entries_shape(entries)
     if workspace is None:
         workspace = torch.empty(ann_search_workspace_bytes(g, m, Q, E, W, L, k, max_iters), dtype=torch.uint8,
                                 device=queries.device)
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, k, queries.device)
-    rc = lib.ann_search(g.handle, m.handle, _queries_ptr(queries, m), Q, _dev_ptr(entries, "entries", torch.int32),
+    _check_out(out_ids, out_scores, Q, k)
+    rc = lib.ann_search(g.handle, m.handle, _queries_ptr(queries, m, Q), Q, _dev_ptr(entries, "entries", torch.int32),
                         E, W, L, k, max_iters, _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                         _dev_ptr(out_ids, "out_ids", torch.int32), _dev_ptr(out_scores, "out_scores", torch.float32),
                         _stream_ptr(stream))
@@ -266,15 +289,16 @@ def ann_search_ragged(g: Graph, m: Mlp, queries, entries, W_q, L_q, iters_q, W_m
                       max_iters_max: int, workspace: Optional[torch.Tensor] = None, out_ids=None, out_scores=None,
                       stream=None):
     lib = load_library()
-    Q, E = entries.shape
+    Q, E = _entries_shape(entries)
     if workspace is None:
         workspace = torch.empty(ann_search_workspace_bytes(g, m, Q, E, W_max, L_max, k, max_iters_max),
                                 dtype=torch.uint8, device=queries.device)
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, k, queries.device)
-    rc = lib.ann_search_ragged(g.handle, m.handle, _queries_ptr(queries, m), Q,
-                               _dev_ptr(entries, "entries", torch.int32), E, _dev_ptr(W_q, "W_q", torch.int32),
-                               _dev_ptr(L_q, "L_q", torch.int32), _dev_ptr(iters_q, "iters_q", torch.int32), W_max,
+    _check_out(out_ids, out_scores, Q, k)
+    rc = lib.ann_search_ragged(g.handle, m.handle, _queries_ptr(queries, m, Q), Q,
+                               _dev_ptr(entries, "entries", torch.int32), E, _per_query_ptr(W_q, "W_q", Q),
+                               _per_query_ptr(L_q, "L_q", Q), _per_query_ptr(iters_q, "iters_q", Q), W_max,
                                L_max, k, max_iters_max, _dev_ptr(workspace, "workspace", torch.uint8),
                                workspace.numel(), _dev_ptr(out_ids, "out_ids", torch.int32),
                                _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
@@ -293,13 +317,14 @@ def ann_search_walkers(g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.T
                        workspace: Optional[torch.Tensor] = None, out_ids=None, out_scores=None, stream=None):
     """One walker per seed, T greedy hops each, one shared result list.  Returns (ids [Q,k], scores [Q,k])."""
     lib = load_library()
-    Q, E = entries.shape
+    Q, E = _entries_shape(entries)
     if workspace is None:
         workspace = torch.empty(ann_search_walkers_workspace_bytes(g, m, Q, E, T, k), dtype=torch.uint8,
                                 device=queries.device)
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, k, queries.device)
-    rc = lib.ann_search_walkers(g.handle, m.handle, _queries_ptr(queries, m), Q,
+    _check_out(out_ids, out_scores, Q, k)
+    rc = lib.ann_search_walkers(g.handle, m.handle, _queries_ptr(queries, m, Q), Q,
                                 _dev_ptr(entries, "entries", torch.int32), E, T, k,
                                 _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                                 _dev_ptr(out_ids, "out_ids", torch.int32),
@@ -322,13 +347,14 @@ def ann_search_stream(g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.Te
     """All queries, `slots` of them in flight at a time; a finished query's slot goes to the next one.
     Returns (ids [Q_total,k], scores [Q_total,k])."""
     lib = load_library()
-    Q, E = entries.shape
+    Q, E = _entries_shape(entries)
     if workspace is None:
         workspace = torch.empty(ann_search_stream_workspace_bytes(g, m, Q, slots, E, W, L, k, max_iters),
                                 dtype=torch.uint8, device=queries.device)
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, k, queries.device)
-    rc = lib.ann_search_stream(g.handle, m.handle, _queries_ptr(queries, m), Q,
+    _check_out(out_ids, out_scores, Q, k)
+    rc = lib.ann_search_stream(g.handle, m.handle, _queries_ptr(queries, m, Q), Q,
                                _dev_ptr(entries, "entries", torch.int32), E, slots, W, L, k, max_iters,
                                _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                                _dev_ptr(out_ids, "out_ids", torch.int32),
@@ -360,14 +386,15 @@ def ann_search_layers(graphs: Sequence[Graph], m: Mlp, queries: torch.Tensor, en
                       stream=None):
     """Layer-by-layer search, coarsest graph first; K_l[-1] results per query.  Returns (ids, scores)."""
     lib = load_library()
-    Q, E = entries.shape
+    Q, E = _entries_shape(entries)
     n, handles, W, L, K = _layer_args(graphs, W_l, L_l, K_l)
     if workspace is None:
         workspace = torch.empty(ann_search_layers_workspace_bytes(graphs, m, Q, E, W_l, L_l, K_l, max_iters),
                                 dtype=torch.uint8, device=queries.device)
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, int(K_l[-1]), queries.device)
-    rc = lib.ann_search_layers(handles, n, m.handle, _queries_ptr(queries, m), Q,
+    _check_out(out_ids, out_scores, Q, int(K_l[-1]))
+    rc = lib.ann_search_layers(handles, n, m.handle, _queries_ptr(queries, m, Q), Q,
                                _dev_ptr(entries, "entries", torch.int32), E, W, L, K, max_iters,
                                _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                                _dev_ptr(out_ids, "out_ids", torch.int32),
@@ -380,8 +407,12 @@ def ann_score_pairs(g: Graph, m: Mlp, queries: torch.Tensor, q_idx: torch.Tensor
                     out: Optional[torch.Tensor] = None, tile_rows: int = 0, stream=None) -> torch.Tensor:
     lib = load_library()
     M = q_idx.numel()
+    if item.numel() != M:
+        raise ValueError(f"q_idx names {M} pairs, item {item.numel()}")
     if out is None:
         out = torch.empty(M, dtype=torch.float32, device=queries.device)
+    if out.numel() != M:
+        raise ValueError(f"out must hold {M} scores, got {out.numel()}")
     rc = lib.ann_score_pairs(g.handle, m.handle, _queries_ptr(queries, m), queries.shape[0], M,
                              _dev_ptr(q_idx, "q_idx", torch.int32), _dev_ptr(item, "item", torch.int32),
                              _dev_ptr(out, "out", torch.float32), tile_rows, _stream_ptr(stream))

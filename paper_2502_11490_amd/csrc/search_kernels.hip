@@ -416,6 +416,7 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
             add_to_totals(stats, st.n_visited, st.n_expanded, st.t, (st.done & 2) ? 1 : 0);
         }
     }
+    __syncthreads();  // every wave has read which query the slot served before thread 0 names the next one
     if (threadIdx.x == 0) {
         int next = Q_total;
         // the counter only grows; once it has passed the total nobody needs to touch it again

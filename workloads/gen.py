@@ -325,7 +325,7 @@ def _knn_global(x: torch.Tensor, K: int, budget: int = 1 << 27) -> torch.Tensor:
 
 def layer_sizes(N: int, n_layers: int, growth: int, R: int) -> List[int]:
     """Item counts of the nested layers, coarsest first: each layer `growth` times the one above
-    (Table 5 of the paper: four layers, about 17x per layer); layers too small to give every
+    (the paper's fourth table, the appendix table of HNSW layer sizes: four layers, about 17x per layer); layers too small to give every
     node R distinct neighbours are left out."""
     sizes = [-(-N // growth ** (n_layers - 1 - l)) for l in range(n_layers)]
     return [n for n in sizes if n > R]
