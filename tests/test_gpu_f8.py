@@ -14,6 +14,10 @@ from workloads import PRESETS, make_workload, random_mlp, scaled, to_host
 
 pytestmark = pytest.mark.gpu
 
+# Budget of the 8-bit metric against the exact (unquantised, fp64) oracle: mean and largest |relevance error|
+# over random pairs, and recall@k lost against the exact oracle's search at equal L.
+F8_MEAN_BUDGET, F8_MAX_BUDGET, F8_RECALL_BUDGET = 1e-2, 6e-2, 0.05
+
 ann = pytest.importorskip("paper_2502_11490_amd")
 sys.path.insert(0, os.path.dirname(__file__))
 from gpu_util import oracle_mlp, same_list_fraction  # noqa: E402
@@ -96,8 +100,11 @@ def test_relevance_f8(preset):
     cost = np.abs(got - exact)
     print(f"{preset} 8-bit metric against the unquantised one: mean |error| {cost.mean():.4f}, max {cost.max():.4f}; "
           f"against the oracle at the kernel's precision: median {np.median(err):.2e}, max {err.max():.2e}")
-    # the price of 3 mantissa bits (relative rounding error up to 1/16 per operand), reported; a loose guard here
-    assert cost.mean() <= 0.03 and cost.max() <= 0.15
+    # The budget of the 8-bit metric against the relevance the paper defines (the exact oracle): three mantissa
+    # bits are a relative rounding error of up to 1/16 per operand; over items, two weight matrices and two
+    # hidden layers that is a mean error of the relevance below 1e-2 and a largest one below 6e-2.  The 16-bit
+    # bar (1e-2 for every pair) is NOT met by this format, and the tests of the 16-bit modes do not use it.
+    assert cost.mean() <= F8_MEAN_BUDGET and cost.max() <= F8_MAX_BUDGET, (cost.mean(), cost.max())
 
 
 def test_relevance_f8_out_of_range_pairs_are_nan():
@@ -131,6 +138,7 @@ def test_search_f8_recall_matches_oracle(preset):
           f"precision {r_kern:.4f}, oracle with the unquantised metric {r_exact:.4f}; identical lists vs the "
           f"kernel-precision oracle {same_list_fraction(ids, kern['ids']):.3f}")
     assert abs(r_gpu - r_kern) <= 0.01 + 1e-9
+    assert r_exact - r_gpu <= F8_RECALL_BUDGET, (r_exact, r_gpu)   # what the format may cost in recall
     valid = ids.ravel() >= 0
     qq = np.repeat(np.arange(cfg.Q), k).astype(np.int32)[valid]
     ref = oracle.score_pairs(v["emb"], v["users"], v["mlp_q"], qq, ids.ravel()[valid], act_round=2, n_threads=8)
