@@ -284,6 +284,24 @@ int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_de
                     int64_t M, const int32_t *q_idx_dev, const int32_t *item_dev, float *out_dev,
                     int32_t tile_rows, void *stream);
 
+/*
+ * ann_score_pairs for callers that cannot allocate device memory: code whose stream is being recorded
+ * into a HIP graph, tight serving loops, harnesses that forbid allocation.  Same arguments and result as
+ * ann_score_pairs (default batch size); the call makes no allocation of any kind and does not
+ * synchronise: it only enqueues kernels on `stream`, and out_dev is valid once they have run.
+ * What ann_score_pairs keeps in a temporary (the pair count the kernels read, the per-query user term of
+ * the first layer, Q x first-hidden-width fp32) lives in a fixed array inside the library, 8 MiB + 384 bytes,
+ * one copy on every GPU the library runs on, held until the process ends.
+ * Limits: Q * first hidden width <= 2^21 (ANN_EINVAL beyond, with the reason in ann_last_error); the
+ * metric's device must be the current device.
+ * Every call on a GPU uses that GPU's one array: calls on the same stream follow each other and are safe;
+ * calls that may overlap in time on one GPU (different streams, different host threads) race and give
+ * wrong scores.  The array keeps the last call's contents; nothing in it needs clearing between calls.
+ */
+int ann_score_pairs_noalloc(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
+                            int64_t M, const int32_t *q_idx_dev, const int32_t *item_dev, float *out_dev,
+                            void *stream);
+
 /* Waits for `stream`, then copies the counters of the last search run on workspace_dev. */
 int ann_search_stats(const void *workspace_dev, ann_stats *out_host, void *stream);
 

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     ann_profile_enable,
     ann_profile_read,
     ann_score_pairs,
+    ann_score_pairs_noalloc,
     ann_users_add_noise,
     ann_quantize_e4m3,
     ann_search,

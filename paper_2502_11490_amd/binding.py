@@ -21,7 +21,7 @@ EXPORTS = [
     "ann_graph_load", "ann_graph_free", "ann_mlp_load", "ann_mlp_free", "ann_mlp_uses_mfma",
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
     "ann_search_layers", "ann_search_walkers_workspace_bytes", "ann_search_walkers",
-    "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs", "ann_users_add_noise", "ann_quantize_e4m3",
+    "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs", "ann_score_pairs_noalloc", "ann_users_add_noise", "ann_quantize_e4m3",
     "ann_search_stats", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
@@ -87,6 +87,8 @@ def load_library():
     lib.ann_search_stream.restype = ctypes.c_int
     lib.ann_score_pairs.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, i32, vp]
     lib.ann_score_pairs.restype = ctypes.c_int
+    lib.ann_score_pairs_noalloc.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, vp]
+    lib.ann_score_pairs_noalloc.restype = ctypes.c_int
     lib.ann_users_add_noise.argtypes = [vp, vp, i32, i32, i32, ctypes.c_double, ctypes.c_uint64, ctypes.c_uint64, vp]
     lib.ann_users_add_noise.restype = ctypes.c_int
     lib.ann_quantize_e4m3.argtypes = [vp, i32, i64, ctypes.c_float, vp, vp]
@@ -416,6 +418,21 @@ def ann_score_pairs(g: Graph, m: Mlp, queries: torch.Tensor, q_idx: torch.Tensor
     rc = lib.ann_score_pairs(g.handle, m.handle, _queries_ptr(queries, m), queries.shape[0], M,
                              _dev_ptr(q_idx, "q_idx", torch.int32), _dev_ptr(item, "item", torch.int32),
                              _dev_ptr(out, "out", torch.float32), tile_rows, _stream_ptr(stream))
+    _check(rc)
+    return out
+
+
+def ann_score_pairs_noalloc(g: Graph, m: Mlp, queries: torch.Tensor, q_idx: torch.Tensor, item: torch.Tensor,
+                            out: torch.Tensor, stream=None) -> torch.Tensor:
+    """ann_score_pairs without any allocation: `out` ([M] fp32) is the caller's, the library's scratch is a
+    fixed array on the device.  Only enqueues; synchronise the stream before reading `out`."""
+    lib = load_library()
+    M = q_idx.numel()
+    if item.numel() != M or out.numel() != M:
+        raise ValueError(f"q_idx names {M} pairs, item {item.numel()}, out {out.numel()}")
+    rc = lib.ann_score_pairs_noalloc(g.handle, m.handle, _queries_ptr(queries, m), queries.shape[0], M,
+                                     _dev_ptr(q_idx, "q_idx", torch.int32), _dev_ptr(item, "item", torch.int32),
+                                     _dev_ptr(out, "out", torch.float32), _stream_ptr(stream))
     _check(rc)
     return out
 
