@@ -139,7 +139,8 @@ size_t ann_search_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t 
  * one can: it launches kernels only).  Work enqueued on `stream` before the call is waited for as
  * long as it takes; ANN_EDEVICE if the stream reports an error or runs dry without the progress
  * the kernels report.
- * Limits: W*R <= 1024, max(L,k) + W*R <= 4096, E <= 1024.
+ * Limits: W*R <= 1024, E <= 1024; L and k are bounded by the workspace only (the list of a query lives in
+ * device memory, 8 bytes per entry, and is merged in place through a tile in LDS).
  * Returns ANN_EWORKSPACE (results still written, for the truncated search) if the call
  * waited on the stream and saw a query fill its visited table; with max_iters > 0 use
  * ann_search_stats to learn about that.

@@ -63,12 +63,10 @@ bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32
     p->max_iters_max = max_iters_max;
     p->C = L_max > k ? L_max : k;
     p->slots = W_max * g->R > E ? W_max * g->R : E;
-    if ((int64_t)p->C + p->slots > MAX_SORT) {
-        set_error("max(L,k) + max(W*R,E) = %lld exceeds %d", (long long)p->C + p->slots, MAX_SORT);
+    if ((int64_t)Q * p->C > (1ll << 40)) {
+        set_error("Q * max(L,k) = %lld list entries is beyond any workspace", (long long)Q * p->C);
         return false;
     }
-    p->sort_n = next_pow2(p->C + p->slots);
-    if (p->sort_n < 2) p->sort_n = 2;
     // ids one query can score: seeds + rounds * W * R with a cap; without one, (2*L + 32*W) * R ids are
     // assumed (twice the expansions a list of L entries needs, plus slack for short lists)
     int64_t rounds = max_iters_max > 0 ? max_iters_max : 2 * (int64_t)((L_max + W_max - 1) / W_max) + 32;
@@ -287,10 +285,6 @@ static int run_search(SearchArgs &a) {
         if ((rc = score_batch(a)) != ANN_OK) return rc;
         {
             StageTimer timer(ANN_STAGE_ROUND, a.stream);
-            if (box) {
-                const int64_t n = box->running(a.mail_tag);
-                a.speculate = n < 0 || 2 * n >= p.Q;
-            }
             if ((rc = launch_round(a)) != ANN_OK) return rc;
         }
     }
@@ -351,10 +345,6 @@ static int run_stream(SearchArgs &a) {
         if ((rc = score_batch(a)) != ANN_OK) return rc;
         {
             StageTimer timer(ANN_STAGE_ROUND, a.stream);
-            if (box) {
-                const int64_t n = box->running(a.mail_tag);
-                a.speculate = n < 0 || 2 * n >= p.Q;
-            }
             if ((rc = launch_round(a)) != ANN_OK) return rc;
         }
     }

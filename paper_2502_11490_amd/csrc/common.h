@@ -14,7 +14,6 @@ constexpr int MAX_LAYERS = 8;
 constexpr int MAX_WIDTH = 2048;
 constexpr int MAX_HEADS = 8;
 constexpr int MAX_WR = 1024;        // W*R survivors per query and round
-constexpr int MAX_SORT = 4096;      // max(L,k) + W*R entries sorted in LDS
 constexpr int MAX_E = 1024;
 constexpr uint32_t EMPTY_SLOT = 0xFFFFFFFFu;
 constexpr uint64_t KEY_SENTINEL = 0xFFFFFFFFFFFFFFFFull;
@@ -89,7 +88,6 @@ struct Plan {
     int32_t Q, E, W_max, L_max, k, C, R, max_iters_max, rounds_assumed;
     int32_t slots;          // survivors kept per query and round: max(W_max*R, E)
     int32_t hash_cap;       // per-query visited table entries (power of two)
-    int32_t sort_n;         // power of two >= C + slots
     int64_t M_max;          // Q * slots
     int32_t H1;             // first hidden width (user-half pre-activations), 0 if unused
     size_t off_ctrl, off_state, off_pool, off_hash, off_cand, off_tag, off_counts, off_offsets,
@@ -106,14 +104,17 @@ struct Ctrl {
 };
 
 // Per-query state at off_state.
-struct QState {
+struct alignas(16) QState {
     int32_t t;            // rounds done
     int32_t done;         // bit 0 = finished, bit 1 = stopped because its visited table was full
     int32_t n_list;       // entries in the list
     int32_t n_visited;    // ids in the visited table = pairs scored for this query
     int32_t W, L, cap;    // this query's parameters
     int32_t n_expanded;   // nodes whose neighbours were fetched
+    int32_t first_open;   // every list rank below this one has been expanded (a lower bound of the first open rank)
+    int32_t pad[3];
 };
+static_assert(sizeof(QState) == 48, "QState is read and written as three 16-byte pieces");
 
 bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32_t W_max,
                int32_t L_max, int32_t k, int32_t max_iters_max, Plan *p);
@@ -142,8 +143,6 @@ struct SearchArgs {
     uint64_t *mailbox = nullptr;
     uint64_t mail_tag = 0;
     int32_t round_index = 0;
-    // round kernel: request a query's list before knowing whether the query still runs (right while most do)
-    bool speculate = true;
 };
 
 // search_kernels.hip

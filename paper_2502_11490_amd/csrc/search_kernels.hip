@@ -331,6 +331,8 @@ __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entri
         s.L = min(max(l, 1), L_max);
         s.cap = cap_max > 0 ? min(max(c, 1), cap_max) : max(c, 0);
         s.n_expanded = 0;
+        s.first_open = 0;
+        s.pad[0] = s.pad[1] = s.pad[2] = 0;
         state[slot] = s;
         counts[slot] = n;
     }
@@ -519,11 +521,23 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
 // ------------------------------------------------------------------------------------------
 // One round of one query.
 //
-// Merge (a6).  Only new entries that can enter the list are kept (better than the current worst
-// entry once the list is full), they are sorted on their own (bitonic, <= W*R keys) and merged
-// with the sorted list by rank: an entry's final position is its index in its own sequence plus
-// the number of entries of the other sequence that precede it (binary search).  Keys are unique
-// (an id is scored once per query), so the ranks are a permutation.
+// The list (a6) lives in global memory, sorted; LDS holds only the new entries of the round and one
+// tile of the list at a time, so the list may be as long as the workspace allows.
+//
+// Merge.  Only new entries that can enter the list are kept (better than the current worst entry once
+// the list is full) and sorted on their own (<= W*R keys).  The list is then walked in tiles from its
+// END towards the front: a tile of old entries is read into LDS, every old entry moves up by the number
+// of new entries that precede it, every new entry that falls behind the tile's first entry goes to its
+// own index plus the number of old entries that precede it (one binary search per entry in each
+// direction), and the walk stops at the tile that takes the smallest new entry: the ranks in front of
+// it do not change and are neither read nor written.  Moving entries towards the end while walking
+// towards the front never overwrites an entry that has not been read yet, so the merge is in place.
+// Keys are unique (an id is scored once per query), so the destinations are a permutation.
+//
+// Choice of parents.  The state keeps `first_open`, a rank below which every entry has been expanded
+// (a lower bound of the first unexpanded rank: it falls to the first insertion point of a round and
+// otherwise only grows).  The scan for the first <= W unexpanded entries among the first L ranks starts
+// there, reading the list in pieces of one entry per thread (four per thread after the first piece).
 __device__ __forceinline__ int lower_bound_keys(const uint64_t *a, int n, uint64_t key) {
     int lo = 0, hi = n;
     while (lo < hi) {
@@ -540,35 +554,31 @@ __global__ void __launch_bounds__(BLK) __attribute__((amdgpu_waves_per_eu(8, 8))
 round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, uint64_t *pool_g, int C,
              uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
              const int32_t *__restrict__ offsets, const float *__restrict__ scores, int new_cap,
-             int W_max, int64_t *stats, uint16_t *tag_g, int walkers, int speculate) {
+             int W_max, int64_t *stats, uint16_t *tag_g, int walkers, int tile_keys) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int q = blockIdx.x;
     PHASE_START
-    // LDS: parents and scan scratch first; then one region used twice: by the list buffers until
-    // the list is written back, by the candidate ids and the dedupe table afterwards
+    // LDS: parents and scan scratch first; then one region used twice: by the new entries and the list
+    // tile during the merge, by the candidate ids and the dedupe tables afterwards
     int32_t *parents = (int32_t *)smem;                       // [W_max]
     int *wave_sums = parents + ((W_max + 3) & ~3);            // one per wave + 1, padded to 8
-    uint64_t *keys = (uint64_t *)(wave_sums + 8);             // [C]       merged list
-    uint64_t *oldk = keys + C;                                // [C]       list as stored
-    uint64_t *newk = oldk + C;                                // [new_cap] new entries, sorted
-    uint64_t *best = newk + new_cap;                          // [W_max]   walkers: best new child of each
-    int32_t *cand = (int32_t *)keys;                          // [slots]
+    int *shared_i = wave_sums + 8;                            // [8] values one thread hands to all
+    uint64_t *newk = (uint64_t *)(shared_i + 8);              // [new_cap]   new entries, sorted
+    uint64_t *best = newk + new_cap;                          // [W_max]     walkers: best new child of each
+    uint64_t *tile = best + ((W_max + 1) & ~1);               // [tile_keys] a piece of the stored list
+    int32_t *cand = (int32_t *)newk;                          // [slots]
     uint64_t *pool = pool_g + (size_t)q * C;
     int32_t *cand_q = cand_g + (size_t)q * slots;
     uint16_t *tag_q = tag_g + (size_t)q * slots;
 
-    // Everything the round needs first is requested at once, before any of it is looked at (the
-    // whole list, not only its n_list valid entries): the workgroups of a launch start together,
-    // and every dependent trip to memory costs them all a few microseconds.  Once most queries of the
-    // batch have finished (the host says so, from what the packing kernel last reported; either way
-    // is correct) a workgroup looks first whether its query is still running: a finished one then
-    // costs four bytes instead of its whole list.
-    if (!speculate && counts[q] < 0) return;  // finished or idle: counts[q] stays -1
-    QState st = state[q];
+    // Everything the round needs first is requested at once, before any of it is looked at: the
+    // workgroups of a launch start together, and every dependent trip to memory costs them all a few
+    // microseconds.  (The worst entry is read whether or not the list is full: C >= 1.)
     const int n_prev = counts[q];
+    QState st = state[q];
     const int off = offsets[q];
-#pragma unroll 4
-    for (int i = threadIdx.x; i < C; i += BLK) oldk[i] = pool[i];
+    const uint64_t stored_worst = pool[C - 1];
+    if (n_prev < 0) return;  // finished or idle: counts[q] stays -1
     if (st.done) {
         if (threadIdx.x == 0) counts[q] = -1;
         return;
@@ -582,12 +592,13 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
 
     if (walkers)
         for (int i = threadIdx.x; i < W_max; i += BLK) best[i] = KEY_SENTINEL;
+    if (threadIdx.x == 0) shared_i[0] = 0x7fffffff;  // rank of the first inserted entry
+    __syncthreads();
+    PHASE_MARK(0);  // state load
 
-    // 1. merge the scores of the previous round (or of the seeds) into the sorted list
-    __syncthreads();  // oldk holds the stored list (entries beyond n_list are not used)
-    PHASE_MARK(0);  // state + list load
+    // 1. the scores of the previous round (or of the seeds) become keys; those that cannot enter are dropped
     const bool full = (st.n_list == C);
-    const uint64_t worst = full ? oldk[C - 1] : KEY_SENTINEL;
+    const uint64_t worst = full ? stored_worst : KEY_SENTINEL;
     int m = 0;
     for (int j0 = 0; j0 < n_prev; j0 += BLK) {
         int j = j0 + threadIdx.x;
@@ -605,42 +616,54 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         m += tot;
     }
     PHASE_MARK(1);  // new keys: scores load + filter
-    const uint64_t *list = oldk;
     int n_list = st.n_list;
     if (m > 0) {
-        int m2 = 2;
-        while (m2 < m) m2 <<= 1;
-        if (m <= BLK && 2 * C >= m2) {
-            rank_sort<BLK>(newk, m, (uint32_t *)keys);  // the merged list's buffer is free until the merge below
+        if (m <= BLK && 2 * tile_keys >= BLK) {
+            rank_sort<BLK>(newk, m, (uint32_t *)tile);  // the tile buffer is free until the merge below
         } else {
+            int m2 = 2;
+            while (m2 < m) m2 <<= 1;
             for (int i = m + threadIdx.x; i < m2; i += BLK) newk[i] = KEY_SENTINEL;
             __syncthreads();
             bitonic_sort<BLK>(newk, m2);
         }
         PHASE_MARK(6);  // sort of the new keys
-        for (int i = threadIdx.x; i < st.n_list + m; i += BLK) {
-            uint64_t key;
-            int pos;
-            if (i < st.n_list) {
-                key = oldk[i];
-                pos = i + lower_bound_keys(newk, m, key);
-            } else {
-                key = newk[i - st.n_list];
-                pos = (i - st.n_list) + lower_bound_keys(oldk, st.n_list, key);
+        // 1b. merge into the stored list, tile by tile from the end
+        int hi = st.n_list, rem = m;
+        while (rem > 0) {
+            const int lo = max(0, hi - tile_keys), cnt = hi - lo;
+            for (int i = threadIdx.x; i < cnt; i += BLK) tile[i] = pool[lo + i];
+            __syncthreads();
+            // new entries [0, nlo) precede the tile's first entry: they belong to tiles further front
+            const int nlo = (lo == 0) ? 0 : lower_bound_keys(newk, rem, tile[0]);
+            for (int i = threadIdx.x; i < cnt; i += BLK) {
+                const uint64_t key = tile[i];
+                const int lb = nlo + lower_bound_keys(newk + nlo, rem - nlo, key);
+                const int dest = lo + i + lb;
+                if (lb > 0 && dest < C) pool[dest] = key;  // lb = 0: the entry stays where it is
             }
-            if (pos < C) keys[pos] = key;
+            for (int j = nlo + threadIdx.x; j < rem; j += BLK) {
+                const uint64_t key = newk[j];
+                const int dest = j + lo + lower_bound_keys(tile, cnt, key);
+                if (dest < C) pool[dest] = key;
+                if (j == 0) shared_i[0] = dest;
+            }
+            __syncthreads();  // the tile buffer is free again
+            hi = lo;
+            rem = nlo;
         }
         n_list = min(C, st.n_list + m);
-        list = keys;
+        // the scan below reads entries this workgroup has just stored
+        __threadfence_block();
+        __syncthreads();
     }
-    __syncthreads();
-    PHASE_MARK(2);  // sort + rank merge
-    uint64_t *lw = const_cast<uint64_t *>(list);
+    PHASE_MARK(2);  // rank merge
 
     // 2. termination test and choice of the parents
     int n_par = 0, n_live = 0;
     const bool capped = (st.cap > 0 && st.t >= st.cap);
     const int lim = walkers ? 0 : min(st.L, n_list);
+    int first_open = min(st.first_open, shared_i[0]);
     if (walkers && !capped) {
         // Paper-literal variant (Alg. 1 read as independent walkers): walker s moves to the best of the
         // neighbours it scored last round (round 0: to its seed); a walker without one is dead (-1) and
@@ -656,35 +679,49 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         n_par = n_live > 0 ? st.W : 0;
     }
     if (!capped && !walkers) {
-        for (int i0 = 0; i0 < lim && n_par < st.W; i0 += BLK) {
-            int i = i0 + threadIdx.x;
-            bool open = (i < lim) && !key_expanded(lw[i]);
-            int tot;
-            int pos = block_excl_count<BLK>(open, wave_sums, &tot);
-            if (open && n_par + pos < st.W) {
-                parents[n_par + pos] = key_id(lw[i]);
-                lw[i] |= 1ull;
-                pool[i] = lw[i];  // ranks below the first inserted entry are not rewritten below
+        int i0 = first_open;
+        bool first_piece = true;
+        while (i0 < lim && n_par < st.W) {
+            // one entry per thread in the first piece (the parents are nearly always found there), four in the
+            // later ones: all four are requested before the first is looked at
+            const int per = first_piece ? 1 : 4;
+            uint64_t e[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * BLK + (int)threadIdx.x;
+                e[u] = (u < per && i < lim) ? pool[i] : KEY_SENTINEL;
             }
-            n_par = min(st.W, n_par + tot);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (u >= per || i0 >= lim || n_par >= st.W) break;  // uniform over the workgroup
+                const int i = i0 + (int)threadIdx.x;
+                const bool open = (i < lim) && !key_expanded(e[u]);
+                int tot;
+                const int pos = block_excl_count<BLK>(open, wave_sums, &tot);
+                if (open && n_par + pos < st.W) {
+                    parents[n_par + pos] = key_id(e[u]);
+                    pool[i] = e[u] | 1ull;
+                    if (n_par + pos == st.W - 1) shared_i[1] = i + 1;  // everything in front of it is expanded now
+                }
+                first_open = (n_par + tot >= st.W) ? -1 : min(i0 + BLK, lim);  // -1: taken from shared_i[1] below
+                n_par = min(st.W, n_par + tot);
+                i0 += BLK;
+            }
+            first_piece = false;
         }
     }
     __syncthreads();
+    if (first_open < 0) first_open = shared_i[1];
     // a visited table that could not take this round's ids ends the query
     bool overflow = false;
     if (n_par > 0 && (int64_t)st.n_visited + (int64_t)n_par * R > (int64_t)(hash_cap / 2)) {
         overflow = true;
         n_par = 0;
     }
-    // write back what moved: the ranks from the first inserted entry on (the chosen parents
-    // have already stored their expanded bit)
-    if (m > 0) {
-        const int first_moved = lower_bound_keys(oldk, st.n_list, newk[0]);
-        for (int i = first_moved + threadIdx.x; i < n_list; i += BLK) pool[i] = lw[i];
-    }
     if (n_par == 0) {
         if (threadIdx.x == 0) {
             st.n_list = n_list;
+            st.first_open = first_open;
             st.done = overflow ? 3 : 1;
             state[q] = st;
             counts[q] = -1;
@@ -693,8 +730,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     }
 
     // 3. neighbour gather: one adjacency row per parent, consecutive lanes read consecutive ids
-    __syncthreads();  // the list buffers are dead from here on; their LDS is reused
-    PHASE_MARK(3);  // selection + write-back
+    PHASE_MARK(3);  // selection
     const int n_cand = n_par * R;
     for (int j = threadIdx.x; j < n_cand; j += BLK) {
         int p = j / R, s = j - p * R;
@@ -709,6 +745,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     PHASE_MARK(5);  // dedupe + visited table
     if (threadIdx.x == 0) {
         st.n_list = n_list;
+        st.first_open = first_open;
         st.t += 1;
         st.n_visited += n_new;
         st.n_expanded += walkers ? n_live : n_par;
@@ -748,12 +785,20 @@ static int new_cap_of(const Plan &p) {
     return n;
 }
 
+// Entries of the stored list that the round kernel holds in LDS at a time during the merge: the whole list
+// when it is short, a quarter of a long one, at most 4,096 (32 KB).
+static int tile_keys_of(const Plan &p) {
+    int t = 1024;
+    while (t < 4096 && 4 * t < p.C) t <<= 1;
+    return t;
+}
+
 static size_t round_smem(const Plan &p) {
     int dd_n = 2;
     while (dd_n < 2 * p.slots) dd_n <<= 1;
-    size_t lists = (size_t)(2 * p.C + new_cap_of(p) + p.W_max) * 8;
+    size_t lists = (size_t)(new_cap_of(p) + ((p.W_max + 1) & ~1) + tile_keys_of(p)) * 8;
     size_t filt = (size_t)((p.slots + 3) & ~3) * 4 + (size_t)dd_n * 16;
-    return (size_t)((p.W_max + 3) & ~3) * 4 + 8 * 4 + (lists > filt ? lists : filt);
+    return (size_t)((p.W_max + 3) & ~3) * 4 + 16 * 4 + (lists > filt ? lists : filt);
 }
 
 static size_t seed_smem(const Plan &p) {
@@ -834,7 +879,7 @@ int launch_round(const SearchArgs &a) {
                        (int32_t *)(a.ws + p.off_counts), (const int32_t *)(a.ws + p.off_offsets),
                        (const float *)(a.ws + p.off_scores), new_cap_of(p), p.W_max,
                        (int64_t *)(a.ws + p.off_stats), (uint16_t *)(a.ws + p.off_tag), a.walkers ? 1 : 0,
-                       a.speculate ? 1 : 0);
+                       tile_keys_of(p));
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }

@@ -116,7 +116,11 @@ def test_search_fp32_tiny_config_matches_oracle():
 
 
 @pytest.mark.parametrize("W,L,k,E,cap", [(1, 8, 8, 1, 0), (4, 16, 40, 3, 0), (3, 24, 10, 2, 5), (8, 20, 100, 4, 3),
-                                         (64, 100, 50, 5, 2)])
+                                         (64, 100, 50, 5, 2),
+                                         # lists of several LDS tiles (the merge walks them from the end), k > L,
+                                         # full-width rounds
+                                         (4, 1500, 2000, 2, 0), (8, 2500, 100, 4, 0), (64, 4500, 4600, 5, 0),
+                                         (5, 1024, 1024, 1, 40), (2, 1025, 7, 3, 0)])
 def test_search_fp32_parameter_sweep(W, L, k, E, cap):
     cfg = replace(scaled(PRESETS["C1"], 5000, n_clusters=8, Q=40), E=E)
     wl = _with_biases(make_workload(cfg, seed=99), cfg, 14)
@@ -132,6 +136,27 @@ def test_search_fp32_parameter_sweep(W, L, k, E, cap):
         assert st.nodes_expanded == int(ref["n_expanded"].sum())
         assert st.max_query_iters == int(ref["n_iters"].max())
     assert st.visited_overflow == 0 and st.queries == cfg.Q
+
+
+@pytest.mark.parametrize("W,L,k", [(32, 9000, 200), (64, 20000, 100)])
+def test_search_fp32_very_long_list(W, L, k):
+    """Lists far beyond what LDS holds (tiles of 4,096 entries): identical to the oracle's."""
+    cfg = replace(scaled(PRESETS["C1"], 40000, n_clusters=40, Q=12), E=6)
+    wl = _with_biases(make_workload(cfg, seed=123), cfg, 15)
+    g, m, dev = open_handles(wl)
+    ws = torch.empty(ann.ann_search_workspace_bytes(g, m, cfg.Q, cfg.E, W, L, k, 0), dtype=torch.uint8, device="cuda")
+    ids, sc = ann.ann_search(g, m, dev["users"], dev["entries"], W, L, k, 0, workspace=ws)
+    ref = _oracle_search(to_host(wl), W, L, k, 0, trace=True)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    assert same_list_fraction(ids, ref["ids"]) >= 0.99
+    same = ids == ref["ids"]
+    np.testing.assert_allclose(sc[same], ref["scores"][same], rtol=1e-5)
+    st = ann.ann_search_stats(ws)
+    if same_list_fraction(ids, ref["ids"]) == 1.0:
+        assert st.pairs_scored == int(ref["n_scored"].sum())
+        assert st.nodes_expanded == int(ref["n_expanded"].sum())
+        assert st.max_query_iters == int(ref["n_iters"].max())
+    assert st.visited_overflow == 0
 
 
 def test_search_invalid_and_repeated_seeds_and_padding():
