@@ -100,8 +100,8 @@ bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32
     o = align256(o + (size_t)Q * p->slots * 4);
     p->off_tag = o;  // which parent (or seed) produced each survivor
     o = align256(o + (size_t)Q * p->slots * 2);
-    p->off_counts = o;
-    o = align256(o + (size_t)Q * 4);
+    p->off_counts = o;  // Q counts padded to a multiple of 256, then two arrays of ceil(Q / 256) group sums
+    o = align256(o + ((size_t)((Q + 255) & ~255) + 2 * (size_t)((Q + 255) >> 8)) * 4);
     p->off_offsets = o;
     o = align256(o + (size_t)Q * 4);
     p->off_pair_q = o;

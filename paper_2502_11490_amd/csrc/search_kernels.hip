@@ -286,9 +286,21 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
 
 // Counters and control block start at zero (a kernel, not a memset, so that a caller may
 // capture the launch sequence into a HIP graph).
-__global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q, int keep_stats) {
+// Group sums of the survivor counts, for the packing step: behind the Q counts (padded to a multiple of 256)
+// sit two arrays of ceil(Q / 256) sums, used alternately.  Whoever sets a query's count to n >= 0 (seeding, the
+// round kernel) adds n to the sum of the query's group of 256 in the array the next packing step reads; that
+// step clears the other array for the round after it.  A packing workgroup then reads the sums of the groups
+// in front of its queries and at most 255 single counts instead of every earlier count.
+__host__ __device__ __forceinline__ int count_groups(int Q) { return (Q + 255) >> 8; }
+__device__ __forceinline__ int32_t *group_sums(int32_t *counts, int Q, int which) {
+    return counts + ((Q + 255) & ~255) + (which & 1) * count_groups(Q);
+}
+
+__global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q, int keep_stats, int32_t *counts) {
     if (threadIdx.x < 16 && !keep_stats) stats[threadIdx.x] = (threadIdx.x == 4) ? Q : 0;
     if (threadIdx.x < 16) ((int32_t *)ctrl)[threadIdx.x] = 0;
+    int32_t *gs = group_sums(counts, Q, 0);
+    for (int i = threadIdx.x; i < 2 * count_groups(Q); i += blockDim.x) gs[i] = 0;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -299,7 +311,8 @@ template <int BLK>
 __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entries, int E, int64_t N, QState *state,
                           uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
                           const int32_t *W_q, const int32_t *L_q, const int32_t *cap_q, int W, int L, int cap,
-                          int W_max, int L_max, int cap_max, int64_t *stats, unsigned char *smem, uint16_t *tag_g) {
+                          int W_max, int L_max, int cap_max, int64_t *stats, unsigned char *smem, uint16_t *tag_g,
+                          int n_slots, int which_sums) {
     int dd_n = 2;
     while (dd_n < 2 * E) dd_n <<= 1;
     int32_t *cand = (int32_t *)smem;                 // [E]
@@ -335,6 +348,7 @@ __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entri
         s.pad[0] = s.pad[1] = s.pad[2] = 0;
         state[slot] = s;
         counts[slot] = n;
+        if (n > 0) atomicAdd(&group_sums(counts, n_slots, which_sums)[slot >> 8], n);
     }
 }
 
@@ -345,7 +359,7 @@ init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state
             int cap_max, int64_t *stats, uint16_t *tag_g) {
     extern __shared__ __align__(16) unsigned char smem[];
     seed_slot<BLOCK>(blockIdx.x, blockIdx.x, entries, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W,
-              L, cap, W_max, L_max, cap_max, stats, smem, tag_g);
+              L, cap, W_max, L_max, cap_max, stats, smem, tag_g, gridDim.x, 0);
 }
 
 // A query's counters join the totals once, when its result is written: every workgroup adding to the
@@ -398,6 +412,7 @@ __global__ void stream_reset_kernel(int64_t *stats, Ctrl *ctrl, QState *state, i
         counts[i] = -1;
         slot_query[i] = -1;
     }
+    if (i < 2 * count_groups(S)) group_sums(counts, S, 0)[i] = 0;
 }
 
 __global__ void __launch_bounds__(BLOCK)
@@ -405,7 +420,7 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
              int32_t *cand_g, int slots, int32_t *counts, const int32_t *W_q, const int32_t *L_q,
              const int32_t *cap_q, int W, int L, int cap, int W_max, int L_max, int cap_max, int64_t *stats,
              Ctrl *ctrl, int32_t *slot_query, int Q_total, const uint64_t *pool_g, int C, int k, int32_t *out_ids,
-             float *out_scores, uint16_t *tag_g) {
+             float *out_scores, uint16_t *tag_g, int which_sums) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int next_s;
     const int slot = blockIdx.x;
@@ -431,37 +446,45 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
     const int next = next_s;
     if (next < 0) return;
     seed_slot<BLOCK>(slot, next, entries, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W, L, cap,
-              W_max, L_max, cap_max, stats, smem, tag_g);
+              W_max, L_max, cap_max, stats, smem, tag_g, gridDim.x, which_sums);
 }
 
 // ------------------------------------------------------------------------------------------
 // Exclusive scan of survivor counts + stable packing into the dense pair list (Algorithm 2).
 // A workgroup owns SCAN_QPB consecutive queries (4 or 8: few, so that many workgroups share the
-// copying).  It first sums the counts of all earlier queries (every workgroup re-reads them from
-// L2: O(Q^2 / SCAN_QPB) four-byte reads in total, no waiting on other workgroups, the same result
-// every run), then scans its own counts and copies its groups, one wave per query at a time.
+// copying).  The pairs in front of its first query are the sums of the groups of 256 queries in front
+// of it (kept by whoever writes a count, see group_sums) plus at most 255 single counts: no waiting on
+// other workgroups, the same result every run.  It then scans its own counts and copies its groups,
+// one wave per query at a time.  The last workgroup also counts the running queries and reports.
 template <int SCAN_QPB>  // queries per workgroup, a multiple of 4
 __global__ void __launch_bounds__(SCAN_BLOCK)
-scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__restrict__ cand_g, int slots,
+scan_compact_kernel(int32_t *counts_rw, int Q, const int32_t *__restrict__ cand_g, int slots,
                     int32_t *offsets, int32_t *pair_q, int32_t *pair_id, Ctrl *ctrl,
-                    const int32_t *__restrict__ slot_query, uint64_t *mailbox, uint64_t mail_word, int Q_total) {
+                    const int32_t *__restrict__ slot_query, uint64_t *mailbox, uint64_t mail_word, int Q_total,
+                    int which_sums) {
     __shared__ int red[SCAN_WAVES];
     __shared__ int red_active[SCAN_WAVES];
     __shared__ int loc_off[SCAN_QPB + 1];
     __shared__ int loc_cnt[SCAN_QPB];
+    const int32_t *counts = counts_rw;
     const int q0 = blockIdx.x * SCAN_QPB;
     const bool last = (blockIdx.x == gridDim.x - 1);
-    // pairs of all earlier queries (and, in the last workgroup, the number of running queries)
+    const int32_t *sums = group_sums(counts_rw, Q, which_sums);
+    if (blockIdx.x == 0) {  // the other array starts the next round at zero
+        int32_t *other = group_sums(counts_rw, Q, which_sums + 1);
+        for (int i = threadIdx.x; i < count_groups(Q); i += SCAN_BLOCK) other[i] = 0;
+    }
     int sum = 0, act = 0;
-    const int lim = last ? Q : q0;
-    // q0 is a multiple of 4 and the array is 256-byte aligned: four counts per load up to q0
+    const int g0 = q0 >> 8;
+    for (int g = threadIdx.x; g < g0; g += SCAN_BLOCK) sum += sums[g];
+    // q0 is a multiple of 4 and the array is 256-byte aligned: four counts per load from the group's start up to q0
     const int4 *counts4 = (const int4 *)counts;
-    for (int i4 = threadIdx.x; i4 < (q0 >> 2); i4 += SCAN_BLOCK) {
+    for (int i4 = (g0 << 6) + threadIdx.x; i4 < (q0 >> 2); i4 += SCAN_BLOCK) {
         const int4 c = counts4[i4];
         sum += max(c.x, 0) + max(c.y, 0) + max(c.z, 0) + max(c.w, 0);
-        act += (c.x >= 0) + (c.y >= 0) + (c.z >= 0) + (c.w >= 0);
     }
-    for (int i = q0 + threadIdx.x; i < lim; i += SCAN_BLOCK) act += (counts[i] >= 0);  // last workgroup only
+    if (last)  // running queries of the whole batch
+        for (int i = threadIdx.x; i < Q; i += SCAN_BLOCK) act += (counts[i] >= 0);
     for (int o = 32; o > 0; o >>= 1) {
         sum += __shfl_down(sum, o);
         act += __shfl_down(act, o);
@@ -554,7 +577,7 @@ __global__ void __launch_bounds__(BLK) __attribute__((amdgpu_waves_per_eu(8, 8))
 round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, uint64_t *pool_g, int C,
              uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
              const int32_t *__restrict__ offsets, const float *__restrict__ scores, int new_cap,
-             int W_max, int64_t *stats, uint16_t *tag_g, int walkers, int tile_keys) {
+             int W_max, int64_t *stats, uint16_t *tag_g, int walkers, int tile_keys, int which_sums) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int q = blockIdx.x;
     PHASE_START
@@ -751,6 +774,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         st.n_expanded += walkers ? n_live : n_par;
         state[q] = st;
         counts[q] = n_new;
+        if (n_new > 0) atomicAdd(&group_sums(counts, gridDim.x, which_sums)[q >> 8], n_new);
     }
 }
 
@@ -812,7 +836,7 @@ int launch_init(const SearchArgs &a) {
     size_t smem = seed_smem(p);
     int64_t *stats = (int64_t *)(a.ws + p.off_stats);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, a.stream, stats, (Ctrl *)(a.ws + p.off_ctrl), p.Q,
-                       a.keep_stats ? 1 : 0);
+                       a.keep_stats ? 1 : 0, (int32_t *)(a.ws + p.off_counts));
     hipLaunchKernelGGL(init_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.entries, p.E, a.g->N,
                        (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), p.hash_cap,
                        (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q,
@@ -839,7 +863,7 @@ int launch_admit(const SearchArgs &a) {
                        (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q, a.L_q,
                        a.cap_q, a.W, a.L, a.cap, p.W_max, p.L_max, p.max_iters_max, (int64_t *)(a.ws + p.off_stats),
                        (Ctrl *)(a.ws + p.off_ctrl), a.slot_query, a.Q_total, (const uint64_t *)(a.ws + p.off_pool), p.C,
-                       p.k, a.out_ids, a.out_scores, (uint16_t *)(a.ws + p.off_tag));
+                       p.k, a.out_ids, a.out_scores, (uint16_t *)(a.ws + p.off_tag), a.round_index & 1);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
@@ -851,10 +875,10 @@ int launch_scan_compact(const SearchArgs &a) {
     const int blocks = (p.Q + qpb - 1) / qpb;
     auto fn = qpb == 4 ? scan_compact_kernel<4> : scan_compact_kernel<8>;
     hipLaunchKernelGGL(fn, dim3(blocks), dim3(SCAN_BLOCK), 0, a.stream,
-                       (const int32_t *)(a.ws + p.off_counts), p.Q, (const int32_t *)(a.ws + p.off_cand),
+                       (int32_t *)(a.ws + p.off_counts), p.Q, (const int32_t *)(a.ws + p.off_cand),
                        p.slots, (int32_t *)(a.ws + p.off_offsets), (int32_t *)(a.ws + p.off_pair_q),
                        (int32_t *)(a.ws + p.off_pair_id), (Ctrl *)(a.ws + p.off_ctrl), a.slot_query, a.mailbox,
-                       a.mail_tag | ((uint64_t)(uint32_t)(a.round_index + 1) << 1), a.Q_total);
+                       a.mail_tag | ((uint64_t)(uint32_t)(a.round_index + 1) << 1), a.Q_total, a.round_index & 1);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
@@ -879,7 +903,7 @@ int launch_round(const SearchArgs &a) {
                        (int32_t *)(a.ws + p.off_counts), (const int32_t *)(a.ws + p.off_offsets),
                        (const float *)(a.ws + p.off_scores), new_cap_of(p), p.W_max,
                        (int64_t *)(a.ws + p.off_stats), (uint16_t *)(a.ws + p.off_tag), a.walkers ? 1 : 0,
-                       tile_keys_of(p));
+                       tile_keys_of(p), (a.round_index + 1) & 1);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
