@@ -70,6 +70,10 @@ typedef struct ann_stats {
     int64_t max_query_iters; /* largest number of rounds any query ran */
     int64_t visited_overflow;/* queries stopped because their visited table filled up */
     int64_t queries;         /* Q of that search */
+    /* algorithmic bytes of the gather stages: what the method has to move, not what the caches moved */
+    int64_t adjacency_bytes; /* nodes_expanded * R * 4: neighbour gather (Algorithm 1) */
+    int64_t embedding_bytes; /* pairs_scored * bytes of one item row: embedding gather of the MLP stage (Eq. 5) */
+    int64_t pair_list_bytes; /* pairs_scored * 12: user index, item id and score of the dense pair list (Algorithm 2) */
 } ann_stats;
 
 /*
@@ -117,7 +121,11 @@ int ann_mlp_uses_mfma(const ann_mlp *m);
  *     E + rounds * W_max * R ids,  rounds = max_iters_max > 0 ? max_iters_max
  *                                                            : 2 * ceil(L_max / W_max) + 32
  * (at most N).  A query that would outgrow its table stops early and is counted in
- * ann_stats.visited_overflow.  Returns 0 on invalid arguments (see ann_last_error).
+ * ann_stats.visited_overflow.  Where such a table takes a megabyte or more and one bit per item (N / 8 bytes
+ * per query) is at most twice its size, the visited set is that bitmap instead, which cannot fill up.  The
+ * environment variable GMPGR_VISITED_SET = "hash" or "bitmap", read by this call and by every search,
+ * overrides the choice (for measurements and tests; it must not change between sizing and searching).
+ * Returns 0 on invalid arguments (see ann_last_error).
  */
 size_t ann_search_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E,
                                   int32_t W_max, int32_t L_max, int32_t k,
@@ -136,10 +144,10 @@ size_t ann_search_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t 
  * device's progress (a word in pinned host memory that the kernels update every round) to learn
  * when every query has converged, stays a few rounds ahead of the device meanwhile, and waits
  * on `stream` once, at the end (so such a call cannot be recorded into a HIP graph; a capped
- * one can: it launches kernels only).  Work enqueued on `stream` before the call is waited for as
- * long as it takes; ANN_EDEVICE if the stream reports an error or runs dry without the progress
- * the kernels report.
- * Limits: W*R <= 1024, E <= 1024; L and k are bounded by the workspace only (the list of a query lives in
+ * one can: it launches kernels only).  Work enqueued on `stream` before the call is waited for up to
+ * the limit of ann_set_progress_timeout; ANN_EDEVICE if the stream reports an error, runs dry without the
+ * progress the kernels report, or reports nothing within that limit.
+ * Limits: W*R <= 4096, E <= 1024; L and k are bounded by the workspace only (the list of a query lives in
  * device memory, 8 bytes per entry, and is merged in place through a tile in LDS).
  * Returns ANN_EWORKSPACE (results still written, for the truncated search) if the call
  * waited on the stream and saw a query fill its visited table; with max_iters > 0 use
@@ -197,7 +205,7 @@ int ann_search_layers(const ann_graph *const *graphs, int32_t n_layers, const an
 /*
  * Paper-literal inter-candidate search (Algorithm 1 read as independent search processes that
  * share one result container; Sec. 3.2), for comparison with the joint best-first rule of
- * ann_search.  One walker per distinct in-range seed (E <= 1024 / R of them).  Per hop every live
+ * ann_search.  One walker per distinct in-range seed (E <= 1024 and E * R <= 4096).  Per hop every live
  * walker scores the neighbours of its position that no walker of the query has scored before
  * (walkers in seed order, first occurrence wins; all walkers read their neighbours before any
  * moves) and moves to the best of its own newly scored neighbours (score descending, id
@@ -302,6 +310,17 @@ int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_de
 int ann_score_pairs_noalloc(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
                             int64_t M, const int32_t *q_idx_dev, const int32_t *item_dev, float *out_dev,
                             void *stream);
+
+/*
+ * Searches that run until every query has converged (ann_search / ann_search_layers with max_iters = 0,
+ * ann_search_stream) follow the progress word their kernels store to pinned host memory every round.  This sets,
+ * for the whole process, how long such a call waits for the NEXT report while `stream` stays busy before it gives
+ * up with ANN_EDEVICE (default 600 s, 0 = wait for ever).  The limit counts from the last report seen, so work
+ * the caller enqueued on the stream ahead of the search must finish within it too.  A call that gives up has
+ * enqueued only complete rounds; its kernels end by themselves, nothing is left waiting on the device, and the
+ * results are undefined.  While it waits the calling thread yields the core between looks at the word.
+ */
+int ann_set_progress_timeout(double seconds);
 
 /* Waits for `stream`, then copies the counters of the last search run on workspace_dev. */
 int ann_search_stats(const void *workspace_dev, ann_stats *out_host, void *stream);

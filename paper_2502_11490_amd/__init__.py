@@ -35,6 +35,7 @@ from .binding import (  # noqa: F401
     ann_search_walkers_workspace_bytes,
     ann_search_stream_workspace_bytes,
     ann_search_stats,
+    ann_set_progress_timeout,
     ann_search_workspace_bytes,
     lib_path,
     load_library,

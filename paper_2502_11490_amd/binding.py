@@ -14,7 +14,8 @@ ANN_F32, ANN_BF16, ANN_F8, ANN_F16 = 0, 1, 2, 3
 ANN_VALIDATE, ANN_MLP_GENERIC = 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libgmpgr_ann.so")
+# GMPGR_ANN_LIB names another build of the same library (measurement builds with other tuning constants)
+_LIB_PATH = os.environ.get("GMPGR_ANN_LIB") or os.path.join(_HERE, "libgmpgr_ann.so")
 _lib = None
 
 EXPORTS = [
@@ -22,7 +23,7 @@ EXPORTS = [
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
     "ann_search_layers", "ann_search_walkers_workspace_bytes", "ann_search_walkers",
     "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs", "ann_score_pairs_noalloc", "ann_users_add_noise", "ann_quantize_e4m3",
-    "ann_search_stats", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
+    "ann_search_stats", "ann_set_progress_timeout", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
 
@@ -35,7 +36,8 @@ class AnnError(RuntimeError):
 class Stats(ctypes.Structure):
     _fields_ = [("pairs_scored", ctypes.c_int64), ("nodes_expanded", ctypes.c_int64),
                 ("max_query_iters", ctypes.c_int64), ("visited_overflow", ctypes.c_int64),
-                ("queries", ctypes.c_int64)]
+                ("queries", ctypes.c_int64), ("adjacency_bytes", ctypes.c_int64),
+                ("embedding_bytes", ctypes.c_int64), ("pair_list_bytes", ctypes.c_int64)]
 
 
 def lib_path() -> str:
@@ -95,6 +97,8 @@ def load_library():
     lib.ann_quantize_e4m3.restype = ctypes.c_int
     lib.ann_search_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
     lib.ann_search_stats.restype = ctypes.c_int
+    lib.ann_set_progress_timeout.argtypes = [ctypes.c_double]
+    lib.ann_set_progress_timeout.restype = ctypes.c_int
     lib.ann_profile_enable.argtypes = [ctypes.c_int]
     lib.ann_profile_enable.restype = ctypes.c_int
     lib.ann_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -474,6 +478,10 @@ def ann_search_stats(workspace: torch.Tensor, stream=None) -> Stats:
     _check(load_library().ann_search_stats(_dev_ptr(workspace, "workspace", torch.uint8), ctypes.byref(st),
                                            _stream_ptr(stream)))
     return st
+
+
+def ann_set_progress_timeout(seconds: float) -> None:
+    _check(load_library().ann_set_progress_timeout(float(seconds)))
 
 
 STAGES = ("score", "round", "pack")

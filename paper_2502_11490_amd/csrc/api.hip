@@ -3,9 +3,11 @@
 // search_kernels.hip, mlp_alu.hip and mlp_mfma.hip; nothing here computes a score or a rank.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <chrono>
+#include <sched.h>
 #include <new>
 #include <vector>
 
@@ -79,6 +81,18 @@ bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32
         return false;
     }
     p->hash_cap = next_pow2(cap < 64 ? 64 : cap);
+    // one bit per item is the smaller visited set once the table outgrows N / 8 bytes (long lists): all probes
+    // of a batch then fall into a far smaller address range, and seeding has far less to clear
+    // (measured: already faster at 1.2 x the table's size; taken up to twice its size, for tables of a megabyte or
+    // more: a small table is cheaper to clear than a bitmap of all items).  GMPGR_VISITED_SET =
+    // "bitmap" / "hash" overrides the rule, for measurements and for tests of either form at any size.
+    const int64_t words = ((g->N + 31) / 32 + 63) & ~63ll;
+    bool bitmap = p->hash_cap >= (1 << 18) && words <= 2 * (int64_t)p->hash_cap;
+    if (const char *force = getenv("GMPGR_VISITED_SET")) {
+        if (!strcmp(force, "bitmap")) bitmap = true;
+        if (!strcmp(force, "hash")) bitmap = false;
+    }
+    p->bitmap_words = bitmap ? (int32_t)words : 0;
     p->M_max = (int64_t)Q * p->slots;
     if (p->M_max > 0x7fffffffll) {
         set_error("Q * max(W*R,E) = %lld pairs per round exceeds 2^31", (long long)p->M_max);
@@ -95,13 +109,13 @@ bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32
     p->off_pool = o;
     o = align256(o + (size_t)Q * p->C * 8);
     p->off_hash = o;
-    o = align256(o + (size_t)Q * p->hash_cap * 4);
+    o = align256(o + (size_t)Q * (size_t)(p->bitmap_words > 0 ? p->bitmap_words : p->hash_cap) * 4);
     p->off_cand = o;
     o = align256(o + (size_t)Q * p->slots * 4);
     p->off_tag = o;  // which parent (or seed) produced each survivor
     o = align256(o + (size_t)Q * p->slots * 2);
-    p->off_counts = o;  // Q counts padded to a multiple of 256, then two arrays of ceil(Q / 256) group sums
-    o = align256(o + ((size_t)((Q + 255) & ~255) + 2 * (size_t)((Q + 255) >> 8)) * 4);
+    p->off_counts = o;
+    o = align256(o + (size_t)Q * 4);
     p->off_offsets = o;
     o = align256(o + (size_t)Q * 4);
     p->off_pair_q = o;
@@ -124,6 +138,10 @@ bool make_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32
 // three launches that find nothing to do.  "Finished" never reverts, so a late look is safe.
 // One word per host thread; the tag tells a search's word from an older search's.  A thread's 64 pinned
 // bytes are never freed: a destructor at thread exit could run after the runtime has shut down.
+// Longest time an uncapped search waits for the next progress report of its kernels while the stream stays busy
+// (seconds, 0 = no limit); see ann_set_progress_timeout.
+static std::atomic<double> g_wait_limit_s{600.0};
+
 struct Mailbox {
     static constexpr int AHEAD = 4;
     volatile uint64_t *host = nullptr;
@@ -167,14 +185,28 @@ struct Mailbox {
             if (w & 1ull) return 1;
             return (int64_t)((w & 0xFFFFFFFFFFull) >> 1) + AHEAD >= i ? 0 : -2;
         };
-        auto last = std::chrono::steady_clock::now();
+        const auto start = std::chrono::steady_clock::now();
+        auto last = start;
+        uint64_t seen = *host;
         for (int spin = 0;; ++spin) {
-            int r = enough(*host);
+            const uint64_t w = *host;
+            int r = enough(w);
             if (r != -2) return r;
-            if ((spin & 1023) == 1023 && std::chrono::steady_clock::now() - last > std::chrono::milliseconds(20)) {
-                last = std::chrono::steady_clock::now();
+            if (spin > 4096) sched_yield();  // a long wait: let another thread have the core between looks
+            if ((spin & 1023) == 1023) {
+                const auto now = std::chrono::steady_clock::now();
+                if (w != seen) {  // the device is making progress: the limit below counts from the last report
+                    seen = w;
+                    last = now;
+                    continue;
+                }
+                if (now - last <= std::chrono::milliseconds(20)) continue;
                 const hipError_t e = hipStreamQuery(stream);
-                if (e == hipErrorNotReady) continue;
+                if (e == hipErrorNotReady) {
+                    const double limit = g_wait_limit_s.load(std::memory_order_relaxed);
+                    if (limit > 0 && std::chrono::duration<double>(now - last).count() > limit) return -3;
+                    continue;
+                }
                 if (e != hipSuccess) return -1;
                 r = enough(*host);  // the stream is idle: every packing kernel enqueued so far has reported
                 return r != -2 ? r : -1;
@@ -267,13 +299,15 @@ static int run_search(SearchArgs &a) {
     bool overflow_seen = false;
     // a query expands only ids it has scored, so it cannot run more rounds than its visited
     // table holds ids: the loop is bounded even if no query ever reported convergence
-    const int64_t round_limit = capped ? (int64_t)p.max_iters_max : (int64_t)p.hash_cap / 2 + 1;
+    const int64_t round_limit = capped ? (int64_t)p.max_iters_max
+                                       : (p.bitmap_words > 0 ? a.g->N : (int64_t)p.hash_cap / 2) + 1;
     for (int64_t i = 0; i <= round_limit; ++i) {
         if (box) {  // no query is running: nothing left to score or merge
             const int g = box->gate(a.mail_tag, i, a.stream);
             if (g > 0) break;
             if (g < 0) {
-                set_error("the stream failed or ran dry without the search's progress report");
+                set_error(g == -3 ? "no progress report from the search's kernels within the time limit (ann_set_progress_timeout)"
+                                  : "the stream failed or ran dry without the search's progress report");
                 return ANN_EDEVICE;
             }
         }
@@ -322,14 +356,16 @@ static int run_stream(SearchArgs &a) {
     a.mail_tag = box->new_tag();
     // every query ends within hash_cap / 2 + 1 rounds of its admission, and at least one slot is
     // re-used per ceil(Q_total / Q) turn-overs: a generous bound that only guards against a bug
-    const int64_t per_query = p.max_iters_max > 0 ? (int64_t)p.max_iters_max + 2 : (int64_t)p.hash_cap / 2 + 3;
+    const int64_t per_query = p.max_iters_max > 0 ? (int64_t)p.max_iters_max + 2
+                                                  : (p.bitmap_words > 0 ? a.g->N : (int64_t)p.hash_cap / 2) + 3;
     const int64_t round_limit = per_query * (((int64_t)a.Q_total + p.Q - 1) / p.Q + 1);
     for (int64_t i = 0; i <= round_limit; ++i) {
         {   // nothing running after an admission step, and nothing left to admit: every result is written
             const int g = box->gate(a.mail_tag, i, a.stream);
             if (g > 0) break;
             if (g < 0) {
-                set_error("the stream failed or ran dry without the search's progress report");
+                set_error(g == -3 ? "no progress report from the search's kernels within the time limit (ann_set_progress_timeout)"
+                                  : "the stream failed or ran dry without the search's progress report");
                 return ANN_EDEVICE;
             }
         }
@@ -919,6 +955,15 @@ int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_de
     return rc;
 }
 
+int ann_set_progress_timeout(double seconds) {
+    if (!(seconds >= 0.0)) {
+        set_error("the time limit must be >= 0 seconds (0 = none)");
+        return ANN_EINVAL;
+    }
+    g_wait_limit_s.store(seconds, std::memory_order_relaxed);
+    return ANN_OK;
+}
+
 int ann_profile_enable(int on) {
     g_prof.on = on != 0;
     g_prof.used = 0;
@@ -977,6 +1022,9 @@ int ann_search_stats(const void *workspace_dev, ann_stats *out_host, void *strea
     out_host->max_query_iters = st[2];
     out_host->visited_overflow = st[3];
     out_host->queries = st[4];
+    out_host->adjacency_bytes = st[1] * st[5];
+    out_host->embedding_bytes = st[0] * st[6];
+    out_host->pair_list_bytes = st[0] * 12;
     return ANN_OK;
 }
 

@@ -13,7 +13,7 @@ namespace gmpgr {
 constexpr int MAX_LAYERS = 8;
 constexpr int MAX_WIDTH = 2048;
 constexpr int MAX_HEADS = 8;
-constexpr int MAX_WR = 1024;        // W*R survivors per query and round
+constexpr int MAX_WR = 4096;        // W*R candidates per query and round
 constexpr int MAX_E = 1024;
 constexpr uint32_t EMPTY_SLOT = 0xFFFFFFFFu;
 constexpr uint64_t KEY_SENTINEL = 0xFFFFFFFFFFFFFFFFull;
@@ -88,6 +88,7 @@ struct Plan {
     int32_t Q, E, W_max, L_max, k, C, R, max_iters_max, rounds_assumed;
     int32_t slots;          // survivors kept per query and round: max(W_max*R, E)
     int32_t hash_cap;       // per-query visited table entries (power of two)
+    int32_t bitmap_words;   // > 0: the visited set is a bitmap of this many 32-bit words per query instead
     int64_t M_max;          // Q * slots
     int32_t H1;             // first hidden width (user-half pre-activations), 0 if unused
     size_t off_ctrl, off_state, off_pool, off_hash, off_cand, off_tag, off_counts, off_offsets,

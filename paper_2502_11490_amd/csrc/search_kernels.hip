@@ -23,6 +23,21 @@ constexpr int BLOCK = QUERY_BLOCK;     // largest workgroup of the per-query ker
 constexpr int WAVES = BLOCK / 64;
 // The functions below are templates over the workgroup size BLK: the round kernel is also built for
 // half-size workgroups (see launch_round).
+#ifndef ROUND_BIG_FROM
+#define ROUND_BIG_FROM 512   // candidates per query and round above which the round kernel runs larger workgroups
+#endif
+#ifndef FILTER_CHUNK
+#define FILTER_CHUNK 1024   // candidates of a round that pass the visited filter together
+#endif
+#ifndef ROUND_TILE_MAX
+#define ROUND_TILE_MAX 4096   // most list entries held in LDS at a time during the merge
+#endif
+#ifndef ROUND_WAVES_MIN
+#define ROUND_WAVES_MIN 8     // waves per SIMD the round kernel is compiled for (8: at most 64 registers per lane)
+#endif
+#ifndef ROUND_BIG_BLOCK
+#define ROUND_BIG_BLOCK 512
+#endif
 constexpr int SCAN_BLOCK = 256;
 constexpr int SCAN_WAVES = SCAN_BLOCK / 64;
 
@@ -147,7 +162,7 @@ __device__ void rank_sort(uint64_t *keys, int m, uint32_t *cnt) {
 //   cand          : LDS int32[n_cand]
 //   dd_key/dd_pos : LDS uint32[dd_n] each, dd_n a power of two >= 2 * n_cand (dedupe by id)
 //   bk_key/bk_cnt : LDS uint32[dd_n] each (arrivals per bucket in this pass)
-//   out_tag       : global uint16[n_new]: candidate position / tag_div of every survivor
+//   out_tag       : global uint16[n_new]: (tag_base + candidate position) / tag_div of every survivor
 //   table         : global uint32[hash_cap]: hash_cap/16 buckets of 16 slots (one 64-byte line);
 //                   a bucket is filled from slot 0 up, EMPTY_SLOT = free.  An id lives in its home
 //                   bucket or, if that one is full, in the next ones up to the first bucket that
@@ -161,7 +176,8 @@ __device__ void rank_sort(uint64_t *keys, int m, uint32_t *cnt) {
 template <int BLK>
 __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_key, uint32_t *dd_pos,
                                  uint32_t *bk_key, uint32_t *bk_cnt, int dd_n, uint32_t *table, int hash_cap,
-                                 int64_t N, int32_t *out, int *wave_sums, uint16_t *out_tag, int tag_div) {
+                                 int64_t N, int32_t *out, int *wave_sums, uint16_t *out_tag, int tag_div,
+                                 int tag_base = 0) {
     const int n_buckets = hash_cap >> 4;
     const uint32_t bmask = (uint32_t)n_buckets - 1u;
     const int bshift = 32 - (31 - __clz(n_buckets));  // n_buckets = 2^b (b >= 2) -> top b bits
@@ -277,30 +293,128 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
         int pos = block_excl_count<BLK>(fresh, wave_sums, &tot);
         if (fresh) {
             out[n_new + pos] = v;
-            out_tag[n_new + pos] = (uint16_t)(p / tag_div);  // the parent (or seed) it came from
+            out_tag[n_new + pos] = (uint16_t)((tag_base + p) / tag_div);  // the parent (or seed) it came from
         }
         n_new += tot;
     }
     return n_new;
 }
 
-// Counters and control block start at zero (a kernel, not a memset, so that a caller may
-// capture the launch sequence into a HIP graph).
-// Group sums of the survivor counts, for the packing step: behind the Q counts (padded to a multiple of 256)
-// sit two arrays of ceil(Q / 256) sums, used alternately.  Whoever sets a query's count to n >= 0 (seeding, the
-// round kernel) adds n to the sum of the query's group of 256 in the array the next packing step reads; that
-// step clears the other array for the round after it.  A packing workgroup then reads the sums of the groups
-// in front of its queries and at most 255 single counts instead of every earlier count.
-__host__ __device__ __forceinline__ int count_groups(int Q) { return (Q + 255) >> 8; }
-__device__ __forceinline__ int32_t *group_sums(int32_t *counts, int Q, int which) {
-    return counts + ((Q + 255) & ~255) + (which & 1) * count_groups(Q);
+// The same filter over a bitmap of the item ids (one bit per item, N / 8 bytes per query) instead of the hash
+// table: chosen where the bitmap is the smaller of the two (long lists on a moderate item count), because the
+// probes of all queries then fall into a much smaller address range and seeding has much less to clear.
+//   bits : global uint32[ceil(N / 32) rounded up to 64 words], all zero at the start of a search
+// Every first occurrence reads its word (4 bytes); the ones whose bit is clear are new.  New ids that share a
+// word meet in an LDS table keyed by the word index, OR their bits together there, and the one that opened the
+// entry stores word | bits: plain loads and stores, the bitmap belongs to this workgroup alone.
+template <int BLK>
+__device__ int filter_and_mark(const int32_t *cand, int n_cand, uint32_t *dd_key, uint32_t *dd_pos, uint32_t *bk_key,
+                               uint32_t *bk_cnt, int dd_n, uint32_t *bits, int64_t N, int32_t *out, int *wave_sums,
+                               uint16_t *out_tag, int tag_div, int tag_base) {
+    uint32_t pre = 0;  // the first BLK candidates request their word right away (nothing is stored before pass 2)
+    if ((int)threadIdx.x < n_cand) {
+        const int32_t v = cand[threadIdx.x];
+        if (v >= 0 && (int64_t)v < N) pre = bits[(uint32_t)v >> 5];
+    }
+    for (int i = threadIdx.x; i < dd_n; i += BLK) {
+        dd_key[i] = EMPTY_SLOT;
+        dd_pos[i] = 0xFFFFFFFFu;
+        bk_key[i] = EMPTY_SLOT;
+        bk_cnt[i] = 0u;
+    }
+    __syncthreads();
+    const uint32_t dd_mask = (uint32_t)dd_n - 1u;
+    // pass 1: smallest position of every distinct id
+    for (int p = threadIdx.x; p < n_cand; p += BLK) {
+        int32_t v = cand[p];
+        if (v < 0 || (int64_t)v >= N) continue;
+        uint32_t s = hash_id((uint32_t)v) & dd_mask;
+        for (;;) {
+            uint32_t old = atomicCAS(&dd_key[s], EMPTY_SLOT, (uint32_t)v);
+            if (old == EMPTY_SLOT || old == (uint32_t)v) {
+                atomicMin(&dd_pos[s], (uint32_t)p);
+                break;
+            }
+            s = (s + 1u) & dd_mask;
+        }
+    }
+    __syncthreads();
+    // pass 2: first occurrences test their bit; the new ones set it
+    int n_new = 0;
+    for (int p0 = 0; p0 < n_cand; p0 += BLK) {
+        const int p = p0 + threadIdx.x;
+        bool fresh = false, owner = false;
+        int32_t v = -1;
+        uint32_t word = 0, old_word = 0, slot = 0;
+        if (p < n_cand) {
+            v = cand[p];
+            if (v >= 0 && (int64_t)v < N) {
+                uint32_t s = hash_id((uint32_t)v) & dd_mask;
+                while (dd_key[s] != (uint32_t)v) s = (s + 1u) & dd_mask;
+                if (dd_pos[s] == (uint32_t)p) {
+                    word = (uint32_t)v >> 5;
+                    old_word = (p0 == 0) ? pre : bits[word];
+                    fresh = ((old_word >> (v & 31)) & 1u) == 0u;
+                }
+            }
+        }
+        if (fresh) {
+            slot = hash_id(word) & dd_mask;
+            for (;;) {
+                uint32_t old = atomicCAS(&bk_key[slot], EMPTY_SLOT, word);
+                if (old == EMPTY_SLOT || old == word) {
+                    owner = (old == EMPTY_SLOT);
+                    break;
+                }
+                slot = (slot + 1u) & dd_mask;
+            }
+            atomicOr(&bk_cnt[slot], 1u << (v & 31));
+        }
+        __syncthreads();  // every new bit of this pass has reached its LDS entry
+        if (owner) bits[word] = old_word | bk_cnt[slot];
+        int tot;
+        const int pos = block_excl_count<BLK>(fresh, wave_sums, &tot);
+        if (fresh) {
+            out[n_new + pos] = v;
+            out_tag[n_new + pos] = (uint16_t)((tag_base + p) / tag_div);
+        }
+        n_new += tot;
+        if (p0 + BLK < n_cand) {
+            // the words stored above must be seen by the next pass; its ids open fresh LDS entries
+            for (int i = threadIdx.x; i < dd_n; i += BLK) {
+                bk_key[i] = EMPTY_SLOT;
+                bk_cnt[i] = 0u;
+            }
+            __threadfence_block();
+            __syncthreads();
+        }
+    }
+    return n_new;
 }
 
-__global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q, int keep_stats, int32_t *counts) {
-    if (threadIdx.x < 16 && !keep_stats) stats[threadIdx.x] = (threadIdx.x == 4) ? Q : 0;
+// Either form of the visited set: table_cap > 0 = hash table of that many entries, table_cap < 0 = bitmap in a
+// region of -table_cap words.
+template <int BLK>
+__device__ __forceinline__ int visited_filter(const int32_t *cand, int n_cand, uint32_t *dd_key, uint32_t *dd_pos,
+                                              uint32_t *bk_key, uint32_t *bk_cnt, int dd_n, uint32_t *table,
+                                              int table_cap, int64_t N, int32_t *out, int *wave_sums, uint16_t *out_tag,
+                                              int tag_div, int tag_base) {
+    if (table_cap < 0)
+        return filter_and_mark<BLK>(cand, n_cand, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, N, out, wave_sums, out_tag,
+                                    tag_div, tag_base);
+    return filter_and_insert<BLK>(cand, n_cand, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, table_cap, N, out, wave_sums,
+                                  out_tag, tag_div, tag_base);
+}
+
+// Counters and control block start at zero (a kernel, not a memset, so that a caller may
+// capture the launch sequence into a HIP graph).
+// stats[5], stats[6]: bytes of one adjacency row and of one item row, from which ann_search_stats derives the
+// algorithmic bytes of the gather stages.
+__global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q, int keep_stats, int adj_row_bytes,
+                                  int item_row_bytes) {
+    if (threadIdx.x < 16 && !keep_stats)
+        stats[threadIdx.x] = threadIdx.x == 4 ? Q : threadIdx.x == 5 ? adj_row_bytes : threadIdx.x == 6 ? item_row_bytes : 0;
     if (threadIdx.x < 16) ((int32_t *)ctrl)[threadIdx.x] = 0;
-    int32_t *gs = group_sums(counts, Q, 0);
-    for (int i = threadIdx.x; i < 2 * count_groups(Q); i += blockDim.x) gs[i] = 0;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -311,8 +425,7 @@ template <int BLK>
 __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entries, int E, int64_t N, QState *state,
                           uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
                           const int32_t *W_q, const int32_t *L_q, const int32_t *cap_q, int W, int L, int cap,
-                          int W_max, int L_max, int cap_max, int64_t *stats, unsigned char *smem, uint16_t *tag_g,
-                          int n_slots, int which_sums) {
+                          int W_max, int L_max, int cap_max, int64_t *stats, unsigned char *smem, uint16_t *tag_g) {
     int dd_n = 2;
     while (dd_n < 2 * E) dd_n <<= 1;
     int32_t *cand = (int32_t *)smem;                 // [E]
@@ -322,17 +435,19 @@ __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entri
     uint32_t *bk_cnt = bk_key + dd_n;
     int *wave_sums = (int *)(bk_cnt + dd_n);
 
-    uint32_t *table = hash + (size_t)slot * hash_cap;
+    const int table_words = hash_cap < 0 ? -hash_cap : hash_cap;  // a multiple of 64, the table 256-byte aligned
+    uint32_t *table = hash + (size_t)slot * table_words;
     {
-        uint4 *t4 = (uint4 *)table;  // hash_cap is a power of two >= 64, the table 256-byte aligned
-        const uint4 e4 = make_uint4(EMPTY_SLOT, EMPTY_SLOT, EMPTY_SLOT, EMPTY_SLOT);
-        for (int i = threadIdx.x; i < hash_cap / 4; i += BLK) t4[i] = e4;
+        uint4 *t4 = (uint4 *)table;
+        const uint32_t e = hash_cap < 0 ? 0u : EMPTY_SLOT;  // bitmap: no bit set; hash table: every slot free
+        const uint4 e4 = make_uint4(e, e, e, e);
+        for (int i = threadIdx.x; i < table_words / 4; i += BLK) t4[i] = e4;
     }
     for (int i = threadIdx.x; i < E; i += BLK) cand[i] = entries[(size_t)query * E + i];
     __threadfence_block();
     __syncthreads();
-    int n = filter_and_insert<BLK>(cand, E, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, hash_cap, N,
-                              cand_g + (size_t)slot * slots, wave_sums, tag_g + (size_t)slot * slots, 1);
+    int n = visited_filter<BLK>(cand, E, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, hash_cap, N,
+                                cand_g + (size_t)slot * slots, wave_sums, tag_g + (size_t)slot * slots, 1, 0);
     if (threadIdx.x == 0) {
         QState s;
         s.t = 0;
@@ -348,7 +463,6 @@ __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entri
         s.pad[0] = s.pad[1] = s.pad[2] = 0;
         state[slot] = s;
         counts[slot] = n;
-        if (n > 0) atomicAdd(&group_sums(counts, n_slots, which_sums)[slot >> 8], n);
     }
 }
 
@@ -359,7 +473,7 @@ init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state
             int cap_max, int64_t *stats, uint16_t *tag_g) {
     extern __shared__ __align__(16) unsigned char smem[];
     seed_slot<BLOCK>(blockIdx.x, blockIdx.x, entries, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W,
-              L, cap, W_max, L_max, cap_max, stats, smem, tag_g, gridDim.x, 0);
+              L, cap, W_max, L_max, cap_max, stats, smem, tag_g);
 }
 
 // A query's counters join the totals once, when its result is written: every workgroup adding to the
@@ -399,10 +513,10 @@ __device__ void emit_row(const QState *state, const uint64_t *pool_g, int C, int
 // finished writes that query's result and takes the next waiting query, in index order (a
 // counter is the queue).  Runs before the packing step of every round.
 __global__ void stream_reset_kernel(int64_t *stats, Ctrl *ctrl, QState *state, int32_t *counts, int32_t *slot_query,
-                                    int S, int Q_total) {
+                                    int S, int Q_total, int adj_row_bytes, int item_row_bytes) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < 16) {
-        stats[i] = (i == 4) ? Q_total : 0;
+        stats[i] = i == 4 ? Q_total : i == 5 ? adj_row_bytes : i == 6 ? item_row_bytes : 0;
         ((int32_t *)ctrl)[i] = 0;
     }
     if (i < S) {
@@ -412,7 +526,6 @@ __global__ void stream_reset_kernel(int64_t *stats, Ctrl *ctrl, QState *state, i
         counts[i] = -1;
         slot_query[i] = -1;
     }
-    if (i < 2 * count_groups(S)) group_sums(counts, S, 0)[i] = 0;
 }
 
 __global__ void __launch_bounds__(BLOCK)
@@ -420,7 +533,7 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
              int32_t *cand_g, int slots, int32_t *counts, const int32_t *W_q, const int32_t *L_q,
              const int32_t *cap_q, int W, int L, int cap, int W_max, int L_max, int cap_max, int64_t *stats,
              Ctrl *ctrl, int32_t *slot_query, int Q_total, const uint64_t *pool_g, int C, int k, int32_t *out_ids,
-             float *out_scores, uint16_t *tag_g, int which_sums) {
+             float *out_scores, uint16_t *tag_g) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int next_s;
     const int slot = blockIdx.x;
@@ -446,45 +559,37 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
     const int next = next_s;
     if (next < 0) return;
     seed_slot<BLOCK>(slot, next, entries, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W, L, cap,
-              W_max, L_max, cap_max, stats, smem, tag_g, gridDim.x, which_sums);
+              W_max, L_max, cap_max, stats, smem, tag_g);
 }
 
 // ------------------------------------------------------------------------------------------
 // Exclusive scan of survivor counts + stable packing into the dense pair list (Algorithm 2).
 // A workgroup owns SCAN_QPB consecutive queries (4 or 8: few, so that many workgroups share the
-// copying).  The pairs in front of its first query are the sums of the groups of 256 queries in front
-// of it (kept by whoever writes a count, see group_sums) plus at most 255 single counts: no waiting on
-// other workgroups, the same result every run.  It then scans its own counts and copies its groups,
-// one wave per query at a time.  The last workgroup also counts the running queries and reports.
+// copying).  It first sums the counts of all earlier queries (every workgroup re-reads them from
+// L2: O(Q^2 / SCAN_QPB) four-byte reads in total, no waiting on other workgroups, the same result
+// every run), then scans its own counts and copies its groups, one wave per query at a time.
 template <int SCAN_QPB>  // queries per workgroup, a multiple of 4
 __global__ void __launch_bounds__(SCAN_BLOCK)
-scan_compact_kernel(int32_t *counts_rw, int Q, const int32_t *__restrict__ cand_g, int slots,
+scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__restrict__ cand_g, int slots,
                     int32_t *offsets, int32_t *pair_q, int32_t *pair_id, Ctrl *ctrl,
-                    const int32_t *__restrict__ slot_query, uint64_t *mailbox, uint64_t mail_word, int Q_total,
-                    int which_sums) {
+                    const int32_t *__restrict__ slot_query, uint64_t *mailbox, uint64_t mail_word, int Q_total) {
     __shared__ int red[SCAN_WAVES];
     __shared__ int red_active[SCAN_WAVES];
     __shared__ int loc_off[SCAN_QPB + 1];
     __shared__ int loc_cnt[SCAN_QPB];
-    const int32_t *counts = counts_rw;
     const int q0 = blockIdx.x * SCAN_QPB;
     const bool last = (blockIdx.x == gridDim.x - 1);
-    const int32_t *sums = group_sums(counts_rw, Q, which_sums);
-    if (blockIdx.x == 0) {  // the other array starts the next round at zero
-        int32_t *other = group_sums(counts_rw, Q, which_sums + 1);
-        for (int i = threadIdx.x; i < count_groups(Q); i += SCAN_BLOCK) other[i] = 0;
-    }
+    // pairs of all earlier queries (and, in the last workgroup, the number of running queries)
     int sum = 0, act = 0;
-    const int g0 = q0 >> 8;
-    for (int g = threadIdx.x; g < g0; g += SCAN_BLOCK) sum += sums[g];
-    // q0 is a multiple of 4 and the array is 256-byte aligned: four counts per load from the group's start up to q0
+    const int lim = last ? Q : q0;
+    // q0 is a multiple of 4 and the array is 256-byte aligned: four counts per load up to q0
     const int4 *counts4 = (const int4 *)counts;
-    for (int i4 = (g0 << 6) + threadIdx.x; i4 < (q0 >> 2); i4 += SCAN_BLOCK) {
+    for (int i4 = threadIdx.x; i4 < (q0 >> 2); i4 += SCAN_BLOCK) {
         const int4 c = counts4[i4];
         sum += max(c.x, 0) + max(c.y, 0) + max(c.z, 0) + max(c.w, 0);
+        act += (c.x >= 0) + (c.y >= 0) + (c.z >= 0) + (c.w >= 0);
     }
-    if (last)  // running queries of the whole batch
-        for (int i = threadIdx.x; i < Q; i += SCAN_BLOCK) act += (counts[i] >= 0);
+    for (int i = q0 + threadIdx.x; i < lim; i += SCAN_BLOCK) act += (counts[i] >= 0);  // last workgroup only
     for (int o = 32; o > 0; o >>= 1) {
         sum += __shfl_down(sum, o);
         act += __shfl_down(act, o);
@@ -572,24 +677,27 @@ __device__ __forceinline__ int lower_bound_keys(const uint64_t *a, int n, uint64
 }
 
 // Eight workgroups of 256 threads fill a CU's wave slots; that needs no more than 64 registers per lane.
-template <int BLK>
-__global__ void __launch_bounds__(BLK) __attribute__((amdgpu_waves_per_eu(8, 8)))
+// BITMAP: the visited set is one bit per item (hash_cap < 0), else the hash table.  PIECES: a round may bring more
+// candidates than pass the filter at once (both are compile-time so that each build holds one filter, once, in
+// its 64 registers).
+template <int BLK, bool BITMAP, bool PIECES>
+__global__ void __launch_bounds__(BLK) __attribute__((amdgpu_waves_per_eu(ROUND_WAVES_MIN, 8)))
 round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, uint64_t *pool_g, int C,
              uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
              const int32_t *__restrict__ offsets, const float *__restrict__ scores, int new_cap,
-             int W_max, int64_t *stats, uint16_t *tag_g, int walkers, int tile_keys, int which_sums) {
+             int W_max, int64_t *stats, uint16_t *tag_g, int walkers, int tile_keys) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int q = blockIdx.x;
     PHASE_START
     // LDS: parents and scan scratch first; then one region used twice: by the new entries and the list
     // tile during the merge, by the candidate ids and the dedupe tables afterwards
     int32_t *parents = (int32_t *)smem;                       // [W_max]
-    int *wave_sums = parents + ((W_max + 3) & ~3);            // one per wave + 1, padded to 8
-    int *shared_i = wave_sums + 8;                            // [8] values one thread hands to all
+    int *wave_sums = parents + ((W_max + 3) & ~3);            // [16] one per wave
+    int *shared_i = wave_sums + 16;                           // [8] values one thread hands to all
     uint64_t *newk = (uint64_t *)(shared_i + 8);              // [new_cap]   new entries, sorted
     uint64_t *best = newk + new_cap;                          // [W_max]     walkers: best new child of each
     uint64_t *tile = best + ((W_max + 1) & ~1);               // [tile_keys] a piece of the stored list
-    int32_t *cand = (int32_t *)newk;                          // [slots]
+    int32_t *cand = (int32_t *)newk;                          // [min(slots, FILTER_CHUNK)]
     uint64_t *pool = pool_g + (size_t)q * C;
     int32_t *cand_q = cand_g + (size_t)q * slots;
     uint16_t *tag_q = tag_g + (size_t)q * slots;
@@ -606,9 +714,10 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         if (threadIdx.x == 0) counts[q] = -1;
         return;
     }
+    const int chunk = min(slots, FILTER_CHUNK);  // candidates that go through the visited filter together
     int dd_n = 2;
-    while (dd_n < 2 * slots) dd_n <<= 1;
-    uint32_t *dd_key = (uint32_t *)(cand + ((slots + 3) & ~3));
+    while (dd_n < 2 * chunk) dd_n <<= 1;
+    uint32_t *dd_key = (uint32_t *)(cand + ((chunk + 3) & ~3));
     uint32_t *dd_pos = dd_key + dd_n;
     uint32_t *bk_key = dd_pos + dd_n;
     uint32_t *bk_cnt = bk_key + dd_n;
@@ -737,7 +846,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     if (first_open < 0) first_open = shared_i[1];
     // a visited table that could not take this round's ids ends the query
     bool overflow = false;
-    if (n_par > 0 && (int64_t)st.n_visited + (int64_t)n_par * R > (int64_t)(hash_cap / 2)) {
+    if (!BITMAP && n_par > 0 && (int64_t)st.n_visited + (int64_t)n_par * R > (int64_t)(hash_cap / 2)) {
         overflow = true;
         n_par = 0;
     }
@@ -752,20 +861,33 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         return;
     }
 
-    // 3. neighbour gather: one adjacency row per parent, consecutive lanes read consecutive ids
+    // 3. neighbour gather: one adjacency row per parent, consecutive lanes read consecutive ids;
+    // 4. visited filter, 5. survivors of this query for the next MLP launch.
+    // A round's candidates go through in pieces of at most `chunk` (what the dedupe tables in LDS hold).  An id
+    // that comes again in a later piece is dropped there because the earlier piece has entered it into the
+    // visited table: the first occurrence still wins, in candidate order.
     PHASE_MARK(3);  // selection
     const int n_cand = n_par * R;
-    for (int j = threadIdx.x; j < n_cand; j += BLK) {
-        int p = j / R, s = j - p * R;
-        cand[j] = parents[p] >= 0 ? adj[(size_t)parents[p] * R + s] : -1;
+    int n_new = 0;
+    for (int c0 = 0; c0 < (PIECES ? n_cand : 1); c0 += chunk) {
+        const int nc = PIECES ? min(chunk, n_cand - c0) : n_cand;
+        if (PIECES && c0 > 0) {  // the table stores of the piece before must be seen by this piece's reads
+            __threadfence_block();
+            __syncthreads();
+        }
+        for (int j = threadIdx.x; j < nc; j += BLK) {
+            const int p = (c0 + j) / R, s = (c0 + j) - p * R;
+            cand[j] = parents[p] >= 0 ? adj[(size_t)parents[p] * R + s] : -1;
+        }
+        __syncthreads();
+        if (BITMAP)
+            n_new += filter_and_mark<BLK>(cand, nc, dd_key, dd_pos, bk_key, bk_cnt, dd_n, hash + (size_t)q * (size_t)(-hash_cap),
+                                          N, cand_q + n_new, wave_sums, tag_q + n_new, R, PIECES ? c0 : 0);
+        else
+            n_new += filter_and_insert<BLK>(cand, nc, dd_key, dd_pos, bk_key, bk_cnt, dd_n, hash + (size_t)q * hash_cap,
+                                            hash_cap, N, cand_q + n_new, wave_sums, tag_q + n_new, R, PIECES ? c0 : 0);
     }
-    __syncthreads();
-    PHASE_MARK(4);  // adjacency gather
-
-    // 4. visited filter, 5. survivors of this query for the next MLP launch
-    int n_new = filter_and_insert<BLK>(cand, n_cand, dd_key, dd_pos, bk_key, bk_cnt, dd_n, hash + (size_t)q * hash_cap,
-                                  hash_cap, N, cand_q, wave_sums, tag_q, R);
-    PHASE_MARK(5);  // dedupe + visited table
+    PHASE_MARK(5);  // adjacency gather, dedupe + visited table
     if (threadIdx.x == 0) {
         st.n_list = n_list;
         st.first_open = first_open;
@@ -774,7 +896,6 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         st.n_expanded += walkers ? n_live : n_par;
         state[q] = st;
         counts[q] = n_new;
-        if (n_new > 0) atomicAdd(&group_sums(counts, gridDim.x, which_sums)[q >> 8], n_new);
     }
 }
 
@@ -803,6 +924,13 @@ emit_kernel(const QState *__restrict__ state, const uint64_t *__restrict__ pool_
 }
 
 // ------------------------------------------------------------------------------------------
+// What the kernels take as `hash_cap`: the hash table's entries, or minus the bitmap's words.
+static int table_cap_arg(const Plan &p) { return p.bitmap_words > 0 ? -p.bitmap_words : p.hash_cap; }
+
+static int item_row_bytes(const ann_graph *g) {
+    return g->d * (g->dtype == ANN_F32 ? 4 : g->dtype == ANN_F8 ? 1 : 2);
+}
+
 static int new_cap_of(const Plan &p) {
     int n = 2;
     while (n < p.slots) n <<= 1;
@@ -813,16 +941,17 @@ static int new_cap_of(const Plan &p) {
 // when it is short, a quarter of a long one, at most 4,096 (32 KB).
 static int tile_keys_of(const Plan &p) {
     int t = 1024;
-    while (t < 4096 && 4 * t < p.C) t <<= 1;
+    while (t < ROUND_TILE_MAX && 4 * t < p.C) t <<= 1;
     return t;
 }
 
 static size_t round_smem(const Plan &p) {
+    const int chunk = p.slots < FILTER_CHUNK ? p.slots : FILTER_CHUNK;
     int dd_n = 2;
-    while (dd_n < 2 * p.slots) dd_n <<= 1;
+    while (dd_n < 2 * chunk) dd_n <<= 1;
     size_t lists = (size_t)(new_cap_of(p) + ((p.W_max + 1) & ~1) + tile_keys_of(p)) * 8;
-    size_t filt = (size_t)((p.slots + 3) & ~3) * 4 + (size_t)dd_n * 16;
-    return (size_t)((p.W_max + 3) & ~3) * 4 + 16 * 4 + (lists > filt ? lists : filt);
+    size_t filt = (size_t)((chunk + 3) & ~3) * 4 + (size_t)dd_n * 16;
+    return (size_t)((p.W_max + 3) & ~3) * 4 + 24 * 4 + (lists > filt ? lists : filt);
 }
 
 static size_t seed_smem(const Plan &p) {
@@ -836,9 +965,9 @@ int launch_init(const SearchArgs &a) {
     size_t smem = seed_smem(p);
     int64_t *stats = (int64_t *)(a.ws + p.off_stats);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, a.stream, stats, (Ctrl *)(a.ws + p.off_ctrl), p.Q,
-                       a.keep_stats ? 1 : 0, (int32_t *)(a.ws + p.off_counts));
+                       a.keep_stats ? 1 : 0, p.R * 4, item_row_bytes(a.g));
     hipLaunchKernelGGL(init_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.entries, p.E, a.g->N,
-                       (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), p.hash_cap,
+                       (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), table_cap_arg(p),
                        (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q,
                        a.L_q, a.cap_q, a.W, a.L, a.cap, p.W_max, p.L_max, p.max_iters_max, stats,
                        (uint16_t *)(a.ws + p.off_tag));
@@ -851,7 +980,7 @@ int launch_stream_reset(const SearchArgs &a) {
     const int n = p.Q > 16 ? p.Q : 16;
     hipLaunchKernelGGL(stream_reset_kernel, dim3((n + 255) / 256), dim3(256), 0, a.stream,
                        (int64_t *)(a.ws + p.off_stats), (Ctrl *)(a.ws + p.off_ctrl), (QState *)(a.ws + p.off_state),
-                       (int32_t *)(a.ws + p.off_counts), a.slot_query, p.Q, a.Q_total);
+                       (int32_t *)(a.ws + p.off_counts), a.slot_query, p.Q, a.Q_total, p.R * 4, item_row_bytes(a.g));
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
@@ -859,11 +988,11 @@ int launch_stream_reset(const SearchArgs &a) {
 int launch_admit(const SearchArgs &a) {
     const Plan &p = a.plan;
     hipLaunchKernelGGL(admit_kernel, dim3(p.Q), dim3(BLOCK), seed_smem(p), a.stream, a.entries, p.E, a.g->N,
-                       (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), p.hash_cap,
+                       (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), table_cap_arg(p),
                        (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q, a.L_q,
                        a.cap_q, a.W, a.L, a.cap, p.W_max, p.L_max, p.max_iters_max, (int64_t *)(a.ws + p.off_stats),
                        (Ctrl *)(a.ws + p.off_ctrl), a.slot_query, a.Q_total, (const uint64_t *)(a.ws + p.off_pool), p.C,
-                       p.k, a.out_ids, a.out_scores, (uint16_t *)(a.ws + p.off_tag), a.round_index & 1);
+                       p.k, a.out_ids, a.out_scores, (uint16_t *)(a.ws + p.off_tag));
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
@@ -875,10 +1004,10 @@ int launch_scan_compact(const SearchArgs &a) {
     const int blocks = (p.Q + qpb - 1) / qpb;
     auto fn = qpb == 4 ? scan_compact_kernel<4> : scan_compact_kernel<8>;
     hipLaunchKernelGGL(fn, dim3(blocks), dim3(SCAN_BLOCK), 0, a.stream,
-                       (int32_t *)(a.ws + p.off_counts), p.Q, (const int32_t *)(a.ws + p.off_cand),
+                       (const int32_t *)(a.ws + p.off_counts), p.Q, (const int32_t *)(a.ws + p.off_cand),
                        p.slots, (int32_t *)(a.ws + p.off_offsets), (int32_t *)(a.ws + p.off_pair_q),
                        (int32_t *)(a.ws + p.off_pair_id), (Ctrl *)(a.ws + p.off_ctrl), a.slot_query, a.mailbox,
-                       a.mail_tag | ((uint64_t)(uint32_t)(a.round_index + 1) << 1), a.Q_total, a.round_index & 1);
+                       a.mail_tag | ((uint64_t)(uint32_t)(a.round_index + 1) << 1), a.Q_total);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
@@ -890,20 +1019,31 @@ int launch_round(const SearchArgs &a) {
     // than what a chip holds at once (2,048 workgroups of 256): twice as many queries are then resident, and
     // the candidates still go through the visited filter in one pass.  (C4: 33 -> 28 ms per step; with few
     // queries the shorter path of the larger workgroup wins: C2 3.9 against 4.2 ms.)
+    // Workgroups of 1,024 threads when a round brings more than 512 candidates per query: the candidates pass the
+    // visited filter in one sweep, and the sort and the merge have a quarter of the work per thread.
     const bool half = (p.slots <= 128 && p.Q >= 8192);
-    auto fn = half ? round_kernel<128> : round_kernel<BLOCK>;
+    const bool big = p.slots > ROUND_BIG_FROM;
+    const int which = half ? 1 : big ? 2 : 0;
+    const int threads = half ? 128 : big ? ROUND_BIG_BLOCK : BLOCK;
+    const bool bm = p.bitmap_words > 0;
+    const bool pieces = p.slots > FILTER_CHUNK;  // then slots > ROUND_BIG_FROM too: the larger workgroup
+    auto fn = half ? (bm ? round_kernel<128, true, false> : round_kernel<128, false, false>)
+              : big ? (pieces ? (bm ? round_kernel<ROUND_BIG_BLOCK, true, true> : round_kernel<ROUND_BIG_BLOCK, false, true>)
+                              : (bm ? round_kernel<ROUND_BIG_BLOCK, true, false> : round_kernel<ROUND_BIG_BLOCK, false, false>))
+                    : (bm ? round_kernel<BLOCK, true, false> : round_kernel<BLOCK, false, false>);
     if (smem > 48 * 1024) {
-        static std::atomic<uint32_t> raised[2];
-        if (int rc = raise_lds_limit((const void *)fn, 128 * 1024, a.m->device, raised[half ? 1 : 0]); rc != ANN_OK)
+        static std::atomic<uint32_t> raised[12];
+        if (int rc = raise_lds_limit((const void *)fn, 128 * 1024, a.m->device, raised[4 * which + (bm ? 2 : 0) + (pieces ? 1 : 0)]);
+            rc != ANN_OK)
             return rc;
     }
-    hipLaunchKernelGGL(fn, dim3(p.Q), dim3(half ? 128 : BLOCK), smem, a.stream, a.g->adj, p.R, a.g->N,
+    hipLaunchKernelGGL(fn, dim3(p.Q), dim3(threads), smem, a.stream, a.g->adj, p.R, a.g->N,
                        (QState *)(a.ws + p.off_state), (uint64_t *)(a.ws + p.off_pool), p.C,
-                       (uint32_t *)(a.ws + p.off_hash), p.hash_cap, (int32_t *)(a.ws + p.off_cand), p.slots,
+                       (uint32_t *)(a.ws + p.off_hash), table_cap_arg(p), (int32_t *)(a.ws + p.off_cand), p.slots,
                        (int32_t *)(a.ws + p.off_counts), (const int32_t *)(a.ws + p.off_offsets),
                        (const float *)(a.ws + p.off_scores), new_cap_of(p), p.W_max,
                        (int64_t *)(a.ws + p.off_stats), (uint16_t *)(a.ws + p.off_tag), a.walkers ? 1 : 0,
-                       tile_keys_of(p), (a.round_index + 1) & 1);
+                       tile_keys_of(p));
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }

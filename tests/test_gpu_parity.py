@@ -120,7 +120,9 @@ def test_search_fp32_tiny_config_matches_oracle():
                                          # lists of several LDS tiles (the merge walks them from the end), k > L,
                                          # full-width rounds
                                          (4, 1500, 2000, 2, 0), (8, 2500, 100, 4, 0), (64, 4500, 4600, 5, 0),
-                                         (5, 1024, 1024, 1, 40), (2, 1025, 7, 3, 0)])
+                                         (5, 1024, 1024, 1, 40), (2, 1025, 7, 3, 0),
+                                         # rounds of more candidates than pass the visited filter at once
+                                         (128, 300, 50, 5, 3), (100, 2000, 64, 4, 0), (256, 64, 10, 2, 2)])
 def test_search_fp32_parameter_sweep(W, L, k, E, cap):
     cfg = replace(scaled(PRESETS["C1"], 5000, n_clusters=8, Q=40), E=E)
     wl = _with_biases(make_workload(cfg, seed=99), cfg, 14)
@@ -136,9 +138,12 @@ def test_search_fp32_parameter_sweep(W, L, k, E, cap):
         assert st.nodes_expanded == int(ref["n_expanded"].sum())
         assert st.max_query_iters == int(ref["n_iters"].max())
     assert st.visited_overflow == 0 and st.queries == cfg.Q
+    # algorithmic bytes of the gather stages follow from the counters and the row sizes
+    assert st.adjacency_bytes == st.nodes_expanded * cfg.R * 4
+    assert st.embedding_bytes == st.pairs_scored * cfg.d * 4 and st.pair_list_bytes == st.pairs_scored * 12
 
 
-@pytest.mark.parametrize("W,L,k", [(32, 9000, 200), (64, 20000, 100)])
+@pytest.mark.parametrize("W,L,k", [(32, 9000, 200), (64, 20000, 100), (256, 9000, 200)])
 def test_search_fp32_very_long_list(W, L, k):
     """Lists far beyond what LDS holds (tiles of 4,096 entries): identical to the oracle's."""
     cfg = replace(scaled(PRESETS["C1"], 40000, n_clusters=40, Q=12), E=6)
@@ -157,6 +162,50 @@ def test_search_fp32_very_long_list(W, L, k):
         assert st.nodes_expanded == int(ref["n_expanded"].sum())
         assert st.max_query_iters == int(ref["n_iters"].max())
     assert st.visited_overflow == 0
+
+
+@pytest.mark.parametrize("W,L,k,E,cap", [(4, 16, 40, 3, 0), (64, 100, 50, 5, 2), (8, 2500, 100, 4, 0), (128, 300, 50, 5, 3)])
+def test_search_fp32_visited_bitmap(W, L, k, E, cap, monkeypatch):
+    """The visited set as one bit per item (the form long lists use at full size), forced at a small size:
+    identical lists and counters as the oracle, repeated ids inside a round, several filter pieces per round;
+    also through the slot re-use of the streamed search, where a slot's bitmap is cleared for its next query."""
+    monkeypatch.setenv("GMPGR_VISITED_SET", "bitmap")
+    cfg = replace(scaled(PRESETS["C1"], 5000, n_clusters=8, Q=40), E=E)
+    wl = _with_biases(make_workload(cfg, seed=99), cfg, 14)
+    g, m, dev = open_handles(wl)
+    bytes_bitmap = ann.ann_search_workspace_bytes(g, m, cfg.Q, E, W, L, k, cap)
+    ws = torch.empty(bytes_bitmap, dtype=torch.uint8, device="cuda")
+    ids, sc = ann.ann_search(g, m, dev["users"], dev["entries"], W, L, k, cap, workspace=ws)
+    ref = _oracle_search(to_host(wl), W, L, k, cap, trace=True)
+    ids = ids.cpu().numpy()
+    assert same_list_fraction(ids, ref["ids"]) >= 0.99
+    st = ann.ann_search_stats(ws)
+    if same_list_fraction(ids, ref["ids"]) == 1.0:
+        assert st.pairs_scored == int(ref["n_scored"].sum())
+        assert st.nodes_expanded == int(ref["n_expanded"].sum())
+    assert st.visited_overflow == 0
+    ids_s, _ = ann.ann_search_stream(g, m, dev["users"], dev["entries"], 7, W, L, k, cap)
+    assert np.array_equal(ids_s.cpu().numpy(), ids)
+    monkeypatch.setenv("GMPGR_VISITED_SET", "hash")
+    assert ann.ann_search_workspace_bytes(g, m, cfg.Q, E, W, L, k, cap) != bytes_bitmap
+    ids_h, _ = ann.ann_search(g, m, dev["users"], dev["entries"], W, L, k, cap)
+    assert np.array_equal(ids_h.cpu().numpy(), ids)
+
+
+def test_search_fp32_batch_beyond_8192_queries():
+    """Batches of more than 8,192 queries pack their survivors with eight queries per workgroup instead of four;
+    the streamed search does so with more than 8,192 slots."""
+    cfg = replace(scaled(PRESETS["C1"], 3000, n_clusters=6, Q=9001), E=2)
+    wl = _with_biases(make_workload(cfg, seed=31), cfg, 16)
+    g, m, dev = open_handles(wl)
+    ref = _oracle_search(to_host(wl), 3, 12, 9, 0, trace=True)
+    ws = torch.empty(ann.ann_search_workspace_bytes(g, m, cfg.Q, cfg.E, 3, 12, 9, 0), dtype=torch.uint8, device="cuda")
+    ids, _ = ann.ann_search(g, m, dev["users"], dev["entries"], 3, 12, 9, 0, workspace=ws)
+    assert same_list_fraction(ids.cpu().numpy(), ref["ids"]) >= 0.999
+    st = ann.ann_search_stats(ws)
+    assert st.pairs_scored == int(ref["n_scored"].sum()) and st.queries == cfg.Q
+    ids_s, _ = ann.ann_search_stream(g, m, dev["users"], dev["entries"], 8500, 3, 12, 9, 0)
+    assert torch.equal(ids_s, ids)
 
 
 def test_search_invalid_and_repeated_seeds_and_padding():
@@ -260,7 +309,7 @@ def test_empty_batch_and_argument_errors():
                        workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
     assert e.value.code == -5
     with pytest.raises(ann.AnnError):   # W*R above the kernel limit
-        ann.ann_search(g, m, dev["users"], dev["entries"], 100, 8, 5, 0)
+        ann.ann_search(g, m, dev["users"], dev["entries"], 300, 8, 5, 0)
     bad_adj = dev["adj"].clone()
     bad_adj[3, 2] = cfg.N
     with pytest.raises(ann.AnnError):
@@ -565,6 +614,34 @@ def test_search_enqueued_behind_long_work_on_its_stream():
         waited = time.perf_counter() - t0
     assert torch.equal(ids.cpu(), want)
     print(f"search returned after {1e3 * waited:.0f} ms behind the stream's earlier work")
+
+
+def test_progress_wait_gives_up_after_its_time_limit():
+    """The wait for a search's progress word is bounded: behind work that outlasts the limit the call returns
+    ANN_EDEVICE instead of spinning on, every kernel it enqueued still runs to its end, and the library works
+    afterwards.  The condition is forced from the host (a tiny limit); nothing on the device waits or hangs."""
+    cfg = scaled(PRESETS["C2"], 20000, n_clusters=16, Q=64)
+    wl = make_workload(cfg)
+    g, m, dev = open_handles(wl)
+    want = ann.ann_search(g, m, dev["users"], dev["entries"], cfg.W, 48, 20, 0)[0].cpu()
+    s = torch.cuda.Stream()
+    a = torch.randn(8192, 8192, device="cuda")
+    ann.ann_set_progress_timeout(0.05)
+    try:
+        with torch.cuda.stream(s):
+            for _ in range(60):          # several hundred milliseconds of work ahead of the search
+                a = (a @ a) * 1e-4
+            with pytest.raises(ann.AnnError) as e:
+                ann.ann_search(g, m, dev["users"], dev["entries"], cfg.W, 48, 20, 0, stream=s)
+            assert e.value.code == -3 and "time limit" in str(e.value)
+            s.synchronize()              # the rounds that were enqueued end by themselves
+    finally:
+        ann.ann_set_progress_timeout(600.0)
+    with pytest.raises(ann.AnnError):
+        ann.ann_set_progress_timeout(-1.0)
+    ids, _ = ann.ann_search(g, m, dev["users"], dev["entries"], cfg.W, 48, 20, 0, stream=s)
+    s.synchronize()
+    assert torch.equal(ids.cpu(), want)
 
 
 def test_binding_rejects_queries_of_the_wrong_type_or_width():
