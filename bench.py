@@ -137,6 +137,7 @@ def main() -> int:
     ap.add_argument("--no-stream", action="store_true", help="skip the continuous-batching run beside the headline")
     ap.add_argument("--no-halves", action="store_true", help="skip the two-half-batches-at-once run beside the headline")
     ap.add_argument("--no-walkers", action="store_true", help="skip the walker-rule run beside the headline")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the capped search on C1 and C2")
     ap.add_argument("--no-f16", action="store_true", help="skip the fp16 metric run beside the headline")
     ap.add_argument("--no-f8", action="store_true", help="skip the 8-bit metric run (on C2) beside the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -524,6 +525,58 @@ def main() -> int:
             del ws2, g2, m2, emb2
         del wl2
 
+    # ---- the two configurations whose rounds are too small to fill the chip (C1, C2: a round is three launches
+    #      of microseconds of work, Sec. 3.2's launch-bound regime): the capped search recorded once into a HIP
+    #      graph and replayed, against the same capped search enqueued launch by launch ----
+    graphs_cmp = None
+    if not args.no_graph:
+        graphs_cmp = {}
+        for name in ("C1", "C2"):
+            cg = PRESETS[name]
+            wlg = make_workload(cg, device="cuda:0")
+            dtg = ann.ANN_BF16 if cg.dtype == "bf16" else ann.ANN_F32
+            gg = ann.ann_graph_load(wlg["adj"], wlg["emb"])
+            mg = ann.ann_mlp_load(wlg["W"], wlg["b"], wlg["head_w"], cg.d, dtg)
+            Lg = 8 * cg.L
+            wsg = torch.empty(ann.ann_search_workspace_bytes(gg, mg, cg.Q, cg.E, cg.W, Lg, cg.k, 0), dtype=torch.uint8,
+                              device="cuda:0")
+            ids_u, _ = ann.ann_search(gg, mg, wlg["users"], wlg["entries"], cg.W, Lg, cg.k, 0, workspace=wsg)
+            capg = int(ann.ann_search_stats(wsg).max_query_iters)      # every query has converged by then
+            del wsg
+            wsg = torch.empty(ann.ann_search_workspace_bytes(gg, mg, cg.Q, cg.E, cg.W, Lg, cg.k, capg), dtype=torch.uint8,
+                              device="cuda:0")
+            oi = torch.empty((cg.Q, cg.k), dtype=torch.int32, device="cuda:0")
+            osc = torch.empty((cg.Q, cg.k), dtype=torch.float32, device="cuda:0")
+            run = lambda: ann.ann_search(gg, mg, wlg["users"], wlg["entries"], cg.W, Lg, cg.k, capg, workspace=wsg,
+                                         out_ids=oi, out_scores=osc)
+            run()
+            torch.cuda.synchronize()
+
+            def timed(fn, reps=20):
+                fn()
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                for _ in range(reps):
+                    fn()
+                torch.cuda.synchronize()
+                return 1e3 * (time.perf_counter() - t) / reps
+
+            ms_uncapped = timed(lambda: ann.ann_search(gg, mg, wlg["users"], wlg["entries"], cg.W, Lg, cg.k, 0))
+            ms_eager = timed(run)
+            same_eager = bool(torch.equal(oi, ids_u))
+            cgraph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(cgraph):
+                run()
+            oi.fill_(-7)
+            ms_graph = timed(cgraph.replay)
+            graphs_cmp[name] = {"Q": cg.Q, "W": cg.W, "L": Lg, "rounds": capg,
+                                "ms_until_converged_following_progress": round(ms_uncapped, 3),
+                                "ms_capped_launch_by_launch": round(ms_eager, 3), "ms_capped_graph_replay": round(ms_graph, 3),
+                                "same_results": bool(same_eager and torch.equal(oi, ids_u))}
+            log(f"{name} (L={Lg}, {capg} rounds): {ms_uncapped:.2f} ms following progress, {ms_eager:.2f} ms capped, "
+                f"{ms_graph:.2f} ms as a HIP graph replay; same results: {graphs_cmp[name]['same_results']}")
+            del wlg, gg, mg, wsg, cgraph
+
     # ---- the fp16 metric (IEEE binary16, the format Sec. 4.3 names) on this workload: the same kernels with the
     #      other 16-bit MFMA; reported beside the headline, not part of the timed step ----
     f16 = None
@@ -719,6 +772,7 @@ def main() -> int:
             "reference_point": reference, "rows_beside_the_headline_run_at": {"W": W_side, "L": L_side},
             "layered_search": layered, "continuous_batching": streamed, "concurrent_halves": halves,
             "walker_search": walkers, "f8_metric": f8, "f16_metric": f16,
+            "hip_graph_capped_search": graphs_cmp,
         },
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -644,6 +644,42 @@ def test_progress_wait_gives_up_after_its_time_limit():
     assert torch.equal(ids.cpu(), want)
 
 
+@pytest.mark.parametrize("preset,N,cap", [("C1", 10000, 24), ("C2", 30000, 12)])
+def test_capped_search_replays_from_a_hip_graph(preset, N, cap):
+    """A search with a round cap only enqueues kernels (no copy, no memset, no look at the device), so the whole
+    call records into a HIP graph.  The graph is replayed several times, with new user vectors written into the
+    captured buffers and eager searches and synchronisations between the replays; every replay must give what the
+    eager call gives for the same inputs."""
+    cfg = scaled(PRESETS[preset], N, Q=48)
+    wl = make_workload(cfg, seed=77)
+    g, m, dev = open_handles(wl)
+    W, L, k = cfg.W, cfg.L, min(cfg.k, 40)
+    ws = torch.empty(ann.ann_search_workspace_bytes(g, m, cfg.Q, cfg.E, W, L, k, cap), dtype=torch.uint8, device="cuda")
+    users, entries = dev["users"].clone(), dev["entries"].clone()
+    out_ids = torch.empty((cfg.Q, k), dtype=torch.int32, device="cuda")
+    out_sc = torch.empty((cfg.Q, k), dtype=torch.float32, device="cuda")
+    run = lambda: ann.ann_search(g, m, users, entries, W, L, k, cap, workspace=ws, out_ids=out_ids, out_scores=out_sc)
+    run()                                   # sets the kernels' LDS limits outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for rep in range(4):
+        if rep:                             # new inputs in the captured buffers
+            users.copy_(torch.randn(users.shape, generator=gen, device="cuda").to(users.dtype))
+            entries.copy_(torch.randint(0, cfg.N, entries.shape, generator=gen, device="cuda", dtype=torch.int32))
+        want_ids, want_sc = ann.ann_search(g, m, users, entries, W, L, k, cap)   # eager, own workspace
+        torch.cuda.synchronize()
+        out_ids.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_ids, want_ids), rep
+        assert torch.equal(out_sc, want_sc), rep
+        st = ann.ann_search_stats(ws)
+        assert st.queries == cfg.Q and st.max_query_iters <= cap
+
+
 def test_binding_rejects_queries_of_the_wrong_type_or_width():
     cfg = scaled(PRESETS["C2"], 2000, n_clusters=4, Q=8)
     wl = make_workload(cfg)
