@@ -364,6 +364,25 @@ def main() -> int:
             streamed["same_results_as_batched"] &= bool(torch.equal(ids_s[:Q], out_ids) and torch.equal(ids_s[3 * Q:], out_ids))
             log(f"continuous batching, {4 * Q} queries through {slots} slots: {ms_s:.1f} ms, {4 * Q / ms_s * 1e3:.0f} queries/s")
             del wss
+        # the same queries ARRIVING while the search runs: eight waves of Q/2, each submitted 16 rounds after the one
+        # before (an open stream; the arrays are filled beforehand, only the arrival is staged)
+        slots = 2 * Q
+        op = ann.ann_stream_open(g, m, users4, entries4, slots, W_side, L_side, k, 0)
+        torch.cuda.synchronize()
+        t5 = time.perf_counter()
+        for wave in range(8):
+            op.submit(Q // 2)
+            if wave < 7:
+                op.step(16)
+        op.drain()
+        ms_o = 1e3 * (time.perf_counter() - t5)
+        streamed["arrival_in_8_waves_16_rounds_apart"] = {
+            "slots": slots, "ms": round(ms_o, 2), "queries_per_s": round(4 * Q / ms_o * 1e3, 1),
+            "same_results_as_batched": bool(torch.equal(op.out_ids[:Q], out_ids) and torch.equal(op.out_ids[3 * Q:], out_ids))}
+        log(f"open stream, {4 * Q} queries arriving in 8 waves through {slots} slots: {ms_o:.1f} ms, "
+            f"{4 * Q / ms_o * 1e3:.0f} queries/s, same results: {streamed['arrival_in_8_waves_16_rounds_apart']['same_results_as_batched']}")
+        op.close()
+        del op
         del users4, entries4
 
     # ---- the batch as two half-batches searched at once from two host threads on two streams (one half's

@@ -248,6 +248,35 @@ int ann_search_stream(const ann_graph *g, const ann_mlp *m, const void *queries_
                       int32_t *out_ids_dev, float *out_scores_dev, void *stream);
 
 /*
+ * Open stream: continuous batching for queries that ARRIVE WHILE others are being searched (Sec. 3.2, Q-HiPANNS:
+ * the scorer keeps listening for requests; Algorithm 2 batches whatever has arrived).  The caller owns four
+ * device arrays of `capacity` rows (queries_dev [capacity][d_user], entry_dev [capacity][E], out_ids_dev and
+ * out_scores_dev [capacity][k]); query number i of the stream's life lives in row i, and its result is written
+ * to row i when it has converged (or reached max_iters rounds).  `slots` search states serve them as in
+ * ann_search_stream, whose workspace size (with Q_total = capacity) applies.  All work goes to `stream`.
+ *   ann_stream_submit : the next n rows of queries_dev / entry_dev are valid (written on `stream` before the
+ *                       call, or otherwise complete); the queries join the search at the next round.  Only
+ *                       enqueues two small kernels; may be called from another host thread than the one that
+ *                       drives the rounds.  ANN_EINVAL beyond `capacity` (a stream does not reuse rows).
+ *   ann_stream_step   : enqueues `rounds` rounds (admission of waiting queries into free states, packing,
+ *                       scoring, list update) without looking at the device.
+ *   ann_stream_drain  : enqueues rounds until every query submitted so far has its result, following the
+ *                       device's progress as ann_search does, then waits on `stream`; queries submitted by
+ *                       another thread meanwhile are served too.  ANN_EWORKSPACE / ANN_EDEVICE as ann_search.
+ *   ann_stream_close  : waits on `stream` and frees the handle (the arrays and the workspace are the caller's).
+ * The result of every query is the one ann_search gives for it, whenever it arrived.
+ */
+typedef struct ann_stream ann_stream; /* opaque */
+int ann_stream_open(const ann_graph *g, const ann_mlp *m, int32_t capacity, int32_t slots, int32_t E, int32_t W,
+                    int32_t L, int32_t k, int32_t max_iters, const void *queries_dev, const int32_t *entry_dev,
+                    int32_t *out_ids_dev, float *out_scores_dev, void *workspace_dev, size_t workspace_bytes,
+                    void *stream, ann_stream **out);
+int ann_stream_submit(ann_stream *s, int32_t n);
+int ann_stream_step(ann_stream *s, int32_t rounds);
+int ann_stream_drain(ann_stream *s);
+int ann_stream_close(ann_stream *s);
+
+/*
  * Serendipity vector of the metric input (Eq. 5: the user half of the input is h_u + h~ with
  * h~ ~ N(0, I)): out_dev[q][c] = users_dev[q][c] + sigma * z(seed, draw, q * d + c), for the
  * caller to pass as `queries_dev` of a search.  sigma = 1 is the paper's distribution, 0 copies.

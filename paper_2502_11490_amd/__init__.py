@@ -31,6 +31,8 @@ from .binding import (  # noqa: F401
     ann_search_layers_workspace_bytes,
     ann_search_ragged,
     ann_search_stream,
+    ann_stream_open,
+    Stream,
     ann_search_walkers,
     ann_search_walkers_workspace_bytes,
     ann_search_stream_workspace_bytes,

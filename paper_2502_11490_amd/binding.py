@@ -22,7 +22,8 @@ EXPORTS = [
     "ann_graph_load", "ann_graph_free", "ann_mlp_load", "ann_mlp_free", "ann_mlp_uses_mfma",
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
     "ann_search_layers", "ann_search_walkers_workspace_bytes", "ann_search_walkers",
-    "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_score_pairs", "ann_score_pairs_noalloc", "ann_users_add_noise", "ann_quantize_e4m3",
+    "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_stream_open", "ann_stream_submit", "ann_stream_step",
+    "ann_stream_drain", "ann_stream_close", "ann_score_pairs", "ann_score_pairs_noalloc", "ann_users_add_noise", "ann_quantize_e4m3",
     "ann_search_stats", "ann_set_progress_timeout", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
@@ -87,6 +88,14 @@ def load_library():
     lib.ann_search_stream_workspace_bytes.restype = sz
     lib.ann_search_stream.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp, vp]
     lib.ann_search_stream.restype = ctypes.c_int
+    lib.ann_stream_open.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(vp)]
+    lib.ann_stream_open.restype = ctypes.c_int
+    lib.ann_stream_submit.argtypes = [vp, i32]
+    lib.ann_stream_step.argtypes = [vp, i32]
+    lib.ann_stream_drain.argtypes = [vp]
+    lib.ann_stream_close.argtypes = [vp]
+    for name in ("ann_stream_submit", "ann_stream_step", "ann_stream_drain", "ann_stream_close"):
+        getattr(lib, name).restype = ctypes.c_int
     lib.ann_score_pairs.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, i32, vp]
     lib.ann_score_pairs.restype = ctypes.c_int
     lib.ann_score_pairs_noalloc.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, vp]
@@ -367,6 +376,56 @@ def ann_search_stream(g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.Te
                                _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
     _check(rc)
     return out_ids, out_scores
+
+
+class Stream:
+    """An open stream (ann_stream_open): queries are written into rows of `queries` / `entries` and submitted
+    while earlier ones are being searched; results land in the same rows of `out_ids` / `out_scores`.  The
+    object keeps the caller's arrays and the workspace alive."""
+
+    def __init__(self, g: Graph, m: Mlp, queries: torch.Tensor, entries: torch.Tensor, slots: int, W: int, L: int,
+                 k: int, max_iters: int = 0, workspace: Optional[torch.Tensor] = None, out_ids=None, out_scores=None,
+                 stream=None):
+        lib = load_library()
+        cap, E = _entries_shape(entries)
+        if workspace is None:
+            workspace = torch.empty(ann_search_stream_workspace_bytes(g, m, cap, slots, E, W, L, k, max_iters),
+                                    dtype=torch.uint8, device=queries.device)
+        if out_ids is None:
+            out_ids, out_scores = _alloc_out(cap, k, queries.device)
+        _check_out(out_ids, out_scores, cap, k)
+        self.g, self.m, self.queries, self.entries, self.workspace = g, m, queries, entries, workspace
+        self.out_ids, self.out_scores, self.capacity = out_ids, out_scores, cap
+        self.handle = ctypes.c_void_p()
+        _check(lib.ann_stream_open(g.handle, m.handle, cap, slots, E, W, L, k, max_iters, _queries_ptr(queries, m, cap),
+                                   _dev_ptr(entries, "entries", torch.int32), _dev_ptr(out_ids, "out_ids", torch.int32),
+                                   _dev_ptr(out_scores, "out_scores", torch.float32),
+                                   _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream_ptr(stream),
+                                   ctypes.byref(self.handle)))
+
+    def submit(self, n: int) -> None:
+        _check(load_library().ann_stream_submit(self.handle, n))
+
+    def step(self, rounds: int) -> None:
+        _check(load_library().ann_stream_step(self.handle, rounds))
+
+    def drain(self) -> None:
+        _check(load_library().ann_stream_drain(self.handle))
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            _check(load_library().ann_stream_close(self.handle))
+            self.handle = None
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.ann_stream_close(self.handle)
+            self.handle = None
+
+
+def ann_stream_open(g: Graph, m: Mlp, queries, entries, slots: int, W: int, L: int, k: int, max_iters: int = 0,
+                    **kw) -> Stream:
+    return Stream(g, m, queries, entries, slots, W, L, k, max_iters, **kw)
 
 
 def _layer_args(graphs: Sequence[Graph], W_l, L_l, K_l):

@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <chrono>
+#include <mutex>
 #include <sched.h>
 #include <new>
 #include <vector>
@@ -163,6 +164,12 @@ struct Mailbox {
         ok = true;
         return true;
     }
+    void release() {  // only for a word that belongs to an object with an explicit end of life
+        if (ok) (void)hipHostFree((void *)host);
+        ok = false;
+        host = nullptr;
+        dev = nullptr;
+    }
     uint64_t new_tag() {
         seq = (seq + 1) & 0xFFFFFFull;
         if (seq == 0) seq = 1;
@@ -179,12 +186,15 @@ struct Mailbox {
     // behind long work of the caller's waits as long as that takes, and a failed device ends the wait.  Rounds
     // take microseconds, so a running search never asks (a stream query is not free: asked every few thousand
     // spins it cost the small configurations, whose host thread mostly waits here, 0.4 ms per search).
-    int gate(uint64_t tag, int64_t i, hipStream_t stream) const {
+    // *seen_rounds (if given): the number of rounds the device had packed in the word the answer came from.
+    int gate(uint64_t tag, int64_t i, hipStream_t stream, int64_t *seen_rounds = nullptr) const {
         auto enough = [&](uint64_t w) {
             if ((w >> 40) != (tag >> 40)) return i <= AHEAD ? 0 : -2;  // nothing reported yet
+            if (seen_rounds) *seen_rounds = (int64_t)((w & 0xFFFFFFFFFFull) >> 1);
             if (w & 1ull) return 1;
             return (int64_t)((w & 0xFFFFFFFFFFull) >> 1) + AHEAD >= i ? 0 : -2;
         };
+        if (seen_rounds) *seen_rounds = 0;
         const auto start = std::chrono::steady_clock::now();
         auto last = start;
         uint64_t seen = *host;
@@ -264,7 +274,7 @@ static int score_batch(const SearchArgs &a) {
     const Plan &p = a.plan;
     const int32_t *M_dev = &((const Ctrl *)(a.ws + p.off_ctrl))->M;
     // pair_q names user vectors: slots and queries coincide unless queries stream through the slots
-    const int32_t n_users = a.Q_total > 0 ? a.Q_total : p.Q;
+    const int32_t n_users = a.Q_total > 0 ? a.Q_total : a.Q_total < 0 ? a.Q_rows : p.Q;
     const float *upre = a.upre_all ? a.upre_all : (const float *)(a.ws + p.off_upre);
     if (a.m->kernel == MLP_MFMA2)
         return launch_mlp_mfma(a.g, a.m, upre, (const int32_t *)(a.ws + p.off_pair_q),
@@ -874,6 +884,214 @@ int ann_search_stream(const ann_graph *g, const ann_mlp *m, const void *queries_
     a.slot_query = (int32_t *)(a.ws + sp.off_slot_query);
     a.upre_all = (float *)(a.ws + sp.off_upre_all);
     return run_stream(a);
+}
+
+}  // extern "C"
+
+// An open stream (Sec. 3.2, Q-HiPANNS: the scorer keeps listening for requests that arrive at any time): the
+// state of ann_search_stream kept between calls, with the number of arrived queries a device word that the
+// admission kernel reads, so that queries submitted while others are being searched join the running batches.
+struct ann_stream {
+    gmpgr::SearchArgs a;
+    gmpgr::Mailbox box;
+    std::mutex mu;               // submit and the enqueuing of rounds may come from different host threads
+    int32_t capacity = 0;        // rows of the caller's arrays
+    int32_t submitted = 0;       // queries that have arrived
+    int64_t rounds = 0;          // rounds enqueued so far
+    int64_t submit_round = 0;    // rounds enqueued when the last submit was published
+    size_t elem = 2;             // bytes of one user-vector element
+};
+
+namespace gmpgr {
+
+// One round of an open stream: admission, packing, scoring, list update.  Caller holds s->mu.
+static int stream_round(ann_stream *s) {
+    SearchArgs &a = s->a;
+    int rc;
+    a.round_index = (int32_t)(s->rounds & 0x3fffffff);
+    {
+        StageTimer timer(ANN_STAGE_ROUND, a.stream);
+        if ((rc = launch_admit(a)) != ANN_OK) return rc;
+    }
+    {
+        StageTimer timer(ANN_STAGE_PACK, a.stream);
+        if ((rc = launch_scan_compact(a)) != ANN_OK) return rc;  // its progress word counts the stream's rounds
+    }
+    if ((rc = score_batch(a)) != ANN_OK) return rc;
+    {
+        StageTimer timer(ANN_STAGE_ROUND, a.stream);
+        if ((rc = launch_round(a)) != ANN_OK) return rc;
+    }
+    s->rounds += 1;
+    return ANN_OK;
+}
+
+}  // namespace gmpgr
+
+extern "C" {
+
+int ann_stream_open(const ann_graph *g, const ann_mlp *m, int32_t capacity, int32_t slots, int32_t E, int32_t W,
+                    int32_t L, int32_t k, int32_t max_iters, const void *queries_dev, const int32_t *entry_dev,
+                    int32_t *out_ids_dev, float *out_scores_dev, void *workspace_dev, size_t workspace_bytes,
+                    void *stream, ann_stream **out) {
+    if (!out) {
+        set_error("out is null");
+        return ANN_EINVAL;
+    }
+    *out = nullptr;
+    StreamPlan sp;
+    if (capacity < 1) {
+        set_error("need capacity >= 1 (got %d)", capacity);
+        return ANN_EINVAL;
+    }
+    if (!make_stream_plan(g, m, capacity, slots, E, W, L, k, max_iters, &sp)) return ANN_EINVAL;
+    if (!queries_dev || !entry_dev || !out_ids_dev || !out_scores_dev) {
+        set_error("queries_dev, entry_dev, out_ids_dev and out_scores_dev must not be null");
+        return ANN_EINVAL;
+    }
+    if (!workspace_dev || ((uintptr_t)workspace_dev & 255)) {
+        set_error("workspace_dev must be a 256-byte aligned device pointer");
+        return ANN_EINVAL;
+    }
+    if (workspace_bytes < sp.total) {
+        set_error("workspace holds %zu bytes, %zu needed", workspace_bytes, sp.total);
+        return ANN_EWORKSPACE;
+    }
+    ann_stream *s = new (std::nothrow) ann_stream;
+    if (!s) {
+        set_error("out of host memory");
+        return ANN_ENOMEM;
+    }
+    if (!s->box.init()) {
+        delete s;
+        set_error("pinned host allocation failed");
+        return ANN_ENOMEM;
+    }
+    SearchArgs &a = s->a;
+    a.plan = sp.plan;
+    a.g = g;
+    a.m = m;
+    a.queries = queries_dev;
+    a.entries = entry_dev;
+    a.W_q = a.L_q = a.cap_q = nullptr;
+    a.W = W;
+    a.L = L;
+    a.cap = max_iters;
+    a.ws = (char *)workspace_dev;
+    a.out_ids = out_ids_dev;
+    a.out_scores = out_scores_dev;
+    a.stream = (hipStream_t)stream;
+    a.Q_total = -1;
+    a.Q_rows = capacity;
+    a.slot_query = (int32_t *)(a.ws + sp.off_slot_query);
+    a.upre_all = (float *)(a.ws + sp.off_upre_all);
+    a.mailbox = s->box.dev;
+    a.mail_tag = s->box.new_tag();
+    s->capacity = capacity;
+    s->elem = m->dtype == ANN_F32 ? 4 : 2;
+    int rc = launch_stream_reset(a);
+    if (rc != ANN_OK) {
+        s->box.release();
+        delete s;
+        return rc;
+    }
+    *out = s;
+    return ANN_OK;
+}
+
+int ann_stream_submit(ann_stream *s, int32_t n) {
+    if (!s || n < 0) {
+        set_error("null stream handle or n < 0");
+        return ANN_EINVAL;
+    }
+    std::lock_guard<std::mutex> guard(s->mu);
+    if ((int64_t)s->submitted + n > s->capacity) {
+        set_error("%d queries have arrived and %d more would exceed the capacity of %d", s->submitted, n, s->capacity);
+        return ANN_EINVAL;
+    }
+    if (n == 0) return ANN_OK;
+    SearchArgs &a = s->a;
+    const int32_t first = s->submitted;
+    int rc;
+    if (a.m->kernel == MLP_MFMA2) {  // the user terms of the new rows
+        const char *rows = (const char *)a.queries + (size_t)first * a.m->d_user * s->elem;
+        if ((rc = launch_user_pre(a.m, rows, n, a.upre_all + (size_t)first * a.plan.H1, a.stream)) != ANN_OK) return rc;
+    }
+    if ((rc = launch_stream_publish(a, first + n)) != ANN_OK) return rc;
+    s->submitted = first + n;
+    s->submit_round = s->rounds;
+    return ANN_OK;
+}
+
+int ann_stream_step(ann_stream *s, int32_t rounds) {
+    if (!s || rounds < 0) {
+        set_error("null stream handle or rounds < 0");
+        return ANN_EINVAL;
+    }
+    std::lock_guard<std::mutex> guard(s->mu);
+    for (int32_t i = 0; i < rounds; ++i)
+        if (int rc = stream_round(s); rc != ANN_OK) return rc;
+    return ANN_OK;
+}
+
+int ann_stream_drain(ann_stream *s) {
+    if (!s) {
+        set_error("null stream handle");
+        return ANN_EINVAL;
+    }
+    SearchArgs &a = s->a;
+    const Plan &p = a.plan;
+    // a query ends within this many rounds of its admission (it cannot score more ids than its visited set
+    // holds); the loop is bounded even if no report ever said "finished"
+    const int64_t per_query = p.max_iters_max > 0 ? (int64_t)p.max_iters_max + 2
+                                                  : (p.bitmap_words > 0 ? a.g->N : (int64_t)p.hash_cap / 2) + 3;
+    int64_t limit;
+    {
+        std::lock_guard<std::mutex> guard(s->mu);
+        limit = s->rounds + per_query * (((int64_t)s->submitted + p.Q - 1) / p.Q + 1);
+    }
+    for (;;) {
+        int64_t enq, need;
+        {
+            std::lock_guard<std::mutex> guard(s->mu);
+            enq = s->rounds;
+            need = s->submit_round;  // a "finished" report counts only from a round enqueued after the last submit
+            if (s->submitted == 0) return ANN_OK;
+        }
+        int64_t seen = 0;
+        const int g = s->box.gate(a.mail_tag, enq, a.stream, &seen);
+        if (g < 0) {
+            set_error(g == -3 ? "no progress report from the search's kernels within the time limit (ann_set_progress_timeout)"
+                              : "the stream failed or ran dry without the search's progress report");
+            return ANN_EDEVICE;
+        }
+        if (g > 0 && seen > need) break;
+        // "finished" from before the last submit: the rounds enqueued since will report; stay a few ahead of them
+        if (g > 0 && seen + Mailbox::AHEAD < enq) continue;
+        if (enq >= limit) {
+            set_error("the stream did not finish within %lld rounds", (long long)limit);
+            return ANN_EDEVICE;
+        }
+        std::lock_guard<std::mutex> guard(s->mu);
+        if (int rc = stream_round(s); rc != ANN_OK) return rc;
+    }
+    int64_t stats[8];
+    ANN_HIP_TRY(hipMemcpyAsync(stats, a.ws + p.off_stats, sizeof(stats), hipMemcpyDeviceToHost, a.stream));
+    ANN_HIP_TRY(hipStreamSynchronize(a.stream));
+    if (stats[3] > 0) {
+        set_error("%lld queries filled their visited table (sized for %d rounds) and stopped early", (long long)stats[3],
+                  p.rounds_assumed);
+        return ANN_EWORKSPACE;
+    }
+    return ANN_OK;
+}
+
+int ann_stream_close(ann_stream *s) {
+    if (!s) return ANN_OK;
+    (void)hipStreamSynchronize(s->a.stream);  // no kernel may store to the progress word after it is freed
+    s->box.release();
+    delete s;
+    return ANN_OK;
 }
 
 int ann_users_add_noise(const void *users_dev, void *out_dev, int32_t Q, int32_t d, int32_t dtype, double sigma,

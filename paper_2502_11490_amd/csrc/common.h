@@ -100,8 +100,9 @@ struct Plan {
 struct Ctrl {
     int32_t M;            // pairs in the current round
     int32_t n_active;     // queries not finished
-    int32_t next_query;   // continuous batching: queries admitted so far (may overshoot the total)
-    int32_t pad[13];
+    int32_t next_query;   // continuous batching: queries admitted so far (a closed batch may overshoot its total)
+    int32_t avail;        // open stream: queries that have arrived so far
+    int32_t pad[12];
 };
 
 // Per-query state at off_state.
@@ -134,7 +135,8 @@ struct SearchArgs {
     hipStream_t stream;
     bool keep_stats = false;  // counters continue from an earlier search on this workspace
     // continuous batching: Q_total queries share plan.Q slots
-    int32_t Q_total = 0;          // 0 = every query owns a slot
+    int32_t Q_total = 0;          // 0 = every query owns a slot; -1 = open stream (queries keep arriving)
+    int32_t Q_rows = 0;           // open stream: rows of the caller's query arrays
     int32_t *slot_query = nullptr;  // [plan.Q] query served by each slot, -1 = idle
     float *upre_all = nullptr;    // [Q_total][H1] user terms of all queries (MFMA path)
     // paper-literal variant: one walker per seed, plan.max_iters_max hops (see round_kernel)
@@ -153,6 +155,7 @@ int launch_round(const SearchArgs &a);
 int launch_emit(const SearchArgs &a);
 int launch_stream_reset(const SearchArgs &a);
 int launch_admit(const SearchArgs &a);
+int launch_stream_publish(const SearchArgs &a, int avail);
 
 // noise.hip: out = users + sigma * N(0, I), element-indexed counter-based draw (Eq. 5)
 int launch_users_add_noise(const void *users, void *out, int64_t n_elem, int dtype, double sigma, uint64_t seed,

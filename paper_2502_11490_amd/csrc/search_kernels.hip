@@ -516,7 +516,7 @@ __global__ void stream_reset_kernel(int64_t *stats, Ctrl *ctrl, QState *state, i
                                     int S, int Q_total, int adj_row_bytes, int item_row_bytes) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < 16) {
-        stats[i] = i == 4 ? Q_total : i == 5 ? adj_row_bytes : i == 6 ? item_row_bytes : 0;
+        stats[i] = i == 4 ? max(Q_total, 0) : i == 5 ? adj_row_bytes : i == 6 ? item_row_bytes : 0;
         ((int32_t *)ctrl)[i] = 0;
     }
     if (i < S) {
@@ -525,6 +525,15 @@ __global__ void stream_reset_kernel(int64_t *stats, Ctrl *ctrl, QState *state, i
         state[i] = s;
         counts[i] = -1;
         slot_query[i] = -1;
+    }
+}
+
+// Open stream: queries [0, avail) have arrived (their rows in the query, entry and user-term arrays are valid).
+// A kernel, so that the word changes in stream order behind the work that made the rows valid.
+__global__ void stream_publish_kernel(Ctrl *ctrl, int64_t *stats, int avail) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        ctrl->avail = avail;
+        stats[4] = avail;
     }
 }
 
@@ -548,10 +557,28 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
     }
     __syncthreads();  // every wave has read which query the slot served before thread 0 names the next one
     if (threadIdx.x == 0) {
-        int next = Q_total;
-        // the counter only grows; once it has passed the total nobody needs to touch it again
-        if (*(volatile int32_t *)&ctrl->next_query < Q_total) next = atomicAdd(&ctrl->next_query, 1);
-        next_s = next < Q_total ? next : -1;
+        int next;
+        if (Q_total >= 0) {
+            next = Q_total;
+            // the counter only grows; once it has passed the total nobody needs to touch it again
+            if (*(volatile int32_t *)&ctrl->next_query < Q_total) next = atomicAdd(&ctrl->next_query, 1);
+            next = next < Q_total ? next : -1;
+        } else {
+            // open stream: the number of queries that have arrived (ctrl->avail) grows while the search runs, so
+            // the counter must never pass it: a query index claimed before its query exists would be lost
+            const int avail = *(volatile int32_t *)&ctrl->avail;
+            int cur = *(volatile int32_t *)&ctrl->next_query;
+            next = -1;
+            while (cur < avail) {
+                const int seen = atomicCAS(&ctrl->next_query, cur, cur + 1);
+                if (seen == cur) {
+                    next = cur;
+                    break;
+                }
+                cur = seen;
+            }
+        }
+        next_s = next;
         slot_query[slot] = next_s;
         if (next_s < 0) counts[slot] = -1;  // idle: contributes no pairs, is not counted as running
     }
@@ -625,7 +652,9 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
         ctrl->n_active = n_active;
         if (mailbox) {
             // progress for the enqueuing host thread: one store to pinned host memory, nobody waits for it
-            const bool finished = n_active == 0 && (Q_total <= 0 || ctrl->next_query >= Q_total);
+            // nothing running and nothing waiting (open stream, Q_total < 0: nothing that has arrived so far)
+            const int waiting_until = Q_total >= 0 ? Q_total : *(volatile int32_t *)&ctrl->avail;
+            const bool finished = n_active == 0 && (Q_total == 0 || ctrl->next_query >= waiting_until);
             __hip_atomic_store(mailbox + 1, (mail_word & ~0xFFFFFFFFFFull) | (uint64_t)(uint32_t)n_active,
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);  // a hint only: see round_kernel
             __hip_atomic_store(mailbox, mail_word | (finished ? 1ull : 0ull), __ATOMIC_RELAXED,
@@ -981,6 +1010,14 @@ int launch_stream_reset(const SearchArgs &a) {
     hipLaunchKernelGGL(stream_reset_kernel, dim3((n + 255) / 256), dim3(256), 0, a.stream,
                        (int64_t *)(a.ws + p.off_stats), (Ctrl *)(a.ws + p.off_ctrl), (QState *)(a.ws + p.off_state),
                        (int32_t *)(a.ws + p.off_counts), a.slot_query, p.Q, a.Q_total, p.R * 4, item_row_bytes(a.g));
+    ANN_HIP_TRY(hipGetLastError());
+    return ANN_OK;
+}
+
+int launch_stream_publish(const SearchArgs &a, int avail) {
+    const Plan &p = a.plan;
+    hipLaunchKernelGGL(stream_publish_kernel, dim3(1), dim3(64), 0, a.stream, (Ctrl *)(a.ws + p.off_ctrl),
+                       (int64_t *)(a.ws + p.off_stats), avail);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }

@@ -680,6 +680,82 @@ def test_capped_search_replays_from_a_hip_graph(preset, N, cap):
         assert st.queries == cfg.Q and st.max_query_iters <= cap
 
 
+@pytest.mark.parametrize("slots,first,rounds_between", [(16, 40, 5), (7, 1, 0), (64, 99, 30)])
+def test_open_stream_second_wave_joins_running_search(slots, first, rounds_between):
+    """Queries that arrive while others are being searched (Sec. 3.2, Q-HiPANNS): a first wave is submitted and
+    searched for a few rounds, then the rest is written into the arrays and submitted; every query's result must
+    be the one the batched search gives, and the counters must add up."""
+    cfg = replace(scaled(PRESETS["C1"], 5000, n_clusters=8, Q=100), E=3)
+    wl = _with_biases(make_workload(cfg, seed=21), cfg, 17)
+    g, m, dev = open_handles(wl)
+    W, L, k = 3, 24, 15
+    ws_b = torch.empty(ann.ann_search_workspace_bytes(g, m, cfg.Q, cfg.E, W, L, k, 0), dtype=torch.uint8, device="cuda")
+    want_ids, want_sc = ann.ann_search(g, m, dev["users"], dev["entries"], W, L, k, 0, workspace=ws_b)
+    want = ann.ann_search_stats(ws_b)
+    users = torch.zeros_like(dev["users"])
+    entries = torch.full_like(dev["entries"], -1)
+    st = ann.ann_stream_open(g, m, users, entries, slots, W, L, k, 0)
+    users[:first] = dev["users"][:first]
+    entries[:first] = dev["entries"][:first]
+    st.submit(first)
+    st.step(rounds_between)                       # the first wave is under way
+    users[first:] = dev["users"][first:]
+    entries[first:] = dev["entries"][first:]
+    st.submit(cfg.Q - first)                      # the second wave joins the running search
+    st.drain()
+    assert torch.equal(st.out_ids, want_ids) and torch.equal(st.out_scores, want_sc)
+    got = ann.ann_search_stats(st.workspace)
+    assert (got.pairs_scored, got.nodes_expanded, got.queries) == (want.pairs_scored, want.nodes_expanded, cfg.Q)
+    st.drain()                                    # nothing left: returns at once
+    with pytest.raises(ann.AnnError):
+        st.submit(1)                              # the arrays are full
+    st.close()
+
+
+def test_open_stream_submit_from_another_thread_bf16():
+    """Waves submitted by a second host thread while the first drives the rounds; bf16 metric on the MFMA kernel
+    (a wave's user terms are computed at its submission)."""
+    import threading
+    import time
+    cfg = scaled(PRESETS["C2"], 30000, n_clusters=24, Q=96)
+    wl = make_workload(cfg, seed=22)
+    g, m, dev = open_handles(wl)
+    assert ann.ann_mlp_uses_mfma(m)
+    W, L, k = cfg.W, 48, 30
+    want_ids, _ = ann.ann_search(g, m, dev["users"], dev["entries"], W, L, k, 0)
+    users, entries = torch.zeros_like(dev["users"]), torch.full_like(dev["entries"], -1)
+    st = ann.ann_stream_open(g, m, users, entries, 20, W, L, k, 0)
+    side = torch.cuda.Stream()
+    waves = [(0, 10), (10, 50), (50, 96)]
+    errors = []
+
+    def producer():
+        try:
+            for a, b in waves:
+                with torch.cuda.stream(side):     # the rows are complete before they are submitted
+                    users[a:b] = dev["users"][a:b]
+                    entries[a:b] = dev["entries"][a:b]
+                side.synchronize()
+                st.submit(b - a)
+                time.sleep(0.002)
+        except Exception as e:  # noqa: BLE001
+            errors.append(repr(e))
+
+    th = threading.Thread(target=producer)
+    th.start()
+    deadline = time.time() + 60
+    done = False
+    while not done and time.time() < deadline:
+        st.drain()
+        done = not th.is_alive()
+    th.join()
+    st.drain()
+    assert not errors, errors
+    assert torch.equal(st.out_ids, want_ids)
+    assert ann.ann_search_stats(st.workspace).queries == cfg.Q
+    st.close()
+
+
 def test_binding_rejects_queries_of_the_wrong_type_or_width():
     cfg = scaled(PRESETS["C2"], 2000, n_clusters=4, Q=8)
     wl = make_workload(cfg)
