@@ -212,10 +212,14 @@ def main() -> int:
         L_star, prev = None, None
         L = cfg.L
         while L <= L_CAP and L < cfg.N:
+            # the full batch must fit at this L too (lists and visited sets grow with it)
+            if ann.ann_search_workspace_bytes(g, m, Q, E, W, L, k, 0) > 0.6 * torch.cuda.mem_get_info()[0]:
+                log(f"L={L}: the workspace of a full batch would not fit; the doubling ends here")
+                break
             r = search_sample(W, L)
             curve[str(L)] = round(r, 4)
             log(f"W={W} L={L}: recall@{kr} = {r:.4f} on {n_gt} queries")
-            if prev is not None and r - prev < PLATEAU_GAIN and r < 0.95:
+            if prev is not None and r - prev < PLATEAU_GAIN and 0.5 <= r < 0.95:  # flat at the top, not at the start
                 plateau = {"L": L, "recall_at_100": round(r, 4), "gain_of_last_doubling": round(r - prev, 4)}
                 break  # L_star stays at the last L that gained two points
             L_star, prev = L, r

@@ -181,16 +181,6 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
     const int n_buckets = hash_cap >> 4;
     const uint32_t bmask = (uint32_t)n_buckets - 1u;
     const int bshift = 32 - (31 - __clz(n_buckets));  // n_buckets = 2^b (b >= 2) -> top b bits
-    // The first BLOCK candidates request their home bucket right away, repeated ids included: the lines
-    // travel while the dedupe below runs in LDS.  Nothing is stored to the table before pass 2.
-    uint4 pre0 = {}, pre1 = {}, pre2 = {}, pre3 = {};
-    if ((int)threadIdx.x < n_cand) {
-        const int32_t v = cand[threadIdx.x];
-        if (v >= 0 && (int64_t)v < N) {
-            const uint4 *line = (const uint4 *)(table + (size_t)(hash_id((uint32_t)v) >> bshift) * 16);
-            pre0 = line[0], pre1 = line[1], pre2 = line[2], pre3 = line[3];
-        }
-    }
     for (int i = threadIdx.x; i < dd_n; i += BLK) {
         dd_key[i] = EMPTY_SLOT;
         dd_pos[i] = 0xFFFFFFFFu;
@@ -228,7 +218,6 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
                 bkt = hash_id((uint32_t)v) >> bshift;
             }
         }
-        bool home = (p0 == 0);  // the bucket requested at the top is this candidate's and still current
         for (;;) {
             for (int i = threadIdx.x; i < dd_n; i += BLK) {
                 bk_key[i] = EMPTY_SLOT;
@@ -238,11 +227,10 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
             bool found = false;
             int cnt = 0;
             if (active) {
-                uint4 q0 = pre0, q1 = pre1, q2 = pre2, q3 = pre3;
-                if (!home) {
-                    const uint4 *line = (const uint4 *)(table + (size_t)bkt * 16);
-                    q0 = line[0], q1 = line[1], q2 = line[2], q3 = line[3];
-                }
+                // (Requesting the home buckets before the dedupe, so that the lines travel meanwhile, keeps 16
+                // registers busy across it: in a kernel held to 64 they spill, which cost C4 a quarter of its time.)
+                const uint4 *line = (const uint4 *)(table + (size_t)bkt * 16);
+                const uint4 q0 = line[0], q1 = line[1], q2 = line[2], q3 = line[3];
                 const uint32_t w[16] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w,
                                         q2.x, q2.y, q2.z, q2.w, q3.x, q3.y, q3.z, q3.w};
 #pragma unroll
@@ -287,7 +275,6 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
             // fence would write the whole L2 slice back.
             __threadfence_block();
             __syncthreads();
-            home = false;
         }
         int tot;
         int pos = block_excl_count<BLK>(fresh, wave_sums, &tot);
@@ -708,8 +695,10 @@ __device__ __forceinline__ int lower_bound_keys(const uint64_t *a, int n, uint64
 // Eight workgroups of 256 threads fill a CU's wave slots; that needs no more than 64 registers per lane.
 // BITMAP: the visited set is one bit per item (hash_cap < 0), else the hash table.  PIECES: a round may bring more
 // candidates than pass the filter at once (both are compile-time so that each build holds one filter, once, in
-// its 64 registers).
-template <int BLK, bool BITMAP, bool PIECES>
+// its 64 registers).  RESIDENT: the whole list fits one tile (C <= tile_keys); it is then requested at the very
+// start, together with the state, merged into a second LDS copy, and the parents are chosen from that copy: two
+// dependent trips to memory fewer per round than the tiled walk, which is what short lists are bound by.
+template <int BLK, bool BITMAP, bool PIECES, bool RESIDENT>
 __global__ void __launch_bounds__(BLK) __attribute__((amdgpu_waves_per_eu(ROUND_WAVES_MIN, 8)))
 round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, uint64_t *pool_g, int C,
              uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
@@ -726,6 +715,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     uint64_t *newk = (uint64_t *)(shared_i + 8);              // [new_cap]   new entries, sorted
     uint64_t *best = newk + new_cap;                          // [W_max]     walkers: best new child of each
     uint64_t *tile = best + ((W_max + 1) & ~1);               // [tile_keys] a piece of the stored list
+    uint64_t *merged = tile + tile_keys;                      // [C]         RESIDENT only: the list after the merge
     int32_t *cand = (int32_t *)newk;                          // [min(slots, FILTER_CHUNK)]
     uint64_t *pool = pool_g + (size_t)q * C;
     int32_t *cand_q = cand_g + (size_t)q * slots;
@@ -734,11 +724,25 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     // Everything the round needs first is requested at once, before any of it is looked at: the
     // workgroups of a launch start together, and every dependent trip to memory costs them all a few
     // microseconds.  (The worst entry is read whether or not the list is full: C >= 1.)
-    const int n_prev = counts[q];
+    const int n_prev = __builtin_amdgcn_readfirstlane(counts[q]);
     QState st = state[q];
-    const int off = offsets[q];
-    const uint64_t stored_worst = pool[C - 1];
+    const int off = __builtin_amdgcn_readfirstlane(offsets[q]);
+    const uint64_t stored_worst = RESIDENT ? 0 : pool[C - 1];
     if (n_prev < 0) return;  // finished or idle: counts[q] stays -1
+    // the state is the same in every lane: kept in scalar registers, it leaves the vector registers to the filter
+    st.t = __builtin_amdgcn_readfirstlane(st.t);
+    st.done = __builtin_amdgcn_readfirstlane(st.done);
+    st.n_list = __builtin_amdgcn_readfirstlane(st.n_list);
+    st.n_visited = __builtin_amdgcn_readfirstlane(st.n_visited);
+    st.W = __builtin_amdgcn_readfirstlane(st.W);
+    st.L = __builtin_amdgcn_readfirstlane(st.L);
+    st.cap = __builtin_amdgcn_readfirstlane(st.cap);
+    st.n_expanded = __builtin_amdgcn_readfirstlane(st.n_expanded);
+    st.first_open = __builtin_amdgcn_readfirstlane(st.first_open);
+    if (RESIDENT) {  // the whole list, not only its n_list valid entries: requested before the state has arrived
+#pragma unroll 4
+        for (int i = threadIdx.x; i < C; i += BLK) tile[i] = pool[i];
+    }
     if (st.done) {
         if (threadIdx.x == 0) counts[q] = -1;
         return;
@@ -759,7 +763,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
 
     // 1. the scores of the previous round (or of the seeds) become keys; those that cannot enter are dropped
     const bool full = (st.n_list == C);
-    const uint64_t worst = full ? stored_worst : KEY_SENTINEL;
+    const uint64_t worst = full ? (RESIDENT ? tile[C - 1] : stored_worst) : KEY_SENTINEL;
     int m = 0;
     for (int j0 = 0; j0 < n_prev; j0 += BLK) {
         int j = j0 + threadIdx.x;
@@ -779,8 +783,9 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     PHASE_MARK(1);  // new keys: scores load + filter
     int n_list = st.n_list;
     if (m > 0) {
-        if (m <= BLK && 2 * tile_keys >= BLK) {
-            rank_sort<BLK>(newk, m, (uint32_t *)tile);  // the tile buffer is free until the merge below
+        if (m <= BLK && 2 * tile_keys >= BLK && (!RESIDENT || 2 * C >= BLK)) {
+            // scratch: a buffer that is free until the merge below
+            rank_sort<BLK>(newk, m, (uint32_t *)(RESIDENT ? merged : tile));
         } else {
             int m2 = 2;
             while (m2 < m) m2 <<= 1;
@@ -789,8 +794,26 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
             bitonic_sort<BLK>(newk, m2);
         }
         PHASE_MARK(6);  // sort of the new keys
-        // 1b. merge into the stored list, tile by tile from the end
-        int hi = st.n_list, rem = m;
+        // 1b. merge into the stored list
+        if (RESIDENT) {
+            // by rank, into the second copy: an entry's position is its index in its own sequence plus the number
+            // of entries of the other sequence in front of it
+            for (int i = threadIdx.x; i < st.n_list + m; i += BLK) {
+                uint64_t key;
+                int pos;
+                if (i < st.n_list) {
+                    key = tile[i];
+                    pos = i + lower_bound_keys(newk, m, key);
+                } else {
+                    key = newk[i - st.n_list];
+                    pos = (i - st.n_list) + lower_bound_keys(tile, st.n_list, key);
+                    if (i == st.n_list) shared_i[0] = pos;  // rank of the first inserted entry
+                }
+                if (pos < C) merged[pos] = key;
+            }
+        }
+        // tile by tile from the end
+        int hi = st.n_list, rem = RESIDENT ? 0 : m;
         while (rem > 0) {
             const int lo = max(0, hi - tile_keys), cnt = hi - lo;
             for (int i = threadIdx.x; i < cnt; i += BLK) tile[i] = pool[lo + i];
@@ -815,10 +838,12 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         }
         n_list = min(C, st.n_list + m);
         // the scan below reads entries this workgroup has just stored
-        __threadfence_block();
+        if (!RESIDENT) __threadfence_block();
         __syncthreads();
     }
     PHASE_MARK(2);  // rank merge
+    // RESIDENT: the list as it stands now, in LDS
+    uint64_t *lw = RESIDENT ? (m > 0 ? merged : tile) : nullptr;
 
     // 2. termination test and choice of the parents
     int n_par = 0, n_live = 0;
@@ -850,7 +875,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int i = i0 + u * BLK + (int)threadIdx.x;
-                e[u] = (u < per && i < lim) ? pool[i] : KEY_SENTINEL;
+                e[u] = (u < per && i < lim) ? (RESIDENT ? lw[i] : pool[i]) : KEY_SENTINEL;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -862,6 +887,7 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
                 if (open && n_par + pos < st.W) {
                     parents[n_par + pos] = key_id(e[u]);
                     pool[i] = e[u] | 1ull;
+                    if (RESIDENT) lw[i] = e[u] | 1ull;  // the ranks from the first inserted entry on are stored below
                     if (n_par + pos == st.W - 1) shared_i[1] = i + 1;  // everything in front of it is expanded now
                 }
                 first_open = (n_par + tot >= st.W) ? -1 : min(i0 + BLK, lim);  // -1: taken from shared_i[1] below
@@ -873,6 +899,8 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     }
     __syncthreads();
     if (first_open < 0) first_open = shared_i[1];
+    if (RESIDENT && m > 0)  // what the merge moved: the ranks from the first inserted entry on
+        for (int i = shared_i[0] + threadIdx.x; i < n_list; i += BLK) pool[i] = lw[i];
     // a visited table that could not take this round's ids ends the query
     bool overflow = false;
     if (!BITMAP && n_par > 0 && (int64_t)st.n_visited + (int64_t)n_par * R > (int64_t)(hash_cap / 2)) {
@@ -881,15 +909,15 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     }
     if (n_par == 0) {
         if (threadIdx.x == 0) {
-            st.n_list = n_list;
-            st.first_open = first_open;
-            st.done = overflow ? 3 : 1;
-            state[q] = st;
+            state[q].n_list = n_list;
+            state[q].first_open = first_open;
+            state[q].done = overflow ? 3 : 1;
             counts[q] = -1;
         }
         return;
     }
 
+    if (RESIDENT) __syncthreads();  // the LDS copies of the list are dead from here on; their space is reused
     // 3. neighbour gather: one adjacency row per parent, consecutive lanes read consecutive ids;
     // 4. visited filter, 5. survivors of this query for the next MLP launch.
     // A round's candidates go through in pieces of at most `chunk` (what the dedupe tables in LDS hold).  An id
@@ -918,12 +946,11 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
     }
     PHASE_MARK(5);  // adjacency gather, dedupe + visited table
     if (threadIdx.x == 0) {
-        st.n_list = n_list;
-        st.first_open = first_open;
-        st.t += 1;
-        st.n_visited += n_new;
-        st.n_expanded += walkers ? n_live : n_par;
-        state[q] = st;
+        state[q].n_list = n_list;
+        state[q].first_open = first_open;
+        state[q].t = st.t + 1;
+        state[q].n_visited = st.n_visited + n_new;
+        state[q].n_expanded = st.n_expanded + (walkers ? n_live : n_par);
         counts[q] = n_new;
     }
 }
@@ -974,11 +1001,11 @@ static int tile_keys_of(const Plan &p) {
     return t;
 }
 
-static size_t round_smem(const Plan &p) {
+static size_t round_smem(const Plan &p, int list_keys = 0) {  // list_keys: list entries held in LDS (0: one tile)
     const int chunk = p.slots < FILTER_CHUNK ? p.slots : FILTER_CHUNK;
     int dd_n = 2;
     while (dd_n < 2 * chunk) dd_n <<= 1;
-    size_t lists = (size_t)(new_cap_of(p) + ((p.W_max + 1) & ~1) + tile_keys_of(p)) * 8;
+    size_t lists = (size_t)(new_cap_of(p) + ((p.W_max + 1) & ~1) + (list_keys > 0 ? list_keys : tile_keys_of(p))) * 8;
     size_t filt = (size_t)((chunk + 3) & ~3) * 4 + (size_t)dd_n * 16;
     return (size_t)((p.W_max + 3) & ~3) * 4 + 24 * 4 + (lists > filt ? lists : filt);
 }
@@ -1064,13 +1091,24 @@ int launch_round(const SearchArgs &a) {
     const int threads = half ? 128 : big ? ROUND_BIG_BLOCK : BLOCK;
     const bool bm = p.bitmap_words > 0;
     const bool pieces = p.slots > FILTER_CHUNK;  // then slots > ROUND_BIG_FROM too: the larger workgroup
-    auto fn = half ? (bm ? round_kernel<128, true, false> : round_kernel<128, false, false>)
-              : big ? (pieces ? (bm ? round_kernel<ROUND_BIG_BLOCK, true, true> : round_kernel<ROUND_BIG_BLOCK, false, true>)
-                              : (bm ? round_kernel<ROUND_BIG_BLOCK, true, false> : round_kernel<ROUND_BIG_BLOCK, false, false>))
-                    : (bm ? round_kernel<BLOCK, true, false> : round_kernel<BLOCK, false, false>);
+    const bool resident = !big && p.C <= tile_keys_of(p);
+    const int tile_keys = resident ? ((p.C + 1) & ~1) : tile_keys_of(p);  // resident: the list itself, twice
+    if (resident) smem = round_smem(p, tile_keys + p.C);
+    using Fn = decltype(&round_kernel<BLOCK, false, false, false>);
+    Fn fn;
+    if (big)
+        fn = pieces ? (bm ? round_kernel<ROUND_BIG_BLOCK, true, true, false> : round_kernel<ROUND_BIG_BLOCK, false, true, false>)
+                    : (bm ? round_kernel<ROUND_BIG_BLOCK, true, false, false> : round_kernel<ROUND_BIG_BLOCK, false, false, false>);
+    else if (half)
+        fn = resident ? (bm ? round_kernel<128, true, false, true> : round_kernel<128, false, false, true>)
+                      : (bm ? round_kernel<128, true, false, false> : round_kernel<128, false, false, false>);
+    else
+        fn = resident ? (bm ? round_kernel<BLOCK, true, false, true> : round_kernel<BLOCK, false, false, true>)
+                      : (bm ? round_kernel<BLOCK, true, false, false> : round_kernel<BLOCK, false, false, false>);
     if (smem > 48 * 1024) {
-        static std::atomic<uint32_t> raised[12];
-        if (int rc = raise_lds_limit((const void *)fn, 128 * 1024, a.m->device, raised[4 * which + (bm ? 2 : 0) + (pieces ? 1 : 0)]);
+        static std::atomic<uint32_t> raised[24];
+        if (int rc = raise_lds_limit((const void *)fn, 128 * 1024, a.m->device,
+                                     raised[8 * which + (bm ? 4 : 0) + (pieces ? 2 : 0) + (resident ? 1 : 0)]);
             rc != ANN_OK)
             return rc;
     }
@@ -1080,7 +1118,7 @@ int launch_round(const SearchArgs &a) {
                        (int32_t *)(a.ws + p.off_counts), (const int32_t *)(a.ws + p.off_offsets),
                        (const float *)(a.ws + p.off_scores), new_cap_of(p), p.W_max,
                        (int64_t *)(a.ws + p.off_stats), (uint16_t *)(a.ws + p.off_tag), a.walkers ? 1 : 0,
-                       tile_keys_of(p));
+                       tile_keys);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }
