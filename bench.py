@@ -137,6 +137,8 @@ def main() -> int:
     ap.add_argument("--no-stream", action="store_true", help="skip the continuous-batching run beside the headline")
     ap.add_argument("--no-halves", action="store_true", help="skip the two-half-batches-at-once run beside the headline")
     ap.add_argument("--no-walkers", action="store_true", help="skip the walker-rule run beside the headline")
+    ap.add_argument("--no-reference", action="store_true",
+                    help="skip the run at the configuration's own point (profile commands: one point per process)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the capped search on C1 and C2")
     ap.add_argument("--no-f16", action="store_true", help="skip the fp16 metric run beside the headline")
     ap.add_argument("--no-f8", action="store_true", help="skip the 8-bit metric run (on C2) beside the headline")
@@ -297,7 +299,7 @@ def main() -> int:
     timed_ids, out_sc_timed = out_ids.clone(), out_sc.clone()
     L_side = L_star if ragged else min(L_star, 8 * cfg.L)
     reference = None
-    if not ragged and (L_side != L_star or W != cfg.W):
+    if not ragged and (L_side != L_star or W != cfg.W) and not args.no_reference:
         del ws
         ws = torch.empty(ann.ann_search_workspace_bytes(g, m, Q, E, cfg.W, L_side, k, 0), dtype=torch.uint8,
                          device="cuda:0")
