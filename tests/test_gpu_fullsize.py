@@ -74,12 +74,15 @@ def _sample_check(wl, cfg, ids, sc, q_sel, W, L, cap, k, recall_k, act_round=1, 
 # sample sizes: the recall difference of two searches has a standard error of about 0.02/sqrt(n)
 # at these recall levels, so 1 point is > 5 standard errors
 # C3 at L = 1024 is the point the benchmark times when the recall sweep stops at its default end
-@pytest.mark.parametrize("preset,n_sample,L", [("C2", 128, 0), ("C3", 192, 0), ("C3", 64, 1024), ("C4", 128, 0)])
-def test_full_size_uniform(preset, n_sample, L):
+# and C3 at W = 64, L = 8192 the point it times when the sweep runs to the plateau of the recall curve (there the
+# list is merged through LDS tiles, the visited set is the bitmap and a round's candidates pass the filter in pieces)
+@pytest.mark.parametrize("preset,n_sample,L,W", [("C2", 128, 0, 0), ("C3", 192, 0, 0), ("C3", 64, 1024, 0),
+                                                 ("C3", 32, 8192, 64), ("C4", 128, 0, 0)])
+def test_full_size_uniform(preset, n_sample, L, W):
     cfg = PRESETS[preset]
     if L:
         from dataclasses import replace
-        cfg = replace(cfg, L=L)
+        cfg = replace(cfg, L=L, W=W or cfg.W)
     torch.cuda.empty_cache()  # C4 needs about 90 GB while its graph is being built
     wl = make_workload(cfg, device="cuda:0")
     dtype = ann.ANN_BF16
