@@ -311,6 +311,9 @@ def ann_search_ragged(g: Graph, m: Mlp, queries, entries, W_q, L_q, iters_q, W_m
     if out_ids is None:
         out_ids, out_scores = _alloc_out(Q, k, queries.device)
     _check_out(out_ids, out_scores, Q, k)
+    for name, t in (("W_q", W_q), ("L_q", L_q), ("iters_q", iters_q)):  # sizes first: they need no device
+        if t is None or t.numel() != Q:
+            raise ValueError(f"{name} must hold one int32 per query ({Q}), got {None if t is None else t.numel()}")
     rc = lib.ann_search_ragged(g.handle, m.handle, _queries_ptr(queries, m, Q), Q,
                                _dev_ptr(entries, "entries", torch.int32), E, _per_query_ptr(W_q, "W_q", Q),
                                _per_query_ptr(L_q, "L_q", Q), _per_query_ptr(iters_q, "iters_q", Q), W_max,

@@ -61,6 +61,75 @@ def test_errors_detected_before_any_device_work(lib):
     lib.ann_graph_free(g)
 
 
+def test_errors_of_the_later_entry_points_without_a_device(lib):
+    """Open stream, allocation-free pair scoring, progress time limit, pair scoring, noise, quantiser: every
+    argument error that can be seen before a HIP call comes back as ANN_EINVAL with a reason."""
+    vp = ctypes.c_void_p
+    out = vp()
+    assert lib.ann_stream_open(None, None, 8, 2, 1, 1, 4, 3, 0, vp(256), vp(256), vp(256), vp(256), vp(256), 1 << 20, None,
+                               ctypes.byref(out)) == -1
+    assert b"null" in lib.ann_last_error() and out.value is None
+    assert lib.ann_stream_open(None, None, 0, 2, 1, 1, 4, 3, 0, vp(256), vp(256), vp(256), vp(256), vp(256), 1 << 20, None,
+                               ctypes.byref(out)) == -1
+    assert b"capacity" in lib.ann_last_error()
+    assert lib.ann_stream_open(None, None, 8, 2, 1, 1, 4, 3, 0, vp(256), vp(256), vp(256), vp(256), vp(256), 1 << 20, None,
+                               None) == -1
+    assert lib.ann_stream_submit(None, 1) == -1 and lib.ann_stream_step(None, 1) == -1 and lib.ann_stream_drain(None) == -1
+    assert lib.ann_stream_close(None) == 0          # closing nothing is not an error
+    assert lib.ann_search_stream_workspace_bytes(None, None, 8, 0, 1, 1, 4, 3, 0) == 0
+    assert lib.ann_score_pairs_noalloc(None, None, vp(256), 1, 4, vp(256), vp(256), vp(256), None) == -1
+    assert lib.ann_score_pairs(None, None, vp(256), 1, 4, vp(256), vp(256), vp(256), 0, None) == -1
+    assert lib.ann_set_progress_timeout(ctypes.c_double(-1.0)) == -1
+    assert lib.ann_set_progress_timeout(ctypes.c_double(float("nan"))) == -1
+    assert lib.ann_set_progress_timeout(ctypes.c_double(600.0)) == 0
+    assert lib.ann_users_add_noise(vp(256), vp(256), 4, 0, 0, ctypes.c_double(1.0), 1, 0, None) == -1       # d < 1
+    assert lib.ann_users_add_noise(vp(256), vp(256), 4, 8, 2, ctypes.c_double(1.0), 1, 0, None) == -1       # 8-bit users
+    assert lib.ann_users_add_noise(vp(256), vp(256), 4, 8, 0, ctypes.c_double(-1.0), 1, 0, None) == -1      # sigma < 0
+    assert lib.ann_users_add_noise(None, None, 0, 8, 0, ctypes.c_double(1.0), 1, 0, None) == 0              # nothing to do
+    assert lib.ann_quantize_e4m3(vp(256), 3, 16, ctypes.c_float(1.0), vp(256), None) == -1                  # fp16 source
+    assert lib.ann_quantize_e4m3(vp(256), 0, 16, ctypes.c_float(0.0), vp(256), None) == -1                  # scale 0
+    assert lib.ann_quantize_e4m3(None, 0, 0, ctypes.c_float(1.0), None, None) == 0
+    # a graph handle and a search plan need no device: limits of the plan
+    g = vp()
+    assert lib.ann_graph_load(vp(256), vp(512), 1000, 32, 8, 0, 0, None, ctypes.byref(g)) == 0
+    assert lib.ann_search_workspace_bytes(g, None, 4, 1, 1, 1, 1, 0) == 0 and b"null" in lib.ann_last_error()
+    assert lib.ann_search_walkers_workspace_bytes(g, None, 4, 1, 0, 1) == 0 and b"T >= 1" in lib.ann_last_error()
+    lib.ann_graph_free(g)
+
+
+def test_binding_checks_shapes_before_the_library_is_called():
+    """The binding refuses tensors whose shapes the C entry points could not check (bare pointers), on CPU tensors
+    already: no GPU needed to see the refusal."""
+    import torch
+
+    import paper_2502_11490_amd.binding as b
+
+    class FakeMlp:
+        handle, dims, d_user, dtype = None, [8, 3], 4, b.ANN_F32
+
+    class FakeGraph:
+        handle = None
+
+    users = torch.zeros(5, 4)
+    with pytest.raises(ValueError, match="rows"):
+        b.ann_search(FakeGraph(), FakeMlp(), users, torch.zeros(6, 2, dtype=torch.int32), 1, 4, 3, 1,
+                     workspace=torch.zeros(8, dtype=torch.uint8))
+    with pytest.raises(ValueError, match=r"\[Q\]\[4\]"):
+        b.ann_search(FakeGraph(), FakeMlp(), torch.zeros(5, 3), torch.zeros(5, 2, dtype=torch.int32), 1, 4, 3, 1,
+                     workspace=torch.zeros(8, dtype=torch.uint8))
+    with pytest.raises(ValueError, match="out_ids"):
+        b.ann_search(FakeGraph(), FakeMlp(), users, torch.zeros(5, 2, dtype=torch.int32), 1, 4, 3, 1,
+                     workspace=torch.zeros(8, dtype=torch.uint8), out_ids=torch.zeros(5, 2, dtype=torch.int32),
+                     out_scores=torch.zeros(5, 3))
+    with pytest.raises(ValueError, match="one int32 per query"):
+        b.ann_search_ragged(FakeGraph(), FakeMlp(), users, torch.zeros(5, 2, dtype=torch.int32),
+                            torch.zeros(4, dtype=torch.int32), torch.zeros(5, dtype=torch.int32),
+                            torch.zeros(5, dtype=torch.int32), 2, 8, 3, 4, workspace=torch.zeros(8, dtype=torch.uint8),
+                            out_ids=torch.zeros(5, 3, dtype=torch.int32), out_scores=torch.zeros(5, 3))
+    with pytest.raises(ValueError, match="pairs"):
+        b.ann_score_pairs(FakeGraph(), FakeMlp(), users, torch.zeros(7, dtype=torch.int32), torch.zeros(6, dtype=torch.int32))
+
+
 def test_missing_library_is_loud(monkeypatch):
     import paper_2502_11490_amd.binding as b
 
