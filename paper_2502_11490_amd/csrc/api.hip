@@ -175,11 +175,6 @@ struct Mailbox {
         if (seq == 0) seq = 1;
         return seq << 40;
     }
-    // Queries still running at the last round the device reported for this search, -1 = nothing reported yet.
-    int64_t running(uint64_t tag) const {
-        const uint64_t w = host[1];
-        return (w >> 40) == (tag >> 40) ? (int64_t)(w & 0xFFFFFFFFull) : -1;
-    }
     // Before enqueuing round `i` (0-based): 1 = the search has finished, 0 = go on, -1 = the stream reports an
     // error, or has run everything enqueued so far without the progress the kernels would have reported.
     // A wait that lasts (20 ms without the word it needs, again every 20 ms) asks the stream: a search enqueued

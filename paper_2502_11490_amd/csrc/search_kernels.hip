@@ -642,8 +642,6 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
             // nothing running and nothing waiting (open stream, Q_total < 0: nothing that has arrived so far)
             const int waiting_until = Q_total >= 0 ? Q_total : *(volatile int32_t *)&ctrl->avail;
             const bool finished = n_active == 0 && (Q_total == 0 || ctrl->next_query >= waiting_until);
-            __hip_atomic_store(mailbox + 1, (mail_word & ~0xFFFFFFFFFFull) | (uint64_t)(uint32_t)n_active,
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);  // a hint only: see round_kernel
             __hip_atomic_store(mailbox, mail_word | (finished ? 1ull : 0ull), __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_SYSTEM);
         }
