@@ -255,6 +255,23 @@ def test_search_ragged_fp32():
     assert same_list_fraction(ids.cpu().numpy(), ref["ids"]) >= 0.99
 
 
+def test_search_ragged_fp32_long_lists():
+    """Per-query parameters with lists of several LDS tiles and rounds of several filter pieces for some queries
+    and tiny ones for others, in one batch."""
+    cfg = replace(scaled(PRESETS["C1"], 20000, n_clusters=20, Q=24), E=3)
+    wl = _with_biases(make_workload(cfg, seed=9), cfg, 18)
+    rng = np.random.default_rng(4)
+    Wq = rng.choice([1, 7, 64, 150], cfg.Q).astype(np.int32)
+    Lq = rng.choice([5, 700, 1500, 5000], cfg.Q).astype(np.int32)
+    cq = rng.choice([0, 3, 40], cfg.Q).astype(np.int32)
+    g, m, dev = open_handles(wl)
+    ids, _ = ann.ann_search_ragged(g, m, dev["users"], dev["entries"], torch.from_numpy(Wq).cuda(),
+                                   torch.from_numpy(Lq).cuda(), torch.from_numpy(cq).cuda(), 150, 5000, 120, 0)
+    h = to_host(wl)
+    ref = oracle.search(h["emb"], h["adj"], h["users"], oracle_mlp(h), h["entries"], Wq, Lq, 120, cq, n_threads=8)
+    assert same_list_fraction(ids.cpu().numpy(), ref["ids"]) >= 0.99
+
+
 def _reachable(adj, seeds):
     seen = set(int(s) for s in seeds)
     todo = list(seen)
@@ -486,7 +503,8 @@ def test_streamed_search_empty_and_errors():
 
 
 # ----------------------------------------------------------------------------- walkers (paper-literal variant)
-@pytest.mark.parametrize("E,T,k", [(1, 6, 10), (4, 1, 30), (5, 9, 64), (16, 3, 200)])
+# (100 walkers of degree 16: 1,600 candidates per hop pass the visited filter in two pieces)
+@pytest.mark.parametrize("E,T,k", [(1, 6, 10), (4, 1, 30), (5, 9, 64), (16, 3, 200), (100, 4, 300)])
 def test_walker_search_fp32_matches_oracle(E, T, k):
     cfg = replace(scaled(PRESETS["C1"], 5000, n_clusters=8, Q=37), E=E)
     wl = _with_biases(make_workload(cfg, seed=41), cfg, 17)
@@ -680,11 +698,13 @@ def test_capped_search_replays_from_a_hip_graph(preset, N, cap):
         assert st.queries == cfg.Q and st.max_query_iters <= cap
 
 
-@pytest.mark.parametrize("slots,first,rounds_between", [(16, 40, 5), (7, 1, 0), (64, 99, 30)])
-def test_open_stream_second_wave_joins_running_search(slots, first, rounds_between):
+@pytest.mark.parametrize("slots,first,rounds_between,visited", [(16, 40, 5, "hash"), (7, 1, 0, "hash"), (64, 99, 30, "hash"),
+                                                                (16, 40, 5, "bitmap")])
+def test_open_stream_second_wave_joins_running_search(slots, first, rounds_between, visited, monkeypatch):
     """Queries that arrive while others are being searched (Sec. 3.2, Q-HiPANNS): a first wave is submitted and
     searched for a few rounds, then the rest is written into the arrays and submitted; every query's result must
     be the one the batched search gives, and the counters must add up."""
+    monkeypatch.setenv("GMPGR_VISITED_SET", visited)
     cfg = replace(scaled(PRESETS["C1"], 5000, n_clusters=8, Q=100), E=3)
     wl = _with_biases(make_workload(cfg, seed=21), cfg, 17)
     g, m, dev = open_handles(wl)
