@@ -140,6 +140,7 @@ def main() -> int:
     ap.add_argument("--no-reference", action="store_true",
                     help="skip the run at the configuration's own point (profile commands: one point per process)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the capped search on C1 and C2")
+    ap.add_argument("--no-exhaustive", action="store_true", help="skip the library's own exhaustive search on the sample")
     ap.add_argument("--no-f16", action="store_true", help="skip the fp16 metric run beside the headline")
     ap.add_argument("--no-f8", action="store_true", help="skip the 8-bit metric run (on C2) beside the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -188,6 +189,25 @@ def main() -> int:
     log(f"exhaustive ground truth for {n_gt} queries in {time.time() - t1:.1f} s")
     sel = torch.tensor(q_sel, device="cuda:0")
     users_s, entries_s = users[sel].contiguous(), entries[sel].contiguous()
+
+    # ---- the library's own exhaustive search (same metric kernels as the graph search) on the same sample:
+    #      reported beside the headline; the recall ground truth stays the independent fp32 one above ----
+    exhaustive = None
+    if not args.no_exhaustive:
+        ann.ann_brute_force(g, m, users_s[:1].contiguous(), kr)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        bf_ids, _ = ann.ann_brute_force(g, m, users_s, kr)
+        torch.cuda.synchronize()
+        bf_s = time.perf_counter() - t1
+        fl = flops_per_pair(cfg.dims, cfg.d, hoisted=bool(mfma))
+        exhaustive = {"queries": n_gt, "ms": round(1e3 * bf_s, 2), "queries_per_s": round(n_gt / bf_s, 1),
+                      "scores_per_s": round(n_gt * cfg.N / bf_s, 1),
+                      "TFLOPs": round(n_gt * cfg.N * fl / bf_s / 1e12, 1),
+                      "recall_at_100_vs_fp32_ground_truth": round(recall_at(bf_ids.cpu(), truth.cpu(), kr), 4)}
+        log(f"exhaustive search by the library, {n_gt} queries x {cfg.N} items: {1e3 * bf_s:.0f} ms, "
+            f"{exhaustive['scores_per_s']:.3e} scores/s, {exhaustive['TFLOPs']} TFLOP/s, agreement with the fp32 "
+            f"ground truth (recall@{kr}) {exhaustive['recall_at_100_vs_fp32_ground_truth']}")
 
     def search_sample(Wx, L):
         if ragged:
@@ -818,7 +838,7 @@ def main() -> int:
             "reference_point": reference, "rows_beside_the_headline_run_at": {"W": W_side, "L": L_side},
             "layered_search": layered, "continuous_batching": streamed, "concurrent_halves": halves,
             "walker_search": walkers, "f8_metric": f8, "f16_metric": f16,
-            "hip_graph_capped_search": graphs_cmp,
+            "hip_graph_capped_search": graphs_cmp, "exhaustive_search": exhaustive,
         },
         "roofline": roofline,
         "cpu_baseline": cpu,

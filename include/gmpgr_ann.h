@@ -323,6 +323,21 @@ int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_de
                     int32_t tile_rows, void *stream);
 
 /*
+ * Exhaustive search: the k most relevant items of the whole table for every query, under the same
+ * relevance (Eq. 5-8) and the same scoring kernels the graph search uses: the ground truth that the recall
+ * measure (Sec. 5.1.3) compares a search with, at the metric's own precision.
+ * queries_dev: [Q][d_user]; out_ids_dev: [Q][k] int32, out_scores_dev: [Q][k] fp32, device memory, written.
+ * Order: relevance descending, equal relevances by ascending id (the order of the search's results);
+ * with k above the number of items the row ends with id -1 / relevance -inf.  1 <= k <= 2,048.
+ * Cost: Q x N relevance scores (the adjacency of `g` is not used).  The call allocates and frees a
+ * temporary (about 200 MB + Q x k x 8 bytes + the per-query user terms) and synchronises `stream`.
+ * ANN_EINVAL for a null handle or pointer, a metric that does not match the graph, Q < 1, k out of range;
+ * ANN_ENOMEM if the temporary cannot be allocated.
+ */
+int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int32_t k,
+                    int32_t *out_ids_dev, float *out_scores_dev, void *stream);
+
+/*
  * ann_score_pairs for callers that cannot allocate device memory: code whose stream is being recorded
  * into a HIP graph, tight serving loops, harnesses that forbid allocation.  Same arguments and result as
  * ann_score_pairs (default batch size); the call makes no allocation of any kind and does not

@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgmpgr_ann.so")
-SOURCES = ["api.hip", "search_kernels.hip", "mlp_alu.hip", "mlp_mfma.hip", "mlp_mfma_stream.hip", "mlp_mfma_f8.hip", "noise.hip", "noalloc.hip"]
+SOURCES = ["api.hip", "search_kernels.hip", "mlp_alu.hip", "mlp_mfma.hip", "mlp_mfma_stream.hip", "mlp_mfma_f8.hip", "noise.hip", "noalloc.hip",
+           "brute_force.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 instructions

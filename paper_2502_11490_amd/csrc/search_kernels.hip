@@ -12,6 +12,7 @@
 //                 copy of every group into the dense pair list (query-major, first-found
 //                 first), which the MLP kernel cuts into fixed-size batches
 #include "common.h"
+#include "keys.h"
 
 namespace gmpgr {
 
@@ -59,20 +60,6 @@ constexpr int SCAN_WAVES = SCAN_BLOCK / 64;
 #define PHASE_START
 #endif
 
-// ---- order-preserving key: ascending uint64 == (score descending, id ascending) ----------
-__device__ __forceinline__ uint64_t make_key(float score, int32_t id, uint32_t expanded) {
-    uint32_t f = __float_as_uint(score);
-    uint32_t asc = (f & 0x80000000u) ? ~f : (f | 0x80000000u);
-    return ((uint64_t)(~asc) << 32) | ((uint64_t)(uint32_t)id << 1) | expanded;
-}
-__device__ __forceinline__ float key_score(uint64_t key) {
-    uint32_t asc = ~(uint32_t)(key >> 32);
-    uint32_t f = (asc & 0x80000000u) ? (asc ^ 0x80000000u) : ~asc;
-    return __uint_as_float(f);
-}
-__device__ __forceinline__ int32_t key_id(uint64_t key) { return (int32_t)((uint32_t)key >> 1); }
-__device__ __forceinline__ uint32_t key_expanded(uint64_t key) { return (uint32_t)key & 1u; }
-
 __device__ __forceinline__ uint32_t hash_id(uint32_t id) { return id * 0x9E3779B1u; }
 
 // Exclusive prefix count of `flag` over the workgroup in thread order; *total = block sum.
@@ -94,41 +81,6 @@ __device__ __forceinline__ int block_excl_count(bool flag, int *wave_sums, int *
     __syncthreads();
     *total = tot;
     return base + excl;
-}
-
-// Ascending bitonic sort of keys[0..n) in LDS, n a power of two.  Thread t owns the t-th
-// compare-exchange of every step (and t + BLOCK, ...): for strides up to 64 the 64 threads of a
-// wave then touch one and the same 128-key segment step after step, so those steps need no
-// workgroup barrier, only the wave's own program order (LDS executes a wave's operations in
-// order); a barrier is needed around the steps with larger strides and at the end.
-__device__ __forceinline__ void wave_lds_fence() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-template <int BLK>
-__device__ void bitonic_sort(uint64_t *keys, int n) {
-    for (int k = 2; k <= n; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            const bool across_waves = j > 64;
-            if (across_waves) __syncthreads();
-            for (int t = threadIdx.x; t < (n >> 1); t += BLK) {
-                // t-th compare-exchange of this step: indices i < ixj
-                int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                int ixj = i | j;
-                bool up = ((i & k) == 0);
-                uint64_t a = keys[i], b = keys[ixj];
-                if ((a > b) == up) {
-                    keys[i] = b;
-                    keys[ixj] = a;
-                }
-            }
-            if (across_waves) __syncthreads();
-            else wave_lds_fence();
-        }
-    }
-    __syncthreads();
 }
 
 // Sorts keys[0..m), 1 <= m <= BLK, ascending, by counting: the keys are distinct, so the rank of a key is the
@@ -680,16 +632,6 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
 // (a lower bound of the first unexpanded rank: it falls to the first insertion point of a round and
 // otherwise only grows).  The scan for the first <= W unexpanded entries among the first L ranks starts
 // there, reading the list in pieces of one entry per thread (four per thread after the first piece).
-__device__ __forceinline__ int lower_bound_keys(const uint64_t *a, int n, uint64_t key) {
-    int lo = 0, hi = n;
-    while (lo < hi) {
-        int mid = (lo + hi) >> 1;
-        if (a[mid] < key) lo = mid + 1;
-        else hi = mid;
-    }
-    return lo;
-}
-
 // Eight workgroups of 256 threads fill a CU's wave slots; that needs no more than 64 registers per lane.
 // BITMAP: the visited set is one bit per item (hash_cap < 0), else the hash table.  PIECES: a round may bring more
 // candidates than pass the filter at once (both are compile-time so that each build holds one filter, once, in

@@ -62,7 +62,8 @@ def test_errors_detected_before_any_device_work(lib):
 
 
 def test_errors_of_the_later_entry_points_without_a_device(lib):
-    """Open stream, allocation-free pair scoring, progress time limit, pair scoring, noise, quantiser: every
+    """Open stream, allocation-free pair scoring, exhaustive search, progress time limit, pair scoring, noise,
+    quantiser: every
     argument error that can be seen before a HIP call comes back as ANN_EINVAL with a reason."""
     vp = ctypes.c_void_p
     out = vp()
@@ -79,6 +80,7 @@ def test_errors_of_the_later_entry_points_without_a_device(lib):
     assert lib.ann_search_stream_workspace_bytes(None, None, 8, 0, 1, 1, 4, 3, 0) == 0
     assert lib.ann_score_pairs_noalloc(None, None, vp(256), 1, 4, vp(256), vp(256), vp(256), None) == -1
     assert lib.ann_score_pairs(None, None, vp(256), 1, 4, vp(256), vp(256), vp(256), 0, None) == -1
+    assert lib.ann_brute_force(None, None, vp(256), 1, 4, vp(256), vp(256), None) == -1 and b"null" in lib.ann_last_error()
     assert lib.ann_set_progress_timeout(ctypes.c_double(-1.0)) == -1
     assert lib.ann_set_progress_timeout(ctypes.c_double(float("nan"))) == -1
     assert lib.ann_set_progress_timeout(ctypes.c_double(600.0)) == 0
