@@ -141,6 +141,7 @@ def main() -> int:
                     help="skip the run at the configuration's own point (profile commands: one point per process)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the capped search on C1 and C2")
     ap.add_argument("--no-exhaustive", action="store_true", help="skip the library's own exhaustive search on the sample")
+    ap.add_argument("--no-locality", action="store_true", help="skip the run on cluster-ordered item ids beside the headline")
     ap.add_argument("--no-f16", action="store_true", help="skip the fp16 metric run beside the headline")
     ap.add_argument("--no-f8", action="store_true", help="skip the 8-bit metric run (on C2) beside the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -679,6 +680,37 @@ def main() -> int:
             f"scoring {prof16['score'][0]:.2f} ms")
         del ws16, g16, m16, emb16, users16
 
+    # ---- the same problem with the items labelled in cluster order (a cluster's members have consecutive ids):
+    #      what id locality is worth to the gathers and to the visited set; beside the headline, never the timed step ----
+    locality = None
+    if not ragged and not args.no_locality:
+        wl_c = make_workload(cfg, device="cuda:0", contiguous_ids=True)
+        g_c = ann.ann_graph_load(wl_c["adj"], wl_c["emb"])
+        ws_c = torch.empty(ann.ann_search_workspace_bytes(g_c, m, Q, E, W, L_star, k, 0), dtype=torch.uint8, device="cuda:0")
+        run = lambda: ann.ann_search(g_c, m, wl_c["users"], wl_c["entries"], W, L_star, k, 0, workspace=ws_c)
+        run()
+        torch.cuda.synchronize()
+        t10 = time.perf_counter()
+        for _ in range(3):
+            ids_c, _ = run()
+        torch.cuda.synchronize()
+        ms_c = 1e3 * (time.perf_counter() - t10) / 3
+        ann.ann_profile_enable(True)
+        ann.ann_profile_read()
+        run()
+        torch.cuda.synchronize()
+        prof_c = ann.ann_profile_read()
+        ann.ann_profile_enable(False)
+        st_c = ann.ann_search_stats(ws_c)
+        truth_c = wl_c["relabel"][truth]
+        locality = {"W": W, "L": L_star, "ms_per_search": round(ms_c, 3), "queries_per_s": round(Q / ms_c * 1e3, 1),
+                    "recall_at_100": round(recall_at(ids_c[sel].cpu(), truth_c.cpu(), kr), 4),
+                    "pairs_scored": int(st_c.pairs_scored),
+                    "stage_ms": {n: round(prof_c[n][0], 3) for n in ("score", "round", "pack") if n in prof_c}}
+        log(f"cluster-ordered item ids at W={W} L={L_star}: {ms_c:.2f} ms per search, recall@{kr} = "
+            f"{locality['recall_at_100']}, stages {locality['stage_ms']}")
+        del ws_c, g_c, wl_c
+
     # ---- what a plain copy reaches on this machine (context for the bandwidth figures below; with
     #      --calibrate-copy it is also the reference of known size for the profiler's traffic counters) ----
     src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 255)
@@ -839,6 +871,7 @@ def main() -> int:
             "layered_search": layered, "continuous_batching": streamed, "concurrent_halves": halves,
             "walker_search": walkers, "f8_metric": f8, "f16_metric": f16,
             "hip_graph_capped_search": graphs_cmp, "exhaustive_search": exhaustive,
+            "cluster_ordered_item_ids": locality,
         },
         "roofline": roofline,
         "cpu_baseline": cpu,

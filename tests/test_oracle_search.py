@@ -436,6 +436,23 @@ def test_entry_order_batch_order_and_threading_do_not_matter():
     assert np.array_equal(base["ids"][:3], sub["ids"])
 
 
+def test_relabelling_the_items_relabels_the_result():
+    """The cluster-ordered labelling of the workload generator is the same problem: the search visits the same
+    items in the same order (relevances are distinct, so the tie rule by id never decides)."""
+    cfg = scaled(PRESETS["C1"], 3000, n_clusters=8, Q=10)
+    a = make_workload(cfg, seed=13)
+    b = make_workload(cfg, seed=13, contiguous_ids=True)
+    relabel = b["relabel"].numpy()
+    a, b = to_host(a), to_host(b)
+    cluster = b["cluster"]
+    assert np.all(cluster[1:] >= cluster[:-1])
+    mlp = oracle.Mlp(a["W"], a["b"], a["head_w"])
+    ra = oracle.search(a["emb"], a["adj"], a["users"], mlp, a["entries"], 3, 40, 15, 0, trace=True)
+    rb = oracle.search(b["emb"], b["adj"], b["users"], mlp, b["entries"], 3, 40, 15, 0, trace=True)
+    assert np.array_equal(relabel[ra["ids"]], rb["ids"]) and np.array_equal(ra["scores"], rb["scores"])
+    assert np.array_equal(ra["n_scored"], rb["n_scored"])
+
+
 def test_per_query_parameters_equal_separate_runs():
     cfg = scaled(PRESETS["C1"], 3000, n_clusters=8, Q=6)
     wl = to_host(make_workload(cfg, seed=8))

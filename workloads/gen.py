@@ -232,8 +232,14 @@ def _fill_random_edges(adj: torch.Tensor, gen: torch.Generator, chunk: int = 1 <
             raise RuntimeError("random edge fill did not converge")
 
 
-def make_workload(cfg: Config, device="cpu", seed: int = SEED_BASE, with_graph: bool = True) -> Dict:
+def make_workload(cfg: Config, device="cpu", seed: int = SEED_BASE, with_graph: bool = True,
+                  contiguous_ids: bool = False) -> Dict:
     """Builds every input of one configuration on `device`.
+
+    contiguous_ids: the same items, graph, users and seeds with the items labelled in cluster order (the members
+    of a cluster have consecutive ids) instead of by the seeded random permutation; `relabel` [N] int64 then
+    maps an id of the standard labelling to the id of the same item here.  A variant for measurements of what
+    id locality is worth; every test and the timed step use the standard labelling.
 
     Returns a dict of torch tensors:
       emb [N,d] (f32|bf16), adj [N,R] int32, W (list, f32|bf16), b (list, f32), head_w [J] f32,
@@ -254,6 +260,12 @@ def make_workload(cfg: Config, device="cpu", seed: int = SEED_BASE, with_graph: 
         x[s:e] = means[assign_sorted[s:e]] + cfg.sigma * torch.randn(e - s, d, generator=g_noise, device=dev)
     perm = torch.randperm(N, generator=_gen(dev, seed + 5), device=dev)  # position -> id
     out: Dict = {"cfg": cfg, "seed": seed}
+    relabel = None
+    if contiguous_ids:
+        relabel = torch.empty(N, dtype=torch.int64, device=dev)
+        relabel[perm] = torch.arange(N, device=dev)  # standard id -> position = id in this labelling
+        perm = torch.arange(N, device=dev)
+        out["relabel"] = relabel
     if with_graph:
         adj_pos = _build_graph(x, starts, counts, cfg.R, seed)  # positions
         adj = torch.empty(N, cfg.R, dtype=torch.int32, device=dev)
@@ -297,6 +309,8 @@ def make_workload(cfg: Config, device="cpu", seed: int = SEED_BASE, with_graph: 
         if n == 0:
             break
         ent[dup] = torch.randint(0, N, (n,), generator=g_e, device=dev)
+    if relabel is not None:
+        ent = relabel[ent]
     out["entries"] = ent.to(torch.int32).contiguous()
 
     if cfg.ragged:
