@@ -93,21 +93,27 @@ def kernel_source_id(names=("mlp_mfma_stream.hip", "mlp_mfma_stream_asm.inc", "m
     return h.hexdigest()[:16]
 
 
-def recorded_traffic(workload: str, W: int, L: int):
-    """HBM bytes per launch of the MLP kernel, as measured with rocprofv3 FETCH_SIZE / WRITE_SIZE for this
-    workload, W and L (profiles/<workload>_W<W>_L<L>_hbm_traffic.txt).  None if no such measurement is
-    committed or if it was taken on other kernel sources than the ones in the tree (a stale figure)."""
+ROUND_KERNEL_SOURCES = ("search_kernels.hip", "keys.h")
+
+
+def recorded_traffic(workload: str, W: int, L: int, kernel: str = "mlp"):
+    """HBM bytes per launch of the MLP kernel (kernel="mlp") or of the round kernel ("round"), as measured with
+    rocprofv3 FETCH_SIZE / WRITE_SIZE for this workload, W and L (profiles/<workload>_W<W>_L<L>_hbm_traffic.txt).
+    None if no such measurement is committed or if it was taken on other kernel sources than the ones in the
+    tree (a stale figure)."""
     path = os.path.join(ROOT, "profiles", f"{workload.lower()}_W{W}_L{L}_hbm_traffic.txt")
+    key = "mlp_kernel" if kernel == "mlp" else "round_kernel"
+    want = kernel_source_id() if kernel == "mlp" else kernel_source_id(ROUND_KERNEL_SOURCES)
     value, stamp = None, None
     try:
         for line in open(path):
-            if line.startswith("mlp_kernel_traffic_bytes_per_launch="):
+            if line.startswith(f"{key}_traffic_bytes_per_launch="):
                 value = float(line.split("=", 1)[1])
-            if line.startswith("kernel_source_id="):
+            if line.startswith("kernel_source_id=" if kernel == "mlp" else "round_kernel_source_id="):
                 stamp = line.split("=", 1)[1].strip()
     except OSError:
         return None
-    return value if stamp == kernel_source_id() else None
+    return value if stamp == want else None
 
 
 def flops_per_pair(dims, d_user, hoisted):
@@ -759,6 +765,21 @@ def main() -> int:
     es = 2 if cfg.dtype == "bf16" else 4
     round_bytes = st.adjacency_bytes                      # the library's own figures (ann_search_stats)
     gather_bytes = st.embedding_bytes + st.pairs_scored * 8
+    # the round kernel (parent choice, neighbour gather, visited filter, merge) against the HBM peak: by the
+    # algorithmic bytes (adjacency rows) and by what the hardware counters saw it move (profiles/)
+    round_us = 1e3 * round_ms / max(round_launches, 1)
+    round_algo = round_bytes / max(round_launches // args.profile_steps, 1)
+    round_traffic = recorded_traffic(cfg.name, W, L_star, "round")
+    roofline_round = {"bound": "hbm", "achieved": round(round_algo / (round_us * 1e-6) / 1e9, 2), "peak": HBM_PEAK_GBS,
+                      "unit": "GB/s", "frac": round(round_algo / (round_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 5),
+                      "traffic": round_traffic,
+                      "traffic_GBps": None if round_traffic is None else round(round_traffic / (round_us * 1e-6) / 1e9, 1),
+                      "traffic_frac": None if round_traffic is None
+                      else round(round_traffic / (round_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                      "kernel": "round_kernel", "avg_launch_us": round(round_us, 2),
+                      "launches_per_step": round_launches // args.profile_steps,
+                      "note": "achieved counts adjacency rows only (R x 4 B per expanded node); traffic is rocprofv3 "
+                              "FETCH_SIZE + WRITE_SIZE per launch: the list, the visited set, scores and ids besides"}
     stages = {
         "score_ms_per_step": round(score_ms / args.profile_steps, 4),
         "round_ms_per_step": round(round_ms / args.profile_steps, 4),
@@ -874,6 +895,7 @@ def main() -> int:
             "cluster_ordered_item_ids": locality,
         },
         "roofline": roofline,
+        "roofline_round_kernel": roofline_round,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
