@@ -3,6 +3,7 @@ argument errors that are detected before any HIP call come back as error codes (
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -205,3 +206,19 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "one GPU" in r.stderr or "--gpus 1" in r.stderr
     assert not r.stdout.strip()
+
+
+def test_the_abi_from_plain_c(lib, tmp_path):
+    """tests/c_abi_check.c: the header compiles as C99 with warnings as errors, every entry point links with the
+    header's prototype, and the argument errors come back from C as they do through ctypes."""
+    import paper_2502_11490_amd as ann
+
+    libdir = os.path.dirname(ann.lib_path())
+    exe = str(tmp_path / "c_abi_check")
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c_abi_check.c"), "-o", exe, "-L", libdir, "-lgmpgr_ann",
+           f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0 and "c abi ok" in run.stdout, run.stdout + run.stderr
