@@ -338,6 +338,21 @@ int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void *queries_de
                     int32_t *out_ids_dev, float *out_scores_dev, void *stream);
 
 /*
+ * Re-ranking: the k most relevant of each query's n candidate items under this metric.  Meant for the lists a
+ * search returned under a cheaper metric (the 8-bit one of Sec. 4.3's quantised deployment): the traversal runs
+ * in 8 bits, its best n candidates are scored once more in 16 bits, and the order of the result is the 16-bit
+ * metric's.  The re-ranking itself is not in the paper; the relevance is Eq. 5-8, by the search's kernels.
+ * cand_dev: [Q][n] int32 item ids, device memory, read only; entries outside [0, N) (the -1 padding of a search
+ * result) are no candidates; an id that occurs several times is returned as often.  1 <= n <= 65,536.
+ * Result as ann_brute_force: [Q][k], relevance descending, equal relevances by ascending id, -1 / -inf where
+ * a query has fewer than k candidates.  1 <= k <= 2,048.  Allocates and frees a temporary (n x 8 bytes per query
+ * of a pass of at most 2^24 pairs, + Q x k x 8 + the per-query user terms) and synchronises `stream`.
+ * Errors as ann_brute_force; ANN_EINVAL also for a null cand_dev or n out of range.
+ */
+int ann_rerank(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, const int32_t *cand_dev,
+               int32_t n, int32_t k, int32_t *out_ids_dev, float *out_scores_dev, void *stream);
+
+/*
  * ann_score_pairs for callers that cannot allocate device memory: code whose stream is being recorded
  * into a HIP graph, tight serving loops, harnesses that forbid allocation.  Same arguments and result as
  * ann_score_pairs (default batch size); the call makes no allocation of any kind and does not

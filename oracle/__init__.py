@@ -239,6 +239,29 @@ def brute_force(emb: np.ndarray, users: np.ndarray, mlp: Mlp, k: int, act_round:
     return {"ids": ids, "scores": scores}
 
 
+def rerank(emb: np.ndarray, users: np.ndarray, mlp: Mlp, cand: np.ndarray, k: int, act_round: int = 0,
+           n_threads: int = 1) -> Dict:
+    """The k most relevant of each query's candidates cand [Q][n] (relevance of Eq. 5-8 by score_pairs, then the
+    search's order: relevance descending, equal relevances by ascending id; numpy's lexsort is the sort).  Ids
+    outside the table are no candidates; an id that occurs several times is kept as often.  Rows with fewer than
+    k candidates end with id -1 / relevance -inf.  All ids of the table as candidates is brute_force."""
+    cand = np.asarray(cand)
+    Q, n = cand.shape
+    N = emb.shape[0]
+    ids = np.full((Q, k), -1, dtype=np.int32)
+    scores = np.full((Q, k), -np.inf, dtype=np.float32)
+    for q in range(Q):
+        c = cand[q][(cand[q] >= 0) & (cand[q] < N)].astype(np.int32)
+        if c.size == 0:
+            continue
+        s = score_pairs(emb, users, mlp, np.full(c.size, q, dtype=np.int32), c, act_round=act_round,
+                        n_threads=n_threads)
+        order = np.lexsort((c, -s.astype(np.float64)))[:k]
+        ids[q, :order.size] = c[order]
+        scores[q, :order.size] = s[order]
+    return {"ids": ids, "scores": scores}
+
+
 def recall_at(found_ids: np.ndarray, truth_ids: np.ndarray, k: int) -> float:
     """Rec@k of Sec. 5.1.3: share of the true top-k found among the first k returned."""
     hits = 0

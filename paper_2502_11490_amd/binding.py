@@ -23,7 +23,7 @@ EXPORTS = [
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
     "ann_search_layers", "ann_search_walkers_workspace_bytes", "ann_search_walkers",
     "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_stream_open", "ann_stream_submit", "ann_stream_step",
-    "ann_stream_drain", "ann_stream_close", "ann_score_pairs", "ann_score_pairs_noalloc", "ann_brute_force", "ann_users_add_noise", "ann_quantize_e4m3",
+    "ann_stream_drain", "ann_stream_close", "ann_score_pairs", "ann_score_pairs_noalloc", "ann_brute_force", "ann_rerank", "ann_users_add_noise", "ann_quantize_e4m3",
     "ann_search_stats", "ann_set_progress_timeout", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
@@ -102,6 +102,8 @@ def load_library():
     lib.ann_score_pairs_noalloc.restype = ctypes.c_int
     lib.ann_brute_force.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
     lib.ann_brute_force.restype = ctypes.c_int
+    lib.ann_rerank.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp, vp]
+    lib.ann_rerank.restype = ctypes.c_int
     lib.ann_users_add_noise.argtypes = [vp, vp, i32, i32, i32, ctypes.c_double, ctypes.c_uint64, ctypes.c_uint64, vp]
     lib.ann_users_add_noise.restype = ctypes.c_int
     lib.ann_quantize_e4m3.argtypes = [vp, i32, i64, ctypes.c_float, vp, vp]
@@ -519,6 +521,26 @@ def ann_brute_force(g: Graph, m: Mlp, queries: torch.Tensor, k: int, out_ids: Op
     rc = lib.ann_brute_force(g.handle, m.handle, _queries_ptr(queries, m), Q, k,
                              _dev_ptr(out_ids, "out_ids", torch.int32),
                              _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
+    _check(rc)
+    return out_ids, out_scores
+
+
+def ann_rerank(g: Graph, m: Mlp, queries: torch.Tensor, cand: torch.Tensor, k: int,
+               out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None, stream=None):
+    """The k most relevant of each query's candidates cand [Q][n] (int32; ids outside the table are skipped)
+    under this metric: ids [Q][k] int32, relevances [Q][k] fp32."""
+    lib = load_library()
+    Q = queries.shape[0]
+    if cand.dim() != 2 or cand.shape[0] != Q:
+        raise ValueError(f"cand must be [{Q}][n], got {tuple(cand.shape)}")
+    if out_ids is None:
+        out_ids = torch.empty(Q, k, dtype=torch.int32, device=queries.device)
+    if out_scores is None:
+        out_scores = torch.empty(Q, k, dtype=torch.float32, device=queries.device)
+    _check_out(out_ids, out_scores, Q, k)
+    rc = lib.ann_rerank(g.handle, m.handle, _queries_ptr(queries, m), Q, _dev_ptr(cand, "cand", torch.int32),
+                        cand.shape[1], k, _dev_ptr(out_ids, "out_ids", torch.int32),
+                        _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
     _check(rc)
     return out_ids, out_scores
 

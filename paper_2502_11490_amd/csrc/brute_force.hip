@@ -6,6 +6,9 @@
 // kernel scores it (the same launchers the search uses, so an item's relevance here is bit for bit the one a
 // search sees), and one workgroup per query folds the chunk's scores into that query's running best-k list.
 // Order: relevance descending, ties by ascending id, i.e. ascending order-preserving keys, as in the search.
+//
+// ann_rerank is the same fold over a caller's candidate lists instead of the whole table: the lists of a search
+// under a cheaper metric (the 8-bit one) are scored again under this metric and its best k returned.
 #include "common.h"
 #include "keys.h"
 
@@ -24,7 +27,7 @@ bf_fill_pairs_kernel(int32_t *pair_q, int32_t *pair_id, int q0, int32_t i0, int 
     for (int p = blockIdx.x * blockDim.x + threadIdx.x; p < total; p += gridDim.x * blockDim.x) {
         const int q = p / nc;
         pair_q[p] = q0 + q;
-        pair_id[p] = i0 + (p - q * nc);
+        if (pair_id) pair_id[p] = i0 + (p - q * nc);
     }
 }
 
@@ -33,17 +36,20 @@ __global__ void __launch_bounds__(256) bf_clear_kernel(uint64_t *best, int64_t n
         best[i] = KEY_SENTINEL;
 }
 
-// Folds scores[b * nc .. (b + 1) * nc) (items i0 .. i0 + nc of query q0 + b) into best[(q0 + b) * k .. + k):
-// ascending keys, KEY_SENTINEL = no entry yet.  Keys that cannot enter (not below the current k-th) are dropped
+// Folds scores[b * nc .. (b + 1) * nc) of query q0 + b into best[(q0 + b) * k .. + k): ascending keys,
+// KEY_SENTINEL = no entry yet.  The scores belong to items i0 .. i0 + nc (ids == nullptr) or to the ids
+// ids[b * nc ..] (entries outside [0, N) are no candidates).  Keys that cannot enter (not below the current k-th) are dropped
 // as they are read; the others wait in an LDS buffer that is sorted and merged by rank whenever the next piece
 // might not fit.  Keys are distinct (an id appears once), so the merge's destinations are a permutation.
 __global__ void __launch_bounds__(BF_BLOCK)
-bf_topk_kernel(const float *__restrict__ scores, int nc, int32_t i0, uint64_t *best_g, int k, int q0) {
+bf_topk_kernel(const float *__restrict__ scores, int nc, int32_t i0, const int32_t *__restrict__ ids, int64_t N,
+               uint64_t *best_g, int k, int q0) {
     __shared__ uint64_t best[2][BF_KMAX];
     __shared__ uint64_t cand[BF_CAND];
     __shared__ int n_cand;
     __shared__ uint64_t worst;  // the k-th key, KEY_SENTINEL while fewer than k entries are held
     const float *row = scores + (size_t)blockIdx.x * nc;
+    const int32_t *row_ids = ids ? ids + (size_t)blockIdx.x * nc : nullptr;
     uint64_t *mine = best_g + (size_t)(q0 + blockIdx.x) * k;
     for (int i = threadIdx.x; i < k; i += BF_BLOCK) best[0][i] = mine[i];
     if (threadIdx.x == 0) n_cand = 0;
@@ -67,9 +73,9 @@ bf_topk_kernel(const float *__restrict__ scores, int nc, int32_t i0, uint64_t *b
             const int pos = i + lower_bound_keys(cand, n, key);
             if (pos < k) to[pos] = key;
         }
-        for (int j = threadIdx.x; j < n; j += BF_BLOCK) {
+        for (int j = threadIdx.x; j < n; j += BF_BLOCK) {  // behind equal keys of the list (a repeated candidate)
             const uint64_t key = cand[j];
-            const int pos = j + lower_bound_keys(from, n_best, key);
+            const int pos = j + lower_bound_keys(from, n_best, key + 1);
             if (pos < k) to[pos] = key;
         }
         n_best = min(k, n_best + n);
@@ -90,16 +96,17 @@ bf_topk_kernel(const float *__restrict__ scores, int nc, int32_t i0, uint64_t *b
         if (held + BF_PIECE > BF_CAND) fold(held);
         const uint64_t bar = worst;
         float s[4];
+        int32_t id[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int idx = base + r * BF_BLOCK + threadIdx.x;
             s[r] = idx < nc ? row[idx] : 0.0f;
+            id[r] = idx >= nc ? -1 : row_ids ? row_ids[idx] : i0 + idx;
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int idx = base + r * BF_BLOCK + threadIdx.x;
-            if (idx < nc) {
-                const uint64_t key = make_key(s[r], i0 + idx, 0);
+            if (id[r] >= 0 && (int64_t)id[r] < N) {
+                const uint64_t key = make_key(s[r], id[r], 0);
                 if (key < bar) cand[atomicAdd(&n_cand, 1)] = key;
             }
         }
@@ -128,8 +135,9 @@ static int grid_for(int64_t n) {
 
 using namespace gmpgr;
 
-extern "C" int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int32_t k,
-                               int32_t *out_ids_dev, float *out_scores_dev, void *stream) {
+// Best k per query over the whole table (cand == nullptr) or over cand[q][0..n) (device, [Q][n]).
+static int best_k(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int32_t k,
+                  const int32_t *cand, int32_t n, int32_t *out_ids_dev, float *out_scores_dev, void *stream) {
     if (!g || !m) {
         set_error("null graph or metric handle");
         return ANN_EINVAL;
@@ -153,14 +161,16 @@ extern "C" int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void 
     }
     hipStream_t s = (hipStream_t)stream;
     const bool mfma = m->kernel == MLP_MFMA2;
-    const int nc_max = (int)(g->N < BF_CHUNK ? g->N : BF_CHUNK);
+    // items (or candidates) per pass and query, queries per pass
+    const int nc_max = cand ? n : (int)(g->N < BF_CHUNK ? g->N : BF_CHUNK);
+    const int64_t total_per_query = cand ? n : g->N;
     int64_t qb64 = BF_PAIRS / nc_max;
     const int Qb = (int)(qb64 > Q ? Q : qb64 < 1 ? 1 : qb64);
     const size_t pairs = (size_t)Qb * nc_max;
     const size_t upre_bytes = mfma ? ((size_t)Q * m->dims[1] + 32) * sizeof(float) : 0;
     auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
     const size_t off_upre = 256, off_pq = up(off_upre + upre_bytes), off_pi = up(off_pq + pairs * 4),
-                 off_sc = up(off_pi + pairs * 4), off_best = up(off_sc + pairs * 4),
+                 off_sc = up(off_pi + (cand ? 0 : pairs * 4)), off_best = up(off_sc + pairs * 4),
                  total = up(off_best + (size_t)Q * k * 8);
     char *tmp = nullptr;
     if (hipMalloc((void **)&tmp, total) != hipSuccess) {
@@ -169,7 +179,7 @@ extern "C" int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void 
     }
     int32_t *count = (int32_t *)tmp;
     float *upre = (float *)(tmp + off_upre);
-    int32_t *pq = (int32_t *)(tmp + off_pq), *pi = (int32_t *)(tmp + off_pi);
+    int32_t *pq = (int32_t *)(tmp + off_pq), *pi = cand ? nullptr : (int32_t *)(tmp + off_pi);
     float *sc = (float *)(tmp + off_sc);
     uint64_t *best = (uint64_t *)(tmp + off_best);
 
@@ -186,17 +196,19 @@ extern "C" int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void 
     if (rc == ANN_OK && mfma) rc = launch_user_pre(m, queries_dev, Q, upre, s);
     for (int q0 = 0; q0 < Q && rc == ANN_OK; q0 += Qb) {
         const int qb = Q - q0 < Qb ? Q - q0 : Qb;
-        for (int64_t i0 = 0; i0 < g->N && rc == ANN_OK; i0 += nc_max) {
-            const int nc = (int)(g->N - i0 < nc_max ? g->N - i0 : nc_max);
+        for (int64_t i0 = 0; i0 < total_per_query && rc == ANN_OK; i0 += nc_max) {
+            const int nc = (int)(total_per_query - i0 < nc_max ? total_per_query - i0 : nc_max);
             const int M = qb * nc;
+            const int32_t *ids = cand ? cand + (size_t)q0 * n : nullptr;  // one pass per block of queries
             hipLaunchKernelGGL(bf_fill_pairs_kernel, dim3(grid_for(M)), dim3(256), 0, s, pq, pi, q0, (int32_t)i0, nc, M,
                                count);
             launched();
             if (rc != ANN_OK) break;
-            rc = mfma ? launch_mlp_mfma(g, m, upre, pq, pi, count, M, Q, sc, 0, s)
-                      : launch_mlp_alu(g, m, queries_dev, pq, pi, nullptr, M, Q, sc, 0, s);
+            rc = mfma ? launch_mlp_mfma(g, m, upre, pq, cand ? ids : pi, count, M, Q, sc, 0, s)
+                      : launch_mlp_alu(g, m, queries_dev, pq, cand ? ids : pi, nullptr, M, Q, sc, 0, s);
             if (rc != ANN_OK) break;
-            hipLaunchKernelGGL(bf_topk_kernel, dim3(qb), dim3(BF_BLOCK), 0, s, sc, nc, (int32_t)i0, best, k, q0);
+            hipLaunchKernelGGL(bf_topk_kernel, dim3(qb), dim3(BF_BLOCK), 0, s, sc, nc, (int32_t)i0, ids, g->N, best, k,
+                               q0);
             launched();
         }
     }
@@ -212,4 +224,19 @@ extern "C" int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void 
     }
     (void)hipFree(tmp);
     return rc;
+}
+
+extern "C" int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int32_t k,
+                               int32_t *out_ids_dev, float *out_scores_dev, void *stream) {
+    return best_k(g, m, queries_dev, Q, k, nullptr, 0, out_ids_dev, out_scores_dev, stream);
+}
+
+extern "C" int ann_rerank(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
+                          const int32_t *cand_dev, int32_t n, int32_t k, int32_t *out_ids_dev, float *out_scores_dev,
+                          void *stream) {
+    if (!cand_dev || n < 1 || n > BF_CHUNK) {
+        set_error("cand_dev must not be null and 1 <= n <= %d", BF_CHUNK);
+        return ANN_EINVAL;
+    }
+    return best_k(g, m, queries_dev, Q, k, cand_dev, n, out_ids_dev, out_scores_dev, stream);
 }

@@ -34,7 +34,7 @@ int main(void) {
                       (void *)ann_search_stream_workspace_bytes, (void *)ann_search_stream, (void *)ann_stream_open,
                       (void *)ann_stream_submit, (void *)ann_stream_step, (void *)ann_stream_drain,
                       (void *)ann_stream_close, (void *)ann_users_add_noise, (void *)ann_quantize_e4m3,
-                      (void *)ann_score_pairs_noalloc, (void *)ann_set_progress_timeout, (void *)ann_search_stats,
+                      (void *)ann_score_pairs_noalloc, (void *)ann_rerank, (void *)ann_set_progress_timeout, (void *)ann_search_stats,
                       (void *)ann_profile_enable, (void *)ann_profile_read, (void *)ann_profile_copy,
                       (void *)ann_last_error};
     size_t i;

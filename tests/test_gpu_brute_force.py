@@ -148,3 +148,98 @@ def test_brute_force_full_size_c3():
     exact = oracle.score_pairs(h["emb"], hu["users"], oracle.Mlp(h["W"], h["b"], h["head_w"]),
                                np.repeat(np.arange(len(q_sel)), k).astype(np.int32), ids_h.reshape(-1), n_threads=16)
     assert np.max(np.abs(sc_h.reshape(-1) - exact)) <= 1e-2
+
+
+# ----------------------------------------------------------------------------- re-ranking of candidate lists
+def _candidates(N, Q, n, seed, with_junk=True):
+    rng = np.random.default_rng(seed)
+    cand = np.stack([rng.choice(N, size=n, replace=False) for _ in range(Q)]).astype(np.int32)
+    if with_junk and n >= 8:
+        cand[:, 3] = -1           # the padding of a search result
+        cand[0, 5] = N            # out of range
+        cand[1 % Q, 6] = cand[1 % Q, 7]   # a repeated id
+    return cand
+
+
+@pytest.mark.parametrize("N,Q,n,k", [(900, 7, 40, 10), (5000, 5, 3000, 100), (5000, 3, 30, 64), (70000, 260, 65536, 20)])
+def test_rerank_fp32_equals_oracle(N, Q, n, k):
+    """The last case is two passes (260 queries of 65,536 candidates) at the largest n."""
+    cfg = scaled(PRESETS["C1"], N, n_clusters=3, Q=Q)
+    wl = make_workload(cfg, seed=N + n)
+    g, m, dev = open_handles(wl)
+    cand = _candidates(N, Q, n, seed=k)
+    ids, sc = ann.ann_rerank(g, m, dev["users"], torch.from_numpy(cand).cuda(), k)
+    h = to_host(wl)
+    rows = list(range(Q)) if Q <= 16 else [0, 1, 2, 255, 256, 257, Q - 1]
+    want = oracle.rerank(h["emb"], np.ascontiguousarray(h["users"][rows]), oracle_mlp(h), cand[rows], k, n_threads=8)
+    got_ids, got_sc = ids.cpu().numpy()[rows], sc.cpu().numpy()[rows]
+    assert np.array_equal(got_ids, want["ids"])
+    held = want["ids"] >= 0
+    np.testing.assert_allclose(got_sc[held], want["scores"][held], rtol=1e-5)
+    assert np.all(np.isneginf(got_sc[~held]))
+
+
+@pytest.mark.parametrize("preset", ["C2", "C3", "C4"])
+def test_rerank_16bit_is_the_top_k_of_the_kernels_relevances(preset):
+    N, Q, n, k = 20000, 6, 5000, 100
+    cfg = scaled(PRESETS[preset], N, n_clusters=8, Q=Q)
+    wl = make_workload(cfg, seed=17)
+    g, m, dev = open_handles(wl)
+    assert ann.ann_mlp_uses_mfma(m)
+    cand = _candidates(N, Q, n, seed=2)
+    cand_d = torch.from_numpy(cand).cuda()
+    ids, sc = ann.ann_rerank(g, m, dev["users"], cand_d, k)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    for q in range(Q):
+        ok = (cand[q] >= 0) & (cand[q] < N)
+        c = cand[q][ok]
+        s = ann.ann_score_pairs(g, m, dev["users"], torch.full((c.size,), q, dtype=torch.int32, device="cuda"),
+                                torch.from_numpy(c).cuda()).cpu().numpy()
+        order = np.lexsort((c, -s.astype(np.float64)))[:k]
+        assert np.array_equal(ids[q], c[order]) and np.array_equal(sc[q], s[order])
+    h = to_host(wl)
+    want = oracle.rerank(h["emb"], h["users"], oracle_mlp(h), cand, k, n_threads=8)
+    exact = oracle.score_pairs(h["emb"], h["users"], oracle_mlp(h), np.repeat(np.arange(Q), k).astype(np.int32),
+                               ids.reshape(-1), n_threads=8).reshape(Q, k)
+    assert np.max(np.abs(sc - exact)) <= 1e-2
+    shared = np.mean([len(set(ids[q]) & set(want["ids"][q])) / k for q in range(Q)])
+    assert shared >= 0.95, shared
+
+
+def test_rerank_of_an_8bit_search_recovers_the_16bit_ranking():
+    """Traversal under the 8-bit metric, its best 512 scored again under the 16-bit metric: the first 100 are
+    then, up to a point of recall, those of the 16-bit search with the same parameters."""
+    cfg = scaled(PRESETS["C3"], 200_000, n_clusters=256, Q=64)
+    wl = make_workload(cfg, seed=23)
+    g, m, dev = open_handles(wl)
+    emb8 = ann.ann_quantize_e4m3(dev["emb"])
+    g8 = ann.ann_graph_load(dev["adj"], emb8)
+    m8 = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, ann.ANN_F8)
+    W, L = 8, 1024
+    ids16, _ = ann.ann_search(g, m, dev["users"], dev["entries"], W, L, 100, 0)
+    ids8, _ = ann.ann_search(g8, m8, dev["users"], dev["entries"], W, L, 512, 0)
+    ids_rr, sc_rr = ann.ann_rerank(g, m, dev["users"], ids8, 100)
+    truth, _ = ann.ann_brute_force(g, m, dev["users"], 100)
+    rec = lambda found: float(np.mean([len(set(a.tolist()) & set(b.tolist()) - {-1}) / 100
+                                       for a, b in zip(found.cpu().numpy(), truth.cpu().numpy())]))
+    r16, r8, rrr = rec(ids16), rec(ids8[:, :100]), rec(ids_rr)
+    print(f"recall@100 against the 16-bit exhaustive ranking: 16-bit search {r16:.4f}, 8-bit search {r8:.4f}, "
+          f"8-bit search re-ranked {rrr:.4f}")
+    assert rrr >= r16 - 0.01 and rrr >= r8
+    s = sc_rr.cpu().numpy()
+    assert np.all(s[:, :-1] >= s[:, 1:])
+
+
+def test_rerank_argument_errors():
+    cfg = scaled(PRESETS["C1"], 500, n_clusters=2, Q=4)
+    wl = make_workload(cfg)
+    g, m, dev = open_handles(wl)
+    cand = torch.zeros(4, 8, dtype=torch.int32, device="cuda")
+    with pytest.raises(ann.AnnError):
+        ann.ann_rerank(g, m, dev["users"], cand, 0)
+    with pytest.raises(ann.AnnError):
+        ann.ann_rerank(g, m, dev["users"], torch.zeros(4, 65537, dtype=torch.int32, device="cuda"), 5)
+    with pytest.raises(ValueError):
+        ann.ann_rerank(g, m, dev["users"], cand[:3].contiguous(), 5)
+    with pytest.raises(TypeError):
+        ann.ann_rerank(g, m, dev["users"], cand.long(), 5)

@@ -155,6 +155,7 @@ def test_full_size_f8():
     ids, sc = ann.ann_search(g, m, wl["users"], wl["entries"], cfg.W, cfg.L, cfg.k, 0, workspace=ws)
     st = ann.ann_search_stats(ws)
     assert st.visited_overflow == 0 and st.queries == cfg.Q
+    ids_dev = ids
     ids, sc = _structure(ids, sc, cfg.N)
     n_sample, k, recall_k = 128, cfg.k, min(100, cfg.k)
     q_sel = np.sort(np.random.default_rng(7).choice(cfg.Q, n_sample, replace=False))
@@ -200,3 +201,19 @@ def test_full_size_f8():
     print(f"C3 e4m3 against the exact oracle: recall@{recall_k} {r_gpu:.4f} vs {r_exact:.4f}; |relevance error| mean "
           f"{cost.mean():.4f} max {cost.max():.4f}")
     assert r_exact - r_gpu <= 0.05 and cost.mean() <= 1e-2 and cost.max() <= 6e-2
+    # two stages: the 8-bit search's k candidates scored again under the 16-bit metric (ann_rerank), against the
+    # oracle doing the same with its own 8-bit list and exact relevances
+    g16 = ann.ann_graph_load(wl["adj"], wl["emb"])
+    m16 = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, ann.ANN_BF16)
+    rr_ids, rr_sc = ann.ann_rerank(g16, m16, wl["users"], ids_dev, recall_k)
+    rr_ids, rr_sc = _structure(rr_ids, rr_sc, cfg.N)
+    rr_ids, rr_sc = rr_ids[q_sel], rr_sc[q_sel]
+    assert all(set(a.tolist()) <= set(b.tolist()) for a, b in zip(rr_ids, got_ids)), "re-ranked ids come from the candidates"
+    want = oracle.rerank(h16["emb"], hu["users"], mlp_x, kern["ids"], recall_k, n_threads=16)
+    r_two, r_two_oracle = (recall_at(torch.from_numpy(v), truth, recall_k) for v in (rr_ids, want["ids"]))
+    qq2 = np.repeat(np.arange(n_sample), recall_k).astype(np.int32)
+    x2 = oracle.score_pairs(h16["emb"], hu["users"], mlp_x, qq2, rr_ids.ravel(), n_threads=16)
+    print(f"C3 8-bit search re-ranked in 16 bits: recall@{recall_k} gpu {r_two:.4f} oracle {r_two_oracle:.4f} "
+          f"(16-bit exact search {r_exact:.4f}, 8-bit search {r_gpu:.4f})")
+    assert np.max(np.abs(rr_sc.ravel() - x2)) <= 1e-2
+    assert abs(r_two - r_two_oracle) <= 0.01 + 1e-9 and r_two >= r_gpu

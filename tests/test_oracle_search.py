@@ -252,6 +252,30 @@ def test_brute_force_pads_when_k_exceeds_n():
     assert sorted(r["ids"][0, :3].tolist()) == [0, 1, 2]
 
 
+def test_rerank_of_every_item_is_brute_force_and_of_a_subset_its_restriction():
+    wl, mlp = _tiny(12)
+    N, Q = wl["emb"].shape[0], wl["users"].shape[0]
+    rng = np.random.default_rng(3)
+    everything = np.stack([rng.permutation(N) for _ in range(Q)]).astype(np.int32)
+    bf = oracle.brute_force(wl["emb"], wl["users"], mlp, 17)
+    rr = oracle.rerank(wl["emb"], wl["users"], mlp, everything, 17)
+    assert np.array_equal(rr["ids"], bf["ids"]) and np.array_equal(rr["scores"], bf["scores"])
+    # a subset, with padding and out-of-range ids among the candidates: the exhaustive ranking restricted to it
+    full = oracle.brute_force(wl["emb"], wl["users"], mlp, N)
+    sub = everything[:, : N // 3].copy()
+    cand = np.concatenate([sub, np.full((Q, 2), -1, np.int32), np.full((Q, 1), N, np.int32)], axis=1)
+    rr = oracle.rerank(wl["emb"], wl["users"], mlp, cand, N // 3 + 4)
+    for q in range(Q):
+        keep = [v for v in full["ids"][q] if v in set(sub[q].tolist())]
+        assert rr["ids"][q, : len(keep)].tolist() == keep
+        assert np.all(rr["ids"][q, len(keep):] == -1) and np.all(np.isneginf(rr["scores"][q, len(keep):]))
+    # a repeated candidate is kept as often as it occurs
+    twice = np.concatenate([sub[:, :5], sub[:, :1]], axis=1)
+    rr = oracle.rerank(wl["emb"], wl["users"], mlp, twice, 6)
+    for q in range(Q):
+        assert sorted(rr["ids"][q].tolist()) == sorted(twice[q].tolist())
+
+
 def test_complete_graph_search_equals_brute_force():
     # one expansion of the seed reaches every item
     wl, mlp = _tiny(12, N=120, R=6)
