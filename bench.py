@@ -534,10 +534,20 @@ def main() -> int:
                     ids8t, _ = run_t()
                 torch.cuda.synchronize()
                 ms8t = 1e3 * (time.perf_counter() - t8t) / 2
+                ann.ann_profile_enable(True)
+                ann.ann_profile_read()
+                run_t()
+                torch.cuda.synchronize()
+                prof8t = ann.ann_profile_read()
+                ann.ann_profile_enable(False)
+                pairs8t = int(ann.ann_search_stats(ws8).pairs_scored)
                 f8["this_workload_e4m3_at_timed_point"] = {
                     "W": W, "L": L_star, "ms_per_search": round(ms8t, 3), "queries_per_s": round(Q / ms8t * 1e3, 1),
                     "recall_at_100": round(recall_at(ids8t[sel].cpu(), truth.cpu(), kr), 4),
-                    "pairs_scored": int(ann.ann_search_stats(ws8).pairs_scored)}
+                    "pairs_scored": pairs8t,
+                    "stage_ms": {n: round(prof8t[n][0], 3) for n in ("score", "round", "pack")},
+                    "score_TFLOPs": round(pairs8t * fl8 / (prof8t["score"][0] * 1e-3) / 1e12, 1),
+                    "score_frac_of_fp8_peak": round(pairs8t * fl8 / (prof8t["score"][0] * 1e-3) / 1e12 / 5000.0, 4)}
                 log(f"e4m3 metric at the timed point: {ms8t:.1f} ms per search, recall@{kr} = "
                     f"{f8['this_workload_e4m3_at_timed_point']['recall_at_100']}")
                 del ids8t
