@@ -560,9 +560,13 @@ def main() -> int:
                 cand8 = torch.empty(Q, n_rr, dtype=torch.int32, device="cuda:0")
                 csc8 = torch.empty(Q, n_rr, dtype=torch.float32, device="cuda:0")
 
+                ws_rr = torch.empty(ann.ann_rerank_workspace_bytes(g, m, Q, n_rr, k), dtype=torch.uint8, device="cuda:0")
+                ids_rr = torch.empty(Q, k, dtype=torch.int32, device="cuda:0")
+                sc_rr = torch.empty(Q, k, dtype=torch.float32, device="cuda:0")
+
                 def run_2():
                     ann.ann_search(g8, m8, users, entries, W, L_star, n_rr, 0, workspace=ws8, out_ids=cand8, out_scores=csc8)
-                    return ann.ann_rerank(g, m, users, cand8, k)
+                    return ann.ann_rerank(g, m, users, cand8, k, out_ids=ids_rr, out_scores=sc_rr, workspace=ws_rr)
 
                 run_2()
                 torch.cuda.synchronize()
@@ -572,7 +576,7 @@ def main() -> int:
                 torch.cuda.synchronize()
                 ms82 = 1e3 * (time.perf_counter() - t82) / 2
                 t_rr = time.perf_counter()
-                ann.ann_rerank(g, m, users, cand8, k)
+                ann.ann_rerank(g, m, users, cand8, k, out_ids=ids_rr, out_scores=sc_rr, workspace=ws_rr)
                 torch.cuda.synchronize()
                 ms_rr = 1e3 * (time.perf_counter() - t_rr)
                 r82 = recall_at(ids82[sel].cpu(), truth.cpu(), kr)
@@ -585,7 +589,7 @@ def main() -> int:
                 log(f"8-bit traversal + 16-bit re-ranking of {n_rr} candidates at the timed point: {ms82:.1f} ms per search "
                     f"({ms_rr:.1f} ms of it re-ranking), recall@{kr} = {r82:.4f} (16-bit search: {recall:.4f} in "
                     f"{ms_per_step:.1f} ms)")
-                del cand8, csc8, ids82
+                del cand8, csc8, ids82, ws_rr
             if not args.no_stream:
                 # the two throughput levers together: four copies of the batch through 2Q slots with the 8-bit metric
                 users4, entries4 = users.repeat(4, 1).contiguous(), entries.repeat(4, 1).contiguous()

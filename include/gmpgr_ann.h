@@ -329,13 +329,19 @@ int ann_score_pairs(const ann_graph *g, const ann_mlp *m, const void *queries_de
  * queries_dev: [Q][d_user]; out_ids_dev: [Q][k] int32, out_scores_dev: [Q][k] fp32, device memory, written.
  * Order: relevance descending, equal relevances by ascending id (the order of the search's results);
  * with k above the number of items the row ends with id -1 / relevance -inf.  1 <= k <= 2,048.
- * Cost: Q x N relevance scores (the adjacency of `g` is not used).  The call allocates and frees a
- * temporary (about 200 MB + Q x k x 8 bytes + the per-query user terms) and synchronises `stream`.
+ * Cost: Q x N relevance scores (the adjacency of `g` is not used).
+ * workspace_dev: device memory of at least ann_brute_force_workspace_bytes(g, m, Q, k) bytes (about 200 MB +
+ * Q x k x 8 bytes + the per-query user terms), 256-byte aligned; the call then only enqueues kernels on `stream`
+ * and the outputs are valid once they have run.  NULL: the call allocates and frees that temporary itself and
+ * synchronises `stream`.
  * ANN_EINVAL for a null handle or pointer, a metric that does not match the graph, Q < 1, k out of range;
- * ANN_ENOMEM if the temporary cannot be allocated.
+ * ANN_EWORKSPACE for a workspace that is too small; ANN_ENOMEM if the temporary cannot be allocated.
+ * ann_brute_force_workspace_bytes returns 0 for arguments the call would refuse.
  */
+size_t ann_brute_force_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t k);
 int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int32_t k,
-                    int32_t *out_ids_dev, float *out_scores_dev, void *stream);
+                    int32_t *out_ids_dev, float *out_scores_dev, void *workspace_dev, size_t workspace_bytes,
+                    void *stream);
 
 /*
  * Re-ranking: the k most relevant of each query's n candidate items under this metric.  Meant for the lists a
@@ -345,12 +351,15 @@ int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void *queries_de
  * cand_dev: [Q][n] int32 item ids, device memory, read only; entries outside [0, N) (the -1 padding of a search
  * result) are no candidates; an id that occurs several times is returned as often.  1 <= n <= 65,536.
  * Result as ann_brute_force: [Q][k], relevance descending, equal relevances by ascending id, -1 / -inf where
- * a query has fewer than k candidates.  1 <= k <= 2,048.  Allocates and frees a temporary (n x 8 bytes per query
- * of a pass of at most 2^24 pairs, + Q x k x 8 + the per-query user terms) and synchronises `stream`.
- * Errors as ann_brute_force; ANN_EINVAL also for a null cand_dev or n out of range.
+ * a query has fewer than k candidates.  1 <= k <= 2,048.
+ * workspace_dev / workspace_bytes as for ann_brute_force, sized by ann_rerank_workspace_bytes(g, m, Q, n, k)
+ * (8 bytes per candidate of a pass of at most 2^24 pairs, + Q x k x 8 + the per-query user terms); NULL = allocate,
+ * free and synchronise.  Errors as ann_brute_force; ANN_EINVAL also for a null cand_dev or n out of range.
  */
+size_t ann_rerank_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t n, int32_t k);
 int ann_rerank(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, const int32_t *cand_dev,
-               int32_t n, int32_t k, int32_t *out_ids_dev, float *out_scores_dev, void *stream);
+               int32_t n, int32_t k, int32_t *out_ids_dev, float *out_scores_dev, void *workspace_dev,
+               size_t workspace_bytes, void *stream);
 
 /*
  * ann_score_pairs for callers that cannot allocate device memory: code whose stream is being recorded

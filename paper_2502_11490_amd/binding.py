@@ -23,7 +23,7 @@ EXPORTS = [
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
     "ann_search_layers", "ann_search_walkers_workspace_bytes", "ann_search_walkers",
     "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_stream_open", "ann_stream_submit", "ann_stream_step",
-    "ann_stream_drain", "ann_stream_close", "ann_score_pairs", "ann_score_pairs_noalloc", "ann_brute_force", "ann_rerank", "ann_users_add_noise", "ann_quantize_e4m3",
+    "ann_stream_drain", "ann_stream_close", "ann_score_pairs", "ann_score_pairs_noalloc", "ann_brute_force", "ann_brute_force_workspace_bytes", "ann_rerank", "ann_rerank_workspace_bytes", "ann_users_add_noise", "ann_quantize_e4m3",
     "ann_search_stats", "ann_set_progress_timeout", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
@@ -100,9 +100,13 @@ def load_library():
     lib.ann_score_pairs.restype = ctypes.c_int
     lib.ann_score_pairs_noalloc.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, vp]
     lib.ann_score_pairs_noalloc.restype = ctypes.c_int
-    lib.ann_brute_force.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+    lib.ann_brute_force.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.ann_brute_force.restype = ctypes.c_int
-    lib.ann_rerank.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp, vp]
+    lib.ann_brute_force_workspace_bytes.argtypes = [vp, vp, i32, i32]
+    lib.ann_brute_force_workspace_bytes.restype = ctypes.c_size_t
+    lib.ann_rerank_workspace_bytes.argtypes = [vp, vp, i32, i32, i32]
+    lib.ann_rerank_workspace_bytes.restype = ctypes.c_size_t
+    lib.ann_rerank.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.ann_rerank.restype = ctypes.c_int
     lib.ann_users_add_noise.argtypes = [vp, vp, i32, i32, i32, ctypes.c_double, ctypes.c_uint64, ctypes.c_uint64, vp]
     lib.ann_users_add_noise.restype = ctypes.c_int
@@ -507,10 +511,31 @@ def ann_score_pairs_noalloc(g: Graph, m: Mlp, queries: torch.Tensor, q_idx: torc
     return out
 
 
+def _workspace_args(workspace: Optional[torch.Tensor]):
+    if workspace is None:
+        return None, 0
+    return _dev_ptr(workspace, "workspace", torch.uint8), workspace.numel()
+
+
+def ann_brute_force_workspace_bytes(g: Graph, m: Mlp, Q: int, k: int) -> int:
+    n = load_library().ann_brute_force_workspace_bytes(g.handle, m.handle, Q, k)
+    if n == 0:
+        raise AnnError(ANN_EINVAL, ann_last_error())
+    return int(n)
+
+
+def ann_rerank_workspace_bytes(g: Graph, m: Mlp, Q: int, n: int, k: int) -> int:
+    b = load_library().ann_rerank_workspace_bytes(g.handle, m.handle, Q, n, k)
+    if b == 0:
+        raise AnnError(ANN_EINVAL, ann_last_error())
+    return int(b)
+
+
 def ann_brute_force(g: Graph, m: Mlp, queries: torch.Tensor, k: int, out_ids: Optional[torch.Tensor] = None,
-                    out_scores: Optional[torch.Tensor] = None, stream=None):
+                    out_scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
     """Exhaustive search: the k most relevant items of the whole table per query (ids [Q][k] int32, relevances
-    [Q][k] fp32; relevance descending, ties by ascending id)."""
+    [Q][k] fp32; relevance descending, ties by ascending id).  With a `workspace` (uint8 device tensor of
+    ann_brute_force_workspace_bytes) the call only enqueues; without one it allocates and synchronises."""
     lib = load_library()
     Q = queries.shape[0]
     if out_ids is None:
@@ -518,17 +543,20 @@ def ann_brute_force(g: Graph, m: Mlp, queries: torch.Tensor, k: int, out_ids: Op
     if out_scores is None:
         out_scores = torch.empty(Q, k, dtype=torch.float32, device=queries.device)
     _check_out(out_ids, out_scores, Q, k)
+    ws, ws_bytes = _workspace_args(workspace)
     rc = lib.ann_brute_force(g.handle, m.handle, _queries_ptr(queries, m), Q, k,
                              _dev_ptr(out_ids, "out_ids", torch.int32),
-                             _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
+                             _dev_ptr(out_scores, "out_scores", torch.float32), ws, ws_bytes, _stream_ptr(stream))
     _check(rc)
     return out_ids, out_scores
 
 
 def ann_rerank(g: Graph, m: Mlp, queries: torch.Tensor, cand: torch.Tensor, k: int,
-               out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None, stream=None):
+               out_ids: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None, stream=None):
     """The k most relevant of each query's candidates cand [Q][n] (int32; ids outside the table are skipped)
-    under this metric: ids [Q][k] int32, relevances [Q][k] fp32."""
+    under this metric: ids [Q][k] int32, relevances [Q][k] fp32.  `workspace` as for ann_brute_force
+    (ann_rerank_workspace_bytes)."""
     lib = load_library()
     Q = queries.shape[0]
     if cand.dim() != 2 or cand.shape[0] != Q:
@@ -538,9 +566,10 @@ def ann_rerank(g: Graph, m: Mlp, queries: torch.Tensor, cand: torch.Tensor, k: i
     if out_scores is None:
         out_scores = torch.empty(Q, k, dtype=torch.float32, device=queries.device)
     _check_out(out_ids, out_scores, Q, k)
+    ws, ws_bytes = _workspace_args(workspace)
     rc = lib.ann_rerank(g.handle, m.handle, _queries_ptr(queries, m), Q, _dev_ptr(cand, "cand", torch.int32),
                         cand.shape[1], k, _dev_ptr(out_ids, "out_ids", torch.int32),
-                        _dev_ptr(out_scores, "out_scores", torch.float32), _stream_ptr(stream))
+                        _dev_ptr(out_scores, "out_scores", torch.float32), ws, ws_bytes, _stream_ptr(stream))
     _check(rc)
     return out_ids, out_scores
 

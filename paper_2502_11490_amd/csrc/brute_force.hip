@@ -135,53 +135,85 @@ static int grid_for(int64_t n) {
 
 using namespace gmpgr;
 
-// Best k per query over the whole table (cand == nullptr) or over cand[q][0..n) (device, [Q][n]).
-static int best_k(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int32_t k,
-                  const int32_t *cand, int32_t n, int32_t *out_ids_dev, float *out_scores_dev, void *stream) {
+// Temporary of one call: count word, per-query user terms, one pass's pair list and scores, the running lists.
+struct BestKPlan {
+    int nc_max, Qb;
+    size_t off_upre, off_pq, off_pi, off_sc, off_best, total;
+};
+
+static bool best_k_plan(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t k, bool cand, int32_t n,
+                        BestKPlan *p) {
     if (!g || !m) {
         set_error("null graph or metric handle");
-        return ANN_EINVAL;
+        return false;
     }
     if (m->d_item != g->d || m->dtype != g->dtype) {
         set_error("metric (item width %d, dtype %d) does not match graph (%d, %d)", m->d_item, m->dtype, g->d,
                   g->dtype);
-        return ANN_EINVAL;
+        return false;
     }
     if (Q < 1 || k < 1 || k > BF_KMAX) {
         set_error("need Q >= 1 and 1 <= k <= %d", BF_KMAX);
-        return ANN_EINVAL;
+        return false;
     }
+    if (cand && (n < 1 || n > BF_CHUNK)) {
+        set_error("need 1 <= n <= %d candidates per query", BF_CHUNK);
+        return false;
+    }
+    if (g->N < 1 || g->N > 0x7fffffffll) {
+        set_error("the item table has %lld rows", (long long)g->N);
+        return false;
+    }
+    // items (or candidates) per pass and query, queries per pass
+    p->nc_max = cand ? n : (int)(g->N < BF_CHUNK ? g->N : BF_CHUNK);
+    const int64_t qb64 = BF_PAIRS / p->nc_max;
+    p->Qb = (int)(qb64 > Q ? Q : qb64 < 1 ? 1 : qb64);
+    const size_t pairs = (size_t)p->Qb * p->nc_max;
+    const size_t upre_bytes = m->kernel == MLP_MFMA2 ? ((size_t)Q * m->dims[1] + 32) * sizeof(float) : 0;
+    auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    p->off_upre = 256;
+    p->off_pq = up(p->off_upre + upre_bytes);
+    p->off_pi = up(p->off_pq + pairs * 4);
+    p->off_sc = up(p->off_pi + (cand ? 0 : pairs * 4));
+    p->off_best = up(p->off_sc + pairs * 4);
+    p->total = up(p->off_best + (size_t)Q * k * 8);
+    return true;
+}
+
+// Best k per query over the whole table (cand == nullptr) or over cand[q][0..n) (device, [Q][n]).
+// ws == nullptr: the temporary is allocated and freed here and the stream is synchronised; otherwise the call
+// only enqueues.
+static int best_k(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int32_t k,
+                  const int32_t *cand, int32_t n, int32_t *out_ids_dev, float *out_scores_dev, void *ws,
+                  size_t ws_bytes, void *stream) {
+    BestKPlan p;
+    if (!best_k_plan(g, m, Q, k, cand != nullptr, n, &p)) return ANN_EINVAL;
     if (!queries_dev || !out_ids_dev || !out_scores_dev) {
         set_error("queries_dev, out_ids_dev and out_scores_dev must not be null");
         return ANN_EINVAL;
     }
-    if (g->N < 1 || g->N > 0x7fffffffll) {
-        set_error("the item table has %lld rows", (long long)g->N);
+    if (ws && ws_bytes < p.total) {
+        set_error("workspace of %zu bytes given, %zu needed", ws_bytes, p.total);
+        return ANN_EWORKSPACE;
+    }
+    if (ws && ((uintptr_t)ws & 255)) {
+        set_error("the workspace must be 256-byte aligned");
         return ANN_EINVAL;
     }
     hipStream_t s = (hipStream_t)stream;
     const bool mfma = m->kernel == MLP_MFMA2;
-    // items (or candidates) per pass and query, queries per pass
-    const int nc_max = cand ? n : (int)(g->N < BF_CHUNK ? g->N : BF_CHUNK);
+    const int nc_max = p.nc_max, Qb = p.Qb;
     const int64_t total_per_query = cand ? n : g->N;
-    int64_t qb64 = BF_PAIRS / nc_max;
-    const int Qb = (int)(qb64 > Q ? Q : qb64 < 1 ? 1 : qb64);
-    const size_t pairs = (size_t)Qb * nc_max;
-    const size_t upre_bytes = mfma ? ((size_t)Q * m->dims[1] + 32) * sizeof(float) : 0;
-    auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
-    const size_t off_upre = 256, off_pq = up(off_upre + upre_bytes), off_pi = up(off_pq + pairs * 4),
-                 off_sc = up(off_pi + (cand ? 0 : pairs * 4)), off_best = up(off_sc + pairs * 4),
-                 total = up(off_best + (size_t)Q * k * 8);
-    char *tmp = nullptr;
-    if (hipMalloc((void **)&tmp, total) != hipSuccess) {
-        set_error("device allocation of %zu bytes failed", total);
+    char *tmp = (char *)ws;
+    if (!tmp && hipMalloc((void **)&tmp, p.total) != hipSuccess) {
+        set_error("device allocation of %zu bytes failed", p.total);
         return ANN_ENOMEM;
     }
     int32_t *count = (int32_t *)tmp;
-    float *upre = (float *)(tmp + off_upre);
-    int32_t *pq = (int32_t *)(tmp + off_pq), *pi = cand ? nullptr : (int32_t *)(tmp + off_pi);
-    float *sc = (float *)(tmp + off_sc);
-    uint64_t *best = (uint64_t *)(tmp + off_best);
+    float *upre = (float *)(tmp + p.off_upre);
+    int32_t *pq = (int32_t *)(tmp + p.off_pq), *pi = cand ? nullptr : (int32_t *)(tmp + p.off_pi);
+    float *sc = (float *)(tmp + p.off_sc);
+    uint64_t *best = (uint64_t *)(tmp + p.off_best);
 
     int rc = ANN_OK;
     auto launched = [&]() {
@@ -217,6 +249,7 @@ static int best_k(const ann_graph *g, const ann_mlp *m, const void *queries_dev,
                            out_ids_dev, out_scores_dev);
         launched();
     }
+    if (ws) return rc;
     const hipError_t e = hipStreamSynchronize(s);
     if (rc == ANN_OK && e != hipSuccess) {
         set_error("hipStreamSynchronize failed: %s", hipGetErrorString(e));
@@ -226,17 +259,30 @@ static int best_k(const ann_graph *g, const ann_mlp *m, const void *queries_dev,
     return rc;
 }
 
+extern "C" size_t ann_brute_force_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t k) {
+    BestKPlan p;
+    return best_k_plan(g, m, Q, k, false, 0, &p) ? p.total : 0;
+}
+
+extern "C" size_t ann_rerank_workspace_bytes(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t n, int32_t k) {
+    BestKPlan p;
+    return best_k_plan(g, m, Q, k, true, n, &p) ? p.total : 0;
+}
+
 extern "C" int ann_brute_force(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q, int32_t k,
-                               int32_t *out_ids_dev, float *out_scores_dev, void *stream) {
-    return best_k(g, m, queries_dev, Q, k, nullptr, 0, out_ids_dev, out_scores_dev, stream);
+                               int32_t *out_ids_dev, float *out_scores_dev, void *workspace_dev,
+                               size_t workspace_bytes, void *stream) {
+    return best_k(g, m, queries_dev, Q, k, nullptr, 0, out_ids_dev, out_scores_dev, workspace_dev, workspace_bytes,
+                  stream);
 }
 
 extern "C" int ann_rerank(const ann_graph *g, const ann_mlp *m, const void *queries_dev, int32_t Q,
                           const int32_t *cand_dev, int32_t n, int32_t k, int32_t *out_ids_dev, float *out_scores_dev,
-                          void *stream) {
-    if (!cand_dev || n < 1 || n > BF_CHUNK) {
-        set_error("cand_dev must not be null and 1 <= n <= %d", BF_CHUNK);
+                          void *workspace_dev, size_t workspace_bytes, void *stream) {
+    if (!cand_dev) {
+        set_error("cand_dev must not be null");
         return ANN_EINVAL;
     }
-    return best_k(g, m, queries_dev, Q, k, cand_dev, n, out_ids_dev, out_scores_dev, stream);
+    return best_k(g, m, queries_dev, Q, k, cand_dev, n, out_ids_dev, out_scores_dev, workspace_dev, workspace_bytes,
+                  stream);
 }

@@ -22,8 +22,8 @@ int main(void) {
                         ann_graph **) = ann_graph_load;
     int (*p_search)(const ann_graph *, const ann_mlp *, const void *, int32_t, const int32_t *, int32_t, int32_t,
                     int32_t, int32_t, int32_t, void *, size_t, int32_t *, float *, void *) = ann_search;
-    int (*p_brute)(const ann_graph *, const ann_mlp *, const void *, int32_t, int32_t, int32_t *, float *,
-                   void *) = ann_brute_force;
+    int (*p_brute)(const ann_graph *, const ann_mlp *, const void *, int32_t, int32_t, int32_t *, float *, void *,
+                   size_t, void *) = ann_brute_force;
     int (*p_pairs)(const ann_graph *, const ann_mlp *, const void *, int32_t, int64_t, const int32_t *,
                    const int32_t *, float *, int32_t, void *) = ann_score_pairs;
     size_t (*p_ws)(const ann_graph *, const ann_mlp *, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t) =
@@ -34,7 +34,8 @@ int main(void) {
                       (void *)ann_search_stream_workspace_bytes, (void *)ann_search_stream, (void *)ann_stream_open,
                       (void *)ann_stream_submit, (void *)ann_stream_step, (void *)ann_stream_drain,
                       (void *)ann_stream_close, (void *)ann_users_add_noise, (void *)ann_quantize_e4m3,
-                      (void *)ann_score_pairs_noalloc, (void *)ann_rerank, (void *)ann_set_progress_timeout, (void *)ann_search_stats,
+                      (void *)ann_score_pairs_noalloc, (void *)ann_rerank, (void *)ann_rerank_workspace_bytes,
+                      (void *)ann_brute_force_workspace_bytes, (void *)ann_set_progress_timeout, (void *)ann_search_stats,
                       (void *)ann_profile_enable, (void *)ann_profile_read, (void *)ann_profile_copy,
                       (void *)ann_last_error};
     size_t i;
@@ -56,7 +57,8 @@ int main(void) {
         CHECK(p_ws(g, NULL, 4, 1, 1, 8, 4, 0) == 0);
         CHECK(p_search(g, NULL, fake, 1, (const int32_t *)fake, 1, 1, 8, 4, 0, fake, sizeof fake, ids, sc, NULL) ==
               ANN_EINVAL);
-        CHECK(p_brute(g, NULL, fake, 1, 4, ids, sc, NULL) == ANN_EINVAL);
+        CHECK(p_brute(g, NULL, fake, 1, 4, ids, sc, NULL, 0, NULL) == ANN_EINVAL);
+        CHECK(ann_brute_force_workspace_bytes(g, NULL, 1, 4) == 0 && ann_rerank_workspace_bytes(g, NULL, 1, 8, 4) == 0);
         CHECK(p_pairs(NULL, NULL, fake, 1, 1, ids, ids, sc, 0, NULL) == ANN_EINVAL);
         CHECK(ann_set_progress_timeout(-1.0) == ANN_EINVAL && ann_set_progress_timeout(600.0) == ANN_OK);
         CHECK(ann_stream_close(NULL) == ANN_OK && ann_stream_submit(NULL, 1) == ANN_EINVAL);

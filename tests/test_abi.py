@@ -81,9 +81,10 @@ def test_errors_of_the_later_entry_points_without_a_device(lib):
     assert lib.ann_search_stream_workspace_bytes(None, None, 8, 0, 1, 1, 4, 3, 0) == 0
     assert lib.ann_score_pairs_noalloc(None, None, vp(256), 1, 4, vp(256), vp(256), vp(256), None) == -1
     assert lib.ann_score_pairs(None, None, vp(256), 1, 4, vp(256), vp(256), vp(256), 0, None) == -1
-    assert lib.ann_brute_force(None, None, vp(256), 1, 4, vp(256), vp(256), None) == -1 and b"null" in lib.ann_last_error()
-    assert lib.ann_rerank(None, None, vp(256), 1, None, 8, 4, vp(256), vp(256), None) == -1 and b"cand_dev" in lib.ann_last_error()
-    assert lib.ann_rerank(None, None, vp(256), 1, vp(256), 70000, 4, vp(256), vp(256), None) == -1
+    assert lib.ann_brute_force(None, None, vp(256), 1, 4, vp(256), vp(256), None, 0, None) == -1 and b"null" in lib.ann_last_error()
+    assert lib.ann_rerank(None, None, vp(256), 1, None, 8, 4, vp(256), vp(256), None, 0, None) == -1 and b"cand_dev" in lib.ann_last_error()
+    assert lib.ann_rerank(None, None, vp(256), 1, vp(256), 70000, 4, vp(256), vp(256), None, 0, None) == -1
+    assert lib.ann_rerank_workspace_bytes(None, None, 4, 8, 4) == 0 and lib.ann_brute_force_workspace_bytes(None, None, 4, 4) == 0
     assert lib.ann_set_progress_timeout(ctypes.c_double(-1.0)) == -1
     assert lib.ann_set_progress_timeout(ctypes.c_double(float("nan"))) == -1
     assert lib.ann_set_progress_timeout(ctypes.c_double(600.0)) == 0

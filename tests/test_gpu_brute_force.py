@@ -243,3 +243,35 @@ def test_rerank_argument_errors():
         ann.ann_rerank(g, m, dev["users"], cand[:3].contiguous(), 5)
     with pytest.raises(TypeError):
         ann.ann_rerank(g, m, dev["users"], cand.long(), 5)
+
+
+def test_caller_workspace_form_only_enqueues_and_gives_the_same_result():
+    """With a caller's workspace the two calls allocate nothing, do not synchronise and return what the allocating
+    form returns; a workspace that is too small is refused before anything runs."""
+    cfg = scaled(PRESETS["C2"], 30000, n_clusters=8, Q=50)
+    wl = make_workload(cfg, seed=31)
+    g, m, dev = open_handles(wl)
+    k, n = 40, 700
+    cand = torch.from_numpy(_candidates(cfg.N, cfg.Q, n, seed=4)).cuda()
+    want_b = ann.ann_brute_force(g, m, dev["users"], k)
+    want_r = ann.ann_rerank(g, m, dev["users"], cand, k)
+    ws_b = torch.empty(ann.ann_brute_force_workspace_bytes(g, m, cfg.Q, k), dtype=torch.uint8, device="cuda")
+    ws_r = torch.empty(ann.ann_rerank_workspace_bytes(g, m, cfg.Q, n, k), dtype=torch.uint8, device="cuda")
+    ids = torch.empty(cfg.Q, k, dtype=torch.int32, device="cuda")
+    sc = torch.empty(cfg.Q, k, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    allocations = lambda: torch.cuda.memory_stats()["allocation.all.allocated"]
+    for _ in range(2):   # the workspace keeps the last call's contents: a second call must not see them
+        before = allocations()
+        ann.ann_brute_force(g, m, dev["users"], k, out_ids=ids, out_scores=sc, workspace=ws_b)
+        assert allocations() == before
+        torch.cuda.synchronize()
+        assert torch.equal(ids, want_b[0]) and torch.equal(sc, want_b[1])
+        before = allocations()
+        ann.ann_rerank(g, m, dev["users"], cand, k, out_ids=ids, out_scores=sc, workspace=ws_r)
+        assert allocations() == before
+        torch.cuda.synchronize()
+        assert torch.equal(ids, want_r[0]) and torch.equal(sc, want_r[1])
+    with pytest.raises(ann.AnnError) as e:
+        ann.ann_rerank(g, m, dev["users"], cand, k, workspace=ws_r[:4096])
+    assert e.value.code == -5
