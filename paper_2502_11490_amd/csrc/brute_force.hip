@@ -38,9 +38,10 @@ __global__ void __launch_bounds__(256) bf_clear_kernel(uint64_t *best, int64_t n
 
 // Folds scores[b * nc .. (b + 1) * nc) of query q0 + b into best[(q0 + b) * k .. + k): ascending keys,
 // KEY_SENTINEL = no entry yet.  The scores belong to items i0 .. i0 + nc (ids == nullptr) or to the ids
-// ids[b * nc ..] (entries outside [0, N) are no candidates).  Keys that cannot enter (not below the current k-th) are dropped
-// as they are read; the others wait in an LDS buffer that is sorted and merged by rank whenever the next piece
-// might not fit.  Keys are distinct (an id appears once), so the merge's destinations are a permutation.
+// ids[b * nc ..] (entries outside [0, N) are no candidates).  Keys that cannot enter (not below the current
+// k-th) are dropped as they are read; the others wait in an LDS buffer that is sorted and merged by rank whenever
+// the next piece might not fit.  A waiting key goes behind the list's keys that equal it (a candidate id given
+// twice), so the merge's destinations are a permutation whether or not the keys are distinct.
 __global__ void __launch_bounds__(BF_BLOCK)
 bf_topk_kernel(const float *__restrict__ scores, int nc, int32_t i0, const int32_t *__restrict__ ids, int64_t N,
                uint64_t *best_g, int k, int q0) {
