@@ -225,3 +225,17 @@ def test_the_abi_from_plain_c(lib, tmp_path):
     assert res.returncode == 0, res.stderr
     run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert run.returncode == 0 and "c abi ok" in run.stdout, run.stdout + run.stderr
+
+
+def test_committed_traffic_summaries_belong_to_the_sources_in_the_tree():
+    """bench.py reads the counter traffic of the scoring kernel and of the round kernel at the timed point from
+    profiles/ and nulls a figure whose summary was taken on other kernel sources: the committed ones must match."""
+    import sys
+
+    sys.path.insert(0, ROOT)
+    import bench
+
+    assert bench.recorded_traffic("C3", 64, 8192) is not None, "profiles/c3_W64_L8192_hbm_traffic.txt: scoring kernels changed"
+    assert bench.recorded_traffic("C3", 64, 8192, "round") is not None, "same file: search_kernels.hip or keys.h changed"
+    assert bench.recorded_traffic("C3", 8, 1024) is not None and bench.recorded_traffic("C3", 8, 1024, "round") is not None
+    assert bench.recorded_traffic("C3", 32, 8192) is None   # no such measurement
