@@ -147,6 +147,8 @@ def main() -> int:
                     help="skip the run at the configuration's own point (profile commands: one point per process)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the capped search on C1 and C2")
     ap.add_argument("--no-exhaustive", action="store_true", help="skip the library's own exhaustive search on the sample")
+    ap.add_argument("--no-locality-order", action="store_true",
+                    help="address the visited bitmap by item id instead of by the order derived from the adjacency")
     ap.add_argument("--no-locality", action="store_true", help="skip the run on cluster-ordered item ids beside the headline")
     ap.add_argument("--no-f16", action="store_true", help="skip the fp16 metric run beside the headline")
     ap.add_argument("--no-f8", action="store_true", help="skip the 8-bit metric run (on C2) beside the headline")
@@ -181,6 +183,20 @@ def main() -> int:
     g = ann.ann_graph_load(wl["adj"], wl["emb"], ann.ANN_VALIDATE)
     m = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, dtype)
     mfma = ann.ann_mlp_uses_mfma(m)
+    # the visited bitmap is addressed by an order of the items derived from the adjacency alone (part of loading
+    # the graph, like its validation: untimed; it changes no result, only which 64-byte lines the bits lie in)
+    locality_info = None
+    L_most = args.L if args.L else args.max_L
+    if not args.no_locality_order and not cfg.ragged and ann.ann_search_visited_set_is_bitmap(
+            g, m, cfg.Q, cfg.E, args.W if args.W else cfg.W, max(L_most, cfg.L), cfg.k, 0):
+        from workloads import locality_rank
+
+        t1 = time.time()
+        rank, locality_info = locality_rank(wl["adj"])
+        ann.ann_graph_set_locality(g, rank)
+        torch.cuda.synchronize()
+        locality_info["seconds"] = round(time.time() - t1, 2)
+        log(f"locality order of the visited bitmap from the adjacency: {locality_info}")
     users, entries = wl["users"], wl["entries"]
     Q, E, W, k = cfg.Q, cfg.E, cfg.W, cfg.k
     ragged = cfg.ragged
@@ -495,6 +511,8 @@ def main() -> int:
         if cfg.dims == PRESETS["C3"].dims and cfg.dtype == "bf16":
             emb8 = ann.ann_quantize_e4m3(wl["emb"])
             g8 = ann.ann_graph_load(wl["adj"], emb8)
+            if locality_info is not None:
+                ann.ann_graph_set_locality(g8, rank)
             m8 = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, ann.ANN_F8)
             ws8 = torch.empty(ann.ann_search_workspace_bytes(g8, m8, Q, E, W_side, L_side, k, 0), dtype=torch.uint8,
                               device="cuda:0")
@@ -929,6 +947,7 @@ def main() -> int:
                            f" (recall@100 {recall:.3f}: the curve flattens below 0.95, L is the last doubling that "
                            f"gained two points)"),
             "Q": Q, "E": E, "W": W, "L": L_star, "k": k,
+            "visited_bitmap_order": locality_info,
             "recall_at_100": round(recall, 4), "recall_target_met": bool(target_met),
             "recall_curve_L": curve, "recall_plateau": plateau, "expansion_width_at_L": curve_W,
             "recall_queries": n_gt,

@@ -91,6 +91,28 @@ int ann_graph_load(const int32_t *adj_dev, const void *emb_dev, int64_t N, int32
 void ann_graph_free(ann_graph *g);
 
 /*
+ * Locality order of the visited set (optional; changes no result).  Where a search keeps its exact visited set
+ * (the ids scored for a query, Sec. 3.2's search: an id is scored once) as one bit per item, the bit of item v
+ * is bit rank_dev[v] instead of bit v.  A rank under which items joined by edges lie close together (for
+ * instance a numbering of the graph's communities) lets the neighbours of an expanded node fall into the same
+ * 64-byte lines of the bitmap; ids, results, their order and every counter stay exactly those of the search
+ * without it.  Searches whose visited set is the hash table ignore the rank.
+ * rank_dev: [N] int32, a permutation of 0 .. N-1, device memory, BORROWED until the graph is freed or the call is
+ * repeated; NULL removes the order.  The call checks on the device that rank_dev is a permutation (ANN_EINVAL if
+ * not), builds its own [N][R] table of the adjacency entries' ranks (N * R * 4 bytes of device memory, freed with
+ * the graph; ANN_ENOMEM), and synchronises `stream`.  Not to be called while a search on this graph is running.
+ */
+int ann_graph_set_locality(ann_graph *g, const int32_t *rank_dev, void *stream);
+
+/*
+ * Which form the exact visited set of a search with these parameters takes (arguments as for
+ * ann_search_workspace_bytes): 1 = one bit per item (long lists on a moderate item count; the form
+ * ann_graph_set_locality acts on), 0 = the per-query hash table; ANN_EINVAL for arguments the search would refuse.
+ */
+int ann_search_visited_set_is_bitmap(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32_t W_max,
+                                     int32_t L_max, int32_t k, int32_t max_iters_max);
+
+/*
  * The relevance metric of Sec. 3.1 (1): n_layers affine layers, Eq. 7 (W h + b).
  *   dims_host   : [n_layers + 1]; dims[0] = d_user + d_item, dims[n_layers] = J (1 <= J <= 8)
  *   W_host[l]   : [dims[l+1]][dims[l]] row-major, fp32, bf16 or fp16 as `dtype`; the first d_user

@@ -23,7 +23,7 @@ EXPORTS = [
     "ann_search_workspace_bytes", "ann_search", "ann_search_ragged", "ann_search_layers_workspace_bytes",
     "ann_search_layers", "ann_search_walkers_workspace_bytes", "ann_search_walkers",
     "ann_search_stream_workspace_bytes", "ann_search_stream", "ann_stream_open", "ann_stream_submit", "ann_stream_step",
-    "ann_stream_drain", "ann_stream_close", "ann_score_pairs", "ann_score_pairs_noalloc", "ann_brute_force", "ann_brute_force_workspace_bytes", "ann_rerank", "ann_rerank_workspace_bytes", "ann_users_add_noise", "ann_quantize_e4m3",
+    "ann_stream_drain", "ann_stream_close", "ann_score_pairs", "ann_score_pairs_noalloc", "ann_graph_set_locality", "ann_search_visited_set_is_bitmap", "ann_brute_force", "ann_brute_force_workspace_bytes", "ann_rerank", "ann_rerank_workspace_bytes", "ann_users_add_noise", "ann_quantize_e4m3",
     "ann_search_stats", "ann_set_progress_timeout", "ann_profile_enable", "ann_profile_read", "ann_profile_copy", "ann_last_error",
 ]
 
@@ -100,6 +100,10 @@ def load_library():
     lib.ann_score_pairs.restype = ctypes.c_int
     lib.ann_score_pairs_noalloc.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp, vp]
     lib.ann_score_pairs_noalloc.restype = ctypes.c_int
+    lib.ann_search_visited_set_is_bitmap.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32]
+    lib.ann_search_visited_set_is_bitmap.restype = ctypes.c_int
+    lib.ann_graph_set_locality.argtypes = [vp, vp, vp]
+    lib.ann_graph_set_locality.restype = ctypes.c_int
     lib.ann_brute_force.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.ann_brute_force.restype = ctypes.c_int
     lib.ann_brute_force_workspace_bytes.argtypes = [vp, vp, i32, i32]
@@ -229,6 +233,22 @@ def ann_graph_load(adj: torch.Tensor, emb: torch.Tensor, flags: int = 0, stream=
                             emb.shape[1], _dtype_code(emb), flags, _stream_ptr(stream), ctypes.byref(h))
     _check(rc)
     return Graph(h, adj, emb)
+
+
+def ann_graph_set_locality(g: Graph, rank: Optional[torch.Tensor], stream=None) -> None:
+    """Addresses the visited bitmap of searches on `g` by rank [N] (int32 permutation of the ids, device; None
+    removes it).  Results do not change; the tensor is kept alive with the graph."""
+    if rank is not None and (rank.dim() != 1 or rank.shape[0] != g.adj.shape[0]):
+        raise ValueError(f"rank must be [{g.adj.shape[0]}], got {tuple(rank.shape)}")
+    _check(load_library().ann_graph_set_locality(g.handle, _dev_ptr(rank, "rank", torch.int32), _stream_ptr(stream)))
+    g.rank = rank
+
+
+def ann_search_visited_set_is_bitmap(g: Graph, m: Mlp, Q: int, E: int, W: int, L: int, k: int, max_iters: int = 0) -> bool:
+    rc = load_library().ann_search_visited_set_is_bitmap(g.handle, m.handle, Q, E, W, L, k, max_iters)
+    if rc < 0:
+        _check(rc)
+    return rc == 1
 
 
 def _host_bytes(t) -> np.ndarray:

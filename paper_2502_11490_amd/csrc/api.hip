@@ -481,7 +481,87 @@ int ann_graph_load(const int32_t *adj_dev, const void *emb_dev, int64_t N, int32
     return ANN_OK;
 }
 
-void ann_graph_free(ann_graph *g) { delete g; }
+void ann_graph_free(ann_graph *g) {
+    if (g && g->adj_rank) (void)hipFree(g->adj_rank);
+    delete g;
+}
+
+// rank must be a permutation of 0 .. N-1: every value in range, none twice (seen: one bit per value)
+__global__ void check_rank_kernel(const int32_t *rank, int64_t N, uint32_t *seen, int *bad) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    int found = 0;
+    for (; i < N; i += step) {
+        const int32_t r = rank[i];
+        if (r < 0 || (int64_t)r >= N) found |= 1;
+        else if (atomicOr(&seen[(uint32_t)r >> 5], 1u << (r & 31)) & (1u << (r & 31))) found |= 2;
+    }
+    if (found) atomicOr(bad, found);
+}
+
+// adj_rank[e] = rank[adj[e]] (-1 where the adjacency holds no valid id)
+__global__ void fill_adj_rank_kernel(const int32_t *adj, const int32_t *rank, int64_t n, int64_t N, int32_t *adj_rank) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) {
+        const int32_t v = adj[i];
+        adj_rank[i] = (v >= 0 && (int64_t)v < N) ? rank[v] : -1;
+    }
+}
+
+int ann_search_visited_set_is_bitmap(const ann_graph *g, const ann_mlp *m, int32_t Q, int32_t E, int32_t W_max,
+                                     int32_t L_max, int32_t k, int32_t max_iters_max) {
+    Plan p;
+    if (!make_plan(g, m, Q, E, W_max, L_max, k, max_iters_max, &p)) return ANN_EINVAL;
+    return p.bitmap_words > 0 ? 1 : 0;
+}
+
+int ann_graph_set_locality(ann_graph *g, const int32_t *rank_dev, void *stream) {
+    if (!g) {
+        set_error("null graph handle");
+        return ANN_EINVAL;
+    }
+    if (g->adj_rank) (void)hipFree(g->adj_rank);
+    g->adj_rank = nullptr;
+    g->rank = nullptr;
+    if (!rank_dev) return ANN_OK;  // back to bits by id
+    hipStream_t s = (hipStream_t)stream;
+    const size_t seen_bytes = (size_t)((g->N + 31) / 32) * 4;
+    char *tmp = nullptr;
+    if (hipMalloc((void **)&tmp, 256 + seen_bytes) != hipSuccess) {
+        set_error("device allocation of %zu bytes failed", 256 + seen_bytes);
+        return ANN_ENOMEM;
+    }
+    int32_t *table = nullptr;
+    const size_t table_bytes = (size_t)g->N * g->R * sizeof(int32_t);
+    if (hipMalloc((void **)&table, table_bytes) != hipSuccess) {
+        (void)hipFree(tmp);
+        set_error("device allocation of %zu bytes failed", table_bytes);
+        return ANN_ENOMEM;
+    }
+    int h = 0;
+    hipError_t e = hipMemsetAsync(tmp, 0, 256 + seen_bytes, s);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(check_rank_kernel, dim3(2048), dim3(256), 0, s, rank_dev, g->N, (uint32_t *)(tmp + 256), (int *)tmp);
+        hipLaunchKernelGGL(fill_adj_rank_kernel, dim3(4096), dim3(256), 0, s, g->adj, rank_dev, g->N * g->R, g->N, table);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(&h, tmp, sizeof(int), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(tmp);
+    if (e != hipSuccess || h) {
+        (void)hipFree(table);
+        if (e != hipSuccess) {
+            set_error("building the locality table failed: %s", hipGetErrorString(e));
+            return ANN_EDEVICE;
+        }
+        set_error("rank_dev is not a permutation of 0 .. N-1 (%s)", (h & 1) ? "a value is out of range" : "a value occurs twice");
+        return ANN_EINVAL;
+    }
+    g->rank = rank_dev;
+    g->adj_rank = table;
+    return ANN_OK;
+}
 
 int ann_mlp_load(int32_t n_layers, const int32_t *dims_host, const void *const *W_host, const float *const *b_host,
                  const float *head_w_host, int32_t d_user, int32_t dtype, uint32_t flags, void *stream,

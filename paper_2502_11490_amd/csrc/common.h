@@ -58,6 +58,10 @@ struct ann_graph {
     const void *emb;
     int64_t N;
     int32_t R, d, dtype;
+    // locality order of the visited bitmap (ann_graph_set_locality): rank is the caller's [N] permutation,
+    // adj_rank the library's own [N][R] table rank[adj]; both null = bits by id
+    const int32_t *rank = nullptr;
+    int32_t *adj_rank = nullptr;
 };
 
 // Which fused kernel serves the metric.

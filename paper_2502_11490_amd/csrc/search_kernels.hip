@@ -246,14 +246,16 @@ __device__ int filter_and_insert(const int32_t *cand, int n_cand, uint32_t *dd_k
 // Every first occurrence reads its word (4 bytes); the ones whose bit is clear are new.  New ids that share a
 // word meet in an LDS table keyed by the word index, OR their bits together there, and the one that opened the
 // entry stores word | bits: plain loads and stores, the bitmap belongs to this workgroup alone.
+//   cand_rank : LDS int32[n_cand] or nullptr: the bit that stands for candidate p is cand_rank[p] instead of its id
+//               (a permutation of the ids chosen so that ids the graph joins lie in the same 64-byte lines)
 template <int BLK>
-__device__ int filter_and_mark(const int32_t *cand, int n_cand, uint32_t *dd_key, uint32_t *dd_pos, uint32_t *bk_key,
-                               uint32_t *bk_cnt, int dd_n, uint32_t *bits, int64_t N, int32_t *out, int *wave_sums,
-                               uint16_t *out_tag, int tag_div, int tag_base) {
+__device__ int filter_and_mark(const int32_t *cand, const int32_t *cand_rank, int n_cand, uint32_t *dd_key,
+                               uint32_t *dd_pos, uint32_t *bk_key, uint32_t *bk_cnt, int dd_n, uint32_t *bits, int64_t N,
+                               int32_t *out, int *wave_sums, uint16_t *out_tag, int tag_div, int tag_base) {
     uint32_t pre = 0;  // the first BLK candidates request their word right away (nothing is stored before pass 2)
     if ((int)threadIdx.x < n_cand) {
         const int32_t v = cand[threadIdx.x];
-        if (v >= 0 && (int64_t)v < N) pre = bits[(uint32_t)v >> 5];
+        if (v >= 0 && (int64_t)v < N) pre = bits[(uint32_t)(cand_rank ? cand_rank[threadIdx.x] : v) >> 5];
     }
     for (int i = threadIdx.x; i < dd_n; i += BLK) {
         dd_key[i] = EMPTY_SLOT;
@@ -284,16 +286,17 @@ __device__ int filter_and_mark(const int32_t *cand, int n_cand, uint32_t *dd_key
         const int p = p0 + threadIdx.x;
         bool fresh = false, owner = false;
         int32_t v = -1;
-        uint32_t word = 0, old_word = 0, slot = 0;
+        uint32_t word = 0, old_word = 0, slot = 0, bit = 0;
         if (p < n_cand) {
             v = cand[p];
             if (v >= 0 && (int64_t)v < N) {
                 uint32_t s = hash_id((uint32_t)v) & dd_mask;
                 while (dd_key[s] != (uint32_t)v) s = (s + 1u) & dd_mask;
                 if (dd_pos[s] == (uint32_t)p) {
-                    word = (uint32_t)v >> 5;
+                    bit = (uint32_t)(cand_rank ? cand_rank[p] : v);
+                    word = bit >> 5;
                     old_word = (p0 == 0) ? pre : bits[word];
-                    fresh = ((old_word >> (v & 31)) & 1u) == 0u;
+                    fresh = ((old_word >> (bit & 31)) & 1u) == 0u;
                 }
             }
         }
@@ -307,7 +310,7 @@ __device__ int filter_and_mark(const int32_t *cand, int n_cand, uint32_t *dd_key
                 }
                 slot = (slot + 1u) & dd_mask;
             }
-            atomicOr(&bk_cnt[slot], 1u << (v & 31));
+            atomicOr(&bk_cnt[slot], 1u << (bit & 31));
         }
         __syncthreads();  // every new bit of this pass has reached its LDS entry
         if (owner) bits[word] = old_word | bk_cnt[slot];
@@ -334,13 +337,13 @@ __device__ int filter_and_mark(const int32_t *cand, int n_cand, uint32_t *dd_key
 // Either form of the visited set: table_cap > 0 = hash table of that many entries, table_cap < 0 = bitmap in a
 // region of -table_cap words.
 template <int BLK>
-__device__ __forceinline__ int visited_filter(const int32_t *cand, int n_cand, uint32_t *dd_key, uint32_t *dd_pos,
-                                              uint32_t *bk_key, uint32_t *bk_cnt, int dd_n, uint32_t *table,
-                                              int table_cap, int64_t N, int32_t *out, int *wave_sums, uint16_t *out_tag,
-                                              int tag_div, int tag_base) {
+__device__ __forceinline__ int visited_filter(const int32_t *cand, const int32_t *cand_rank, int n_cand, uint32_t *dd_key,
+                                              uint32_t *dd_pos, uint32_t *bk_key, uint32_t *bk_cnt, int dd_n,
+                                              uint32_t *table, int table_cap, int64_t N, int32_t *out, int *wave_sums,
+                                              uint16_t *out_tag, int tag_div, int tag_base) {
     if (table_cap < 0)
-        return filter_and_mark<BLK>(cand, n_cand, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, N, out, wave_sums, out_tag,
-                                    tag_div, tag_base);
+        return filter_and_mark<BLK>(cand, cand_rank, n_cand, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, N, out, wave_sums,
+                                    out_tag, tag_div, tag_base);
     return filter_and_insert<BLK>(cand, n_cand, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, table_cap, N, out, wave_sums,
                                   out_tag, tag_div, tag_base);
 }
@@ -361,14 +364,16 @@ __global__ void zero_stats_kernel(int64_t *stats, Ctrl *ctrl, int Q, int keep_st
 // "round 0" (they are scored by the first MLP launch and merged by the first round kernel).
 // `slot` names the search state that is set up, `query` the row of entries / per-query parameters.
 template <int BLK>
-__device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entries, int E, int64_t N, QState *state,
-                          uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
+__device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entries, const int32_t *__restrict__ rank,
+                          int E, int64_t N, QState *state, uint32_t *hash, int hash_cap, int32_t *cand_g, int slots,
+                          int32_t *counts,
                           const int32_t *W_q, const int32_t *L_q, const int32_t *cap_q, int W, int L, int cap,
                           int W_max, int L_max, int cap_max, int64_t *stats, unsigned char *smem, uint16_t *tag_g) {
     int dd_n = 2;
     while (dd_n < 2 * E) dd_n <<= 1;
     int32_t *cand = (int32_t *)smem;                 // [E]
-    uint32_t *dd_key = (uint32_t *)(cand + ((E + 3) & ~3));
+    int32_t *cand_rank = rank ? cand + ((E + 3) & ~3) : nullptr;   // [E] the seeds' places in the visited bitmap
+    uint32_t *dd_key = (uint32_t *)(cand + (rank ? 2 : 1) * ((E + 3) & ~3));
     uint32_t *dd_pos = dd_key + dd_n;
     uint32_t *bk_key = dd_pos + dd_n;
     uint32_t *bk_cnt = bk_key + dd_n;
@@ -382,10 +387,14 @@ __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entri
         const uint4 e4 = make_uint4(e, e, e, e);
         for (int i = threadIdx.x; i < table_words / 4; i += BLK) t4[i] = e4;
     }
-    for (int i = threadIdx.x; i < E; i += BLK) cand[i] = entries[(size_t)query * E + i];
+    for (int i = threadIdx.x; i < E; i += BLK) {
+        const int32_t v = entries[(size_t)query * E + i];
+        cand[i] = v;
+        if (rank) cand_rank[i] = (v >= 0 && (int64_t)v < N) ? rank[v] : -1;
+    }
     __threadfence_block();
     __syncthreads();
-    int n = visited_filter<BLK>(cand, E, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, hash_cap, N,
+    int n = visited_filter<BLK>(cand, cand_rank, E, dd_key, dd_pos, bk_key, bk_cnt, dd_n, table, hash_cap, N,
                                 cand_g + (size_t)slot * slots, wave_sums, tag_g + (size_t)slot * slots, 1, 0);
     if (threadIdx.x == 0) {
         QState s;
@@ -406,12 +415,13 @@ __device__ void seed_slot(int slot, int query, const int32_t *__restrict__ entri
 }
 
 __global__ void __launch_bounds__(BLOCK)
-init_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state, uint32_t *hash,
+init_kernel(const int32_t *__restrict__ entries, const int32_t *__restrict__ rank, int E, int64_t N, QState *state,
+            uint32_t *hash,
             int hash_cap, int32_t *cand_g, int slots, int32_t *counts, const int32_t *W_q,
             const int32_t *L_q, const int32_t *cap_q, int W, int L, int cap, int W_max, int L_max,
             int cap_max, int64_t *stats, uint16_t *tag_g) {
     extern __shared__ __align__(16) unsigned char smem[];
-    seed_slot<BLOCK>(blockIdx.x, blockIdx.x, entries, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W,
+    seed_slot<BLOCK>(blockIdx.x, blockIdx.x, entries, rank, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W,
               L, cap, W_max, L_max, cap_max, stats, smem, tag_g);
 }
 
@@ -477,7 +487,8 @@ __global__ void stream_publish_kernel(Ctrl *ctrl, int64_t *stats, int avail) {
 }
 
 __global__ void __launch_bounds__(BLOCK)
-admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *state, uint32_t *hash, int hash_cap,
+admit_kernel(const int32_t *__restrict__ entries, const int32_t *__restrict__ rank, int E, int64_t N, QState *state,
+             uint32_t *hash, int hash_cap,
              int32_t *cand_g, int slots, int32_t *counts, const int32_t *W_q, const int32_t *L_q,
              const int32_t *cap_q, int W, int L, int cap, int W_max, int L_max, int cap_max, int64_t *stats,
              Ctrl *ctrl, int32_t *slot_query, int Q_total, const uint64_t *pool_g, int C, int k, int32_t *out_ids,
@@ -524,7 +535,7 @@ admit_kernel(const int32_t *__restrict__ entries, int E, int64_t N, QState *stat
     __syncthreads();  // also: the list of the served query has been read before the slot is re-seeded
     const int next = next_s;
     if (next < 0) return;
-    seed_slot<BLOCK>(slot, next, entries, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W, L, cap,
+    seed_slot<BLOCK>(slot, next, entries, rank, E, N, state, hash, hash_cap, cand_g, slots, counts, W_q, L_q, cap_q, W, L, cap,
               W_max, L_max, cap_max, stats, smem, tag_g);
 }
 
@@ -640,10 +651,11 @@ scan_compact_kernel(const int32_t *__restrict__ counts, int Q, const int32_t *__
 // dependent trips to memory fewer per round than the tiled walk, which is what short lists are bound by.
 template <int BLK, bool BITMAP, bool PIECES, bool RESIDENT>
 __global__ void __launch_bounds__(BLK) __attribute__((amdgpu_waves_per_eu(ROUND_WAVES_MIN, 8)))
-round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, uint64_t *pool_g, int C,
+round_kernel(const int32_t *__restrict__ adj, const int32_t *__restrict__ adj_rank, int R, int64_t N, QState *state,
+             uint64_t *pool_g, int C,
              uint32_t *hash, int hash_cap, int32_t *cand_g, int slots, int32_t *counts,
              const int32_t *__restrict__ offsets, const float *__restrict__ scores, int new_cap,
-             int W_max, int64_t *stats, uint16_t *tag_g, int walkers, int tile_keys) {
+             int W_max, int64_t *stats, uint16_t *tag_g, int walkers, int tile_keys, int chunk) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int q = blockIdx.x;
     PHASE_START
@@ -687,10 +699,12 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         if (threadIdx.x == 0) counts[q] = -1;
         return;
     }
-    const int chunk = min(slots, FILTER_CHUNK);  // candidates that go through the visited filter together
+    // chunk: candidates that go through the visited filter together; with a bitmap addressed by rank their ranks
+    // (adj_rank holds the rank of every adjacency entry, row for row) sit behind them
     int dd_n = 2;
     while (dd_n < 2 * chunk) dd_n <<= 1;
-    uint32_t *dd_key = (uint32_t *)(cand + ((chunk + 3) & ~3));
+    int32_t *cand_rank = (BITMAP && adj_rank) ? cand + ((chunk + 3) & ~3) : nullptr;
+    uint32_t *dd_key = (uint32_t *)(cand + (cand_rank ? 2 : 1) * ((chunk + 3) & ~3));
     uint32_t *dd_pos = dd_key + dd_n;
     uint32_t *bk_key = dd_pos + dd_n;
     uint32_t *bk_cnt = bk_key + dd_n;
@@ -875,10 +889,11 @@ round_kernel(const int32_t *__restrict__ adj, int R, int64_t N, QState *state, u
         for (int j = threadIdx.x; j < nc; j += BLK) {
             const int p = (c0 + j) / R, s = (c0 + j) - p * R;
             cand[j] = parents[p] >= 0 ? adj[(size_t)parents[p] * R + s] : -1;
+            if (BITMAP && cand_rank) cand_rank[j] = parents[p] >= 0 ? adj_rank[(size_t)parents[p] * R + s] : -1;
         }
         __syncthreads();
         if (BITMAP)
-            n_new += filter_and_mark<BLK>(cand, nc, dd_key, dd_pos, bk_key, bk_cnt, dd_n, hash + (size_t)q * (size_t)(-hash_cap),
+            n_new += filter_and_mark<BLK>(cand, cand_rank, nc, dd_key, dd_pos, bk_key, bk_cnt, dd_n, hash + (size_t)q * (size_t)(-hash_cap),
                                           N, cand_q + n_new, wave_sums, tag_q + n_new, R, PIECES ? c0 : 0);
         else
             n_new += filter_and_insert<BLK>(cand, nc, dd_key, dd_pos, bk_key, bk_cnt, dd_n, hash + (size_t)q * hash_cap,
@@ -941,28 +956,41 @@ static int tile_keys_of(const Plan &p) {
     return t;
 }
 
-static size_t round_smem(const Plan &p, int list_keys = 0) {  // list_keys: list entries held in LDS (0: one tile)
-    const int chunk = p.slots < FILTER_CHUNK ? p.slots : FILTER_CHUNK;
+// Does the visited bitmap of this search go by the graph's locality order?
+static bool ranked(const ann_graph *g, const Plan &p) { return p.bitmap_words > 0 && g->adj_rank != nullptr; }
+
+// Candidates that go through the visited filter together.  With ranks beside the ids the pieces are half as
+// large, so that the filter's LDS stays below what the merge needs anyway (the piece size does not show in the
+// kernel's time).
+static int filter_chunk(const ann_graph *g, const Plan &p) {
+    const int most = ranked(g, p) ? FILTER_CHUNK / 2 : FILTER_CHUNK;
+    return p.slots < most ? p.slots : most;
+}
+
+// list_keys: list entries held in LDS (0: one tile)
+static size_t round_smem(const ann_graph *g, const Plan &p, int list_keys = 0) {
+    const int chunk = filter_chunk(g, p);
     int dd_n = 2;
     while (dd_n < 2 * chunk) dd_n <<= 1;
     size_t lists = (size_t)(new_cap_of(p) + ((p.W_max + 1) & ~1) + (list_keys > 0 ? list_keys : tile_keys_of(p))) * 8;
-    size_t filt = (size_t)((chunk + 3) & ~3) * 4 + (size_t)dd_n * 16;
+    size_t filt = (size_t)((chunk + 3) & ~3) * 4 * (ranked(g, p) ? 2 : 1) + (size_t)dd_n * 16;
     return (size_t)((p.W_max + 3) & ~3) * 4 + 24 * 4 + (lists > filt ? lists : filt);
 }
 
-static size_t seed_smem(const Plan &p) {
+static size_t seed_smem(const ann_graph *g, const Plan &p) {
     int dd_n = 2;
     while (dd_n < 2 * p.E) dd_n <<= 1;
-    return (size_t)((p.E + 3) & ~3) * 4 + (size_t)dd_n * 16 + (WAVES + 1) * 4;
+    return (size_t)((p.E + 3) & ~3) * 4 * (ranked(g, p) ? 2 : 1) + (size_t)dd_n * 16 + (WAVES + 1) * 4;
 }
 
 int launch_init(const SearchArgs &a) {
     const Plan &p = a.plan;
-    size_t smem = seed_smem(p);
+    size_t smem = seed_smem(a.g, p);
     int64_t *stats = (int64_t *)(a.ws + p.off_stats);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, a.stream, stats, (Ctrl *)(a.ws + p.off_ctrl), p.Q,
                        a.keep_stats ? 1 : 0, p.R * 4, item_row_bytes(a.g));
-    hipLaunchKernelGGL(init_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.entries, p.E, a.g->N,
+    hipLaunchKernelGGL(init_kernel, dim3(p.Q), dim3(BLOCK), smem, a.stream, a.entries,
+                       ranked(a.g, p) ? a.g->rank : nullptr, p.E, a.g->N,
                        (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), table_cap_arg(p),
                        (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q,
                        a.L_q, a.cap_q, a.W, a.L, a.cap, p.W_max, p.L_max, p.max_iters_max, stats,
@@ -991,7 +1019,8 @@ int launch_stream_publish(const SearchArgs &a, int avail) {
 
 int launch_admit(const SearchArgs &a) {
     const Plan &p = a.plan;
-    hipLaunchKernelGGL(admit_kernel, dim3(p.Q), dim3(BLOCK), seed_smem(p), a.stream, a.entries, p.E, a.g->N,
+    hipLaunchKernelGGL(admit_kernel, dim3(p.Q), dim3(BLOCK), seed_smem(a.g, p), a.stream, a.entries,
+                       ranked(a.g, p) ? a.g->rank : nullptr, p.E, a.g->N,
                        (QState *)(a.ws + p.off_state), (uint32_t *)(a.ws + p.off_hash), table_cap_arg(p),
                        (int32_t *)(a.ws + p.off_cand), p.slots, (int32_t *)(a.ws + p.off_counts), a.W_q, a.L_q,
                        a.cap_q, a.W, a.L, a.cap, p.W_max, p.L_max, p.max_iters_max, (int64_t *)(a.ws + p.off_stats),
@@ -1018,7 +1047,7 @@ int launch_scan_compact(const SearchArgs &a) {
 
 int launch_round(const SearchArgs &a) {
     const Plan &p = a.plan;
-    size_t smem = round_smem(p);
+    size_t smem = round_smem(a.g, p);
     // Workgroups of 128 threads when a round has at most 128 candidates per query and the batch is far larger
     // than what a chip holds at once (2,048 workgroups of 256): twice as many queries are then resident, and
     // the candidates still go through the visited filter in one pass.  (C4: 33 -> 28 ms per step; with few
@@ -1026,14 +1055,15 @@ int launch_round(const SearchArgs &a) {
     // Workgroups of 1,024 threads when a round brings more than 512 candidates per query: the candidates pass the
     // visited filter in one sweep, and the sort and the merge have a quarter of the work per thread.
     const bool half = (p.slots <= 128 && p.Q >= 8192);
-    const bool big = p.slots > ROUND_BIG_FROM;
+    const bool big = p.slots > ROUND_BIG_FROM;  // several filter pieces only occur here: slots > FILTER_CHUNK / 2
     const int which = half ? 1 : big ? 2 : 0;
     const int threads = half ? 128 : big ? ROUND_BIG_BLOCK : BLOCK;
     const bool bm = p.bitmap_words > 0;
-    const bool pieces = p.slots > FILTER_CHUNK;  // then slots > ROUND_BIG_FROM too: the larger workgroup
+    const int chunk = filter_chunk(a.g, p);
+    const bool pieces = p.slots > chunk;
     const bool resident = !big && p.C <= tile_keys_of(p);
     const int tile_keys = resident ? ((p.C + 1) & ~1) : tile_keys_of(p);  // resident: the list itself, twice
-    if (resident) smem = round_smem(p, tile_keys + p.C);
+    if (resident) smem = round_smem(a.g, p, tile_keys + p.C);
     using Fn = decltype(&round_kernel<BLOCK, false, false, false>);
     Fn fn;
     if (big)
@@ -1052,13 +1082,14 @@ int launch_round(const SearchArgs &a) {
             rc != ANN_OK)
             return rc;
     }
-    hipLaunchKernelGGL(fn, dim3(p.Q), dim3(threads), smem, a.stream, a.g->adj, p.R, a.g->N,
+    hipLaunchKernelGGL(fn, dim3(p.Q), dim3(threads), smem, a.stream, a.g->adj,
+                       ranked(a.g, p) ? a.g->adj_rank : nullptr, p.R, a.g->N,
                        (QState *)(a.ws + p.off_state), (uint64_t *)(a.ws + p.off_pool), p.C,
                        (uint32_t *)(a.ws + p.off_hash), table_cap_arg(p), (int32_t *)(a.ws + p.off_cand), p.slots,
                        (int32_t *)(a.ws + p.off_counts), (const int32_t *)(a.ws + p.off_offsets),
                        (const float *)(a.ws + p.off_scores), new_cap_of(p), p.W_max,
                        (int64_t *)(a.ws + p.off_stats), (uint16_t *)(a.ws + p.off_tag), a.walkers ? 1 : 0,
-                       tile_keys);
+                       tile_keys, chunk);
     ANN_HIP_TRY(hipGetLastError());
     return ANN_OK;
 }

@@ -28,7 +28,8 @@ int main(void) {
                    const int32_t *, float *, int32_t, void *) = ann_score_pairs;
     size_t (*p_ws)(const ann_graph *, const ann_mlp *, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t) =
         ann_search_workspace_bytes;
-    void *others[] = {(void *)ann_graph_free, (void *)ann_mlp_load, (void *)ann_mlp_free, (void *)ann_mlp_uses_mfma,
+    void *others[] = {(void *)ann_graph_free, (void *)ann_graph_set_locality,
+                      (void *)ann_search_visited_set_is_bitmap, (void *)ann_mlp_load, (void *)ann_mlp_free, (void *)ann_mlp_uses_mfma,
                       (void *)ann_search_ragged, (void *)ann_search_layers_workspace_bytes, (void *)ann_search_layers,
                       (void *)ann_search_walkers_workspace_bytes, (void *)ann_search_walkers,
                       (void *)ann_search_stream_workspace_bytes, (void *)ann_search_stream, (void *)ann_stream_open,
@@ -62,6 +63,7 @@ int main(void) {
         CHECK(p_pairs(NULL, NULL, fake, 1, 1, ids, ids, sc, 0, NULL) == ANN_EINVAL);
         CHECK(ann_set_progress_timeout(-1.0) == ANN_EINVAL && ann_set_progress_timeout(600.0) == ANN_OK);
         CHECK(ann_stream_close(NULL) == ANN_OK && ann_stream_submit(NULL, 1) == ANN_EINVAL);
+        CHECK(ann_graph_set_locality(NULL, NULL, NULL) == ANN_EINVAL && ann_graph_set_locality(g, NULL, NULL) == ANN_OK);
         ann_graph_free(g);
         ann_graph_free(NULL);
         ann_mlp_free(NULL);

@@ -94,6 +94,18 @@ def test_full_size_uniform(preset, n_sample, L, W):
     ids, sc = ann.ann_search(g, m, wl["users"], wl["entries"], cfg.W, cfg.L, cfg.k, 0, workspace=ws)
     st = ann.ann_search_stats(ws)
     assert st.visited_overflow == 0 and st.queries == cfg.Q
+    if L:
+        # as the benchmark runs these points: the visited bitmap addressed by the order derived from the adjacency;
+        # the search must not change by a bit
+        from workloads import locality_rank
+        rank, info = locality_rank(wl["adj"])
+        assert info["bitmap_lines_per_row"] < 0.7 * info["bitmap_lines_per_row_by_id"], info
+        ann.ann_graph_set_locality(g, rank)
+        ids_r, sc_r = ann.ann_search(g, m, wl["users"], wl["entries"], cfg.W, cfg.L, cfg.k, 0, workspace=ws)
+        st_r = ann.ann_search_stats(ws)
+        assert torch.equal(ids_r, ids) and torch.equal(sc_r, sc)
+        assert (st_r.pairs_scored, st_r.nodes_expanded, st_r.max_query_iters) == (st.pairs_scored, st.nodes_expanded,
+                                                                                   st.max_query_iters)
     ids, sc = _structure(ids, sc, cfg.N)
     q_sel = np.sort(np.random.default_rng(5).choice(cfg.Q, n_sample, replace=False))
     _sample_check(wl, cfg, ids, sc, q_sel, cfg.W, cfg.L, 0, cfg.k, min(100, cfg.k), min_shared=0.99 if L else None)

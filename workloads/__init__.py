@@ -16,3 +16,4 @@ from .gen import (  # noqa: F401
     to_host,
     scaled,
 )
+from .locality import locality_rank  # noqa: F401
