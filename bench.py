@@ -184,19 +184,24 @@ def main() -> int:
     m = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, dtype)
     mfma = ann.ann_mlp_uses_mfma(m)
     # the visited bitmap is addressed by an order of the items derived from the adjacency alone (part of loading
-    # the graph, like its validation: untimed; it changes no result, only which 64-byte lines the bits lie in)
-    locality_info = None
-    L_most = args.L if args.L else args.max_L
-    if not args.no_locality_order and not cfg.ragged and ann.ann_search_visited_set_is_bitmap(
-            g, m, cfg.Q, cfg.E, args.W if args.W else cfg.W, max(L_most, cfg.L), cfg.k, 0):
+    # the graph, like its validation: untimed; it changes no result, only which 64-byte lines the bits lie in).
+    # Computed when the first full-batch search whose visited set is the bitmap comes up.
+    vorder = {"info": None, "rank": None}
+
+    def ensure_locality(Wx, Lx):
+        if vorder["info"] is not None or args.no_locality_order or cfg.ragged:
+            return
+        if not ann.ann_search_visited_set_is_bitmap(g, m, cfg.Q, cfg.E, Wx, Lx, cfg.k, 0):
+            return
         from workloads import locality_rank
 
         t1 = time.time()
-        rank, locality_info = locality_rank(wl["adj"])
-        ann.ann_graph_set_locality(g, rank)
+        vorder["rank"], vorder["info"] = locality_rank(wl["adj"])
+        ann.ann_graph_set_locality(g, vorder["rank"])
         torch.cuda.synchronize()
-        locality_info["seconds"] = round(time.time() - t1, 2)
-        log(f"locality order of the visited bitmap from the adjacency: {locality_info}")
+        vorder["info"]["seconds"] = round(time.time() - t1, 2)
+        log(f"locality order of the visited bitmap from the adjacency: {vorder['info']}")
+
     users, entries = wl["users"], wl["entries"]
     Q, E, W, k = cfg.Q, cfg.E, cfg.W, cfg.k
     ragged = cfg.ragged
@@ -281,6 +286,7 @@ def main() -> int:
                 if Wx * cfg.R > 4096:
                     break
                 rx = r_ref if Wx == W else search_sample(Wx, L_star)
+                ensure_locality(Wx, L_star)
                 wsx = torch.empty(ann.ann_search_workspace_bytes(g, m, Q, E, Wx, L_star, k, 0), dtype=torch.uint8,
                                   device="cuda:0")
                 ann.ann_search(g, m, users, entries, Wx, L_star, k, 0, workspace=wsx)
@@ -301,6 +307,7 @@ def main() -> int:
         Wm, Lm, capm = cfg.W_range[1], cfg.L_range[1], cfg.cap_range[1]
         ws = torch.empty(ann.ann_search_workspace_bytes(g, m, Q, E, Wm, Lm, k, capm), dtype=torch.uint8, device="cuda:0")
     else:
+        ensure_locality(W, L_star)
         ws = torch.empty(ann.ann_search_workspace_bytes(g, m, Q, E, W, L_star, k, 0), dtype=torch.uint8, device="cuda:0")
     out_ids = torch.empty((Q, k), dtype=torch.int32, device="cuda:0")
     out_sc = torch.empty((Q, k), dtype=torch.float32, device="cuda:0")
@@ -511,8 +518,8 @@ def main() -> int:
         if cfg.dims == PRESETS["C3"].dims and cfg.dtype == "bf16":
             emb8 = ann.ann_quantize_e4m3(wl["emb"])
             g8 = ann.ann_graph_load(wl["adj"], emb8)
-            if locality_info is not None:
-                ann.ann_graph_set_locality(g8, rank)
+            if vorder["rank"] is not None:
+                ann.ann_graph_set_locality(g8, vorder["rank"])
             m8 = ann.ann_mlp_load(wl["W"], wl["b"], wl["head_w"], cfg.d, ann.ANN_F8)
             ws8 = torch.empty(ann.ann_search_workspace_bytes(g8, m8, Q, E, W_side, L_side, k, 0), dtype=torch.uint8,
                               device="cuda:0")
@@ -947,7 +954,7 @@ def main() -> int:
                            f" (recall@100 {recall:.3f}: the curve flattens below 0.95, L is the last doubling that "
                            f"gained two points)"),
             "Q": Q, "E": E, "W": W, "L": L_star, "k": k,
-            "visited_bitmap_order": locality_info,
+            "visited_bitmap_order": vorder["info"],
             "recall_at_100": round(recall, 4), "recall_target_met": bool(target_met),
             "recall_curve_L": curve, "recall_plateau": plateau, "expansion_width_at_L": curve_W,
             "recall_queries": n_gt,
