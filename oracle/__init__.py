@@ -4,6 +4,10 @@ Only tests, the smoke check and the CPU-baseline leg of the benchmark may import
 this package.  It shares nothing with the HIP library.  The wrapper marshals
 arguments (numpy arrays, bf16 passed as raw uint16 bits) and does no arithmetic
 of the method itself; weights in bf16 are widened to fp32, which is exact.
+Two functions are written out here rather than in C, each a few lines over the
+C routines: search_layers (a loop of searches, one per layer) and rerank
+(relevances by score_pairs, then numpy's lexsort for the search's order; pinned
+to brute_force in tests/test_oracle_search.py).
 """
 from __future__ import annotations
 
