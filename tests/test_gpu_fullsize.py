@@ -77,7 +77,7 @@ def _sample_check(wl, cfg, ids, sc, q_sel, W, L, cap, k, recall_k, act_round=1, 
 # and C3 at W = 64, L = 8192 the point it times when the sweep runs to the plateau of the recall curve (there the
 # list is merged through LDS tiles, the visited set is the bitmap and a round's candidates pass the filter in pieces)
 @pytest.mark.parametrize("preset,n_sample,L,W", [("C2", 128, 0, 0), ("C3", 192, 0, 0), ("C3", 64, 1024, 0),
-                                                 ("C3", 32, 8192, 64), ("C4", 128, 0, 0)])
+                                                 ("C3", 16, 8192, 64), ("C4", 128, 0, 0)])
 def test_full_size_uniform(preset, n_sample, L, W):
     cfg = PRESETS[preset]
     if L:
